@@ -1,0 +1,251 @@
+/*
+ * shifter.h - C ABI of the prune-and-compact pass for CNN variant portfolios
+ *             (DNNShifter, arXiv 2309.06973), implemented as HIP kernels for gfx950.
+ *
+ * The pass turns one dense fp32 CNN into a sparse variant and then into a smaller
+ * dense ("pruned") variant:
+ *
+ *   shifter_global_threshold   unstructured magnitude ranking over all prunable
+ *                              weights (Sec. II-A, Sec. III-C)
+ *   shifter_apply_mask         the sparse model: zeros written in place of the
+ *                              lowest-magnitude weights (Sec. II-A, Sec. III-C)
+ *   shifter_dead_channel_scan  Module 2, Sparsity Analyser (Sec. III-D)
+ *   shifter_propagate_groups   Module 3, Prune Planner, Algorithm 1 (Sec. III-D)
+ *   shifter_compact            Module 4, Model Pruner, Algorithm 2 (Sec. III-D)
+ *
+ * Conventions
+ *   - Pointers named d_* are DEVICE pointers owned by the caller; h_* are HOST
+ *     pointers owned by the caller.  The library never frees or keeps either.
+ *   - A network is a flat fp32 weight arena (every conv / linear weight tensor, OIHW
+ *     row-major, at the element offset its descriptor names) and a flat fp32 vector
+ *     arena (BatchNorm gamma / beta / running mean / running variance, biases).
+ *   - Channel groups: a group is a channel space.  Tensors whose out_group is G write
+ *     it (producers), vectors whose group is G hold one value per channel of it,
+ *     tensors whose in_group is G read it (consumers).  Residual adds put several
+ *     producers into one group.  Pinned groups (network input, logits) never shrink.
+ *   - Global index g: prunable tensors in descriptor order, each row-major.  The
+ *     order on weights is (|w|, g) ascending; |w| is compared as the fp32 bit pattern
+ *     with the sign cleared, so -0.0 == +0.0, denormals are exact, +-inf is largest.
+ *     NaN among prunable weights is an error.
+ *   - Every call enqueues its kernels on the context's stream and returns without
+ *     waiting, except where a non-NULL h_* output is passed (documented per call):
+ *     then the call waits for the stream and fills it.
+ *   - Every function returns a shifter_status.  No exceptions or aborts cross the
+ *     ABI; shifter_last_error() gives the text of the last failure.  Argument and
+ *     descriptor errors are found on the host before anything is launched.
+ *   - The library allocates device memory only in shifter_create and the first call
+ *     that uses a model with a context (tables and scratch sized from the model);
+ *     later calls allocate nothing.
+ */
+#ifndef SHIFTER_H
+#define SHIFTER_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct shifter_ctx shifter_ctx;     /* device, stream, scratch              */
+typedef struct shifter_model shifter_model; /* validated copy of the descriptors    */
+
+typedef enum {
+    SHIFTER_OK = 0,
+    SHIFTER_ERR_INVALID_ARG = 1, /* NULL pointer, count out of range, ...             */
+    SHIFTER_ERR_BAD_MODEL = 2,   /* descriptors inconsistent                          */
+    SHIFTER_ERR_NONFINITE = 3,   /* NaN among the prunable weights                    */
+    SHIFTER_ERR_CAPACITY = 4,    /* output buffer too small; needed sizes reported    */
+    SHIFTER_ERR_NO_DEVICE = 5,   /* no usable GPU                                     */
+    SHIFTER_ERR_HIP = 6,         /* a HIP call failed                                 */
+    SHIFTER_ERR_OOM = 7,         /* device or host allocation failed                  */
+    SHIFTER_WARN_COLLAPSE = 100  /* some group has no surviving channel (layer
+                                    collapse, Sec. IV-B.1); outputs are still valid    */
+} shifter_status;
+
+/* One conv / linear weight tensor, OIHW row-major. linear: kh = kw = 1. */
+typedef struct {
+    uint64_t offset;    /* fp32 element offset in the weight arena                    */
+    uint32_t out_ch;    /* O: must equal width of out_group                           */
+    uint32_t in_ch;     /* I: input features = width of in_group * in_mult            */
+    uint32_t kh, kw;
+    uint32_t in_mult;   /* input features per input channel (flatten -> linear), else 1 */
+    int32_t out_group;
+    int32_t in_group;
+    uint32_t prunable;  /* 1: ranked and masked; 0: copied, scanned and compacted only */
+} shifter_tensor_desc;
+
+typedef struct {
+    uint64_t offset;    /* fp32 element offset in the vector arena                    */
+    uint32_t len;       /* must equal width of group                                  */
+    int32_t group;
+} shifter_vec_desc;
+
+typedef struct {
+    uint32_t width;
+    uint32_t pinned;    /* 1: never shrunk                                            */
+} shifter_group_desc;
+
+/* Result of the ranking for one prune count P.  Weight g is removed iff
+ *      ((uint64_t)key(w_g) << 32 | g)  <  cut
+ * i.e. iff (|w_g|, g) is among the P smallest pairs.  P = 0 gives cut = 0. */
+typedef struct {
+    uint64_t cut;
+    uint32_t t_key;     /* bit pattern of |w| of the P-th smallest pair (0 if P = 0)  */
+    uint32_t reserved;
+    uint64_t g_cut;     /* global index of that pair (UINT64_MAX if P = 0)            */
+    uint64_t n_prune;   /* P                                                          */
+    uint64_t n_less;    /* weights with key <  t_key                                  */
+    uint64_t n_equal;   /* weights with key == t_key                                  */
+} shifter_threshold;
+
+/* Sizes derived from the descriptors; the caller sizes its buffers from these. */
+typedef struct {
+    uint64_t n_prunable;      /* N: length of the global index space and of the mask  */
+    uint64_t w_extent;        /* weight arena must hold at least this many floats     */
+    uint64_t v_extent;        /* vector arena likewise                                */
+    uint64_t w_elems;         /* sum of tensor sizes (capacity that always suffices)  */
+    uint64_t v_elems;         /* sum of vector lengths                                */
+    uint64_t sum_out_ch;      /* length of the out_alive flag array                   */
+    uint64_t sum_in_ch;       /* length of the in_alive flag array                    */
+    uint64_t sum_group_width; /* length of group_alive / index_map / keep             */
+    uint32_t n_tensors, n_vecs, n_groups, reserved;
+} shifter_model_info;
+
+#define SHIFTER_GROUPS_JOINT 0u           /* residual-add groups pruned jointly        */
+#define SHIFTER_PAPER_FREEZE_RESIDUAL 1u  /* groups with several producers left whole:
+                                             skip / downsample connections are not
+                                             pruned (Sec. IV-B.2)                      */
+
+#define SHIFTER_MAX_VARIANTS 64u          /* prune counts per shifter_global_threshold */
+
+/* --- contexts and models ---------------------------------------------------------- */
+
+/* Creates a context on `device` (HIP ordinal).  `hip_stream` is a hipStream_t owned by
+ * the caller (NULL = the default stream); every kernel of this context runs on it.
+ * Fails with SHIFTER_ERR_NO_DEVICE when the device does not exist. */
+int shifter_create(shifter_ctx** out, int device, void* hip_stream);
+int shifter_destroy(shifter_ctx* ctx);
+
+/* Text of the last failure on this context (or of the last failed call that had no
+ * context when ctx is NULL).  Valid until the next call on the same thread. */
+const char* shifter_last_error(const shifter_ctx* ctx);
+
+/* Validates and copies the descriptor tables.  Host only: touches no GPU.
+ * Errors (SHIFTER_ERR_BAD_MODEL): group index out of range, out_ch / in_ch / len not
+ * matching the group widths, zero-sized dimension, overlapping tensors or vectors,
+ * tensor of 2^32 or more elements, N >= 2^32 - 1, more than 65535 tensors. */
+int shifter_model_create(const shifter_tensor_desc* tensors, uint32_t n_tensors,
+                         const shifter_vec_desc* vecs, uint32_t n_vecs,
+                         const shifter_group_desc* groups, uint32_t n_groups,
+                         shifter_model** out);
+int shifter_model_destroy(shifter_model* model);
+int shifter_model_get_info(const shifter_model* model, shifter_model_info* out);
+
+/* Offsets of tensor t inside the out_alive / in_alive arrays and of group g inside the
+ * per-group arrays (arrays of n_tensors / n_tensors / n_groups entries, any may be
+ * NULL). */
+int shifter_model_get_layout(const shifter_model* model, uint64_t* h_out_flag_off,
+                             uint64_t* h_in_flag_off, uint64_t* h_group_off);
+
+/* --- the five steps ---------------------------------------------------------------- */
+
+/* Unstructured magnitude ranking (Sec. II-A; Sec. III-C): for each of the K prune
+ * counts h_n_prune[k] (0 <= P <= N, K <= SHIFTER_MAX_VARIANTS) finds the P-th smallest
+ * pair (|w_g|, g) over all prunable weights and writes its record to d_thr[k].  One
+ * pass structure serves all K counts (a portfolio ranks the same dense weights).
+ *   d_w        device, weight arena, w_extent floats, read only
+ *   d_thr      device, K records, written
+ *   h_thr      host, K records, or NULL.  Non-NULL: the call waits for the stream,
+ *              copies the records and reports SHIFTER_ERR_NONFINITE if a prunable
+ *              weight is NaN.  NULL: no wait; a NaN is then reported by the next
+ *              waiting call on this context. */
+int shifter_global_threshold(shifter_ctx* ctx, const shifter_model* model,
+                             const float* d_w, const uint64_t* h_n_prune, uint32_t K,
+                             shifter_threshold* d_thr, shifter_threshold* h_thr);
+
+/* The sparse model (Sec. II-A; Sec. III-C): d_w_out[e] = removed ? +0.0f : d_w[e] for
+ * every element of every tensor (non-prunable tensors are copied), d_mask[g] = 0 for
+ * removed weights else 1.
+ *   d_thr        device, ONE record (as written by shifter_global_threshold)
+ *   d_w_out      device, w_extent floats; may equal d_w (in place); gaps between
+ *                tensors are not written
+ *   d_mask       device, N bytes, or NULL
+ *   d_out_alive, d_in_alive
+ *                both NULL, or both non-NULL: the scan of shifter_dead_channel_scan
+ *                is then done on the sparse values in the same pass (same outputs). */
+int shifter_apply_mask(shifter_ctx* ctx, const shifter_model* model, const float* d_w,
+                       const shifter_threshold* d_thr, float* d_w_out, uint8_t* d_mask,
+                       uint8_t* d_out_alive, uint8_t* d_in_alive);
+
+/* Module 2, Sparsity Analyser (Sec. III-D): a kernel is the kh x kw slice of one
+ * (filter, input feature) pair.  For every tensor t (prunable or not):
+ *   d_out_alive[out_flag_off[t] + o] = 1 iff filter o holds a non-zero, else 0
+ *   d_in_alive [in_flag_off[t]  + i] = 1 iff input feature i holds a non-zero in any
+ *                                       filter, else 0
+ * Arrays of sum_out_ch / sum_in_ch bytes, fully written.  -0.0 counts as zero. */
+int shifter_dead_channel_scan(shifter_ctx* ctx, const shifter_model* model,
+                              const float* d_w_sparse, uint8_t* d_out_alive,
+                              uint8_t* d_in_alive);
+
+/* Module 3, Prune Planner (Algorithm 1, Sec. III-D), stated on groups: channel c of
+ * group G survives iff G is pinned or some producer of G has out_alive on c (with
+ * SHIFTER_PAPER_FREEZE_RESIDUAL also iff G has more than one producer).  On a chain
+ * this gives, for layer n, C_out = zero filters of layer n and C_in = zero filters of
+ * layer n-1, and no C_in for the first layer.  Single pass: removing input channels
+ * never triggers further removals.  d_in_alive is accepted for symmetry and not used
+ * by either rule (may be NULL).
+ *   d_group_alive  device, sum_group_width bytes: 1 survives / 0 removed
+ *   d_index_map    device, sum_group_width int32: new index of a channel, or -1
+ *   d_keep         device, sum_group_width uint32: per group, the surviving old
+ *                  indices ascending, then UINT32_MAX up to the group's width
+ *   d_new_width    device, n_groups uint32
+ *   h_new_width    host, n_groups uint32, or NULL.  Non-NULL: waits for the stream and
+ *                  returns SHIFTER_WARN_COLLAPSE if some group kept no channel. */
+int shifter_propagate_groups(shifter_ctx* ctx, const shifter_model* model,
+                             const uint8_t* d_out_alive, const uint8_t* d_in_alive,
+                             uint32_t flags, uint8_t* d_group_alive,
+                             int32_t* d_index_map, uint32_t* d_keep,
+                             uint32_t* d_new_width, uint32_t* h_new_width);
+
+/* Module 4, Model Pruner (Algorithm 2, Sec. III-D): every layer rebuilt without its
+ * prunable channels.  For tensor t with out-group A, in-group B, m = in_mult:
+ *   W'[o', i', y, x] = W[keep_A[o'], keep_B[i' / m] * m + i' % m, y, x]
+ * and for every vector v of group A: v'[j] = v[keep_A[j]].  Outputs are dense, in
+ * descriptor order, row-major, the first tensor at element 0.
+ *   d_w_sparse, d_vecs   device, source arenas
+ *   d_keep, d_new_width  device, as written by shifter_propagate_groups
+ *   d_w_out, cap_w       device, capacity in floats (w_elems always suffices)
+ *   d_vecs_out, cap_v    device, capacity in floats (v_elems always suffices)
+ *   h_out_tensors        host, n_tensors descriptors of the rebuilt tensors, or NULL
+ *   h_out_vecs           host, n_vecs descriptors, or NULL
+ *   h_elems_w, h_elems_v host, floats written to each output arena, or NULL
+ * If any h_* is non-NULL the call waits for the stream and fills them.  When a
+ * capacity is too small nothing is gathered; a waiting call then returns
+ * SHIFTER_ERR_CAPACITY with the needed sizes in h_elems_w / h_elems_v. */
+int shifter_compact(shifter_ctx* ctx, const shifter_model* model, const float* d_w_sparse,
+                    const float* d_vecs, const uint32_t* d_keep,
+                    const uint32_t* d_new_width, float* d_w_out, uint64_t cap_w,
+                    float* d_vecs_out, uint64_t cap_v, shifter_tensor_desc* h_out_tensors,
+                    shifter_vec_desc* h_out_vecs, uint64_t* h_elems_w,
+                    uint64_t* h_elems_v);
+
+/* --- measurement ------------------------------------------------------------------- */
+
+/* Per-kernel timing with HIP events on the context's stream.  While enabled every
+ * kernel launch of this context is bracketed by two events.  shifter_profile_read waits
+ * for the stream, then for each kernel that ran since the last reset writes its name,
+ * launch count and total milliseconds (up to `cap` entries; returns the number in
+ * *n_out) and resets the records.  Names are static strings owned by the library. */
+int shifter_profile_enable(shifter_ctx* ctx, int on);
+int shifter_profile_read(shifter_ctx* ctx, const char** names, uint32_t* counts,
+                         double* total_ms, uint32_t cap, uint32_t* n_out);
+
+/* Plain device-to-device copy kernel of n floats (dwordx4 loads and stores), used to
+ * calibrate the memory-traffic counters against a transfer of known size and to
+ * measure the copy bandwidth this chip sustains. */
+int shifter_copy_f32(shifter_ctx* ctx, const float* d_src, float* d_dst, uint64_t n);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SHIFTER_H */

@@ -1,0 +1,508 @@
+// Host side of the C ABI: descriptor validation, device tables and scratch, argument
+// checks, stream-ordered launches and the small read-backs the ABI documents.
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "internal.h"
+
+using namespace shifter;
+
+namespace shifter {
+const char* const kKernelNames[K_COUNT] = {
+    "sel_init", "hist_round0", "hist_round1", "hist_round2", "select", "tie_count",
+    "tie_final", "zero_flags", "mask_scan", "scan", "propagate", "plan", "gather",
+    "gather_vec", "copy"};
+
+ProfileScope::ProfileScope(shifter_ctx* c, int id) : ctx(c), idx(-1) {
+    if (!c->profiling) return;
+    hipEvent_t a = nullptr, b = nullptr;
+    if (c->pool.size() >= 2) {
+        a = c->pool.back(); c->pool.pop_back();
+        b = c->pool.back(); c->pool.pop_back();
+    } else if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
+        return;
+    }
+    (void)hipEventRecord(a, c->stream);
+    c->recs.push_back({id, a, b});
+    idx = (int)c->recs.size() - 1;
+}
+ProfileScope::~ProfileScope() {
+    if (idx >= 0) (void)hipEventRecord(ctx->recs[idx].b, ctx->stream);
+}
+}  // namespace shifter
+
+static thread_local std::string g_err;
+
+static int fail(shifter_ctx* ctx, int code, const std::string& msg) {
+    g_err = msg;
+    if (ctx) ctx->err = msg;
+    return code;
+}
+
+#define HIP_TRY(ctx, expr)                                                              \
+    do {                                                                                \
+        hipError_t e_ = (expr);                                                         \
+        if (e_ != hipSuccess)                                                           \
+            return fail(ctx, e_ == hipErrorOutOfMemory ? SHIFTER_ERR_OOM : SHIFTER_ERR_HIP, \
+                        std::string(#expr) + ": " + hipGetErrorString(e_));             \
+    } while (0)
+
+extern "C" const char* shifter_last_error(const shifter_ctx* ctx) {
+    return ctx ? ctx->err.c_str() : g_err.c_str();
+}
+
+extern "C" int shifter_create(shifter_ctx** out, int device, void* hip_stream) {
+    if (!out) return fail(nullptr, SHIFTER_ERR_INVALID_ARG, "shifter_create: out is NULL");
+    *out = nullptr;
+    int n = 0;
+    if (hipGetDeviceCount(&n) != hipSuccess || n <= 0) {
+        (void)hipGetLastError();
+        return fail(nullptr, SHIFTER_ERR_NO_DEVICE, "shifter_create: no HIP device visible");
+    }
+    if (device < 0 || device >= n)
+        return fail(nullptr, SHIFTER_ERR_NO_DEVICE, "shifter_create: device ordinal out of range");
+    HIP_TRY(nullptr, hipSetDevice(device));
+    shifter_ctx* c = new (std::nothrow) shifter_ctx();
+    if (!c) return fail(nullptr, SHIFTER_ERR_OOM, "shifter_create: host allocation failed");
+    c->device = device;
+    c->stream = reinterpret_cast<hipStream_t>(hip_stream);
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device) == hipSuccess && prop.multiProcessorCount > 0)
+        c->hist_grid = (uint32_t)prop.multiProcessorCount * 8u;
+    *out = c;
+    return SHIFTER_OK;
+}
+
+static void unbind(shifter_model* m) {
+    auto& b = m->b;
+    if (!b.ctx) return;
+    (void)hipSetDevice(b.device);
+    void* ptrs[] = {b.tens, b.groups, b.vecs, b.producers, b.tile_prefix, b.sel, b.ghist,
+                    b.tile_cnt, b.plan_t, b.plan_v, b.plan_h, b.out_tile_prefix};
+    for (void* p : ptrs)
+        if (p) (void)hipFree(p);
+    if (b.host_stage) (void)hipHostFree(b.host_stage);
+    b = shifter_model::Bound();
+}
+
+extern "C" int shifter_destroy(shifter_ctx* ctx) {
+    if (!ctx) return SHIFTER_OK;
+    (void)hipSetDevice(ctx->device);
+    (void)hipStreamSynchronize(ctx->stream);
+    for (auto& r : ctx->recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+    for (auto e : ctx->pool) (void)hipEventDestroy(e);
+    delete ctx;
+    return SHIFTER_OK;
+}
+
+static uint32_t magic_for(uint32_t d) {
+    if (d <= 1 || d > 2 * TILE) return 0;
+    return (uint32_t)((1ull << 32) / d) + 1u;
+}
+
+extern "C" int shifter_model_create(const shifter_tensor_desc* tensors, uint32_t n_tensors,
+                                    const shifter_vec_desc* vecs, uint32_t n_vecs,
+                                    const shifter_group_desc* groups, uint32_t n_groups,
+                                    shifter_model** out) {
+    if (!out) return fail(nullptr, SHIFTER_ERR_INVALID_ARG, "model_create: out is NULL");
+    *out = nullptr;
+    if (!tensors || !groups || n_tensors == 0 || n_groups == 0 || (n_vecs && !vecs))
+        return fail(nullptr, SHIFTER_ERR_INVALID_ARG,
+                    "model_create: tensors and groups must be non-empty, non-NULL");
+    if (n_tensors > 65535u)
+        return fail(nullptr, SHIFTER_ERR_BAD_MODEL, "model_create: more than 65535 tensors");
+    char buf[256];
+    shifter_model* m = new (std::nothrow) shifter_model();
+    if (!m) return fail(nullptr, SHIFTER_ERR_OOM, "model_create: host allocation failed");
+    auto bad = [&](const char* what, uint32_t idx) {
+        snprintf(buf, sizeof buf, "model_create: %s (index %u)", what, idx);
+        delete m;
+        return fail(nullptr, SHIFTER_ERR_BAD_MODEL, buf);
+    };
+    m->t.assign(tensors, tensors + n_tensors);
+    m->g.assign(groups, groups + n_groups);
+    if (n_vecs) m->v.assign(vecs, vecs + n_vecs);
+
+    uint64_t goff = 0;
+    m->dg.resize(n_groups);
+    for (uint32_t g = 0; g < n_groups; ++g) {
+        if (groups[g].width == 0) return bad("group of width 0", g);
+        m->group_off.push_back(goff);
+        m->dg[g].width = groups[g].width;
+        m->dg[g].pinned = groups[g].pinned ? 1u : 0u;
+        m->dg[g].off = (uint32_t)goff;
+        goff += groups[g].width;
+        if (goff >= (1ull << 32)) return bad("sum of group widths reaches 2^32", g);
+    }
+    uint64_t gbase = 0, so = 0, si = 0, w_ext = 0, w_el = 0, tiles = 0;
+    m->dt.resize(n_tensors);
+    std::vector<std::pair<uint64_t, uint64_t>> spans;
+    for (uint32_t i = 0; i < n_tensors; ++i) {
+        const shifter_tensor_desc& t = tensors[i];
+        if (!t.out_ch || !t.in_ch || !t.kh || !t.kw || !t.in_mult) return bad("zero-sized tensor dimension", i);
+        if (t.out_group < 0 || (uint32_t)t.out_group >= n_groups || t.in_group < 0 ||
+            (uint32_t)t.in_group >= n_groups)
+            return bad("tensor group index out of range", i);
+        if (groups[t.out_group].width != t.out_ch) return bad("out_ch differs from the width of out_group", i);
+        if ((uint64_t)groups[t.in_group].width * t.in_mult != t.in_ch)
+            return bad("in_ch differs from width of in_group times in_mult", i);
+        const uint64_t khw = (uint64_t)t.kh * t.kw;
+        const uint64_t numel = (uint64_t)t.out_ch * t.in_ch * khw;
+        if (khw >= (1ull << 32) || numel >= (1ull << 32) || khw * t.in_mult >= (1ull << 32))
+            return bad("tensor of 2^32 or more elements", i);
+        DevTensor& d = m->dt[i];
+        d.offset = t.offset;
+        d.gbase = t.prunable ? gbase : 0;
+        d.numel = (uint32_t)numel;
+        d.out_ch = t.out_ch;
+        d.in_ch = t.in_ch;
+        d.khw = (uint32_t)khw;
+        d.row_len = (uint32_t)(t.in_ch * khw);
+        d.kk = (uint32_t)(khw * t.in_mult);
+        d.cin = t.in_ch / t.in_mult;
+        d.magic_khw = magic_for(d.khw);
+        d.magic_row = magic_for(d.row_len);
+        d.magic_in = magic_for(d.in_ch);
+        d.out_group = t.out_group;
+        d.in_group = t.in_group;
+        d.out_flag_off = (uint32_t)so;
+        d.in_flag_off = (uint32_t)si;
+        d.prunable = t.prunable ? 1u : 0u;
+        d.pad = 0;
+        m->out_flag_off.push_back(so);
+        m->in_flag_off.push_back(si);
+        m->tile_prefix.push_back((uint32_t)tiles);
+        so += t.out_ch;
+        si += t.in_ch;
+        if (t.prunable) gbase += numel;
+        tiles += (numel + TILE - 1) / TILE;
+        w_el += numel;
+        w_ext = std::max(w_ext, t.offset + numel);
+        spans.push_back({t.offset, t.offset + numel});
+        if (so >= (1ull << 32) || si >= (1ull << 32) || tiles >= (1ull << 31))
+            return bad("model too large for 32-bit flag or tile indices", i);
+    }
+    m->tile_prefix.push_back((uint32_t)tiles);
+    m->n_tiles = (uint32_t)tiles;
+    if (gbase >= (1ull << 32) - 1) return bad("N (prunable weights) reaches 2^32 - 1", n_tensors - 1);
+    std::sort(spans.begin(), spans.end());
+    for (size_t i = 1; i < spans.size(); ++i)
+        if (spans[i].first < spans[i - 1].second) return bad("tensors overlap in the weight arena", (uint32_t)i);
+
+    uint64_t v_ext = 0, v_el = 0;
+    m->dv.resize(n_vecs);
+    spans.clear();
+    for (uint32_t i = 0; i < n_vecs; ++i) {
+        const shifter_vec_desc& v = vecs[i];
+        if (v.group < 0 || (uint32_t)v.group >= n_groups) return bad("vector group index out of range", i);
+        if (groups[v.group].width != v.len) return bad("vector length differs from the width of its group", i);
+        m->dv[i] = {v.offset, v.len, v.group};
+        v_ext = std::max(v_ext, v.offset + v.len);
+        v_el += v.len;
+        spans.push_back({v.offset, v.offset + v.len});
+    }
+    std::sort(spans.begin(), spans.end());
+    for (size_t i = 1; i < spans.size(); ++i)
+        if (spans[i].first < spans[i - 1].second) return bad("vectors overlap in the vector arena", (uint32_t)i);
+
+    // producers of each group, in tensor order
+    for (uint32_t g = 0; g < n_groups; ++g) {
+        m->dg[g].prod_begin = (uint32_t)m->producers.size();
+        for (uint32_t i = 0; i < n_tensors; ++i)
+            if ((uint32_t)tensors[i].out_group == g) m->producers.push_back(i);
+        m->dg[g].prod_end = (uint32_t)m->producers.size();
+        m->dg[g].pad = 0;
+    }
+    shifter_model_info& inf = m->info;
+    inf.n_prunable = gbase;
+    inf.w_extent = w_ext;
+    inf.v_extent = v_ext;
+    inf.w_elems = w_el;
+    inf.v_elems = v_el;
+    inf.sum_out_ch = so;
+    inf.sum_in_ch = si;
+    inf.sum_group_width = goff;
+    inf.n_tensors = n_tensors;
+    inf.n_vecs = n_vecs;
+    inf.n_groups = n_groups;
+    inf.reserved = 0;
+    *out = m;
+    return SHIFTER_OK;
+}
+
+extern "C" int shifter_model_destroy(shifter_model* m) {
+    if (!m) return SHIFTER_OK;
+    unbind(m);
+    delete m;
+    return SHIFTER_OK;
+}
+
+extern "C" int shifter_model_get_info(const shifter_model* m, shifter_model_info* out) {
+    if (!m || !out) return fail(nullptr, SHIFTER_ERR_INVALID_ARG, "model_get_info: NULL argument");
+    *out = m->info;
+    return SHIFTER_OK;
+}
+
+extern "C" int shifter_model_get_layout(const shifter_model* m, uint64_t* h_out_flag_off,
+                                        uint64_t* h_in_flag_off, uint64_t* h_group_off) {
+    if (!m) return fail(nullptr, SHIFTER_ERR_INVALID_ARG, "model_get_layout: model is NULL");
+    if (h_out_flag_off) std::copy(m->out_flag_off.begin(), m->out_flag_off.end(), h_out_flag_off);
+    if (h_in_flag_off) std::copy(m->in_flag_off.begin(), m->in_flag_off.end(), h_in_flag_off);
+    if (h_group_off) std::copy(m->group_off.begin(), m->group_off.end(), h_group_off);
+    return SHIFTER_OK;
+}
+
+template <typename T>
+static int upload(shifter_ctx* ctx, T** dptr, const T* src, size_t n) {
+    const size_t bytes = std::max<size_t>(n, 1) * sizeof(T);
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(dptr), bytes));
+    if (n) HIP_TRY(ctx, hipMemcpy(*dptr, src, n * sizeof(T), hipMemcpyHostToDevice));
+    return SHIFTER_OK;
+}
+
+// Device tables and scratch of a model, created once per (model, context).
+static int bind(shifter_ctx* ctx, const shifter_model* cm) {
+    shifter_model* m = const_cast<shifter_model*>(cm);
+    if (m->b.ctx == ctx) return SHIFTER_OK;
+    unbind(m);
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    auto& b = m->b;
+    b.ctx = ctx;
+    b.device = ctx->device;
+    int rc;
+    const size_t n_t = m->t.size(), n_v = m->v.size();
+    if ((rc = upload(ctx, &b.tens, m->dt.data(), n_t))) return rc;
+    if ((rc = upload(ctx, &b.groups, m->dg.data(), m->dg.size()))) return rc;
+    if ((rc = upload(ctx, &b.vecs, m->dv.data(), n_v))) return rc;
+    if ((rc = upload(ctx, &b.producers, m->producers.data(), m->producers.size()))) return rc;
+    if ((rc = upload(ctx, &b.tile_prefix, m->tile_prefix.data(), m->tile_prefix.size()))) return rc;
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.sel), sizeof(SelState)));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.ghist), sizeof(uint32_t) * MAXK * HIST_BINS));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.tile_cnt),
+                           sizeof(uint32_t) * (size_t)MAXK * std::max<uint32_t>(m->n_tiles, 1)));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.plan_t), sizeof(PlanTensor) * n_t));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.plan_v), sizeof(PlanVec) * std::max<size_t>(n_v, 1)));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.plan_h), sizeof(PlanHeader)));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.out_tile_prefix), sizeof(uint32_t) * (n_t + 1)));
+    b.host_stage_bytes = sizeof(SelState) + sizeof(shifter_threshold) * MAXK + sizeof(PlanHeader) +
+                         sizeof(PlanTensor) * n_t + sizeof(PlanVec) * n_v +
+                         sizeof(uint32_t) * m->g.size() + 256;
+    HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&b.host_stage), b.host_stage_bytes, hipHostMallocDefault));
+    return SHIFTER_OK;
+}
+
+static int enter(shifter_ctx* ctx, const shifter_model* m, const char* fn) {
+    if (!ctx) return fail(nullptr, SHIFTER_ERR_INVALID_ARG, std::string(fn) + ": ctx is NULL");
+    if (!m) return fail(ctx, SHIFTER_ERR_INVALID_ARG, std::string(fn) + ": model is NULL");
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    return bind(ctx, m);
+}
+
+static bool misaligned(const void* p, uintptr_t a) {
+    return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0;
+}
+
+static int after_launch(shifter_ctx* ctx, const char* fn) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess)
+        return fail(ctx, SHIFTER_ERR_HIP, std::string(fn) + ": launch failed: " + hipGetErrorString(e));
+    return SHIFTER_OK;
+}
+
+extern "C" int shifter_global_threshold(shifter_ctx* ctx, const shifter_model* model,
+                                        const float* d_w, const uint64_t* h_n_prune, uint32_t K,
+                                        shifter_threshold* d_thr, shifter_threshold* h_thr) {
+    int rc = enter(ctx, model, "global_threshold");
+    if (rc) return rc;
+    if (!d_w || !h_n_prune || !d_thr)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "global_threshold: NULL pointer argument");
+    if (misaligned(d_w, 16) || misaligned(d_thr, 8))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "global_threshold: d_w must be 16-byte aligned");
+    if (K == 0 || K > MAXK)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "global_threshold: K must be in [1, SHIFTER_MAX_VARIANTS]");
+    PruneCounts pc;
+    memset(&pc, 0, sizeof pc);
+    for (uint32_t k = 0; k < K; ++k) {
+        if (h_n_prune[k] > model->info.n_prunable)
+            return fail(ctx, SHIFTER_ERR_INVALID_ARG, "global_threshold: prune count exceeds N");
+        pc.p[k] = h_n_prune[k];
+    }
+    launch_select(ctx, model, d_w, pc, K, d_thr);
+    if ((rc = after_launch(ctx, "global_threshold"))) return rc;
+    if (h_thr) {
+        uint8_t* st = model->b.host_stage;
+        HIP_TRY(ctx, hipMemcpyAsync(st, d_thr, sizeof(shifter_threshold) * K, hipMemcpyDeviceToHost, ctx->stream));
+        HIP_TRY(ctx, hipMemcpyAsync(st + sizeof(shifter_threshold) * MAXK, &model->b.sel->nan_seen,
+                                    sizeof(uint32_t), hipMemcpyDeviceToHost, ctx->stream));
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+        memcpy(h_thr, st, sizeof(shifter_threshold) * K);
+        uint32_t nan_seen;
+        memcpy(&nan_seen, st + sizeof(shifter_threshold) * MAXK, sizeof nan_seen);
+        if (nan_seen)
+            return fail(ctx, SHIFTER_ERR_NONFINITE, "global_threshold: NaN among the prunable weights");
+    }
+    return SHIFTER_OK;
+}
+
+extern "C" int shifter_apply_mask(shifter_ctx* ctx, const shifter_model* model, const float* d_w,
+                                  const shifter_threshold* d_thr, float* d_w_out, uint8_t* d_mask,
+                                  uint8_t* d_out_alive, uint8_t* d_in_alive) {
+    int rc = enter(ctx, model, "apply_mask");
+    if (rc) return rc;
+    if (!d_w || !d_thr || !d_w_out)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "apply_mask: NULL pointer argument");
+    if (misaligned(d_w, 16) || misaligned(d_w_out, 16) || misaligned(d_mask, 4) || misaligned(d_thr, 8))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG,
+                    "apply_mask: arenas must be 16-byte aligned, the mask 4-byte aligned");
+    if ((d_out_alive == nullptr) != (d_in_alive == nullptr))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG,
+                    "apply_mask: d_out_alive and d_in_alive must both be NULL or both be given");
+    launch_mask_scan(ctx, model, d_w, d_thr, d_w_out, d_mask, d_out_alive, d_in_alive);
+    return after_launch(ctx, "apply_mask");
+}
+
+extern "C" int shifter_dead_channel_scan(shifter_ctx* ctx, const shifter_model* model,
+                                         const float* d_w_sparse, uint8_t* d_out_alive,
+                                         uint8_t* d_in_alive) {
+    int rc = enter(ctx, model, "dead_channel_scan");
+    if (rc) return rc;
+    if (!d_w_sparse || !d_out_alive || !d_in_alive)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "dead_channel_scan: NULL pointer argument");
+    if (misaligned(d_w_sparse, 16))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "dead_channel_scan: arena must be 16-byte aligned");
+    launch_scan(ctx, model, d_w_sparse, d_out_alive, d_in_alive);
+    return after_launch(ctx, "dead_channel_scan");
+}
+
+extern "C" int shifter_propagate_groups(shifter_ctx* ctx, const shifter_model* model,
+                                        const uint8_t* d_out_alive, const uint8_t* d_in_alive,
+                                        uint32_t flags, uint8_t* d_group_alive,
+                                        int32_t* d_index_map, uint32_t* d_keep,
+                                        uint32_t* d_new_width, uint32_t* h_new_width) {
+    (void)d_in_alive;
+    int rc = enter(ctx, model, "propagate_groups");
+    if (rc) return rc;
+    if (!d_out_alive || !d_group_alive || !d_index_map || !d_keep || !d_new_width)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "propagate_groups: NULL pointer argument");
+    if (flags & ~SHIFTER_PAPER_FREEZE_RESIDUAL)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "propagate_groups: unknown flag bits");
+    launch_propagate(ctx, model, d_out_alive, flags, d_group_alive, d_index_map, d_keep, d_new_width);
+    if ((rc = after_launch(ctx, "propagate_groups"))) return rc;
+    if (h_new_width) {
+        const size_t n_g = model->g.size();
+        uint32_t* st = reinterpret_cast<uint32_t*>(model->b.host_stage);
+        HIP_TRY(ctx, hipMemcpyAsync(st, d_new_width, sizeof(uint32_t) * n_g, hipMemcpyDeviceToHost, ctx->stream));
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+        bool collapse = false;
+        for (size_t g = 0; g < n_g; ++g) {
+            h_new_width[g] = st[g];
+            collapse |= st[g] == 0;
+        }
+        if (collapse) {
+            fail(ctx, SHIFTER_WARN_COLLAPSE, "propagate_groups: a group kept no channel (layer collapse)");
+            return SHIFTER_WARN_COLLAPSE;
+        }
+    }
+    return SHIFTER_OK;
+}
+
+extern "C" int shifter_compact(shifter_ctx* ctx, const shifter_model* model, const float* d_w_sparse,
+                               const float* d_vecs, const uint32_t* d_keep,
+                               const uint32_t* d_new_width, float* d_w_out, uint64_t cap_w,
+                               float* d_vecs_out, uint64_t cap_v,
+                               shifter_tensor_desc* h_out_tensors, shifter_vec_desc* h_out_vecs,
+                               uint64_t* h_elems_w, uint64_t* h_elems_v) {
+    int rc = enter(ctx, model, "compact");
+    if (rc) return rc;
+    const size_t n_t = model->t.size(), n_v = model->v.size();
+    if (!d_w_sparse || !d_keep || !d_new_width || !d_w_out || (n_v && (!d_vecs || !d_vecs_out)))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "compact: NULL pointer argument");
+    launch_compact(ctx, model, d_w_sparse, d_vecs, d_keep, d_new_width, d_w_out, cap_w, d_vecs_out, cap_v);
+    if ((rc = after_launch(ctx, "compact"))) return rc;
+    if (h_out_tensors || h_out_vecs || h_elems_w || h_elems_v) {
+        const auto& b = model->b;
+        uint8_t* st = b.host_stage;
+        PlanHeader* hh = reinterpret_cast<PlanHeader*>(st);
+        PlanTensor* ht = reinterpret_cast<PlanTensor*>(st + sizeof(PlanHeader));
+        PlanVec* hv = reinterpret_cast<PlanVec*>(st + sizeof(PlanHeader) + sizeof(PlanTensor) * n_t);
+        HIP_TRY(ctx, hipMemcpyAsync(hh, b.plan_h, sizeof(PlanHeader), hipMemcpyDeviceToHost, ctx->stream));
+        HIP_TRY(ctx, hipMemcpyAsync(ht, b.plan_t, sizeof(PlanTensor) * n_t, hipMemcpyDeviceToHost, ctx->stream));
+        if (n_v) HIP_TRY(ctx, hipMemcpyAsync(hv, b.plan_v, sizeof(PlanVec) * n_v, hipMemcpyDeviceToHost, ctx->stream));
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+        if (h_elems_w) *h_elems_w = hh->elems_w;
+        if (h_elems_v) *h_elems_v = hh->elems_v;
+        if (h_out_tensors) {
+            for (size_t i = 0; i < n_t; ++i) {
+                shifter_tensor_desc d = model->t[i];
+                d.offset = ht[i].out_off;
+                d.out_ch = ht[i].o2;
+                d.in_ch = ht[i].c2 * d.in_mult;
+                h_out_tensors[i] = d;
+            }
+        }
+        if (h_out_vecs) {
+            for (size_t i = 0; i < n_v; ++i) {
+                shifter_vec_desc d = model->v[i];
+                d.offset = hv[i].out_off;
+                d.len = hv[i].len2;
+                h_out_vecs[i] = d;
+            }
+        }
+        if (hh->status & 1u)
+            return fail(ctx, SHIFTER_ERR_CAPACITY, "compact: output capacity too small; nothing gathered");
+        if (hh->status & 2u) {
+            fail(ctx, SHIFTER_WARN_COLLAPSE, "compact: a group kept no channel (layer collapse)");
+            return SHIFTER_WARN_COLLAPSE;
+        }
+    }
+    return SHIFTER_OK;
+}
+
+extern "C" int shifter_profile_enable(shifter_ctx* ctx, int on) {
+    if (!ctx) return fail(nullptr, SHIFTER_ERR_INVALID_ARG, "profile_enable: ctx is NULL");
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    ctx->profiling = on != 0;
+    return SHIFTER_OK;
+}
+
+extern "C" int shifter_profile_read(shifter_ctx* ctx, const char** names, uint32_t* counts,
+                                    double* total_ms, uint32_t cap, uint32_t* n_out) {
+    if (!ctx || !n_out) return fail(ctx, SHIFTER_ERR_INVALID_ARG, "profile_read: NULL argument");
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    uint32_t cnt[K_COUNT] = {0};
+    double ms[K_COUNT] = {0};
+    for (auto& r : ctx->recs) {
+        float t = 0;
+        if (hipEventElapsedTime(&t, r.a, r.b) == hipSuccess) {
+            cnt[r.id]++;
+            ms[r.id] += t;
+        }
+        ctx->pool.push_back(r.a);
+        ctx->pool.push_back(r.b);
+    }
+    ctx->recs.clear();
+    uint32_t n = 0;
+    for (int i = 0; i < K_COUNT; ++i) {
+        if (!cnt[i]) continue;
+        if (n < cap && names && counts && total_ms) {
+            names[n] = kKernelNames[i];
+            counts[n] = cnt[i];
+            total_ms[n] = ms[i];
+        }
+        ++n;
+    }
+    *n_out = n < cap ? n : cap;
+    return SHIFTER_OK;
+}
+
+extern "C" int shifter_copy_f32(shifter_ctx* ctx, const float* d_src, float* d_dst, uint64_t n) {
+    if (!ctx || !d_src || !d_dst) return fail(ctx, SHIFTER_ERR_INVALID_ARG, "copy_f32: NULL argument");
+    if ((reinterpret_cast<uintptr_t>(d_src) | reinterpret_cast<uintptr_t>(d_dst)) & 15u)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "copy_f32: pointers must be 16-byte aligned");
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    launch_copy(ctx, d_src, d_dst, n);
+    return after_launch(ctx, "copy_f32");
+}

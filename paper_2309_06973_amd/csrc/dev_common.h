@@ -1,0 +1,57 @@
+// Device helpers shared by the kernels (wave64, gfx950).
+#pragma once
+
+#include "internal.h"
+
+namespace shifter {
+
+// Largest t with prefix[t] <= tile; requires prefix[0] <= tile < prefix[n].
+// `tile` is uniform over the block, so the search runs on scalar registers.
+__device__ __forceinline__ uint32_t find_tensor(const uint32_t* __restrict__ prefix,
+                                                uint32_t n, uint32_t tile) {
+    uint32_t lo = 0, hi = n;
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (prefix[mid] <= tile) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// Small-quotient division used to index tile-relative flag slots.  The host sets
+// magic = floor(2^32 / d) + 1 when 1 < d <= 2 * TILE (exact while x * d < 2^32, and here
+// x < d + TILE + 2); for larger d the callers guarantee x < 2 * d.
+__device__ __forceinline__ uint32_t div_small(uint32_t x, uint32_t d, uint32_t magic) {
+    return d == 1 ? x : (magic ? __umulhi(x, magic) : (x >= d ? 1u : 0u));
+}
+__device__ __forceinline__ uint32_t mod_small(uint32_t x, uint32_t d, uint32_t magic) {
+    return d == 1 ? 0u : (magic ? x - __umulhi(x, magic) * d : (x >= d ? x - d : x));
+}
+
+__device__ __forceinline__ uint32_t key_of(float w) {
+    return __float_as_uint(w) & 0x7fffffffu;
+}
+
+// Exclusive scan of one u64 per thread over a block of BLOCK threads.
+// smem: at least BLOCK / 64 + 1 entries.  Contains two barriers.
+__device__ __forceinline__ uint64_t block_excl_scan_u64(uint64_t v, uint64_t* smem,
+                                                        uint64_t* total) {
+    const uint32_t lane = threadIdx.x & 63u, wid = threadIdx.x >> 6;
+    unsigned long long x = v;
+    for (uint32_t d = 1; d < 64; d <<= 1) {
+        const unsigned long long y = __shfl_up(x, d, 64);
+        if (lane >= d) x += y;
+    }
+    __syncthreads();   // protects smem against a previous use
+    if (lane == 63) smem[wid] = x;
+    __syncthreads();
+    uint64_t woff = 0, tot = 0;
+    for (uint32_t i = 0; i < BLOCK / 64; ++i) {
+        const uint64_t s = smem[i];
+        if (i < wid) woff += s;
+        tot += s;
+    }
+    *total = tot;
+    return woff + x - v;
+}
+
+}  // namespace shifter

@@ -1,0 +1,174 @@
+// Internal declarations shared by the host API and the kernel launchers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "shifter.h"
+
+namespace shifter {
+
+constexpr uint32_t TILE = 4096;      // elements per tile of the streaming kernels
+constexpr uint32_t BLOCK = 256;      // threads per block (4 wavefronts of 64)
+constexpr uint32_t HIST_BINS = 2048; // stride of one histogram slot
+constexpr uint32_t MAXK = SHIFTER_MAX_VARIANTS;
+constexpr uint32_t SLOTS_PER_PASS = 8;
+
+// Device-side view of one weight tensor.
+struct DevTensor {
+    uint64_t offset;     // element offset in the weight arena
+    uint64_t gbase;      // global index of element 0 (0 if not prunable)
+    uint32_t numel;
+    uint32_t out_ch, in_ch, khw;
+    uint32_t row_len;    // in_ch * khw: elements per filter
+    uint32_t kk;         // khw * in_mult: elements per (filter, input channel)
+    uint32_t cin;        // in_ch / in_mult: width of the in-group
+    uint32_t magic_khw;  // floor(2^32 / khw) + 1 when 1 < khw <= 2 * TILE, else 0
+    uint32_t magic_row;  // same for row_len
+    uint32_t magic_in;   // same for in_ch
+    int32_t out_group, in_group;
+    uint32_t out_flag_off, in_flag_off;
+    uint32_t prunable;
+    uint32_t pad;
+};
+
+struct DevGroup {
+    uint32_t width, pinned;
+    uint32_t off;        // offset in the per-group arrays
+    uint32_t prod_begin, prod_end;  // range in the producer list
+    uint32_t pad;
+};
+
+struct DevVec {
+    uint64_t offset;
+    uint32_t len;
+    int32_t group;
+};
+
+// State of the multi-rank radix select, one entry per requested prune count.
+struct SelRank {
+    uint64_t rank;     // remaining 1-based rank inside the current prefix; 0: P == 0
+    uint64_t n_less;   // weights known to be smaller than every key with this prefix
+    uint64_t n_equal;  // weights sharing the prefix
+    uint32_t prefix;   // decided high bits of the key, right aligned
+    uint32_t slot;     // histogram slot of this prefix in the next round
+};
+
+struct SelState {
+    SelRank r[MAXK];
+    uint32_t slot_prefix[MAXK];
+    uint32_t n_slots;
+    uint32_t k;
+    uint32_t nan_seen;
+    uint32_t pad;
+};
+
+struct PruneCounts {
+    uint64_t p[MAXK];
+};
+
+// Device-side rebuild plan (sizes and offsets of the compacted tensors).
+struct PlanTensor {
+    uint64_t out_off;
+    uint32_t o2, c2;     // surviving filters, surviving input channels
+    uint32_t numel2;
+    uint32_t pad;
+};
+
+struct PlanVec {
+    uint64_t out_off;
+    uint32_t len2;
+    uint32_t pad;
+};
+
+struct PlanHeader {
+    uint64_t elems_w, elems_v;
+    uint32_t total_tiles;
+    uint32_t status;     // bit 0: capacity exceeded; bit 1: some group collapsed
+};
+
+enum KernelId {
+    K_SEL_INIT = 0, K_HIST0, K_HIST1, K_HIST2, K_SELECT, K_TIE_COUNT, K_TIE_FINAL,
+    K_ZERO_FLAGS, K_MASK_SCAN, K_SCAN, K_PROPAGATE, K_PLAN, K_GATHER, K_GATHER_VEC,
+    K_COPY, K_COUNT
+};
+extern const char* const kKernelNames[K_COUNT];
+
+}  // namespace shifter
+
+struct shifter_model {
+    std::vector<shifter_tensor_desc> t;
+    std::vector<shifter_vec_desc> v;
+    std::vector<shifter_group_desc> g;
+    shifter_model_info info{};
+    std::vector<shifter::DevTensor> dt;
+    std::vector<shifter::DevGroup> dg;
+    std::vector<shifter::DevVec> dv;
+    std::vector<uint32_t> producers;     // tensor indices, grouped by out_group
+    std::vector<uint32_t> tile_prefix;   // n_tensors + 1
+    std::vector<uint64_t> out_flag_off, in_flag_off, group_off;
+    uint32_t n_tiles = 0;
+
+    // device side, created by the first call that uses the model with a context
+    struct Bound {
+        shifter_ctx* ctx = nullptr;
+        int device = 0;
+        shifter::DevTensor* tens = nullptr;
+        shifter::DevGroup* groups = nullptr;
+        shifter::DevVec* vecs = nullptr;
+        uint32_t* producers = nullptr;
+        uint32_t* tile_prefix = nullptr;
+        shifter::SelState* sel = nullptr;
+        uint32_t* ghist = nullptr;       // MAXK * HIST_BINS
+        uint32_t* tile_cnt = nullptr;    // MAXK * n_tiles
+        shifter::PlanTensor* plan_t = nullptr;
+        shifter::PlanVec* plan_v = nullptr;
+        shifter::PlanHeader* plan_h = nullptr;
+        uint32_t* out_tile_prefix = nullptr;  // n_tensors + 1
+        uint8_t* host_stage = nullptr;        // pinned, for small read-backs
+        size_t host_stage_bytes = 0;
+    } b;
+};
+
+struct shifter_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    std::string err;
+    bool profiling = false;
+    struct Rec { int id; hipEvent_t a, b; };
+    std::vector<Rec> recs;
+    std::vector<hipEvent_t> pool;
+    uint32_t hist_grid = 2048;
+};
+
+namespace shifter {
+
+// Launchers (defined next to their kernels).  All enqueue on ctx->stream.
+void launch_select(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
+                   const PruneCounts& pc, uint32_t k, shifter_threshold* d_thr);
+void launch_mask_scan(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
+                      const shifter_threshold* d_thr, float* d_w_out, uint8_t* d_mask,
+                      uint8_t* d_out_alive, uint8_t* d_in_alive);
+void launch_scan(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
+                 uint8_t* d_out_alive, uint8_t* d_in_alive);
+void launch_propagate(shifter_ctx* ctx, const shifter_model* m, const uint8_t* d_out_alive,
+                      uint32_t flags, uint8_t* d_group_alive, int32_t* d_index_map,
+                      uint32_t* d_keep, uint32_t* d_new_width);
+void launch_compact(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
+                    const float* d_vecs, const uint32_t* d_keep,
+                    const uint32_t* d_new_width, float* d_w_out, uint64_t cap_w,
+                    float* d_vecs_out, uint64_t cap_v);
+void launch_copy(shifter_ctx* ctx, const float* src, float* dst, uint64_t n);
+
+// Event bracketing for per-kernel timing.
+struct ProfileScope {
+    shifter_ctx* ctx;
+    int idx;
+    ProfileScope(shifter_ctx* c, int id);
+    ~ProfileScope();
+};
+
+}  // namespace shifter

@@ -1,0 +1,87 @@
+"""Device-side buffers for one network and the five calls of the pass in order.
+
+Buffer management and argument marshalling only: every step runs in libshifter's HIP
+kernels on the current torch stream.  Raises if no ROCm device is visible."""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import shifter as S
+
+
+class Pipeline:
+    def __init__(self, spec, w: np.ndarray, v: np.ndarray, device: int = 0,
+                 max_variants: int = S.SHIFTER_MAX_VARIANTS):
+        if not torch.cuda.is_available():
+            raise RuntimeError("no ROCm device visible: the prune-and-compact pass has no "
+                               "CPU path")
+        self.spec = spec
+        self.dev = torch.device("cuda", device)
+        torch.cuda.set_device(self.dev)
+        self.ctx = S.shifter_create(device, torch.cuda.current_stream().cuda_stream)
+        self.model = S.shifter_model_create(spec.tensors, spec.vecs, spec.groups)
+        info = self.model.info
+        assert w.size >= info.w_extent and v.size >= info.v_extent
+        u8 = dict(dtype=torch.uint8, device=self.dev)
+        self.d_w = torch.from_numpy(w).to(self.dev)
+        self.d_vecs = torch.from_numpy(v).to(self.dev)
+        self.d_w_sparse = torch.empty_like(self.d_w)
+        self.d_mask = torch.empty(max(info.n_prunable, 4), **u8)
+        self.d_out_alive = torch.empty(info.sum_out_ch, **u8)
+        self.d_in_alive = torch.empty(info.sum_in_ch, **u8)
+        self.d_group_alive = torch.empty(info.sum_group_width, **u8)
+        self.d_index_map = torch.empty(info.sum_group_width, dtype=torch.int32, device=self.dev)
+        self.d_keep = torch.empty(info.sum_group_width, dtype=torch.int32, device=self.dev)
+        self.d_new_width = torch.empty(info.n_groups, dtype=torch.int32, device=self.dev)
+        self.d_w_out = torch.empty(max(info.w_elems, 4), dtype=torch.float32, device=self.dev)
+        self.d_vecs_out = torch.empty(max(info.v_elems, 4), dtype=torch.float32,
+                                      device=self.dev)
+        self.d_thr = torch.zeros(max_variants * S.THRESHOLD_BYTES, **u8)
+        self.n_thr = 0
+
+    def close(self):
+        if self.model is not None:
+            S.shifter_model_destroy(self.model)
+            S.shifter_destroy(self.ctx)
+            self.model = None
+
+    # ---- the five steps -----------------------------------------------------------
+    def global_threshold(self, n_prune: Sequence[int], sync: bool = True):
+        self.n_thr = len(n_prune)
+        return S.shifter_global_threshold(self.ctx, self.model, self.d_w, n_prune,
+                                          self.d_thr, sync)
+
+    def apply_mask(self, k: int = 0, fused_scan: bool = True, in_place: bool = False):
+        dst = self.d_w if in_place else self.d_w_sparse
+        S.shifter_apply_mask(self.ctx, self.model, self.d_w, self.d_thr, dst, self.d_mask,
+                             self.d_out_alive if fused_scan else None,
+                             self.d_in_alive if fused_scan else None, thr_index=k)
+
+    def dead_channel_scan(self, src=None):
+        S.shifter_dead_channel_scan(self.ctx, self.model,
+                                    self.d_w_sparse if src is None else src,
+                                    self.d_out_alive, self.d_in_alive)
+
+    def propagate_groups(self, flags: int = 0, sync: bool = True):
+        return S.shifter_propagate_groups(self.ctx, self.model, self.d_out_alive,
+                                          self.d_in_alive, flags, self.d_group_alive,
+                                          self.d_index_map, self.d_keep, self.d_new_width,
+                                          sync)
+
+    def compact(self, sync: bool = True, src=None):
+        return S.shifter_compact(self.ctx, self.model,
+                                 self.d_w_sparse if src is None else src, self.d_vecs,
+                                 self.d_keep, self.d_new_width, self.d_w_out,
+                                 self.d_vecs_out, sync)
+
+    def variant(self, k: int = 0, flags: int = 0, fused_scan: bool = True,
+                sync: bool = True):
+        """Steps 2-5 for threshold record k.  Returns compact()'s tuple."""
+        self.apply_mask(k, fused_scan)
+        if not fused_scan:
+            self.dead_channel_scan()
+        self.propagate_groups(flags, sync=False)
+        return self.compact(sync)

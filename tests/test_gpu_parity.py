@@ -1,0 +1,238 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle, element
+by element and bit-exact (masks, sparse weights, alive flags, index maps, keep lists,
+compacted tensors and vectors, threshold records)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import shifter_oracle as O
+from paper_2309_06973_amd import shifter as S
+from paper_2309_06973_amd import synth
+from paper_2309_06973_amd.pipeline import Pipeline
+
+pytestmark = pytest.mark.gpu
+
+
+def bits(a):
+    return np.ascontiguousarray(a).view(np.uint32)
+
+
+def check_threshold(rec, sel, a_prunable):
+    assert rec.n_prune == sel.n_prune
+    if sel.n_prune == 0:
+        assert rec.cut == 0
+        return
+    key = int(np.float32(sel.thr_value).view(np.uint32))
+    assert rec.t_key == key
+    assert rec.g_cut == sel.thr_index
+    assert rec.cut == ((key << 32) | sel.thr_index) + 1
+    assert rec.n_less == int((a_prunable < np.float32(sel.thr_value)).sum())
+    assert rec.n_equal == int((a_prunable == np.float32(sel.thr_value)).sum())
+
+
+def check_variant(pl, spec, w, v, ref, flags=0, fused=True, label=""):
+    """Runs steps 2-5 on the GPU for the threshold record already on the device and
+    compares every output with the oracle's `ref` (a VariantResult)."""
+    info = pl.model.info
+    rc, ot, ov, ew, ev = pl.variant(ref._k, flags=flags, fused_scan=fused)
+    torch.cuda.synchronize()
+    n = info.n_prunable
+    mask = pl.d_mask[:n].cpu().numpy()
+    assert np.array_equal(mask, ref.mask), label + " mask"
+    ws = pl.d_w_sparse.cpu().numpy()
+    for t in spec.tensors:
+        sl = slice(t.offset, t.offset + t.numel)
+        assert np.array_equal(bits(ws[sl]), bits(ref.w_sparse[sl])), label + " sparse weights"
+    oa = pl.d_out_alive.cpu().numpy()
+    ia = pl.d_in_alive.cpu().numpy()
+    assert np.array_equal(oa, np.concatenate(ref.out_alive)), label + " out_alive"
+    assert np.array_equal(ia, np.concatenate(ref.in_alive)), label + " in_alive"
+    ga = pl.d_group_alive.cpu().numpy()
+    im = pl.d_index_map.cpu().numpy()
+    kp = pl.d_keep.cpu().numpy().view(np.uint32)
+    nw = pl.d_new_width.cpu().numpy().view(np.uint32)
+    assert np.array_equal(nw, ref.plan.new_width), label + " new_width"
+    for gi, g in enumerate(spec.groups):
+        o = pl.model.group_off[gi]
+        assert np.array_equal(ga[o:o + g.width], ref.plan.alive[gi]), label + " group_alive"
+        assert np.array_equal(im[o:o + g.width], ref.plan.index_map[gi]), label + " index_map"
+        k = int(nw[gi])
+        assert np.array_equal(kp[o:o + k], ref.plan.keep[gi]), label + " keep"
+        assert np.all(kp[o + k:o + g.width] == 0xFFFFFFFF), label + " keep tail"
+    collapse = bool((ref.plan.new_width == 0).any())
+    assert rc == (S.SHIFTER_WARN_COLLAPSE if collapse else S.SHIFTER_OK)
+    assert ew == ref.compacted.w.size and ev == ref.compacted.v.size
+    wc = pl.d_w_out[:ew].cpu().numpy()
+    vc = pl.d_vecs_out[:ev].cpu().numpy()
+    assert np.array_equal(bits(wc), bits(ref.compacted.w)), label + " compacted weights"
+    assert np.array_equal(bits(vc), bits(ref.compacted.v)), label + " compacted vectors"
+    for d, (off, o2, i2, kh, kw), t in zip(ot, ref.compacted.tensor_shapes, spec.tensors):
+        assert (d.offset, d.out_ch, d.in_ch, d.kh, d.kw) == (off, o2, i2, kh, kw)
+        assert (d.out_group, d.in_group, d.in_mult) == (t.out_group, t.in_group, t.in_mult)
+    for d, (off, ln) in zip(ov, ref.compacted.vec_shapes):
+        assert (d.offset, d.len) == (off, ln)
+
+
+def run_config(spec, w, v, n_prune, flags=0, fused=True, check_every=1):
+    refs = O.prune_and_compact(w, v, spec.tensors, spec.vecs, spec.groups, n_prune, flags)
+    a = np.abs(O.gather_prunable(w, spec.tensors))
+    pl = Pipeline(spec, w, v)
+    try:
+        recs = pl.global_threshold(n_prune)
+        for k, (rec, ref) in enumerate(zip(recs, refs)):
+            check_threshold(rec, ref.sel, a)
+            if k % check_every == 0 or k == len(refs) - 1:
+                ref._k = k
+                check_variant(pl, spec, w, v, ref, flags, fused, f"{spec.name} k={k}")
+    finally:
+        pl.close()
+    return refs
+
+
+def portfolio_counts(c, spec):
+    return [synth.prune_count(spec.n_prunable, s) for s in synth.config_sparsities(c)]
+
+
+def test_c1_tiny_cnn():
+    spec, w, v = synth.generate_config(1)
+    n = spec.n_prunable
+    run_config(spec, w, v, portfolio_counts(1, spec) + [0, 1, n // 2, n - 1, n])
+
+
+def test_c1_unfused_scan_and_freeze_flag():
+    spec, w, v = synth.generate_config(1)
+    run_config(spec, w, v, portfolio_counts(1, spec), fused=False)
+    spec, w, v = synth.generate_config(3)
+    ps = portfolio_counts(3, spec)
+    run_config(spec, w, v, ps[7:9], flags=S.SHIFTER_PAPER_FREEZE_RESIDUAL)
+
+
+def test_c3_resnet56_portfolio():
+    spec, w, v = synth.generate_config(3)
+    run_config(spec, w, v, portfolio_counts(3, spec))
+
+
+def test_c2_vgg16_portfolio():
+    spec, w, v = synth.generate_config(2)
+    run_config(spec, w, v, portfolio_counts(2, spec), check_every=3)
+
+
+def test_c4_resnet50_portfolio():
+    spec, w, v = synth.generate_config(4)
+    run_config(spec, w, v, portfolio_counts(4, spec), check_every=6)
+
+
+def test_scaled_wide_vgg():
+    # the stress shape at 1/4 of its widths (20 M weights): element-wise parity at a size
+    # the oracle sorts in seconds; still thousands of tiles and 30 % designed-dead filters
+    spec = synth.wide_vgg19(width_mult=1, n_cls=1000)
+    w, v = synth.generate_weights(spec, synth.SEED_BASE + 55)
+    n = spec.n_prunable
+    ps = [synth.prune_count(n, 0.95)] + [synth.prune_count(n, 1 - 0.8 ** k) for k in (1, 5, 10)]
+    run_config(spec, w, v, ps)
+
+
+@pytest.mark.parametrize("kind", synth.ADVERSARIAL_KINDS)
+def test_adversarial_values_ragged_chain(kind):
+    # ragged sizes (nothing a multiple of 4 or of the tile), 1x1 / 3x3 / 5x5 kernels, ties
+    spec = synth.chain_spec([7, 13, 5], k=3, in_ch=3, n_cls=3, name="ragged")
+    spec2 = synth.chain_spec([37, 129, 61], k=5, in_ch=5, n_cls=7, name="ragged5")
+    for sp in (spec, spec2):
+        w = synth.adversarial_arena(kind, sp.w_elems, seed=sp.w_elems)
+        _, v = synth.generate_weights(sp, 3)
+        n = sp.n_prunable
+        ps = sorted({0, 1, n // 7, n // 3, n // 2, (9 * n) // 10, n - 1, n})
+        run_config(sp, w, v, ps)
+
+
+def test_residual_toy_with_planted_dead_filters():
+    spec = synth.residual_toy_spec(width=70, mid=33, n_blocks=3)
+    w, v = synth.generate_weights(spec, 99)
+    rng = np.random.Generator(np.random.Philox(4))
+    for t in spec.tensors[:-1]:
+        x = w[t.offset:t.offset + t.numel].reshape(t.out_ch, -1)
+        x[rng.random(t.out_ch) < 0.4] = 0
+    n = spec.n_prunable
+    run_config(spec, w, v, [0, n // 4, n // 2])
+    run_config(spec, w, v, [n // 4], flags=S.SHIFTER_PAPER_FREEZE_RESIDUAL)
+
+
+def test_non_prunable_tensor_offsets_and_gaps():
+    # a non-prunable first layer, a gap in the arena, tensors at unaligned offsets
+    import copy
+    spec = copy.deepcopy(synth.chain_spec([9, 11, 6], k=3, in_ch=2, n_cls=5))
+    spec.tensors[0].prunable = 0
+    shift = 0
+    for t in spec.tensors:
+        shift += 3
+        t.offset += shift
+    spec.w_elems = spec.tensors[-1].offset + spec.tensors[-1].numel + 5
+    rng = np.random.Generator(np.random.Philox(8))
+    w = rng.standard_normal(spec.w_elems, dtype=np.float32)
+    _, v = synth.generate_weights(synth.chain_spec([9, 11, 6], k=3, in_ch=2, n_cls=5), 1)
+    n = spec.n_prunable
+    refs = run_config(spec, w, v, [0, n // 2, n])
+    # the non-prunable layer is untouched even when everything else is removed
+    t0 = spec.tensors[0]
+    assert np.array_equal(refs[-1].w_sparse[t0.offset:t0.offset + t0.numel],
+                          w[t0.offset:t0.offset + t0.numel])
+
+
+def test_in_place_mask_and_determinism():
+    spec, w, v = synth.generate_config(3)
+    ps = portfolio_counts(3, spec)[5:6]
+    ref = O.prune_and_compact(w, v, spec.tensors, spec.vecs, spec.groups, ps)[0]
+    pl = Pipeline(spec, w, v)
+    try:
+        pl.global_threshold(ps)
+        outs = []
+        for _ in range(2):
+            pl.variant(0)
+            torch.cuda.synchronize()
+            outs.append((pl.d_w_sparse.cpu().numpy().copy(), pl.d_w_out.cpu().numpy().copy(),
+                         pl.d_out_alive.cpu().numpy().copy()))
+        for a, b in zip(outs[0], outs[1]):
+            assert np.array_equal(bits(a) if a.dtype == np.float32 else a,
+                                  bits(b) if b.dtype == np.float32 else b)
+        pl.apply_mask(0, fused_scan=True, in_place=True)
+        torch.cuda.synchronize()
+        assert np.array_equal(bits(pl.d_w.cpu().numpy()), bits(ref.w_sparse))
+    finally:
+        pl.close()
+
+
+def test_errors_on_device():
+    spec, w, v = synth.generate_config(1)
+    w = w.copy()
+    w[100] = np.nan
+    pl = Pipeline(spec, w, v)
+    try:
+        with pytest.raises(S.ShifterError) as e:
+            pl.global_threshold([10])
+        assert e.value.code == S.SHIFTER_ERR_NONFINITE
+        with pytest.raises(S.ShifterError) as e:
+            pl.global_threshold([spec.n_prunable + 1])
+        assert e.value.code == S.SHIFTER_ERR_INVALID_ARG
+    finally:
+        pl.close()
+    spec, w, v = synth.generate_config(1)
+    pl = Pipeline(spec, w, v)
+    try:
+        pl.global_threshold([0])
+        pl.apply_mask(0)
+        pl.propagate_groups(sync=False)
+        small = torch.empty(16, dtype=torch.float32, device=pl.dev)
+        pl.d_w_out = small
+        with pytest.raises(S.ShifterError) as e:
+            pl.compact()
+        assert e.value.code == S.SHIFTER_ERR_CAPACITY
+        assert str(spec.n_prunable) in str(e.value)
+    finally:
+        pl.close()
+
+
+def test_collapse_is_a_warning_with_valid_outputs():
+    spec, w, v = synth.generate_config(1)
+    n = spec.n_prunable
+    refs = run_config(spec, w, v, [n])
+    assert (refs[0].plan.new_width[1:-1] == 0).all()
