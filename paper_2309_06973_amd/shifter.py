@@ -101,6 +101,10 @@ def load_library() -> C.CDLL:
             raise RuntimeError(
                 f"{_LIB_PATH} is missing: build it with "
                 "`python -m paper_2309_06973_amd.build` (hipcc, gfx950)")
+        # The device pointers and streams handed to the library come from torch, so the
+        # library must run on the HIP runtime torch has loaded: import torch first, then
+        # libshifter's dependency on libamdhip64.so.7 resolves to that same runtime.
+        import torch  # noqa: F401
         lib = C.CDLL(_LIB_PATH)
         for name, argtypes in EXPORTS.items():
             fn = getattr(lib, name)
