@@ -157,11 +157,36 @@ int shifter_model_get_layout(const shifter_model* model, uint64_t* h_out_flag_of
  *   d_thr      device, K records, written
  *   h_thr      host, K records, or NULL.  Non-NULL: the call waits for the stream,
  *              copies the records and reports SHIFTER_ERR_NONFINITE if a prunable
- *              weight is NaN.  NULL: no wait; a NaN is then reported by the next
- *              waiting call on this context. */
+ *              weight is NaN.  NULL: no wait and no NaN report (a NaN compares above
+ *              +inf; the records are then meaningless).  A waiting call with K = 1 may
+ *              use the single-pass selection (see shifter_set_select_path). */
 int shifter_global_threshold(shifter_ctx* ctx, const shifter_model* model,
                              const float* d_w, const uint64_t* h_n_prune, uint32_t K,
                              shifter_threshold* d_thr, shifter_threshold* h_thr);
+
+/* Which selection algorithm shifter_global_threshold and shifter_prune_fused may use:
+ * 0 (default) the single-pass selection where it applies (one prune count, waiting
+ * call), with the multi-pass radix select as its fall-back; 1 the multi-pass radix
+ * select only.  Both give the same records. */
+int shifter_set_select_path(shifter_ctx* ctx, int path);
+
+/* Ranking, sparse model and zero-channel scan for ONE prune count in a single read of
+ * the arena (Sec. II-A; Sec. III-C; Module 2 of Sec. III-D): same outputs as
+ * shifter_global_threshold(K = 1) followed by shifter_apply_mask with the scan.
+ * The pass predicts a narrow key interval around the threshold from a sample, writes
+ * the final value of every weight outside it while counting, and settles the few
+ * weights inside it once the exact threshold is known; if the prediction fails its own
+ * exactness check the two separate steps are run instead.
+ *   d_w_out      device, w_extent floats; must differ from d_w
+ *   d_mask       device, N bytes, or NULL
+ *   d_out_alive, d_in_alive   device, required
+ *   d_thr, h_thr device / host, one record each, both required.  The call always waits
+ *                for the stream; a NaN among the prunable weights gives
+ *                SHIFTER_ERR_NONFINITE (outputs are then unspecified). */
+int shifter_prune_fused(shifter_ctx* ctx, const shifter_model* model, const float* d_w,
+                        uint64_t n_prune, shifter_threshold* d_thr, float* d_w_out,
+                        uint8_t* d_mask, uint8_t* d_out_alive, uint8_t* d_in_alive,
+                        shifter_threshold* h_thr);
 
 /* The sparse model (Sec. II-A; Sec. III-C): d_w_out[e] = removed ? +0.0f : d_w[e] for
  * every element of every tensor (non-prunable tensors are copied), d_mask[g] = 0 for
@@ -240,7 +265,8 @@ int shifter_profile_enable(shifter_ctx* ctx, int on);
 int shifter_profile_read(shifter_ctx* ctx, const char** names, uint32_t* counts,
                          double* total_ms, uint32_t cap, uint32_t* n_out);
 
-/* Plain device-to-device copy kernel of n floats (dwordx4 loads and stores), used to
+/* Plain device-to-device copy kernel of n floats (dwordx4 loads and stores; both
+ * pointers 16-byte aligned), used to
  * calibrate the memory-traffic counters against a transfer of known size and to
  * measure the copy bandwidth this chip sustains. */
 int shifter_copy_f32(shifter_ctx* ctx, const float* d_src, float* d_dst, uint64_t n);

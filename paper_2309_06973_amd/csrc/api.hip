@@ -13,7 +13,8 @@ namespace shifter {
 const char* const kKernelNames[K_COUNT] = {
     "sel_init", "hist_round0", "hist_round1", "hist_round2", "select", "tie_count",
     "tie_final", "zero_flags", "mask_scan", "scan", "propagate", "plan", "gather",
-    "gather_vec", "copy"};
+    "gather_vec", "copy", "spec_init", "spec_sample", "spec_predict", "spec_pass",
+    "spec_finish", "spec_fixup"};
 
 ProfileScope::ProfileScope(shifter_ctx* c, int id) : ctx(c), idx(-1) {
     if (!c->profiling) return;
@@ -80,7 +81,8 @@ static void unbind(shifter_model* m) {
     if (!b.ctx) return;
     (void)hipSetDevice(b.device);
     void* ptrs[] = {b.tens, b.groups, b.vecs, b.producers, b.tile_prefix, b.sel, b.ghist,
-                    b.tile_cnt, b.plan_t, b.plan_v, b.plan_h, b.out_tile_prefix};
+                    b.tile_cnt, b.plan_t, b.plan_v, b.plan_h, b.out_tile_prefix, b.spec, b.shist,
+                    b.sprefix, b.hist2, b.cand, b.small, b.ranked_ids};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     if (b.host_stage) (void)hipHostFree(b.host_stage);
@@ -186,6 +188,9 @@ extern "C" int shifter_model_create(const shifter_tensor_desc* tensors, uint32_t
     }
     m->tile_prefix.push_back((uint32_t)tiles);
     m->n_tiles = (uint32_t)tiles;
+    for (uint32_t i = 0; i < n_tensors; ++i)
+        if (tensors[i].prunable) m->ranked_ids.push_back(i);
+    m->n_ranked = (uint32_t)m->ranked_ids.size();
     if (gbase >= (1ull << 32) - 1) return bad("N (prunable weights) reaches 2^32 - 1", n_tensors - 1);
     std::sort(spans.begin(), spans.end());
     for (size_t i = 1; i < spans.size(); ++i)
@@ -286,9 +291,17 @@ static int bind(shifter_ctx* ctx, const shifter_model* cm) {
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.plan_v), sizeof(PlanVec) * std::max<size_t>(n_v, 1)));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.plan_h), sizeof(PlanHeader)));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.out_tile_prefix), sizeof(uint32_t) * (n_t + 1)));
+    if ((rc = upload(ctx, &b.ranked_ids, m->ranked_ids.data(), m->ranked_ids.size()))) return rc;
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.spec), sizeof(SpecState)));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.shist), sizeof(uint32_t) * 65536));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.sprefix), sizeof(uint32_t) * 65536));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.hist2), sizeof(uint32_t) * 65536));
+    b.cand_cap = (uint32_t)std::max<uint64_t>(m->info.n_prunable / 16, 262144);
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.cand), sizeof(uint2) * (size_t)b.cand_cap));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.small), sizeof(uint2) * SPEC_SMALL_CAP));
     b.host_stage_bytes = sizeof(SelState) + sizeof(shifter_threshold) * MAXK + sizeof(PlanHeader) +
                          sizeof(PlanTensor) * n_t + sizeof(PlanVec) * n_v +
-                         sizeof(uint32_t) * m->g.size() + 256;
+                         sizeof(uint32_t) * m->g.size() + sizeof(SpecState) + 256;
     HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&b.host_stage), b.host_stage_bytes, hipHostMallocDefault));
     return SHIFTER_OK;
 }
@@ -311,6 +324,23 @@ static int after_launch(shifter_ctx* ctx, const char* fn) {
     return SHIFTER_OK;
 }
 
+// Waits for the stream and reads back the outcome of the single-pass selection.
+static int spec_result(shifter_ctx* ctx, const shifter_model* model, const shifter_threshold* d_thr,
+                       shifter_threshold* h_thr, int* decided) {
+    uint8_t* st = model->b.host_stage;
+    HIP_TRY(ctx, hipMemcpyAsync(st, model->b.spec, sizeof(SpecState), hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipMemcpyAsync(st + sizeof(SpecState), d_thr, sizeof(shifter_threshold),
+                                hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    SpecState ss;
+    memcpy(&ss, st, sizeof ss);
+    if (ss.status & 2u)
+        return fail(ctx, SHIFTER_ERR_NONFINITE, "NaN among the prunable weights");
+    *decided = (ss.status & 1u) ? 0 : 1;
+    if (*decided) memcpy(h_thr, st + sizeof(SpecState), sizeof(shifter_threshold));
+    return SHIFTER_OK;
+}
+
 extern "C" int shifter_global_threshold(shifter_ctx* ctx, const shifter_model* model,
                                         const float* d_w, const uint64_t* h_n_prune, uint32_t K,
                                         shifter_threshold* d_thr, shifter_threshold* h_thr) {
@@ -328,6 +358,14 @@ extern "C" int shifter_global_threshold(shifter_ctx* ctx, const shifter_model* m
         if (h_n_prune[k] > model->info.n_prunable)
             return fail(ctx, SHIFTER_ERR_INVALID_ARG, "global_threshold: prune count exceeds N");
         pc.p[k] = h_n_prune[k];
+    }
+    if (h_thr && K == 1 && ctx->select_path == 0) {
+        // single pass; exact when its own check holds, else fall through to the radix select
+        launch_spec_select(ctx, model, d_w, pc.p[0], d_thr, nullptr, nullptr, nullptr, nullptr);
+        if ((rc = after_launch(ctx, "global_threshold"))) return rc;
+        int decided = 0;
+        if ((rc = spec_result(ctx, model, d_thr, h_thr, &decided))) return rc;
+        if (decided) return SHIFTER_OK;
     }
     launch_select(ctx, model, d_w, pc, K, d_thr);
     if ((rc = after_launch(ctx, "global_threshold"))) return rc;
@@ -361,6 +399,52 @@ extern "C" int shifter_apply_mask(shifter_ctx* ctx, const shifter_model* model, 
                     "apply_mask: d_out_alive and d_in_alive must both be NULL or both be given");
     launch_mask_scan(ctx, model, d_w, d_thr, d_w_out, d_mask, d_out_alive, d_in_alive);
     return after_launch(ctx, "apply_mask");
+}
+
+extern "C" int shifter_prune_fused(shifter_ctx* ctx, const shifter_model* model, const float* d_w,
+                                   uint64_t n_prune, shifter_threshold* d_thr, float* d_w_out,
+                                   uint8_t* d_mask, uint8_t* d_out_alive, uint8_t* d_in_alive,
+                                   shifter_threshold* h_thr) {
+    int rc = enter(ctx, model, "prune_fused");
+    if (rc) return rc;
+    if (!d_w || !d_thr || !d_w_out || !d_out_alive || !d_in_alive || !h_thr)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "prune_fused: NULL pointer argument");
+    if (d_w == d_w_out)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "prune_fused: cannot work in place");
+    if (misaligned(d_w, 16) || misaligned(d_w_out, 16) || misaligned(d_mask, 4) || misaligned(d_thr, 8))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG,
+                    "prune_fused: arenas must be 16-byte aligned, the mask 4-byte aligned");
+    if (n_prune > model->info.n_prunable)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "prune_fused: prune count exceeds N");
+    if (ctx->select_path == 0) {
+        launch_spec_select(ctx, model, d_w, n_prune, d_thr, d_w_out, d_mask, d_out_alive, d_in_alive);
+        if ((rc = after_launch(ctx, "prune_fused"))) return rc;
+        int decided = 0;
+        if ((rc = spec_result(ctx, model, d_thr, h_thr, &decided))) return rc;
+        if (decided) return SHIFTER_OK;
+    }
+    // the single pass could not decide (or is switched off): rank, then mask and scan
+    rc = shifter_global_threshold(ctx, model, d_w, &n_prune, 1, d_thr, nullptr);
+    if (rc) return rc;
+    launch_mask_scan(ctx, model, d_w, d_thr, d_w_out, d_mask, d_out_alive, d_in_alive);
+    if ((rc = after_launch(ctx, "prune_fused"))) return rc;
+    uint8_t* st = model->b.host_stage;
+    HIP_TRY(ctx, hipMemcpyAsync(st, d_thr, sizeof(shifter_threshold), hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipMemcpyAsync(st + sizeof(shifter_threshold), &model->b.sel->nan_seen, sizeof(uint32_t),
+                                hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    memcpy(h_thr, st, sizeof(shifter_threshold));
+    uint32_t nan_seen;
+    memcpy(&nan_seen, st + sizeof(shifter_threshold), sizeof nan_seen);
+    if (nan_seen) return fail(ctx, SHIFTER_ERR_NONFINITE, "prune_fused: NaN among the prunable weights");
+    return SHIFTER_OK;
+}
+
+extern "C" int shifter_set_select_path(shifter_ctx* ctx, int path) {
+    if (!ctx || path < 0 || path > 1)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "set_select_path: path must be 0 or 1");
+    ctx->select_path = path;
+    return SHIFTER_OK;
 }
 
 extern "C" int shifter_dead_channel_scan(shifter_ctx* ctx, const shifter_model* model,

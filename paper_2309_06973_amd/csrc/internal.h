@@ -66,6 +66,24 @@ struct SelState {
     uint32_t pad;
 };
 
+// State of the single-pass (sample, predict, one pass, finish) selection.
+constexpr uint32_t SPEC_SMALL_CAP = 1024;
+struct SpecState {
+    uint64_t p;          // prune count
+    uint64_t r2;         // 1-based rank of the P-th pair inside the selected bin
+    uint64_t less;       // weights below the selected bin
+    uint32_t lo, hi;     // inclusive key interval of the candidates
+    uint32_t sh;         // candidate histogram bin = (key - lo) >> sh
+    uint32_t n_below;    // weights with key < lo
+    uint32_t n_inside;   // weights with lo <= key <= hi
+    uint32_t n_cand;     // candidate pairs appended (exceeds the capacity on overflow)
+    uint32_t m_valid;    // sample size
+    uint32_t status;     // bit 0: not decided, use the multi-pass select; bit 1: NaN seen
+    uint32_t bin, bin_cnt;
+    uint32_t small_cnt;
+    uint32_t pad;
+};
+
 struct PruneCounts {
     uint64_t p[MAXK];
 };
@@ -93,7 +111,8 @@ struct PlanHeader {
 enum KernelId {
     K_SEL_INIT = 0, K_HIST0, K_HIST1, K_HIST2, K_SELECT, K_TIE_COUNT, K_TIE_FINAL,
     K_ZERO_FLAGS, K_MASK_SCAN, K_SCAN, K_PROPAGATE, K_PLAN, K_GATHER, K_GATHER_VEC,
-    K_COPY, K_COUNT
+    K_COPY, K_SPEC_INIT, K_SPEC_SAMPLE, K_SPEC_PREDICT, K_SPEC_PASS, K_SPEC_FINISH, K_SPEC_FIXUP,
+    K_COUNT
 };
 extern const char* const kKernelNames[K_COUNT];
 
@@ -111,6 +130,8 @@ struct shifter_model {
     std::vector<uint32_t> tile_prefix;   // n_tensors + 1
     std::vector<uint64_t> out_flag_off, in_flag_off, group_off;
     uint32_t n_tiles = 0;
+    std::vector<uint32_t> ranked_ids;    // indices of the prunable tensors, in order
+    uint32_t n_ranked = 0;
 
     // device side, created by the first call that uses the model with a context
     struct Bound {
@@ -128,6 +149,14 @@ struct shifter_model {
         shifter::PlanVec* plan_v = nullptr;
         shifter::PlanHeader* plan_h = nullptr;
         uint32_t* out_tile_prefix = nullptr;  // n_tensors + 1
+        shifter::SpecState* spec = nullptr;
+        uint32_t* shist = nullptr;            // 65536 sample bins
+        uint32_t* sprefix = nullptr;          // 65536
+        uint32_t* hist2 = nullptr;            // 65536 candidate bins
+        uint2* cand = nullptr;                // candidate (key, g) pairs
+        uint32_t cand_cap = 0;
+        uint2* small = nullptr;               // SPEC_SMALL_CAP pairs
+        uint32_t* ranked_ids = nullptr;
         uint8_t* host_stage = nullptr;        // pinned, for small read-backs
         size_t host_stage_bytes = 0;
     } b;
@@ -142,6 +171,7 @@ struct shifter_ctx {
     std::vector<Rec> recs;
     std::vector<hipEvent_t> pool;
     uint32_t hist_grid = 2048;
+    int select_path = 0;   // 0: single-pass where it applies; 1: multi-pass radix only
 };
 
 namespace shifter {
@@ -149,6 +179,9 @@ namespace shifter {
 // Launchers (defined next to their kernels).  All enqueue on ctx->stream.
 void launch_select(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
                    const PruneCounts& pc, uint32_t k, shifter_threshold* d_thr);
+void launch_spec_select(shifter_ctx* ctx, const shifter_model* m, const float* d_w, uint64_t p,
+                        shifter_threshold* d_thr, float* d_w_out, uint8_t* d_mask,
+                        uint8_t* d_out_alive, uint8_t* d_in_alive);
 void launch_mask_scan(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
                       const shifter_threshold* d_thr, float* d_w_out, uint8_t* d_mask,
                       uint8_t* d_out_alive, uint8_t* d_in_alive);

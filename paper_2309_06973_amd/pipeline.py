@@ -54,6 +54,13 @@ class Pipeline:
         return S.shifter_global_threshold(self.ctx, self.model, self.d_w, n_prune,
                                           self.d_thr, sync)
 
+    def prune_fused(self, n_prune: int):
+        """Steps 1-3 for one prune count in a single read of the arena."""
+        self.n_thr = 1
+        return S.shifter_prune_fused(self.ctx, self.model, self.d_w, n_prune, self.d_thr,
+                                     self.d_w_sparse, self.d_mask, self.d_out_alive,
+                                     self.d_in_alive)
+
     def apply_mask(self, k: int = 0, fused_scan: bool = True, in_place: bool = False):
         dst = self.d_w if in_place else self.d_w_sparse
         S.shifter_apply_mask(self.ctx, self.model, self.d_w, self.d_thr, dst, self.d_mask,

@@ -69,6 +69,10 @@ EXPORTS = {
     "shifter_global_threshold": [C.c_void_p, C.c_void_p, C.c_void_p,
                                  C.POINTER(C.c_uint64), C.c_uint32, C.c_void_p,
                                  C.POINTER(Threshold)],
+    "shifter_set_select_path": [C.c_void_p, C.c_int],
+    "shifter_prune_fused": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p,
+                            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                            C.POINTER(Threshold)],
     "shifter_apply_mask": [C.c_void_p] * 8,
     "shifter_dead_channel_scan": [C.c_void_p] * 5,
     "shifter_propagate_groups": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
@@ -195,6 +199,20 @@ def shifter_global_threshold(ctx: Context, model: Model, d_w, n_prune: Sequence[
     _check(load_library().shifter_global_threshold(ctx.handle, model.handle, _ptr(d_w), arr, k,
                                                    _ptr(d_thr), h), ctx.handle)
     return list(h)[:k] if sync else None
+
+
+def shifter_set_select_path(ctx: Context, path: int) -> None:
+    _check(load_library().shifter_set_select_path(ctx.handle, path), ctx.handle)
+
+
+def shifter_prune_fused(ctx: Context, model: Model, d_w, n_prune: int, d_thr, d_w_out, d_mask,
+                        d_out_alive, d_in_alive) -> Threshold:
+    h = Threshold()
+    _check(load_library().shifter_prune_fused(ctx.handle, model.handle, _ptr(d_w), int(n_prune),
+                                              _ptr(d_thr), _ptr(d_w_out), _ptr(d_mask),
+                                              _ptr(d_out_alive), _ptr(d_in_alive), C.byref(h)),
+           ctx.handle)
+    return h
 
 
 def shifter_apply_mask(ctx: Context, model: Model, d_w, d_thr, d_w_out, d_mask,

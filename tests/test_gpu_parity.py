@@ -30,11 +30,16 @@ def check_threshold(rec, sel, a_prunable):
     assert rec.n_equal == int((a_prunable == np.float32(sel.thr_value)).sum())
 
 
-def check_variant(pl, spec, w, v, ref, flags=0, fused=True, label=""):
-    """Runs steps 2-5 on the GPU for the threshold record already on the device and
-    compares every output with the oracle's `ref` (a VariantResult)."""
+def check_variant(pl, spec, w, v, ref, flags=0, fused=True, label="", steps_1_to_3_done=False):
+    """Runs steps 2-5 on the GPU for the threshold record already on the device (or only
+    steps 4-5 after a fused steps-1-to-3 call) and compares every output with the
+    oracle's `ref` (a VariantResult)."""
     info = pl.model.info
-    rc, ot, ov, ew, ev = pl.variant(ref._k, flags=flags, fused_scan=fused)
+    if steps_1_to_3_done:
+        pl.propagate_groups(flags, sync=False)
+        rc, ot, ov, ew, ev = pl.compact()
+    else:
+        rc, ot, ov, ew, ev = pl.variant(ref._k, flags=flags, fused_scan=fused)
     torch.cuda.synchronize()
     n = info.n_prunable
     mask = pl.d_mask[:n].cpu().numpy()
@@ -73,9 +78,14 @@ def check_variant(pl, spec, w, v, ref, flags=0, fused=True, label=""):
         assert (d.offset, d.len) == (off, ln)
 
 
-def run_config(spec, w, v, n_prune, flags=0, fused=True, check_every=1):
+def run_config(spec, w, v, n_prune, flags=0, fused=True, check_every=1, single_every=None):
+    """Every selection path against the oracle: all prune counts in one call (multi-pass
+    radix select), and for every `single_every`-th count the single-count call (single
+    pass with fall-back), the same with the single pass switched off, and the fused
+    steps-1-to-3 call followed by plan and rebuild."""
     refs = O.prune_and_compact(w, v, spec.tensors, spec.vecs, spec.groups, n_prune, flags)
     a = np.abs(O.gather_prunable(w, spec.tensors))
+    single_every = single_every or check_every
     pl = Pipeline(spec, w, v)
     try:
         recs = pl.global_threshold(n_prune)
@@ -84,6 +94,20 @@ def run_config(spec, w, v, n_prune, flags=0, fused=True, check_every=1):
             if k % check_every == 0 or k == len(refs) - 1:
                 ref._k = k
                 check_variant(pl, spec, w, v, ref, flags, fused, f"{spec.name} k={k}")
+        for k, ref in enumerate(refs):
+            if k % single_every and k != len(refs) - 1:
+                continue
+            p = n_prune[k]
+            check_threshold(pl.global_threshold([p])[0], ref.sel, a)
+            S.shifter_set_select_path(pl.ctx, 1)
+            check_threshold(pl.global_threshold([p])[0], ref.sel, a)
+            S.shifter_set_select_path(pl.ctx, 0)
+            pl.d_w_sparse.fill_(float("nan"))
+            pl.d_mask.fill_(7)
+            check_threshold(pl.prune_fused(p), ref.sel, a)
+            ref._k = 0
+            check_variant(pl, spec, w, v, ref, flags, label=f"{spec.name} fused k={k}",
+                          steps_1_to_3_done=True)
     finally:
         pl.close()
     return refs
@@ -114,12 +138,12 @@ def test_c3_resnet56_portfolio():
 
 def test_c2_vgg16_portfolio():
     spec, w, v = synth.generate_config(2)
-    run_config(spec, w, v, portfolio_counts(2, spec), check_every=3)
+    run_config(spec, w, v, portfolio_counts(2, spec), check_every=3, single_every=4)
 
 
 def test_c4_resnet50_portfolio():
     spec, w, v = synth.generate_config(4)
-    run_config(spec, w, v, portfolio_counts(4, spec), check_every=6)
+    run_config(spec, w, v, portfolio_counts(4, spec), check_every=6, single_every=9)
 
 
 def test_scaled_wide_vgg():
@@ -236,3 +260,31 @@ def test_collapse_is_a_warning_with_valid_outputs():
     n = spec.n_prunable
     refs = run_config(spec, w, v, [n])
     assert (refs[0].plan.new_width[1:-1] == 0).all()
+
+
+def test_single_pass_selection_is_taken_and_falls_back_on_ties():
+    # continuous weights: the single pass must decide by itself (no radix kernels run)
+    spec, w, v = synth.generate_config(2)
+    p = synth.prune_count(spec.n_prunable, 0.9)
+    pl = Pipeline(spec, w, v)
+    try:
+        S.shifter_profile_enable(pl.ctx, True)
+        pl.global_threshold([p])
+        pl.prune_fused(p)
+        prof = S.shifter_profile_read(pl.ctx)
+        assert prof["spec_pass"][0] == 2 and "hist_round0" not in prof, prof
+        S.shifter_profile_enable(pl.ctx, False)
+    finally:
+        pl.close()
+    # all weights equal: the interval holds every weight, the single pass gives up and
+    # the radix select answers (exactly: checked against the oracle in the other tests)
+    w2 = np.full_like(w, 0.25)
+    pl = Pipeline(spec, w2, v)
+    try:
+        S.shifter_profile_enable(pl.ctx, True)
+        rec = pl.global_threshold([p])[0]
+        prof = S.shifter_profile_read(pl.ctx)
+        assert "spec_pass" in prof and "hist_round0" in prof, prof
+        assert rec.g_cut == p - 1 and rec.n_equal == spec.n_prunable
+    finally:
+        pl.close()
