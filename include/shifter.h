@@ -170,6 +170,19 @@ int shifter_global_threshold(shifter_ctx* ctx, const shifter_model* model,
  * select only.  Both give the same records. */
 int shifter_set_select_path(shifter_ctx* ctx, int path);
 
+/* Half-width of the key interval the single-pass selection predicts from its sample,
+ * in standard deviations of a binomial sample of the same size (default 8).  A wider
+ * interval means more candidate weights to settle after the pass, a narrower one a
+ * higher chance that the pass cannot decide and the multi-pass select runs.  Never
+ * affects results. */
+int shifter_set_margin_sigmas(shifter_ctx* ctx, double sigmas);
+
+/* Outcome of the last waiting selection on this context, for measurement:
+ * out8 = { path (1 single pass decided, 2 multi-pass select ran, 0 none yet), P,
+ *          weights below the interval, weights inside it, sample size, interval low key,
+ *          interval high key, status bits of the single pass }. */
+int shifter_get_select_stats(const shifter_ctx* ctx, uint64_t* out8);
+
 /* Ranking, sparse model and zero-channel scan for ONE prune count in a single read of
  * the arena (Sec. II-A; Sec. III-C; Module 2 of Sec. III-D): same outputs as
  * shifter_global_threshold(K = 1) followed by shifter_apply_mask with the scan.

@@ -82,7 +82,7 @@ static void unbind(shifter_model* m) {
     (void)hipSetDevice(b.device);
     void* ptrs[] = {b.tens, b.groups, b.vecs, b.producers, b.tile_prefix, b.sel, b.ghist,
                     b.tile_cnt, b.plan_t, b.plan_v, b.plan_h, b.out_tile_prefix, b.spec, b.shist,
-                    b.sprefix, b.hist2, b.cand, b.small, b.ranked_ids};
+                    b.sprefix, b.spec_cnt, b.partial, b.cand, b.list, b.ranked_ids};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     if (b.host_stage) (void)hipHostFree(b.host_stage);
@@ -295,10 +295,12 @@ static int bind(shifter_ctx* ctx, const shifter_model* cm) {
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.spec), sizeof(SpecState)));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.shist), sizeof(uint32_t) * 65536));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.sprefix), sizeof(uint32_t) * 65536));
-    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.hist2), sizeof(uint32_t) * 65536));
-    b.cand_cap = (uint32_t)std::max<uint64_t>(m->info.n_prunable / 16, 262144);
-    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.cand), sizeof(uint2) * (size_t)b.cand_cap));
-    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.small), sizeof(uint2) * SPEC_SMALL_CAP));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.spec_cnt), sizeof(uint32_t) * 2 * SPEC_SUB * 32));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.partial), sizeof(uint32_t) * SPEC_FIN_BLOCKS * 4096));
+    // candidate pairs: 1/16 of N in total, at least two tiles per sub-buffer
+    b.cand_cap_sb = (uint32_t)std::max<uint64_t>(m->info.n_prunable / 16 / SPEC_SUB, 2 * TILE);
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.cand), sizeof(uint2) * (size_t)b.cand_cap_sb * SPEC_SUB));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.list), sizeof(uint2) * SPEC_LIST_CAP));
     b.host_stage_bytes = sizeof(SelState) + sizeof(shifter_threshold) * MAXK + sizeof(PlanHeader) +
                          sizeof(PlanTensor) * n_t + sizeof(PlanVec) * n_v +
                          sizeof(uint32_t) * m->g.size() + sizeof(SpecState) + 256;
@@ -334,6 +336,8 @@ static int spec_result(shifter_ctx* ctx, const shifter_model* model, const shift
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     SpecState ss;
     memcpy(&ss, st, sizeof ss);
+    ctx->last_spec = ss;
+    ctx->last_path = (ss.status & 1u) ? 2 : 1;
     if (ss.status & 2u)
         return fail(ctx, SHIFTER_ERR_NONFINITE, "NaN among the prunable weights");
     *decided = (ss.status & 1u) ? 0 : 1;
@@ -437,6 +441,27 @@ extern "C" int shifter_prune_fused(shifter_ctx* ctx, const shifter_model* model,
     uint32_t nan_seen;
     memcpy(&nan_seen, st + sizeof(shifter_threshold), sizeof nan_seen);
     if (nan_seen) return fail(ctx, SHIFTER_ERR_NONFINITE, "prune_fused: NaN among the prunable weights");
+    return SHIFTER_OK;
+}
+
+extern "C" int shifter_get_select_stats(const shifter_ctx* ctx, uint64_t* out8) {
+    if (!ctx || !out8) return fail(nullptr, SHIFTER_ERR_INVALID_ARG, "get_select_stats: NULL argument");
+    const SpecState& ss = ctx->last_spec;
+    out8[0] = (uint64_t)ctx->last_path;
+    out8[1] = ss.p;
+    out8[2] = ss.n_below;
+    out8[3] = ss.n_inside;
+    out8[4] = ss.m_valid;
+    out8[5] = ss.lo;
+    out8[6] = ss.hi;
+    out8[7] = ss.status;
+    return SHIFTER_OK;
+}
+
+extern "C" int shifter_set_margin_sigmas(shifter_ctx* ctx, double sigmas) {
+    if (!ctx || !(sigmas >= 0.0 && sigmas <= 1e6))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "set_margin_sigmas: value out of range");
+    ctx->margin_sigmas = sigmas;
     return SHIFTER_OK;
 }
 

@@ -67,21 +67,22 @@ struct SelState {
 };
 
 // State of the single-pass (sample, predict, one pass, finish) selection.
-constexpr uint32_t SPEC_SMALL_CAP = 1024;
+constexpr uint32_t SPEC_SUB = 256;         // split counters / candidate sub-buffers
+constexpr uint32_t SPEC_FIN_BLOCKS = 128;  // blocks of the finishing passes
+constexpr uint32_t SPEC_LIST_CAP = 16384;  // pairs of the selected round-1 bin
+constexpr uint32_t SPEC_SMALL_CAP = 1024;  // pairs of the selected round-2 bin
 struct SpecState {
     uint64_t p;          // prune count
-    uint64_t r2;         // 1-based rank of the P-th pair inside the selected bin
-    uint64_t less;       // weights below the selected bin
+    uint64_t r2;         // 1-based rank of the P-th pair inside the selected round-1 bin
+    uint64_t less;       // weights below that bin
+    uint64_t n_below;    // weights with key < lo
+    uint64_t n_inside;   // weights with lo <= key <= hi (the candidates)
     uint32_t lo, hi;     // inclusive key interval of the candidates
-    uint32_t sh;         // candidate histogram bin = (key - lo) >> sh
-    uint32_t n_below;    // weights with key < lo
-    uint32_t n_inside;   // weights with lo <= key <= hi
-    uint32_t n_cand;     // candidate pairs appended (exceeds the capacity on overflow)
+    uint32_t sh;         // round-1 bin = (key - lo) >> sh
     uint32_t m_valid;    // sample size
     uint32_t status;     // bit 0: not decided, use the multi-pass select; bit 1: NaN seen
     uint32_t bin, bin_cnt;
-    uint32_t small_cnt;
-    uint32_t pad;
+    uint32_t list_cnt;
 };
 
 struct PruneCounts {
@@ -152,10 +153,11 @@ struct shifter_model {
         shifter::SpecState* spec = nullptr;
         uint32_t* shist = nullptr;            // 65536 sample bins
         uint32_t* sprefix = nullptr;          // 65536
-        uint32_t* hist2 = nullptr;            // 65536 candidate bins
-        uint2* cand = nullptr;                // candidate (key, g) pairs
-        uint32_t cand_cap = 0;
-        uint2* small = nullptr;               // SPEC_SMALL_CAP pairs
+        uint32_t* spec_cnt = nullptr;         // 2 * SPEC_SUB counters, one 128-byte line each
+        uint32_t* partial = nullptr;          // SPEC_FIN_BLOCKS * 4096 partial histograms
+        uint2* cand = nullptr;                // SPEC_SUB sub-buffers of (key, g) pairs
+        uint32_t cand_cap_sb = 0;             // pairs per sub-buffer
+        uint2* list = nullptr;                // SPEC_LIST_CAP pairs
         uint32_t* ranked_ids = nullptr;
         uint8_t* host_stage = nullptr;        // pinned, for small read-backs
         size_t host_stage_bytes = 0;
@@ -172,6 +174,9 @@ struct shifter_ctx {
     std::vector<hipEvent_t> pool;
     uint32_t hist_grid = 2048;
     int select_path = 0;   // 0: single-pass where it applies; 1: multi-pass radix only
+    double margin_sigmas = 8.0;   // half-width of the predicted interval, in binomial sigmas
+    shifter::SpecState last_spec{};  // outcome of the last single-pass selection
+    int last_path = 0;               // 1: single pass decided; 2: multi-pass select ran
 };
 
 namespace shifter {

@@ -11,9 +11,9 @@
 //                  form the same pass already writes the sparse weights, the mask and
 //                  the alive flags for every weight outside the interval;
 //   4. finish      if  n_below < P <= n_below + n_candidates  the P-th pair is the
-//                  (P - n_below)-th candidate: a 65536-bin histogram of the candidate
-//                  keys, one scan, and an exact rank inside the selected bin give the
-//                  record; the fused form then fixes up the candidates only.
+//                  (P - n_below)-th candidate: two rounds of 4096-bin LDS histograms
+//                  over the candidates and an exact rank inside the last bin give the
+//                  record; the fused form then settles the candidates only.
 //
 // The result is exact whenever step 4's check holds; otherwise (a sample that misled,
 // an interval with too many ties, a full buffer) a status bit is raised and the host
@@ -22,29 +22,39 @@
 
 namespace shifter {
 
-constexpr uint32_t SBINS = 65536;       // sample / candidate histogram bins
+constexpr uint32_t SBINS = 65536;       // sample histogram bins
 constexpr uint32_t SAMPLE_SHIFT = 15;   // sample bins: top 16 of the 31 key bits
+constexpr uint32_t FBINS = 4096;        // bins of the two finishing histograms (LDS)
+constexpr uint32_t FIN_BLOCKS = SPEC_FIN_BLOCKS;  // blocks of the passes over candidates
+
+// Global atomics to one address serialise (about 11 ns each on this chip), so every
+// counter that all blocks touch is split into SPEC_SUB copies, one 128-byte line each,
+// chosen by blockIdx; the candidate buffer is split the same way.
+enum { CNT_CAND = 0, CNT_BELOW = 1 };
+__device__ __forceinline__ uint32_t* sub_counter(uint32_t* cnt, uint32_t which, uint32_t sb) {
+    return cnt + (which * SPEC_SUB + sb) * 32u;
+}
 
 __global__ __launch_bounds__(BLOCK) void spec_init_kernel(SpecState* ss, uint32_t* shist,
-                                                          uint32_t* hist2, uint64_t p,
+                                                          uint32_t* cnt, uint64_t p,
                                                           uint8_t* fa, uint64_t na,
                                                           uint8_t* fb, uint64_t nb) {
     const uint64_t tid = (uint64_t)blockIdx.x * BLOCK + threadIdx.x;
     const uint64_t stride = (uint64_t)gridDim.x * BLOCK;
-    for (uint64_t i = tid; i < SBINS; i += stride) { shist[i] = 0; hist2[i] = 0; }
+    for (uint64_t i = tid; i < SBINS; i += stride) shist[i] = 0;
+    for (uint64_t i = tid; i < 2u * SPEC_SUB * 32u; i += stride) cnt[i] = 0;
     for (uint64_t i = tid; i < na; i += stride) fa[i] = 0;
     for (uint64_t i = tid; i < nb; i += stride) fb[i] = 0;
     if (tid == 0) {
         ss->p = p;
         ss->n_below = 0;
         ss->n_inside = 0;
-        ss->n_cand = 0;
         ss->m_valid = 0;
         ss->status = 0;
-        ss->small_cnt = 0;
+        ss->list_cnt = 0;
         ss->lo = 0;
         ss->hi = 0x7fffffffu;
-        ss->sh = 15;
+        ss->sh = 19;
     }
 }
 
@@ -80,7 +90,8 @@ __global__ __launch_bounds__(BLOCK) void spec_sample_kernel(
 __global__ __launch_bounds__(BLOCK) void spec_predict_kernel(SpecState* ss,
                                                              const uint32_t* __restrict__ shist,
                                                              uint32_t* sprefix,
-                                                             uint64_t n_prunable) {
+                                                             uint64_t n_prunable,
+                                                             double margin_sigmas) {
     __shared__ uint64_t smem[BLOCK / 64 + 1];
     constexpr uint32_t PER = SBINS / BLOCK;
     const uint32_t b0 = threadIdx.x * PER;
@@ -101,9 +112,8 @@ __global__ __launch_bounds__(BLOCK) void spec_predict_kernel(SpecState* ss,
     if (p > 0 && m >= 256 && n_prunable > 0) {
         const double frac = (double)p / (double)n_prunable;
         const double centre = frac * (double)m;
-        // 24 standard deviations of a simple random sample: the sample is systematic and
-        // clustered by lines, so its error can exceed the binomial one several times
-        const double delta = 24.0 * sqrt((double)m * frac * (1.0 - frac)) + 16.0;
+        // a multiple of the binomial deviation of a simple random sample of this size
+        const double delta = margin_sigmas * sqrt((double)m * frac * (1.0 - frac)) + 16.0;
         const double r_lo = centre - delta, r_hi = centre + delta;
         // first bin whose inclusive prefix exceeds r (holds the r-th sample, 0-based)
         auto bin_of = [&](double r) -> uint32_t {
@@ -119,7 +129,7 @@ __global__ __launch_bounds__(BLOCK) void spec_predict_kernel(SpecState* ss,
         if (r_hi < (double)(m - 1)) hi = ((bin_of(r_hi) + 1u) << SAMPLE_SHIFT) - 1u;
     }
     uint32_t sh = 0;
-    while (((uint64_t)(hi - lo) >> sh) >= SBINS) ++sh;
+    while (((hi - lo) >> sh) >= FBINS) ++sh;
     ss->lo = lo;
     ss->hi = hi;
     ss->sh = sh;
@@ -131,12 +141,12 @@ __global__ __launch_bounds__(BLOCK) void spec_predict_kernel(SpecState* ss,
 template <bool FUSED>
 __global__ __launch_bounds__(BLOCK) void spec_pass_kernel(
     const DevTensor* __restrict__ tens, const uint32_t* __restrict__ tile_prefix,
-    uint32_t n_t, const float* __restrict__ w, SpecState* ss, uint2* __restrict__ cand,
-    uint32_t cap, float* __restrict__ w_out, uint8_t* __restrict__ mask, uint8_t* out_alive,
-    uint8_t* in_alive) {
+    uint32_t n_t, const float* __restrict__ w, SpecState* ss, uint32_t* cnt,
+    uint2* __restrict__ cand, uint32_t cap_sb, float* __restrict__ w_out,
+    uint8_t* __restrict__ mask, uint8_t* out_alive, uint8_t* in_alive) {
     __shared__ uint8_t rowf[FUSED ? TILE + 16 : 16];
     __shared__ uint8_t colf[FUSED ? TILE + 16 : 16];
-    __shared__ uint32_t s_below, s_inside, s_nan;
+    __shared__ uint32_t s_below, s_nan, s_base, s_wtot[BLOCK / 64];
 
     const uint32_t tile = blockIdx.x;
     const uint32_t t = find_tensor(tile_prefix, n_t, tile);
@@ -147,9 +157,11 @@ __global__ __launch_bounds__(BLOCK) void spec_pass_kernel(
     const uint32_t e0 = (tile - tile_prefix[t]) * TILE;
     const uint32_t n = min(TILE, T.numel - e0);
     const uint32_t g0 = (uint32_t)(T.gbase + e0);
-    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t lane = threadIdx.x & 63u, wid = threadIdx.x >> 6;
+    const uint32_t sb = blockIdx.x & (SPEC_SUB - 1);
+    uint2* my_cand = cand + (size_t)sb * cap_sb;
     uint32_t c0 = 0, r0 = 0, nrows = 0, ncols = 0;
-    if (threadIdx.x == 0) { s_below = 0; s_inside = 0; s_nan = 0; }
+    if (threadIdx.x == 0) { s_below = 0; s_nan = 0; s_base = 0; }
     if (FUSED) {
         c0 = e0 % T.khw;
         r0 = e0 % T.row_len;
@@ -206,36 +218,45 @@ __global__ __launch_bounds__(BLOCK) void spec_pass_kernel(
                         k0 | (k1 << 8) | (k2 << 16) | (k3 << 24);
             }
         }
-        // append this wavefront's candidates with one atomic
-        if (__ballot(cmask != 0)) {
-            const uint32_t c = __popc(cmask);
-            uint32_t incl = c;
-            for (uint32_t d = 1; d < 64; d <<= 1) {
-                const uint32_t y = __shfl_up(incl, d, 64);
-                if (lane >= d) incl += y;
-            }
-            const uint32_t wave_total = __shfl(incl, 63, 64);
-            uint32_t base = 0;
-            if (lane == 63) {
-                base = atomicAdd(&ss->n_cand, wave_total);
-                atomicAdd(&s_inside, wave_total);
-            }
-            base = __shfl(base, 63, 64);
-            uint32_t pos = base + incl - c;
+        // append the block's candidates with one global atomic: scan the per-thread
+        // counts over the block, reserve a range in this block's sub-buffer, scatter
+        const uint32_t c = __popc(cmask);
+        uint32_t incl = c;
+        for (uint32_t d = 1; d < 64; d <<= 1) {
+            const uint32_t y = __shfl_up(incl, d, 64);
+            if (lane >= d) incl += y;
+        }
+        if (lane == 63) s_wtot[wid] = incl;
+        __syncthreads();
+        uint32_t woff = 0, btot = 0;
 #pragma unroll
-            for (uint32_t u = 0; u < U; ++u) {
-                const uint32_t j = (threadIdx.x + BLOCK * u) * 4;
-                const uint32_t vv[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+        for (uint32_t i = 0; i < BLOCK / 64; ++i) {
+            const uint32_t x = s_wtot[i];
+            if (i < wid) woff += x;
+            btot += x;
+        }
+        if (btot) {   // uniform over the block
+            if (threadIdx.x == 0) s_base = atomicAdd(sub_counter(cnt, CNT_CAND, sb), btot);
+            __syncthreads();
+            uint32_t pos = s_base + woff + incl - c;
+            if (cmask) {
 #pragma unroll
-                for (uint32_t q = 0; q < 4; ++q) {
-                    if (cmask & (1u << (4 * u + q))) {
-                        if (pos < cap) cand[pos] = make_uint2(vv[q] & 0x7fffffffu, g0 + j + q);
-                        ++pos;
+                for (uint32_t u = 0; u < U; ++u) {
+                    const uint32_t j = (threadIdx.x + BLOCK * u) * 4;
+                    const uint32_t vv[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+                    for (uint32_t q = 0; q < 4; ++q) {
+                        if (cmask & (1u << (4 * u + q))) {
+                            if (pos < cap_sb)
+                                my_cand[pos] = make_uint2(vv[q] & 0x7fffffffu, g0 + j + q);
+                            ++pos;
+                        }
                     }
                 }
             }
         }
     } else {
+        // ragged or unaligned tile (at most a few per tensor): one atomic per candidate
         for (uint32_t j = threadIdx.x; j < n; j += BLOCK) {
             uint32_t k;
             bool q;
@@ -245,17 +266,9 @@ __global__ __launch_bounds__(BLOCK) void spec_pass_kernel(
                 dst[j] = __uint_as_float(o);
                 if (mdst) mdst[j] = (uint8_t)k;
             }
-            const unsigned long long bal = __ballot(q);
             if (q) {
-                const uint32_t leader = (uint32_t)__ffsll((long long)bal) - 1u;
-                uint32_t base = 0;
-                if (lane == leader) {
-                    base = atomicAdd(&ss->n_cand, (uint32_t)__popcll(bal));
-                    atomicAdd(&s_inside, (uint32_t)__popcll(bal));
-                }
-                base = __shfl(base, leader, 64);
-                const uint32_t pos = base + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
-                if (pos < cap) cand[pos] = make_uint2(bits & 0x7fffffffu, g0 + j);
+                const uint32_t pos = atomicAdd(sub_counter(cnt, CNT_CAND, sb), 1u);
+                if (pos < cap_sb) my_cand[pos] = make_uint2(bits & 0x7fffffffu, g0 + j);
             }
         }
     }
@@ -269,8 +282,7 @@ __global__ __launch_bounds__(BLOCK) void spec_pass_kernel(
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        if (s_below) atomicAdd(&ss->n_below, s_below);
-        if (s_inside) atomicAdd(&ss->n_inside, s_inside);
+        if (s_below) atomicAdd(sub_counter(cnt, CNT_BELOW, sb), s_below);
         if (s_nan) atomicOr(&ss->status, 2u);
     }
     if (FUSED) {
@@ -291,74 +303,124 @@ __global__ __launch_bounds__(BLOCK) void spec_pass_kernel(
     }
 }
 
-// Histogram of the candidate keys relative to lo (exact keys when sh == 0).
-__global__ __launch_bounds__(BLOCK) void spec_hist2_kernel(const SpecState* __restrict__ ss,
-                                                           const uint2* __restrict__ cand,
-                                                           uint32_t cap, uint32_t* hist2) {
-    const uint32_t n = min(ss->n_cand, cap);
-    const uint32_t lo = ss->lo, sh = ss->sh;
-    for (uint32_t i = blockIdx.x * BLOCK + threadIdx.x; i < n; i += gridDim.x * BLOCK)
-        atomicAdd(&hist2[(cand[i].x - lo) >> sh], 1u);
+// Visits every candidate pair: block b of nb walks sub-buffers b, b + nb, ...
+// Every thread of the block calls f the same number of times per sub-buffer round; on
+// the last, ragged round `valid` is false for the threads past the end.
+template <typename F>
+__device__ __forceinline__ void for_each_candidate(const uint32_t* cnt, const uint2* cand,
+                                                   uint32_t cap_sb, F&& f) {
+    for (uint32_t sb = blockIdx.x; sb < SPEC_SUB; sb += gridDim.x) {
+        const uint32_t n = min(cnt[(CNT_CAND * SPEC_SUB + sb) * 32u], cap_sb);
+        const uint2* src = cand + (size_t)sb * cap_sb;
+        for (uint32_t i0 = 0; i0 < n; i0 += BLOCK) {
+            const uint32_t i = i0 + threadIdx.x;
+            const bool valid = i < n;
+            f(valid ? src[i] : make_uint2(0, 0), valid);
+        }
+    }
 }
 
-// One block: the check that makes the result exact, then the bin holding the P-th pair.
+// Round 1: per-block LDS histogram of (key - lo) >> sh over the candidates; the partial
+// histograms go to global memory side by side (no atomics), the locate kernel sums them.
+__global__ __launch_bounds__(BLOCK) void spec_hist_kernel(const SpecState* __restrict__ ss,
+                                                          const uint32_t* __restrict__ cnt,
+                                                          const uint2* __restrict__ cand,
+                                                          uint32_t cap_sb, uint32_t* partial) {
+    __shared__ uint32_t h[FBINS];
+    for (uint32_t i = threadIdx.x; i < FBINS; i += BLOCK) h[i] = 0;
+    __syncthreads();
+    const uint32_t lo = ss->lo, sh = ss->sh;
+    for_each_candidate(cnt, cand, cap_sb, [&](uint2 c, bool valid) {
+        if (valid) atomicAdd(&h[(c.x - lo) >> sh], 1u);
+    });
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < FBINS; i += BLOCK) partial[blockIdx.x * FBINS + i] = h[i];
+}
+
+// One block: totals of the split counters, the check that makes the result exact, then
+// the round-1 bin holding the P-th pair.
 __global__ __launch_bounds__(BLOCK) void spec_locate_kernel(SpecState* ss,
-                                                            const uint32_t* __restrict__ hist2,
-                                                            uint32_t cap) {
+                                                            const uint32_t* __restrict__ cnt,
+                                                            const uint32_t* __restrict__ partial,
+                                                            uint32_t cap_sb) {
     __shared__ uint64_t smem[BLOCK / 64 + 1];
+    __shared__ uint32_t s_over;
     const uint64_t p = ss->p;
+    if (threadIdx.x == 0) s_over = 0;
+    __syncthreads();
+    uint64_t below = 0, inside = 0, tot;
+    static_assert(SPEC_SUB == BLOCK, "one split counter per thread");
+    {
+        const uint32_t c = cnt[(CNT_CAND * SPEC_SUB + threadIdx.x) * 32u];
+        const uint32_t b = cnt[(CNT_BELOW * SPEC_SUB + threadIdx.x) * 32u];
+        block_excl_scan_u64(c, smem, &inside);
+        block_excl_scan_u64(b, smem, &below);
+        if (c > cap_sb) s_over = 1;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) { ss->n_below = below; ss->n_inside = inside; }
     if (p == 0) return;
-    const uint64_t below = ss->n_below, inside = ss->n_inside;
-    if (ss->n_cand > cap || !(below < p && p <= below + inside)) {
+    if (s_over || !(below < p && p <= below + inside)) {
         if (threadIdx.x == 0) atomicOr(&ss->status, 1u);
         return;
     }
     const uint64_t r = p - below;
-    constexpr uint32_t PER = SBINS / BLOCK;
+    constexpr uint32_t PER = FBINS / BLOCK;
     const uint32_t b0 = threadIdx.x * PER;
+    uint32_t c[PER];
     uint64_t sum = 0;
-    for (uint32_t i = 0; i < PER; ++i) sum += hist2[b0 + i];
-    uint64_t total;
-    uint64_t base = block_excl_scan_u64(sum, smem, &total);
+    for (uint32_t i = 0; i < PER; ++i) c[i] = 0;
+    for (uint32_t q = 0; q < FIN_BLOCKS; ++q)
+        for (uint32_t i = 0; i < PER; ++i) c[i] += partial[q * FBINS + b0 + i];
+    for (uint32_t i = 0; i < PER; ++i) sum += c[i];
+    uint64_t base = block_excl_scan_u64(sum, smem, &tot);
     if (base < r && r <= base + sum) {
         for (uint32_t i = 0; i < PER; ++i) {
-            const uint32_t c = hist2[b0 + i];
-            if (r <= base + c) {
+            if (r <= base + c[i]) {
                 ss->bin = b0 + i;
-                ss->bin_cnt = c;
+                ss->bin_cnt = c[i];
                 ss->r2 = r - base;
                 ss->less = below + base;
-                if (c > SPEC_SMALL_CAP) atomicOr(&ss->status, 1u);
+                if (c[i] > SPEC_LIST_CAP) atomicOr(&ss->status, 1u);
                 break;
             }
-            base += c;
+            base += c[i];
         }
     }
 }
 
-// Candidates of the selected bin -> a small list.
+// Candidates of the selected round-1 bin -> list (one atomic per wavefront that has any).
 __global__ __launch_bounds__(BLOCK) void spec_filter_kernel(SpecState* ss,
+                                                            const uint32_t* __restrict__ cnt,
                                                             const uint2* __restrict__ cand,
-                                                            uint32_t cap, uint2* small) {
+                                                            uint32_t cap_sb, uint2* list) {
     if (ss->p == 0 || (ss->status & 1u)) return;
-    const uint32_t n = min(ss->n_cand, cap);
     const uint32_t lo = ss->lo, sh = ss->sh, bin = ss->bin;
-    for (uint32_t i = blockIdx.x * BLOCK + threadIdx.x; i < n; i += gridDim.x * BLOCK) {
-        const uint2 c = cand[i];
-        if (((c.x - lo) >> sh) == bin) {
-            const uint32_t pos = atomicAdd(&ss->small_cnt, 1u);
-            if (pos < SPEC_SMALL_CAP) small[pos] = c;
+    const uint32_t lane = threadIdx.x & 63u;
+    for_each_candidate(cnt, cand, cap_sb, [&](uint2 c, bool valid) {
+        const bool hit = valid && ((c.x - lo) >> sh) == bin;
+        const unsigned long long bal = __ballot(hit);
+        if (bal) {   // uniform over the wavefront
+            const uint32_t leader = (uint32_t)__ffsll((long long)bal) - 1u;
+            uint32_t base = 0;
+            if (lane == leader) base = atomicAdd(&ss->list_cnt, (uint32_t)__popcll(bal));
+            base = __shfl(base, leader, 64);
+            const uint32_t pos = base + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
+            if (hit && pos < SPEC_LIST_CAP) list[pos] = c;
         }
-    }
+    });
 }
 
-// One block: exact rank inside the small list by counting, then the record.
+// One block: round-2 histogram over the list, then an exact rank (by counting) among the
+// pairs of the selected round-2 bin, then the record.
 __global__ __launch_bounds__(BLOCK) void spec_rank_kernel(SpecState* ss,
-                                                          const uint2* __restrict__ small,
+                                                          const uint2* __restrict__ list,
                                                           shifter_threshold* thr) {
+    __shared__ uint32_t h[FBINS];
     __shared__ uint64_t comp[SPEC_SMALL_CAP];
-    __shared__ uint64_t s_sel;
-    __shared__ uint32_t s_lt, s_eq;
+    __shared__ uint64_t smem[BLOCK / 64 + 1];
+    __shared__ uint64_t s_sel, s_less2, s_r3;
+    __shared__ uint32_t s_lt, s_eq, s_bin2, s_cnt2, s_nb;
     shifter_threshold out;
     out.reserved = 0;
     out.n_prune = ss->p;
@@ -370,27 +432,65 @@ __global__ __launch_bounds__(BLOCK) void spec_rank_kernel(SpecState* ss,
         return;
     }
     if (ss->status & 1u) return;
-    const uint32_t n = min(ss->small_cnt, SPEC_SMALL_CAP);
+    const uint32_t n = min(ss->list_cnt, SPEC_LIST_CAP);
     if (n != ss->bin_cnt) {   // cannot happen unless the buffers were disturbed
         if (threadIdx.x == 0) atomicOr(&ss->status, 1u);
         return;
     }
-    for (uint32_t i = threadIdx.x; i < n; i += BLOCK)
-        comp[i] = ((uint64_t)small[i].x << 32) | small[i].y;
-    if (threadIdx.x == 0) { s_lt = 0; s_eq = 0; s_sel = 0; }
+    // round 2: the list's keys span 2^sh values starting at lo + (bin << sh)
+    const uint32_t sh = ss->sh;
+    const uint32_t sh2 = sh > 12 ? sh - 12 : 0;
+    const uint32_t lo1 = ss->lo + (ss->bin << sh);
+    for (uint32_t i = threadIdx.x; i < FBINS; i += BLOCK) h[i] = 0;
+    if (threadIdx.x == 0) { s_lt = 0; s_eq = 0; s_sel = 0; s_nb = 0; s_cnt2 = 0; s_bin2 = 0; }
     __syncthreads();
-    const uint64_t want = ss->r2 - 1;   // 0-based rank among the list
+    for (uint32_t i = threadIdx.x; i < n; i += BLOCK) atomicAdd(&h[(list[i].x - lo1) >> sh2], 1u);
+    __syncthreads();
+    constexpr uint32_t PER = FBINS / BLOCK;
+    const uint32_t b0 = threadIdx.x * PER;
+    uint64_t sum = 0, tot;
+    for (uint32_t i = 0; i < PER; ++i) sum += h[b0 + i];
+    uint64_t base = block_excl_scan_u64(sum, smem, &tot);
+    const uint64_t r = ss->r2;
+    if (base < r && r <= base + sum) {
+        for (uint32_t i = 0; i < PER; ++i) {
+            const uint32_t c = h[b0 + i];
+            if (r <= base + c) {
+                s_bin2 = b0 + i;
+                s_cnt2 = c;
+                s_r3 = r - base;
+                s_less2 = base;
+                break;
+            }
+            base += c;
+        }
+    }
+    __syncthreads();
+    const uint32_t bin2 = s_bin2, cnt2 = s_cnt2;
+    if (cnt2 == 0 || cnt2 > SPEC_SMALL_CAP) {
+        if (threadIdx.x == 0) atomicOr(&ss->status, 1u);
+        return;
+    }
     for (uint32_t i = threadIdx.x; i < n; i += BLOCK) {
+        const uint2 c = list[i];
+        if (((c.x - lo1) >> sh2) == bin2) {
+            const uint32_t pos = atomicAdd(&s_nb, 1u);
+            comp[pos] = ((uint64_t)c.x << 32) | c.y;   // pos < cnt2 <= SPEC_SMALL_CAP
+        }
+    }
+    __syncthreads();
+    const uint64_t want = s_r3 - 1;   // 0-based rank inside the bin
+    for (uint32_t i = threadIdx.x; i < cnt2; i += BLOCK) {
         const uint64_t c = comp[i];
         uint32_t rank = 0;
-        for (uint32_t f = 0; f < n; ++f) rank += comp[f] < c;
+        for (uint32_t f = 0; f < cnt2; ++f) rank += comp[f] < c;
         if (rank == want) s_sel = c;    // composites are distinct: exactly one hit
     }
     __syncthreads();
     const uint64_t sel = s_sel;
     const uint32_t key = (uint32_t)(sel >> 32);
     uint32_t lt = 0, eq = 0;
-    for (uint32_t i = threadIdx.x; i < n; i += BLOCK) {
+    for (uint32_t i = threadIdx.x; i < cnt2; i += BLOCK) {
         const uint32_t k = (uint32_t)(comp[i] >> 32);
         lt += k < key;
         eq += k == key;
@@ -402,7 +502,7 @@ __global__ __launch_bounds__(BLOCK) void spec_rank_kernel(SpecState* ss,
         out.t_key = key;
         out.g_cut = sel & 0xffffffffull;
         out.cut = sel + 1;
-        out.n_less = ss->less + s_lt;
+        out.n_less = ss->less + s_less2 + s_lt;
         out.n_equal = s_eq;
         *thr = out;
     }
@@ -411,14 +511,14 @@ __global__ __launch_bounds__(BLOCK) void spec_rank_kernel(SpecState* ss,
 // Fused form only: settle the candidates that the pass wrote as kept.
 __global__ __launch_bounds__(BLOCK) void spec_fixup_kernel(
     const DevTensor* __restrict__ tens, const uint32_t* __restrict__ ranked_ids,
-    uint32_t n_ranked, const SpecState* __restrict__ ss, const uint2* __restrict__ cand,
-    uint32_t cap, const shifter_threshold* __restrict__ thr, float* __restrict__ w_out,
-    uint8_t* __restrict__ mask, uint8_t* out_alive, uint8_t* in_alive) {
-    if (ss->status & 1u) return;
-    const uint32_t n = min(ss->n_cand, cap);
+    uint32_t n_ranked, const SpecState* __restrict__ ss, const uint32_t* __restrict__ cnt,
+    const uint2* __restrict__ cand, uint32_t cap_sb, const shifter_threshold* __restrict__ thr,
+    float* __restrict__ w_out, uint8_t* __restrict__ mask, uint8_t* out_alive,
+    uint8_t* in_alive) {
+    if (ss->p == 0 || (ss->status & 1u)) return;
     const uint64_t cut = thr->cut;
-    for (uint32_t i = blockIdx.x * BLOCK + threadIdx.x; i < n; i += gridDim.x * BLOCK) {
-        const uint2 c = cand[i];
+    for_each_candidate(cnt, cand, cap_sb, [&](uint2 c, bool valid) {
+        if (!valid) return;
         // tensor holding global index c.y: last ranked tensor with gbase <= g
         uint32_t a = 0, b = n_ranked;
         while (b - a > 1) {
@@ -436,7 +536,7 @@ __global__ __launch_bounds__(BLOCK) void spec_fixup_kernel(
             f = in_alive + T.in_flag_off + (e / T.khw) % T.in_ch;
             if (*f == 0) *f = 1;
         }
-    }
+    });
 }
 
 void launch_spec_select(shifter_ctx* ctx, const shifter_model* m, const float* d_w, uint64_t p,
@@ -446,48 +546,50 @@ void launch_spec_select(shifter_ctx* ctx, const shifter_model* m, const float* d
     const uint32_t n_t = (uint32_t)m->t.size();
     const bool fused = d_w_out != nullptr;
     hipStream_t s = ctx->stream;
-    const uint32_t tile_stride = m->n_tiles > 32768u ? m->n_tiles / 32768u : 1u;
-    const uint32_t small_grid = ctx->hist_grid;
+    const uint32_t tile_stride = m->n_tiles > 4096u ? m->n_tiles / 4096u : 1u;
     {
         ProfileScope ps(ctx, K_SPEC_INIT);
-        spec_init_kernel<<<128, BLOCK, 0, s>>>(b.spec, b.shist, b.hist2, p, d_out_alive,
-                                               fused ? m->info.sum_out_ch : 0, d_in_alive,
-                                               fused ? m->info.sum_in_ch : 0);
+        spec_init_kernel<<<64, BLOCK, 0, s>>>(b.spec, b.shist, b.spec_cnt, p, d_out_alive,
+                                              fused ? m->info.sum_out_ch : 0, d_in_alive,
+                                              fused ? m->info.sum_in_ch : 0);
     }
     {
         ProfileScope ps(ctx, K_SPEC_SAMPLE);
         const uint32_t sampled = (m->n_tiles + tile_stride - 1) / tile_stride;
-        const uint32_t grid = min(small_grid, (sampled + BLOCK / 64 - 1) / (BLOCK / 64));
+        const uint32_t grid = min(ctx->hist_grid, (sampled + BLOCK / 64 - 1) / (BLOCK / 64));
         spec_sample_kernel<<<grid, BLOCK, 0, s>>>(b.tens, b.tile_prefix, n_t, m->n_tiles,
                                                   tile_stride, d_w, b.spec, b.shist);
     }
     {
         ProfileScope ps(ctx, K_SPEC_PREDICT);
-        spec_predict_kernel<<<1, BLOCK, 0, s>>>(b.spec, b.shist, b.sprefix, m->info.n_prunable);
+        spec_predict_kernel<<<1, BLOCK, 0, s>>>(b.spec, b.shist, b.sprefix, m->info.n_prunable,
+                                                ctx->margin_sigmas);
     }
     {
         ProfileScope ps(ctx, K_SPEC_PASS);
         if (fused)
             spec_pass_kernel<true><<<m->n_tiles, BLOCK, 0, s>>>(
-                b.tens, b.tile_prefix, n_t, d_w, b.spec, b.cand, b.cand_cap, d_w_out, d_mask,
-                d_out_alive, d_in_alive);
+                b.tens, b.tile_prefix, n_t, d_w, b.spec, b.spec_cnt, b.cand, b.cand_cap_sb,
+                d_w_out, d_mask, d_out_alive, d_in_alive);
         else
             spec_pass_kernel<false><<<m->n_tiles, BLOCK, 0, s>>>(
-                b.tens, b.tile_prefix, n_t, d_w, b.spec, b.cand, b.cand_cap, nullptr, nullptr,
-                nullptr, nullptr);
+                b.tens, b.tile_prefix, n_t, d_w, b.spec, b.spec_cnt, b.cand, b.cand_cap_sb,
+                nullptr, nullptr, nullptr, nullptr);
     }
     {
         ProfileScope ps(ctx, K_SPEC_FINISH);
-        spec_hist2_kernel<<<small_grid, BLOCK, 0, s>>>(b.spec, b.cand, b.cand_cap, b.hist2);
-        spec_locate_kernel<<<1, BLOCK, 0, s>>>(b.spec, b.hist2, b.cand_cap);
-        spec_filter_kernel<<<small_grid, BLOCK, 0, s>>>(b.spec, b.cand, b.cand_cap, b.small);
-        spec_rank_kernel<<<1, BLOCK, 0, s>>>(b.spec, b.small, d_thr);
+        spec_hist_kernel<<<FIN_BLOCKS, BLOCK, 0, s>>>(b.spec, b.spec_cnt, b.cand, b.cand_cap_sb,
+                                                      b.partial);
+        spec_locate_kernel<<<1, BLOCK, 0, s>>>(b.spec, b.spec_cnt, b.partial, b.cand_cap_sb);
+        spec_filter_kernel<<<FIN_BLOCKS, BLOCK, 0, s>>>(b.spec, b.spec_cnt, b.cand,
+                                                        b.cand_cap_sb, b.list);
+        spec_rank_kernel<<<1, BLOCK, 0, s>>>(b.spec, b.list, d_thr);
     }
     if (fused) {
         ProfileScope ps(ctx, K_SPEC_FIXUP);
-        spec_fixup_kernel<<<small_grid, BLOCK, 0, s>>>(
-            b.tens, b.ranked_ids, m->n_ranked, b.spec, b.cand, b.cand_cap, d_thr, d_w_out,
-            d_mask, d_out_alive, d_in_alive);
+        spec_fixup_kernel<<<SPEC_SUB, BLOCK, 0, s>>>(
+            b.tens, b.ranked_ids, m->n_ranked, b.spec, b.spec_cnt, b.cand, b.cand_cap_sb, d_thr,
+            d_w_out, d_mask, d_out_alive, d_in_alive);
     }
 }
 

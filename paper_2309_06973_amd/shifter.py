@@ -70,6 +70,8 @@ EXPORTS = {
                                  C.POINTER(C.c_uint64), C.c_uint32, C.c_void_p,
                                  C.POINTER(Threshold)],
     "shifter_set_select_path": [C.c_void_p, C.c_int],
+    "shifter_set_margin_sigmas": [C.c_void_p, C.c_double],
+    "shifter_get_select_stats": [C.c_void_p, C.POINTER(C.c_uint64)],
     "shifter_prune_fused": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p,
                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                             C.POINTER(Threshold)],
@@ -203,6 +205,17 @@ def shifter_global_threshold(ctx: Context, model: Model, d_w, n_prune: Sequence[
 
 def shifter_set_select_path(ctx: Context, path: int) -> None:
     _check(load_library().shifter_set_select_path(ctx.handle, path), ctx.handle)
+
+
+def shifter_set_margin_sigmas(ctx: Context, sigmas: float) -> None:
+    _check(load_library().shifter_set_margin_sigmas(ctx.handle, float(sigmas)), ctx.handle)
+
+
+def shifter_get_select_stats(ctx: Context) -> dict:
+    out = (C.c_uint64 * 8)()
+    _check(load_library().shifter_get_select_stats(ctx.handle, out), ctx.handle)
+    keys = ("path", "n_prune", "n_below", "n_inside", "sample", "lo_key", "hi_key", "status")
+    return dict(zip(keys, [int(x) for x in out]))
 
 
 def shifter_prune_fused(ctx: Context, model: Model, d_w, n_prune: int, d_thr, d_w_out, d_mask,
