@@ -133,7 +133,7 @@ const char* shifter_last_error(const shifter_ctx* ctx);
 /* Validates and copies the descriptor tables.  Host only: touches no GPU.
  * Errors (SHIFTER_ERR_BAD_MODEL): group index out of range, out_ch / in_ch / len not
  * matching the group widths, zero-sized dimension, overlapping tensors or vectors,
- * tensor of 2^32 or more elements, N >= 2^32 - 1, more than 65535 tensors. */
+ * tensor of 2^32 - 8192 or more elements, N >= 2^32 - 1, more than 65535 tensors. */
 int shifter_model_create(const shifter_tensor_desc* tensors, uint32_t n_tensors,
                          const shifter_vec_desc* vecs, uint32_t n_vecs,
                          const shifter_group_desc* groups, uint32_t n_groups,
@@ -171,7 +171,8 @@ int shifter_global_threshold(shifter_ctx* ctx, const shifter_model* model,
 int shifter_set_select_path(shifter_ctx* ctx, int path);
 
 /* Half-width of the key interval the single-pass selection predicts from its sample,
- * in standard deviations of a binomial sample of the same size (default 8).  A wider
+ * in standard deviations of a binomial sample of the same size (default 4; doubled
+ * automatically, up to 64, each time a prediction misses).  A wider
  * interval means more candidate weights to settle after the pass, a narrower one a
  * higher chance that the pass cannot decide and the multi-pass select runs.  Never
  * affects results. */

@@ -82,7 +82,7 @@ static void unbind(shifter_model* m) {
     (void)hipSetDevice(b.device);
     void* ptrs[] = {b.tens, b.groups, b.vecs, b.producers, b.tile_prefix, b.sel, b.ghist,
                     b.tile_cnt, b.plan_t, b.plan_v, b.plan_h, b.out_tile_prefix, b.spec, b.shist,
-                    b.sprefix, b.spec_cnt, b.partial, b.cand, b.list, b.ranked_ids};
+                    b.spec_cnt, b.partial, b.cand, b.list, b.ranked_ids};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     if (b.host_stage) (void)hipHostFree(b.host_stage);
@@ -152,7 +152,7 @@ extern "C" int shifter_model_create(const shifter_tensor_desc* tensors, uint32_t
             return bad("in_ch differs from width of in_group times in_mult", i);
         const uint64_t khw = (uint64_t)t.kh * t.kw;
         const uint64_t numel = (uint64_t)t.out_ch * t.in_ch * khw;
-        if (khw >= (1ull << 32) || numel >= (1ull << 32) || khw * t.in_mult >= (1ull << 32))
+        if (khw >= (1ull << 32) || numel >= (1ull << 32) - 2 * TILE || khw * t.in_mult >= (1ull << 32))
             return bad("tensor of 2^32 or more elements", i);
         DevTensor& d = m->dt[i];
         d.offset = t.offset;
@@ -191,6 +191,20 @@ extern "C" int shifter_model_create(const shifter_tensor_desc* tensors, uint32_t
     for (uint32_t i = 0; i < n_tensors; ++i)
         if (tensors[i].prunable) m->ranked_ids.push_back(i);
     m->n_ranked = (uint32_t)m->ranked_ids.size();
+    // the single-pass selection samples two 32-float lines (rotating with the tile index)
+    // of every sample_tile_stride-th tile; its size is fixed by the descriptors
+    m->sample_tile_stride = m->n_tiles > 4096u ? m->n_tiles / 4096u : 1u;
+    for (uint32_t tile = 0, ti = 0; tile < m->n_tiles; tile += m->sample_tile_stride) {
+        while (m->tile_prefix[ti + 1] <= tile) ++ti;
+        if (!tensors[ti].prunable) continue;
+        const uint64_t e0 = (uint64_t)(tile - m->tile_prefix[ti]) * TILE;
+        const uint64_t n = std::min<uint64_t>(TILE, m->dt[ti].numel - e0);
+        const uint32_t l0 = (tile * 37u) & 63u;
+        for (uint32_t half = 0; half < 2; ++half) {
+            const uint64_t first = (uint64_t)(l0 + half * 64u) * 32u;
+            if (first < n) m->sample_size += (uint32_t)std::min<uint64_t>(32, n - first);
+        }
+    }
     if (gbase >= (1ull << 32) - 1) return bad("N (prunable weights) reaches 2^32 - 1", n_tensors - 1);
     std::sort(spans.begin(), spans.end());
     for (size_t i = 1; i < spans.size(); ++i)
@@ -294,9 +308,8 @@ static int bind(shifter_ctx* ctx, const shifter_model* cm) {
     if ((rc = upload(ctx, &b.ranked_ids, m->ranked_ids.data(), m->ranked_ids.size()))) return rc;
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.spec), sizeof(SpecState)));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.shist), sizeof(uint32_t) * 65536));
-    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.sprefix), sizeof(uint32_t) * 65536));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.spec_cnt), sizeof(uint32_t) * 2 * SPEC_SUB * 32));
-    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.partial), sizeof(uint32_t) * SPEC_FIN_BLOCKS * 4096));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.partial), sizeof(uint32_t) * SPEC_FIN_BLOCKS * 256));
     // candidate pairs: 1/16 of N in total, at least two tiles per sub-buffer
     b.cand_cap_sb = (uint32_t)std::max<uint64_t>(m->info.n_prunable / 16 / SPEC_SUB, 2 * TILE);
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.cand), sizeof(uint2) * (size_t)b.cand_cap_sb * SPEC_SUB));
@@ -338,6 +351,10 @@ static int spec_result(shifter_ctx* ctx, const shifter_model* model, const shift
     memcpy(&ss, st, sizeof ss);
     ctx->last_spec = ss;
     ctx->last_path = (ss.status & 1u) ? 2 : 1;
+    // a prediction that missed (not a tie overflow) widens the margin of later calls
+    if ((ss.status & 1u) && ss.p > 0 && !(ss.n_below < ss.p && ss.p <= ss.n_below + ss.n_inside) &&
+        ctx->margin_sigmas < 64.0)
+        ctx->margin_sigmas *= 2.0;
     if (ss.status & 2u)
         return fail(ctx, SHIFTER_ERR_NONFINITE, "NaN among the prunable weights");
     *decided = (ss.status & 1u) ? 0 : 1;
@@ -528,6 +545,8 @@ extern "C" int shifter_compact(shifter_ctx* ctx, const shifter_model* model, con
     const size_t n_t = model->t.size(), n_v = model->v.size();
     if (!d_w_sparse || !d_keep || !d_new_width || !d_w_out || (n_v && (!d_vecs || !d_vecs_out)))
         return fail(ctx, SHIFTER_ERR_INVALID_ARG, "compact: NULL pointer argument");
+    if (misaligned(d_w_out, 16))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "compact: d_w_out must be 16-byte aligned");
     launch_compact(ctx, model, d_w_sparse, d_vecs, d_keep, d_new_width, d_w_out, cap_w, d_vecs_out, cap_v);
     if ((rc = after_launch(ctx, "compact"))) return rc;
     if (h_out_tensors || h_out_vecs || h_elems_w || h_elems_v) {

@@ -68,8 +68,8 @@ struct SelState {
 
 // State of the single-pass (sample, predict, one pass, finish) selection.
 constexpr uint32_t SPEC_SUB = 256;         // split counters / candidate sub-buffers
-constexpr uint32_t SPEC_FIN_BLOCKS = 128;  // blocks of the finishing passes
-constexpr uint32_t SPEC_LIST_CAP = 16384;  // pairs of the selected round-1 bin
+constexpr uint32_t SPEC_FIN_BLOCKS = 256;  // blocks of the finishing passes
+constexpr uint32_t SPEC_LIST_CAP = 65536;  // pairs of the selected round-1 bin
 constexpr uint32_t SPEC_SMALL_CAP = 1024;  // pairs of the selected round-2 bin
 struct SpecState {
     uint64_t p;          // prune count
@@ -78,11 +78,14 @@ struct SpecState {
     uint64_t n_below;    // weights with key < lo
     uint64_t n_inside;   // weights with lo <= key <= hi (the candidates)
     uint32_t lo, hi;     // inclusive key interval of the candidates
+    uint32_t mid;        // provisional threshold key of the fused pass, lo <= mid <= hi
     uint32_t sh;         // round-1 bin = (key - lo) >> sh
     uint32_t m_valid;    // sample size
     uint32_t status;     // bit 0: not decided, use the multi-pass select; bit 1: NaN seen
     uint32_t bin, bin_cnt;
     uint32_t list_cnt;
+    uint32_t ticket_hist, ticket_filter;   // arrival counters of the finishing kernels
+    uint32_t pad;
 };
 
 struct PruneCounts {
@@ -133,6 +136,8 @@ struct shifter_model {
     uint32_t n_tiles = 0;
     std::vector<uint32_t> ranked_ids;    // indices of the prunable tensors, in order
     uint32_t n_ranked = 0;
+    uint32_t sample_tile_stride = 1;     // every how many tiles the selection samples
+    uint32_t sample_size = 0;            // weights in that sample
 
     // device side, created by the first call that uses the model with a context
     struct Bound {
@@ -152,9 +157,8 @@ struct shifter_model {
         uint32_t* out_tile_prefix = nullptr;  // n_tensors + 1
         shifter::SpecState* spec = nullptr;
         uint32_t* shist = nullptr;            // 65536 sample bins
-        uint32_t* sprefix = nullptr;          // 65536
         uint32_t* spec_cnt = nullptr;         // 2 * SPEC_SUB counters, one 128-byte line each
-        uint32_t* partial = nullptr;          // SPEC_FIN_BLOCKS * 4096 partial histograms
+        uint32_t* partial = nullptr;          // SPEC_FIN_BLOCKS * 256 partial histograms
         uint2* cand = nullptr;                // SPEC_SUB sub-buffers of (key, g) pairs
         uint32_t cand_cap_sb = 0;             // pairs per sub-buffer
         uint2* list = nullptr;                // SPEC_LIST_CAP pairs
@@ -174,7 +178,7 @@ struct shifter_ctx {
     std::vector<hipEvent_t> pool;
     uint32_t hist_grid = 2048;
     int select_path = 0;   // 0: single-pass where it applies; 1: multi-pass radix only
-    double margin_sigmas = 8.0;   // half-width of the predicted interval, in binomial sigmas
+    double margin_sigmas = 4.0;   // half-width of the predicted interval, in binomial sigmas
     shifter::SpecState last_spec{};  // outcome of the last single-pass selection
     int last_path = 0;               // 1: single pass decided; 2: multi-pass select ran
 };

@@ -1,6 +1,8 @@
 // Prune planner (Module 3 / Algorithm 1 of the paper, stated on channel groups) and
 // model pruner (Module 4 / Algorithm 2): per-group survivor lists, then every tensor
 // and per-channel vector gathered into its smaller dense shape.
+#include <algorithm>
+
 #include "dev_common.h"
 
 namespace shifter {
@@ -50,91 +52,132 @@ __global__ __launch_bounds__(BLOCK) void propagate_kernel(
 
 // One block: sizes and offsets of every rebuilt tensor and vector (Algorithm 2, the
 // "create new layer" step), tile prefix of the gather launch, capacity check.
+// A rebuilt tensor is tiled in units of TILE floats of the OUTPUT ARENA starting at the
+// 16-byte boundary at or below its first element, so that the gather stores whole
+// aligned float4s; the ragged first and last quads are written element by element.
 __global__ __launch_bounds__(BLOCK) void plan_kernel(
     const DevTensor* __restrict__ tens, uint32_t n_t, const DevVec* __restrict__ vecs,
     uint32_t n_v, const DevGroup* __restrict__ groups, uint32_t n_g,
     const uint32_t* __restrict__ new_width, uint64_t cap_w, uint64_t cap_v,
     PlanTensor* __restrict__ pt, PlanVec* __restrict__ pv, uint32_t* __restrict__ otp,
     PlanHeader* __restrict__ hdr) {
-    if (threadIdx.x != 0) return;
-    uint64_t off = 0;
-    uint32_t tiles = 0;
-    for (uint32_t t = 0; t < n_t; ++t) {
+    __shared__ uint64_t smem[BLOCK / 64 + 1];
+    __shared__ uint32_t s_collapse;
+    if (threadIdx.x == 0) s_collapse = 0;
+    uint64_t off = 0, tiles = 0, tot;
+    for (uint32_t t0 = 0; t0 < n_t; t0 += BLOCK) {
+        const uint32_t t = t0 + threadIdx.x;
         PlanTensor p;
-        p.o2 = new_width[tens[t].out_group];
-        p.c2 = new_width[tens[t].in_group];
-        p.numel2 = p.o2 * p.c2 * tens[t].kk;
-        p.out_off = off;
-        p.pad = 0;
-        pt[t] = p;
-        otp[t] = tiles;
-        off += p.numel2;
-        tiles += (p.numel2 + TILE - 1) / TILE;
+        p.o2 = p.c2 = p.numel2 = p.pad = 0;
+        if (t < n_t) {
+            p.o2 = new_width[tens[t].out_group];
+            p.c2 = new_width[tens[t].in_group];
+            p.numel2 = p.o2 * p.c2 * tens[t].kk;
+        }
+        const uint64_t my_off = off + block_excl_scan_u64(p.numel2, smem, &tot);
+        off += tot;
+        const uint32_t span = p.numel2 ? (uint32_t)(my_off & 3u) + p.numel2 : 0;
+        const uint32_t my_tiles = (span + TILE - 1) / TILE;
+        const uint64_t my_tile0 = tiles + block_excl_scan_u64(my_tiles, smem, &tot);
+        tiles += tot;
+        if (t < n_t) {
+            p.out_off = my_off;
+            pt[t] = p;
+            otp[t] = (uint32_t)my_tile0;
+        }
     }
-    otp[n_t] = tiles;
     uint64_t voff = 0;
-    for (uint32_t v = 0; v < n_v; ++v) {
+    for (uint32_t v0 = 0; v0 < n_v; v0 += BLOCK) {
+        const uint32_t v = v0 + threadIdx.x;
         PlanVec p;
-        p.len2 = new_width[vecs[v].group];
-        p.out_off = voff;
+        p.len2 = v < n_v ? new_width[vecs[v].group] : 0;
         p.pad = 0;
-        pv[v] = p;
-        voff += p.len2;
+        p.out_off = voff + block_excl_scan_u64(p.len2, smem, &tot);
+        voff += tot;
+        if (v < n_v) pv[v] = p;
     }
-    uint32_t status = 0;
-    if (off > cap_w || voff > cap_v) status |= 1u;
-    for (uint32_t g = 0; g < n_g; ++g)
-        if (new_width[g] == 0) status |= 2u;
-    hdr->elems_w = off;
-    hdr->elems_v = voff;
-    hdr->total_tiles = tiles;
-    hdr->status = status;
+    for (uint32_t g = threadIdx.x; g < n_g; g += BLOCK)
+        if (new_width[g] == 0) s_collapse = 1;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        otp[n_t] = (uint32_t)tiles;
+        hdr->elems_w = off;
+        hdr->elems_v = voff;
+        hdr->total_tiles = (uint32_t)tiles;
+        hdr->status = ((off > cap_w || voff > cap_v) ? 1u : 0u) | (s_collapse ? 2u : 0u);
+    }
 }
 
-// One block per tile of TILE consecutive elements of one rebuilt tensor.  Element
-// (o', c', k) of the output comes from (keep_out[o'], keep_in[c'], k) of the source,
-// where k runs over the kk = kh * kw * in_mult elements of one (filter, channel) pair.
+// Element (o', c', k) of a rebuilt tensor comes from (keep_out[o'], keep_in[c'], k) of the
+// source, where k runs over the kk = kh * kw * in_mult elements of one (filter, channel)
+// pair.  Blocks walk the output tiles; each thread fills aligned quads of the output
+// arena (two divisions per quad, then incremental indices), and the blocks then share
+// the per-channel vectors: v'[j] = v[keep[j]].
 __global__ __launch_bounds__(BLOCK) void gather_kernel(
     const DevTensor* __restrict__ tens, const DevGroup* __restrict__ groups, uint32_t n_t,
     const PlanTensor* __restrict__ pt, const uint32_t* __restrict__ otp,
     const PlanHeader* __restrict__ hdr, const float* __restrict__ w,
-    const uint32_t* __restrict__ keep, float* __restrict__ w_out) {
+    const uint32_t* __restrict__ keep, float* __restrict__ w_out,
+    const DevVec* __restrict__ vecs, uint32_t n_v, const PlanVec* __restrict__ pv,
+    const float* __restrict__ v, float* __restrict__ v_out) {
     if (hdr->status & 1u) return;
-    const uint32_t tile = blockIdx.x;
-    if (tile >= hdr->total_tiles) return;
-    const uint32_t t = find_tensor(otp, n_t, tile);
-    const DevTensor T = tens[t];
-    const PlanTensor P = pt[t];
-    const uint32_t e0 = (tile - otp[t]) * TILE;
-    const uint32_t n = min(TILE, P.numel2 - e0);
-    const uint32_t* keep_o = keep + groups[T.out_group].off;
-    const uint32_t* keep_i = keep + groups[T.in_group].off;
-    const uint32_t row2 = P.c2 * T.kk;
-    const float* src = w + T.offset;
-    float* dst = w_out + P.out_off + e0;
-    for (uint32_t j = threadIdx.x; j < n; j += BLOCK) {
-        const uint32_t idx = e0 + j;
-        const uint32_t o2 = idx / row2;
-        const uint32_t rem = idx - o2 * row2;
-        const uint32_t c2 = rem / T.kk;
-        const uint32_t k = rem - c2 * T.kk;
-        const uint64_t s = ((uint64_t)keep_o[o2] * T.cin + keep_i[c2]) * T.kk + k;
-        dst[j] = src[s];
+    const uint32_t total = hdr->total_tiles;
+    for (uint32_t tile = blockIdx.x; tile < total; tile += gridDim.x) {
+        const uint32_t t = find_tensor(otp, n_t, tile);
+        const DevTensor T = tens[t];
+        const PlanTensor P = pt[t];
+        const uint32_t* keep_o = keep + groups[T.out_group].off;
+        const uint32_t* keep_i = keep + groups[T.in_group].off;
+        const uint32_t row2 = P.c2 * T.kk;
+        const float* src = w + T.offset;
+        // arena position of this tile's first quad, and of the tensor's ends
+        const uint64_t a0 = (P.out_off & ~3ull) + (uint64_t)(tile - otp[t]) * TILE;
+        const uint64_t begin = P.out_off, end = P.out_off + P.numel2;
+#pragma unroll
+        for (uint32_t u = 0; u < TILE / BLOCK / 4; ++u) {
+            const uint64_t pq = a0 + 4ull * (threadIdx.x + BLOCK * u);
+            if (pq >= end || pq + 4 <= begin) continue;
+            const uint64_t first = pq < begin ? begin : pq;
+            const uint32_t idx = (uint32_t)(first - begin);
+            uint32_t o2 = idx / row2;
+            const uint32_t rem = idx - o2 * row2;
+            uint32_t c2 = rem / T.kk;
+            uint32_t k = rem - c2 * T.kk;
+            uint64_t so = (uint64_t)keep_o[o2] * T.cin;
+            uint64_t sc = (so + keep_i[c2]) * T.kk;
+            float val[4];
+            const uint32_t n_valid = (uint32_t)((pq + 4 < end ? pq + 4 : end) - first);
+#pragma unroll
+            for (uint32_t c = 0; c < 4; ++c) {
+                if (c < n_valid) {
+                    val[c] = src[sc + k];
+                    if (++k == T.kk) {
+                        k = 0;
+                        if (++c2 == P.c2) {
+                            c2 = 0;
+                            ++o2;
+                            if (o2 < P.o2) so = (uint64_t)keep_o[o2] * T.cin;
+                        }
+                        if (o2 < P.o2) sc = (so + keep_i[c2]) * T.kk;
+                    }
+                }
+            }
+            if (first == pq && n_valid == 4) {
+                *reinterpret_cast<float4*>(w_out + pq) = make_float4(val[0], val[1], val[2], val[3]);
+            } else {
+#pragma unroll
+                for (uint32_t c = 0; c < 4; ++c)
+                    if (c < n_valid) w_out[first + c] = val[c];
+            }
+        }
     }
-}
-
-// One block per vector: v'[j] = v[keep[j]].
-__global__ __launch_bounds__(BLOCK) void gather_vec_kernel(
-    const DevVec* __restrict__ vecs, const DevGroup* __restrict__ groups,
-    const PlanVec* __restrict__ pv, const PlanHeader* __restrict__ hdr,
-    const float* __restrict__ v, const uint32_t* __restrict__ keep,
-    float* __restrict__ v_out) {
-    if (hdr->status & 1u) return;
-    const DevVec V = vecs[blockIdx.x];
-    const PlanVec P = pv[blockIdx.x];
-    const uint32_t* kp = keep + groups[V.group].off;
-    for (uint32_t j = threadIdx.x; j < P.len2; j += BLOCK)
-        v_out[P.out_off + j] = v[V.offset + kp[j]];
+    for (uint32_t vi = blockIdx.x; vi < n_v; vi += gridDim.x) {
+        const DevVec V = vecs[vi];
+        const PlanVec P = pv[vi];
+        const uint32_t* kp = keep + groups[V.group].off;
+        for (uint32_t j = threadIdx.x; j < P.len2; j += BLOCK)
+            v_out[P.out_off + j] = v[V.offset + kp[j]];
+    }
 }
 
 __global__ __launch_bounds__(BLOCK) void copy_kernel(const float4* __restrict__ src,
@@ -178,15 +221,13 @@ void launch_compact(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
                                                   b.plan_h);
     }
     {
-        // worst-case grid (nothing removed); blocks past the real tile count exit at once
+        // the tile count is only known on the device: a fixed grid walks the tiles
         ProfileScope p(ctx, K_GATHER);
-        gather_kernel<<<m->n_tiles, BLOCK, 0, ctx->stream>>>(
-            b.tens, b.groups, n_t, b.plan_t, b.out_tile_prefix, b.plan_h, d_w, d_keep, d_w_out);
-    }
-    if (n_v) {
-        ProfileScope p(ctx, K_GATHER_VEC);
-        gather_vec_kernel<<<n_v, BLOCK, 0, ctx->stream>>>(b.vecs, b.groups, b.plan_v, b.plan_h,
-                                                          d_vecs, d_keep, d_vecs_out);
+        const uint32_t bound = m->n_tiles + n_t;   // tiles when nothing is removed, at most
+        const uint32_t grid = std::max(1u, std::min(bound, ctx->hist_grid * 2));
+        gather_kernel<<<grid, BLOCK, 0, ctx->stream>>>(
+            b.tens, b.groups, n_t, b.plan_t, b.out_tile_prefix, b.plan_h, d_w, d_keep, d_w_out,
+            b.vecs, n_v, b.plan_v, d_vecs, d_vecs_out);
     }
 }
 

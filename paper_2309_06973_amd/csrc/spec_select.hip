@@ -11,9 +11,9 @@
 //                  form the same pass already writes the sparse weights, the mask and
 //                  the alive flags for every weight outside the interval;
 //   4. finish      if  n_below < P <= n_below + n_candidates  the P-th pair is the
-//                  (P - n_below)-th candidate: two rounds of 4096-bin LDS histograms
-//                  over the candidates and an exact rank inside the last bin give the
-//                  record; the fused form then settles the candidates only.
+//                  (P - n_below)-th candidate: a 256-bin histogram over the candidates,
+//                  a 4096-bin one over the selected bin, and an exact rank inside the
+//                  last bin give the record; the fused form then settles the candidates.
 //
 // The result is exact whenever step 4's check holds; otherwise (a sample that misled,
 // an interval with too many ties, a full buffer) a status bit is raised and the host
@@ -22,9 +22,10 @@
 
 namespace shifter {
 
-constexpr uint32_t SBINS = 65536;       // sample histogram bins
-constexpr uint32_t SAMPLE_SHIFT = 15;   // sample bins: top 16 of the 31 key bits
-constexpr uint32_t FBINS = 4096;        // bins of the two finishing histograms (LDS)
+constexpr uint32_t SBINS = 16384;       // sample histogram bins
+constexpr uint32_t SAMPLE_SHIFT = 17;   // sample bins: top 14 of the 31 key bits
+constexpr uint32_t FBINS1 = 256;        // round-1 finishing histogram: one bin per thread
+constexpr uint32_t FBINS = 4096;        // round-2 finishing histogram (one block, LDS)
 constexpr uint32_t FIN_BLOCKS = SPEC_FIN_BLOCKS;  // blocks of the passes over candidates
 
 // Global atomics to one address serialise (about 11 ns each on this chip), so every
@@ -37,8 +38,8 @@ __device__ __forceinline__ uint32_t* sub_counter(uint32_t* cnt, uint32_t which, 
 
 __global__ __launch_bounds__(BLOCK) void spec_init_kernel(SpecState* ss, uint32_t* shist,
                                                           uint32_t* cnt, uint64_t p,
-                                                          uint8_t* fa, uint64_t na,
-                                                          uint8_t* fb, uint64_t nb) {
+                                                          uint32_t m_valid, uint8_t* fa,
+                                                          uint64_t na, uint8_t* fb, uint64_t nb) {
     const uint64_t tid = (uint64_t)blockIdx.x * BLOCK + threadIdx.x;
     const uint64_t stride = (uint64_t)gridDim.x * BLOCK;
     for (uint64_t i = tid; i < SBINS; i += stride) shist[i] = 0;
@@ -49,11 +50,14 @@ __global__ __launch_bounds__(BLOCK) void spec_init_kernel(SpecState* ss, uint32_
         ss->p = p;
         ss->n_below = 0;
         ss->n_inside = 0;
-        ss->m_valid = 0;
+        ss->m_valid = m_valid;
         ss->status = 0;
         ss->list_cnt = 0;
+        ss->ticket_hist = 0;
+        ss->ticket_filter = 0;
         ss->lo = 0;
         ss->hi = 0x7fffffffu;
+        ss->mid = 0;
         ss->sh = 19;
     }
 }
@@ -63,11 +67,10 @@ __global__ __launch_bounds__(BLOCK) void spec_init_kernel(SpecState* ss, uint32_
 __global__ __launch_bounds__(BLOCK) void spec_sample_kernel(
     const DevTensor* __restrict__ tens, const uint32_t* __restrict__ tile_prefix,
     uint32_t n_t, uint32_t n_tiles, uint32_t tile_stride, const float* __restrict__ w,
-    SpecState* ss, uint32_t* shist) {
+    uint32_t* shist) {
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = blockIdx.x * (BLOCK / 64) + (threadIdx.x >> 6);
     const uint32_t n_waves = gridDim.x * (BLOCK / 64);
-    uint32_t taken = 0;
     for (uint32_t s = wave; (uint64_t)s * tile_stride < n_tiles; s += n_waves) {
         const uint32_t tile = s * tile_stride;
         const uint32_t t = find_tensor(tile_prefix, n_t, tile);
@@ -79,65 +82,81 @@ __global__ __launch_bounds__(BLOCK) void spec_sample_kernel(
         if (j < n) {
             const uint32_t key = key_of(w[tens[t].offset + e0 + j]);
             atomicAdd(&shist[key >> SAMPLE_SHIFT], 1u);
-            ++taken;
         }
     }
-    for (uint32_t d = 32; d > 0; d >>= 1) taken += __shfl_down(taken, d, 64);
-    if (lane == 0 && taken) atomicAdd(&ss->m_valid, taken);
 }
 
-// One block: inclusive prefix of the sample histogram, then the candidate interval.
+// One block: the sample's order statistics around P/N give the candidate interval
+// [lo, hi] and a provisional threshold mid (the fused pass writes candidates below mid as
+// removed, the others as kept; few of them then need correcting).
+// The histogram is read as 64 segments of 256 bins, one coalesced load per wavefront.
 __global__ __launch_bounds__(BLOCK) void spec_predict_kernel(SpecState* ss,
                                                              const uint32_t* __restrict__ shist,
-                                                             uint32_t* sprefix,
                                                              uint64_t n_prunable,
                                                              double margin_sigmas) {
+    constexpr uint32_t SEG = 256, NSEG = SBINS / SEG;   // 64 segments
+    static_assert(NSEG <= BLOCK, "one segment sum per thread");
     __shared__ uint64_t smem[BLOCK / 64 + 1];
-    constexpr uint32_t PER = SBINS / BLOCK;
-    const uint32_t b0 = threadIdx.x * PER;
-    uint64_t sum = 0;
-    for (uint32_t i = 0; i < PER; ++i) sum += shist[b0 + i];
-    uint64_t total;
-    uint64_t run = block_excl_scan_u64(sum, smem, &total);
-    for (uint32_t i = 0; i < PER; ++i) {
-        run += shist[b0 + i];
-        sprefix[b0 + i] = (uint32_t)run;
+    __shared__ uint32_t seg_sum[NSEG];
+    __shared__ uint32_t s_bin[3];
+    const uint32_t lane = threadIdx.x & 63u, wid = threadIdx.x >> 6;
+    for (uint32_t sg = wid; sg < NSEG; sg += BLOCK / 64) {
+        const uint4 x = reinterpret_cast<const uint4*>(shist + sg * SEG)[lane];
+        uint32_t v = x.x + x.y + x.z + x.w;
+        for (uint32_t d = 32; d > 0; d >>= 1) v += __shfl_down(v, d, 64);
+        if (lane == 0) seg_sum[sg] = v;
     }
-    __threadfence();
+    if (threadIdx.x < 3) s_bin[threadIdx.x] = 0xffffffffu;
     __syncthreads();
-    if (threadIdx.x != 0) return;
+    const uint64_t mine = threadIdx.x < NSEG ? seg_sum[threadIdx.x] : 0;
+    uint64_t total;
+    const uint64_t base = block_excl_scan_u64(mine, smem, &total);
     const uint64_t p = ss->p;
     const uint32_t m = ss->m_valid;
-    uint32_t lo = 0, hi = 0x7fffffffu;
-    if (p > 0 && m >= 256 && n_prunable > 0) {
+    const bool use = p > 0 && m >= 256 && n_prunable > 0 && total == m;
+    double r[3] = {0, 0, 0};   // 0-based sample ranks: low end, high end, centre
+    if (use) {
         const double frac = (double)p / (double)n_prunable;
         const double centre = frac * (double)m;
         // a multiple of the binomial deviation of a simple random sample of this size
         const double delta = margin_sigmas * sqrt((double)m * frac * (1.0 - frac)) + 16.0;
-        const double r_lo = centre - delta, r_hi = centre + delta;
-        // first bin whose inclusive prefix exceeds r (holds the r-th sample, 0-based)
-        auto bin_of = [&](double r) -> uint32_t {
-            const uint32_t target = (uint32_t)r;
-            uint32_t a = 0, b = SBINS - 1;
-            while (a < b) {
-                const uint32_t mid = (a + b) >> 1;
-                if (sprefix[mid] > target) b = mid; else a = mid + 1;
-            }
-            return a;
-        };
-        if (r_lo > 0.0) lo = bin_of(r_lo) << SAMPLE_SHIFT;
-        if (r_hi < (double)(m - 1)) hi = ((bin_of(r_hi) + 1u) << SAMPLE_SHIFT) - 1u;
+        r[0] = centre - delta;
+        r[1] = centre + delta;
+        r[2] = centre;
     }
+    // bin holding the r-th sample: the thread whose segment covers that rank walks it
+    for (uint32_t q = 0; q < 3; ++q) {
+        if (!use || r[q] < 0.0 || r[q] >= (double)m) continue;
+        const uint64_t target = (uint64_t)r[q];
+        if (base <= target && target < base + mine) {
+            uint64_t run = base;
+            for (uint32_t i = 0; i < SEG; ++i) {
+                run += shist[threadIdx.x * SEG + i];
+                if (run > target) { s_bin[q] = threadIdx.x * SEG + i; break; }
+            }
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    uint32_t lo = 0, hi = 0x7fffffffu;
+    if (s_bin[0] != 0xffffffffu) lo = s_bin[0] << SAMPLE_SHIFT;
+    if (s_bin[1] != 0xffffffffu && r[1] < (double)(m - 1)) hi = ((s_bin[1] + 1u) << SAMPLE_SHIFT) - 1u;
+    uint32_t mid = lo;
+    if (s_bin[2] != 0xffffffffu) mid = (s_bin[2] << SAMPLE_SHIFT) + (1u << (SAMPLE_SHIFT - 1));
+    mid = max(lo, min(mid, hi));
     uint32_t sh = 0;
-    while (((hi - lo) >> sh) >= FBINS) ++sh;
+    while (((hi - lo) >> sh) >= FBINS1) ++sh;
     ss->lo = lo;
     ss->hi = hi;
+    ss->mid = mid;
     ss->sh = sh;
 }
 
-// The one pass over the arena.  FUSED also writes the sparse weights, the mask and the
-// alive flags of every weight outside the candidate interval (candidates are written as
-// kept and carry no flag yet; spec_fixup_kernel settles them).
+// The one pass over the arena.  FUSED also writes the sparse weights and the mask of
+// every weight (those of the candidates provisionally: removed below mid, kept from mid
+// on) and the alive flags of the kept weights outside the candidate interval;
+// spec_fixup_kernel settles the candidates.  A candidate pair holds the weight's full bit
+// pattern (sign included, so a wrongly removed weight can be restored) and its index.
 template <bool FUSED>
 __global__ __launch_bounds__(BLOCK) void spec_pass_kernel(
     const DevTensor* __restrict__ tens, const uint32_t* __restrict__ tile_prefix,
@@ -153,7 +172,7 @@ __global__ __launch_bounds__(BLOCK) void spec_pass_kernel(
     const DevTensor T = tens[t];
     if (!FUSED && !T.prunable) return;
     const bool ranked = T.prunable != 0 && ss->p != 0;   // P = 0: nothing is removed
-    const uint32_t lo = ss->lo, hi = ss->hi;
+    const uint32_t lo = ss->lo, hi = ss->hi, mid = ss->mid;
     const uint32_t e0 = (tile - tile_prefix[t]) * TILE;
     const uint32_t n = min(TILE, T.numel - e0);
     const uint32_t g0 = (uint32_t)(T.gbase + e0);
@@ -180,9 +199,9 @@ __global__ __launch_bounds__(BLOCK) void spec_pass_kernel(
     // classifies one weight: returns the bits to store, sets keep / is_cand
     auto one = [&](uint32_t j, uint32_t bits, uint32_t& keep, bool& is_cand) -> uint32_t {
         const uint32_t key = bits & 0x7fffffffu;
-        const bool removed = ranked && key < lo;
+        const bool removed = ranked && key < mid;       // lo <= mid <= hi
         is_cand = ranked && key >= lo && key <= hi;
-        below += removed ? 1u : 0u;
+        below += (ranked && key < lo) ? 1u : 0u;
         nan |= (ranked && key > 0x7f800000u) ? 1u : 0u;
         keep = removed ? 0u : 1u;
         if (FUSED && !removed && !is_cand && key != 0) {
@@ -248,7 +267,7 @@ __global__ __launch_bounds__(BLOCK) void spec_pass_kernel(
                     for (uint32_t q = 0; q < 4; ++q) {
                         if (cmask & (1u << (4 * u + q))) {
                             if (pos < cap_sb)
-                                my_cand[pos] = make_uint2(vv[q] & 0x7fffffffu, g0 + j + q);
+                                my_cand[pos] = make_uint2(vv[q], g0 + j + q);
                             ++pos;
                         }
                     }
@@ -268,7 +287,7 @@ __global__ __launch_bounds__(BLOCK) void spec_pass_kernel(
             }
             if (q) {
                 const uint32_t pos = atomicAdd(sub_counter(cnt, CNT_CAND, sb), 1u);
-                if (pos < cap_sb) my_cand[pos] = make_uint2(bits & 0x7fffffffu, g0 + j);
+                if (pos < cap_sb) my_cand[pos] = make_uint2(bits, g0 + j);
             }
         }
     }
@@ -303,47 +322,41 @@ __global__ __launch_bounds__(BLOCK) void spec_pass_kernel(
     }
 }
 
-// Visits every candidate pair: block b of nb walks sub-buffers b, b + nb, ...
-// Every thread of the block calls f the same number of times per sub-buffer round; on
-// the last, ragged round `valid` is false for the threads past the end.
+// Visits every candidate pair.  The grid is a multiple of SPEC_SUB blocks: block b walks
+// sub-buffer b % SPEC_SUB, taking every (gridDim / SPEC_SUB)-th chunk of BLOCK pairs.
+// Every thread of the block calls f the same number of times; `valid` is false for the
+// threads past the end of the last, ragged chunk.
 template <typename F>
 __device__ __forceinline__ void for_each_candidate(const uint32_t* cnt, const uint2* cand,
                                                    uint32_t cap_sb, F&& f) {
-    for (uint32_t sb = blockIdx.x; sb < SPEC_SUB; sb += gridDim.x) {
-        const uint32_t n = min(cnt[(CNT_CAND * SPEC_SUB + sb) * 32u], cap_sb);
-        const uint2* src = cand + (size_t)sb * cap_sb;
-        for (uint32_t i0 = 0; i0 < n; i0 += BLOCK) {
-            const uint32_t i = i0 + threadIdx.x;
-            const bool valid = i < n;
-            f(valid ? src[i] : make_uint2(0, 0), valid);
-        }
+    const uint32_t sb = blockIdx.x % SPEC_SUB, part = blockIdx.x / SPEC_SUB;
+    const uint32_t parts = gridDim.x / SPEC_SUB;
+    const uint32_t n = min(cnt[(CNT_CAND * SPEC_SUB + sb) * 32u], cap_sb);
+    const uint2* src = cand + (size_t)sb * cap_sb;
+    for (uint32_t i0 = part * BLOCK; i0 < n; i0 += parts * BLOCK) {
+        const uint32_t i = i0 + threadIdx.x;
+        const bool valid = i < n;
+        f(valid ? src[i] : make_uint2(0, 0), valid);
     }
 }
 
-// Round 1: per-block LDS histogram of (key - lo) >> sh over the candidates; the partial
-// histograms go to global memory side by side (no atomics), the locate kernel sums them.
-__global__ __launch_bounds__(BLOCK) void spec_hist_kernel(const SpecState* __restrict__ ss,
-                                                          const uint32_t* __restrict__ cnt,
-                                                          const uint2* __restrict__ cand,
-                                                          uint32_t cap_sb, uint32_t* partial) {
-    __shared__ uint32_t h[FBINS];
-    for (uint32_t i = threadIdx.x; i < FBINS; i += BLOCK) h[i] = 0;
+// True for the block that arrives last at a kernel-wide rendezvous; every thread's
+// earlier global writes are then visible to that block.
+__device__ __forceinline__ bool last_block(uint32_t* ticket) {
+    __shared__ uint32_t s_last;
+    __threadfence();
     __syncthreads();
-    const uint32_t lo = ss->lo, sh = ss->sh;
-    for_each_candidate(cnt, cand, cap_sb, [&](uint2 c, bool valid) {
-        if (valid) atomicAdd(&h[(c.x - lo) >> sh], 1u);
-    });
+    if (threadIdx.x == 0) s_last = atomicAdd(ticket, 1u) == gridDim.x - 1 ? 1u : 0u;
     __syncthreads();
-    for (uint32_t i = threadIdx.x; i < FBINS; i += BLOCK) partial[blockIdx.x * FBINS + i] = h[i];
+    if (!s_last) return false;
+    __threadfence();
+    return true;
 }
 
-// One block: totals of the split counters, the check that makes the result exact, then
-// the round-1 bin holding the P-th pair.
-__global__ __launch_bounds__(BLOCK) void spec_locate_kernel(SpecState* ss,
-                                                            const uint32_t* __restrict__ cnt,
-                                                            const uint32_t* __restrict__ partial,
-                                                            uint32_t cap_sb) {
-    __shared__ uint64_t smem[BLOCK / 64 + 1];
+// Totals of the split counters, the check that makes the result exact, then the round-1
+// bin holding the P-th pair.  Run by one block.
+__device__ void spec_locate(SpecState* ss, const uint32_t* cnt, const uint32_t* partial,
+                            uint32_t cap_sb, uint64_t* smem) {
     __shared__ uint32_t s_over;
     const uint64_t p = ss->p;
     if (threadIdx.x == 0) s_over = 0;
@@ -365,73 +378,50 @@ __global__ __launch_bounds__(BLOCK) void spec_locate_kernel(SpecState* ss,
         return;
     }
     const uint64_t r = p - below;
-    constexpr uint32_t PER = FBINS / BLOCK;
-    const uint32_t b0 = threadIdx.x * PER;
-    uint32_t c[PER];
-    uint64_t sum = 0;
-    for (uint32_t i = 0; i < PER; ++i) c[i] = 0;
-    for (uint32_t q = 0; q < FIN_BLOCKS; ++q)
-        for (uint32_t i = 0; i < PER; ++i) c[i] += partial[q * FBINS + b0 + i];
-    for (uint32_t i = 0; i < PER; ++i) sum += c[i];
-    uint64_t base = block_excl_scan_u64(sum, smem, &tot);
-    if (base < r && r <= base + sum) {
-        for (uint32_t i = 0; i < PER; ++i) {
-            if (r <= base + c[i]) {
-                ss->bin = b0 + i;
-                ss->bin_cnt = c[i];
-                ss->r2 = r - base;
-                ss->less = below + base;
-                if (c[i] > SPEC_LIST_CAP) atomicOr(&ss->status, 1u);
-                break;
-            }
-            base += c[i];
-        }
+    static_assert(FBINS1 == BLOCK, "one round-1 bin per thread");
+    uint32_t c = 0;
+#pragma unroll 8
+    for (uint32_t q = 0; q < FIN_BLOCKS; ++q) c += partial[q * FBINS1 + threadIdx.x];
+    const uint64_t base = block_excl_scan_u64(c, smem, &tot);
+    if (base < r && r <= base + c) {
+        ss->bin = threadIdx.x;
+        ss->bin_cnt = c;
+        ss->r2 = r - base;
+        ss->less = below + base;
+        if (c > SPEC_LIST_CAP) atomicOr(&ss->status, 1u);
     }
 }
 
-// Candidates of the selected round-1 bin -> list (one atomic per wavefront that has any).
-__global__ __launch_bounds__(BLOCK) void spec_filter_kernel(SpecState* ss,
-                                                            const uint32_t* __restrict__ cnt,
-                                                            const uint2* __restrict__ cand,
-                                                            uint32_t cap_sb, uint2* list) {
-    if (ss->p == 0 || (ss->status & 1u)) return;
-    const uint32_t lo = ss->lo, sh = ss->sh, bin = ss->bin;
-    const uint32_t lane = threadIdx.x & 63u;
+// Round 1: per-block LDS histogram of (key - lo) >> sh (256 bins) over the candidates; the partial
+// histograms go to global memory side by side (no atomics); the block that finishes last
+// sums them and locates the bin.
+__global__ __launch_bounds__(BLOCK) void spec_hist_kernel(SpecState* ss,
+                                                          const uint32_t* cnt,
+                                                          const uint2* __restrict__ cand,
+                                                          uint32_t cap_sb, uint32_t* partial) {
+    __shared__ uint32_t h[FBINS1];
+    __shared__ uint64_t smem[BLOCK / 64 + 1];
+    h[threadIdx.x] = 0;
+    __syncthreads();
+    const uint32_t lo = ss->lo, sh = ss->sh;
     for_each_candidate(cnt, cand, cap_sb, [&](uint2 c, bool valid) {
-        const bool hit = valid && ((c.x - lo) >> sh) == bin;
-        const unsigned long long bal = __ballot(hit);
-        if (bal) {   // uniform over the wavefront
-            const uint32_t leader = (uint32_t)__ffsll((long long)bal) - 1u;
-            uint32_t base = 0;
-            if (lane == leader) base = atomicAdd(&ss->list_cnt, (uint32_t)__popcll(bal));
-            base = __shfl(base, leader, 64);
-            const uint32_t pos = base + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
-            if (hit && pos < SPEC_LIST_CAP) list[pos] = c;
-        }
+        if (valid) atomicAdd(&h[((c.x & 0x7fffffffu) - lo) >> sh], 1u);
     });
+    __syncthreads();
+    partial[blockIdx.x * FBINS1 + threadIdx.x] = h[threadIdx.x];
+    if (!last_block(&ss->ticket_hist)) return;
+    spec_locate(ss, cnt, partial, cap_sb, smem);
 }
 
-// One block: round-2 histogram over the list, then an exact rank (by counting) among the
-// pairs of the selected round-2 bin, then the record.
-__global__ __launch_bounds__(BLOCK) void spec_rank_kernel(SpecState* ss,
-                                                          const uint2* __restrict__ list,
-                                                          shifter_threshold* thr) {
-    __shared__ uint32_t h[FBINS];
-    __shared__ uint64_t comp[SPEC_SMALL_CAP];
-    __shared__ uint64_t smem[BLOCK / 64 + 1];
+// Round-2 histogram over the list, then an exact rank (by counting) among the pairs of
+// the selected round-2 bin, then the record.  Run by one block.
+__device__ void spec_rank(SpecState* ss, const uint2* list, shifter_threshold* thr,
+                          uint32_t* h, uint64_t* comp, uint64_t* smem) {
     __shared__ uint64_t s_sel, s_less2, s_r3;
     __shared__ uint32_t s_lt, s_eq, s_bin2, s_cnt2, s_nb;
     shifter_threshold out;
     out.reserved = 0;
     out.n_prune = ss->p;
-    if (ss->p == 0) {
-        if (threadIdx.x == 0) {
-            out.cut = 0; out.t_key = 0; out.g_cut = ~0ull; out.n_less = 0; out.n_equal = 0;
-            *thr = out;
-        }
-        return;
-    }
-    if (ss->status & 1u) return;
     const uint32_t n = min(ss->list_cnt, SPEC_LIST_CAP);
     if (n != ss->bin_cnt) {   // cannot happen unless the buffers were disturbed
         if (threadIdx.x == 0) atomicOr(&ss->status, 1u);
@@ -439,12 +429,13 @@ __global__ __launch_bounds__(BLOCK) void spec_rank_kernel(SpecState* ss,
     }
     // round 2: the list's keys span 2^sh values starting at lo + (bin << sh)
     const uint32_t sh = ss->sh;
-    const uint32_t sh2 = sh > 12 ? sh - 12 : 0;
+    const uint32_t sh2 = sh > 12 ? sh - 12 : 0;   // 2^sh keys over FBINS = 2^12 bins
     const uint32_t lo1 = ss->lo + (ss->bin << sh);
     for (uint32_t i = threadIdx.x; i < FBINS; i += BLOCK) h[i] = 0;
     if (threadIdx.x == 0) { s_lt = 0; s_eq = 0; s_sel = 0; s_nb = 0; s_cnt2 = 0; s_bin2 = 0; }
     __syncthreads();
-    for (uint32_t i = threadIdx.x; i < n; i += BLOCK) atomicAdd(&h[(list[i].x - lo1) >> sh2], 1u);
+    for (uint32_t i = threadIdx.x; i < n; i += BLOCK)
+        atomicAdd(&h[((list[i].x & 0x7fffffffu) - lo1) >> sh2], 1u);
     __syncthreads();
     constexpr uint32_t PER = FBINS / BLOCK;
     const uint32_t b0 = threadIdx.x * PER;
@@ -473,9 +464,10 @@ __global__ __launch_bounds__(BLOCK) void spec_rank_kernel(SpecState* ss,
     }
     for (uint32_t i = threadIdx.x; i < n; i += BLOCK) {
         const uint2 c = list[i];
-        if (((c.x - lo1) >> sh2) == bin2) {
+        const uint32_t key = c.x & 0x7fffffffu;
+        if (((key - lo1) >> sh2) == bin2) {
             const uint32_t pos = atomicAdd(&s_nb, 1u);
-            comp[pos] = ((uint64_t)c.x << 32) | c.y;   // pos < cnt2 <= SPEC_SMALL_CAP
+            comp[pos] = ((uint64_t)key << 32) | c.y;   // pos < cnt2 <= SPEC_SMALL_CAP
         }
     }
     __syncthreads();
@@ -508,29 +500,92 @@ __global__ __launch_bounds__(BLOCK) void spec_rank_kernel(SpecState* ss,
     }
 }
 
-// Fused form only: settle the candidates that the pass wrote as kept.
+// Candidates of the selected round-1 bin -> list (one atomic per wavefront that has any);
+// the block that finishes last ranks the list and writes the record.
+__global__ __launch_bounds__(BLOCK) void spec_filter_kernel(SpecState* ss, const uint32_t* cnt,
+                                                            const uint2* __restrict__ cand,
+                                                            uint32_t cap_sb, uint2* list,
+                                                            shifter_threshold* thr) {
+    __shared__ uint32_t h[FBINS];
+    __shared__ uint64_t comp[SPEC_SMALL_CAP];
+    __shared__ uint64_t smem[BLOCK / 64 + 1];
+    if (ss->p == 0) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            shifter_threshold out;
+            out.cut = 0; out.t_key = 0; out.reserved = 0; out.g_cut = ~0ull; out.n_prune = 0;
+            out.n_less = 0; out.n_equal = 0;
+            *thr = out;
+        }
+        return;
+    }
+    if (ss->status & 1u) return;
+    const uint32_t lo = ss->lo, sh = ss->sh, bin = ss->bin;
+    const uint32_t lane = threadIdx.x & 63u, wid = threadIdx.x >> 6;
+    __shared__ uint32_t s_wtot[BLOCK / 64], s_base;
+    for_each_candidate(cnt, cand, cap_sb, [&](uint2 c, bool valid) {
+        // one global atomic per block and chunk that has a hit
+        const bool hit = valid && (((c.x & 0x7fffffffu) - lo) >> sh) == bin;
+        const unsigned long long bal = __ballot(hit);
+        if (lane == 0) s_wtot[wid] = (uint32_t)__popcll(bal);
+        __syncthreads();
+        uint32_t woff = 0, btot = 0;
+#pragma unroll
+        for (uint32_t i = 0; i < BLOCK / 64; ++i) {
+            const uint32_t x = s_wtot[i];
+            if (i < wid) woff += x;
+            btot += x;
+        }
+        if (btot) {   // uniform over the block
+            if (threadIdx.x == 0) s_base = atomicAdd(&ss->list_cnt, btot);
+            __syncthreads();
+            const uint32_t pos = s_base + woff + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
+            if (hit && pos < SPEC_LIST_CAP) list[pos] = c;
+        }
+        __syncthreads();
+    });
+    if (!last_block(&ss->ticket_filter)) return;
+    spec_rank(ss, list, thr, h, comp, smem);
+}
+
+// Fused form only: settle the candidates.  The pass wrote those below mid as removed and
+// the others as kept without flags; with the exact cut known, the few on the wrong side
+// are rewritten and every kept non-zero candidate marks its filter and input feature.
 __global__ __launch_bounds__(BLOCK) void spec_fixup_kernel(
     const DevTensor* __restrict__ tens, const uint32_t* __restrict__ ranked_ids,
     uint32_t n_ranked, const SpecState* __restrict__ ss, const uint32_t* __restrict__ cnt,
     const uint2* __restrict__ cand, uint32_t cap_sb, const shifter_threshold* __restrict__ thr,
     float* __restrict__ w_out, uint8_t* __restrict__ mask, uint8_t* out_alive,
     uint8_t* in_alive) {
+    constexpr uint32_t LDS_T = 1024;
+    __shared__ uint32_t s_gbase[LDS_T];
     if (ss->p == 0 || (ss->status & 1u)) return;
     const uint64_t cut = thr->cut;
+    const uint32_t mid = ss->mid;
+    const bool in_lds = n_ranked <= LDS_T;
+    if (in_lds)
+        for (uint32_t i = threadIdx.x; i < n_ranked; i += BLOCK)
+            s_gbase[i] = (uint32_t)tens[ranked_ids[i]].gbase;
+    __syncthreads();
     for_each_candidate(cnt, cand, cap_sb, [&](uint2 c, bool valid) {
         if (!valid) return;
+        const uint32_t key = c.x & 0x7fffffffu;
+        const bool removed = (((uint64_t)key << 32) | c.y) < cut;
+        const bool written_removed = key < mid;
+        if (removed == written_removed && (removed || key == 0)) return;   // nothing to do
         // tensor holding global index c.y: last ranked tensor with gbase <= g
         uint32_t a = 0, b = n_ranked;
         while (b - a > 1) {
-            const uint32_t mid = (a + b) >> 1;
-            if (tens[ranked_ids[mid]].gbase <= c.y) a = mid; else b = mid;
+            const uint32_t m2 = (a + b) >> 1;
+            const uint32_t gb = in_lds ? s_gbase[m2] : (uint32_t)tens[ranked_ids[m2]].gbase;
+            if (gb <= c.y) a = m2; else b = m2;
         }
         const DevTensor& T = tens[ranked_ids[a]];
         const uint32_t e = c.y - (uint32_t)T.gbase;
-        if ((((uint64_t)c.x << 32) | c.y) < cut) {
-            w_out[T.offset + e] = 0.0f;
-            if (mask) mask[c.y] = 0;
-        } else if (c.x != 0) {
+        if (removed != written_removed) {
+            w_out[T.offset + e] = removed ? 0.0f : __uint_as_float(c.x);
+            if (mask) mask[c.y] = removed ? 0 : 1;
+        }
+        if (!removed && key != 0) {
             uint8_t* f = out_alive + T.out_flag_off + e / T.row_len;
             if (*f == 0) *f = 1;
             f = in_alive + T.in_flag_off + (e / T.khw) % T.in_ch;
@@ -546,10 +601,11 @@ void launch_spec_select(shifter_ctx* ctx, const shifter_model* m, const float* d
     const uint32_t n_t = (uint32_t)m->t.size();
     const bool fused = d_w_out != nullptr;
     hipStream_t s = ctx->stream;
-    const uint32_t tile_stride = m->n_tiles > 4096u ? m->n_tiles / 4096u : 1u;
+    const uint32_t tile_stride = m->sample_tile_stride;
     {
         ProfileScope ps(ctx, K_SPEC_INIT);
-        spec_init_kernel<<<64, BLOCK, 0, s>>>(b.spec, b.shist, b.spec_cnt, p, d_out_alive,
+        spec_init_kernel<<<64, BLOCK, 0, s>>>(b.spec, b.shist, b.spec_cnt, p, m->sample_size,
+                                              d_out_alive,
                                               fused ? m->info.sum_out_ch : 0, d_in_alive,
                                               fused ? m->info.sum_in_ch : 0);
     }
@@ -558,11 +614,11 @@ void launch_spec_select(shifter_ctx* ctx, const shifter_model* m, const float* d
         const uint32_t sampled = (m->n_tiles + tile_stride - 1) / tile_stride;
         const uint32_t grid = min(ctx->hist_grid, (sampled + BLOCK / 64 - 1) / (BLOCK / 64));
         spec_sample_kernel<<<grid, BLOCK, 0, s>>>(b.tens, b.tile_prefix, n_t, m->n_tiles,
-                                                  tile_stride, d_w, b.spec, b.shist);
+                                                  tile_stride, d_w, b.shist);
     }
     {
         ProfileScope ps(ctx, K_SPEC_PREDICT);
-        spec_predict_kernel<<<1, BLOCK, 0, s>>>(b.spec, b.shist, b.sprefix, m->info.n_prunable,
+        spec_predict_kernel<<<1, BLOCK, 0, s>>>(b.spec, b.shist, m->info.n_prunable,
                                                 ctx->margin_sigmas);
     }
     {
@@ -580,14 +636,12 @@ void launch_spec_select(shifter_ctx* ctx, const shifter_model* m, const float* d
         ProfileScope ps(ctx, K_SPEC_FINISH);
         spec_hist_kernel<<<FIN_BLOCKS, BLOCK, 0, s>>>(b.spec, b.spec_cnt, b.cand, b.cand_cap_sb,
                                                       b.partial);
-        spec_locate_kernel<<<1, BLOCK, 0, s>>>(b.spec, b.spec_cnt, b.partial, b.cand_cap_sb);
         spec_filter_kernel<<<FIN_BLOCKS, BLOCK, 0, s>>>(b.spec, b.spec_cnt, b.cand,
-                                                        b.cand_cap_sb, b.list);
-        spec_rank_kernel<<<1, BLOCK, 0, s>>>(b.spec, b.list, d_thr);
+                                                        b.cand_cap_sb, b.list, d_thr);
     }
     if (fused) {
         ProfileScope ps(ctx, K_SPEC_FIXUP);
-        spec_fixup_kernel<<<SPEC_SUB, BLOCK, 0, s>>>(
+        spec_fixup_kernel<<<SPEC_SUB * 4, BLOCK, 0, s>>>(
             b.tens, b.ranked_ids, m->n_ranked, b.spec, b.spec_cnt, b.cand, b.cand_cap_sb, d_thr,
             d_w_out, d_mask, d_out_alive, d_in_alive);
     }
