@@ -14,7 +14,7 @@ const char* const kKernelNames[K_COUNT] = {
     "sel_init", "hist_round0", "hist_round1", "hist_round2", "select", "tie_count",
     "tie_final", "zero_flags", "mask_scan", "scan", "propagate", "plan", "gather",
     "gather_vec", "copy", "spec_init", "spec_sample", "spec_predict", "spec_pass",
-    "spec_finish", "spec_fixup"};
+    "spec_hist_locate", "spec_filter_rank", "spec_fixup"};
 
 ProfileScope::ProfileScope(shifter_ctx* c, int id) : ctx(c), idx(-1) {
     if (!c->profiling) return;

@@ -84,8 +84,6 @@ struct SpecState {
     uint32_t status;     // bit 0: not decided, use the multi-pass select; bit 1: NaN seen
     uint32_t bin, bin_cnt;
     uint32_t list_cnt;
-    uint32_t ticket_hist, ticket_filter;   // arrival counters of the finishing kernels
-    uint32_t pad;
 };
 
 struct PruneCounts {
@@ -115,7 +113,7 @@ struct PlanHeader {
 enum KernelId {
     K_SEL_INIT = 0, K_HIST0, K_HIST1, K_HIST2, K_SELECT, K_TIE_COUNT, K_TIE_FINAL,
     K_ZERO_FLAGS, K_MASK_SCAN, K_SCAN, K_PROPAGATE, K_PLAN, K_GATHER, K_GATHER_VEC,
-    K_COPY, K_SPEC_INIT, K_SPEC_SAMPLE, K_SPEC_PREDICT, K_SPEC_PASS, K_SPEC_FINISH, K_SPEC_FIXUP,
+    K_COPY, K_SPEC_INIT, K_SPEC_SAMPLE, K_SPEC_PREDICT, K_SPEC_PASS, K_SPEC_FINISH, K_SPEC_FINISH2, K_SPEC_FIXUP,
     K_COUNT
 };
 extern const char* const kKernelNames[K_COUNT];

@@ -20,7 +20,7 @@ __global__ __launch_bounds__(BLOCK) void zero_flags_kernel(uint8_t* a, uint64_t 
     if (i < nb) b[i] = 0;
 }
 
-template <bool DO_MASK, bool DO_SCAN>
+template <bool DO_MASK, bool DO_SCAN, bool NT>
 __global__ __launch_bounds__(BLOCK) void mask_scan_kernel(
     const DevTensor* __restrict__ tens, const uint32_t* __restrict__ tile_prefix,
     uint32_t n_t, const float* w, const shifter_threshold* __restrict__ thr, float* w_out,
@@ -71,7 +71,7 @@ __global__ __launch_bounds__(BLOCK) void mask_scan_kernel(
         const uint4* s4 = reinterpret_cast<const uint4*>(src);
         uint4 v[U];
 #pragma unroll
-        for (uint32_t u = 0; u < U; ++u) v[u] = s4[threadIdx.x + BLOCK * u];
+        for (uint32_t u = 0; u < U; ++u) v[u] = load_u4<NT>(s4 + threadIdx.x + BLOCK * u);
 #pragma unroll
         for (uint32_t u = 0; u < U; ++u) {
             const uint32_t j = (threadIdx.x + BLOCK * u) * 4;
@@ -82,10 +82,10 @@ __global__ __launch_bounds__(BLOCK) void mask_scan_kernel(
             o.z = one(j + 2, v[u].z, k2);
             o.w = one(j + 3, v[u].w, k3);
             if (DO_MASK) {
-                reinterpret_cast<uint4*>(dst)[threadIdx.x + BLOCK * u] = o;
+                store_u4<NT>(reinterpret_cast<uint4*>(dst) + threadIdx.x + BLOCK * u, o);
                 if (mdst)
-                    reinterpret_cast<uint32_t*>(mdst)[threadIdx.x + BLOCK * u] =
-                        k0 | (k1 << 8) | (k2 << 16) | (k3 << 24);
+                    store_u1<NT>(reinterpret_cast<uint32_t*>(mdst) + threadIdx.x + BLOCK * u,
+                                 k0 | (k1 << 8) | (k2 << 16) | (k3 << 24));
             }
         }
     } else {
@@ -128,20 +128,27 @@ static void zero_flags(shifter_ctx* ctx, const shifter_model* m, uint8_t* d_out_
         d_out_alive, na, d_in_alive, nb);
 }
 
+// Arenas beyond this size cannot stay in the 256 MB last-level cache between passes:
+// stream them with the non-temporal hint.
+static bool streaming(const shifter_model* m) { return m->info.w_extent * 4 > (192ull << 20); }
+
 void launch_mask_scan(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
                       const shifter_threshold* d_thr, float* d_w_out, uint8_t* d_mask,
                       uint8_t* d_out_alive, uint8_t* d_in_alive) {
     const auto& b = m->b;
     const uint32_t n_t = (uint32_t)m->t.size();
+    const bool nt = streaming(m);
     if (d_out_alive) {
         zero_flags(ctx, m, d_out_alive, d_in_alive);
         ProfileScope p(ctx, K_MASK_SCAN);
-        mask_scan_kernel<true, true><<<m->n_tiles, BLOCK, 0, ctx->stream>>>(
-            b.tens, b.tile_prefix, n_t, d_w, d_thr, d_w_out, d_mask, d_out_alive, d_in_alive);
+        auto k = nt ? mask_scan_kernel<true, true, true> : mask_scan_kernel<true, true, false>;
+        k<<<m->n_tiles, BLOCK, 0, ctx->stream>>>(b.tens, b.tile_prefix, n_t, d_w, d_thr, d_w_out,
+                                                 d_mask, d_out_alive, d_in_alive);
     } else {
         ProfileScope p(ctx, K_MASK_SCAN);
-        mask_scan_kernel<true, false><<<m->n_tiles, BLOCK, 0, ctx->stream>>>(
-            b.tens, b.tile_prefix, n_t, d_w, d_thr, d_w_out, d_mask, nullptr, nullptr);
+        auto k = nt ? mask_scan_kernel<true, false, true> : mask_scan_kernel<true, false, false>;
+        k<<<m->n_tiles, BLOCK, 0, ctx->stream>>>(b.tens, b.tile_prefix, n_t, d_w, d_thr, d_w_out,
+                                                 d_mask, nullptr, nullptr);
     }
 }
 
@@ -150,9 +157,9 @@ void launch_scan(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
     const auto& b = m->b;
     zero_flags(ctx, m, d_out_alive, d_in_alive);
     ProfileScope p(ctx, K_SCAN);
-    mask_scan_kernel<false, true><<<m->n_tiles, BLOCK, 0, ctx->stream>>>(
-        b.tens, b.tile_prefix, (uint32_t)m->t.size(), d_w, nullptr, nullptr, nullptr,
-        d_out_alive, d_in_alive);
+    auto k = streaming(m) ? mask_scan_kernel<false, true, true> : mask_scan_kernel<false, true, false>;
+    k<<<m->n_tiles, BLOCK, 0, ctx->stream>>>(b.tens, b.tile_prefix, (uint32_t)m->t.size(), d_w,
+                                             nullptr, nullptr, nullptr, d_out_alive, d_in_alive);
 }
 
 }  // namespace shifter

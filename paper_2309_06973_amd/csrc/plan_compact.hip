@@ -133,45 +133,67 @@ __global__ __launch_bounds__(BLOCK) void gather_kernel(
         // arena position of this tile's first quad, and of the tensor's ends
         const uint64_t a0 = (P.out_off & ~3ull) + (uint64_t)(tile - otp[t]) * TILE;
         const uint64_t begin = P.out_off, end = P.out_off + P.numel2;
+        constexpr uint32_t U = TILE / BLOCK / 4;
+        // phase 1: where each of this thread's quads starts in the rebuilt tensor
+        uint64_t pq[U], first[U];
+        uint32_t nv[U], o2[U], c2[U], k[U], ko[U], ki[U];
 #pragma unroll
-        for (uint32_t u = 0; u < TILE / BLOCK / 4; ++u) {
-            const uint64_t pq = a0 + 4ull * (threadIdx.x + BLOCK * u);
-            if (pq >= end || pq + 4 <= begin) continue;
-            const uint64_t first = pq < begin ? begin : pq;
-            const uint32_t idx = (uint32_t)(first - begin);
-            uint32_t o2 = idx / row2;
-            const uint32_t rem = idx - o2 * row2;
-            uint32_t c2 = rem / T.kk;
-            uint32_t k = rem - c2 * T.kk;
-            uint64_t so = (uint64_t)keep_o[o2] * T.cin;
-            uint64_t sc = (so + keep_i[c2]) * T.kk;
-            float val[4];
-            const uint32_t n_valid = (uint32_t)((pq + 4 < end ? pq + 4 : end) - first);
+        for (uint32_t u = 0; u < U; ++u) {
+            pq[u] = a0 + 4ull * (threadIdx.x + BLOCK * u);
+            nv[u] = 0;
+            if (pq[u] >= end || pq[u] + 4 <= begin) continue;
+            first[u] = pq[u] < begin ? begin : pq[u];
+            nv[u] = (uint32_t)((pq[u] + 4 < end ? pq[u] + 4 : end) - first[u]);
+            const uint32_t idx = (uint32_t)(first[u] - begin);
+            o2[u] = idx / row2;
+            const uint32_t rem = idx - o2[u] * row2;
+            c2[u] = rem / T.kk;
+            k[u] = rem - c2[u] * T.kk;
+        }
+        // phase 2: survivor indices of the quads' first elements (independent loads)
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u) {
+            if (nv[u]) { ko[u] = keep_o[o2[u]]; ki[u] = keep_i[c2[u]]; }
+        }
+        // phase 3: the source elements; a quad crosses into the next channel or filter at
+        // most a few times, each crossing costs one more index load
+        float val[U][4];
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u) {
+            if (!nv[u]) continue;
+            uint32_t oo = o2[u], cc = c2[u], kk2 = k[u];
+            uint64_t so = (uint64_t)ko[u] * T.cin;
+            uint64_t sc = (so + ki[u]) * T.kk;
 #pragma unroll
             for (uint32_t c = 0; c < 4; ++c) {
-                if (c < n_valid) {
-                    val[c] = src[sc + k];
-                    if (++k == T.kk) {
-                        k = 0;
-                        if (++c2 == P.c2) {
-                            c2 = 0;
-                            ++o2;
-                            if (o2 < P.o2) so = (uint64_t)keep_o[o2] * T.cin;
+                if (c < nv[u]) {
+                    val[u][c] = src[sc + kk2];
+                    if (++kk2 == T.kk) {
+                        kk2 = 0;
+                        if (++cc == P.c2) {
+                            cc = 0;
+                            ++oo;
+                            if (oo < P.o2) so = (uint64_t)keep_o[oo] * T.cin;
                         }
-                        if (o2 < P.o2) sc = (so + keep_i[c2]) * T.kk;
+                        if (oo < P.o2) sc = (so + keep_i[cc]) * T.kk;
                     }
                 }
             }
-            if (first == pq && n_valid == 4) {
-                *reinterpret_cast<float4*>(w_out + pq) = make_float4(val[0], val[1], val[2], val[3]);
-            } else {
+        }
 #pragma unroll
-                for (uint32_t c = 0; c < 4; ++c)
-                    if (c < n_valid) w_out[first + c] = val[c];
+        for (uint32_t u = 0; u < U; ++u) {
+            if (!nv[u]) continue;
+            if (first[u] == pq[u] && nv[u] == 4) {
+                *reinterpret_cast<float4*>(w_out + pq[u]) =
+                    make_float4(val[u][0], val[u][1], val[u][2], val[u][3]);
+            } else {
+                for (uint32_t c = 0; c < nv[u]; ++c) w_out[first[u] + c] = val[u][c];
             }
         }
     }
-    for (uint32_t vi = blockIdx.x; vi < n_v; vi += gridDim.x) {
+    // the per-channel vectors, starting from the last blocks (those with no tile when
+    // much was removed)
+    for (uint32_t vi = gridDim.x - 1 - blockIdx.x; vi < n_v; vi += gridDim.x) {
         const DevVec V = vecs[vi];
         const PlanVec P = pv[vi];
         const uint32_t* kp = keep + groups[V.group].off;

@@ -53,8 +53,6 @@ __global__ __launch_bounds__(BLOCK) void spec_init_kernel(SpecState* ss, uint32_
         ss->m_valid = m_valid;
         ss->status = 0;
         ss->list_cnt = 0;
-        ss->ticket_hist = 0;
-        ss->ticket_filter = 0;
         ss->lo = 0;
         ss->hi = 0x7fffffffu;
         ss->mid = 0;
@@ -63,11 +61,16 @@ __global__ __launch_bounds__(BLOCK) void spec_init_kernel(SpecState* ss, uint32_
 }
 
 // One wavefront per sampled tile: lanes 0..31 read line l0, lanes 32..63 line l0 + 64
-// of the tile's 128 lines of 32 floats; l0 rotates with the tile index.
+// of the tile's 128 lines of 32 floats; l0 rotates with the tile index.  The samples go
+// to a per-block LDS histogram first: a global atomic costs about 11 ns per lane on one
+// address, and the bins around the mode of the weight distribution are hot.
 __global__ __launch_bounds__(BLOCK) void spec_sample_kernel(
     const DevTensor* __restrict__ tens, const uint32_t* __restrict__ tile_prefix,
     uint32_t n_t, uint32_t n_tiles, uint32_t tile_stride, const float* __restrict__ w,
     uint32_t* shist) {
+    __shared__ uint32_t h[SBINS];
+    for (uint32_t i = threadIdx.x; i < SBINS; i += BLOCK) h[i] = 0;
+    __syncthreads();
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = blockIdx.x * (BLOCK / 64) + (threadIdx.x >> 6);
     const uint32_t n_waves = gridDim.x * (BLOCK / 64);
@@ -79,10 +82,12 @@ __global__ __launch_bounds__(BLOCK) void spec_sample_kernel(
         const uint32_t n = min(TILE, tens[t].numel - e0);
         const uint32_t l0 = (tile * 37u) & 63u;
         const uint32_t j = (l0 + (lane >> 5) * 64u) * 32u + (lane & 31u);
-        if (j < n) {
-            const uint32_t key = key_of(w[tens[t].offset + e0 + j]);
-            atomicAdd(&shist[key >> SAMPLE_SHIFT], 1u);
-        }
+        if (j < n) atomicAdd(&h[key_of(w[tens[t].offset + e0 + j]) >> SAMPLE_SHIFT], 1u);
+    }
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < SBINS; i += BLOCK) {
+        const uint32_t c = h[i];
+        if (c) atomicAdd(&shist[i], c);
     }
 }
 
@@ -157,7 +162,7 @@ __global__ __launch_bounds__(BLOCK) void spec_predict_kernel(SpecState* ss,
 // on) and the alive flags of the kept weights outside the candidate interval;
 // spec_fixup_kernel settles the candidates.  A candidate pair holds the weight's full bit
 // pattern (sign included, so a wrongly removed weight can be restored) and its index.
-template <bool FUSED>
+template <bool FUSED, bool NT>
 __global__ __launch_bounds__(BLOCK) void spec_pass_kernel(
     const DevTensor* __restrict__ tens, const uint32_t* __restrict__ tile_prefix,
     uint32_t n_t, const float* __restrict__ w, SpecState* ss, uint32_t* cnt,
@@ -217,7 +222,7 @@ __global__ __launch_bounds__(BLOCK) void spec_pass_kernel(
         const uint4* s4 = reinterpret_cast<const uint4*>(src);
         uint4 v[U];
 #pragma unroll
-        for (uint32_t u = 0; u < U; ++u) v[u] = s4[threadIdx.x + BLOCK * u];
+        for (uint32_t u = 0; u < U; ++u) v[u] = load_u4<NT>(s4 + threadIdx.x + BLOCK * u);
         uint32_t cmask = 0;
 #pragma unroll
         for (uint32_t u = 0; u < U; ++u) {
@@ -231,10 +236,10 @@ __global__ __launch_bounds__(BLOCK) void spec_pass_kernel(
             o.w = one(j + 3, v[u].w, k3, q3);
             cmask |= ((q0 ? 1u : 0u) | (q1 ? 2u : 0u) | (q2 ? 4u : 0u) | (q3 ? 8u : 0u)) << (4 * u);
             if (FUSED) {
-                reinterpret_cast<uint4*>(dst)[threadIdx.x + BLOCK * u] = o;
+                store_u4<NT>(reinterpret_cast<uint4*>(dst) + threadIdx.x + BLOCK * u, o);
                 if (mdst)
-                    reinterpret_cast<uint32_t*>(mdst)[threadIdx.x + BLOCK * u] =
-                        k0 | (k1 << 8) | (k2 << 16) | (k3 << 24);
+                    store_u1<NT>(reinterpret_cast<uint32_t*>(mdst) + threadIdx.x + BLOCK * u,
+                                 k0 | (k1 << 8) | (k2 << 16) | (k3 << 24));
             }
         }
         // append the block's candidates with one global atomic: scan the per-thread
@@ -340,23 +345,14 @@ __device__ __forceinline__ void for_each_candidate(const uint32_t* cnt, const ui
     }
 }
 
-// True for the block that arrives last at a kernel-wide rendezvous; every thread's
-// earlier global writes are then visible to that block.
-__device__ __forceinline__ bool last_block(uint32_t* ticket) {
-    __shared__ uint32_t s_last;
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) s_last = atomicAdd(ticket, 1u) == gridDim.x - 1 ? 1u : 0u;
-    __syncthreads();
-    if (!s_last) return false;
-    __threadfence();
-    return true;
-}
-
 // Totals of the split counters, the check that makes the result exact, then the round-1
-// bin holding the P-th pair.  Run by one block.
-__device__ void spec_locate(SpecState* ss, const uint32_t* cnt, const uint32_t* partial,
-                            uint32_t cap_sb, uint64_t* smem) {
+// bin holding the P-th pair.  Every block of the filter kernel runs this on the same
+// inputs (64 KB of partial histograms from L2) and gets the same answer, which is cheaper
+// than a kernel of its own or a fenced rendezvous; `publish` is set for one block, which
+// records the outcome.  Returns false when the single pass cannot decide.
+__device__ bool spec_locate(SpecState* ss, const uint32_t* __restrict__ cnt,
+                            const uint32_t* __restrict__ partial, uint32_t cap_sb,
+                            uint64_t* smem, bool publish, uint32_t* bin_out) {
     __shared__ uint32_t s_over;
     const uint64_t p = ss->p;
     if (threadIdx.x == 0) s_over = 0;
@@ -371,36 +367,62 @@ __device__ void spec_locate(SpecState* ss, const uint32_t* cnt, const uint32_t* 
         if (c > cap_sb) s_over = 1;
     }
     __syncthreads();
-    if (threadIdx.x == 0) { ss->n_below = below; ss->n_inside = inside; }
-    if (p == 0) return;
+    if (publish && threadIdx.x == 0) { ss->n_below = below; ss->n_inside = inside; }
     if (s_over || !(below < p && p <= below + inside)) {
-        if (threadIdx.x == 0) atomicOr(&ss->status, 1u);
-        return;
+        if (publish && threadIdx.x == 0) atomicOr(&ss->status, 1u);
+        return false;
     }
     const uint64_t r = p - below;
     static_assert(FBINS1 == BLOCK, "one round-1 bin per thread");
-    uint32_t c = 0;
-#pragma unroll 8
-    for (uint32_t q = 0; q < FIN_BLOCKS; ++q) c += partial[q * FBINS1 + threadIdx.x];
-    const uint64_t base = block_excl_scan_u64(c, smem, &tot);
-    if (base < r && r <= base + c) {
-        ss->bin = threadIdx.x;
-        ss->bin_cnt = c;
-        ss->r2 = r - base;
-        ss->less = below + base;
-        if (c > SPEC_LIST_CAP) atomicOr(&ss->status, 1u);
+    // sum the FIN_BLOCKS partial histograms: thread t reads the uint4s t, t + 256, ...;
+    // each covers the same four bins (4t mod 256 ...), so it keeps four sums and four
+    // threads then meet in LDS.  All loads are independent of each other.
+    __shared__ uint32_t s_bins[FBINS1];
+    s_bins[threadIdx.x] = 0;
+    __syncthreads();
+    {
+        const uint4* p4 = reinterpret_cast<const uint4*>(partial);
+        uint4 acc = make_uint4(0, 0, 0, 0);
+        constexpr uint32_t N4 = FIN_BLOCKS * FBINS1 / 4 / BLOCK;
+#pragma unroll 16
+        for (uint32_t i = 0; i < N4; ++i) {
+            const uint4 x = p4[threadIdx.x + BLOCK * i];
+            acc.x += x.x; acc.y += x.y; acc.z += x.z; acc.w += x.w;
+        }
+        const uint32_t b4 = (4u * threadIdx.x) & (FBINS1 - 1);
+        atomicAdd(&s_bins[b4], acc.x);
+        atomicAdd(&s_bins[b4 + 1], acc.y);
+        atomicAdd(&s_bins[b4 + 2], acc.z);
+        atomicAdd(&s_bins[b4 + 3], acc.w);
     }
+    __syncthreads();
+    const uint32_t c = s_bins[threadIdx.x];
+    const uint64_t base = block_excl_scan_u64(c, smem, &tot);
+    __shared__ uint32_t s_bin, s_ok;
+    if (base < r && r <= base + c) {
+        s_bin = threadIdx.x;
+        s_ok = c <= SPEC_LIST_CAP ? 1u : 0u;
+        if (publish) {
+            ss->bin = threadIdx.x;
+            ss->bin_cnt = c;
+            ss->r2 = r - base;
+            ss->less = below + base;
+            if (c > SPEC_LIST_CAP) atomicOr(&ss->status, 1u);
+        }
+    }
+    __syncthreads();
+    *bin_out = s_bin;
+    return s_ok != 0;
 }
 
-// Round 1: per-block LDS histogram of (key - lo) >> sh (256 bins) over the candidates; the partial
-// histograms go to global memory side by side (no atomics); the block that finishes last
-// sums them and locates the bin.
-__global__ __launch_bounds__(BLOCK) void spec_hist_kernel(SpecState* ss,
-                                                          const uint32_t* cnt,
+// Round 1: per-block LDS histogram of (key - lo) >> sh (256 bins) over the candidates; the
+// partial histograms go to global memory side by side (no atomics).
+__global__ __launch_bounds__(BLOCK) void spec_hist_kernel(const SpecState* __restrict__ ss,
+                                                          const uint32_t* __restrict__ cnt,
                                                           const uint2* __restrict__ cand,
-                                                          uint32_t cap_sb, uint32_t* partial) {
+                                                          uint32_t cap_sb,
+                                                          uint32_t* __restrict__ partial) {
     __shared__ uint32_t h[FBINS1];
-    __shared__ uint64_t smem[BLOCK / 64 + 1];
     h[threadIdx.x] = 0;
     __syncthreads();
     const uint32_t lo = ss->lo, sh = ss->sh;
@@ -409,19 +431,29 @@ __global__ __launch_bounds__(BLOCK) void spec_hist_kernel(SpecState* ss,
     });
     __syncthreads();
     partial[blockIdx.x * FBINS1 + threadIdx.x] = h[threadIdx.x];
-    if (!last_block(&ss->ticket_hist)) return;
-    spec_locate(ss, cnt, partial, cap_sb, smem);
 }
 
-// Round-2 histogram over the list, then an exact rank (by counting) among the pairs of
-// the selected round-2 bin, then the record.  Run by one block.
-__device__ void spec_rank(SpecState* ss, const uint2* list, shifter_threshold* thr,
-                          uint32_t* h, uint64_t* comp, uint64_t* smem) {
+// One block: round-2 histogram over the list, then an exact rank (by counting) among the
+// pairs of the selected round-2 bin, then the record.
+__global__ __launch_bounds__(BLOCK) void spec_rank_kernel(SpecState* ss,
+                                                          const uint2* __restrict__ list,
+                                                          shifter_threshold* thr) {
+    __shared__ uint32_t h[FBINS];
+    __shared__ uint64_t comp[SPEC_SMALL_CAP];
+    __shared__ uint64_t smem[BLOCK / 64 + 1];
     __shared__ uint64_t s_sel, s_less2, s_r3;
     __shared__ uint32_t s_lt, s_eq, s_bin2, s_cnt2, s_nb;
     shifter_threshold out;
     out.reserved = 0;
     out.n_prune = ss->p;
+    if (ss->p == 0) {
+        if (threadIdx.x == 0) {
+            out.cut = 0; out.t_key = 0; out.g_cut = ~0ull; out.n_less = 0; out.n_equal = 0;
+            *thr = out;
+        }
+        return;
+    }
+    if (ss->status & 1u) return;
     const uint32_t n = min(ss->list_cnt, SPEC_LIST_CAP);
     if (n != ss->bin_cnt) {   // cannot happen unless the buffers were disturbed
         if (threadIdx.x == 0) atomicOr(&ss->status, 1u);
@@ -500,51 +532,39 @@ __device__ void spec_rank(SpecState* ss, const uint2* list, shifter_threshold* t
     }
 }
 
-// Candidates of the selected round-1 bin -> list (one atomic per wavefront that has any);
-// the block that finishes last ranks the list and writes the record.
-__global__ __launch_bounds__(BLOCK) void spec_filter_kernel(SpecState* ss, const uint32_t* cnt,
+// Candidates of the selected round-1 bin -> list.  Each block stages its hits in LDS and
+// reserves its range of the list with one global atomic.
+__global__ __launch_bounds__(BLOCK) void spec_filter_kernel(SpecState* ss,
+                                                            const uint32_t* __restrict__ cnt,
+                                                            const uint32_t* __restrict__ partial,
                                                             const uint2* __restrict__ cand,
-                                                            uint32_t cap_sb, uint2* list,
-                                                            shifter_threshold* thr) {
-    __shared__ uint32_t h[FBINS];
-    __shared__ uint64_t comp[SPEC_SMALL_CAP];
+                                                            uint32_t cap_sb, uint2* list) {
+    constexpr uint32_t STAGE = 2048;
+    __shared__ uint2 stage[STAGE];
     __shared__ uint64_t smem[BLOCK / 64 + 1];
-    if (ss->p == 0) {
-        if (blockIdx.x == 0 && threadIdx.x == 0) {
-            shifter_threshold out;
-            out.cut = 0; out.t_key = 0; out.reserved = 0; out.g_cut = ~0ull; out.n_prune = 0;
-            out.n_less = 0; out.n_equal = 0;
-            *thr = out;
+    __shared__ uint32_t s_n, s_base;
+    if (ss->p == 0) return;
+    uint32_t bin;
+    if (threadIdx.x == 0) s_n = 0;
+    if (!spec_locate(ss, cnt, partial, cap_sb, smem, blockIdx.x == 0, &bin)) return;
+    const uint32_t lo = ss->lo, sh = ss->sh;
+    for_each_candidate(cnt, cand, cap_sb, [&](uint2 c, bool valid) {
+        if (valid && (((c.x & 0x7fffffffu) - lo) >> sh) == bin) {
+            const uint32_t pos = atomicAdd(&s_n, 1u);
+            if (pos < STAGE) stage[pos] = c;
         }
+    });
+    __syncthreads();
+    const uint32_t n = s_n;
+    if (n > STAGE) {   // far more ties than the stage holds: leave it to the radix select
+        if (threadIdx.x == 0) atomicOr(&ss->status, 1u);
         return;
     }
-    if (ss->status & 1u) return;
-    const uint32_t lo = ss->lo, sh = ss->sh, bin = ss->bin;
-    const uint32_t lane = threadIdx.x & 63u, wid = threadIdx.x >> 6;
-    __shared__ uint32_t s_wtot[BLOCK / 64], s_base;
-    for_each_candidate(cnt, cand, cap_sb, [&](uint2 c, bool valid) {
-        // one global atomic per block and chunk that has a hit
-        const bool hit = valid && (((c.x & 0x7fffffffu) - lo) >> sh) == bin;
-        const unsigned long long bal = __ballot(hit);
-        if (lane == 0) s_wtot[wid] = (uint32_t)__popcll(bal);
-        __syncthreads();
-        uint32_t woff = 0, btot = 0;
-#pragma unroll
-        for (uint32_t i = 0; i < BLOCK / 64; ++i) {
-            const uint32_t x = s_wtot[i];
-            if (i < wid) woff += x;
-            btot += x;
-        }
-        if (btot) {   // uniform over the block
-            if (threadIdx.x == 0) s_base = atomicAdd(&ss->list_cnt, btot);
-            __syncthreads();
-            const uint32_t pos = s_base + woff + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
-            if (hit && pos < SPEC_LIST_CAP) list[pos] = c;
-        }
-        __syncthreads();
-    });
-    if (!last_block(&ss->ticket_filter)) return;
-    spec_rank(ss, list, thr, h, comp, smem);
+    if (n == 0) return;
+    if (threadIdx.x == 0) s_base = atomicAdd(&ss->list_cnt, n);
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < n; i += BLOCK)
+        if (s_base + i < SPEC_LIST_CAP) list[s_base + i] = stage[i];
 }
 
 // Fused form only: settle the candidates.  The pass wrote those below mid as removed and
@@ -612,7 +632,7 @@ void launch_spec_select(shifter_ctx* ctx, const shifter_model* m, const float* d
     {
         ProfileScope ps(ctx, K_SPEC_SAMPLE);
         const uint32_t sampled = (m->n_tiles + tile_stride - 1) / tile_stride;
-        const uint32_t grid = min(ctx->hist_grid, (sampled + BLOCK / 64 - 1) / (BLOCK / 64));
+        const uint32_t grid = min(256u, (sampled + BLOCK / 64 - 1) / (BLOCK / 64));
         spec_sample_kernel<<<grid, BLOCK, 0, s>>>(b.tens, b.tile_prefix, n_t, m->n_tiles,
                                                   tile_stride, d_w, b.shist);
     }
@@ -623,21 +643,22 @@ void launch_spec_select(shifter_ctx* ctx, const shifter_model* m, const float* d
     }
     {
         ProfileScope ps(ctx, K_SPEC_PASS);
-        if (fused)
-            spec_pass_kernel<true><<<m->n_tiles, BLOCK, 0, s>>>(
-                b.tens, b.tile_prefix, n_t, d_w, b.spec, b.spec_cnt, b.cand, b.cand_cap_sb,
-                d_w_out, d_mask, d_out_alive, d_in_alive);
-        else
-            spec_pass_kernel<false><<<m->n_tiles, BLOCK, 0, s>>>(
-                b.tens, b.tile_prefix, n_t, d_w, b.spec, b.spec_cnt, b.cand, b.cand_cap_sb,
-                nullptr, nullptr, nullptr, nullptr);
+        const bool nt = m->info.w_extent * 4 > (192ull << 20);   // beyond the last-level cache
+        auto k = fused ? (nt ? spec_pass_kernel<true, true> : spec_pass_kernel<true, false>)
+                       : (nt ? spec_pass_kernel<false, true> : spec_pass_kernel<false, false>);
+        k<<<m->n_tiles, BLOCK, 0, s>>>(b.tens, b.tile_prefix, n_t, d_w, b.spec, b.spec_cnt, b.cand,
+                                       b.cand_cap_sb, d_w_out, d_mask, d_out_alive, d_in_alive);
     }
     {
         ProfileScope ps(ctx, K_SPEC_FINISH);
         spec_hist_kernel<<<FIN_BLOCKS, BLOCK, 0, s>>>(b.spec, b.spec_cnt, b.cand, b.cand_cap_sb,
                                                       b.partial);
-        spec_filter_kernel<<<FIN_BLOCKS, BLOCK, 0, s>>>(b.spec, b.spec_cnt, b.cand,
-                                                        b.cand_cap_sb, b.list, d_thr);
+    }
+    {
+        ProfileScope ps(ctx, K_SPEC_FINISH2);
+        spec_filter_kernel<<<FIN_BLOCKS, BLOCK, 0, s>>>(b.spec, b.spec_cnt, b.partial, b.cand,
+                                                        b.cand_cap_sb, b.list);
+        spec_rank_kernel<<<1, BLOCK, 0, s>>>(b.spec, b.list, d_thr);
     }
     if (fused) {
         ProfileScope ps(ctx, K_SPEC_FIXUP);
