@@ -268,6 +268,47 @@ int shifter_compact(shifter_ctx* ctx, const shifter_model* model, const float* d
                     shifter_vec_desc* h_out_vecs, uint64_t* h_elems_w,
                     uint64_t* h_elems_v);
 
+/* --- a whole portfolio per call ------------------------------------------------------ */
+
+/* Steps 2-5 for the K variants of a portfolio in one launch per step (Sec. III-C: the
+ * variants of a portfolio mask the same dense weights at growing sparsity; Sec. III-D
+ * Module 4: all channels pruned "in a single batch operation").  Results per variant are
+ * identical to the single-variant calls; variant k's buffers sit k strides after
+ * variant 0's.  The dense arena is read once for all K sparse arenas.
+ *
+ * shifter_apply_mask_batch
+ *   d_thr        device, K records (as written by shifter_global_threshold)
+ *   d_w_out      device, K arenas, w_stride floats apart (w_stride >= w_extent, multiple
+ *                of 4 for full speed); must not overlap d_w
+ *   d_mask       device, K masks, mask_stride bytes apart (>= N), or NULL
+ *   d_out_alive  device, K * sum_out_ch bytes, required
+ *   d_in_alive   device, K * sum_in_ch bytes, or NULL
+ * shifter_propagate_groups_batch
+ *   d_out_alive  as above; d_group_alive / d_index_map / d_keep: K * sum_group_width
+ *   entries; d_new_width: K * n_groups; h_new_width: host, K * n_groups, or NULL (waits)
+ * shifter_compact_batch
+ *   d_w_sparse   the K sparse arenas (w_stride apart); d_keep, d_new_width as above
+ *   d_w_out      device, K output arenas cap_w floats apart (cap_w a multiple of 4);
+ *   d_vecs_out   K vector arenas cap_v floats apart
+ *   h_out_tensors K * n_tensors, h_out_vecs K * n_vecs, h_elems_w / h_elems_v K entries,
+ *   each or NULL; any non-NULL makes the call wait.  SHIFTER_ERR_CAPACITY if any variant
+ *   does not fit (that variant is not gathered), SHIFTER_WARN_COLLAPSE if any collapsed. */
+int shifter_apply_mask_batch(shifter_ctx* ctx, const shifter_model* model, const float* d_w,
+                             const shifter_threshold* d_thr, uint32_t K, float* d_w_out,
+                             uint64_t w_stride, uint8_t* d_mask, uint64_t mask_stride,
+                             uint8_t* d_out_alive, uint8_t* d_in_alive);
+int shifter_propagate_groups_batch(shifter_ctx* ctx, const shifter_model* model,
+                                   const uint8_t* d_out_alive, uint32_t K, uint32_t flags,
+                                   uint8_t* d_group_alive, int32_t* d_index_map,
+                                   uint32_t* d_keep, uint32_t* d_new_width,
+                                   uint32_t* h_new_width);
+int shifter_compact_batch(shifter_ctx* ctx, const shifter_model* model, const float* d_w_sparse,
+                          uint64_t w_stride, const float* d_vecs, const uint32_t* d_keep,
+                          const uint32_t* d_new_width, uint32_t K, float* d_w_out,
+                          uint64_t cap_w, float* d_vecs_out, uint64_t cap_v,
+                          shifter_tensor_desc* h_out_tensors, shifter_vec_desc* h_out_vecs,
+                          uint64_t* h_elems_w, uint64_t* h_elems_v);
+
 /* --- measurement ------------------------------------------------------------------- */
 
 /* Per-kernel timing with HIP events on the context's stream.  While enabled every

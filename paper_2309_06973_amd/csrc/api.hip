@@ -13,7 +13,7 @@ namespace shifter {
 const char* const kKernelNames[K_COUNT] = {
     "sel_init", "hist_round0", "hist_round1", "hist_round2", "select", "tie_count",
     "tie_final", "zero_flags", "mask_scan", "scan", "propagate", "plan", "gather",
-    "gather_vec", "copy", "spec_init", "spec_sample", "spec_predict", "spec_pass",
+    "gather_vec", "copy", "mask_scan_batch", "expand_levels", "spec_init", "spec_sample", "spec_predict", "spec_pass",
     "spec_hist_locate", "spec_filter_rank", "spec_fixup"};
 
 ProfileScope::ProfileScope(shifter_ctx* c, int id) : ctx(c), idx(-1) {
@@ -81,7 +81,7 @@ static void unbind(shifter_model* m) {
     if (!b.ctx) return;
     (void)hipSetDevice(b.device);
     void* ptrs[] = {b.tens, b.groups, b.vecs, b.producers, b.tile_prefix, b.sel, b.ghist,
-                    b.tile_cnt, b.plan_t, b.plan_v, b.plan_h, b.out_tile_prefix, b.spec, b.shist,
+                    b.tile_cnt, b.plan_t, b.plan_v, b.plan_h, b.out_tile_prefix, b.levels, b.spec, b.shist,
                     b.spec_cnt, b.partial, b.cand, b.list, b.ranked_ids};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
@@ -301,10 +301,12 @@ static int bind(shifter_ctx* ctx, const shifter_model* cm) {
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.ghist), sizeof(uint32_t) * MAXK * HIST_BINS));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.tile_cnt),
                            sizeof(uint32_t) * (size_t)MAXK * std::max<uint32_t>(m->n_tiles, 1)));
-    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.plan_t), sizeof(PlanTensor) * n_t));
-    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.plan_v), sizeof(PlanVec) * std::max<size_t>(n_v, 1)));
-    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.plan_h), sizeof(PlanHeader)));
-    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.out_tile_prefix), sizeof(uint32_t) * (n_t + 1)));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.plan_t), sizeof(PlanTensor) * n_t * MAXK));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.plan_v), sizeof(PlanVec) * std::max<size_t>(n_v, 1) * MAXK));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.plan_h), sizeof(PlanHeader) * MAXK));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.out_tile_prefix), sizeof(uint32_t) * (n_t + 1) * MAXK));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.levels),
+                           sizeof(uint32_t) * (m->info.sum_out_ch + m->info.sum_in_ch)));
     if ((rc = upload(ctx, &b.ranked_ids, m->ranked_ids.data(), m->ranked_ids.size()))) return rc;
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.spec), sizeof(SpecState)));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.shist), sizeof(uint32_t) * 65536));
@@ -314,9 +316,10 @@ static int bind(shifter_ctx* ctx, const shifter_model* cm) {
     b.cand_cap_sb = (uint32_t)std::max<uint64_t>(m->info.n_prunable / 16 / SPEC_SUB, 2 * TILE);
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.cand), sizeof(uint2) * (size_t)b.cand_cap_sb * SPEC_SUB));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.list), sizeof(uint2) * SPEC_LIST_CAP));
-    b.host_stage_bytes = sizeof(SelState) + sizeof(shifter_threshold) * MAXK + sizeof(PlanHeader) +
-                         sizeof(PlanTensor) * n_t + sizeof(PlanVec) * n_v +
-                         sizeof(uint32_t) * m->g.size() + sizeof(SpecState) + 256;
+    b.host_stage_bytes = sizeof(SelState) + sizeof(shifter_threshold) * MAXK +
+                         MAXK * (sizeof(PlanHeader) + sizeof(PlanTensor) * n_t + sizeof(PlanVec) * n_v +
+                                 sizeof(uint32_t) * m->g.size()) +
+                         sizeof(SpecState) + 256;
     HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&b.host_stage), b.host_stage_bytes, hipHostMallocDefault));
     return SHIFTER_OK;
 }
@@ -502,32 +505,127 @@ extern "C" int shifter_dead_channel_scan(shifter_ctx* ctx, const shifter_model* 
     return after_launch(ctx, "dead_channel_scan");
 }
 
+extern "C" int shifter_apply_mask_batch(shifter_ctx* ctx, const shifter_model* model, const float* d_w,
+                                       const shifter_threshold* d_thr, uint32_t K, float* d_w_out,
+                                       uint64_t w_stride, uint8_t* d_mask, uint64_t mask_stride,
+                                       uint8_t* d_out_alive, uint8_t* d_in_alive) {
+    int rc = enter(ctx, model, "apply_mask_batch");
+    if (rc) return rc;
+    if (!d_w || !d_thr || !d_w_out || !d_out_alive)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "apply_mask_batch: NULL pointer argument");
+    if (K == 0 || K > MAXK)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "apply_mask_batch: K must be in [1, SHIFTER_MAX_VARIANTS]");
+    if (misaligned(d_w, 16) || misaligned(d_w_out, 16) || misaligned(d_mask, 4) || misaligned(d_thr, 8))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG,
+                    "apply_mask_batch: arenas must be 16-byte aligned, the masks 4-byte aligned");
+    if (w_stride < model->info.w_extent || (d_mask && mask_stride < model->info.n_prunable))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "apply_mask_batch: stride smaller than one variant");
+    if (d_w_out == d_w)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "apply_mask_batch: cannot work in place");
+    launch_mask_scan_batch(ctx, model, d_w, d_thr, K, d_w_out, w_stride, d_mask, mask_stride,
+                           d_out_alive, d_in_alive);
+    return after_launch(ctx, "apply_mask_batch");
+}
+
+extern "C" int shifter_propagate_groups_batch(shifter_ctx* ctx, const shifter_model* model,
+                                             const uint8_t* d_out_alive, uint32_t K, uint32_t flags,
+                                             uint8_t* d_group_alive, int32_t* d_index_map,
+                                             uint32_t* d_keep, uint32_t* d_new_width,
+                                             uint32_t* h_new_width) {
+    int rc = enter(ctx, model, "propagate_groups");
+    if (rc) return rc;
+    if (!d_out_alive || !d_group_alive || !d_index_map || !d_keep || !d_new_width)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "propagate_groups: NULL pointer argument");
+    if (K == 0 || K > MAXK)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "propagate_groups: K must be in [1, SHIFTER_MAX_VARIANTS]");
+    if (flags & ~SHIFTER_PAPER_FREEZE_RESIDUAL)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "propagate_groups: unknown flag bits");
+    launch_propagate(ctx, model, d_out_alive, flags, d_group_alive, d_index_map, d_keep, d_new_width, K);
+    if ((rc = after_launch(ctx, "propagate_groups"))) return rc;
+    if (h_new_width) {
+        const size_t n = model->g.size() * K;
+        uint32_t* st = reinterpret_cast<uint32_t*>(model->b.host_stage);
+        HIP_TRY(ctx, hipMemcpyAsync(st, d_new_width, sizeof(uint32_t) * n, hipMemcpyDeviceToHost, ctx->stream));
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+        bool collapse = false;
+        for (size_t g = 0; g < n; ++g) {
+            h_new_width[g] = st[g];
+            collapse |= st[g] == 0;
+        }
+        if (collapse) {
+            fail(ctx, SHIFTER_WARN_COLLAPSE, "propagate_groups: a group kept no channel (layer collapse)");
+            return SHIFTER_WARN_COLLAPSE;
+        }
+    }
+    return SHIFTER_OK;
+}
+
 extern "C" int shifter_propagate_groups(shifter_ctx* ctx, const shifter_model* model,
                                         const uint8_t* d_out_alive, const uint8_t* d_in_alive,
                                         uint32_t flags, uint8_t* d_group_alive,
                                         int32_t* d_index_map, uint32_t* d_keep,
                                         uint32_t* d_new_width, uint32_t* h_new_width) {
     (void)d_in_alive;
-    int rc = enter(ctx, model, "propagate_groups");
+    return shifter_propagate_groups_batch(ctx, model, d_out_alive, 1, flags, d_group_alive, d_index_map,
+                                          d_keep, d_new_width, h_new_width);
+}
+
+extern "C" int shifter_compact_batch(shifter_ctx* ctx, const shifter_model* model, const float* d_w_sparse,
+                                     uint64_t w_stride, const float* d_vecs, const uint32_t* d_keep,
+                                     const uint32_t* d_new_width, uint32_t K, float* d_w_out,
+                                     uint64_t cap_w, float* d_vecs_out, uint64_t cap_v,
+                                     shifter_tensor_desc* h_out_tensors, shifter_vec_desc* h_out_vecs,
+                                     uint64_t* h_elems_w, uint64_t* h_elems_v) {
+    int rc = enter(ctx, model, "compact");
     if (rc) return rc;
-    if (!d_out_alive || !d_group_alive || !d_index_map || !d_keep || !d_new_width)
-        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "propagate_groups: NULL pointer argument");
-    if (flags & ~SHIFTER_PAPER_FREEZE_RESIDUAL)
-        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "propagate_groups: unknown flag bits");
-    launch_propagate(ctx, model, d_out_alive, flags, d_group_alive, d_index_map, d_keep, d_new_width);
-    if ((rc = after_launch(ctx, "propagate_groups"))) return rc;
-    if (h_new_width) {
-        const size_t n_g = model->g.size();
-        uint32_t* st = reinterpret_cast<uint32_t*>(model->b.host_stage);
-        HIP_TRY(ctx, hipMemcpyAsync(st, d_new_width, sizeof(uint32_t) * n_g, hipMemcpyDeviceToHost, ctx->stream));
+    const size_t n_t = model->t.size(), n_v = model->v.size();
+    if (!d_w_sparse || !d_keep || !d_new_width || !d_w_out || (n_v && (!d_vecs || !d_vecs_out)))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "compact: NULL pointer argument");
+    if (K == 0 || K > MAXK)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "compact: K must be in [1, SHIFTER_MAX_VARIANTS]");
+    if (misaligned(d_w_out, 16) || (K > 1 && (cap_w & 3u)))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG,
+                    "compact: d_w_out must be 16-byte aligned (and cap_w a multiple of 4 in a batch)");
+    launch_compact(ctx, model, d_w_sparse, w_stride, d_vecs, d_keep, d_new_width, d_w_out, cap_w,
+                   d_vecs_out, cap_v, K);
+    if ((rc = after_launch(ctx, "compact"))) return rc;
+    if (h_out_tensors || h_out_vecs || h_elems_w || h_elems_v) {
+        const auto& b = model->b;
+        uint8_t* st = b.host_stage;
+        PlanHeader* hh = reinterpret_cast<PlanHeader*>(st);
+        PlanTensor* ht = reinterpret_cast<PlanTensor*>(st + sizeof(PlanHeader) * K);
+        PlanVec* hv = reinterpret_cast<PlanVec*>(st + sizeof(PlanHeader) * K + sizeof(PlanTensor) * n_t * K);
+        HIP_TRY(ctx, hipMemcpyAsync(hh, b.plan_h, sizeof(PlanHeader) * K, hipMemcpyDeviceToHost, ctx->stream));
+        HIP_TRY(ctx, hipMemcpyAsync(ht, b.plan_t, sizeof(PlanTensor) * n_t * K, hipMemcpyDeviceToHost, ctx->stream));
+        if (n_v) HIP_TRY(ctx, hipMemcpyAsync(hv, b.plan_v, sizeof(PlanVec) * n_v * K, hipMemcpyDeviceToHost, ctx->stream));
         HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
-        bool collapse = false;
-        for (size_t g = 0; g < n_g; ++g) {
-            h_new_width[g] = st[g];
-            collapse |= st[g] == 0;
+        uint32_t status = 0;
+        for (uint32_t k = 0; k < K; ++k) {
+            status |= hh[k].status;
+            if (h_elems_w) h_elems_w[k] = hh[k].elems_w;
+            if (h_elems_v) h_elems_v[k] = hh[k].elems_v;
+            if (h_out_tensors) {
+                for (size_t i = 0; i < n_t; ++i) {
+                    shifter_tensor_desc d = model->t[i];
+                    d.offset = ht[k * n_t + i].out_off;
+                    d.out_ch = ht[k * n_t + i].o2;
+                    d.in_ch = ht[k * n_t + i].c2 * d.in_mult;
+                    h_out_tensors[k * n_t + i] = d;
+                }
+            }
+            if (h_out_vecs) {
+                for (size_t i = 0; i < n_v; ++i) {
+                    shifter_vec_desc d = model->v[i];
+                    d.offset = hv[k * n_v + i].out_off;
+                    d.len = hv[k * n_v + i].len2;
+                    h_out_vecs[k * n_v + i] = d;
+                }
+            }
         }
-        if (collapse) {
-            fail(ctx, SHIFTER_WARN_COLLAPSE, "propagate_groups: a group kept no channel (layer collapse)");
+        if (status & 1u)
+            return fail(ctx, SHIFTER_ERR_CAPACITY, "compact: output capacity too small; nothing gathered");
+        if (status & 2u) {
+            fail(ctx, SHIFTER_WARN_COLLAPSE, "compact: a group kept no channel (layer collapse)");
             return SHIFTER_WARN_COLLAPSE;
         }
     }
@@ -540,52 +638,8 @@ extern "C" int shifter_compact(shifter_ctx* ctx, const shifter_model* model, con
                                float* d_vecs_out, uint64_t cap_v,
                                shifter_tensor_desc* h_out_tensors, shifter_vec_desc* h_out_vecs,
                                uint64_t* h_elems_w, uint64_t* h_elems_v) {
-    int rc = enter(ctx, model, "compact");
-    if (rc) return rc;
-    const size_t n_t = model->t.size(), n_v = model->v.size();
-    if (!d_w_sparse || !d_keep || !d_new_width || !d_w_out || (n_v && (!d_vecs || !d_vecs_out)))
-        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "compact: NULL pointer argument");
-    if (misaligned(d_w_out, 16))
-        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "compact: d_w_out must be 16-byte aligned");
-    launch_compact(ctx, model, d_w_sparse, d_vecs, d_keep, d_new_width, d_w_out, cap_w, d_vecs_out, cap_v);
-    if ((rc = after_launch(ctx, "compact"))) return rc;
-    if (h_out_tensors || h_out_vecs || h_elems_w || h_elems_v) {
-        const auto& b = model->b;
-        uint8_t* st = b.host_stage;
-        PlanHeader* hh = reinterpret_cast<PlanHeader*>(st);
-        PlanTensor* ht = reinterpret_cast<PlanTensor*>(st + sizeof(PlanHeader));
-        PlanVec* hv = reinterpret_cast<PlanVec*>(st + sizeof(PlanHeader) + sizeof(PlanTensor) * n_t);
-        HIP_TRY(ctx, hipMemcpyAsync(hh, b.plan_h, sizeof(PlanHeader), hipMemcpyDeviceToHost, ctx->stream));
-        HIP_TRY(ctx, hipMemcpyAsync(ht, b.plan_t, sizeof(PlanTensor) * n_t, hipMemcpyDeviceToHost, ctx->stream));
-        if (n_v) HIP_TRY(ctx, hipMemcpyAsync(hv, b.plan_v, sizeof(PlanVec) * n_v, hipMemcpyDeviceToHost, ctx->stream));
-        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
-        if (h_elems_w) *h_elems_w = hh->elems_w;
-        if (h_elems_v) *h_elems_v = hh->elems_v;
-        if (h_out_tensors) {
-            for (size_t i = 0; i < n_t; ++i) {
-                shifter_tensor_desc d = model->t[i];
-                d.offset = ht[i].out_off;
-                d.out_ch = ht[i].o2;
-                d.in_ch = ht[i].c2 * d.in_mult;
-                h_out_tensors[i] = d;
-            }
-        }
-        if (h_out_vecs) {
-            for (size_t i = 0; i < n_v; ++i) {
-                shifter_vec_desc d = model->v[i];
-                d.offset = hv[i].out_off;
-                d.len = hv[i].len2;
-                h_out_vecs[i] = d;
-            }
-        }
-        if (hh->status & 1u)
-            return fail(ctx, SHIFTER_ERR_CAPACITY, "compact: output capacity too small; nothing gathered");
-        if (hh->status & 2u) {
-            fail(ctx, SHIFTER_WARN_COLLAPSE, "compact: a group kept no channel (layer collapse)");
-            return SHIFTER_WARN_COLLAPSE;
-        }
-    }
-    return SHIFTER_OK;
+    return shifter_compact_batch(ctx, model, d_w_sparse, 0, d_vecs, d_keep, d_new_width, 1, d_w_out, cap_w,
+                                 d_vecs_out, cap_v, h_out_tensors, h_out_vecs, h_elems_w, h_elems_v);
 }
 
 extern "C" int shifter_profile_enable(shifter_ctx* ctx, int on) {

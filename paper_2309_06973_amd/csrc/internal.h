@@ -113,7 +113,7 @@ struct PlanHeader {
 enum KernelId {
     K_SEL_INIT = 0, K_HIST0, K_HIST1, K_HIST2, K_SELECT, K_TIE_COUNT, K_TIE_FINAL,
     K_ZERO_FLAGS, K_MASK_SCAN, K_SCAN, K_PROPAGATE, K_PLAN, K_GATHER, K_GATHER_VEC,
-    K_COPY, K_SPEC_INIT, K_SPEC_SAMPLE, K_SPEC_PREDICT, K_SPEC_PASS, K_SPEC_FINISH, K_SPEC_FINISH2, K_SPEC_FIXUP,
+    K_COPY, K_MASK_SCAN_BATCH, K_EXPAND_LEVELS, K_SPEC_INIT, K_SPEC_SAMPLE, K_SPEC_PREDICT, K_SPEC_PASS, K_SPEC_FINISH, K_SPEC_FINISH2, K_SPEC_FIXUP,
     K_COUNT
 };
 extern const char* const kKernelNames[K_COUNT];
@@ -152,7 +152,8 @@ struct shifter_model {
         shifter::PlanTensor* plan_t = nullptr;
         shifter::PlanVec* plan_v = nullptr;
         shifter::PlanHeader* plan_h = nullptr;
-        uint32_t* out_tile_prefix = nullptr;  // n_tensors + 1
+        uint32_t* out_tile_prefix = nullptr;  // MAXK * (n_tensors + 1)
+        uint32_t* levels = nullptr;           // sum_out_ch + sum_in_ch
         shifter::SpecState* spec = nullptr;
         uint32_t* shist = nullptr;            // 65536 sample bins
         uint32_t* spec_cnt = nullptr;         // 2 * SPEC_SUB counters, one 128-byte line each
@@ -194,13 +195,17 @@ void launch_mask_scan(shifter_ctx* ctx, const shifter_model* m, const float* d_w
                       uint8_t* d_out_alive, uint8_t* d_in_alive);
 void launch_scan(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
                  uint8_t* d_out_alive, uint8_t* d_in_alive);
+void launch_mask_scan_batch(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
+                            const shifter_threshold* d_thr, uint32_t k_var, float* d_w_out,
+                            uint64_t w_stride, uint8_t* d_mask, uint64_t mask_stride,
+                            uint8_t* d_out_alive, uint8_t* d_in_alive);
 void launch_propagate(shifter_ctx* ctx, const shifter_model* m, const uint8_t* d_out_alive,
                       uint32_t flags, uint8_t* d_group_alive, int32_t* d_index_map,
-                      uint32_t* d_keep, uint32_t* d_new_width);
-void launch_compact(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
+                      uint32_t* d_keep, uint32_t* d_new_width, uint32_t k_var);
+void launch_compact(shifter_ctx* ctx, const shifter_model* m, const float* d_w, uint64_t w_stride,
                     const float* d_vecs, const uint32_t* d_keep,
                     const uint32_t* d_new_width, float* d_w_out, uint64_t cap_w,
-                    float* d_vecs_out, uint64_t cap_v);
+                    float* d_vecs_out, uint64_t cap_v, uint32_t k_var);
 void launch_copy(shifter_ctx* ctx, const float* src, float* dst, uint64_t n);
 
 // Event bracketing for per-kernel timing.

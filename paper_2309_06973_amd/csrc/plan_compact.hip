@@ -7,14 +7,21 @@
 
 namespace shifter {
 
-// One block per group.  alive[c] = frozen | OR over producers of out_alive[p][c];
+// One block per group (and per variant of a batch).  alive[c] = frozen | OR over producers of out_alive[p][c];
 // an exclusive scan of alive gives the old -> new map and the keep list.
 __global__ __launch_bounds__(BLOCK) void propagate_kernel(
     const DevGroup* __restrict__ groups, const uint32_t* __restrict__ producers,
     const DevTensor* __restrict__ tens, const uint8_t* __restrict__ out_alive,
     uint32_t flags, uint8_t* __restrict__ group_alive, int32_t* __restrict__ index_map,
-    uint32_t* __restrict__ keep, uint32_t* __restrict__ new_width) {
+    uint32_t* __restrict__ keep, uint32_t* __restrict__ new_width, uint64_t out_alive_stride,
+    uint64_t group_stride, uint32_t n_groups) {
     __shared__ uint32_t wave_cnt[BLOCK / 64];
+    // blockIdx.y = variant of a batch
+    out_alive += blockIdx.y * out_alive_stride;
+    group_alive += blockIdx.y * group_stride;
+    index_map += blockIdx.y * group_stride;
+    keep += blockIdx.y * group_stride;
+    new_width += blockIdx.y * n_groups;
     const DevGroup G = groups[blockIdx.x];
     const uint32_t n_prod = G.prod_end - G.prod_begin;
     const bool frozen = G.pinned || ((flags & SHIFTER_PAPER_FREEZE_RESIDUAL) && n_prod > 1);
@@ -50,7 +57,7 @@ __global__ __launch_bounds__(BLOCK) void propagate_kernel(
     if (threadIdx.x == 0) new_width[blockIdx.x] = base;
 }
 
-// One block: sizes and offsets of every rebuilt tensor and vector (Algorithm 2, the
+// One block per variant: sizes and offsets of every rebuilt tensor and vector (Algorithm 2, the
 // "create new layer" step), tile prefix of the gather launch, capacity check.
 // A rebuilt tensor is tiled in units of TILE floats of the OUTPUT ARENA starting at the
 // 16-byte boundary at or below its first element, so that the gather stores whole
@@ -63,6 +70,12 @@ __global__ __launch_bounds__(BLOCK) void plan_kernel(
     PlanHeader* __restrict__ hdr) {
     __shared__ uint64_t smem[BLOCK / 64 + 1];
     __shared__ uint32_t s_collapse;
+    // blockIdx.x = variant of a batch
+    new_width += blockIdx.x * n_g;
+    pt += blockIdx.x * n_t;
+    pv += blockIdx.x * n_v;
+    otp += blockIdx.x * (n_t + 1);
+    hdr += blockIdx.x;
     if (threadIdx.x == 0) s_collapse = 0;
     uint64_t off = 0, tiles = 0, tot;
     for (uint32_t t0 = 0; t0 < n_t; t0 += BLOCK) {
@@ -119,7 +132,17 @@ __global__ __launch_bounds__(BLOCK) void gather_kernel(
     const PlanHeader* __restrict__ hdr, const float* __restrict__ w,
     const uint32_t* __restrict__ keep, float* __restrict__ w_out,
     const DevVec* __restrict__ vecs, uint32_t n_v, const PlanVec* __restrict__ pv,
-    const float* __restrict__ v, float* __restrict__ v_out) {
+    const float* __restrict__ v, float* __restrict__ v_out, uint64_t w_stride,
+    uint64_t group_stride, uint64_t cap_w, uint64_t cap_v) {
+    // blockIdx.y = variant of a batch
+    pt += blockIdx.y * n_t;
+    otp += blockIdx.y * (n_t + 1);
+    hdr += blockIdx.y;
+    pv += blockIdx.y * n_v;
+    w += blockIdx.y * w_stride;
+    keep += blockIdx.y * group_stride;
+    w_out += blockIdx.y * cap_w;
+    v_out += blockIdx.y * cap_v;
     if (hdr->status & 1u) return;
     const uint32_t total = hdr->total_tiles;
     for (uint32_t tile = blockIdx.x; tile < total; tile += gridDim.x) {
@@ -221,35 +244,37 @@ __global__ __launch_bounds__(BLOCK) void copy_tail_kernel(const float* __restric
 
 void launch_propagate(shifter_ctx* ctx, const shifter_model* m, const uint8_t* d_out_alive,
                       uint32_t flags, uint8_t* d_group_alive, int32_t* d_index_map,
-                      uint32_t* d_keep, uint32_t* d_new_width) {
+                      uint32_t* d_keep, uint32_t* d_new_width, uint32_t k_var) {
     const auto& b = m->b;
     ProfileScope p(ctx, K_PROPAGATE);
-    propagate_kernel<<<(uint32_t)m->g.size(), BLOCK, 0, ctx->stream>>>(
+    propagate_kernel<<<dim3((uint32_t)m->g.size(), k_var), BLOCK, 0, ctx->stream>>>(
         b.groups, b.producers, b.tens, d_out_alive, flags, d_group_alive, d_index_map, d_keep,
-        d_new_width);
+        d_new_width, m->info.sum_out_ch, m->info.sum_group_width, (uint32_t)m->g.size());
 }
 
-void launch_compact(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
+void launch_compact(shifter_ctx* ctx, const shifter_model* m, const float* d_w, uint64_t w_stride,
                     const float* d_vecs, const uint32_t* d_keep,
                     const uint32_t* d_new_width, float* d_w_out, uint64_t cap_w,
-                    float* d_vecs_out, uint64_t cap_v) {
+                    float* d_vecs_out, uint64_t cap_v, uint32_t k_var) {
     const auto& b = m->b;
     const uint32_t n_t = (uint32_t)m->t.size(), n_v = (uint32_t)m->v.size();
     {
         ProfileScope p(ctx, K_PLAN);
-        plan_kernel<<<1, BLOCK, 0, ctx->stream>>>(b.tens, n_t, b.vecs, n_v, b.groups,
-                                                  (uint32_t)m->g.size(), d_new_width, cap_w,
-                                                  cap_v, b.plan_t, b.plan_v, b.out_tile_prefix,
-                                                  b.plan_h);
+        plan_kernel<<<k_var, BLOCK, 0, ctx->stream>>>(b.tens, n_t, b.vecs, n_v, b.groups,
+                                                      (uint32_t)m->g.size(), d_new_width, cap_w,
+                                                      cap_v, b.plan_t, b.plan_v, b.out_tile_prefix,
+                                                      b.plan_h);
     }
     {
-        // the tile count is only known on the device: a fixed grid walks the tiles
+        // the tile counts are only known on the device: a fixed grid walks the tiles
         ProfileScope p(ctx, K_GATHER);
         const uint32_t bound = m->n_tiles + n_t;   // tiles when nothing is removed, at most
-        const uint32_t grid = std::max(1u, std::min(bound, ctx->hist_grid * 2));
-        gather_kernel<<<grid, BLOCK, 0, ctx->stream>>>(
+        const uint32_t per_variant = std::max(256u, ctx->hist_grid * 2 / k_var);
+        const uint32_t grid = std::max(1u, std::min(bound, per_variant));
+        gather_kernel<<<dim3(grid, k_var), BLOCK, 0, ctx->stream>>>(
             b.tens, b.groups, n_t, b.plan_t, b.out_tile_prefix, b.plan_h, d_w, d_keep, d_w_out,
-            b.vecs, n_v, b.plan_v, d_vecs, d_vecs_out);
+            b.vecs, n_v, b.plan_v, d_vecs, d_vecs_out, w_stride, m->info.sum_group_width, cap_w,
+            cap_v);
     }
 }
 

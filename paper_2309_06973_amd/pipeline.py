@@ -84,6 +84,48 @@ class Pipeline:
                                  self.d_keep, self.d_new_width, self.d_w_out,
                                  self.d_vecs_out, sync)
 
+    # ---- a whole portfolio per call -------------------------------------------------
+    def enable_batch(self, k: int):
+        """Allocates the K-variant output buffers (strides rounded to 64 elements)."""
+        info = self.model.info
+        r64 = lambda x: (int(x) + 63) // 64 * 64
+        self.bk = k
+        self.w_stride = r64(info.w_extent)
+        self.m_stride = r64(max(info.n_prunable, 4))
+        self.cap_w = r64(max(info.w_elems, 4))
+        self.cap_v = r64(max(info.v_elems, 4))
+        u8 = dict(dtype=torch.uint8, device=self.dev)
+        i32 = dict(dtype=torch.int32, device=self.dev)
+        f32 = dict(dtype=torch.float32, device=self.dev)
+        self.b_w_sparse = torch.empty(k * self.w_stride, **f32)
+        self.b_mask = torch.empty(k * self.m_stride, **u8)
+        self.b_out_alive = torch.empty(k * info.sum_out_ch, **u8)
+        self.b_in_alive = torch.empty(k * info.sum_in_ch, **u8)
+        self.b_group_alive = torch.empty(k * info.sum_group_width, **u8)
+        self.b_index_map = torch.empty(k * info.sum_group_width, **i32)
+        self.b_keep = torch.empty(k * info.sum_group_width, **i32)
+        self.b_new_width = torch.empty(k * info.n_groups, **i32)
+        self.b_w_out = torch.empty(k * self.cap_w, **f32)
+        self.b_vecs_out = torch.empty(k * self.cap_v, **f32)
+
+    def portfolio(self, n_prune: Sequence[int], flags: int = 0, with_in_alive: bool = True,
+                  sync: bool = True):
+        """All five steps for every prune count: one ranking call, then one batched call
+        per step.  Returns (threshold records, compact_batch's tuple)."""
+        k = len(n_prune)
+        assert k == self.bk
+        recs = self.global_threshold(n_prune, sync=True)
+        S.shifter_apply_mask_batch(self.ctx, self.model, self.d_w, self.d_thr, k, self.b_w_sparse,
+                                   self.w_stride, self.b_mask, self.m_stride, self.b_out_alive,
+                                   self.b_in_alive if with_in_alive else None)
+        S.shifter_propagate_groups_batch(self.ctx, self.model, self.b_out_alive, k, flags,
+                                         self.b_group_alive, self.b_index_map, self.b_keep,
+                                         self.b_new_width, sync=False)
+        out = S.shifter_compact_batch(self.ctx, self.model, self.b_w_sparse, self.w_stride,
+                                      self.d_vecs, self.b_keep, self.b_new_width, k, self.b_w_out,
+                                      self.cap_w, self.b_vecs_out, self.cap_v, sync=sync)
+        return recs, out
+
     def variant(self, k: int = 0, flags: int = 0, fused_scan: bool = True,
                 sync: bool = True):
         """Steps 2-5 for threshold record k.  Returns compact()'s tuple."""

@@ -84,6 +84,17 @@ EXPORTS = {
                         C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64,
                         C.POINTER(TensorDesc), C.POINTER(VecDesc), C.POINTER(C.c_uint64),
                         C.POINTER(C.c_uint64)],
+    "shifter_apply_mask_batch": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
+                                 C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64, C.c_void_p,
+                                 C.c_void_p],
+    "shifter_propagate_groups_batch": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
+                                       C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                       C.c_void_p, C.POINTER(C.c_uint32)],
+    "shifter_compact_batch": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p,
+                              C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint64,
+                              C.c_void_p, C.c_uint64, C.POINTER(TensorDesc),
+                              C.POINTER(VecDesc), C.POINTER(C.c_uint64),
+                              C.POINTER(C.c_uint64)],
     "shifter_profile_enable": [C.c_void_p, C.c_int],
     "shifter_profile_read": [C.c_void_p, C.POINTER(C.c_char_p), C.POINTER(C.c_uint32),
                              C.POINTER(C.c_double), C.c_uint32, C.POINTER(C.c_uint32)],
@@ -279,6 +290,50 @@ def shifter_compact(ctx: Context, model: Model, d_w_sparse, d_vecs, d_keep, d_ne
                                f"{ev.value} vector floats)")
     _check(rc, ctx.handle, allow=(SHIFTER_WARN_COLLAPSE,))
     return rc, list(ot), list(ov)[:model.info.n_vecs], ew.value, ev.value
+
+
+def shifter_apply_mask_batch(ctx: Context, model: Model, d_w, d_thr, k: int, d_w_out,
+                             w_stride: int, d_mask, mask_stride: int, d_out_alive,
+                             d_in_alive=None) -> None:
+    _check(load_library().shifter_apply_mask_batch(
+        ctx.handle, model.handle, _ptr(d_w), _ptr(d_thr), k, _ptr(d_w_out), w_stride,
+        _ptr(d_mask), mask_stride, _ptr(d_out_alive), _ptr(d_in_alive)), ctx.handle)
+
+
+def shifter_propagate_groups_batch(ctx: Context, model: Model, d_out_alive, k: int, flags: int,
+                                   d_group_alive, d_index_map, d_keep, d_new_width,
+                                   sync: bool = True):
+    h = (C.c_uint32 * (model.info.n_groups * k))() if sync else None
+    rc = _check(load_library().shifter_propagate_groups_batch(
+        ctx.handle, model.handle, _ptr(d_out_alive), k, flags, _ptr(d_group_alive),
+        _ptr(d_index_map), _ptr(d_keep), _ptr(d_new_width), h), ctx.handle,
+        allow=(SHIFTER_WARN_COLLAPSE,))
+    return rc, (list(h) if sync else None)
+
+
+def shifter_compact_batch(ctx: Context, model: Model, d_w_sparse, w_stride: int, d_vecs, d_keep,
+                          d_new_width, k: int, d_w_out, cap_w: int, d_vecs_out, cap_v: int,
+                          sync: bool = True):
+    """When sync: (status, K lists of tensor descs, K lists of vec descs, elems_w[K],
+    elems_v[K])."""
+    if not sync:
+        _check(load_library().shifter_compact_batch(
+            ctx.handle, model.handle, _ptr(d_w_sparse), w_stride, _ptr(d_vecs), _ptr(d_keep),
+            _ptr(d_new_width), k, _ptr(d_w_out), cap_w, _ptr(d_vecs_out), cap_v, None, None,
+            None, None), ctx.handle)
+        return SHIFTER_OK, None, None, None, None
+    n_t, n_v = model.info.n_tensors, model.info.n_vecs
+    ot = (TensorDesc * (n_t * k))()
+    ov = (VecDesc * max(n_v * k, 1))()
+    ew = (C.c_uint64 * k)()
+    ev = (C.c_uint64 * k)()
+    rc = _check(load_library().shifter_compact_batch(
+        ctx.handle, model.handle, _ptr(d_w_sparse), w_stride, _ptr(d_vecs), _ptr(d_keep),
+        _ptr(d_new_width), k, _ptr(d_w_out), cap_w, _ptr(d_vecs_out), cap_v, ot, ov, ew, ev),
+        ctx.handle, allow=(SHIFTER_WARN_COLLAPSE,))
+    ot, ov = list(ot), list(ov)
+    return (rc, [ot[i * n_t:(i + 1) * n_t] for i in range(k)],
+            [ov[i * n_v:(i + 1) * n_v] for i in range(k)], list(ew), list(ev))
 
 
 def shifter_profile_enable(ctx: Context, on: bool) -> None:

@@ -288,3 +288,84 @@ def test_single_pass_selection_is_taken_and_falls_back_on_ties():
         assert rec.g_cut == p - 1 and rec.n_equal == spec.n_prunable
     finally:
         pl.close()
+
+
+# ------------------------------------------------------------------ portfolio per call
+def check_batch(spec, w, v, n_prune, flags=0, check=None, with_in_alive=True):
+    """Batched steps 2-5 for all prune counts at once, every variant against the oracle."""
+    refs = O.prune_and_compact(w, v, spec.tensors, spec.vecs, spec.groups, n_prune, flags)
+    a = np.abs(O.gather_prunable(w, spec.tensors))
+    k_var = len(n_prune)
+    pl = Pipeline(spec, w, v)
+    try:
+        pl.enable_batch(k_var)
+        info = pl.model.info
+        recs, (rc, ots, ovs, ews, evs) = pl.portfolio(n_prune, flags, with_in_alive)
+        torch.cuda.synchronize()
+        collapse = any((r.plan.new_width == 0).any() for r in refs)
+        assert rc == (S.SHIFTER_WARN_COLLAPSE if collapse else S.SHIFTER_OK)
+        n = info.n_prunable
+        for k in (check if check is not None else range(k_var)):
+            ref, lab = refs[k], f"{spec.name} batch k={k}"
+            check_threshold(recs[k], ref.sel, a)
+            mask = pl.b_mask[k * pl.m_stride:k * pl.m_stride + n].cpu().numpy()
+            assert np.array_equal(mask, ref.mask), lab + " mask"
+            ws = pl.b_w_sparse[k * pl.w_stride:(k + 1) * pl.w_stride].cpu().numpy()
+            for t in spec.tensors:
+                sl = slice(t.offset, t.offset + t.numel)
+                assert np.array_equal(bits(ws[sl]), bits(ref.w_sparse[sl])), lab + " sparse"
+            so, si, sg = info.sum_out_ch, info.sum_in_ch, info.sum_group_width
+            oa = pl.b_out_alive[k * so:(k + 1) * so].cpu().numpy()
+            assert np.array_equal(oa, np.concatenate(ref.out_alive)), lab + " out_alive"
+            if with_in_alive:
+                ia = pl.b_in_alive[k * si:(k + 1) * si].cpu().numpy()
+                assert np.array_equal(ia, np.concatenate(ref.in_alive)), lab + " in_alive"
+            ga = pl.b_group_alive[k * sg:(k + 1) * sg].cpu().numpy()
+            im = pl.b_index_map[k * sg:(k + 1) * sg].cpu().numpy()
+            kp = pl.b_keep[k * sg:(k + 1) * sg].cpu().numpy().view(np.uint32)
+            ng = info.n_groups
+            nw = pl.b_new_width[k * ng:(k + 1) * ng].cpu().numpy().view(np.uint32)
+            assert np.array_equal(nw, ref.plan.new_width), lab + " new_width"
+            for gi, g in enumerate(spec.groups):
+                o = pl.model.group_off[gi]
+                assert np.array_equal(ga[o:o + g.width], ref.plan.alive[gi]), lab + " alive"
+                assert np.array_equal(im[o:o + g.width], ref.plan.index_map[gi]), lab + " map"
+                kk = int(nw[gi])
+                assert np.array_equal(kp[o:o + kk], ref.plan.keep[gi]), lab + " keep"
+            assert ews[k] == ref.compacted.w.size and evs[k] == ref.compacted.v.size
+            wc = pl.b_w_out[k * pl.cap_w:k * pl.cap_w + ews[k]].cpu().numpy()
+            vc = pl.b_vecs_out[k * pl.cap_v:k * pl.cap_v + evs[k]].cpu().numpy()
+            assert np.array_equal(bits(wc), bits(ref.compacted.w)), lab + " compacted w"
+            assert np.array_equal(bits(vc), bits(ref.compacted.v)), lab + " compacted v"
+            for d, (off, o2, i2, kh, kw) in zip(ots[k], ref.compacted.tensor_shapes):
+                assert (d.offset, d.out_ch, d.in_ch, d.kh, d.kw) == (off, o2, i2, kh, kw)
+            for d, (off, ln) in zip(ovs[k], ref.compacted.vec_shapes):
+                assert (d.offset, d.len) == (off, ln)
+    finally:
+        pl.close()
+
+
+def test_batch_small_configs_any_order_of_counts():
+    spec, w, v = synth.generate_config(1)
+    n = spec.n_prunable
+    check_batch(spec, w, v, [n // 2, 0, n, synth.prune_count(n, 0.9), n // 2, 17, n - 1])
+    spec, w, v = synth.generate_config(3)
+    check_batch(spec, w, v, portfolio_counts(3, spec))
+    check_batch(spec, w, v, portfolio_counts(3, spec)[4:9], flags=S.SHIFTER_PAPER_FREEZE_RESIDUAL,
+                with_in_alive=False)
+
+
+def test_batch_resnet50_and_vgg16_portfolios():
+    spec, w, v = synth.generate_config(4)
+    check_batch(spec, w, v, portfolio_counts(4, spec), check=[0, 7, 13, 19])
+    spec, w, v = synth.generate_config(2)
+    check_batch(spec, w, v, portfolio_counts(2, spec), check=[0, 4, 9])
+
+
+@pytest.mark.parametrize("kind", ["half_zero", "quantised", "all_equal", "inf_negzero"])
+def test_batch_adversarial_ragged(kind):
+    spec = synth.chain_spec([37, 129, 61], k=5, in_ch=5, n_cls=7, name="ragged5")
+    w = synth.adversarial_arena(kind, spec.w_elems, seed=5)
+    _, v = synth.generate_weights(spec, 3)
+    n = spec.n_prunable
+    check_batch(spec, w, v, [n // 3, n // 2, 1, (9 * n) // 10, n // 2 + 1, 0])
