@@ -99,6 +99,20 @@ extern "C" int shifter_destroy(shifter_ctx* ctx) {
     return SHIFTER_OK;
 }
 
+// (magic, shift) with x / d == (((x - mulhi(x, magic)) >> 1) + mulhi(x, magic)) >> shift
+// for every 32-bit x, d >= 2 (the round-up method of division by an invariant integer).
+static void magic_u32(uint32_t d, uint32_t* magic, uint32_t* shift) {
+    uint32_t l = 31;
+    while (!(d >> l)) --l;              // floor(log2 d)
+    if ((d & (d - 1)) == 0) { *magic = 0; *shift = l - 1; return; }
+    uint64_t pm = (1ull << (32 + l)) / d;
+    const uint64_t rem = (1ull << (32 + l)) - pm * d;
+    pm *= 2;
+    if (2 * rem >= d) pm += 1;
+    *magic = (uint32_t)(pm + 1);
+    *shift = l;
+}
+
 static uint32_t magic_for(uint32_t d) {
     if (d <= 1 || d > 2 * TILE) return 0;
     return (uint32_t)((1ull << 32) / d) + 1u;
@@ -167,6 +181,18 @@ extern "C" int shifter_model_create(const shifter_tensor_desc* tensors, uint32_t
         d.magic_khw = magic_for(d.khw);
         d.magic_row = magic_for(d.row_len);
         d.magic_in = magic_for(d.in_ch);
+        d.magic_kk = d.shift_kk = 0;
+        if (d.kk >= 2) magic_u32(d.kk, &d.magic_kk, &d.shift_kk);
+        d.pad2[0] = d.pad2[1] = 0;
+        {
+            // work units of the gather when nothing is removed (see plan_kernel)
+            const uint32_t chunks = (d.row_len + GATHER_CHUNK - 1) / GATHER_CHUNK;
+            uint32_t lg = 6;
+            while (lg < 10 && (1u << lg) < d.row_len) ++lg;
+            const uint32_t rows_par = GATHER_CHUNK >> lg;
+            const uint32_t rb = 4u * std::max(rows_par, 4u);
+            m->gather_units_bound += chunks * ((t.out_ch + rb - 1) / rb);
+        }
         d.out_group = t.out_group;
         d.in_group = t.in_group;
         d.out_flag_off = (uint32_t)so;

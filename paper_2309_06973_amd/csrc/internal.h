@@ -16,6 +16,8 @@ constexpr uint32_t BLOCK = 256;      // threads per block (4 wavefronts of 64)
 constexpr uint32_t HIST_BINS = 2048; // stride of one histogram slot
 constexpr uint32_t MAXK = SHIFTER_MAX_VARIANTS;
 constexpr uint32_t SLOTS_PER_PASS = 8;
+constexpr uint32_t GATHER_CHUNK = 1024;  // columns of a gather work unit (16 per lane)
+constexpr uint32_t GATHER_ROWS = 16;     // its rows, for rows of GATHER_CHUNK or more columns
 
 // Device-side view of one weight tensor.
 struct DevTensor {
@@ -29,10 +31,12 @@ struct DevTensor {
     uint32_t magic_khw;  // floor(2^32 / khw) + 1 when 1 < khw <= 2 * TILE, else 0
     uint32_t magic_row;  // same for row_len
     uint32_t magic_in;   // same for in_ch
+    uint32_t magic_kk, shift_kk;  // any 32-bit x / kk (kk >= 2): see div_u32
     int32_t out_group, in_group;
     uint32_t out_flag_off, in_flag_off;
     uint32_t prunable;
     uint32_t pad;
+    uint32_t pad2[2];
 };
 
 struct DevGroup {
@@ -95,7 +99,9 @@ struct PlanTensor {
     uint64_t out_off;
     uint32_t o2, c2;     // surviving filters, surviving input channels
     uint32_t numel2;
-    uint32_t pad;
+    uint32_t row2;       // c2 * kk: elements per rebuilt filter
+    uint32_t chunks;     // column chunks per row
+    uint32_t rb;         // rows per work unit
 };
 
 struct PlanVec {
@@ -106,7 +112,7 @@ struct PlanVec {
 
 struct PlanHeader {
     uint64_t elems_w, elems_v;
-    uint32_t total_tiles;
+    uint32_t total_units;
     uint32_t status;     // bit 0: capacity exceeded; bit 1: some group collapsed
 };
 
@@ -136,6 +142,7 @@ struct shifter_model {
     uint32_t n_ranked = 0;
     uint32_t sample_tile_stride = 1;     // every how many tiles the selection samples
     uint32_t sample_size = 0;            // weights in that sample
+    uint32_t gather_units_bound = 0;     // gather work units when nothing is removed
 
     // device side, created by the first call that uses the model with a context
     struct Bound {
