@@ -82,7 +82,8 @@ static void unbind(shifter_model* m) {
     (void)hipSetDevice(b.device);
     void* ptrs[] = {b.tens, b.groups, b.vecs, b.producers, b.tile_prefix, b.sel, b.ghist,
                     b.tile_cnt, b.plan_t, b.plan_v, b.plan_h, b.out_tile_prefix, b.levels, b.spec, b.shist,
-                    b.spec_cnt, b.partial, b.cand, b.list, b.ranked_ids};
+                    b.spec_cnt, b.partial, b.cand, b.list, b.ranked_ids, b.multi, b.multi_cnt,
+                    b.multi_partial, b.multi_seg, b.multi_seg_cnt};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     if (b.host_stage) (void)hipHostFree(b.host_stage);
@@ -338,14 +339,22 @@ static int bind(shifter_ctx* ctx, const shifter_model* cm) {
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.shist), sizeof(uint32_t) * 65536));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.spec_cnt), sizeof(uint32_t) * 2 * SPEC_SUB * 32));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.partial), sizeof(uint32_t) * SPEC_FIN_BLOCKS * 256));
-    // candidate pairs: 1/16 of N in total, at least two tiles per sub-buffer
-    b.cand_cap_sb = (uint32_t)std::max<uint64_t>(m->info.n_prunable / 16 / SPEC_SUB, 2 * TILE);
+    // candidate pairs: 1/4 of N in total (a 20-variant portfolio on a mid-size model makes
+    // candidates of about a tenth of the weights), at least two tiles per sub-buffer
+    b.cand_cap_sb = (uint32_t)std::max<uint64_t>(m->info.n_prunable / 4 / SPEC_SUB, 2 * TILE);
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.cand), sizeof(uint2) * (size_t)b.cand_cap_sb * SPEC_SUB));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.list), sizeof(uint2) * SPEC_LIST_CAP));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.multi), sizeof(MultiState)));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.multi_cnt), sizeof(uint32_t) * (MAXK + 2) * SPEC_SUB * 32));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.multi_partial),
+                           sizeof(uint32_t) * SPEC_SUB * SPEC_MULTI_MAXK * 256));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.multi_seg),
+                           sizeof(uint2) * (size_t)SPEC_MULTI_MAXK * SPEC_SUB * SPEC_SEG_CAP));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.multi_seg_cnt), sizeof(uint32_t) * SPEC_MULTI_MAXK * SPEC_SUB));
     b.host_stage_bytes = sizeof(SelState) + sizeof(shifter_threshold) * MAXK +
                          MAXK * (sizeof(PlanHeader) + sizeof(PlanTensor) * n_t + sizeof(PlanVec) * n_v +
                                  sizeof(uint32_t) * m->g.size()) +
-                         sizeof(SpecState) + 256;
+                         sizeof(SpecState) + sizeof(MultiState) + 256;
     HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&b.host_stage), b.host_stage_bytes, hipHostMallocDefault));
     return SHIFTER_OK;
 }
@@ -416,6 +425,39 @@ extern "C" int shifter_global_threshold(shifter_ctx* ctx, const shifter_model* m
         int decided = 0;
         if ((rc = spec_result(ctx, model, d_thr, h_thr, &decided))) return rc;
         if (decided) return SHIFTER_OK;
+    }
+    if (h_thr && K > 1 && ctx->select_path == 0) {
+        // all counts in a single pass; the counts > 0 sorted ascending, at most
+        // SPEC_MULTI_MAXK of them
+        PruneCounts sp;
+        MultiPerm perm;
+        memset(&sp, 0, sizeof sp);
+        memset(&perm, 0, sizeof perm);
+        uint32_t idx[MAXK], k_eff = 0;
+        uint64_t zero_mask = 0;
+        for (uint32_t k = 0; k < K; ++k) {
+            if (pc.p[k] == 0) zero_mask |= 1ull << k; else idx[k_eff++] = k;
+        }
+        if (k_eff <= SPEC_MULTI_MAXK) {
+            std::stable_sort(idx, idx + k_eff, [&](uint32_t a, uint32_t b) { return pc.p[a] < pc.p[b]; });
+            for (uint32_t i = 0; i < k_eff; ++i) { sp.p[i] = pc.p[idx[i]]; perm.v[i] = idx[i]; }
+            launch_spec_multi(ctx, model, d_w, sp, perm, k_eff, zero_mask, d_thr);
+            if ((rc = after_launch(ctx, "global_threshold"))) return rc;
+            uint8_t* st = model->b.host_stage;
+            HIP_TRY(ctx, hipMemcpyAsync(st, &model->b.multi->status, sizeof(uint32_t), hipMemcpyDeviceToHost, ctx->stream));
+            HIP_TRY(ctx, hipMemcpyAsync(st + 64, d_thr, sizeof(shifter_threshold) * K, hipMemcpyDeviceToHost, ctx->stream));
+            HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+            uint32_t status;
+            memcpy(&status, st, sizeof status);
+            if (status & 2u)
+                return fail(ctx, SHIFTER_ERR_NONFINITE, "global_threshold: NaN among the prunable weights");
+            ctx->last_path = (status & 1u) ? 2 : 1;
+            if (!(status & 1u)) {
+                memcpy(h_thr, st + 64, sizeof(shifter_threshold) * K);
+                return SHIFTER_OK;
+            }
+            if (ctx->margin_sigmas < 64.0) ctx->margin_sigmas *= 2.0;
+        }
     }
     launch_select(ctx, model, d_w, pc, K, d_thr);
     if ((rc = after_launch(ctx, "global_threshold"))) return rc;

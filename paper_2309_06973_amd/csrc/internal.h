@@ -90,6 +90,22 @@ struct SpecState {
     uint32_t list_cnt;
 };
 
+// State of the single-pass selection for all prune counts of a portfolio (ranks sorted by
+// prune count, zero counts left out).
+constexpr uint32_t SPEC_MULTI_MAXK = 32;   // LDS of the round-1 histograms: 1 KB per rank
+constexpr uint32_t SPEC_SEG_CAP = 256;     // pairs per (rank, block) list segment
+struct MultiState {
+    uint64_t p[MAXK];
+    uint64_t r2[MAXK], less[MAXK];
+    uint32_t perm[MAXK];   // original position of sorted rank k
+    uint32_t lo[MAXK], hi[MAXK], sh[MAXK];
+    uint32_t bin[MAXK], bin_cnt[MAXK], seg_over[MAXK];
+    uint32_t k, m_valid, status, pad;
+};
+struct MultiPerm {
+    uint32_t v[MAXK];
+};
+
 struct PruneCounts {
     uint64_t p[MAXK];
 };
@@ -169,6 +185,11 @@ struct shifter_model {
         uint32_t cand_cap_sb = 0;             // pairs per sub-buffer
         uint2* list = nullptr;                // SPEC_LIST_CAP pairs
         uint32_t* ranked_ids = nullptr;
+        shifter::MultiState* multi = nullptr;
+        uint32_t* multi_cnt = nullptr;        // (MAXK + 2) * SPEC_SUB counters, 128-byte lines
+        uint32_t* multi_partial = nullptr;    // SPEC_SUB * SPEC_MULTI_MAXK * 256
+        uint2* multi_seg = nullptr;           // SPEC_MULTI_MAXK * SPEC_SUB * SPEC_SEG_CAP pairs
+        uint32_t* multi_seg_cnt = nullptr;    // SPEC_MULTI_MAXK * SPEC_SUB
         uint8_t* host_stage = nullptr;        // pinned, for small read-backs
         size_t host_stage_bytes = 0;
     } b;
@@ -197,6 +218,10 @@ void launch_select(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
 void launch_spec_select(shifter_ctx* ctx, const shifter_model* m, const float* d_w, uint64_t p,
                         shifter_threshold* d_thr, float* d_w_out, uint8_t* d_mask,
                         uint8_t* d_out_alive, uint8_t* d_in_alive);
+void launch_spec_sample(shifter_ctx* ctx, const shifter_model* m, const float* d_w);
+void launch_spec_multi(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
+                       const PruneCounts& sorted_p, const MultiPerm& perm, uint32_t k,
+                       uint64_t zero_mask, shifter_threshold* d_thr);
 void launch_mask_scan(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
                       const shifter_threshold* d_thr, float* d_w_out, uint8_t* d_mask,
                       uint8_t* d_out_alive, uint8_t* d_in_alive);

@@ -614,6 +614,15 @@ __global__ __launch_bounds__(BLOCK) void spec_fixup_kernel(
     });
 }
 
+void launch_spec_sample(shifter_ctx* ctx, const shifter_model* m, const float* d_w) {
+    const auto& b = m->b;
+    const uint32_t sampled = (m->n_tiles + m->sample_tile_stride - 1) / m->sample_tile_stride;
+    const uint32_t grid = min(256u, (sampled + BLOCK / 64 - 1) / (BLOCK / 64));
+    spec_sample_kernel<<<grid, BLOCK, 0, ctx->stream>>>(b.tens, b.tile_prefix, (uint32_t)m->t.size(),
+                                                        m->n_tiles, m->sample_tile_stride, d_w,
+                                                        b.shist);
+}
+
 void launch_spec_select(shifter_ctx* ctx, const shifter_model* m, const float* d_w, uint64_t p,
                         shifter_threshold* d_thr, float* d_w_out, uint8_t* d_mask,
                         uint8_t* d_out_alive, uint8_t* d_in_alive) {
@@ -621,7 +630,6 @@ void launch_spec_select(shifter_ctx* ctx, const shifter_model* m, const float* d
     const uint32_t n_t = (uint32_t)m->t.size();
     const bool fused = d_w_out != nullptr;
     hipStream_t s = ctx->stream;
-    const uint32_t tile_stride = m->sample_tile_stride;
     {
         ProfileScope ps(ctx, K_SPEC_INIT);
         spec_init_kernel<<<64, BLOCK, 0, s>>>(b.spec, b.shist, b.spec_cnt, p, m->sample_size,
@@ -631,10 +639,7 @@ void launch_spec_select(shifter_ctx* ctx, const shifter_model* m, const float* d
     }
     {
         ProfileScope ps(ctx, K_SPEC_SAMPLE);
-        const uint32_t sampled = (m->n_tiles + tile_stride - 1) / tile_stride;
-        const uint32_t grid = min(256u, (sampled + BLOCK / 64 - 1) / (BLOCK / 64));
-        spec_sample_kernel<<<grid, BLOCK, 0, s>>>(b.tens, b.tile_prefix, n_t, m->n_tiles,
-                                                  tile_stride, d_w, b.shist);
+        launch_spec_sample(ctx, m, d_w);
     }
     {
         ProfileScope ps(ctx, K_SPEC_PREDICT);

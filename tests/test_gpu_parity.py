@@ -369,3 +369,24 @@ def test_batch_adversarial_ragged(kind):
     _, v = synth.generate_weights(spec, 3)
     n = spec.n_prunable
     check_batch(spec, w, v, [n // 3, n // 2, 1, (9 * n) // 10, n // 2 + 1, 0])
+
+
+def test_portfolio_ranking_takes_the_single_pass():
+    # every count of a portfolio in one read of the arena (no radix kernels run), in any
+    # order of the counts, zero counts included
+    spec, w, v = synth.generate_config(2)
+    n = spec.n_prunable
+    ps = portfolio_counts(2, spec)
+    ps = [ps[3], 0, ps[9], ps[0]] + ps[4:9] + [0, ps[1], ps[2]]
+    refs = O.select_pruned(w, spec.tensors, ps)
+    a = np.abs(O.gather_prunable(w, spec.tensors))
+    pl = Pipeline(spec, w, v)
+    try:
+        S.shifter_profile_enable(pl.ctx, True)
+        recs = pl.global_threshold(ps)
+        prof = S.shifter_profile_read(pl.ctx)
+        assert "spec_pass" in prof and "hist_round0" not in prof, prof
+        for rec, ref in zip(recs, refs):
+            check_threshold(rec, ref, a)
+    finally:
+        pl.close()
