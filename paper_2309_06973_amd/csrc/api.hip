@@ -2,6 +2,7 @@
 // checks, stream-ordered launches and the small read-backs the ABI documents.
 #include <algorithm>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -218,24 +219,23 @@ extern "C" int shifter_model_create(const shifter_tensor_desc* tensors, uint32_t
     for (uint32_t i = 0; i < n_tensors; ++i)
         if (tensors[i].prunable) m->ranked_ids.push_back(i);
     m->n_ranked = (uint32_t)m->ranked_ids.size();
-    // the single-pass selection samples two 32-float lines (rotating with the tile index)
-    // of every sample_tile_stride-th tile; its size is fixed by the descriptors
-    m->sample_tile_stride = m->n_tiles > 4096u ? m->n_tiles / 4096u : 1u;
+    // the single-pass selection samples one 16-weight sector per 1024 weights of every
+    // sample_tile_stride-th tile (see spec_sample_kernel); its size is fixed by the
+    // descriptors.  About N / 64 samples, at most ~8 M.
+    m->sample_tile_stride = m->n_tiles > 131072u ? m->n_tiles / 131072u : 1u;
     for (uint32_t tile = 0, ti = 0; tile < m->n_tiles; tile += m->sample_tile_stride) {
         while (m->tile_prefix[ti + 1] <= tile) ++ti;
         if (!tensors[ti].prunable) continue;
         const uint64_t e0 = (uint64_t)(tile - m->tile_prefix[ti]) * TILE;
         const uint64_t n = std::min<uint64_t>(TILE, m->dt[ti].numel - e0);
-        const uint32_t l0 = (tile * 37u) & 63u;
-        for (uint32_t half = 0; half < 2; ++half) {
-            const uint64_t first = (uint64_t)(l0 + half * 64u) * 32u;
-            if (first < n) m->sample_size += (uint32_t)std::min<uint64_t>(32, n - first);
+        for (uint32_t quarter = 0; quarter < 4; ++quarter) {
+            const uint32_t sector = (tile * 37u + quarter * 11u) & 63u;
+            for (uint32_t part = 0; part < 4; ++part) {
+                const uint64_t j = quarter * 1024u + sector * 16u + part * 4u;
+                if (j + 3 < n) m->sample_size += 4;
+            }
         }
     }
-    if (gbase >= (1ull << 32) - 1) return bad("N (prunable weights) reaches 2^32 - 1", n_tensors - 1);
-    std::sort(spans.begin(), spans.end());
-    for (size_t i = 1; i < spans.size(); ++i)
-        if (spans[i].first < spans[i - 1].second) return bad("tensors overlap in the weight arena", (uint32_t)i);
 
     uint64_t v_ext = 0, v_el = 0;
     m->dv.resize(n_vecs);
@@ -449,6 +449,24 @@ extern "C" int shifter_global_threshold(shifter_ctx* ctx, const shifter_model* m
             HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
             uint32_t status;
             memcpy(&status, st, sizeof status);
+            if ((status & 1u) && getenv("SHIFTER_DEBUG")) {
+                MultiState dbg;
+                std::vector<uint32_t> cnts((MAXK + 2) * SPEC_SUB * 32);
+                (void)hipMemcpy(&dbg, model->b.multi, sizeof dbg, hipMemcpyDeviceToHost);
+                (void)hipMemcpy(cnts.data(), model->b.multi_cnt, cnts.size() * 4, hipMemcpyDeviceToHost);
+                uint64_t cand = 0, maxsb = 0;
+                for (uint32_t sb = 0; sb < SPEC_SUB; ++sb) { cand += cnts[sb * 32]; maxsb = std::max<uint64_t>(maxsb, cnts[sb * 32]); }
+                fprintf(stderr, "multi failed: status %u k %u m %u cand %llu max/sb %llu cap/sb %u\n", dbg.status, dbg.k,
+                        dbg.m_valid, (unsigned long long)cand, (unsigned long long)maxsb, model->b.cand_cap_sb);
+                for (uint32_t k = 0; k < dbg.k; ++k) {
+                    uint64_t below = 0;
+                    for (uint32_t j = 0; j <= k; ++j)
+                        for (uint32_t sb = 0; sb < SPEC_SUB; ++sb) below += cnts[((1 + j) * SPEC_SUB + sb) * 32];
+                    fprintf(stderr, "  k %u p %llu lo %08x hi %08x sh %u below %llu bin %u bin_cnt %u r2 %llu\n", k,
+                            (unsigned long long)dbg.p[k], dbg.lo[k], dbg.hi[k], dbg.sh[k], (unsigned long long)below,
+                            dbg.bin[k], dbg.bin_cnt[k], (unsigned long long)dbg.r2[k]);
+                }
+            }
             if (status & 2u)
                 return fail(ctx, SHIFTER_ERR_NONFINITE, "global_threshold: NaN among the prunable weights");
             ctx->last_path = (status & 1u) ? 2 : 1;

@@ -18,6 +18,8 @@
 // The result is exact whenever step 4's check holds; otherwise (a sample that misled,
 // an interval with too many ties, a full buffer) a status bit is raised and the host
 // runs the multi-pass radix select instead.
+#include <algorithm>
+
 #include "dev_common.h"
 
 namespace shifter {
@@ -60,10 +62,18 @@ __global__ __launch_bounds__(BLOCK) void spec_init_kernel(SpecState* ss, uint32_
     }
 }
 
-// One wavefront per sampled tile: lanes 0..31 read line l0, lanes 32..63 line l0 + 64
-// of the tile's 128 lines of 32 floats; l0 rotates with the tile index.  The samples go
-// to a per-block LDS histogram first: a global atomic costs about 11 ns per lane on one
-// address, and the bins around the mode of the weight distribution are hot.
+// The sample: from every quarter (1024 weights) of every sample_tile_stride-th tile one
+// 64-byte sector of 16 weights, at a position that rotates with the tile and the quarter.
+// Every filter of 1024 or more weights is thus sampled in proportion to its size - the
+// sample is stratified by filter, which matters because filters differ in scale by
+// orders of magnitude and a sample clustered on few filters misjudges the quantiles.
+// A wavefront takes four tiles per step (16 lanes per tile, 4 lanes per sector, one
+// float4 each).  The samples go to a per-block LDS histogram first: a global atomic
+// costs about 11 ns per lane on one address, and the bins around the mode are hot.
+__host__ __device__ __forceinline__ uint32_t sample_sector(uint32_t tile, uint32_t quarter) {
+    return (tile * 37u + quarter * 11u) & 63u;
+}
+
 __global__ __launch_bounds__(BLOCK) void spec_sample_kernel(
     const DevTensor* __restrict__ tens, const uint32_t* __restrict__ tile_prefix,
     uint32_t n_t, uint32_t n_tiles, uint32_t tile_stride, const float* __restrict__ w,
@@ -74,15 +84,28 @@ __global__ __launch_bounds__(BLOCK) void spec_sample_kernel(
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = blockIdx.x * (BLOCK / 64) + (threadIdx.x >> 6);
     const uint32_t n_waves = gridDim.x * (BLOCK / 64);
-    for (uint32_t s = wave; (uint64_t)s * tile_stride < n_tiles; s += n_waves) {
-        const uint32_t tile = s * tile_stride;
+    const uint32_t quarter = (lane >> 2) & 3u, part = lane & 3u;
+    for (uint64_t s = (uint64_t)wave * 4 + (lane >> 4); s * tile_stride < n_tiles;
+         s += (uint64_t)n_waves * 4) {
+        const uint32_t tile = (uint32_t)(s * tile_stride);
         const uint32_t t = find_tensor(tile_prefix, n_t, tile);
         if (!tens[t].prunable) continue;
         const uint32_t e0 = (tile - tile_prefix[t]) * TILE;
         const uint32_t n = min(TILE, tens[t].numel - e0);
-        const uint32_t l0 = (tile * 37u) & 63u;
-        const uint32_t j = (l0 + (lane >> 5) * 64u) * 32u + (lane & 31u);
-        if (j < n) atomicAdd(&h[key_of(w[tens[t].offset + e0 + j]) >> SAMPLE_SHIFT], 1u);
+        const uint32_t j = quarter * 1024u + sample_sector(tile, quarter) * 16u + part * 4u;
+        if (j + 3 < n) {
+            const float* p = w + tens[t].offset + e0 + j;
+            float4 x;
+            if ((reinterpret_cast<uintptr_t>(p) & 15u) == 0) {
+                x = *reinterpret_cast<const float4*>(p);
+            } else {
+                x.x = p[0]; x.y = p[1]; x.z = p[2]; x.w = p[3];
+            }
+            atomicAdd(&h[key_of(x.x) >> SAMPLE_SHIFT], 1u);
+            atomicAdd(&h[key_of(x.y) >> SAMPLE_SHIFT], 1u);
+            atomicAdd(&h[key_of(x.z) >> SAMPLE_SHIFT], 1u);
+            atomicAdd(&h[key_of(x.w) >> SAMPLE_SHIFT], 1u);
+        }
     }
     __syncthreads();
     for (uint32_t i = threadIdx.x; i < SBINS; i += BLOCK) {
@@ -617,7 +640,7 @@ __global__ __launch_bounds__(BLOCK) void spec_fixup_kernel(
 void launch_spec_sample(shifter_ctx* ctx, const shifter_model* m, const float* d_w) {
     const auto& b = m->b;
     const uint32_t sampled = (m->n_tiles + m->sample_tile_stride - 1) / m->sample_tile_stride;
-    const uint32_t grid = min(256u, (sampled + BLOCK / 64 - 1) / (BLOCK / 64));
+    const uint32_t grid = std::min(512u, (sampled + 15) / 16);   // 16 tiles per block and step
     spec_sample_kernel<<<grid, BLOCK, 0, ctx->stream>>>(b.tens, b.tile_prefix, (uint32_t)m->t.size(),
                                                         m->n_tiles, m->sample_tile_stride, d_w,
                                                         b.shist);
