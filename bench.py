@@ -108,7 +108,7 @@ def main():
         # a portfolio: one ranking call for all counts, then one batched call per step
         _, out = pl.portfolio(n_prune, 0, with_in_alive=True, sync=True)
         if collect is not None:
-            collect.extend(out[3])
+            collect.extend(int(x) for x in out[3])
 
     # set-up: the HIP runtime finishes some one-time work (staging for device-to-host
     # copies among it) only after a few calls; keep that out of warm-up and timing

@@ -221,8 +221,8 @@ extern "C" int shifter_model_create(const shifter_tensor_desc* tensors, uint32_t
     m->n_ranked = (uint32_t)m->ranked_ids.size();
     // the single-pass selection samples one 16-weight sector per 1024 weights of every
     // sample_tile_stride-th tile (see spec_sample_kernel); its size is fixed by the
-    // descriptors.  About N / 64 samples, at most ~8 M.
-    m->sample_tile_stride = m->n_tiles > 131072u ? m->n_tiles / 131072u : 1u;
+    // descriptors.  N / 64 samples for models up to 164 M weights, at most 2.6 M beyond.
+    m->sample_tile_stride = (m->n_tiles + 39999u) / 40000u;   // 1 up to 164 M weights
     for (uint32_t tile = 0, ti = 0; tile < m->n_tiles; tile += m->sample_tile_stride) {
         while (m->tile_prefix[ti + 1] <= tile) ++ti;
         if (!tensors[ti].prunable) continue;

@@ -151,7 +151,9 @@ __global__ __launch_bounds__(BLOCK) void ms_pass_kernel(
     const float* __restrict__ w, MultiState* ms, uint32_t* cnt, uint2* __restrict__ cand,
     uint32_t cap_sb) {
     __shared__ uint32_t s_lo[MAXK + 1], s_hi[MAXK + 1];
-    __shared__ uint32_t s_cnt[MAXK + 1];
+    // counts per j: one private column per thread (no conflicts, no atomics), summed at
+    // the end; rows 0 .. k_var
+    __shared__ uint32_t s_col[(SPEC_MULTI_MAXK + 1) * BLOCK];
     __shared__ uint32_t s_nan, s_base, s_wtot[BLOCK / 64];
     const uint32_t tile = blockIdx.x;
     const uint32_t t = find_tensor(tile_prefix, n_t, tile);
@@ -163,11 +165,12 @@ __global__ __launch_bounds__(BLOCK) void ms_pass_kernel(
     const uint32_t lane = threadIdx.x & 63u, wid = threadIdx.x >> 6;
     const uint32_t sb = blockIdx.x & (SPEC_SUB - 1);
     uint2* my_cand = cand + (size_t)sb * cap_sb;
+    const uint32_t k_var = ms->k;
     if (threadIdx.x <= MAXK) {
         s_lo[threadIdx.x] = threadIdx.x < MAXK ? ms->lo[threadIdx.x] : 0xffffffffu;
         s_hi[threadIdx.x] = threadIdx.x < MAXK ? ms->hi[threadIdx.x] : 0xffffffffu;
-        s_cnt[threadIdx.x] = 0;
     }
+    for (uint32_t j = 0; j <= k_var; ++j) s_col[j * BLOCK + threadIdx.x] = 0;
     if (threadIdx.x == 0) { s_nan = 0; s_base = 0; }
     __syncthreads();
 
@@ -182,18 +185,7 @@ __global__ __launch_bounds__(BLOCK) void ms_pass_kernel(
             if (s_lo[j + step - 1] <= key) j += step;
         j += s_lo[j] <= key ? 1u : 0u;          // j in [0, MAXK]; s_lo[MAXK] is padding
         const bool is_cand = j >= 1 && key <= s_hi[j - 1];
-        // count j: lanes with equal j add once per wavefront
-        bool pending = true;
-        while (__ballot(pending)) {
-            if (pending) {
-                const uint32_t jj = __builtin_amdgcn_readfirstlane(j);
-                const bool same = j == jj;
-                const unsigned long long msk = __ballot(same);
-                if (lane == (uint32_t)__ffsll((long long)msk) - 1u)
-                    atomicAdd(&s_cnt[jj], (uint32_t)__popcll(msk));
-                if (same) pending = false;
-            }
-        }
+        s_col[j * BLOCK + threadIdx.x] += 1;    // j <= k_var <= SPEC_MULTI_MAXK
         return is_cand;
     };
 
@@ -259,10 +251,12 @@ __global__ __launch_bounds__(BLOCK) void ms_pass_kernel(
     for (uint32_t d = 32; d > 0; d >>= 1) nan |= __shfl_down(nan, d, 64);
     if (lane == 0 && nan) s_nan = 1;
     __syncthreads();
-    const uint32_t k_var = ms->k;
-    if (threadIdx.x <= k_var) {
-        const uint32_t c = s_cnt[threadIdx.x];
-        if (c) atomicAdd(mcnt(cnt, MC_BELOW + threadIdx.x, sb), c);
+    // column sums: four threads per j, a quarter of the columns each
+    if (threadIdx.x < 4 * (k_var + 1)) {
+        const uint32_t j = threadIdx.x >> 2, q = threadIdx.x & 3u;
+        uint32_t c = 0;
+        for (uint32_t i = 0; i < BLOCK / 4; ++i) c += s_col[j * BLOCK + ((i * 4 + q + j) & (BLOCK - 1))];
+        if (c) atomicAdd(mcnt(cnt, MC_BELOW + j, sb), c);
     }
     if (threadIdx.x == 0 && s_nan) atomicOr(&ms->status, 2u);
 }

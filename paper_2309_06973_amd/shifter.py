@@ -314,8 +314,8 @@ def shifter_propagate_groups_batch(ctx: Context, model: Model, d_out_alive, k: i
 def shifter_compact_batch(ctx: Context, model: Model, d_w_sparse, w_stride: int, d_vecs, d_keep,
                           d_new_width, k: int, d_w_out, cap_w: int, d_vecs_out, cap_v: int,
                           sync: bool = True):
-    """When sync: (status, K lists of tensor descs, K lists of vec descs, elems_w[K],
-    elems_v[K])."""
+    """When sync: (status, tensor descs, vec descs, elems_w, elems_v) as flat ctypes arrays
+    (variant k's tensor i at [k * n_tensors + i], vector i at [k * n_vecs + i])."""
     if not sync:
         _check(load_library().shifter_compact_batch(
             ctx.handle, model.handle, _ptr(d_w_sparse), w_stride, _ptr(d_vecs), _ptr(d_keep),
@@ -331,9 +331,7 @@ def shifter_compact_batch(ctx: Context, model: Model, d_w_sparse, w_stride: int,
         ctx.handle, model.handle, _ptr(d_w_sparse), w_stride, _ptr(d_vecs), _ptr(d_keep),
         _ptr(d_new_width), k, _ptr(d_w_out), cap_w, _ptr(d_vecs_out), cap_v, ot, ov, ew, ev),
         ctx.handle, allow=(SHIFTER_WARN_COLLAPSE,))
-    ot, ov = list(ot), list(ov)
-    return (rc, [ot[i * n_t:(i + 1) * n_t] for i in range(k)],
-            [ov[i * n_v:(i + 1) * n_v] for i in range(k)], list(ew), list(ev))
+    return rc, ot, ov, ew, ev
 
 
 def shifter_profile_enable(ctx: Context, on: bool) -> None:

@@ -337,9 +337,12 @@ def check_batch(spec, w, v, n_prune, flags=0, check=None, with_in_alive=True):
             vc = pl.b_vecs_out[k * pl.cap_v:k * pl.cap_v + evs[k]].cpu().numpy()
             assert np.array_equal(bits(wc), bits(ref.compacted.w)), lab + " compacted w"
             assert np.array_equal(bits(vc), bits(ref.compacted.v)), lab + " compacted v"
-            for d, (off, o2, i2, kh, kw) in zip(ots[k], ref.compacted.tensor_shapes):
+            n_t, n_v = info.n_tensors, info.n_vecs
+            for i, (off, o2, i2, kh, kw) in enumerate(ref.compacted.tensor_shapes):
+                d = ots[k * n_t + i]
                 assert (d.offset, d.out_ch, d.in_ch, d.kh, d.kw) == (off, o2, i2, kh, kw)
-            for d, (off, ln) in zip(ovs[k], ref.compacted.vec_shapes):
+            for i, (off, ln) in enumerate(ref.compacted.vec_shapes):
+                d = ovs[k * n_v + i]
                 assert (d.offset, d.len) == (off, ln)
     finally:
         pl.close()
