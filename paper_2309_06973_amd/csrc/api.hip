@@ -14,7 +14,7 @@ namespace shifter {
 const char* const kKernelNames[K_COUNT] = {
     "sel_init", "hist_round0", "hist_round1", "hist_round2", "select", "tie_count",
     "tie_final", "zero_flags", "mask_scan", "scan", "propagate", "plan", "gather",
-    "gather_vec", "copy", "mask_scan_batch", "expand_levels", "spec_init", "spec_sample", "spec_predict", "spec_pass",
+    "copy", "mask_scan_batch", "expand_levels", "spec_init", "spec_sample", "spec_predict", "spec_pass",
     "spec_hist_locate", "spec_filter_rank", "spec_fixup"};
 
 ProfileScope::ProfileScope(shifter_ctx* c, int id) : ctx(c), idx(-1) {
@@ -216,6 +216,9 @@ extern "C" int shifter_model_create(const shifter_tensor_desc* tensors, uint32_t
     }
     m->tile_prefix.push_back((uint32_t)tiles);
     m->n_tiles = (uint32_t)tiles;
+    std::sort(spans.begin(), spans.end());
+    for (size_t i = 1; i < spans.size(); ++i)
+        if (spans[i].first < spans[i - 1].second) return bad("tensors overlap in the weight arena", (uint32_t)i);
     for (uint32_t i = 0; i < n_tensors; ++i)
         if (tensors[i].prunable) m->ranked_ids.push_back(i);
     m->n_ranked = (uint32_t)m->ranked_ids.size();
@@ -449,24 +452,6 @@ extern "C" int shifter_global_threshold(shifter_ctx* ctx, const shifter_model* m
             HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
             uint32_t status;
             memcpy(&status, st, sizeof status);
-            if ((status & 1u) && getenv("SHIFTER_DEBUG")) {
-                MultiState dbg;
-                std::vector<uint32_t> cnts((MAXK + 2) * SPEC_SUB * 32);
-                (void)hipMemcpy(&dbg, model->b.multi, sizeof dbg, hipMemcpyDeviceToHost);
-                (void)hipMemcpy(cnts.data(), model->b.multi_cnt, cnts.size() * 4, hipMemcpyDeviceToHost);
-                uint64_t cand = 0, maxsb = 0;
-                for (uint32_t sb = 0; sb < SPEC_SUB; ++sb) { cand += cnts[sb * 32]; maxsb = std::max<uint64_t>(maxsb, cnts[sb * 32]); }
-                fprintf(stderr, "multi failed: status %u k %u m %u cand %llu max/sb %llu cap/sb %u\n", dbg.status, dbg.k,
-                        dbg.m_valid, (unsigned long long)cand, (unsigned long long)maxsb, model->b.cand_cap_sb);
-                for (uint32_t k = 0; k < dbg.k; ++k) {
-                    uint64_t below = 0;
-                    for (uint32_t j = 0; j <= k; ++j)
-                        for (uint32_t sb = 0; sb < SPEC_SUB; ++sb) below += cnts[((1 + j) * SPEC_SUB + sb) * 32];
-                    fprintf(stderr, "  k %u p %llu lo %08x hi %08x sh %u below %llu bin %u bin_cnt %u r2 %llu\n", k,
-                            (unsigned long long)dbg.p[k], dbg.lo[k], dbg.hi[k], dbg.sh[k], (unsigned long long)below,
-                            dbg.bin[k], dbg.bin_cnt[k], (unsigned long long)dbg.r2[k]);
-                }
-            }
             if (status & 2u)
                 return fail(ctx, SHIFTER_ERR_NONFINITE, "global_threshold: NaN among the prunable weights");
             ctx->last_path = (status & 1u) ? 2 : 1;

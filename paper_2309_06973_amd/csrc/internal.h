@@ -99,7 +99,7 @@ struct MultiState {
     uint64_t r2[MAXK], less[MAXK];
     uint32_t perm[MAXK];   // original position of sorted rank k
     uint32_t lo[MAXK], hi[MAXK], sh[MAXK];
-    uint32_t bin[MAXK], bin_cnt[MAXK], seg_over[MAXK];
+    uint32_t bin[MAXK], bin_cnt[MAXK];
     uint32_t k, m_valid, status, pad;
 };
 struct MultiPerm {
@@ -134,7 +134,7 @@ struct PlanHeader {
 
 enum KernelId {
     K_SEL_INIT = 0, K_HIST0, K_HIST1, K_HIST2, K_SELECT, K_TIE_COUNT, K_TIE_FINAL,
-    K_ZERO_FLAGS, K_MASK_SCAN, K_SCAN, K_PROPAGATE, K_PLAN, K_GATHER, K_GATHER_VEC,
+    K_ZERO_FLAGS, K_MASK_SCAN, K_SCAN, K_PROPAGATE, K_PLAN, K_GATHER,
     K_COPY, K_MASK_SCAN_BATCH, K_EXPAND_LEVELS, K_SPEC_INIT, K_SPEC_SAMPLE, K_SPEC_PREDICT, K_SPEC_PASS, K_SPEC_FINISH, K_SPEC_FINISH2, K_SPEC_FIXUP,
     K_COUNT
 };

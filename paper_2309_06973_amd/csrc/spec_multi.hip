@@ -47,7 +47,6 @@ __global__ __launch_bounds__(BLOCK) void ms_init_kernel(MultiState* ms, uint32_t
         ms->bin_cnt[tid] = 0;
         ms->r2[tid] = 0;
         ms->less[tid] = 0;
-        ms->seg_over[tid] = 0;
     }
     if (tid < MAXK && ((zero_mask >> tid) & 1ull)) {
         shifter_threshold out;
