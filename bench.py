@@ -1,14 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the prune-and-compact pass on one MI355X.
 
-A step is one pass of the whole hot path over one synthetic network: one ranking call
-for all K prune counts of the workload, then per variant: threshold-and-mask fused with
-the zero-channel scan, the group plan, and the gather rebuild.  Inputs are resident in
-HBM before the timed region starts.  Prints ONE JSON line.
+A step is one pass of the whole hot path over one synthetic network: the ranking for all
+K prune counts of the workload, the threshold-and-mask pass fused with the zero-channel
+scan, the group plan, and the gather rebuild of every variant.  Inputs are resident in
+HBM before the timed region starts.  Prints ONE JSON line: the headline workload on top,
+the other full-size workloads of the target under "other_workloads".
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5|c5p|c4|c2|c3|c1]
+                  [--others c4,c5p | --others none] [--no-cpu-baseline]
 """
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -29,12 +32,51 @@ WORKLOADS = {
     "c1": (1, None, "tiny CNN (N=24,112), s=0.9"),
 }
 
+_generated = {}
+
+
+def generated(c):
+    from paper_2309_06973_amd import synth
+    if c not in _generated:
+        _generated.clear()          # one large arena on the host at a time
+        _generated[c] = synth.generate_config(c)
+    return _generated[c]
+
+
+def kernel_source_digest():
+    """Digest of the kernel sources: measured counter figures are only quoted while the
+    kernels are the ones they were taken on."""
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2309_06973_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".h")):
+            with open(os.path.join(d, name), "rb") as f:
+                h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
+
+
+def recorded_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed counter summary of `workload`
+    (FETCH_SIZE and WRITE_SIZE, calibrated on the copy kernel), or None when there is no
+    summary or the kernel sources have changed since it was taken."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_hbm_counters.txt")
+    if not os.path.exists(path):
+        return None
+    digest, value = None, None
+    with open(path) as f:
+        for line in f:
+            parts = line.split()
+            if len(parts) == 2 and parts[0] == "kernel_source_digest:":
+                digest = parts[1]
+            if len(parts) == 3 and parts[0] == "traffic_bytes_per_launch:" and parts[1] == kernel:
+                value = int(parts[2])
+    return value if digest == kernel_source_digest() else None
+
 
 def cpu_baseline_sample(spec, w, v, sparsity):
     """The oracle, as it stands, on a bounded sample of the workload: the leading layers
     of the network up to ~40 M weights (same values), one variant."""
     import copy
-    import numpy as np
     from oracle import shifter_oracle as O
     from paper_2309_06973_amd import synth
     n_t, tot = 0, 0
@@ -60,34 +102,15 @@ def cpu_baseline_sample(spec, w, v, sparsity):
                       f"{1.0 / dt:.4f} variants/s"}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c5", choices=sorted(WORKLOADS))
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only; --gpus must be 1 (the pass "
-              "shards by variant or by arena range, see DESIGN.md, but no multi-GPU path "
-              "is built)", file=sys.stderr)
-        sys.exit(2)
-
+def measure(name, steps, warmup):
+    """Times `steps` steps of one workload; returns the fields of its report."""
     import torch
     from paper_2309_06973_amd import shifter as S
     from paper_2309_06973_amd import synth
     from paper_2309_06973_amd.pipeline import Pipeline
 
-    if not torch.cuda.is_available():
-        print("bench.py: no ROCm device visible", file=sys.stderr)
-        sys.exit(1)
-    if not os.path.exists(S._LIB_PATH):
-        import __graft_entry__
-        __graft_entry__.build()
-
-    c, sparsities, desc = WORKLOADS[args.workload]
-    spec, w, v = synth.generate_config(c)
+    c, sparsities, desc = WORKLOADS[name]
+    spec, w, v = generated(c)
     sparsities = sparsities or synth.config_sparsities(c)
     n = spec.n_prunable
     n_prune = [synth.prune_count(n, s) for s in sparsities]
@@ -117,31 +140,31 @@ def main():
         step()
     # warm-up; the first one also records the (deterministic) compacted sizes
     step(kept)
-    for _ in range(max(args.warmup - 1, 0)):
+    for _ in range(max(warmup - 1, 0)):
         step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
+    ms_per_step = dt / steps * 1e3
 
     # algorithmic bytes of one step: ranking reads the arena once per portfolio (4N);
     # each variant reads 4N, writes 4N sparse + N mask, and moves 4N' in and 4N' out
     b_alg = 4 * n + sum(9 * n + 8 * n2 for n2 in kept)
-    gbs = b_alg / (dt / args.steps) / 1e9
+    gbs = b_alg / (dt / steps) / 1e9
 
-    # dominant kernel (threshold-and-mask + scan): HIP events around each launch, on the
-    # stream the kernels run on, over a second timed run of the same steps
+    # dominant kernel: HIP events around each launch, on the stream the kernels run on,
+    # over a second timed run of the same steps
     S.shifter_profile_enable(pl.ctx, True)
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     prof = S.shifter_profile_read(pl.ctx)
     S.shifter_profile_enable(pl.ctx, False)
-    # the kernel that reads the arena and writes the sparse arena and the mask: it must move
-    # 4N + 4N + N bytes whether or not the ranking is fused into it
-    # (the batched kernel reads the arena once and writes K sparse arenas and K masks)
+    # the kernel that reads the arena and writes the sparse arena and the mask: it must
+    # move 4N + 4N + N bytes whether or not the ranking is fused into it; the batched
+    # kernel reads the arena once and writes K sparse arenas and K masks
     if k_var == 1:
         dom = "spec_pass" if "spec_pass" in prof else "mask_scan"
         dom_bytes = 9 * n
@@ -150,10 +173,10 @@ def main():
     cnt, tot_ms = prof[dom]
     avg_ms = tot_ms / cnt
     achieved = dom_bytes / (avg_ms * 1e-3) / 1e9
-    kernels = {name: {"launches_per_step": c_ // args.steps,
-                      "avg_us": round(ms / c_ * 1e3, 2),
-                      "us_per_step": round(ms / args.steps * 1e3, 2)}
-               for name, (c_, ms) in sorted(prof.items(), key=lambda kv: -kv[1][1])}
+    kernels = {kn: {"launches_per_step": c_ // steps,
+                    "avg_us": round(ms / c_ * 1e3, 2),
+                    "us_per_step": round(ms / steps * 1e3, 2)}
+               for kn, (c_, ms) in sorted(prof.items(), key=lambda kv: -kv[1][1])}
 
     # plain copy kernel of the same arena: the bandwidth this chip sustains for a
     # read-once / write-once stream, and the known-size dispatch the memory-traffic
@@ -166,26 +189,19 @@ def main():
     copy_gbs = 8 * n / (c_ms / c_cnt * 1e-3) / 1e9
 
     out = {
-        "metric": "prune+compact GB/s and % of HBM peak; variants/sec per portfolio",
         "value": round(gbs, 2),
         "unit": "GB/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "u32",
-        "data": "synthetic",
+        "steps": steps,
         "config": {"workload": desc, "variants_per_step": k_var,
                    "sparsities": [round(s, 5) for s in sparsities],
                    "kept_weights": kept, "algorithmic_bytes_per_step": b_alg},
         "pct_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
-        "variants_per_s": round(k_var / (dt / args.steps), 2),
+        "variants_per_s": round(k_var / (dt / steps), 2),
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": recorded_traffic(name, dom),
                      "bytes_per_launch": dom_bytes, "avg_launch_ms": round(avg_ms, 5)},
         "selection": S.shifter_get_select_stats(pl.ctx),
         "copy_kernel": {"bytes_per_launch": 8 * n, "gbs": round(copy_gbs, 1),
@@ -195,8 +211,75 @@ def main():
     pl.close()
     del pl
     torch.cuda.empty_cache()
+    return out, (spec, w, v, sparsities)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c5", choices=sorted(WORKLOADS))
+    ap.add_argument("--others", default=None,
+                    help="comma-separated workloads also measured (default: c5p,c4 with "
+                         "the default workload, none otherwise)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1 (the pass "
+              "shards by variant or by arena range, but no multi-GPU path is built)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2309_06973_amd import shifter as S
+
+    if not torch.cuda.is_available():
+        print("bench.py: no ROCm device visible", file=sys.stderr)
+        sys.exit(1)
+    if not os.path.exists(S._LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+
+    if args.others is None:
+        others = ["c5p", "c4"] if args.workload == "c5" else []
+    else:
+        others = [o for o in args.others.split(",") if o and o != "none"]
+    for o in others:
+        if o not in WORKLOADS:
+            ap.error(f"unknown workload {o!r}")
+
+    main_out, (spec, w, v, sparsities) = measure(args.workload, args.steps, args.warmup)
+    cpu = None
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline_sample(spec, w, v, sparsities[-1])
+        cpu = cpu_baseline_sample(spec, w, v, sparsities[-1])
+    del spec, w, v
+
+    out = {
+        "metric": "prune+compact GB/s and % of HBM peak; variants/sec per portfolio",
+        "value": main_out.pop("value"),
+        "unit": main_out.pop("unit"),
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": main_out.pop("ms_per_step"),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32",
+        "data": "synthetic",
+    }
+    main_out.pop("steps")
+    out.update(main_out)
+    if cpu is not None:
+        out["cpu_baseline"] = cpu
+    if others:
+        # same measurement, same fields, for the other full-size workloads; keyed by name,
+        # sorted so that workloads sharing an arena are generated once
+        out["other_workloads"] = {}
+        for o in sorted(others, key=lambda o: (WORKLOADS[o][0] != WORKLOADS[args.workload][0], o)):
+            res, _ = measure(o, args.steps, args.warmup)
+            out["other_workloads"][o] = res
     print(json.dumps(out))
 
 

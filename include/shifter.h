@@ -292,7 +292,13 @@ int shifter_compact(shifter_ctx* ctx, const shifter_model* model, const float* d
  *   d_vecs_out   K vector arenas cap_v floats apart
  *   h_out_tensors K * n_tensors, h_out_vecs K * n_vecs, h_elems_w / h_elems_v K entries,
  *   each or NULL; any non-NULL makes the call wait.  SHIFTER_ERR_CAPACITY if any variant
- *   does not fit (that variant is not gathered), SHIFTER_WARN_COLLAPSE if any collapsed. */
+ *   does not fit (that variant is not gathered), SHIFTER_WARN_COLLAPSE if any collapsed.
+ * shifter_compact_batch_masked
+ *   the same rebuild with the dense arena d_w and the K threshold records d_thr as its
+ *   source: variant k's mask (removed <=> composite < d_thr[k].cut, prunable tensors
+ *   only) is applied while its weights are gathered, so the K rebuilds share one source
+ *   and the K sparse arenas are not read again.  Outputs are identical to
+ *   shifter_compact_batch on the arenas shifter_apply_mask_batch wrote for d_thr. */
 int shifter_apply_mask_batch(shifter_ctx* ctx, const shifter_model* model, const float* d_w,
                              const shifter_threshold* d_thr, uint32_t K, float* d_w_out,
                              uint64_t w_stride, uint8_t* d_mask, uint64_t mask_stride,
@@ -308,6 +314,13 @@ int shifter_compact_batch(shifter_ctx* ctx, const shifter_model* model, const fl
                           uint64_t cap_w, float* d_vecs_out, uint64_t cap_v,
                           shifter_tensor_desc* h_out_tensors, shifter_vec_desc* h_out_vecs,
                           uint64_t* h_elems_w, uint64_t* h_elems_v);
+int shifter_compact_batch_masked(shifter_ctx* ctx, const shifter_model* model, const float* d_w,
+                                 const shifter_threshold* d_thr, const float* d_vecs,
+                                 const uint32_t* d_keep, const uint32_t* d_new_width,
+                                 uint32_t K, float* d_w_out, uint64_t cap_w, float* d_vecs_out,
+                                 uint64_t cap_v, shifter_tensor_desc* h_out_tensors,
+                                 shifter_vec_desc* h_out_vecs, uint64_t* h_elems_w,
+                                 uint64_t* h_elems_v);
 
 /* --- measurement ------------------------------------------------------------------- */
 

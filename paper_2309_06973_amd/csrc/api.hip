@@ -82,7 +82,7 @@ static void unbind(shifter_model* m) {
     if (!b.ctx) return;
     (void)hipSetDevice(b.device);
     void* ptrs[] = {b.tens, b.groups, b.vecs, b.producers, b.tile_prefix, b.sel, b.ghist,
-                    b.tile_cnt, b.plan_t, b.plan_v, b.plan_h, b.out_tile_prefix, b.levels, b.spec, b.shist,
+                    b.tile_cnt, b.plan_t, b.plan_v, b.plan_h, b.out_tile_prefix, b.band_prefix, b.levels, b.spec, b.shist,
                     b.spec_cnt, b.partial, b.cand, b.list, b.ranked_ids, b.multi, b.multi_cnt,
                     b.multi_partial, b.multi_seg, b.multi_seg_cnt};
     for (void* p : ptrs)
@@ -185,7 +185,6 @@ extern "C" int shifter_model_create(const shifter_tensor_desc* tensors, uint32_t
         d.magic_in = magic_for(d.in_ch);
         d.magic_kk = d.shift_kk = 0;
         if (d.kk >= 2) magic_u32(d.kk, &d.magic_kk, &d.shift_kk);
-        d.pad2[0] = d.pad2[1] = 0;
         {
             // work units of the gather when nothing is removed (see plan_kernel)
             const uint32_t chunks = (d.row_len + GATHER_CHUNK - 1) / GATHER_CHUNK;
@@ -194,13 +193,24 @@ extern "C" int shifter_model_create(const shifter_tensor_desc* tensors, uint32_t
             const uint32_t rows_par = GATHER_CHUNK >> lg;
             const uint32_t rb = 4u * std::max(rows_par, 4u);
             m->gather_units_bound += chunks * ((t.out_ch + rb - 1) / rb);
+            // portfolio rebuild in source order: bands of filters times rectangles of
+            // about GATHER_CHUNK columns, in whole channels (see gather_band_kernel)
+            d.band_rows = std::min(64u, 2 * rb);
+            if (d.kk > GATHER_CHUNK) m->band_ok = false;
+            d.chunk_ch = d.row_len <= GATHER_CHUNK / 2 ? d.cin : std::max(1u, GATHER_CHUNK / d.kk);
+            d.src_chunks = (d.cin + d.chunk_ch - 1) / d.chunk_ch;
+            const uint64_t bands = (t.out_ch + d.band_rows - 1) / d.band_rows;
+            const uint64_t bu = (bands + 7) / 8 * d.src_chunks;
+            if (m->band_prefix.empty()) m->band_prefix.push_back(0);
+            if ((m->band_prefix.back() + bu) * 8 * (MAXK / 4) >= (1ull << 31))
+                return bad("model too large for 32-bit gather unit indices", i);
+            m->band_prefix.push_back(m->band_prefix.back() + (uint32_t)bu);
         }
         d.out_group = t.out_group;
         d.in_group = t.in_group;
         d.out_flag_off = (uint32_t)so;
         d.in_flag_off = (uint32_t)si;
         d.prunable = t.prunable ? 1u : 0u;
-        d.pad = 0;
         m->out_flag_off.push_back(so);
         m->in_flag_off.push_back(si);
         m->tile_prefix.push_back((uint32_t)tiles);
@@ -216,6 +226,7 @@ extern "C" int shifter_model_create(const shifter_tensor_desc* tensors, uint32_t
     }
     m->tile_prefix.push_back((uint32_t)tiles);
     m->n_tiles = (uint32_t)tiles;
+    if (m->band_prefix.empty()) m->band_prefix.push_back(0);
     std::sort(spans.begin(), spans.end());
     for (size_t i = 1; i < spans.size(); ++i)
         if (spans[i].first < spans[i - 1].second) return bad("tensors overlap in the weight arena", (uint32_t)i);
@@ -327,6 +338,7 @@ static int bind(shifter_ctx* ctx, const shifter_model* cm) {
     if ((rc = upload(ctx, &b.vecs, m->dv.data(), n_v))) return rc;
     if ((rc = upload(ctx, &b.producers, m->producers.data(), m->producers.size()))) return rc;
     if ((rc = upload(ctx, &b.tile_prefix, m->tile_prefix.data(), m->tile_prefix.size()))) return rc;
+    if ((rc = upload(ctx, &b.band_prefix, m->band_prefix.data(), m->band_prefix.size()))) return rc;
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.sel), sizeof(SelState)));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.ghist), sizeof(uint32_t) * MAXK * HIST_BINS));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.tile_cnt),
@@ -641,12 +653,14 @@ extern "C" int shifter_propagate_groups(shifter_ctx* ctx, const shifter_model* m
                                           d_keep, d_new_width, h_new_width);
 }
 
-extern "C" int shifter_compact_batch(shifter_ctx* ctx, const shifter_model* model, const float* d_w_sparse,
-                                     uint64_t w_stride, const float* d_vecs, const uint32_t* d_keep,
-                                     const uint32_t* d_new_width, uint32_t K, float* d_w_out,
-                                     uint64_t cap_w, float* d_vecs_out, uint64_t cap_v,
-                                     shifter_tensor_desc* h_out_tensors, shifter_vec_desc* h_out_vecs,
-                                     uint64_t* h_elems_w, uint64_t* h_elems_v) {
+// d_thr == NULL: d_w holds K sparse arenas w_stride apart; else d_w is the dense arena
+// (w_stride 0) and variant k is masked by d_thr[k] while it is gathered.
+static int compact_impl(shifter_ctx* ctx, const shifter_model* model, const float* d_w_sparse,
+                        uint64_t w_stride, const shifter_threshold* d_thr, const float* d_vecs,
+                        const uint32_t* d_keep, const uint32_t* d_new_width, uint32_t K,
+                        float* d_w_out, uint64_t cap_w, float* d_vecs_out, uint64_t cap_v,
+                        shifter_tensor_desc* h_out_tensors, shifter_vec_desc* h_out_vecs,
+                        uint64_t* h_elems_w, uint64_t* h_elems_v) {
     int rc = enter(ctx, model, "compact");
     if (rc) return rc;
     const size_t n_t = model->t.size(), n_v = model->v.size();
@@ -658,7 +672,7 @@ extern "C" int shifter_compact_batch(shifter_ctx* ctx, const shifter_model* mode
         return fail(ctx, SHIFTER_ERR_INVALID_ARG,
                     "compact: d_w_out must be 16-byte aligned (and cap_w a multiple of 4 in a batch)");
     launch_compact(ctx, model, d_w_sparse, w_stride, d_vecs, d_keep, d_new_width, d_w_out, cap_w,
-                   d_vecs_out, cap_v, K);
+                   d_vecs_out, cap_v, K, d_thr);
     if ((rc = after_launch(ctx, "compact"))) return rc;
     if (h_out_tensors || h_out_vecs || h_elems_w || h_elems_v) {
         const auto& b = model->b;
@@ -701,6 +715,30 @@ extern "C" int shifter_compact_batch(shifter_ctx* ctx, const shifter_model* mode
         }
     }
     return SHIFTER_OK;
+}
+
+extern "C" int shifter_compact_batch(shifter_ctx* ctx, const shifter_model* model, const float* d_w_sparse,
+                                     uint64_t w_stride, const float* d_vecs, const uint32_t* d_keep,
+                                     const uint32_t* d_new_width, uint32_t K, float* d_w_out,
+                                     uint64_t cap_w, float* d_vecs_out, uint64_t cap_v,
+                                     shifter_tensor_desc* h_out_tensors, shifter_vec_desc* h_out_vecs,
+                                     uint64_t* h_elems_w, uint64_t* h_elems_v) {
+    return compact_impl(ctx, model, d_w_sparse, w_stride, nullptr, d_vecs, d_keep, d_new_width, K,
+                        d_w_out, cap_w, d_vecs_out, cap_v, h_out_tensors, h_out_vecs, h_elems_w,
+                        h_elems_v);
+}
+
+extern "C" int shifter_compact_batch_masked(shifter_ctx* ctx, const shifter_model* model, const float* d_w,
+                                            const shifter_threshold* d_thr, const float* d_vecs,
+                                            const uint32_t* d_keep, const uint32_t* d_new_width,
+                                            uint32_t K, float* d_w_out, uint64_t cap_w,
+                                            float* d_vecs_out, uint64_t cap_v,
+                                            shifter_tensor_desc* h_out_tensors,
+                                            shifter_vec_desc* h_out_vecs, uint64_t* h_elems_w,
+                                            uint64_t* h_elems_v) {
+    if (!d_thr) return fail(ctx, SHIFTER_ERR_INVALID_ARG, "compact: d_thr is NULL");
+    return compact_impl(ctx, model, d_w, 0, d_thr, d_vecs, d_keep, d_new_width, K, d_w_out, cap_w,
+                        d_vecs_out, cap_v, h_out_tensors, h_out_vecs, h_elems_w, h_elems_v);
 }
 
 extern "C" int shifter_compact(shifter_ctx* ctx, const shifter_model* model, const float* d_w_sparse,

@@ -35,8 +35,9 @@ struct DevTensor {
     int32_t out_group, in_group;
     uint32_t out_flag_off, in_flag_off;
     uint32_t prunable;
-    uint32_t pad;
-    uint32_t pad2[2];
+    uint32_t band_rows;   // portfolio rebuild: filters per source band (at most 64)
+    uint32_t chunk_ch;    //   in-group channels per source rectangle
+    uint32_t src_chunks;  //   rectangles per band: ceil(cin / chunk_ch)
 };
 
 struct DevGroup {
@@ -159,6 +160,8 @@ struct shifter_model {
     uint32_t sample_tile_stride = 1;     // every how many tiles the selection samples
     uint32_t sample_size = 0;            // weights in that sample
     uint32_t gather_units_bound = 0;     // gather work units when nothing is removed
+    std::vector<uint32_t> band_prefix;   // portfolio rebuild: ceil(bands / 8) * src_chunks per tensor, prefix sums
+    bool band_ok = true;                 // every tensor has kk <= GATHER_CHUNK
 
     // device side, created by the first call that uses the model with a context
     struct Bound {
@@ -176,6 +179,7 @@ struct shifter_model {
         shifter::PlanVec* plan_v = nullptr;
         shifter::PlanHeader* plan_h = nullptr;
         uint32_t* out_tile_prefix = nullptr;  // MAXK * (n_tensors + 1)
+        uint32_t* band_prefix = nullptr;      // n_tensors + 1
         uint32_t* levels = nullptr;           // sum_out_ch + sum_in_ch
         shifter::SpecState* spec = nullptr;
         uint32_t* shist = nullptr;            // 65536 sample bins
@@ -237,7 +241,8 @@ void launch_propagate(shifter_ctx* ctx, const shifter_model* m, const uint8_t* d
 void launch_compact(shifter_ctx* ctx, const shifter_model* m, const float* d_w, uint64_t w_stride,
                     const float* d_vecs, const uint32_t* d_keep,
                     const uint32_t* d_new_width, float* d_w_out, uint64_t cap_w,
-                    float* d_vecs_out, uint64_t cap_v, uint32_t k_var);
+                    float* d_vecs_out, uint64_t cap_v, uint32_t k_var,
+                    const shifter_threshold* d_thr);
 void launch_copy(shifter_ctx* ctx, const float* src, float* dst, uint64_t n);
 
 // Event bracketing for per-kernel timing.

@@ -109,9 +109,11 @@ class Pipeline:
         self.b_vecs_out = torch.empty(k * self.cap_v, **f32)
 
     def portfolio(self, n_prune: Sequence[int], flags: int = 0, with_in_alive: bool = True,
-                  sync: bool = True):
+                  sync: bool = True, from_sparse: bool = False):
         """All five steps for every prune count: one ranking call, then one batched call
-        per step.  Returns (threshold records, compact_batch's tuple)."""
+        per step.  The rebuild reads the dense arena and masks on the way unless
+        from_sparse asks for the K sparse arenas as its source (same result).
+        Returns (threshold records, compact_batch's tuple)."""
         k = len(n_prune)
         assert k == self.bk
         recs = self.global_threshold(n_prune, sync=True)
@@ -121,9 +123,16 @@ class Pipeline:
         S.shifter_propagate_groups_batch(self.ctx, self.model, self.b_out_alive, k, flags,
                                          self.b_group_alive, self.b_index_map, self.b_keep,
                                          self.b_new_width, sync=False)
-        out = S.shifter_compact_batch(self.ctx, self.model, self.b_w_sparse, self.w_stride,
-                                      self.d_vecs, self.b_keep, self.b_new_width, k, self.b_w_out,
-                                      self.cap_w, self.b_vecs_out, self.cap_v, sync=sync)
+        if from_sparse:
+            out = S.shifter_compact_batch(self.ctx, self.model, self.b_w_sparse, self.w_stride,
+                                          self.d_vecs, self.b_keep, self.b_new_width, k,
+                                          self.b_w_out, self.cap_w, self.b_vecs_out, self.cap_v,
+                                          sync=sync)
+        else:
+            out = S.shifter_compact_batch_masked(self.ctx, self.model, self.d_w, self.d_thr,
+                                                 self.d_vecs, self.b_keep, self.b_new_width, k,
+                                                 self.b_w_out, self.cap_w, self.b_vecs_out,
+                                                 self.cap_v, sync=sync)
         return recs, out
 
     def variant(self, k: int = 0, flags: int = 0, fused_scan: bool = True,

@@ -95,6 +95,11 @@ EXPORTS = {
                               C.c_void_p, C.c_uint64, C.POINTER(TensorDesc),
                               C.POINTER(VecDesc), C.POINTER(C.c_uint64),
                               C.POINTER(C.c_uint64)],
+    "shifter_compact_batch_masked": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint64,
+                                     C.c_void_p, C.c_uint64, C.POINTER(TensorDesc),
+                                     C.POINTER(VecDesc), C.POINTER(C.c_uint64),
+                                     C.POINTER(C.c_uint64)],
     "shifter_profile_enable": [C.c_void_p, C.c_int],
     "shifter_profile_read": [C.c_void_p, C.POINTER(C.c_char_p), C.POINTER(C.c_uint32),
                              C.POINTER(C.c_double), C.c_uint32, C.POINTER(C.c_uint32)],
@@ -331,6 +336,28 @@ def shifter_compact_batch(ctx: Context, model: Model, d_w_sparse, w_stride: int,
         ctx.handle, model.handle, _ptr(d_w_sparse), w_stride, _ptr(d_vecs), _ptr(d_keep),
         _ptr(d_new_width), k, _ptr(d_w_out), cap_w, _ptr(d_vecs_out), cap_v, ot, ov, ew, ev),
         ctx.handle, allow=(SHIFTER_WARN_COLLAPSE,))
+    return rc, ot, ov, ew, ev
+
+
+def shifter_compact_batch_masked(ctx: Context, model: Model, d_w, d_thr, d_vecs, d_keep,
+                                 d_new_width, k: int, d_w_out, cap_w: int, d_vecs_out, cap_v: int,
+                                 sync: bool = True):
+    """shifter_compact_batch with the dense arena and the K threshold records as its source;
+    same return value."""
+    fn = load_library().shifter_compact_batch_masked
+    if not sync:
+        _check(fn(ctx.handle, model.handle, _ptr(d_w), _ptr(d_thr), _ptr(d_vecs), _ptr(d_keep),
+                  _ptr(d_new_width), k, _ptr(d_w_out), cap_w, _ptr(d_vecs_out), cap_v, None,
+                  None, None, None), ctx.handle)
+        return SHIFTER_OK, None, None, None, None
+    n_t, n_v = model.info.n_tensors, model.info.n_vecs
+    ot = (TensorDesc * (n_t * k))()
+    ov = (VecDesc * max(n_v * k, 1))()
+    ew = (C.c_uint64 * k)()
+    ev = (C.c_uint64 * k)()
+    rc = _check(fn(ctx.handle, model.handle, _ptr(d_w), _ptr(d_thr), _ptr(d_vecs), _ptr(d_keep),
+                   _ptr(d_new_width), k, _ptr(d_w_out), cap_w, _ptr(d_vecs_out), cap_v, ot, ov,
+                   ew, ev), ctx.handle, allow=(SHIFTER_WARN_COLLAPSE,))
     return rc, ot, ov, ew, ev
 
 

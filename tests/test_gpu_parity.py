@@ -300,52 +300,63 @@ def check_batch(spec, w, v, n_prune, flags=0, check=None, with_in_alive=True):
     try:
         pl.enable_batch(k_var)
         info = pl.model.info
-        recs, (rc, ots, ovs, ews, evs) = pl.portfolio(n_prune, flags, with_in_alive)
-        torch.cuda.synchronize()
-        collapse = any((r.plan.new_width == 0).any() for r in refs)
-        assert rc == (S.SHIFTER_WARN_COLLAPSE if collapse else S.SHIFTER_OK)
-        n = info.n_prunable
-        for k in (check if check is not None else range(k_var)):
-            ref, lab = refs[k], f"{spec.name} batch k={k}"
-            check_threshold(recs[k], ref.sel, a)
-            mask = pl.b_mask[k * pl.m_stride:k * pl.m_stride + n].cpu().numpy()
-            assert np.array_equal(mask, ref.mask), lab + " mask"
-            ws = pl.b_w_sparse[k * pl.w_stride:(k + 1) * pl.w_stride].cpu().numpy()
-            for t in spec.tensors:
-                sl = slice(t.offset, t.offset + t.numel)
-                assert np.array_equal(bits(ws[sl]), bits(ref.w_sparse[sl])), lab + " sparse"
-            so, si, sg = info.sum_out_ch, info.sum_in_ch, info.sum_group_width
-            oa = pl.b_out_alive[k * so:(k + 1) * so].cpu().numpy()
-            assert np.array_equal(oa, np.concatenate(ref.out_alive)), lab + " out_alive"
-            if with_in_alive:
-                ia = pl.b_in_alive[k * si:(k + 1) * si].cpu().numpy()
-                assert np.array_equal(ia, np.concatenate(ref.in_alive)), lab + " in_alive"
-            ga = pl.b_group_alive[k * sg:(k + 1) * sg].cpu().numpy()
-            im = pl.b_index_map[k * sg:(k + 1) * sg].cpu().numpy()
-            kp = pl.b_keep[k * sg:(k + 1) * sg].cpu().numpy().view(np.uint32)
-            ng = info.n_groups
-            nw = pl.b_new_width[k * ng:(k + 1) * ng].cpu().numpy().view(np.uint32)
-            assert np.array_equal(nw, ref.plan.new_width), lab + " new_width"
-            for gi, g in enumerate(spec.groups):
-                o = pl.model.group_off[gi]
-                assert np.array_equal(ga[o:o + g.width], ref.plan.alive[gi]), lab + " alive"
-                assert np.array_equal(im[o:o + g.width], ref.plan.index_map[gi]), lab + " map"
-                kk = int(nw[gi])
-                assert np.array_equal(kp[o:o + kk], ref.plan.keep[gi]), lab + " keep"
-            assert ews[k] == ref.compacted.w.size and evs[k] == ref.compacted.v.size
-            wc = pl.b_w_out[k * pl.cap_w:k * pl.cap_w + ews[k]].cpu().numpy()
-            vc = pl.b_vecs_out[k * pl.cap_v:k * pl.cap_v + evs[k]].cpu().numpy()
-            assert np.array_equal(bits(wc), bits(ref.compacted.w)), lab + " compacted w"
-            assert np.array_equal(bits(vc), bits(ref.compacted.v)), lab + " compacted v"
-            n_t, n_v = info.n_tensors, info.n_vecs
-            for i, (off, o2, i2, kh, kw) in enumerate(ref.compacted.tensor_shapes):
-                d = ots[k * n_t + i]
-                assert (d.offset, d.out_ch, d.in_ch, d.kh, d.kw) == (off, o2, i2, kh, kw)
-            for i, (off, ln) in enumerate(ref.compacted.vec_shapes):
-                d = ovs[k * n_v + i]
-                assert (d.offset, d.len) == (off, ln)
+        for from_sparse in (False, True):
+            # the rebuild from the dense arena (masking on the way) and from the K sparse arenas
+            pl.b_w_out.fill_(float("nan"))
+            pl.b_vecs_out.fill_(float("nan"))
+            _check_batch_run(pl, spec, refs, a, n_prune, flags, check, with_in_alive, from_sparse)
     finally:
         pl.close()
+
+
+def _check_batch_run(pl, spec, refs, a, n_prune, flags, check, with_in_alive, from_sparse):
+    info = pl.model.info
+    k_var = len(n_prune)
+    recs, (rc, ots, ovs, ews, evs) = pl.portfolio(n_prune, flags, with_in_alive,
+                                                  from_sparse=from_sparse)
+    torch.cuda.synchronize()
+    collapse = any((r.plan.new_width == 0).any() for r in refs)
+    assert rc == (S.SHIFTER_WARN_COLLAPSE if collapse else S.SHIFTER_OK)
+    n = info.n_prunable
+    for k in (check if check is not None else range(k_var)):
+        ref, lab = refs[k], f"{spec.name} batch k={k} from_sparse={from_sparse}"
+        check_threshold(recs[k], ref.sel, a)
+        mask = pl.b_mask[k * pl.m_stride:k * pl.m_stride + n].cpu().numpy()
+        assert np.array_equal(mask, ref.mask), lab + " mask"
+        ws = pl.b_w_sparse[k * pl.w_stride:(k + 1) * pl.w_stride].cpu().numpy()
+        for t in spec.tensors:
+            sl = slice(t.offset, t.offset + t.numel)
+            assert np.array_equal(bits(ws[sl]), bits(ref.w_sparse[sl])), lab + " sparse"
+        so, si, sg = info.sum_out_ch, info.sum_in_ch, info.sum_group_width
+        oa = pl.b_out_alive[k * so:(k + 1) * so].cpu().numpy()
+        assert np.array_equal(oa, np.concatenate(ref.out_alive)), lab + " out_alive"
+        if with_in_alive:
+            ia = pl.b_in_alive[k * si:(k + 1) * si].cpu().numpy()
+            assert np.array_equal(ia, np.concatenate(ref.in_alive)), lab + " in_alive"
+        ga = pl.b_group_alive[k * sg:(k + 1) * sg].cpu().numpy()
+        im = pl.b_index_map[k * sg:(k + 1) * sg].cpu().numpy()
+        kp = pl.b_keep[k * sg:(k + 1) * sg].cpu().numpy().view(np.uint32)
+        ng = info.n_groups
+        nw = pl.b_new_width[k * ng:(k + 1) * ng].cpu().numpy().view(np.uint32)
+        assert np.array_equal(nw, ref.plan.new_width), lab + " new_width"
+        for gi, g in enumerate(spec.groups):
+            o = pl.model.group_off[gi]
+            assert np.array_equal(ga[o:o + g.width], ref.plan.alive[gi]), lab + " alive"
+            assert np.array_equal(im[o:o + g.width], ref.plan.index_map[gi]), lab + " map"
+            kk = int(nw[gi])
+            assert np.array_equal(kp[o:o + kk], ref.plan.keep[gi]), lab + " keep"
+        assert ews[k] == ref.compacted.w.size and evs[k] == ref.compacted.v.size
+        wc = pl.b_w_out[k * pl.cap_w:k * pl.cap_w + ews[k]].cpu().numpy()
+        vc = pl.b_vecs_out[k * pl.cap_v:k * pl.cap_v + evs[k]].cpu().numpy()
+        assert np.array_equal(bits(wc), bits(ref.compacted.w)), lab + " compacted w"
+        assert np.array_equal(bits(vc), bits(ref.compacted.v)), lab + " compacted v"
+        n_t, n_v = info.n_tensors, info.n_vecs
+        for i, (off, o2, i2, kh, kw) in enumerate(ref.compacted.tensor_shapes):
+            d = ots[k * n_t + i]
+            assert (d.offset, d.out_ch, d.in_ch, d.kh, d.kw) == (off, o2, i2, kh, kw)
+        for i, (off, ln) in enumerate(ref.compacted.vec_shapes):
+            d = ovs[k * n_v + i]
+            assert (d.offset, d.len) == (off, ln)
 
 
 def test_batch_small_configs_any_order_of_counts():
