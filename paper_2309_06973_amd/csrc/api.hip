@@ -82,7 +82,7 @@ static void unbind(shifter_model* m) {
     if (!b.ctx) return;
     (void)hipSetDevice(b.device);
     void* ptrs[] = {b.tens, b.groups, b.vecs, b.producers, b.tile_prefix, b.sel, b.ghist,
-                    b.tile_cnt, b.plan_t, b.plan_v, b.plan_h, b.out_tile_prefix, b.band_prefix, b.levels, b.spec, b.shist,
+                    b.tile_cnt, b.plan_t, b.plan_v, b.plan_h, b.out_tile_prefix, b.rect_prefix, b.rowtab_prefix, b.coltab_prefix, b.rowtab, b.coltab, b.levels, b.spec, b.shist,
                     b.spec_cnt, b.partial, b.cand, b.list, b.ranked_ids, b.multi, b.multi_cnt,
                     b.multi_partial, b.multi_seg, b.multi_seg_cnt};
     for (void* p : ptrs)
@@ -193,18 +193,26 @@ extern "C" int shifter_model_create(const shifter_tensor_desc* tensors, uint32_t
             const uint32_t rows_par = GATHER_CHUNK >> lg;
             const uint32_t rb = 4u * std::max(rows_par, 4u);
             m->gather_units_bound += chunks * ((t.out_ch + rb - 1) / rb);
-            // portfolio rebuild in source order: bands of filters times rectangles of
-            // about GATHER_CHUNK columns, in whole channels (see gather_band_kernel)
-            d.band_rows = std::min(64u, 2 * rb);
-            if (d.kk > GATHER_CHUNK) m->band_ok = false;
-            d.chunk_ch = d.row_len <= GATHER_CHUNK / 2 ? d.cin : std::max(1u, GATHER_CHUNK / d.kk);
+            // portfolio rebuild: the source is cut into rectangles of band_rows filters
+            // times chunk_ch whole channels (at most GATHER_CHUNK columns), sized to the
+            // RECT_ELEMS floats a block stages in LDS (see gather_rect_kernel)
+            if (d.kk > GATHER_CHUNK) m->rect_ok = false;
+            d.chunk_ch = std::min(d.cin, std::max(1u, GATHER_CHUNK / d.kk));
             d.src_chunks = (d.cin + d.chunk_ch - 1) / d.chunk_ch;
+            const uint32_t wp = (d.chunk_ch * d.kk + 127u) & ~127u;
+            d.band_rows = std::max(1u, std::min(64u, RECT_ELEMS / std::max(wp, 128u)));
             const uint64_t bands = (t.out_ch + d.band_rows - 1) / d.band_rows;
-            const uint64_t bu = (bands + 7) / 8 * d.src_chunks;
-            if (m->band_prefix.empty()) m->band_prefix.push_back(0);
-            if ((m->band_prefix.back() + bu) * 8 * (MAXK / 4) >= (1ull << 31))
+            if (m->rect_prefix.empty()) {
+                m->rect_prefix.push_back(0);
+                m->rowtab_prefix.push_back(0);
+                m->coltab_prefix.push_back(0);
+            }
+            if (m->rect_prefix.back() + bands * d.src_chunks >= (1ull << 31) ||
+                m->rowtab_prefix.back() + bands + 1 >= (1ull << 31) / MAXK)
                 return bad("model too large for 32-bit gather unit indices", i);
-            m->band_prefix.push_back(m->band_prefix.back() + (uint32_t)bu);
+            m->rect_prefix.push_back(m->rect_prefix.back() + (uint32_t)(bands * d.src_chunks));
+            m->rowtab_prefix.push_back(m->rowtab_prefix.back() + (uint32_t)bands + 1);
+            m->coltab_prefix.push_back(m->coltab_prefix.back() + d.src_chunks + 1);
         }
         d.out_group = t.out_group;
         d.in_group = t.in_group;
@@ -226,7 +234,11 @@ extern "C" int shifter_model_create(const shifter_tensor_desc* tensors, uint32_t
     }
     m->tile_prefix.push_back((uint32_t)tiles);
     m->n_tiles = (uint32_t)tiles;
-    if (m->band_prefix.empty()) m->band_prefix.push_back(0);
+    if (m->rect_prefix.empty()) {
+        m->rect_prefix.push_back(0);
+        m->rowtab_prefix.push_back(0);
+        m->coltab_prefix.push_back(0);
+    }
     std::sort(spans.begin(), spans.end());
     for (size_t i = 1; i < spans.size(); ++i)
         if (spans[i].first < spans[i - 1].second) return bad("tensors overlap in the weight arena", (uint32_t)i);
@@ -338,7 +350,13 @@ static int bind(shifter_ctx* ctx, const shifter_model* cm) {
     if ((rc = upload(ctx, &b.vecs, m->dv.data(), n_v))) return rc;
     if ((rc = upload(ctx, &b.producers, m->producers.data(), m->producers.size()))) return rc;
     if ((rc = upload(ctx, &b.tile_prefix, m->tile_prefix.data(), m->tile_prefix.size()))) return rc;
-    if ((rc = upload(ctx, &b.band_prefix, m->band_prefix.data(), m->band_prefix.size()))) return rc;
+    if ((rc = upload(ctx, &b.rect_prefix, m->rect_prefix.data(), m->rect_prefix.size()))) return rc;
+    if ((rc = upload(ctx, &b.rowtab_prefix, m->rowtab_prefix.data(), m->rowtab_prefix.size()))) return rc;
+    if ((rc = upload(ctx, &b.coltab_prefix, m->coltab_prefix.data(), m->coltab_prefix.size()))) return rc;
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.rowtab),
+                           sizeof(uint32_t) * MAXK * std::max<size_t>(m->rowtab_prefix.back(), 1)));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.coltab),
+                           sizeof(uint32_t) * MAXK * std::max<size_t>(m->coltab_prefix.back(), 1)));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.sel), sizeof(SelState)));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.ghist), sizeof(uint32_t) * MAXK * HIST_BINS));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.tile_cnt),

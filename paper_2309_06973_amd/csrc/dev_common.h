@@ -17,6 +17,15 @@ __device__ __forceinline__ uint32_t find_tensor(const uint32_t* __restrict__ pre
     return lo;
 }
 
+// A value that is the same in every lane, moved to scalar registers.  The builtin returns
+// a signed int: without the casts the low word of a 64-bit value would be sign-extended.
+__device__ __forceinline__ uint32_t uniform_u32(uint32_t x) {
+    return (uint32_t)__builtin_amdgcn_readfirstlane((int)x);
+}
+__device__ __forceinline__ uint64_t uniform_u64(uint64_t x) {
+    return ((uint64_t)uniform_u32((uint32_t)(x >> 32)) << 32) | (uint64_t)uniform_u32((uint32_t)x);
+}
+
 // Small-quotient division used to index tile-relative flag slots.  The host sets
 // magic = floor(2^32 / d) + 1 when 1 < d <= 2 * TILE (exact while x * d < 2^32, and here
 // x < d + TILE + 2); for larger d the callers guarantee x < 2 * d.

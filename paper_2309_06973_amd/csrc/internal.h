@@ -17,7 +17,8 @@ constexpr uint32_t HIST_BINS = 2048; // stride of one histogram slot
 constexpr uint32_t MAXK = SHIFTER_MAX_VARIANTS;
 constexpr uint32_t SLOTS_PER_PASS = 8;
 constexpr uint32_t GATHER_CHUNK = 1024;  // columns of a gather work unit (16 per lane)
-constexpr uint32_t GATHER_ROWS = 16;     // its rows, for rows of GATHER_CHUNK or more columns
+constexpr uint32_t GATHER_ROWS = 16;
+constexpr uint32_t RECT_ELEMS = 8192;    // floats of a source rectangle staged in LDS by the portfolio rebuild     // its rows, for rows of GATHER_CHUNK or more columns
 
 // Device-side view of one weight tensor.
 struct DevTensor {
@@ -35,9 +36,9 @@ struct DevTensor {
     int32_t out_group, in_group;
     uint32_t out_flag_off, in_flag_off;
     uint32_t prunable;
-    uint32_t band_rows;   // portfolio rebuild: filters per source band (at most 64)
+    uint32_t band_rows;   // portfolio rebuild: filters per source rectangle (at most 64)
     uint32_t chunk_ch;    //   in-group channels per source rectangle
-    uint32_t src_chunks;  //   rectangles per band: ceil(cin / chunk_ch)
+    uint32_t src_chunks;  //   rectangles per band of filters: ceil(cin / chunk_ch)
 };
 
 struct DevGroup {
@@ -160,8 +161,10 @@ struct shifter_model {
     uint32_t sample_tile_stride = 1;     // every how many tiles the selection samples
     uint32_t sample_size = 0;            // weights in that sample
     uint32_t gather_units_bound = 0;     // gather work units when nothing is removed
-    std::vector<uint32_t> band_prefix;   // portfolio rebuild: ceil(bands / 8) * src_chunks per tensor, prefix sums
-    bool band_ok = true;                 // every tensor has kk <= GATHER_CHUNK
+    // portfolio rebuild: per tensor prefix sums of its source rectangles, of its row-table
+    // entries (bands + 1) and of its column-table entries (src_chunks + 1)
+    std::vector<uint32_t> rect_prefix, rowtab_prefix, coltab_prefix;
+    bool rect_ok = true;                 // every tensor has kk <= GATHER_CHUNK
 
     // device side, created by the first call that uses the model with a context
     struct Bound {
@@ -179,7 +182,11 @@ struct shifter_model {
         shifter::PlanVec* plan_v = nullptr;
         shifter::PlanHeader* plan_h = nullptr;
         uint32_t* out_tile_prefix = nullptr;  // MAXK * (n_tensors + 1)
-        uint32_t* band_prefix = nullptr;      // n_tensors + 1
+        uint32_t* rect_prefix = nullptr;      // n_tensors + 1 each
+        uint32_t* rowtab_prefix = nullptr;
+        uint32_t* coltab_prefix = nullptr;
+        uint32_t* rowtab = nullptr;           // MAXK * rowtab_prefix.back()
+        uint32_t* coltab = nullptr;           // MAXK * coltab_prefix.back()
         uint32_t* levels = nullptr;           // sum_out_ch + sum_in_ch
         shifter::SpecState* spec = nullptr;
         uint32_t* shist = nullptr;            // 65536 sample bins

@@ -295,93 +295,264 @@ __global__ __launch_bounds__(BLOCK) void gather_kernel(
     }
 }
 
-// Number of entries of the ascending list arr[0..n) that are below x, found by the whole
-// wavefront: 64 evenly spaced probes per round narrow the range 64-fold, so lists of up
-// to 4096 entries take two dependent loads.  Uniform result.
-__device__ __forceinline__ uint32_t wave_lower_bound(const uint32_t* __restrict__ arr, uint32_t n,
-                                                     uint32_t x, uint32_t lane) {
-    uint32_t lo = 0, len = n;
-    while (len > 0) {
-        const uint32_t step = (len + 63u) >> 6;
-        const uint32_t idx = lo + (lane + 1u) * step - 1u;
-        const bool below = idx < lo + len && arr[idx] < x;
-        const uint32_t c = (uint32_t)__popcll(__ballot(below));   // the probes below x are a prefix
-        const uint32_t end = lo + len;
-        lo += c * step;
-        len = min(step - 1u, end - lo);
+// Row and column tables of the portfolio rebuild, per variant: for every band of
+// band_rows source filters the number of surviving filters below its first one, and for
+// every chunk of chunk_ch source channels the number of surviving channels below its
+// first one (keep lists are ascending, so these are lower bounds).  What a variant keeps
+// of a source rectangle is then the range between two neighbouring entries of each.
+__global__ __launch_bounds__(BLOCK) void rect_tables_kernel(
+    const DevTensor* __restrict__ tens, const DevGroup* __restrict__ groups, uint32_t n_t,
+    const uint32_t* __restrict__ rowtab_prefix, const uint32_t* __restrict__ coltab_prefix,
+    const uint32_t* __restrict__ keep_all, const uint32_t* __restrict__ new_width_all,
+    uint64_t group_stride, uint32_t n_groups, uint32_t* __restrict__ rowtab,
+    uint32_t* __restrict__ coltab) {
+    const uint32_t k = blockIdx.y;
+    const uint32_t n_row = rowtab_prefix[n_t], n_col = coltab_prefix[n_t];
+    const uint32_t i = blockIdx.x * BLOCK + threadIdx.x;
+    if (i >= n_row + n_col) return;
+    const bool is_row = i < n_row;
+    const uint32_t e = is_row ? i : i - n_row;
+    const uint32_t* prefix = is_row ? rowtab_prefix : coltab_prefix;
+    uint32_t lo = 0, hi = n_t;   // tensor of entry e
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (prefix[mid] <= e) lo = mid; else hi = mid;
     }
-    return lo;
+    const DevTensor& T = tens[lo];
+    const uint32_t j = e - prefix[lo];
+    const int32_t grp = is_row ? T.out_group : T.in_group;
+    const uint32_t x = is_row ? min(j * T.band_rows, T.out_ch) : min(j * T.chunk_ch, T.cin);
+    const uint32_t* keep = keep_all + k * group_stride + groups[grp].off;
+    const uint32_t n = min(new_width_all[k * n_groups + grp], groups[grp].width);
+    uint32_t a = 0, len = n;     // entries of keep[0..n) below x
+    while (len > 0) {
+        const uint32_t half = len >> 1;
+        if (keep[a + half] < x) { a += half + 1; len -= half + 1; } else len = half;
+    }
+    (is_row ? rowtab + (uint64_t)k * n_row : coltab + (uint64_t)k * n_col)[e] = a;
 }
 
-// The rebuild of all K variants of a portfolio from one source, in source order.  A
-// work unit is a rectangle of the SOURCE tensor - band_rows consecutive filters times
-// chunk_ch consecutive input channels (about GATHER_CHUNK columns) - for one variant.
-// What a variant keeps of the rectangle is a contiguous range of its keep lists (they
-// are ascending; wave_lower_bound finds the ends), so the unit is an ordinary piece of
-// the rebuilt tensor and gather_rows copies it.  The K units of a rectangle run in
-// neighbouring blocks of the same XCD (blocks are dealt to the eight XCDs in turn;
-// blocks 8 apart share one), each XCD working through a band of its own: a source line
-// comes in from memory once and the other K - 1 variants find it in that XCD's L2.
-__global__ __launch_bounds__(BLOCK) void gather_band_kernel(
+// Position of column c of a staged rectangle row in LDS: within each group of 128
+// columns, column 4 i + j sits at 32 j + i, so lanes reading every fourth column (four
+// consecutive outputs per lane) fall into different banks.
+__device__ __forceinline__ uint32_t rect_swizzle(uint32_t c) {
+    return (c & ~127u) | ((c & 3u) << 5) | ((c >> 2) & 31u);
+}
+
+typedef float float4_a4 __attribute__((ext_vector_type(4), aligned(4)));   // dword-aligned
+
+// What one variant keeps of a source rectangle (gather_rect_kernel).
+struct RectVariant {
+    uint32_t row_begin, n_rows;   // rows [row_begin, row_begin + n_rows) of the rebuilt tensor
+    uint32_t width, row2;         // width columns from col0 on; row2 = its filter length
+    uint32_t a0, n_ch;            // its surviving channels: entries [a0, a0 + n_ch) of the keep list
+    uint64_t dst;                 // element offset of (row 0, col0) in the output arenas
+    uint64_t cut;                 // 0: nothing masked
+};
+
+// The rebuild of all K variants of a portfolio from the dense arena in one read of it
+// (Algorithm 2 for the whole portfolio; Sec. III-D Module 4's single batch operation).
+// One block per source rectangle - band_rows filters times chunk_ch whole channels, at
+// most RECT_ELEMS floats.  All threads stage the rectangle in LDS with 16-byte loads
+// while the first K threads fetch what each variant keeps of it (rows [row_begin,
+// +n_rows) and columns [col0, +width) of its rebuilt tensor, from the two tables).
+// Then the four wavefronts take the variants in turn (an LDS counter hands them out):
+// a lane owns four consecutive output columns of four quad slots, works out their LDS
+// positions once per variant from the keep list, and per row reads them, applies the
+// variant's cut (removed <=> (|w| bits, global index) < cut) and stores 16 bytes.
+// Narrow pieces put several rows into one step.  Against the dword gather this needs
+// about an eighth of the vector-memory instructions per KB moved, which is what bounded
+// that kernel.
+__global__ __launch_bounds__(BLOCK) void gather_rect_kernel(
     const DevTensor* __restrict__ tens, const DevGroup* __restrict__ groups, uint32_t n_t,
-    const PlanTensor* __restrict__ pt_all, const uint32_t* __restrict__ band_prefix,
-    const PlanHeader* __restrict__ hdr_all, const float* __restrict__ w_all,
+    const PlanTensor* __restrict__ pt_all, const uint32_t* __restrict__ rect_prefix,
+    const uint32_t* __restrict__ rowtab_prefix, const uint32_t* __restrict__ coltab_prefix,
+    const uint32_t* __restrict__ rowtab, const uint32_t* __restrict__ coltab,
+    const PlanHeader* __restrict__ hdr_all, const float* __restrict__ w, uint64_t w_extent,
     const uint32_t* __restrict__ keep_all, float* __restrict__ w_out_all,
     const DevVec* __restrict__ vecs, uint32_t n_v, const PlanVec* __restrict__ pv_all,
-    const float* __restrict__ v, float* __restrict__ v_out_all, uint64_t w_stride,
-    uint64_t group_stride, uint64_t cap_w, uint64_t cap_v,
-    const shifter_threshold* __restrict__ thr, uint32_t k_var, uint32_t k_blocks,
-    uint32_t n_slots) {
+    const float* __restrict__ v, float* __restrict__ v_out_all, uint64_t group_stride,
+    uint64_t cap_w, uint64_t cap_v, const shifter_threshold* __restrict__ thr, uint32_t k_var,
+    uint32_t n_rects) {
+    __shared__ float tile[RECT_ELEMS];
+    __shared__ RectVariant meta[MAXK];
+    __shared__ uint32_t next_k;
     const uint32_t lane = threadIdx.x & 63u;
-    // block -> (band within its group of eight = XCD, variant block, rectangle slot)
-    const uint32_t x = blockIdx.x & 7u, j = blockIdx.x >> 3;
-    const uint32_t slot = j / k_blocks, vb = j - slot * k_blocks;
-    const uint32_t k = vb * (BLOCK / 64) + (threadIdx.x >> 6);
-    if (slot < n_slots && k < k_var && !(hdr_all[k].status & 1u)) {
-        const uint32_t t = find_tensor(band_prefix, n_t, slot);
+    if (blockIdx.x < n_rects) {
+        const uint32_t t = find_tensor(rect_prefix, n_t, blockIdx.x);
         const DevTensor& T = tens[t];
-        const PlanTensor P = pt_all[(uint64_t)k * n_t + t];
-        const uint32_t local = slot - band_prefix[t];
-        const uint32_t grp = local / T.src_chunks, chunk = local - grp * T.src_chunks;
-        const uint32_t r0 = (grp * 8u + x) * T.band_rows;
-        if (P.numel2 != 0 && r0 < T.out_ch) {
-            const uint32_t* keep = keep_all + (uint64_t)k * group_stride;
-            const uint32_t* keep_i = keep + groups[T.in_group].off;
-            const uint32_t* keep_o = keep + groups[T.out_group].off;
-            const uint32_t kk = T.kk;
-            // surviving channels of the rectangle -> columns [col0, col0 + width) of the rebuilt filter
-            const uint32_t ch0 = chunk * T.chunk_ch, ch1 = ch0 + T.chunk_ch;
-            const uint32_t a0 = wave_lower_bound(keep_i, P.c2, ch0, lane);
-            const uint32_t a1 = ch1 >= T.cin ? P.c2 : wave_lower_bound(keep_i, P.c2, ch1, lane);
-            const uint32_t col0 = a0 * kk, width = (a1 - a0) * kk;
-            // surviving filters of the band -> rows [row_begin, row_begin + n_rows)
-            const uint32_t row_begin = wave_lower_bound(keep_o, P.o2, r0, lane);
-            const uint32_t ko_lane = row_begin + lane < P.o2 ? keep_o[row_begin + lane] : 0xffffffffu;
-            const uint32_t n_rows = (uint32_t)__popcll(__ballot(ko_lane < r0 + T.band_rows));
-            if (width != 0 && n_rows != 0) {
-                constexpr uint32_t U = GATHER_CHUNK / 64;
-                const uint32_t lg = gather_cols_log2(width);
-                uint32_t off[U], col[U], valid = 0;
-#pragma unroll
-                for (uint32_t u = 0; u < U; ++u) {
-                    const uint32_t e = (lane + 64 * u) & ((1u << lg) - 1);
-                    valid |= (e < width ? 1u : 0u) << u;
-                    const uint32_t r = col0 + min(e, width - 1);
-                    col[u] = r;
-                    const uint32_t c2 = kk == 1 ? r : div_u32(r, T.magic_kk, T.shift_kk);
-                    off[u] = keep_i[c2] * kk + (r - c2 * kk);
+        const uint32_t local = blockIdx.x - rect_prefix[t];
+        const uint32_t band = local / T.src_chunks, chunk = local - band * T.src_chunks;
+        const uint32_t kk = T.kk, row_len = T.row_len;
+        const uint32_t r0 = band * T.band_rows, nr = min(T.band_rows, T.out_ch - r0);
+        const uint32_t ch0 = chunk * T.chunk_ch, nch = min(T.chunk_ch, T.cin - ch0);
+        const uint32_t c_base = ch0 * kk, wsrc = nch * kk;
+        const uint32_t wp = (T.chunk_ch * kk + 127u) & ~127u;   // LDS row stride
+        const uint32_t off_out = groups[T.out_group].off, off_in = groups[T.in_group].off;
+        const uint32_t g_base = (uint32_t)T.gbase + c_base;
+        // what each variant keeps of the rectangle
+        if (threadIdx.x < k_var) {
+            const uint32_t k = threadIdx.x;
+            const uint32_t n_rowtab = rowtab_prefix[n_t], n_coltab = coltab_prefix[n_t];
+            const PlanTensor P = pt_all[(uint64_t)k * n_t + t];
+            const uint32_t* rt = rowtab + (uint64_t)k * n_rowtab + rowtab_prefix[t] + band;
+            const uint32_t* ct = coltab + (uint64_t)k * n_coltab + coltab_prefix[t] + chunk;
+            const uint32_t rb = rt[0], re = rt[1], a0 = ct[0], a1 = ct[1];
+            RectVariant M;
+            M.row_begin = rb;
+            M.width = (a1 - a0) * kk;
+            M.n_rows = ((hdr_all[k].status & 1u) || P.numel2 == 0 || M.width == 0) ? 0u : re - rb;
+            M.row2 = P.row2;
+            M.a0 = a0;
+            M.n_ch = a1 - a0;
+            M.dst = (uint64_t)k * cap_w + P.out_off + (uint64_t)a0 * kk;
+            M.cut = T.prunable ? thr[k].cut : 0;
+            meta[k] = M;
+        }
+        if (threadIdx.x == 0) next_k = 0;
+        // stage rows r0 .. r0 + nr, columns c_base .. c_base + wsrc: a row takes 1 << lgt
+        // threads (16 bytes each), so the block covers BLOCK >> lgt rows per round
+        {
+            const uint32_t qpr = (wsrc + 3u) >> 2;
+            uint32_t lgt = 0;
+            while ((1u << lgt) < qpr) ++lgt;
+            const uint32_t c = (threadIdx.x & ((1u << lgt) - 1u)) * 4u;
+            if (c < wsrc) {
+                float* d = tile + rect_swizzle(c);
+                for (uint32_t r = threadIdx.x >> lgt; r < nr; r += BLOCK >> lgt) {
+                    const uint64_t gi = T.offset + (uint64_t)(r0 + r) * row_len + c_base + c;
+                    float x0, x1, x2, x3;
+                    if (gi + 3 < w_extent) {
+                        const float4_a4 x = *reinterpret_cast<const float4_a4*>(w + gi);
+                        x0 = x.x; x1 = x.y; x2 = x.z; x3 = x.w;
+                    } else {
+                        x0 = w[gi];
+                        x1 = gi + 1 < w_extent ? w[gi + 1] : 0.0f;
+                        x2 = gi + 2 < w_extent ? w[gi + 2] : 0.0f;
+                        x3 = 0.0f;
+                    }
+                    // columns c .. c + 3 share (c & ~127) and (c >> 2) & 31: positions 32 apart
+                    float* dr = d + r * wp;
+                    dr[0] = x0; dr[32] = x1; dr[64] = x2; dr[96] = x3;
                 }
-                const uint32_t row_end = row_begin + n_rows;
-                const float* src = w_all + (uint64_t)k * w_stride + T.offset;
-                float* dst = w_out_all + (uint64_t)k * cap_w + P.out_off;
-                const uint64_t cut = (thr && T.prunable) ? thr[k].cut : 0;
-                const uint32_t cut_key = (uint32_t)(cut >> 32), cut_g = (uint32_t)cut, gb = (uint32_t)T.gbase;
-                switch (lg) {
-                    case 10: gather_rows<10>(src, dst, ko_lane, off, col, valid, row_begin, row_end, T.row_len, P.row2, gb, cut_key, cut_g); break;
-                    case 9: gather_rows<9>(src, dst, ko_lane, off, col, valid, row_begin, row_end, T.row_len, P.row2, gb, cut_key, cut_g); break;
-                    case 8: gather_rows<8>(src, dst, ko_lane, off, col, valid, row_begin, row_end, T.row_len, P.row2, gb, cut_key, cut_g); break;
-                    case 7: gather_rows<7>(src, dst, ko_lane, off, col, valid, row_begin, row_end, T.row_len, P.row2, gb, cut_key, cut_g); break;
-                    default: gather_rows<6>(src, dst, ko_lane, off, col, valid, row_begin, row_end, T.row_len, P.row2, gb, cut_key, cut_g); break;
+            }
+        }
+        __syncthreads();
+
+        for (;;) {
+            uint32_t k = 0;
+            if (lane == 0) k = atomicAdd(&next_k, 1u);
+            k = uniform_u32(k);
+            if (k >= k_var) break;
+            // the record is the same for every lane: keep it in scalar registers
+            const uint32_t n_rows = uniform_u32(meta[k].n_rows);
+            if (n_rows == 0) continue;
+            const uint32_t row_begin = uniform_u32(meta[k].row_begin);
+            const uint32_t width = uniform_u32(meta[k].width);
+            const uint32_t row2 = uniform_u32(meta[k].row2);
+            const uint32_t a0 = uniform_u32(meta[k].a0);
+            const uint32_t n_ch = uniform_u32(meta[k].n_ch);
+            const uint64_t dst_off = uniform_u64(meta[k].dst);
+            const uint64_t cut = uniform_u64(meta[k].cut);
+            const uint32_t* keep = keep_all + k * group_stride;
+            const uint32_t* keep_i = keep + off_in + a0;
+            const uint32_t lrow_lane = keep[off_out + row_begin + min(lane, n_rows - 1u)] - r0;
+            // quad slots: 256 per step; a row takes 1 << lgq of them
+            const uint32_t quads = (width + 3u) >> 2;
+            uint32_t lgq = 0;
+            while ((1u << lgq) < quads) ++lgq;
+            // this lane's quads: byte position in a staged row and column in the rectangle
+            uint32_t pos4[4][4], scol[4][4], e0[4];
+#pragma unroll
+            for (uint32_t u = 0; u < 4; ++u) {
+                e0[u] = ((lane + 64u * u) & ((1u << lgq) - 1u)) * 4u;
+                const uint32_t eq = min(e0[u], width - 1u);
+                const uint32_t c2 = kk == 1 ? eq : div_u32(eq, T.magic_kk, T.shift_kk);
+                const uint32_t rem = eq - c2 * kk;
+                if (kk >= 4) {
+                    // four consecutive columns lie in at most two surviving channels
+                    const uint32_t base_a = (keep_i[c2] - ch0) * kk;
+                    const uint32_t base_b = (keep_i[min(c2 + 1u, n_ch - 1u)] - ch0) * kk - kk;
+#pragma unroll
+                    for (uint32_t j = 0; j < 4; ++j)
+                        scol[u][j] = (rem + j >= kk ? base_b : base_a) + rem + j;
+                } else {
+#pragma unroll
+                    for (uint32_t j = 0; j < 4; ++j) {
+                        const uint32_t e = min(e0[u] + j, width - 1u);
+                        const uint32_t cj = kk == 1 ? e : div_u32(e, T.magic_kk, T.shift_kk);
+                        scol[u][j] = (keep_i[cj] - ch0) * kk + (e - cj * kk);
+                    }
+                }
+#pragma unroll
+                for (uint32_t j = 0; j < 4; ++j) pos4[u][j] = rect_swizzle(scol[u][j]) * 4u;
+            }
+            float* dst = w_out_all + dst_off;
+            const unsigned char* tile_b = reinterpret_cast<const unsigned char*>(tile);
+            if (lgq >= 6) {
+                // wide piece: quad slot group u belongs to one row, everything about the
+                // row is scalar
+                const uint32_t rows_par = 256u >> lgq;
+                for (uint32_t row0 = 0; row0 < n_rows; row0 += rows_par) {
+#pragma unroll
+                    for (uint32_t u = 0; u < 4; ++u) {
+                        const uint32_t row = row0 + ((64u * u) >> lgq);
+                        if (row < n_rows) {
+                            const uint32_t lrow = __builtin_amdgcn_readlane(lrow_lane, row);
+                            const unsigned char* trow = tile_b + lrow * wp * 4u;
+                            const uint32_t g_row = g_base + (r0 + lrow) * row_len;
+                            float x[4];
+#pragma unroll
+                            for (uint32_t j = 0; j < 4; ++j) {
+                                const float y = *reinterpret_cast<const float*>(trow + pos4[u][j]);
+                                const uint64_t comp = ((uint64_t)(__float_as_uint(y) & 0x7fffffffu) << 32) |
+                                                      (g_row + scol[u][j]);
+                                x[j] = comp < cut ? 0.0f : y;
+                            }
+                            float* d = dst + (uint64_t)(row_begin + row) * row2 + e0[u];
+                            if (e0[u] + 4u <= width) {
+                                float4_a4 o;
+                                o.x = x[0]; o.y = x[1]; o.z = x[2]; o.w = x[3];
+                                *reinterpret_cast<float4_a4*>(d) = o;
+                            } else if (e0[u] < width) {
+                                d[0] = x[0];
+                                if (e0[u] + 1u < width) d[1] = x[1];
+                                if (e0[u] + 2u < width) d[2] = x[2];
+                            }
+                        }
+                    }
+                }
+            } else {
+                // narrow piece: 64 >> lgq rows per slot group, the row differs by lane
+                const uint32_t rows_par = 256u >> lgq;
+                for (uint32_t row0 = 0; row0 < n_rows; row0 += rows_par) {
+#pragma unroll
+                    for (uint32_t u = 0; u < 4; ++u) {
+                        const uint32_t row = row0 + ((lane + 64u * u) >> lgq);
+                        const uint32_t lrow = __shfl(lrow_lane, min(row, n_rows - 1u));
+                        const unsigned char* trow = tile_b + lrow * wp * 4u;
+                        const uint32_t g_row = g_base + (r0 + lrow) * row_len;
+                        float x[4];
+#pragma unroll
+                        for (uint32_t j = 0; j < 4; ++j) {
+                            const float y = *reinterpret_cast<const float*>(trow + pos4[u][j]);
+                            const uint64_t comp = ((uint64_t)(__float_as_uint(y) & 0x7fffffffu) << 32) |
+                                                  (g_row + scol[u][j]);
+                            x[j] = comp < cut ? 0.0f : y;
+                        }
+                        if (row < n_rows && e0[u] < width) {
+                            float* d = dst + (uint64_t)(row_begin + row) * row2 + e0[u];
+                            if (e0[u] + 4u <= width) {
+                                float4_a4 o;
+                                o.x = x[0]; o.y = x[1]; o.z = x[2]; o.w = x[3];
+                                *reinterpret_cast<float4_a4*>(d) = o;
+                            } else {
+                                d[0] = x[0];
+                                if (e0[u] + 1u < width) d[1] = x[1];
+                                if (e0[u] + 2u < width) d[2] = x[2];
+                            }
+                        }
+                    }
                 }
             }
         }
@@ -443,17 +614,20 @@ void launch_compact(shifter_ctx* ctx, const shifter_model* m, const float* d_w, 
         // the unit counts are only known on the device: the grid covers the case that
         // nothing is removed; wavefronts past the real count exit at once
         ProfileScope p(ctx, K_GATHER);
-        if (d_thr && k_var > 1 && m->band_ok) {
-            // K rebuilds from one shared source: source order, see gather_band_kernel
-            // (measured: with K separate sparse arenas as the source there is nothing to
-            // share and the output-ordered kernel below is the faster one)
-            const uint32_t n_slots = m->band_prefix.back();
-            const uint32_t k_blocks = (k_var + BLOCK / 64 - 1) / (BLOCK / 64);
-            const uint32_t grid = std::max(1u, n_slots * k_blocks * 8u);
-            gather_band_kernel<<<grid, BLOCK, 0, ctx->stream>>>(
-                b.tens, b.groups, n_t, b.plan_t, b.band_prefix, b.plan_h, d_w, d_keep, d_w_out,
-                b.vecs, n_v, b.plan_v, d_vecs, d_vecs_out, w_stride, m->info.sum_group_width,
-                cap_w, cap_v, d_thr, k_var, k_blocks, n_slots);
+        if (d_thr && k_var > 1 && m->rect_ok && m->rect_prefix.back() > 0) {
+            // K rebuilds from one shared source: one read of it, see gather_rect_kernel
+            // (with K separate sparse arenas as the source there is nothing to share and
+            // the output-ordered kernel below is used)
+            const uint32_t n_rects = m->rect_prefix.back();
+            const uint32_t n_tab = m->rowtab_prefix.back() + m->coltab_prefix.back();
+            rect_tables_kernel<<<dim3((n_tab + BLOCK - 1) / BLOCK, k_var), BLOCK, 0, ctx->stream>>>(
+                b.tens, b.groups, n_t, b.rowtab_prefix, b.coltab_prefix, d_keep, d_new_width,
+                m->info.sum_group_width, (uint32_t)m->g.size(), b.rowtab, b.coltab);
+            gather_rect_kernel<<<std::max(1u, n_rects), BLOCK, 0, ctx->stream>>>(
+                b.tens, b.groups, n_t, b.plan_t, b.rect_prefix, b.rowtab_prefix, b.coltab_prefix,
+                b.rowtab, b.coltab, b.plan_h, d_w, m->info.w_extent, d_keep, d_w_out, b.vecs, n_v,
+                b.plan_v, d_vecs, d_vecs_out, m->info.sum_group_width, cap_w, cap_v, d_thr, k_var,
+                n_rects);
             return;
         }
         const uint32_t grid = std::max(1u, (m->gather_units_bound + BLOCK / 64 - 1) / (BLOCK / 64));
