@@ -207,10 +207,13 @@ extern "C" int shifter_model_create(const shifter_tensor_desc* tensors, uint32_t
                 m->rowtab_prefix.push_back(0);
                 m->coltab_prefix.push_back(0);
             }
-            if (m->rect_prefix.back() + bands * d.src_chunks >= (1ull << 31) ||
+            // blocks are dealt to the eight XCDs in turn: eight bands side by side, one per
+            // XCD, each XCD walking its band chunk by chunk (see gather_rect_kernel)
+            const uint64_t rects = (bands + 7) / 8 * 8 * d.src_chunks;
+            if (m->rect_prefix.back() + rects >= (1ull << 31) ||
                 m->rowtab_prefix.back() + bands + 1 >= (1ull << 31) / MAXK)
                 return bad("model too large for 32-bit gather unit indices", i);
-            m->rect_prefix.push_back(m->rect_prefix.back() + (uint32_t)(bands * d.src_chunks));
+            m->rect_prefix.push_back(m->rect_prefix.back() + (uint32_t)rects);
             m->rowtab_prefix.push_back(m->rowtab_prefix.back() + (uint32_t)bands + 1);
             m->coltab_prefix.push_back(m->coltab_prefix.back() + d.src_chunks + 1);
         }

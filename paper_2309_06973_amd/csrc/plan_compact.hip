@@ -378,11 +378,21 @@ __global__ __launch_bounds__(BLOCK) void gather_rect_kernel(
     __shared__ RectVariant meta[MAXK];
     __shared__ uint32_t next_k;
     const uint32_t lane = threadIdx.x & 63u;
+    uint32_t t = 0;
+    bool live = false;   // blocks past the last band of a tensor only help with the vectors
     if (blockIdx.x < n_rects) {
-        const uint32_t t = find_tensor(rect_prefix, n_t, blockIdx.x);
-        const DevTensor& T = tens[t];
+        t = find_tensor(rect_prefix, n_t, blockIdx.x);
         const uint32_t local = blockIdx.x - rect_prefix[t];
-        const uint32_t band = local / T.src_chunks, chunk = local - band * T.src_chunks;
+        live = (((local >> 3) / tens[t].src_chunks) * 8u + (local & 7u)) * tens[t].band_rows < tens[t].out_ch;
+    }
+    if (live) {
+        const DevTensor& T = tens[t];
+        // eight neighbouring blocks take the same chunk of eight neighbouring bands, so an
+        // XCD (blocks 8 apart) walks one band chunk by chunk and the pieces of a rebuilt
+        // filter meet in one L2 before they are written back
+        const uint32_t local = blockIdx.x - rect_prefix[t];
+        const uint32_t grp = (local >> 3) / T.src_chunks, chunk = (local >> 3) - grp * T.src_chunks;
+        const uint32_t band = grp * 8u + (local & 7u);
         const uint32_t kk = T.kk, row_len = T.row_len;
         const uint32_t r0 = band * T.band_rows, nr = min(T.band_rows, T.out_ch - r0);
         const uint32_t ch0 = chunk * T.chunk_ch, nch = min(T.chunk_ch, T.cin - ch0);
