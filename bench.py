@@ -75,13 +75,13 @@ def recorded_traffic(workload, kernel):
 
 def cpu_baseline_sample(spec, w, v, sparsity):
     """The oracle, as it stands, on a bounded sample of the workload: the leading layers
-    of the network up to ~40 M weights (same values), one variant."""
+    of the network up to ~120 M weights (same values), one variant."""
     import copy
     from oracle import shifter_oracle as O
     from paper_2309_06973_amd import synth
     n_t, tot = 0, 0
     for t in spec.tensors:
-        if tot + t.numel > 40_000_000 and n_t > 0:
+        if tot + t.numel > 120_000_000 and n_t > 0:
             break
         tot += t.numel
         n_t += 1
@@ -119,7 +119,7 @@ def measure(name, steps, warmup):
     if k_var > 1:
         pl.enable_batch(k_var)
 
-    def step(collect=None):
+    def step(collect=None, sparse_arenas=True):
         if k_var == 1:
             # one prune count: ranking, mask and scan in a single read of the arena
             pl.prune_fused(n_prune[0])
@@ -129,7 +129,8 @@ def measure(name, steps, warmup):
                 collect.append(out[3])
             return
         # a portfolio: one ranking call for all counts, then one batched call per step
-        _, out = pl.portfolio(n_prune, 0, with_in_alive=True, sync=True)
+        _, out = pl.portfolio(n_prune, 0, with_in_alive=True, sync=True,
+                              sparse_arenas=sparse_arenas)
         if collect is not None:
             collect.extend(int(x) for x in out[3])
 
@@ -188,6 +189,24 @@ def measure(name, steps, warmup):
     S.shifter_profile_enable(pl.ctx, False)
     copy_gbs = 8 * n / (c_ms / c_cnt * 1e-3) / 1e9
 
+    # the same portfolio without materialising the K sparse arenas (masks, flags, plans
+    # and rebuilt variants only): ranking 4N, one more read of the arena 4N, K masks, and
+    # 8N'_k per rebuilt variant
+    lean = None
+    if k_var > 1:
+        for _ in range(3):
+            step(sparse_arenas=False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step(sparse_arenas=False)
+        torch.cuda.synchronize()
+        dt2 = (time.perf_counter() - t0) / steps
+        b2 = 8 * n + sum(n + 8 * n2 for n2 in kept)
+        lean = {"ms_per_step": round(dt2 * 1e3, 4), "variants_per_s": round(k_var / dt2, 2),
+                "algorithmic_bytes_per_step": b2, "gbs": round(b2 / dt2 / 1e9, 2),
+                "pct_hbm_peak": round(100.0 * b2 / dt2 / 1e9 / HBM_PEAK_GBS, 2)}
+
     out = {
         "value": round(gbs, 2),
         "unit": "GB/s",
@@ -208,6 +227,8 @@ def measure(name, steps, warmup):
                         "frac_of_peak": round(copy_gbs / HBM_PEAK_GBS, 4)},
         "kernels": kernels,
     }
+    if lean is not None:
+        out["without_sparse_arenas"] = lean
     pl.close()
     del pl
     torch.cuda.empty_cache()

@@ -279,7 +279,9 @@ int shifter_compact(shifter_ctx* ctx, const shifter_model* model, const float* d
  * shifter_apply_mask_batch
  *   d_thr        device, K records (as written by shifter_global_threshold)
  *   d_w_out      device, K arenas, w_stride floats apart (w_stride >= w_extent, multiple
- *                of 4 for full speed); must not overlap d_w
+ *                of 4 for full speed); must not overlap d_w.  NULL: the sparse arenas
+ *                are not materialised (shifter_compact_batch_masked rebuilds from the
+ *                dense arena and d_thr); masks and flags are produced as usual
  *   d_mask       device, K masks, mask_stride bytes apart (>= N), or NULL
  *   d_out_alive  device, K * sum_out_ch bytes, required
  *   d_in_alive   device, K * sum_in_ch bytes, or NULL

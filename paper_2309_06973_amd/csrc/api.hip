@@ -615,14 +615,14 @@ extern "C" int shifter_apply_mask_batch(shifter_ctx* ctx, const shifter_model* m
                                        uint8_t* d_out_alive, uint8_t* d_in_alive) {
     int rc = enter(ctx, model, "apply_mask_batch");
     if (rc) return rc;
-    if (!d_w || !d_thr || !d_w_out || !d_out_alive)
+    if (!d_w || !d_thr || !d_out_alive)
         return fail(ctx, SHIFTER_ERR_INVALID_ARG, "apply_mask_batch: NULL pointer argument");
     if (K == 0 || K > MAXK)
         return fail(ctx, SHIFTER_ERR_INVALID_ARG, "apply_mask_batch: K must be in [1, SHIFTER_MAX_VARIANTS]");
     if (misaligned(d_w, 16) || misaligned(d_w_out, 16) || misaligned(d_mask, 4) || misaligned(d_thr, 8))
         return fail(ctx, SHIFTER_ERR_INVALID_ARG,
                     "apply_mask_batch: arenas must be 16-byte aligned, the masks 4-byte aligned");
-    if (w_stride < model->info.w_extent || (d_mask && mask_stride < model->info.n_prunable))
+    if ((d_w_out && w_stride < model->info.w_extent) || (d_mask && mask_stride < model->info.n_prunable))
         return fail(ctx, SHIFTER_ERR_INVALID_ARG, "apply_mask_batch: stride smaller than one variant");
     if (d_w_out == d_w)
         return fail(ctx, SHIFTER_ERR_INVALID_ARG, "apply_mask_batch: cannot work in place");

@@ -70,7 +70,9 @@ __global__ __launch_bounds__(BLOCK) void mask_scan_batch_kernel(
         }
     };
 
-    const bool vec_ok = n == TILE && (T.offset & 3u) == 0 && (w_stride & 3u) == 0 &&
+    // w_out == nullptr: the sparse arenas are not wanted (the rebuild can mask the dense
+    // arena on the way), only masks and levels are produced
+    const bool vec_ok = n == TILE && (T.offset & 3u) == 0 && (!w_out || (w_stride & 3u) == 0) &&
                         (!want_mask || ((T.gbase & 3u) == 0 && (mask_stride & 3u) == 0));
     if (vec_ok) {
         constexpr uint32_t U = TILE / BLOCK / 4;
@@ -97,8 +99,9 @@ __global__ __launch_bounds__(BLOCK) void mask_scan_batch_kernel(
                     o[q] = keep[q] ? b[q] : 0u;
                     lvl[u][q] += keep[q];
                 }
-                store_u4<NT>(reinterpret_cast<uint4*>(dst) + threadIdx.x + BLOCK * u,
-                             make_uint4(o[0], o[1], o[2], o[3]));
+                if (w_out)
+                    store_u4<NT>(reinterpret_cast<uint4*>(dst) + threadIdx.x + BLOCK * u,
+                                 make_uint4(o[0], o[1], o[2], o[3]));
                 if (mdst)
                     store_u1<NT>(reinterpret_cast<uint32_t*>(mdst) + threadIdx.x + BLOCK * u,
                                  keep[0] | (keep[1] << 8) | (keep[2] << 16) | (keep[3] << 24));
@@ -120,7 +123,8 @@ __global__ __launch_bounds__(BLOCK) void mask_scan_batch_kernel(
             for (uint32_t k = 0; k < k_var; ++k) {
                 const bool removed = ranked && comp < s_cut[k];
                 level += removed ? 0u : 1u;
-                w_out[(uint64_t)k * w_stride + T.offset + e0 + j] = removed ? 0.0f : __uint_as_float(bits);
+                if (w_out)
+                    w_out[(uint64_t)k * w_stride + T.offset + e0 + j] = removed ? 0.0f : __uint_as_float(bits);
                 if (want_mask) mask[(uint64_t)k * mask_stride + T.gbase + e0 + j] = removed ? 0 : 1;
             }
             mark(j, bits, level);

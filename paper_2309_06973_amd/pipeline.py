@@ -109,15 +109,18 @@ class Pipeline:
         self.b_vecs_out = torch.empty(k * self.cap_v, **f32)
 
     def portfolio(self, n_prune: Sequence[int], flags: int = 0, with_in_alive: bool = True,
-                  sync: bool = True, from_sparse: bool = False):
+                  sync: bool = True, from_sparse: bool = False, sparse_arenas: bool = True):
         """All five steps for every prune count: one ranking call, then one batched call
         per step.  The rebuild reads the dense arena and masks on the way unless
         from_sparse asks for the K sparse arenas as its source (same result).
-        Returns (threshold records, compact_batch's tuple)."""
+        sparse_arenas=False skips writing the K sparse arenas (masks, flags, plans and
+        rebuilt variants only).  Returns (threshold records, compact_batch's tuple)."""
+        assert sparse_arenas or not from_sparse
         k = len(n_prune)
         assert k == self.bk
         recs = self.global_threshold(n_prune, sync=True)
-        S.shifter_apply_mask_batch(self.ctx, self.model, self.d_w, self.d_thr, k, self.b_w_sparse,
+        S.shifter_apply_mask_batch(self.ctx, self.model, self.d_w, self.d_thr, k,
+                                   self.b_w_sparse if sparse_arenas else None,
                                    self.w_stride, self.b_mask, self.m_stride, self.b_out_alive,
                                    self.b_in_alive if with_in_alive else None)
         S.shifter_propagate_groups_batch(self.ctx, self.model, self.b_out_alive, k, flags,

@@ -300,33 +300,41 @@ def check_batch(spec, w, v, n_prune, flags=0, check=None, with_in_alive=True):
     try:
         pl.enable_batch(k_var)
         info = pl.model.info
-        for from_sparse in (False, True):
-            # the rebuild from the dense arena (masking on the way) and from the K sparse arenas
+        for from_sparse, sparse_arenas in ((False, True), (True, True), (False, False)):
+            # the rebuild from the dense arena (masking on the way), from the K sparse
+            # arenas, and from the dense arena with no sparse arenas written at all
             pl.b_w_out.fill_(float("nan"))
             pl.b_vecs_out.fill_(float("nan"))
-            _check_batch_run(pl, spec, refs, a, n_prune, flags, check, with_in_alive, from_sparse)
+            pl.b_w_sparse.fill_(float("nan"))
+            _check_batch_run(pl, spec, refs, a, n_prune, flags, check, with_in_alive, from_sparse,
+                             sparse_arenas)
     finally:
         pl.close()
 
 
-def _check_batch_run(pl, spec, refs, a, n_prune, flags, check, with_in_alive, from_sparse):
+def _check_batch_run(pl, spec, refs, a, n_prune, flags, check, with_in_alive, from_sparse,
+                     sparse_arenas):
     info = pl.model.info
     k_var = len(n_prune)
     recs, (rc, ots, ovs, ews, evs) = pl.portfolio(n_prune, flags, with_in_alive,
-                                                  from_sparse=from_sparse)
+                                                  from_sparse=from_sparse,
+                                                  sparse_arenas=sparse_arenas)
     torch.cuda.synchronize()
     collapse = any((r.plan.new_width == 0).any() for r in refs)
     assert rc == (S.SHIFTER_WARN_COLLAPSE if collapse else S.SHIFTER_OK)
     n = info.n_prunable
     for k in (check if check is not None else range(k_var)):
-        ref, lab = refs[k], f"{spec.name} batch k={k} from_sparse={from_sparse}"
+        ref, lab = refs[k], f"{spec.name} batch k={k} from_sparse={from_sparse} sparse_arenas={sparse_arenas}"
         check_threshold(recs[k], ref.sel, a)
         mask = pl.b_mask[k * pl.m_stride:k * pl.m_stride + n].cpu().numpy()
         assert np.array_equal(mask, ref.mask), lab + " mask"
         ws = pl.b_w_sparse[k * pl.w_stride:(k + 1) * pl.w_stride].cpu().numpy()
         for t in spec.tensors:
             sl = slice(t.offset, t.offset + t.numel)
-            assert np.array_equal(bits(ws[sl]), bits(ref.w_sparse[sl])), lab + " sparse"
+            if sparse_arenas:
+                assert np.array_equal(bits(ws[sl]), bits(ref.w_sparse[sl])), lab + " sparse"
+            else:
+                assert np.isnan(ws[sl]).all(), lab + " sparse arena written though not asked for"
         so, si, sg = info.sum_out_ch, info.sum_in_ch, info.sum_group_width
         oa = pl.b_out_alive[k * so:(k + 1) * so].cpu().numpy()
         assert np.array_equal(oa, np.concatenate(ref.out_alive)), lab + " out_alive"
