@@ -8,7 +8,7 @@ HBM before the timed region starts.  Prints ONE JSON line: the headline workload
 the other full-size workloads of the target under "other_workloads".
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5|c5p|c4|c2|c3|c1]
-                  [--others c4,c5p | --others none] [--no-cpu-baseline]
+                  [--others c4,c5p | --others none] [--no-cpu-baseline] [--no-lean]
 """
 import argparse
 import hashlib
@@ -102,7 +102,7 @@ def cpu_baseline_sample(spec, w, v, sparsity):
                       f"{1.0 / dt:.4f} variants/s"}
 
 
-def measure(name, steps, warmup):
+def measure(name, steps, warmup, lean_run=True):
     """Times `steps` steps of one workload; returns the fields of its report."""
     import torch
     from paper_2309_06973_amd import shifter as S
@@ -193,7 +193,7 @@ def measure(name, steps, warmup):
     # and rebuilt variants only): ranking 4N, one more read of the arena 4N, K masks, and
     # 8N'_k per rebuilt variant
     lean = None
-    if k_var > 1:
+    if k_var > 1 and lean_run:
         for _ in range(3):
             step(sparse_arenas=False)
         torch.cuda.synchronize()
@@ -245,6 +245,8 @@ def main():
                     help="comma-separated workloads also measured (default: c5p,c4 with "
                          "the default workload, none otherwise)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-lean", action="store_true",
+                    help="skip the extra timing of portfolios without sparse arenas")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 (the pass "
@@ -270,7 +272,8 @@ def main():
         if o not in WORKLOADS:
             ap.error(f"unknown workload {o!r}")
 
-    main_out, (spec, w, v, sparsities) = measure(args.workload, args.steps, args.warmup)
+    main_out, (spec, w, v, sparsities) = measure(args.workload, args.steps, args.warmup,
+                                                  not args.no_lean)
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline_sample(spec, w, v, sparsities[-1])
@@ -299,7 +302,7 @@ def main():
         # sorted so that workloads sharing an arena are generated once
         out["other_workloads"] = {}
         for o in sorted(others, key=lambda o: (WORKLOADS[o][0] != WORKLOADS[args.workload][0], o)):
-            res, _ = measure(o, args.steps, args.warmup)
+            res, _ = measure(o, args.steps, args.warmup, not args.no_lean)
             out["other_workloads"][o] = res
     print(json.dumps(out))
 
