@@ -19,6 +19,11 @@ The method is exact, so each function is the plain definition written out:
 * ``compact``            - Module 4 / Algorithm 2 (Model Pruner): new smaller layers
   holding the surviving out-channels, their per-channel vectors, and the surviving
   in-channels.
+* ``kernel_scan`` / ``propagate_groups_fixpoint`` - an extension beyond Algorithm 1's
+  single pass, on Module 2's kernel-level zero index: a channel also goes when every
+  non-zero kernel writing it reads a removed channel, or when no surviving filter reads
+  it through a non-zero kernel; repeated until nothing changes (the largest set of
+  channels that is consistent with both rules).
 
 Every function is pinned by tests that do not go through it (brute-force rank
 counting, closed forms, hand-enumerated toy networks, Algorithm 1 on a chain, forward
@@ -37,6 +42,7 @@ import numpy as np
 
 FLAG_JOINT = 0            # residual-add groups pruned jointly
 FLAG_FREEZE_RESIDUAL = 1  # Sec. IV-B.2: skip / downsample connections left untouched
+FLAG_FIXPOINT = 2         # liveness fixpoint on the kernel-level zero index (extension)
 
 
 def _numel(t) -> int:
@@ -156,6 +162,70 @@ def propagate_groups(tensors, groups, out_alive, flags: int = FLAG_JOINT) -> Pla
     return Plan(alive, index_map, keep, new_width)
 
 
+def kernel_scan(w_sparse: np.ndarray, tensors) -> List[np.ndarray]:
+    """Module 2's kernel-level index: nz[t][o, i] = 1 iff the kh x kw kernel of filter o
+    and input feature i of tensor t holds a non-zero (-0.0 counts as zero)."""
+    out = []
+    for t in tensors:
+        x = w_sparse[t.offset:t.offset + _numel(t)].reshape(t.out_ch, t.in_ch,
+                                                             t.kh * t.kw)
+        out.append((x != 0).any(axis=2).astype(np.uint8))
+    return out
+
+
+def propagate_groups_fixpoint(tensors, groups, kernel_nz, flags: int = FLAG_FIXPOINT) -> Plan:
+    """Prune plan with liveness propagated to a fixpoint.
+
+    Start from every channel alive.  A channel c of a group that is neither pinned nor
+    frozen stays alive only if
+      * it is produced: some tensor writing the group has, in filter c, a non-zero kernel
+        whose input feature belongs to an alive channel of that tensor's in-group, and
+      * it is read: some tensor reading the group has a non-zero kernel on one of the
+        input features of c in a filter whose out-channel is alive.
+    Channels failing either rule are removed and the rules are applied again until no
+    channel changes.  Removal only ever makes more channels fail, so the result is the
+    largest rule-consistent set whatever the order of removal."""
+    n_g = len(groups)
+    producers = [[ti for ti, t in enumerate(tensors) if t.out_group == gi] for gi in range(n_g)]
+    consumers = [[ti for ti, t in enumerate(tensors) if t.in_group == gi] for gi in range(n_g)]
+    frozen = [bool(g.pinned) or bool((flags & FLAG_FREEZE_RESIDUAL) and len(producers[gi]) > 1)
+              for gi, g in enumerate(groups)]
+    alive = [np.ones(g.width, dtype=bool) for g in groups]
+    changed = True
+    while changed:
+        changed = False
+        new_alive = []
+        for gi, g in enumerate(groups):
+            if frozen[gi]:
+                new_alive.append(alive[gi])
+                continue
+            produced = np.zeros(g.width, dtype=bool)
+            for ti in producers[gi]:
+                t = tensors[ti]
+                feat_alive = np.repeat(alive[t.in_group], t.in_mult)        # per input feature
+                produced |= (kernel_nz[ti].astype(bool) & feat_alive[None, :]).any(axis=1)
+            read = np.zeros(g.width, dtype=bool)
+            for ti in consumers[gi]:
+                t = tensors[ti]
+                feat_read = (kernel_nz[ti].astype(bool) & alive[t.out_group][:, None]).any(axis=0)
+                read |= feat_read.reshape(g.width, t.in_mult).any(axis=1)
+            a = alive[gi] & produced & read
+            changed = changed or not np.array_equal(a, alive[gi])
+            new_alive.append(a)
+        alive = new_alive
+    alive_u8, index_map, keep = [], [], []
+    for gi, g in enumerate(groups):
+        a = alive[gi].astype(np.uint8)
+        k = np.flatnonzero(a).astype(np.uint32)
+        m = np.full(g.width, -1, dtype=np.int32)
+        m[k] = np.arange(k.size, dtype=np.int32)
+        alive_u8.append(a)
+        keep.append(k)
+        index_map.append(m)
+    new_width = np.array([k.size for k in keep], dtype=np.uint32)
+    return Plan(alive_u8, index_map, keep, new_width)
+
+
 @dataclass
 class Compacted:
     w: np.ndarray                 # compacted weight arena (dense, descriptor order)
@@ -215,7 +285,11 @@ def prune_and_compact(w, v, tensors, vecs, groups, n_prune: Sequence[int],
     for sel in select_pruned(w, tensors, n_prune):
         w_sparse, mask = apply_mask(w, tensors, sel)
         out_alive, in_alive = dead_channel_scan(w_sparse, tensors)
-        plan = propagate_groups(tensors, groups, out_alive, flags)
+        if flags & FLAG_FIXPOINT:
+            plan = propagate_groups_fixpoint(tensors, groups, kernel_scan(w_sparse, tensors),
+                                             flags)
+        else:
+            plan = propagate_groups(tensors, groups, out_alive, flags)
         res.append(VariantResult(sel, w_sparse, mask, out_alive, in_alive, plan,
                                  compact(w_sparse, v, tensors, vecs, plan)))
     return res
