@@ -58,6 +58,7 @@ typedef enum {
     SHIFTER_ERR_NO_DEVICE = 5,   /* no usable GPU                                     */
     SHIFTER_ERR_HIP = 6,         /* a HIP call failed                                 */
     SHIFTER_ERR_OOM = 7,         /* device or host allocation failed                  */
+    SHIFTER_ERR_INTERNAL = 8,    /* an invariant of the library did not hold           */
     SHIFTER_WARN_COLLAPSE = 100  /* some group has no surviving channel (layer
                                     collapse, Sec. IV-B.1); outputs are still valid    */
 } shifter_status;
@@ -115,6 +116,9 @@ typedef struct {
 #define SHIFTER_PAPER_FREEZE_RESIDUAL 1u  /* groups with several producers left whole:
                                              skip / downsample connections are not
                                              pruned (Sec. IV-B.2)                      */
+
+#define SHIFTER_GROUPS_FIXPOINT 2u        /* accepted (and implied) by
+                                             shifter_propagate_groups_fixpoint        */
 
 #define SHIFTER_MAX_VARIANTS 64u          /* prune counts per shifter_global_threshold */
 
@@ -245,6 +249,46 @@ int shifter_propagate_groups(shifter_ctx* ctx, const shifter_model* model,
                              uint32_t flags, uint8_t* d_group_alive,
                              int32_t* d_index_map, uint32_t* d_keep,
                              uint32_t* d_new_width, uint32_t* h_new_width);
+
+/* --- liveness fixpoint (an extension beyond Algorithm 1's single pass) --------------
+ *
+ * Module 2 indexes zero kernels before it indexes zero channels (Sec. III-D).  On that
+ * kernel-level index the plan can go further than Algorithm 1: a channel c of a group
+ * that is neither pinned nor frozen stays only while it is
+ *   produced: some tensor writing the group has, in filter c, a non-zero kernel whose
+ *             input feature belongs to a surviving channel, and
+ *   read:     some tensor reading the group has a non-zero kernel on a feature of c in a
+ *             filter whose channel survives.
+ * Starting from all channels, failing channels are removed and the rules applied again
+ * until nothing changes; the result is the largest rule-consistent set.  It is a subset
+ * of the single-pass plan.  (Under the convention that a removed channel emits 0, which
+ * Algorithm 2 already applies by dropping its bias, the rebuilt network computes the same
+ * function.)
+ *
+ * shifter_model_get_kernel_layout
+ *   h_kernel_off   host, n_tensors: offset of tensor t's [out_ch][in_ch] block in the
+ *                  kernel index, or NULL;  h_sum_kernels: its total length, or NULL
+ * shifter_kernel_scan
+ *   d_kernel_nz    device, sum_kernels bytes, fully written: byte kernel_off[t] +
+ *                  o * in_ch + i is 1 iff the kernel of filter o and input feature i of
+ *                  tensor t holds a non-zero (-0.0 counts as zero), else 0
+ * shifter_propagate_groups_fixpoint
+ *   d_kernel_nz    as written by shifter_kernel_scan
+ *   flags          SHIFTER_PAPER_FREEZE_RESIDUAL keeps groups with several producers
+ *                  whole; SHIFTER_GROUPS_FIXPOINT is accepted
+ *   outputs        as shifter_propagate_groups
+ *   h_rounds       host, number of rounds run (the last one removed nothing), or NULL
+ * The call waits for the stream after every round (the host decides whether another
+ * round is needed). */
+int shifter_model_get_kernel_layout(const shifter_model* model, uint64_t* h_kernel_off,
+                                    uint64_t* h_sum_kernels);
+int shifter_kernel_scan(shifter_ctx* ctx, const shifter_model* model, const float* d_w_sparse,
+                        uint8_t* d_kernel_nz);
+int shifter_propagate_groups_fixpoint(shifter_ctx* ctx, const shifter_model* model,
+                                      const uint8_t* d_kernel_nz, uint32_t flags,
+                                      uint8_t* d_group_alive, int32_t* d_index_map,
+                                      uint32_t* d_keep, uint32_t* d_new_width,
+                                      uint32_t* h_new_width, uint32_t* h_rounds);
 
 /* Module 4, Model Pruner (Algorithm 2, Sec. III-D): every layer rebuilt without its
  * prunable channels.  For tensor t with out-group A, in-group B, m = in_mult:

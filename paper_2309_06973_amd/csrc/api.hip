@@ -14,7 +14,7 @@ namespace shifter {
 const char* const kKernelNames[K_COUNT] = {
     "sel_init", "hist_round0", "hist_round1", "hist_round2", "select", "tie_count",
     "tie_final", "zero_flags", "mask_scan", "scan", "propagate", "plan", "gather",
-    "copy", "mask_scan_batch", "expand_levels", "spec_init", "spec_sample", "spec_predict", "spec_pass",
+    "copy", "kernel_scan", "fix_round", "mask_scan_batch", "expand_levels", "spec_init", "spec_sample", "spec_predict", "spec_pass",
     "spec_hist_locate", "spec_filter_rank", "spec_fixup"};
 
 ProfileScope::ProfileScope(shifter_ctx* c, int id) : ctx(c), idx(-1) {
@@ -82,7 +82,8 @@ static void unbind(shifter_model* m) {
     if (!b.ctx) return;
     (void)hipSetDevice(b.device);
     void* ptrs[] = {b.tens, b.groups, b.vecs, b.producers, b.tile_prefix, b.sel, b.ghist,
-                    b.tile_cnt, b.plan_t, b.plan_v, b.plan_h, b.out_tile_prefix, b.rect_prefix, b.rowtab_prefix, b.coltab_prefix, b.rowtab, b.coltab, b.levels, b.spec, b.shist,
+                    b.tile_cnt, b.plan_t, b.plan_v, b.plan_h, b.out_tile_prefix, b.rect_prefix, b.rowtab_prefix, b.coltab_prefix, b.rowtab, b.coltab, b.kernel_off, b.fix_prefix, b.cons_prefix, b.consumers, b.fix_alive,
+                    b.fix_produced, b.fix_read, b.fix_out_flags, b.fix_removed, b.levels, b.spec, b.shist,
                     b.spec_cnt, b.partial, b.cand, b.list, b.ranked_ids, b.multi, b.multi_cnt,
                     b.multi_partial, b.multi_seg, b.multi_seg_cnt};
     for (void* p : ptrs)
@@ -216,6 +217,15 @@ extern "C" int shifter_model_create(const shifter_tensor_desc* tensors, uint32_t
             m->rect_prefix.push_back(m->rect_prefix.back() + (uint32_t)rects);
             m->rowtab_prefix.push_back(m->rowtab_prefix.back() + (uint32_t)bands + 1);
             m->coltab_prefix.push_back(m->coltab_prefix.back() + d.src_chunks + 1);
+            // kernel-level index of the liveness fixpoint: one byte per (filter, feature),
+            // walked in tiles of 16 filters x 1024 features
+            m->kernel_off.push_back(m->sum_kernels);
+            m->sum_kernels += (uint64_t)t.out_ch * t.in_ch;
+            const uint64_t ft = (uint64_t)((t.out_ch + 15) / 16) * ((t.in_ch + 1023) / 1024);
+            if (m->fix_prefix.empty()) m->fix_prefix.push_back(0);
+            if (m->fix_prefix.back() + ft >= (1ull << 31))
+                return bad("model too large for 32-bit kernel-index tiles", i);
+            m->fix_prefix.push_back(m->fix_prefix.back() + (uint32_t)ft);
         }
         d.out_group = t.out_group;
         d.in_group = t.in_group;
@@ -242,6 +252,7 @@ extern "C" int shifter_model_create(const shifter_tensor_desc* tensors, uint32_t
         m->rowtab_prefix.push_back(0);
         m->coltab_prefix.push_back(0);
     }
+    if (m->fix_prefix.empty()) m->fix_prefix.push_back(0);
     std::sort(spans.begin(), spans.end());
     for (size_t i = 1; i < spans.size(); ++i)
         if (spans[i].first < spans[i - 1].second) return bad("tensors overlap in the weight arena", (uint32_t)i);
@@ -282,6 +293,13 @@ extern "C" int shifter_model_create(const shifter_tensor_desc* tensors, uint32_t
     for (size_t i = 1; i < spans.size(); ++i)
         if (spans[i].first < spans[i - 1].second) return bad("vectors overlap in the vector arena", (uint32_t)i);
 
+    // consumers of each group, in tensor order
+    for (uint32_t g = 0; g < n_groups; ++g) {
+        m->cons_prefix.push_back((uint32_t)m->consumers.size());
+        for (uint32_t i = 0; i < n_tensors; ++i)
+            if ((uint32_t)tensors[i].in_group == g) m->consumers.push_back(i);
+    }
+    m->cons_prefix.push_back((uint32_t)m->consumers.size());
     // producers of each group, in tensor order
     for (uint32_t g = 0; g < n_groups; ++g) {
         m->dg[g].prod_begin = (uint32_t)m->producers.size();
@@ -368,6 +386,15 @@ static int bind(shifter_ctx* ctx, const shifter_model* cm) {
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.plan_v), sizeof(PlanVec) * std::max<size_t>(n_v, 1) * MAXK));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.plan_h), sizeof(PlanHeader) * MAXK));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.out_tile_prefix), sizeof(uint32_t) * (n_t + 1) * MAXK));
+    if ((rc = upload(ctx, &b.kernel_off, m->kernel_off.data(), m->kernel_off.size()))) return rc;
+    if ((rc = upload(ctx, &b.fix_prefix, m->fix_prefix.data(), m->fix_prefix.size()))) return rc;
+    if ((rc = upload(ctx, &b.cons_prefix, m->cons_prefix.data(), m->cons_prefix.size()))) return rc;
+    if ((rc = upload(ctx, &b.consumers, m->consumers.data(), m->consumers.size()))) return rc;
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.fix_alive), std::max<uint64_t>(m->info.sum_group_width, 16)));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.fix_produced), std::max<uint64_t>(m->info.sum_out_ch, 16)));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.fix_read), std::max<uint64_t>(m->info.sum_in_ch, 16)));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.fix_out_flags), std::max<uint64_t>(m->info.sum_out_ch, 16)));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.fix_removed), 16));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.levels),
                            sizeof(uint32_t) * (m->info.sum_out_ch + m->info.sum_in_ch)));
     if ((rc = upload(ctx, &b.ranked_ids, m->ranked_ids.data(), m->ranked_ids.size()))) return rc;
@@ -672,6 +699,64 @@ extern "C" int shifter_propagate_groups(shifter_ctx* ctx, const shifter_model* m
     (void)d_in_alive;
     return shifter_propagate_groups_batch(ctx, model, d_out_alive, 1, flags, d_group_alive, d_index_map,
                                           d_keep, d_new_width, h_new_width);
+}
+
+extern "C" int shifter_model_get_kernel_layout(const shifter_model* model, uint64_t* h_kernel_off,
+                                               uint64_t* h_sum_kernels) {
+    if (!model) return fail(nullptr, SHIFTER_ERR_INVALID_ARG, "model_get_kernel_layout: model is NULL");
+    if (h_kernel_off)
+        for (size_t i = 0; i < model->kernel_off.size(); ++i) h_kernel_off[i] = model->kernel_off[i];
+    if (h_sum_kernels) *h_sum_kernels = model->sum_kernels;
+    return SHIFTER_OK;
+}
+
+extern "C" int shifter_kernel_scan(shifter_ctx* ctx, const shifter_model* model, const float* d_w_sparse,
+                                   uint8_t* d_kernel_nz) {
+    int rc = enter(ctx, model, "kernel_scan");
+    if (rc) return rc;
+    if (!d_w_sparse || !d_kernel_nz)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "kernel_scan: NULL pointer argument");
+    if (misaligned(d_w_sparse, 16))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "kernel_scan: arena must be 16-byte aligned");
+    launch_kernel_scan(ctx, model, d_w_sparse, d_kernel_nz);
+    return after_launch(ctx, "kernel_scan");
+}
+
+extern "C" int shifter_propagate_groups_fixpoint(shifter_ctx* ctx, const shifter_model* model,
+                                                 const uint8_t* d_kernel_nz, uint32_t flags,
+                                                 uint8_t* d_group_alive, int32_t* d_index_map,
+                                                 uint32_t* d_keep, uint32_t* d_new_width,
+                                                 uint32_t* h_new_width, uint32_t* h_rounds) {
+    int rc = enter(ctx, model, "propagate_groups_fixpoint");
+    if (rc) return rc;
+    if (!d_kernel_nz || !d_group_alive || !d_index_map || !d_keep || !d_new_width)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "propagate_groups_fixpoint: NULL pointer argument");
+    if (flags & ~(uint32_t)(SHIFTER_PAPER_FREEZE_RESIDUAL | SHIFTER_GROUPS_FIXPOINT))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "propagate_groups_fixpoint: unknown flag");
+    const auto& b = model->b;
+    launch_fix_begin(ctx, model);
+    // every round that changes something removes at least one channel
+    const uint64_t max_rounds = model->info.sum_group_width + 1;
+    uint32_t rounds = 0;
+    for (;;) {
+        launch_fix_round(ctx, model, d_kernel_nz, flags);
+        if ((rc = after_launch(ctx, "propagate_groups_fixpoint"))) return rc;
+        ++rounds;
+        uint8_t* st = b.host_stage;
+        HIP_TRY(ctx, hipMemcpyAsync(st, b.fix_removed, sizeof(uint32_t), hipMemcpyDeviceToHost, ctx->stream));
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+        uint32_t removed;
+        memcpy(&removed, st, sizeof removed);
+        if (removed == 0) break;
+        if (rounds > max_rounds)
+            return fail(ctx, SHIFTER_ERR_INTERNAL, "propagate_groups_fixpoint: did not settle");
+    }
+    if (h_rounds) *h_rounds = rounds;
+    launch_fix_out_flags(ctx, model);
+    if ((rc = after_launch(ctx, "propagate_groups_fixpoint"))) return rc;
+    return shifter_propagate_groups_batch(ctx, model, b.fix_out_flags, 1,
+                                          flags & SHIFTER_PAPER_FREEZE_RESIDUAL, d_group_alive,
+                                          d_index_map, d_keep, d_new_width, h_new_width);
 }
 
 // d_thr == NULL: d_w holds K sparse arenas w_stride apart; else d_w is the dense arena

@@ -137,7 +137,7 @@ struct PlanHeader {
 enum KernelId {
     K_SEL_INIT = 0, K_HIST0, K_HIST1, K_HIST2, K_SELECT, K_TIE_COUNT, K_TIE_FINAL,
     K_ZERO_FLAGS, K_MASK_SCAN, K_SCAN, K_PROPAGATE, K_PLAN, K_GATHER,
-    K_COPY, K_MASK_SCAN_BATCH, K_EXPAND_LEVELS, K_SPEC_INIT, K_SPEC_SAMPLE, K_SPEC_PREDICT, K_SPEC_PASS, K_SPEC_FINISH, K_SPEC_FINISH2, K_SPEC_FIXUP,
+    K_COPY, K_KERNEL_SCAN, K_FIX_ROUND, K_MASK_SCAN_BATCH, K_EXPAND_LEVELS, K_SPEC_INIT, K_SPEC_SAMPLE, K_SPEC_PREDICT, K_SPEC_PASS, K_SPEC_FINISH, K_SPEC_FINISH2, K_SPEC_FIXUP,
     K_COUNT
 };
 extern const char* const kKernelNames[K_COUNT];
@@ -165,6 +165,11 @@ struct shifter_model {
     // entries (bands + 1) and of its column-table entries (src_chunks + 1)
     std::vector<uint32_t> rect_prefix, rowtab_prefix, coltab_prefix;
     bool rect_ok = true;                 // every tensor has kk <= GATHER_CHUNK
+    // liveness fixpoint: offset of every tensor's [out_ch][in_ch] block in the kernel
+    // index, its size, tiles of that index per tensor (prefix sums), consumers per group
+    std::vector<uint64_t> kernel_off;
+    uint64_t sum_kernels = 0;
+    std::vector<uint32_t> fix_prefix, cons_prefix, consumers;
 
     // device side, created by the first call that uses the model with a context
     struct Bound {
@@ -188,6 +193,15 @@ struct shifter_model {
         uint32_t* rowtab = nullptr;           // MAXK * rowtab_prefix.back()
         uint32_t* coltab = nullptr;           // MAXK * coltab_prefix.back()
         uint32_t* levels = nullptr;           // sum_out_ch + sum_in_ch
+        uint64_t* kernel_off = nullptr;       // n_tensors
+        uint32_t* fix_prefix = nullptr;       // n_tensors + 1
+        uint32_t* cons_prefix = nullptr;      // n_groups + 1
+        uint32_t* consumers = nullptr;        // tensor indices, grouped by in_group
+        uint8_t* fix_alive = nullptr;         // sum_group_width
+        uint8_t* fix_produced = nullptr;      // sum_out_ch
+        uint8_t* fix_read = nullptr;          // sum_in_ch
+        uint8_t* fix_out_flags = nullptr;     // sum_out_ch
+        uint32_t* fix_removed = nullptr;      // 1
         shifter::SpecState* spec = nullptr;
         uint32_t* shist = nullptr;            // 65536 sample bins
         uint32_t* spec_cnt = nullptr;         // 2 * SPEC_SUB counters, one 128-byte line each
@@ -251,6 +265,10 @@ void launch_compact(shifter_ctx* ctx, const shifter_model* m, const float* d_w, 
                     float* d_vecs_out, uint64_t cap_v, uint32_t k_var,
                     const shifter_threshold* d_thr);
 void launch_copy(shifter_ctx* ctx, const float* src, float* dst, uint64_t n);
+void launch_kernel_scan(shifter_ctx* ctx, const shifter_model* m, const float* d_w, uint8_t* d_nz);
+void launch_fix_begin(shifter_ctx* ctx, const shifter_model* m);
+void launch_fix_round(shifter_ctx* ctx, const shifter_model* m, const uint8_t* d_nz, uint32_t flags);
+void launch_fix_out_flags(shifter_ctx* ctx, const shifter_model* m);
 
 // Event bracketing for per-kernel timing.
 struct ProfileScope {

@@ -78,6 +78,19 @@ class Pipeline:
                                           self.d_index_map, self.d_keep, self.d_new_width,
                                           sync)
 
+    def kernel_scan(self, src=None):
+        """Kernel-level zero index of the sparse arena (input of the liveness fixpoint)."""
+        if getattr(self, "d_kernel_nz", None) is None:
+            self.d_kernel_nz = torch.empty(max(self.model.sum_kernels, 16), dtype=torch.uint8,
+                                           device=self.dev)
+        S.shifter_kernel_scan(self.ctx, self.model, self.d_w_sparse if src is None else src,
+                              self.d_kernel_nz)
+
+    def propagate_groups_fixpoint(self, flags: int = 0):
+        return S.shifter_propagate_groups_fixpoint(self.ctx, self.model, self.d_kernel_nz, flags,
+                                                   self.d_group_alive, self.d_index_map,
+                                                   self.d_keep, self.d_new_width)
+
     def compact(self, sync: bool = True, src=None):
         return S.shifter_compact(self.ctx, self.model,
                                  self.d_w_sparse if src is None else src, self.d_vecs,

@@ -18,9 +18,11 @@ SHIFTER_ERR_CAPACITY = 4
 SHIFTER_ERR_NO_DEVICE = 5
 SHIFTER_ERR_HIP = 6
 SHIFTER_ERR_OOM = 7
+SHIFTER_ERR_INTERNAL = 8
 SHIFTER_WARN_COLLAPSE = 100
 SHIFTER_GROUPS_JOINT = 0
 SHIFTER_PAPER_FREEZE_RESIDUAL = 1
+SHIFTER_GROUPS_FIXPOINT = 2
 SHIFTER_MAX_VARIANTS = 64
 
 
@@ -100,6 +102,11 @@ EXPORTS = {
                                      C.c_void_p, C.c_uint64, C.POINTER(TensorDesc),
                                      C.POINTER(VecDesc), C.POINTER(C.c_uint64),
                                      C.POINTER(C.c_uint64)],
+    "shifter_model_get_kernel_layout": [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)],
+    "shifter_kernel_scan": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
+    "shifter_propagate_groups_fixpoint": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
+                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)],
     "shifter_profile_enable": [C.c_void_p, C.c_int],
     "shifter_profile_read": [C.c_void_p, C.POINTER(C.c_char_p), C.POINTER(C.c_uint32),
                              C.POINTER(C.c_double), C.c_uint32, C.POINTER(C.c_uint32)],
@@ -200,7 +207,13 @@ def shifter_model_create(tensors: Sequence, vecs: Sequence, groups: Sequence) ->
     i_ = (C.c_uint64 * info.n_tensors)()
     g_ = (C.c_uint64 * info.n_groups)()
     _check(lib.shifter_model_get_layout(h, o, i_, g_))
-    return Model(h, info, list(o), list(i_), list(g_))
+    model = Model(h, info, list(o), list(i_), list(g_))
+    ko = (C.c_uint64 * max(info.n_tensors, 1))()
+    sk = C.c_uint64()
+    _check(lib.shifter_model_get_kernel_layout(h, ko, C.byref(sk)))
+    model.kernel_off = list(ko)[:info.n_tensors]
+    model.sum_kernels = int(sk.value)
+    return model
 
 
 def shifter_model_destroy(model: Model) -> None:
@@ -269,6 +282,23 @@ def shifter_propagate_groups(ctx: Context, model: Model, d_out_alive, d_in_alive
         _ptr(d_group_alive), _ptr(d_index_map), _ptr(d_keep), _ptr(d_new_width), h),
         ctx.handle, allow=(SHIFTER_WARN_COLLAPSE,))
     return rc, (list(h) if sync else None)
+
+
+def shifter_kernel_scan(ctx: Context, model: Model, d_w_sparse, d_kernel_nz) -> None:
+    _check(load_library().shifter_kernel_scan(ctx.handle, model.handle, _ptr(d_w_sparse),
+                                              _ptr(d_kernel_nz)), ctx.handle)
+
+
+def shifter_propagate_groups_fixpoint(ctx: Context, model: Model, d_kernel_nz, flags: int,
+                                      d_group_alive, d_index_map, d_keep, d_new_width):
+    """Returns (status, new_width list, rounds).  Always waits."""
+    h = (C.c_uint32 * model.info.n_groups)()
+    rounds = C.c_uint32()
+    rc = _check(load_library().shifter_propagate_groups_fixpoint(
+        ctx.handle, model.handle, _ptr(d_kernel_nz), flags, _ptr(d_group_alive),
+        _ptr(d_index_map), _ptr(d_keep), _ptr(d_new_width), h, C.byref(rounds)),
+        ctx.handle, allow=(SHIFTER_WARN_COLLAPSE,))
+    return rc, list(h), int(rounds.value)
 
 
 def shifter_compact(ctx: Context, model: Model, d_w_sparse, d_vecs, d_keep, d_new_width,

@@ -412,3 +412,71 @@ def test_portfolio_ranking_takes_the_single_pass():
             check_threshold(rec, ref, a)
     finally:
         pl.close()
+
+
+# ----------------------------------------------------------------------------- liveness fixpoint
+def check_fixpoint(spec, w, v, p, flags=0):
+    """Kernel-level index, fixpoint plan and the rebuilt model against the oracle."""
+    ref = O.prune_and_compact(w, v, spec.tensors, spec.vecs, spec.groups, [p],
+                              flags | O.FLAG_FIXPOINT)[0]
+    nz_ref = O.kernel_scan(ref.w_sparse, spec.tensors)
+    pl = Pipeline(spec, w, v)
+    try:
+        pl.prune_fused(p)
+        pl.kernel_scan()
+        nz = pl.d_kernel_nz.cpu().numpy()
+        for ti, t in enumerate(spec.tensors):
+            o = pl.model.kernel_off[ti]
+            got = nz[o:o + t.out_ch * t.in_ch].reshape(t.out_ch, t.in_ch)
+            assert np.array_equal(got, nz_ref[ti]), f"{spec.name} kernel index of tensor {ti}"
+        rc, nw, rounds = pl.propagate_groups_fixpoint(flags | S.SHIFTER_GROUPS_FIXPOINT)
+        collapse = bool((ref.plan.new_width == 0).any())
+        assert rc == (S.SHIFTER_WARN_COLLAPSE if collapse else S.SHIFTER_OK)
+        assert rounds >= 1
+        assert np.array_equal(np.array(nw, dtype=np.uint32), ref.plan.new_width)
+        ga = pl.d_group_alive.cpu().numpy()
+        im = pl.d_index_map.cpu().numpy()
+        kp = pl.d_keep.cpu().numpy().view(np.uint32)
+        for gi, g in enumerate(spec.groups):
+            o = pl.model.group_off[gi]
+            assert np.array_equal(ga[o:o + g.width], ref.plan.alive[gi]), f"group {gi} alive"
+            assert np.array_equal(im[o:o + g.width], ref.plan.index_map[gi])
+            assert np.array_equal(kp[o:o + int(nw[gi])], ref.plan.keep[gi])
+        rc, ots, ovs, ew, ev = pl.compact()
+        assert ew == ref.compacted.w.size and ev == ref.compacted.v.size
+        assert np.array_equal(bits(pl.d_w_out[:ew].cpu().numpy()), bits(ref.compacted.w))
+        assert np.array_equal(bits(pl.d_vecs_out[:ev].cpu().numpy()), bits(ref.compacted.v))
+        return ref, rounds
+    finally:
+        pl.close()
+
+
+@pytest.mark.gpu
+def test_fixpoint_planted_chain_takes_several_rounds():
+    spec = synth.chain_spec([6, 5, 7], k=3)
+    w, v = synth.generate_weights(spec, 5)
+    t0, t1, t2 = spec.tensors[0], spec.tensors[1], spec.tensors[2]
+    w[t0.offset:t0.offset + t0.numel].reshape(t0.out_ch, t0.in_ch, 9)[2] = 0
+    x1 = w[t1.offset:t1.offset + t1.numel].reshape(t1.out_ch, t1.in_ch, 9)
+    x1[3, :2] = 0
+    x1[3, 3:] = 0
+    w[t2.offset:t2.offset + t2.numel].reshape(t2.out_ch, t2.in_ch, 9)[:, 1] = 0
+    ref, rounds = check_fixpoint(spec, w, v, 0)
+    assert ref.plan.keep[t1.out_group].tolist() == [0, 2, 4]
+    assert rounds >= 2
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("c,s", [(1, 0.9), (1, 0.5), (3, 0.8), (3, 0.93), (2, 0.9), (4, 0.9)])
+def test_fixpoint_configs(c, s):
+    spec, w, v = synth.generate_config(c)
+    check_fixpoint(spec, w, v, synth.prune_count(spec.n_prunable, s))
+
+
+@pytest.mark.gpu
+def test_fixpoint_residual_toy_joint_and_frozen():
+    spec = synth.residual_toy_spec(width=8, mid=6, n_blocks=3)
+    w, v = synth.generate_weights(spec, 21)
+    p = synth.prune_count(spec.n_prunable, 0.85)
+    for flags in (0, S.SHIFTER_PAPER_FREEZE_RESIDUAL):
+        check_fixpoint(spec, w, v, p, flags)
