@@ -207,6 +207,32 @@ def measure(name, steps, warmup, lean_run=True):
                 "algorithmic_bytes_per_step": b2, "gbs": round(b2 / dt2 / 1e9, 2),
                 "pct_hbm_peak": round(100.0 * b2 / dt2 / 1e9 / HBM_PEAK_GBS, 2)}
 
+    # the liveness-fixpoint plan (kernel-level index + rounds + rebuild) on the same sparse
+    # arena, for the single-variant workloads: what it costs and what it removes on top
+    fixpoint = None
+    if k_var == 1:
+        step()                      # the copy above overwrote the sparse arena
+        pl.kernel_scan()
+        pl.propagate_groups_fixpoint(0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            pl.kernel_scan()
+            _, _, rounds = pl.propagate_groups_fixpoint(0)
+            fout = pl.compact(sync=True)
+        torch.cuda.synchronize()
+        dt3 = (time.perf_counter() - t0) / steps
+        fixpoint = {"ms_per_step_scan_plan_rebuild": round(dt3 * 1e3, 4), "rounds": rounds,
+                    "kept_weights": int(fout[3]), "kept_weights_single_pass": int(kept[0])}
+        S.shifter_profile_enable(pl.ctx, True)
+        for _ in range(5):
+            pl.kernel_scan()
+        ks = S.shifter_profile_read(pl.ctx)
+        S.shifter_profile_enable(pl.ctx, False)
+        ks_ms = ks["kernel_scan"][1] / ks["kernel_scan"][0]
+        fixpoint["kernel_scan_us"] = round(ks_ms * 1e3, 2)
+        fixpoint["kernel_scan_read_gbs"] = round(4 * n / (ks_ms * 1e-3) / 1e9, 1)
+
     out = {
         "value": round(gbs, 2),
         "unit": "GB/s",
@@ -229,6 +255,8 @@ def measure(name, steps, warmup, lean_run=True):
     }
     if lean is not None:
         out["without_sparse_arenas"] = lean
+    if fixpoint is not None:
+        out["liveness_fixpoint"] = fixpoint
     pl.close()
     del pl
     torch.cuda.empty_cache()

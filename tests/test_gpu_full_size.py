@@ -81,6 +81,25 @@ def test_c5_single_sweep_fused(c5):
         assert np.array_equal(bits(pl.d_vecs_out[:ev].cpu().numpy()), bits(comp.v))
         for d, (off, o2, i2, kh, kw) in zip(ot, comp.tensor_shapes):
             assert (d.offset, d.out_ch, d.in_ch, d.kh, d.kw) == (off, o2, i2, kh, kw)
+        # the liveness fixpoint on the same sparse arena
+        nz_ref = O.kernel_scan(ws, spec.tensors)
+        plan_f = O.propagate_groups_fixpoint(spec.tensors, spec.groups, nz_ref)
+        comp_f = O.compact(ws, v, spec.tensors, spec.vecs, plan_f)
+        pl.kernel_scan()
+        rc, nw, rounds = pl.propagate_groups_fixpoint(0)
+        nz = pl.d_kernel_nz.cpu().numpy()
+        for ti, t in enumerate(spec.tensors):
+            o = pl.model.kernel_off[ti]
+            assert np.array_equal(nz[o:o + t.out_ch * t.in_ch].reshape(t.out_ch, t.in_ch), nz_ref[ti])
+        assert np.array_equal(np.array(nw, dtype=np.uint32), plan_f.new_width)
+        kp = pl.d_keep.cpu().numpy().view(np.uint32)
+        for gi in range(len(spec.groups)):
+            o = pl.model.group_off[gi]
+            assert np.array_equal(kp[o:o + plan_f.keep[gi].size], plan_f.keep[gi])
+        rc, ot, ov, ew, ev = pl.compact()
+        assert ew == comp_f.w.size and ev == comp_f.v.size and ew <= comp.w.size
+        assert np.array_equal(bits(pl.d_w_out[:ew].cpu().numpy()), bits(comp_f.w))
+        assert np.array_equal(bits(pl.d_vecs_out[:ev].cpu().numpy()), bits(comp_f.v))
     finally:
         pl.close()
 
