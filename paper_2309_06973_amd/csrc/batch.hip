@@ -12,6 +12,8 @@
 
 namespace shifter {
 
+typedef uint32_t uint4_a4 __attribute__((ext_vector_type(4), aligned(4)));   // dword-aligned
+
 // pos[k] = number of variants whose cut is smaller than variant k's (ties by index).
 __device__ __forceinline__ void load_cuts(const shifter_threshold* __restrict__ thr, uint32_t k_var,
                                           uint64_t* s_cut, uint32_t* s_pos) {
@@ -44,6 +46,7 @@ __global__ __launch_bounds__(BLOCK) void mask_scan_batch_kernel(
     __shared__ uint32_t colmax[TILE + 16];
     __shared__ uint64_t s_cut[MAXK];
     __shared__ uint32_t s_pos[MAXK];
+    __shared__ __align__(16) uint32_t s_xm[TILE / 4];   // mask words of the tile, per wavefront
 
     const uint32_t tile = blockIdx.x;
     const uint32_t t = find_tensor(tile_prefix, n_t, tile);
@@ -75,21 +78,29 @@ __global__ __launch_bounds__(BLOCK) void mask_scan_batch_kernel(
     const bool vec_ok = n == TILE && (T.offset & 3u) == 0 && (!w_out || (w_stride & 3u) == 0) &&
                         (!want_mask || ((T.gbase & 3u) == 0 && (mask_stride & 3u) == 0));
     if (vec_ok) {
+        // wavefront w owns the w-th quarter of the tile: quad 256 w + 64 u + lane in step u,
+        // so every load and store covers 1 KB and the wavefront's mask bytes are one
+        // contiguous KB - written with one 16-byte store per lane after a wavefront-local
+        // exchange through LDS (four 4-byte stores cost as much issue time as four
+        // 16-byte ones)
         constexpr uint32_t U = TILE / BLOCK / 4;
+        const uint32_t lane = threadIdx.x & 63u, wid = threadIdx.x >> 6;
+        const uint32_t q0 = wid * (64u * U) + lane;      // quad of step 0
         const uint4* s4 = reinterpret_cast<const uint4*>(src);
         uint4 v[U];
 #pragma unroll
-        for (uint32_t u = 0; u < U; ++u) v[u] = load_u4<NT>(s4 + threadIdx.x + BLOCK * u);
+        for (uint32_t u = 0; u < U; ++u) v[u] = load_u4<NT>(s4 + q0 + 64u * u);
         uint32_t lvl[U][4];
 #pragma unroll
         for (uint32_t u = 0; u < U; ++u) lvl[u][0] = lvl[u][1] = lvl[u][2] = lvl[u][3] = 0;
+        uint32_t* xm = s_xm + wid * (64u * U);
         for (uint32_t k = 0; k < k_var; ++k) {
             const uint64_t cut = ranked ? s_cut[k] : 0;
             float* dst = w_out + (uint64_t)k * w_stride + T.offset + e0;
             uint8_t* mdst = want_mask ? mask + (uint64_t)k * mask_stride + T.gbase + e0 : nullptr;
 #pragma unroll
             for (uint32_t u = 0; u < U; ++u) {
-                const uint32_t j = (threadIdx.x + BLOCK * u) * 4;
+                const uint32_t j = (q0 + 64u * u) * 4;
                 const uint32_t b[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
                 uint32_t o[4], keep[4];
 #pragma unroll
@@ -100,16 +111,27 @@ __global__ __launch_bounds__(BLOCK) void mask_scan_batch_kernel(
                     lvl[u][q] += keep[q];
                 }
                 if (w_out)
-                    store_u4<NT>(reinterpret_cast<uint4*>(dst) + threadIdx.x + BLOCK * u,
+                    store_u4<NT>(reinterpret_cast<uint4*>(dst) + q0 + 64u * u,
                                  make_uint4(o[0], o[1], o[2], o[3]));
-                if (mdst)
-                    store_u1<NT>(reinterpret_cast<uint32_t*>(mdst) + threadIdx.x + BLOCK * u,
-                                 keep[0] | (keep[1] << 8) | (keep[2] << 16) | (keep[3] << 24));
+                if (mdst) xm[64u * u + lane] = keep[0] | (keep[1] << 8) | (keep[2] << 16) | (keep[3] << 24);
+            }
+            if (mdst) {
+                // lanes exchange within their own wavefront only: order the LDS accesses
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                const uint4 mm = *reinterpret_cast<const uint4*>(xm + 4u * lane);
+                uint4_a4 out;
+                out.x = mm.x; out.y = mm.y; out.z = mm.z; out.w = mm.w;
+                *reinterpret_cast<uint4_a4*>(mdst + wid * (256u * U) + 16u * lane) = out;
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             }
         }
 #pragma unroll
         for (uint32_t u = 0; u < U; ++u) {
-            const uint32_t j = (threadIdx.x + BLOCK * u) * 4;
+            const uint32_t j = (q0 + 64u * u) * 4;
             mark(j, v[u].x, lvl[u][0]);
             mark(j + 1, v[u].y, lvl[u][1]);
             mark(j + 2, v[u].z, lvl[u][2]);
