@@ -345,6 +345,17 @@ int shifter_compact(shifter_ctx* ctx, const shifter_model* model, const float* d
  *   only) is applied while its weights are gathered, so the K rebuilds share one source
  *   and the K sparse arenas are not read again.  Outputs are identical to
  *   shifter_compact_batch on the arenas shifter_apply_mask_batch wrote for d_thr. */
+/* Steps 1-3 for the K prune counts of a portfolio in ONE read of the dense arena: the
+ * ranking of shifter_global_threshold (records in d_thr / h_thr, caller order) and the
+ * outputs of shifter_apply_mask_batch (d_w_out may be NULL, d_mask may be NULL, d_in_alive
+ * may be NULL), identical to calling the two in turn.  Always waits (the host decides
+ * whether the single pass was exact; if not, it runs the two calls instead).
+ * SHIFTER_ERR_NONFINITE if a prunable weight is NaN. */
+int shifter_prune_fused_batch(shifter_ctx* ctx, const shifter_model* model, const float* d_w,
+                              const uint64_t* h_n_prune, uint32_t K, shifter_threshold* d_thr,
+                              float* d_w_out, uint64_t w_stride, uint8_t* d_mask,
+                              uint64_t mask_stride, uint8_t* d_out_alive, uint8_t* d_in_alive,
+                              shifter_threshold* h_thr);
 int shifter_apply_mask_batch(shifter_ctx* ctx, const shifter_model* model, const float* d_w,
                              const shifter_threshold* d_thr, uint32_t K, float* d_w_out,
                              uint64_t w_stride, uint8_t* d_mask, uint64_t mask_stride,

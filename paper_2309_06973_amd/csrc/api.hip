@@ -504,7 +504,7 @@ extern "C" int shifter_global_threshold(shifter_ctx* ctx, const shifter_model* m
         if (k_eff <= SPEC_MULTI_MAXK) {
             std::stable_sort(idx, idx + k_eff, [&](uint32_t a, uint32_t b) { return pc.p[a] < pc.p[b]; });
             for (uint32_t i = 0; i < k_eff; ++i) { sp.p[i] = pc.p[idx[i]]; perm.v[i] = idx[i]; }
-            launch_spec_multi(ctx, model, d_w, sp, perm, k_eff, zero_mask, d_thr);
+            launch_spec_multi(ctx, model, d_w, sp, perm, k_eff, zero_mask, d_thr, nullptr);
             if ((rc = after_launch(ctx, "global_threshold"))) return rc;
             uint8_t* st = model->b.host_stage;
             HIP_TRY(ctx, hipMemcpyAsync(st, &model->b.multi->status, sizeof(uint32_t), hipMemcpyDeviceToHost, ctx->stream));
@@ -656,6 +656,69 @@ extern "C" int shifter_apply_mask_batch(shifter_ctx* ctx, const shifter_model* m
     launch_mask_scan_batch(ctx, model, d_w, d_thr, K, d_w_out, w_stride, d_mask, mask_stride,
                            d_out_alive, d_in_alive);
     return after_launch(ctx, "apply_mask_batch");
+}
+
+extern "C" int shifter_prune_fused_batch(shifter_ctx* ctx, const shifter_model* model, const float* d_w,
+                                         const uint64_t* h_n_prune, uint32_t K, shifter_threshold* d_thr,
+                                         float* d_w_out, uint64_t w_stride, uint8_t* d_mask,
+                                         uint64_t mask_stride, uint8_t* d_out_alive,
+                                         uint8_t* d_in_alive, shifter_threshold* h_thr) {
+    int rc = enter(ctx, model, "prune_fused_batch");
+    if (rc) return rc;
+    if (!d_w || !h_n_prune || !d_thr || !d_out_alive || !h_thr)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "prune_fused_batch: NULL pointer argument");
+    if (K == 0 || K > MAXK)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "prune_fused_batch: K must be in [1, SHIFTER_MAX_VARIANTS]");
+    if (misaligned(d_w, 16) || misaligned(d_w_out, 16) || misaligned(d_mask, 4) || misaligned(d_thr, 8))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG,
+                    "prune_fused_batch: arenas must be 16-byte aligned, the masks 4-byte aligned");
+    if ((d_w_out && w_stride < model->info.w_extent) || (d_mask && mask_stride < model->info.n_prunable))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "prune_fused_batch: stride smaller than one variant");
+    if (d_w_out == d_w)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "prune_fused_batch: cannot work in place");
+    PruneCounts pc, sp;
+    MultiPerm perm;
+    memset(&pc, 0, sizeof pc);
+    memset(&sp, 0, sizeof sp);
+    memset(&perm, 0, sizeof perm);
+    uint32_t idx[MAXK], k_eff = 0;
+    uint64_t zero_mask = 0;
+    for (uint32_t k = 0; k < K; ++k) {
+        if (h_n_prune[k] > model->info.n_prunable)
+            return fail(ctx, SHIFTER_ERR_INVALID_ARG, "prune_fused_batch: prune count exceeds N");
+        pc.p[k] = h_n_prune[k];
+        if (pc.p[k] == 0) zero_mask |= 1ull << k; else idx[k_eff++] = k;
+    }
+    if (ctx->select_path == 0 && k_eff <= SPEC_MULTI_MAXK) {
+        std::stable_sort(idx, idx + k_eff, [&](uint32_t a, uint32_t b) { return pc.p[a] < pc.p[b]; });
+        for (uint32_t i = 0; i < k_eff; ++i) { sp.p[i] = pc.p[idx[i]]; perm.v[i] = idx[i]; }
+        FusedBatch fb{K, d_w_out, w_stride, d_mask, mask_stride, d_out_alive, d_in_alive};
+        launch_spec_multi(ctx, model, d_w, sp, perm, k_eff, zero_mask, d_thr, &fb);
+        if ((rc = after_launch(ctx, "prune_fused_batch"))) return rc;
+        uint8_t* st = model->b.host_stage;
+        HIP_TRY(ctx, hipMemcpyAsync(st, &model->b.multi->status, sizeof(uint32_t), hipMemcpyDeviceToHost, ctx->stream));
+        HIP_TRY(ctx, hipMemcpyAsync(st + 64, d_thr, sizeof(shifter_threshold) * K, hipMemcpyDeviceToHost, ctx->stream));
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+        uint32_t status;
+        memcpy(&status, st, sizeof status);
+        if (status & 2u)
+            return fail(ctx, SHIFTER_ERR_NONFINITE, "prune_fused_batch: NaN among the prunable weights");
+        ctx->last_path = (status & 1u) ? 2 : 1;
+        if (!(status & 1u)) {
+            memcpy(h_thr, st + 64, sizeof(shifter_threshold) * K);
+            return SHIFTER_OK;
+        }
+        if (ctx->margin_sigmas < 64.0) ctx->margin_sigmas *= 2.0;
+    }
+    // the single pass could not decide (or is switched off, or too many counts): rank with
+    // the multi-pass select, then mask and scan
+    const int saved = ctx->select_path;
+    ctx->select_path = 1;
+    rc = shifter_global_threshold(ctx, model, d_w, h_n_prune, K, d_thr, h_thr);
+    ctx->select_path = saved;
+    if (rc) return rc;
+    return shifter_apply_mask_batch(ctx, model, d_w, d_thr, K, d_w_out, w_stride, d_mask, mask_stride,
+                                    d_out_alive, d_in_alive);
 }
 
 extern "C" int shifter_propagate_groups_batch(shifter_ctx* ctx, const shifter_model* model,

@@ -8,6 +8,8 @@
 // filter and per input feature: its LEVEL, the largest count of variants that keep one
 // of its non-zero weights.  A filter is alive in the variant holding the p-th smallest cut
 // iff its level exceeds p.  Levels are maxima, so they are order-independent.
+#include <algorithm>
+
 #include "dev_common.h"
 
 namespace shifter {
@@ -185,19 +187,31 @@ __global__ __launch_bounds__(BLOCK) void expand_levels_kernel(
     if (i < n_in && in_alive) in_alive[(uint64_t)k * n_in + i] = in_level[i] > s_pos[k] ? 1 : 0;
 }
 
+void launch_zero_levels(shifter_ctx* ctx, const shifter_model* m) {
+    const uint64_t n = m->info.sum_out_ch + m->info.sum_in_ch;
+    ProfileScope p(ctx, K_ZERO_FLAGS);
+    zero_u32_kernel<<<(uint32_t)((std::max<uint64_t>(n, 1) + BLOCK - 1) / BLOCK), BLOCK, 0, ctx->stream>>>(
+        m->b.levels, n);
+}
+
+void launch_expand_levels(shifter_ctx* ctx, const shifter_model* m, const shifter_threshold* d_thr,
+                          uint32_t k_var, uint8_t* d_out_alive, uint8_t* d_in_alive) {
+    const uint64_t n_out = m->info.sum_out_ch, n_in = m->info.sum_in_ch;
+    ProfileScope p(ctx, K_EXPAND_LEVELS);
+    const uint64_t mx = std::max<uint64_t>(n_out > n_in ? n_out : n_in, 1);
+    expand_levels_kernel<<<dim3((uint32_t)((mx + BLOCK - 1) / BLOCK), k_var), BLOCK, 0, ctx->stream>>>(
+        d_thr, k_var, m->b.levels, n_out, m->b.levels + n_out, n_in, d_out_alive, d_in_alive);
+}
+
 void launch_mask_scan_batch(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
                             const shifter_threshold* d_thr, uint32_t k_var, float* d_w_out,
                             uint64_t w_stride, uint8_t* d_mask, uint64_t mask_stride,
                             uint8_t* d_out_alive, uint8_t* d_in_alive) {
     const auto& b = m->b;
     const uint32_t n_t = (uint32_t)m->t.size();
-    const uint64_t n_out = m->info.sum_out_ch, n_in = m->info.sum_in_ch;
+    const uint64_t n_out = m->info.sum_out_ch;
     hipStream_t s = ctx->stream;
-    {
-        ProfileScope p(ctx, K_ZERO_FLAGS);
-        zero_u32_kernel<<<(uint32_t)((n_out + n_in + BLOCK - 1) / BLOCK), BLOCK, 0, s>>>(
-            b.levels, n_out + n_in);
-    }
+    launch_zero_levels(ctx, m);
     {
         ProfileScope p(ctx, K_MASK_SCAN_BATCH);
         // measured: with ten output streams per block the non-temporal hint costs about
@@ -209,12 +223,7 @@ void launch_mask_scan_batch(shifter_ctx* ctx, const shifter_model* m, const floa
         k<<<m->n_tiles, BLOCK, 0, s>>>(b.tens, b.tile_prefix, n_t, d_w, d_thr, k_var, d_w_out,
                                        w_stride, d_mask, mask_stride, b.levels, b.levels + n_out);
     }
-    {
-        ProfileScope p(ctx, K_EXPAND_LEVELS);
-        const uint64_t mx = n_out > n_in ? n_out : n_in;
-        expand_levels_kernel<<<dim3((uint32_t)((mx + BLOCK - 1) / BLOCK), k_var), BLOCK, 0, s>>>(
-            d_thr, k_var, b.levels, n_out, b.levels + n_out, n_in, d_out_alive, d_in_alive);
-    }
+    launch_expand_levels(ctx, m, d_thr, k_var, d_out_alive, d_in_alive);
 }
 
 }  // namespace shifter

@@ -101,6 +101,7 @@ struct MultiState {
     uint64_t r2[MAXK], less[MAXK];
     uint32_t perm[MAXK];   // original position of sorted rank k
     uint32_t lo[MAXK], hi[MAXK], sh[MAXK];
+    uint32_t mid[MAXK];    // predicted threshold key of rank k, lo <= mid <= hi, non-decreasing
     uint32_t bin[MAXK], bin_cnt[MAXK];
     uint32_t k, m_valid, status, pad;
 };
@@ -244,9 +245,23 @@ void launch_spec_select(shifter_ctx* ctx, const shifter_model* m, const float* d
                         shifter_threshold* d_thr, float* d_w_out, uint8_t* d_mask,
                         uint8_t* d_out_alive, uint8_t* d_in_alive);
 void launch_spec_sample(shifter_ctx* ctx, const shifter_model* m, const float* d_w);
+// Outputs of the fused portfolio pass (steps 1-3 in one read): k_all variants in caller order.
+struct FusedBatch {
+    uint32_t k_all;
+    float* d_w_out;          // or nullptr
+    uint64_t w_stride;
+    uint8_t* d_mask;         // or nullptr
+    uint64_t mask_stride;
+    uint8_t* d_out_alive;
+    uint8_t* d_in_alive;     // or nullptr
+};
 void launch_spec_multi(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
-                       const PruneCounts& sorted_p, const MultiPerm& perm, uint32_t k,
-                       uint64_t zero_mask, shifter_threshold* d_thr);
+                       const shifter::PruneCounts& sorted_p, const shifter::MultiPerm& perm,
+                       uint32_t k, uint64_t zero_mask, shifter_threshold* d_thr,
+                       const FusedBatch* fb);
+void launch_zero_levels(shifter_ctx* ctx, const shifter_model* m);
+void launch_expand_levels(shifter_ctx* ctx, const shifter_model* m, const shifter_threshold* d_thr,
+                          uint32_t k_var, uint8_t* d_out_alive, uint8_t* d_in_alive);
 void launch_mask_scan(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
                       const shifter_threshold* d_thr, float* d_w_out, uint8_t* d_mask,
                       uint8_t* d_out_alive, uint8_t* d_in_alive);

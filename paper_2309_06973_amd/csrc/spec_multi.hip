@@ -42,6 +42,7 @@ __global__ __launch_bounds__(BLOCK) void ms_init_kernel(MultiState* ms, uint32_t
         ms->perm[tid] = tid < k ? perm.v[tid] : 0;
         ms->lo[tid] = 0xffffffffu;     // padding sorts last in the searches
         ms->hi[tid] = 0xffffffffu;
+        ms->mid[tid] = 0xffffffffu;
         ms->sh[tid] = 0;
         ms->bin[tid] = 0;
         ms->bin_cnt[tid] = 0;
@@ -71,7 +72,7 @@ __global__ __launch_bounds__(BLOCK) void ms_predict_kernel(MultiState* ms,
     __shared__ uint32_t prefix[MS_BINS];          // 64 KB
     __shared__ uint64_t smem[BLOCK / 64 + 1];
     __shared__ uint32_t seg_sum[NSEG];
-    __shared__ uint32_t s_lo[MAXK], s_hi[MAXK];
+    __shared__ uint32_t s_lo[MAXK], s_hi[MAXK], s_mid[MAXK];
     const uint32_t lane = threadIdx.x & 63u, wid = threadIdx.x >> 6;
     // phase 1: segment sums
     for (uint32_t sg = wid; sg < NSEG; sg += BLOCK / 64) {
@@ -107,7 +108,7 @@ __global__ __launch_bounds__(BLOCK) void ms_predict_kernel(MultiState* ms,
     const uint32_t m = ms->m_valid;
     if (threadIdx.x < k_var) {
         const uint64_t p = ms->p[threadIdx.x];
-        uint32_t lo = 0, hi = 0x7fffffffu;
+        uint32_t lo = 0, hi = 0x7fffffffu, mid = 0;
         if (p > 0 && m >= 256 && n_prunable > 0 && total == m) {
             const double frac = (double)p / (double)n_prunable;
             const double centre = frac * (double)m;
@@ -124,21 +125,28 @@ __global__ __launch_bounds__(BLOCK) void ms_predict_kernel(MultiState* ms,
             const double r_lo = centre - delta, r_hi = centre + delta;
             if (r_lo > 0.0) lo = bin_of(r_lo) << MS_SHIFT;
             if (r_hi < (double)(m - 1)) hi = ((bin_of(r_hi) + 1u) << MS_SHIFT) - 1u;
+            mid = bin_of(min(max(centre, 0.0), (double)(m - 1))) << MS_SHIFT;
         }
         s_lo[threadIdx.x] = lo;
         s_hi[threadIdx.x] = hi;
+        s_mid[threadIdx.x] = mid;
     }
     __syncthreads();
     if (threadIdx.x == 0) {
         // widen so that both ends are non-decreasing in k (ranks are sorted by P)
         for (uint32_t k = 1; k < k_var; ++k) s_hi[k] = max(s_hi[k], s_hi[k - 1]);
         for (uint32_t k = k_var - 1; k > 0; --k) s_lo[k - 1] = min(s_lo[k - 1], s_lo[k]);
+        uint32_t prev_mid = 0;
         for (uint32_t k = 0; k < k_var; ++k) {
             uint32_t sh = 0;
             while (((s_hi[k] - s_lo[k]) >> sh) >= MF_BINS1) ++sh;
             ms->lo[k] = s_lo[k];
             ms->hi[k] = s_hi[k];
             ms->sh[k] = sh;
+            // provisional threshold of the fused pass: inside the interval, non-decreasing
+            prev_mid = max(prev_mid, min(max(s_mid[k], s_lo[k]), s_hi[k]));
+            ms->mid[k] = min(prev_mid, s_hi[k]);
+            prev_mid = ms->mid[k];
         }
     }
 }
@@ -497,9 +505,312 @@ __global__ __launch_bounds__(BLOCK) void ms_rank_kernel(MultiState* ms,
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Steps 1-3 for the K variants of a portfolio in ONE read of the arena: ms_pass_kernel's
+// counting and candidate capture merged with the batched mask pass.  For a weight with
+// j = #{r : lo_r <= key} over the sorted ranks, rank r removes it for sure when r >= j and
+// keeps it for sure when hi_r < key; in between it is a candidate of r.  The pass writes
+// every variant's sparse weight and mask byte - candidates provisionally - and the
+// levels of the weights that are no rank's candidate; ms_fixup_kernel, once the exact cuts
+// are known, rewrites the candidates written on the wrong side of their rank's cut (the
+// pass decides by the predicted threshold mid of the last rank) and adds their levels.
+// rv[v] = sorted rank of variant v, or -1 for a variant that removes nothing (P = 0).
+struct VariantRanks {
+    int32_t r[MAXK];
+};
+
+typedef uint32_t ms_uint4_a4 __attribute__((ext_vector_type(4), aligned(4)));   // dword-aligned
+
+template <bool NT>
+__global__ __launch_bounds__(BLOCK) void ms_fused_kernel(
+    const DevTensor* __restrict__ tens, const uint32_t* __restrict__ tile_prefix, uint32_t n_t,
+    const float* __restrict__ w, MultiState* ms, uint32_t* cnt, uint2* __restrict__ cand,
+    uint32_t cap_sb, VariantRanks rv, uint32_t k_all, float* __restrict__ w_out,
+    uint64_t w_stride, uint8_t* __restrict__ mask, uint64_t mask_stride, uint32_t* out_level,
+    uint32_t* in_level) {
+    __shared__ uint32_t rowmax[TILE + 16];
+    __shared__ uint32_t colmax[TILE + 16];
+    __shared__ uint32_t s_lo[MAXK + 1], s_hi[MAXK + 1], s_mid[MAXK + 1];
+    __shared__ int32_t s_rv[MAXK];
+    __shared__ uint8_t s_col[(SPEC_MULTI_MAXK + 1) * BLOCK];   // private counters, <= 16 each
+    __shared__ __align__(16) uint32_t s_xm[TILE / 4];
+    __shared__ uint32_t s_nan, s_base, s_wtot[BLOCK / 64];
+
+    const uint32_t tile = blockIdx.x;
+    const uint32_t t = find_tensor(tile_prefix, n_t, tile);
+    const DevTensor T = tens[t];
+    const uint32_t e0 = (tile - tile_prefix[t]) * TILE;
+    const uint32_t n = min(TILE, T.numel - e0);
+    const bool ranked = T.prunable != 0;
+    const uint32_t g0 = (uint32_t)(T.gbase + e0);
+    const uint32_t lane = threadIdx.x & 63u, wid = threadIdx.x >> 6;
+    const uint32_t sb = blockIdx.x & (SPEC_SUB - 1);
+    uint2* my_cand = cand + (size_t)sb * cap_sb;
+    const uint32_t k_var = ms->k;
+    const uint32_t c0 = e0 % T.khw, r0 = e0 % T.row_len;
+    const uint32_t nrows = (r0 + n - 1) / T.row_len + 1;
+    const uint32_t ncols = (c0 + n - 1) / T.khw + 1;
+    for (uint32_t s = threadIdx.x; s < nrows; s += BLOCK) rowmax[s] = 0;
+    for (uint32_t s = threadIdx.x; s < ncols; s += BLOCK) colmax[s] = 0;
+    if (threadIdx.x <= MAXK) {
+        s_lo[threadIdx.x] = threadIdx.x < MAXK ? ms->lo[threadIdx.x] : 0xffffffffu;
+        s_hi[threadIdx.x] = threadIdx.x < MAXK ? ms->hi[threadIdx.x] : 0xffffffffu;
+        s_mid[threadIdx.x] = threadIdx.x < MAXK ? ms->mid[threadIdx.x] : 0xffffffffu;
+    }
+    if (threadIdx.x < MAXK) s_rv[threadIdx.x] = rv.r[threadIdx.x];
+    for (uint32_t j = 0; j <= k_var; ++j) s_col[j * BLOCK + threadIdx.x] = 0;
+    if (threadIdx.x == 0) { s_nan = 0; s_base = 0; }
+    __syncthreads();
+
+    uint32_t nan = 0;
+    // number of ranks that keep one weight in what the pass writes (127 in tensors that are
+    // not ranked: no rank removes it) and whether it is a candidate; counts it under
+    // j = #{r : lo_r <= key}.  Ranks below j keep a weight that is no candidate.
+    auto classify = [&](uint32_t bits, bool& is_cand) -> uint32_t {
+        is_cand = false;
+        if (!ranked) return 127u;
+        const uint32_t key = bits & 0x7fffffffu;
+        nan |= key > 0x7f800000u ? 1u : 0u;
+        uint32_t j = 0;
+#pragma unroll
+        for (uint32_t step = MAXK / 2; step >= 1; step >>= 1)
+            if (s_lo[j + step - 1] <= key) j += step;
+        j += s_lo[j] <= key ? 1u : 0u;
+        is_cand = j >= 1 && key <= s_hi[j - 1];
+        s_col[j * BLOCK + threadIdx.x] += 1;
+        // a candidate is written as kept by the ranks below j - 1 and, by rank j - 1 (with
+        // intervals that do not overlap, the only rank it is a candidate of), iff it does
+        // not lie below that rank's predicted threshold
+        if (is_cand && key < s_mid[j - 1]) j -= 1;
+        return j;
+    };
+    auto mark = [&](uint32_t j, uint32_t bits, uint32_t level) {
+        if (level && (bits & 0x7fffffffu)) {
+            atomicMax(&rowmax[div_small(r0 + j, T.row_len, T.magic_row)], level);
+            atomicMax(&colmax[div_small(c0 + j, T.khw, T.magic_khw)], level);
+        }
+    };
+
+    const float* src = w + T.offset + e0;
+    const bool want_mask = ranked && mask != nullptr;
+    const bool vec_ok = n == TILE && (T.offset & 3u) == 0 && (!w_out || (w_stride & 3u) == 0) &&
+                        (!want_mask || ((T.gbase & 3u) == 0 && (mask_stride & 3u) == 0));
+    if (vec_ok) {
+        constexpr uint32_t U = TILE / BLOCK / 4;
+        const uint32_t q0 = wid * (64u * U) + lane;      // quad of step 0 (see the batched mask pass)
+        const uint4* s4 = reinterpret_cast<const uint4*>(src);
+        uint4 v[U];
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u) v[u] = load_u4<NT>(s4 + q0 + 64u * u);
+        uint32_t jj[U], cmask = 0, lvl[U][4];
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u) {
+            bool c_0, c_1, c_2, c_3;
+            const uint32_t j_0 = classify(v[u].x, c_0), j_1 = classify(v[u].y, c_1);
+            const uint32_t j_2 = classify(v[u].z, c_2), j_3 = classify(v[u].w, c_3);
+            jj[u] = j_0 | (j_1 << 8) | (j_2 << 16) | (j_3 << 24);
+            cmask |= ((c_0 ? 1u : 0u) | (c_1 ? 2u : 0u) | (c_2 ? 4u : 0u) | (c_3 ? 8u : 0u)) << (4 * u);
+            lvl[u][0] = lvl[u][1] = lvl[u][2] = lvl[u][3] = 0;
+        }
+        uint32_t* xm = s_xm + wid * (64u * U);
+        for (uint32_t k = 0; k < k_all; ++k) {
+            const int32_t r = s_rv[k];
+            float* dst = w_out + (uint64_t)k * w_stride + T.offset + e0;
+            uint8_t* mdst = want_mask ? mask + (uint64_t)k * mask_stride + T.gbase + e0 : nullptr;
+#pragma unroll
+            for (uint32_t u = 0; u < U; ++u) {
+                const uint32_t b[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+                uint32_t o[4], keep[4];
+#pragma unroll
+                for (uint32_t q = 0; q < 4; ++q) {
+                    keep[q] = r < (int32_t)((jj[u] >> (8 * q)) & 0xffu) ? 1u : 0u;
+                    o[q] = keep[q] ? b[q] : 0u;
+                    lvl[u][q] += keep[q];
+                }
+                if (w_out)
+                    store_u4<NT>(reinterpret_cast<uint4*>(dst) + q0 + 64u * u,
+                                 make_uint4(o[0], o[1], o[2], o[3]));
+                if (mdst) xm[64u * u + lane] = keep[0] | (keep[1] << 8) | (keep[2] << 16) | (keep[3] << 24);
+            }
+            if (mdst) {
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                const uint4 mm = *reinterpret_cast<const uint4*>(xm + 4u * lane);
+                ms_uint4_a4 out;
+                out.x = mm.x; out.y = mm.y; out.z = mm.z; out.w = mm.w;
+                *reinterpret_cast<ms_uint4_a4*>(mdst + wid * (256u * U) + 16u * lane) = out;
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            }
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u) {
+            const uint32_t j = (q0 + 64u * u) * 4;
+            const uint32_t b[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+            for (uint32_t q = 0; q < 4; ++q)
+                if (!(cmask & (1u << (4 * u + q)))) mark(j + q, b[q], lvl[u][q]);
+        }
+        // candidate pairs: one reservation per block in this block's sub-buffer
+        const uint32_t c = __popc(cmask);
+        uint32_t incl = c;
+        for (uint32_t d = 1; d < 64; d <<= 1) {
+            const uint32_t y = __shfl_up(incl, d, 64);
+            if (lane >= d) incl += y;
+        }
+        if (lane == 63) s_wtot[wid] = incl;
+        __syncthreads();
+        uint32_t woff = 0, btot = 0;
+#pragma unroll
+        for (uint32_t i = 0; i < BLOCK / 64; ++i) {
+            const uint32_t x = s_wtot[i];
+            if (i < wid) woff += x;
+            btot += x;
+        }
+        if (btot) {   // uniform over the block
+            if (threadIdx.x == 0) s_base = atomicAdd(mcnt(cnt, MC_CAND, sb), btot);
+            __syncthreads();
+            uint32_t pos = s_base + woff + incl - c;
+            if (cmask) {
+#pragma unroll
+                for (uint32_t u = 0; u < U; ++u) {
+                    const uint32_t j = (q0 + 64u * u) * 4;
+                    const uint32_t vv[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+                    for (uint32_t q = 0; q < 4; ++q) {
+                        if (cmask & (1u << (4 * u + q))) {
+                            if (pos < cap_sb) my_cand[pos] = make_uint2(vv[q], g0 + j + q);
+                            ++pos;
+                        }
+                    }
+                }
+            }
+        }
+    } else {
+        for (uint32_t j0 = 0; j0 < n; j0 += BLOCK) {
+            const uint32_t j = j0 + threadIdx.x;
+            if (j < n) {
+                const uint32_t bits = __float_as_uint(src[j]);
+                bool is_cand;
+                const uint32_t jr = classify(bits, is_cand);
+                uint32_t level = 0;
+                for (uint32_t k = 0; k < k_all; ++k) {
+                    const bool keep = s_rv[k] < (int32_t)jr;
+                    level += keep ? 1u : 0u;
+                    if (w_out)
+                        w_out[(uint64_t)k * w_stride + T.offset + e0 + j] = keep ? __uint_as_float(bits) : 0.0f;
+                    if (want_mask) mask[(uint64_t)k * mask_stride + T.gbase + e0 + j] = keep ? 1 : 0;
+                }
+                if (is_cand) {
+                    const uint32_t pos = atomicAdd(mcnt(cnt, MC_CAND, sb), 1u);
+                    if (pos < cap_sb) my_cand[pos] = make_uint2(bits, g0 + j);
+                } else {
+                    mark(j, bits, level);
+                }
+            }
+        }
+    }
+    for (uint32_t d = 32; d > 0; d >>= 1) nan |= __shfl_down(nan, d, 64);
+    if (lane == 0 && nan) s_nan = 1;
+    __syncthreads();
+    // column sums: four threads per j, a quarter of the columns each
+    if (ranked && threadIdx.x < 4 * (k_var + 1)) {
+        const uint32_t j = threadIdx.x >> 2, q = threadIdx.x & 3u;
+        uint32_t c = 0;
+        for (uint32_t i = 0; i < BLOCK / 4; ++i) c += s_col[j * BLOCK + ((i * 4 + q + j) & (BLOCK - 1))];
+        if (c) atomicAdd(mcnt(cnt, MC_BELOW + j, sb), c);
+    }
+    if (threadIdx.x == 0 && s_nan) atomicOr(&ms->status, 2u);
+    // levels of the tile's filters and input features
+    const uint32_t row_first = e0 / T.row_len;
+    for (uint32_t s = threadIdx.x; s < nrows; s += BLOCK) {
+        const uint32_t l = rowmax[s];
+        if (l) {
+            uint32_t* f = out_level + T.out_flag_off + row_first + s;
+            if (*f < l) atomicMax(f, l);
+        }
+    }
+    const uint32_t bfeat = (e0 / T.khw) % T.in_ch;
+    for (uint32_t s = threadIdx.x; s < ncols; s += BLOCK) {
+        const uint32_t l = colmax[s];
+        if (l) {
+            uint32_t* f = in_level + T.in_flag_off + mod_small(bfeat + s, T.in_ch, T.magic_in);
+            if (*f < l) atomicMax(f, l);
+        }
+    }
+}
+
+// Settles the candidates of ms_fused_kernel with the exact cuts: the pass wrote a
+// candidate of ranks [a, j) as kept in all of them but the last, and in rank j - 1 iff
+// key >= mid_{j-1}; here it is rewritten in every rank where that was the wrong side of
+// the exact cut, and its level (variants that keep it: those that remove nothing, the
+// ranks below a, and the ranks of [a, j) that keep it) goes into the level arrays.
+__global__ __launch_bounds__(BLOCK) void ms_fixup_kernel(
+    const DevTensor* __restrict__ tens, const uint32_t* __restrict__ ranked_ids, uint32_t n_ranked,
+    const MultiState* __restrict__ ms, const uint32_t* __restrict__ cnt,
+    const uint2* __restrict__ cand, uint32_t cap_sb, const shifter_threshold* __restrict__ thr,
+    uint32_t n_zero, float* __restrict__ w_out, uint64_t w_stride, uint8_t* __restrict__ mask,
+    uint64_t mask_stride, uint32_t* out_level, uint32_t* in_level) {
+    constexpr uint32_t LDS_T = 1024;
+    __shared__ uint32_t s_gbase[LDS_T];
+    __shared__ uint32_t s_lo[MAXK + 1], s_hi[MAXK + 1], s_mid[MAXK], s_perm[MAXK];
+    __shared__ uint64_t s_cut[MAXK];
+    if (ms->status & 1u) return;
+    const uint32_t k_var = ms->k;
+    const bool in_lds = n_ranked <= LDS_T;
+    if (in_lds)
+        for (uint32_t i = threadIdx.x; i < n_ranked; i += BLOCK)
+            s_gbase[i] = (uint32_t)tens[ranked_ids[i]].gbase;
+    if (threadIdx.x <= MAXK) {
+        s_lo[threadIdx.x] = threadIdx.x < MAXK ? ms->lo[threadIdx.x] : 0xffffffffu;
+        s_hi[threadIdx.x] = threadIdx.x < MAXK ? ms->hi[threadIdx.x] : 0xffffffffu;
+    }
+    if (threadIdx.x < k_var) {
+        s_perm[threadIdx.x] = ms->perm[threadIdx.x];
+        s_cut[threadIdx.x] = thr[ms->perm[threadIdx.x]].cut;
+        s_mid[threadIdx.x] = ms->mid[threadIdx.x];
+    }
+    __syncthreads();
+    ms_for_each_candidate(cnt, cand, cap_sb, [&](uint2 c, bool valid) {
+        if (!valid) return;
+        const uint32_t key = c.x & 0x7fffffffu;
+        uint32_t ka, kb;
+        rank_range(s_lo, s_hi, key, &ka, &kb);
+        kb = min(kb, k_var);
+        const uint64_t comp = ((uint64_t)key << 32) | c.y;
+        uint32_t a = 0, b = n_ranked;   // tensor holding global index c.y
+        while (b - a > 1) {
+            const uint32_t m2 = (a + b) >> 1;
+            const uint32_t gb = in_lds ? s_gbase[m2] : (uint32_t)tens[ranked_ids[m2]].gbase;
+            if (gb <= c.y) a = m2; else b = m2;
+        }
+        const DevTensor& T = tens[ranked_ids[a]];
+        const uint32_t e = c.y - (uint32_t)T.gbase;
+        uint32_t level = n_zero + ka;
+        for (uint32_t r = ka; r < kb; ++r) {
+            const bool removed = comp < s_cut[r];
+            const bool written_removed = r + 1 == kb && key < s_mid[r];
+            if (removed != written_removed) {    // written on the wrong side of the exact cut
+                const uint32_t v = s_perm[r];
+                if (w_out) w_out[(uint64_t)v * w_stride + T.offset + e] = removed ? 0.0f : __uint_as_float(c.x);
+                if (mask) mask[(uint64_t)v * mask_stride + c.y] = removed ? 0 : 1;
+            }
+            level += removed ? 0u : 1u;
+        }
+        if (key != 0 && level != 0) {
+            uint32_t* f = out_level + T.out_flag_off + e / T.row_len;
+            if (*f < level) atomicMax(f, level);
+            f = in_level + T.in_flag_off + (e / T.khw) % T.in_ch;
+            if (*f < level) atomicMax(f, level);
+        }
+    });
+}
+
 void launch_spec_multi(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
                        const PruneCounts& sorted_p, const MultiPerm& perm, uint32_t k,
-                       uint64_t zero_mask, shifter_threshold* d_thr) {
+                       uint64_t zero_mask, shifter_threshold* d_thr, const FusedBatch* fb) {
     const auto& b = m->b;
     const uint32_t n_t = (uint32_t)m->t.size();
     hipStream_t s = ctx->stream;
@@ -508,34 +819,60 @@ void launch_spec_multi(shifter_ctx* ctx, const shifter_model* m, const float* d_
         ms_init_kernel<<<64, BLOCK, 0, s>>>(b.multi, b.shist, b.multi_cnt, sorted_p, perm, k,
                                             m->sample_size, zero_mask, d_thr);
     }
-    if (k == 0) return;   // every count was zero
-    {
-        ProfileScope ps(ctx, K_SPEC_SAMPLE);
-        launch_spec_sample(ctx, m, d_w);
+    if (k == 0 && !fb) return;   // every count was zero
+    if (k != 0) {
+        {
+            ProfileScope ps(ctx, K_SPEC_SAMPLE);
+            launch_spec_sample(ctx, m, d_w);
+        }
+        {
+            ProfileScope ps(ctx, K_SPEC_PREDICT);
+            ms_predict_kernel<<<1, BLOCK, 0, s>>>(b.multi, b.shist, m->info.n_prunable,
+                                                  ctx->margin_sigmas);
+        }
     }
-    {
-        ProfileScope ps(ctx, K_SPEC_PREDICT);
-        ms_predict_kernel<<<1, BLOCK, 0, s>>>(b.multi, b.shist, m->info.n_prunable,
-                                              ctx->margin_sigmas);
-    }
-    {
+    const bool nt = m->info.w_extent * 4 > (192ull << 20);
+    if (fb) {
+        VariantRanks rv;
+        for (uint32_t v = 0; v < MAXK; ++v) rv.r[v] = -1;
+        for (uint32_t r = 0; r < k; ++r) rv.r[perm.v[r]] = (int32_t)r;
+        launch_zero_levels(ctx, m);
+        ProfileScope ps(ctx, K_MASK_SCAN_BATCH);
+        // non-temporal hint as in the batched mask pass: only for cache-sized arenas
+        auto kern = !nt ? ms_fused_kernel<true> : ms_fused_kernel<false>;
+        kern<<<m->n_tiles, BLOCK, 0, s>>>(b.tens, b.tile_prefix, n_t, d_w, b.multi, b.multi_cnt, b.cand,
+                                          b.cand_cap_sb, rv, fb->k_all, fb->d_w_out, fb->w_stride,
+                                          fb->d_mask, fb->mask_stride, b.levels,
+                                          b.levels + m->info.sum_out_ch);
+    } else {
         ProfileScope ps(ctx, K_SPEC_PASS);
-        const bool nt = m->info.w_extent * 4 > (192ull << 20);
         auto kern = nt ? ms_pass_kernel<true> : ms_pass_kernel<false>;
         kern<<<m->n_tiles, BLOCK, 0, s>>>(b.tens, b.tile_prefix, n_t, d_w, b.multi, b.multi_cnt,
                                           b.cand, b.cand_cap_sb);
     }
-    {
-        ProfileScope ps(ctx, K_SPEC_FINISH);
-        ms_hist_kernel<<<MF_BLOCKS, BLOCK, k * MF_BINS1 * sizeof(uint32_t), s>>>(
-            b.multi, b.multi_cnt, b.cand, b.cand_cap_sb, b.multi_partial);
-        ms_locate_kernel<<<k, BLOCK, 0, s>>>(b.multi, b.multi_cnt, b.multi_partial, b.cand_cap_sb);
+    if (k != 0) {
+        {
+            ProfileScope ps(ctx, K_SPEC_FINISH);
+            ms_hist_kernel<<<MF_BLOCKS, BLOCK, k * MF_BINS1 * sizeof(uint32_t), s>>>(
+                b.multi, b.multi_cnt, b.cand, b.cand_cap_sb, b.multi_partial);
+            ms_locate_kernel<<<k, BLOCK, 0, s>>>(b.multi, b.multi_cnt, b.multi_partial, b.cand_cap_sb);
+        }
+        {
+            ProfileScope ps(ctx, K_SPEC_FINISH2);
+            ms_filter_kernel<<<MF_BLOCKS, BLOCK, 0, s>>>(b.multi, b.multi_cnt, b.cand, b.cand_cap_sb,
+                                                         b.multi_seg, b.multi_seg_cnt);
+            ms_rank_kernel<<<k, BLOCK, 0, s>>>(b.multi, b.multi_seg, b.multi_seg_cnt, d_thr);
+        }
     }
-    {
-        ProfileScope ps(ctx, K_SPEC_FINISH2);
-        ms_filter_kernel<<<MF_BLOCKS, BLOCK, 0, s>>>(b.multi, b.multi_cnt, b.cand, b.cand_cap_sb,
-                                                     b.multi_seg, b.multi_seg_cnt);
-        ms_rank_kernel<<<k, BLOCK, 0, s>>>(b.multi, b.multi_seg, b.multi_seg_cnt, d_thr);
+    if (fb) {
+        if (k != 0) {
+            ProfileScope ps(ctx, K_SPEC_FIXUP);
+            ms_fixup_kernel<<<MF_BLOCKS * 4, BLOCK, 0, s>>>(
+                b.tens, b.ranked_ids, m->n_ranked, b.multi, b.multi_cnt, b.cand, b.cand_cap_sb, d_thr,
+                fb->k_all - k, fb->d_w_out, fb->w_stride, fb->d_mask, fb->mask_stride, b.levels,
+                b.levels + m->info.sum_out_ch);
+        }
+        launch_expand_levels(ctx, m, d_thr, fb->k_all, fb->d_out_alive, fb->d_in_alive);
     }
 }
 

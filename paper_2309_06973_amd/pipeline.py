@@ -122,20 +122,33 @@ class Pipeline:
         self.b_vecs_out = torch.empty(k * self.cap_v, **f32)
 
     def portfolio(self, n_prune: Sequence[int], flags: int = 0, with_in_alive: bool = True,
-                  sync: bool = True, from_sparse: bool = False, sparse_arenas: bool = True):
-        """All five steps for every prune count: one ranking call, then one batched call
-        per step.  The rebuild reads the dense arena and masks on the way unless
-        from_sparse asks for the K sparse arenas as its source (same result).
-        sparse_arenas=False skips writing the K sparse arenas (masks, flags, plans and
-        rebuilt variants only).  Returns (threshold records, compact_batch's tuple)."""
+                  sync: bool = True, from_sparse: bool = False, sparse_arenas: bool = True,
+                  fused: Optional[bool] = None):
+        """All five steps for every prune count.  fused: ranking, masks and flags in one read
+        of the arena (else one ranking call, then the batched mask pass); by default for
+        arenas larger than the last-level cache, where the second read costs a trip to
+        memory (measured: 7 % faster on a 1.3 GB arena, 5 % slower on a 100 MB one).  The rebuild reads
+        the dense arena and masks on the way unless from_sparse asks for the K sparse
+        arenas as its source (same result).  sparse_arenas=False skips writing the K sparse
+        arenas (masks, flags, plans and rebuilt variants only).
+        Returns (threshold records, compact_batch's tuple)."""
         assert sparse_arenas or not from_sparse
         k = len(n_prune)
         assert k == self.bk
-        recs = self.global_threshold(n_prune, sync=True)
-        S.shifter_apply_mask_batch(self.ctx, self.model, self.d_w, self.d_thr, k,
-                                   self.b_w_sparse if sparse_arenas else None,
-                                   self.w_stride, self.b_mask, self.m_stride, self.b_out_alive,
-                                   self.b_in_alive if with_in_alive else None)
+        self.n_thr = k
+        if fused is None:
+            fused = self.model.info.w_extent * 4 > (192 << 20)
+        if fused:
+            recs = S.shifter_prune_fused_batch(
+                self.ctx, self.model, self.d_w, n_prune, self.d_thr,
+                self.b_w_sparse if sparse_arenas else None, self.w_stride, self.b_mask,
+                self.m_stride, self.b_out_alive, self.b_in_alive if with_in_alive else None)
+        else:
+            recs = self.global_threshold(n_prune, sync=True)
+            S.shifter_apply_mask_batch(self.ctx, self.model, self.d_w, self.d_thr, k,
+                                       self.b_w_sparse if sparse_arenas else None,
+                                       self.w_stride, self.b_mask, self.m_stride, self.b_out_alive,
+                                       self.b_in_alive if with_in_alive else None)
         S.shifter_propagate_groups_batch(self.ctx, self.model, self.b_out_alive, k, flags,
                                          self.b_group_alive, self.b_index_map, self.b_keep,
                                          self.b_new_width, sync=False)

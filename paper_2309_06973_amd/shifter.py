@@ -107,6 +107,9 @@ EXPORTS = {
     "shifter_propagate_groups_fixpoint": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)],
+    "shifter_prune_fused_batch": [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_uint64),
+                                  C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p,
+                                  C.c_uint64, C.c_void_p, C.c_void_p, C.POINTER(Threshold)],
     "shifter_profile_enable": [C.c_void_p, C.c_int],
     "shifter_profile_read": [C.c_void_p, C.POINTER(C.c_char_p), C.POINTER(C.c_uint32),
                              C.POINTER(C.c_double), C.c_uint32, C.POINTER(C.c_uint32)],
@@ -282,6 +285,18 @@ def shifter_propagate_groups(ctx: Context, model: Model, d_out_alive, d_in_alive
         _ptr(d_group_alive), _ptr(d_index_map), _ptr(d_keep), _ptr(d_new_width), h),
         ctx.handle, allow=(SHIFTER_WARN_COLLAPSE,))
     return rc, (list(h) if sync else None)
+
+
+def shifter_prune_fused_batch(ctx: Context, model: Model, d_w, n_prune: Sequence[int], d_thr,
+                              d_w_out, w_stride: int, d_mask, mask_stride: int, d_out_alive,
+                              d_in_alive) -> List[Threshold]:
+    k = len(n_prune)
+    arr = (C.c_uint64 * max(k, 1))(*[int(p) for p in n_prune])
+    h = (Threshold * max(k, 1))()
+    _check(load_library().shifter_prune_fused_batch(
+        ctx.handle, model.handle, _ptr(d_w), arr, k, _ptr(d_thr), _ptr(d_w_out), w_stride,
+        _ptr(d_mask), mask_stride, _ptr(d_out_alive), _ptr(d_in_alive), h), ctx.handle)
+    return list(h)[:k]
 
 
 def shifter_kernel_scan(ctx: Context, model: Model, d_w_sparse, d_kernel_nz) -> None:

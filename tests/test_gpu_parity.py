@@ -300,31 +300,36 @@ def check_batch(spec, w, v, n_prune, flags=0, check=None, with_in_alive=True):
     try:
         pl.enable_batch(k_var)
         info = pl.model.info
-        for from_sparse, sparse_arenas in ((False, True), (True, True), (False, False)):
-            # the rebuild from the dense arena (masking on the way), from the K sparse
-            # arenas, and from the dense arena with no sparse arenas written at all
+        for fused, from_sparse, sparse_arenas in ((True, False, True), (False, True, True),
+                                                  (True, False, False), (False, False, True)):
+            # ranking + masks in one read or in two calls; the rebuild from the dense arena
+            # (masking on the way), from the K sparse arenas, and from the dense arena with
+            # no sparse arenas written at all
             pl.b_w_out.fill_(float("nan"))
             pl.b_vecs_out.fill_(float("nan"))
             pl.b_w_sparse.fill_(float("nan"))
+            pl.b_mask.fill_(7)
+            pl.b_out_alive.fill_(7)
+            pl.b_in_alive.fill_(7)
             _check_batch_run(pl, spec, refs, a, n_prune, flags, check, with_in_alive, from_sparse,
-                             sparse_arenas)
+                             sparse_arenas, fused)
     finally:
         pl.close()
 
 
 def _check_batch_run(pl, spec, refs, a, n_prune, flags, check, with_in_alive, from_sparse,
-                     sparse_arenas):
+                     sparse_arenas, fused):
     info = pl.model.info
     k_var = len(n_prune)
     recs, (rc, ots, ovs, ews, evs) = pl.portfolio(n_prune, flags, with_in_alive,
                                                   from_sparse=from_sparse,
-                                                  sparse_arenas=sparse_arenas)
+                                                  sparse_arenas=sparse_arenas, fused=fused)
     torch.cuda.synchronize()
     collapse = any((r.plan.new_width == 0).any() for r in refs)
     assert rc == (S.SHIFTER_WARN_COLLAPSE if collapse else S.SHIFTER_OK)
     n = info.n_prunable
     for k in (check if check is not None else range(k_var)):
-        ref, lab = refs[k], f"{spec.name} batch k={k} from_sparse={from_sparse} sparse_arenas={sparse_arenas}"
+        ref, lab = refs[k], f"{spec.name} batch k={k} from_sparse={from_sparse} sparse_arenas={sparse_arenas} fused={fused}"
         check_threshold(recs[k], ref.sel, a)
         mask = pl.b_mask[k * pl.m_stride:k * pl.m_stride + n].cpu().numpy()
         assert np.array_equal(mask, ref.mask), lab + " mask"
