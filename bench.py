@@ -121,10 +121,9 @@ def measure(name, steps, warmup, lean_run=True):
 
     def step(collect=None, sparse_arenas=True):
         if k_var == 1:
-            # one prune count: ranking, mask and scan in a single read of the arena
-            pl.prune_fused(n_prune[0])
-            pl.propagate_groups(0, sync=False)
-            out = pl.compact(sync=True)
+            # one prune count: ranking, mask and scan in a single read of the arena; plan
+            # and rebuild enqueued behind it, one wait for the whole step
+            _, out = pl.single(n_prune[0])
             if collect is not None:
                 collect.append(out[3])
             return

@@ -198,13 +198,27 @@ int shifter_get_select_stats(const shifter_ctx* ctx, uint64_t* out8);
  *   d_w_out      device, w_extent floats; must differ from d_w
  *   d_mask       device, N bytes, or NULL
  *   d_out_alive, d_in_alive   device, required
- *   d_thr, h_thr device / host, one record each, both required.  The call always waits
- *                for the stream; a NaN among the prunable weights gives
- *                SHIFTER_ERR_NONFINITE (outputs are then unspecified). */
+ *   d_thr        device, one record, required
+ *   h_thr        host, one record, or NULL.  Non-NULL: the call waits for the stream; a NaN
+ *                among the prunable weights gives SHIFTER_ERR_NONFINITE (outputs are then
+ *                unspecified).  NULL (and the single pass allowed): the call only
+ *                enqueues work and the outcome is collected later by
+ *                shifter_prune_fused_result; the caller may enqueue the steps that
+ *                consume the outputs in between, at the risk of having to repeat them.
+ *                The pointers of a deferred call must stay valid until it is collected,
+ *                and no other shifter_prune_fused may be issued on the context before.
+ *
+ * shifter_prune_fused_result waits for the stream and settles a deferred call: h_thr
+ * (may be NULL) receives the record; *h_redone = 0 if the single pass was exact, 1 if the
+ * two separate steps had to be run now - every output of shifter_prune_fused has then been
+ * rewritten and whatever was derived from them since must be computed again.  Without a
+ * deferred call pending it only waits and h_thr receives the record of the last
+ * shifter_prune_fused that waited itself. */
 int shifter_prune_fused(shifter_ctx* ctx, const shifter_model* model, const float* d_w,
                         uint64_t n_prune, shifter_threshold* d_thr, float* d_w_out,
                         uint8_t* d_mask, uint8_t* d_out_alive, uint8_t* d_in_alive,
                         shifter_threshold* h_thr);
+int shifter_prune_fused_result(shifter_ctx* ctx, shifter_threshold* h_thr, int* h_redone);
 
 /* The sparse model (Sec. II-A; Sec. III-C): d_w_out[e] = removed ? +0.0f : d_w[e] for
  * every element of every tensor (non-prunable tensors are copied), d_mask[g] = 0 for

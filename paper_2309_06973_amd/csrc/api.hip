@@ -89,6 +89,7 @@ static void unbind(shifter_model* m) {
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     if (b.host_stage) (void)hipHostFree(b.host_stage);
+    if (b.host_spec) (void)hipHostFree(b.host_spec);
     b = shifter_model::Bound();
 }
 
@@ -419,6 +420,8 @@ static int bind(shifter_ctx* ctx, const shifter_model* cm) {
                                  sizeof(uint32_t) * m->g.size()) +
                          sizeof(SpecState) + sizeof(MultiState) + 256;
     HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&b.host_stage), b.host_stage_bytes, hipHostMallocDefault));
+    HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&b.host_spec),
+                               sizeof(SpecState) + sizeof(shifter_threshold), hipHostMallocDefault));
     return SHIFTER_OK;
 }
 
@@ -440,13 +443,18 @@ static int after_launch(shifter_ctx* ctx, const char* fn) {
     return SHIFTER_OK;
 }
 
-// Waits for the stream and reads back the outcome of the single-pass selection.
-static int spec_result(shifter_ctx* ctx, const shifter_model* model, const shifter_threshold* d_thr,
-                       shifter_threshold* h_thr, int* decided) {
-    uint8_t* st = model->b.host_stage;
+// Enqueues the read-back of the single-pass selection's outcome into pinned memory `st`.
+static int spec_result_enqueue(shifter_ctx* ctx, const shifter_model* model,
+                               const shifter_threshold* d_thr, uint8_t* st) {
     HIP_TRY(ctx, hipMemcpyAsync(st, model->b.spec, sizeof(SpecState), hipMemcpyDeviceToHost, ctx->stream));
     HIP_TRY(ctx, hipMemcpyAsync(st + sizeof(SpecState), d_thr, sizeof(shifter_threshold),
                                 hipMemcpyDeviceToHost, ctx->stream));
+    return SHIFTER_OK;
+}
+
+// Waits for the stream and evaluates the outcome read back into `st`.
+static int spec_result_collect(shifter_ctx* ctx, const uint8_t* st, shifter_threshold* h_thr,
+                               int* decided) {
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     SpecState ss;
     memcpy(&ss, st, sizeof ss);
@@ -459,8 +467,18 @@ static int spec_result(shifter_ctx* ctx, const shifter_model* model, const shift
     if (ss.status & 2u)
         return fail(ctx, SHIFTER_ERR_NONFINITE, "NaN among the prunable weights");
     *decided = (ss.status & 1u) ? 0 : 1;
-    if (*decided) memcpy(h_thr, st + sizeof(SpecState), sizeof(shifter_threshold));
+    if (*decided) {
+        memcpy(&ctx->last_record, st + sizeof(SpecState), sizeof(shifter_threshold));
+        if (h_thr) *h_thr = ctx->last_record;
+    }
     return SHIFTER_OK;
+}
+
+static int spec_result(shifter_ctx* ctx, const shifter_model* model, const shifter_threshold* d_thr,
+                       shifter_threshold* h_thr, int* decided) {
+    int rc = spec_result_enqueue(ctx, model, d_thr, model->b.host_stage);
+    if (rc) return rc;
+    return spec_result_collect(ctx, model->b.host_stage, h_thr, decided);
 }
 
 extern "C" int shifter_global_threshold(shifter_ctx* ctx, const shifter_model* model,
@@ -556,30 +574,14 @@ extern "C" int shifter_apply_mask(shifter_ctx* ctx, const shifter_model* model, 
     return after_launch(ctx, "apply_mask");
 }
 
-extern "C" int shifter_prune_fused(shifter_ctx* ctx, const shifter_model* model, const float* d_w,
-                                   uint64_t n_prune, shifter_threshold* d_thr, float* d_w_out,
-                                   uint8_t* d_mask, uint8_t* d_out_alive, uint8_t* d_in_alive,
-                                   shifter_threshold* h_thr) {
-    int rc = enter(ctx, model, "prune_fused");
-    if (rc) return rc;
-    if (!d_w || !d_thr || !d_w_out || !d_out_alive || !d_in_alive || !h_thr)
-        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "prune_fused: NULL pointer argument");
-    if (d_w == d_w_out)
-        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "prune_fused: cannot work in place");
-    if (misaligned(d_w, 16) || misaligned(d_w_out, 16) || misaligned(d_mask, 4) || misaligned(d_thr, 8))
-        return fail(ctx, SHIFTER_ERR_INVALID_ARG,
-                    "prune_fused: arenas must be 16-byte aligned, the mask 4-byte aligned");
-    if (n_prune > model->info.n_prunable)
-        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "prune_fused: prune count exceeds N");
-    if (ctx->select_path == 0) {
-        launch_spec_select(ctx, model, d_w, n_prune, d_thr, d_w_out, d_mask, d_out_alive, d_in_alive);
-        if ((rc = after_launch(ctx, "prune_fused"))) return rc;
-        int decided = 0;
-        if ((rc = spec_result(ctx, model, d_thr, h_thr, &decided))) return rc;
-        if (decided) return SHIFTER_OK;
-    }
-    // the single pass could not decide (or is switched off): rank, then mask and scan
-    rc = shifter_global_threshold(ctx, model, d_w, &n_prune, 1, d_thr, nullptr);
+// The two separate steps, for when the single pass could not decide or is switched off.
+static int prune_unfused(shifter_ctx* ctx, const shifter_model* model, const float* d_w,
+                         uint64_t n_prune, shifter_threshold* d_thr, float* d_w_out, uint8_t* d_mask,
+                         uint8_t* d_out_alive, uint8_t* d_in_alive, shifter_threshold* h_thr) {
+    const int saved = ctx->select_path;
+    ctx->select_path = 1;
+    int rc = shifter_global_threshold(ctx, model, d_w, &n_prune, 1, d_thr, nullptr);
+    ctx->select_path = saved;
     if (rc) return rc;
     launch_mask_scan(ctx, model, d_w, d_thr, d_w_out, d_mask, d_out_alive, d_in_alive);
     if ((rc = after_launch(ctx, "prune_fused"))) return rc;
@@ -588,11 +590,70 @@ extern "C" int shifter_prune_fused(shifter_ctx* ctx, const shifter_model* model,
     HIP_TRY(ctx, hipMemcpyAsync(st + sizeof(shifter_threshold), &model->b.sel->nan_seen, sizeof(uint32_t),
                                 hipMemcpyDeviceToHost, ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
-    memcpy(h_thr, st, sizeof(shifter_threshold));
+    memcpy(&ctx->last_record, st, sizeof(shifter_threshold));
+    if (h_thr) *h_thr = ctx->last_record;
     uint32_t nan_seen;
     memcpy(&nan_seen, st + sizeof(shifter_threshold), sizeof nan_seen);
     if (nan_seen) return fail(ctx, SHIFTER_ERR_NONFINITE, "prune_fused: NaN among the prunable weights");
     return SHIFTER_OK;
+}
+
+extern "C" int shifter_prune_fused(shifter_ctx* ctx, const shifter_model* model, const float* d_w,
+                                   uint64_t n_prune, shifter_threshold* d_thr, float* d_w_out,
+                                   uint8_t* d_mask, uint8_t* d_out_alive, uint8_t* d_in_alive,
+                                   shifter_threshold* h_thr) {
+    int rc = enter(ctx, model, "prune_fused");
+    if (rc) return rc;
+    if (!d_w || !d_thr || !d_w_out || !d_out_alive || !d_in_alive)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "prune_fused: NULL pointer argument");
+    if (d_w == d_w_out)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "prune_fused: cannot work in place");
+    if (misaligned(d_w, 16) || misaligned(d_w_out, 16) || misaligned(d_mask, 4) || misaligned(d_thr, 8))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG,
+                    "prune_fused: arenas must be 16-byte aligned, the mask 4-byte aligned");
+    if (n_prune > model->info.n_prunable)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "prune_fused: prune count exceeds N");
+    if (ctx->pending.active)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG,
+                    "prune_fused: the outcome of an earlier deferred call has not been collected");
+    if (ctx->select_path == 0) {
+        launch_spec_select(ctx, model, d_w, n_prune, d_thr, d_w_out, d_mask, d_out_alive, d_in_alive);
+        if ((rc = after_launch(ctx, "prune_fused"))) return rc;
+        if (!h_thr) {
+            // deferred: the outcome is read back behind the kernels and looked at later
+            if ((rc = spec_result_enqueue(ctx, model, d_thr, model->b.host_spec))) return rc;
+            ctx->pending = {true, model, d_w, n_prune, d_thr, d_w_out, d_mask, d_out_alive, d_in_alive};
+            return SHIFTER_OK;
+        }
+        int decided = 0;
+        if ((rc = spec_result(ctx, model, d_thr, h_thr, &decided))) return rc;
+        if (decided) return SHIFTER_OK;
+    }
+    // the single pass could not decide (or is switched off): rank, then mask and scan
+    return prune_unfused(ctx, model, d_w, n_prune, d_thr, d_w_out, d_mask, d_out_alive, d_in_alive, h_thr);
+}
+
+extern "C" int shifter_prune_fused_result(shifter_ctx* ctx, shifter_threshold* h_thr, int* h_redone) {
+    if (!ctx || !h_redone)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "prune_fused_result: NULL argument");
+    *h_redone = 0;
+    if (!ctx->pending.active) {
+        // the call was not deferred (or ran the separate steps at once): nothing to collect
+        HIP_TRY(ctx, hipSetDevice(ctx->device));
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+        if (h_thr) *h_thr = ctx->last_record;
+        return SHIFTER_OK;
+    }
+    const shifter_ctx::Pending p = ctx->pending;
+    ctx->pending.active = false;
+    int rc = enter(ctx, p.model, "prune_fused_result");
+    if (rc) return rc;
+    int decided = 0;
+    if ((rc = spec_result_collect(ctx, p.model->b.host_spec, h_thr, &decided))) return rc;
+    if (decided) return SHIFTER_OK;
+    *h_redone = 1;
+    return prune_unfused(ctx, p.model, p.d_w, p.n_prune, p.d_thr, p.d_w_out, p.d_mask, p.d_out_alive,
+                         p.d_in_alive, h_thr);
 }
 
 extern "C" int shifter_get_select_stats(const shifter_ctx* ctx, uint64_t* out8) {

@@ -217,6 +217,7 @@ struct shifter_model {
         uint2* multi_seg = nullptr;           // SPEC_MULTI_MAXK * SPEC_SUB * SPEC_SEG_CAP pairs
         uint32_t* multi_seg_cnt = nullptr;    // SPEC_MULTI_MAXK * SPEC_SUB
         uint8_t* host_stage = nullptr;        // pinned, for small read-backs
+        uint8_t* host_spec = nullptr;         // pinned: outcome of a deferred shifter_prune_fused
         size_t host_stage_bytes = 0;
     } b;
 };
@@ -234,6 +235,19 @@ struct shifter_ctx {
     double margin_sigmas = 4.0;   // half-width of the predicted interval, in binomial sigmas
     shifter::SpecState last_spec{};  // outcome of the last single-pass selection
     int last_path = 0;               // 1: single pass decided; 2: multi-pass select ran
+    shifter_threshold last_record{};  // record of the last shifter_prune_fused that waited
+    // a shifter_prune_fused call whose outcome has not been collected yet
+    struct Pending {
+        bool active = false;
+        const shifter_model* model = nullptr;
+        const float* d_w = nullptr;
+        uint64_t n_prune = 0;
+        shifter_threshold* d_thr = nullptr;
+        float* d_w_out = nullptr;
+        uint8_t* d_mask = nullptr;
+        uint8_t* d_out_alive = nullptr;
+        uint8_t* d_in_alive = nullptr;
+    } pending;
 };
 
 namespace shifter {

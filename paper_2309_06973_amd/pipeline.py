@@ -54,12 +54,30 @@ class Pipeline:
         return S.shifter_global_threshold(self.ctx, self.model, self.d_w, n_prune,
                                           self.d_thr, sync)
 
-    def prune_fused(self, n_prune: int):
-        """Steps 1-3 for one prune count in a single read of the arena."""
+    def prune_fused(self, n_prune: int, defer: bool = False):
+        """Steps 1-3 for one prune count in a single read of the arena.  defer: do not wait
+        for the outcome (see prune_result)."""
         self.n_thr = 1
         return S.shifter_prune_fused(self.ctx, self.model, self.d_w, n_prune, self.d_thr,
                                      self.d_w_sparse, self.d_mask, self.d_out_alive,
-                                     self.d_in_alive)
+                                     self.d_in_alive, defer)
+
+    def prune_result(self):
+        """(record, redone) of a deferred prune_fused; redone: repeat the later steps."""
+        return S.shifter_prune_fused_result(self.ctx)
+
+    def single(self, n_prune: int, flags: int = 0):
+        """All five steps for one prune count with one wait: the plan and the rebuild are
+        enqueued behind the fused pass before its outcome is known and repeated in the
+        rare case that the pass has to be redone.  Returns (record, compact's tuple)."""
+        self.prune_fused(n_prune, defer=True)
+        self.propagate_groups(flags, sync=False)
+        out = self.compact(sync=True)
+        rec, redone = self.prune_result()
+        if redone:
+            self.propagate_groups(flags, sync=False)
+            out = self.compact(sync=True)
+        return rec, out
 
     def apply_mask(self, k: int = 0, fused_scan: bool = True, in_place: bool = False):
         dst = self.d_w if in_place else self.d_w_sparse

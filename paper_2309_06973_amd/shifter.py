@@ -107,6 +107,7 @@ EXPORTS = {
     "shifter_propagate_groups_fixpoint": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)],
+    "shifter_prune_fused_result": [C.c_void_p, C.POINTER(Threshold), C.POINTER(C.c_int)],
     "shifter_prune_fused_batch": [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_uint64),
                                   C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p,
                                   C.c_uint64, C.c_void_p, C.c_void_p, C.POINTER(Threshold)],
@@ -251,13 +252,25 @@ def shifter_get_select_stats(ctx: Context) -> dict:
 
 
 def shifter_prune_fused(ctx: Context, model: Model, d_w, n_prune: int, d_thr, d_w_out, d_mask,
-                        d_out_alive, d_in_alive) -> Threshold:
-    h = Threshold()
+                        d_out_alive, d_in_alive, defer: bool = False) -> Optional[Threshold]:
+    """defer: only enqueue; collect the outcome with shifter_prune_fused_result."""
+    h = None if defer else Threshold()
     _check(load_library().shifter_prune_fused(ctx.handle, model.handle, _ptr(d_w), int(n_prune),
                                               _ptr(d_thr), _ptr(d_w_out), _ptr(d_mask),
-                                              _ptr(d_out_alive), _ptr(d_in_alive), C.byref(h)),
+                                              _ptr(d_out_alive), _ptr(d_in_alive),
+                                              None if defer else C.byref(h)),
            ctx.handle)
     return h
+
+
+def shifter_prune_fused_result(ctx: Context):
+    """Returns (record, redone): redone means the outputs of the deferred
+    shifter_prune_fused were recomputed and everything derived from them is stale."""
+    h = Threshold()
+    redone = C.c_int()
+    _check(load_library().shifter_prune_fused_result(ctx.handle, C.byref(h), C.byref(redone)),
+           ctx.handle)
+    return h, bool(redone.value)
 
 
 def shifter_apply_mask(ctx: Context, model: Model, d_w, d_thr, d_w_out, d_mask,

@@ -485,3 +485,39 @@ def test_fixpoint_residual_toy_joint_and_frozen():
     p = synth.prune_count(spec.n_prunable, 0.85)
     for flags in (0, S.SHIFTER_PAPER_FREEZE_RESIDUAL):
         check_fixpoint(spec, w, v, p, flags)
+
+
+# ----------------------------------------------------------------------------- deferred outcome
+@pytest.mark.gpu
+def test_deferred_fused_pass_and_its_redo():
+    """All five steps with a single wait: exact at once on continuous weights, repeated
+    after the fall-back on an arena of ties; either way the oracle's results."""
+    spec, w, v = synth.generate_config(1)
+    p = synth.prune_count(spec.n_prunable, 0.9)
+    for arena, expect_redone in ((w, False), (np.where(w != 0, np.sign(w) * 0.25, w).astype(np.float32), True)):
+        ref = O.prune_and_compact(arena, v, spec.tensors, spec.vecs, spec.groups, [p])[0]
+        pl = Pipeline(spec, arena, v)
+        try:
+            pl.prune_fused(p, defer=True)
+            pl.propagate_groups(0, sync=False)
+            pl.compact(sync=True)
+            rec, redone = pl.prune_result()
+            assert redone == expect_redone
+            check_threshold(rec, ref.sel, np.abs(O.gather_prunable(arena, spec.tensors)))
+            # the convenience wrapper does the same and repeats what is stale
+            rec2, (rc, ot, ov, ew, ev) = pl.single(p)
+            assert (rec2.cut, rec2.n_less, rec2.n_equal) == (rec.cut, rec.n_less, rec.n_equal)
+            n = pl.model.info.n_prunable
+            assert np.array_equal(pl.d_mask[:n].cpu().numpy(), ref.mask)
+            assert np.array_equal(bits(pl.d_w_sparse.cpu().numpy()[:ref.w_sparse.size]), bits(ref.w_sparse))
+            assert np.array_equal(pl.d_new_width.cpu().numpy().view(np.uint32), ref.plan.new_width)
+            assert ew == ref.compacted.w.size and ev == ref.compacted.v.size
+            assert np.array_equal(bits(pl.d_w_out[:ew].cpu().numpy()), bits(ref.compacted.w))
+            assert np.array_equal(bits(pl.d_vecs_out[:ev].cpu().numpy()), bits(ref.compacted.v))
+            # a second deferred call before collecting the first is refused
+            pl.prune_fused(p, defer=True)
+            with pytest.raises(S.ShifterError):
+                pl.prune_fused(p, defer=True)
+            pl.prune_result()
+        finally:
+            pl.close()
