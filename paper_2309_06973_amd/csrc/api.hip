@@ -81,7 +81,7 @@ static void unbind(shifter_model* m) {
     auto& b = m->b;
     if (!b.ctx) return;
     (void)hipSetDevice(b.device);
-    void* ptrs[] = {b.tens, b.groups, b.vecs, b.producers, b.tile_prefix, b.sel, b.ghist,
+    void* ptrs[] = {b.tens, b.groups, b.vecs, b.producers, b.tile_prefix, b.tile_tensor, b.sel, b.ghist,
                     b.tile_cnt, b.plan_t, b.plan_v, b.plan_h, b.out_tile_prefix, b.rect_prefix, b.rowtab_prefix, b.coltab_prefix, b.rowtab, b.coltab, b.kernel_off, b.fix_prefix, b.cons_prefix, b.consumers, b.fix_alive,
                     b.fix_produced, b.fix_read, b.fix_out_flags, b.fix_removed, b.levels, b.spec, b.shist,
                     b.spec_cnt, b.partial, b.cand, b.list, b.ranked_ids, b.multi, b.multi_cnt,
@@ -372,6 +372,12 @@ static int bind(shifter_ctx* ctx, const shifter_model* cm) {
     if ((rc = upload(ctx, &b.vecs, m->dv.data(), n_v))) return rc;
     if ((rc = upload(ctx, &b.producers, m->producers.data(), m->producers.size()))) return rc;
     if ((rc = upload(ctx, &b.tile_prefix, m->tile_prefix.data(), m->tile_prefix.size()))) return rc;
+    {
+        std::vector<uint16_t> tt(m->n_tiles);
+        for (size_t t = 0; t < n_t; ++t)
+            for (uint32_t tile = m->tile_prefix[t]; tile < m->tile_prefix[t + 1]; ++tile) tt[tile] = (uint16_t)t;
+        if ((rc = upload(ctx, &b.tile_tensor, tt.data(), tt.size()))) return rc;
+    }
     if ((rc = upload(ctx, &b.rect_prefix, m->rect_prefix.data(), m->rect_prefix.size()))) return rc;
     if ((rc = upload(ctx, &b.rowtab_prefix, m->rowtab_prefix.data(), m->rowtab_prefix.size()))) return rc;
     if ((rc = upload(ctx, &b.coltab_prefix, m->coltab_prefix.data(), m->coltab_prefix.size()))) return rc;

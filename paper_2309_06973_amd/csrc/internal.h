@@ -181,6 +181,7 @@ struct shifter_model {
         shifter::DevVec* vecs = nullptr;
         uint32_t* producers = nullptr;
         uint32_t* tile_prefix = nullptr;
+        uint16_t* tile_tensor = nullptr;      // n_tiles: tensor of every tile
         shifter::SelState* sel = nullptr;
         uint32_t* ghist = nullptr;       // MAXK * HIST_BINS
         uint32_t* tile_cnt = nullptr;    // MAXK * n_tiles

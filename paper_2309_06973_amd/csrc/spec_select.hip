@@ -76,8 +76,8 @@ __host__ __device__ __forceinline__ uint32_t sample_sector(uint32_t tile, uint32
 
 __global__ __launch_bounds__(BLOCK) void spec_sample_kernel(
     const DevTensor* __restrict__ tens, const uint32_t* __restrict__ tile_prefix,
-    uint32_t n_t, uint32_t n_tiles, uint32_t tile_stride, const float* __restrict__ w,
-    uint32_t* shist) {
+    const uint16_t* __restrict__ tile_tensor, uint32_t n_tiles, uint32_t tile_stride,
+    const float* __restrict__ w, uint32_t* shist) {
     __shared__ uint32_t h[SBINS];
     for (uint32_t i = threadIdx.x; i < SBINS; i += BLOCK) h[i] = 0;
     __syncthreads();
@@ -85,27 +85,45 @@ __global__ __launch_bounds__(BLOCK) void spec_sample_kernel(
     const uint32_t wave = blockIdx.x * (BLOCK / 64) + (threadIdx.x >> 6);
     const uint32_t n_waves = gridDim.x * (BLOCK / 64);
     const uint32_t quarter = (lane >> 2) & 3u, part = lane & 3u;
-    for (uint64_t s = (uint64_t)wave * 4 + (lane >> 4); s * tile_stride < n_tiles;
-         s += (uint64_t)n_waves * 4) {
+    // address of this lane's four samples of sampled tile s, or nullptr; the tensor of a
+    // tile comes from a table (one load instead of a search per lane)
+    auto locate = [&](uint64_t s) -> const float* {
+        if (s * tile_stride >= n_tiles) return nullptr;
         const uint32_t tile = (uint32_t)(s * tile_stride);
-        const uint32_t t = find_tensor(tile_prefix, n_t, tile);
-        if (!tens[t].prunable) continue;
+        const uint32_t t = tile_tensor[tile];
+        if (!tens[t].prunable) return nullptr;
         const uint32_t e0 = (tile - tile_prefix[t]) * TILE;
         const uint32_t n = min(TILE, tens[t].numel - e0);
         const uint32_t j = quarter * 1024u + sample_sector(tile, quarter) * 16u + part * 4u;
-        if (j + 3 < n) {
-            const float* p = w + tens[t].offset + e0 + j;
-            float4 x;
+        return j + 3 < n ? w + tens[t].offset + e0 + j : nullptr;
+    };
+    auto fetch = [&](const float* p) -> float4 {
+        float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (p) {
             if ((reinterpret_cast<uintptr_t>(p) & 15u) == 0) {
                 x = *reinterpret_cast<const float4*>(p);
             } else {
                 x.x = p[0]; x.y = p[1]; x.z = p[2]; x.w = p[3];
             }
-            atomicAdd(&h[key_of(x.x) >> SAMPLE_SHIFT], 1u);
-            atomicAdd(&h[key_of(x.y) >> SAMPLE_SHIFT], 1u);
-            atomicAdd(&h[key_of(x.z) >> SAMPLE_SHIFT], 1u);
-            atomicAdd(&h[key_of(x.w) >> SAMPLE_SHIFT], 1u);
         }
+        return x;
+    };
+    auto count = [&](const float* p, const float4& x) {
+        if (!p) return;
+        atomicAdd(&h[key_of(x.x) >> SAMPLE_SHIFT], 1u);
+        atomicAdd(&h[key_of(x.y) >> SAMPLE_SHIFT], 1u);
+        atomicAdd(&h[key_of(x.z) >> SAMPLE_SHIFT], 1u);
+        atomicAdd(&h[key_of(x.w) >> SAMPLE_SHIFT], 1u);
+    };
+    // two sampled tiles per lane group and step, their loads in flight together
+    const uint64_t step = (uint64_t)n_waves * 4;
+    for (uint64_t s = (uint64_t)wave * 4 + (lane >> 4); s * tile_stride < n_tiles; s += 2 * step) {
+        const float* pa = locate(s);
+        const float* pb = locate(s + step);
+        const float4 xa = fetch(pa);
+        const float4 xb = fetch(pb);
+        count(pa, xa);
+        count(pb, xb);
     }
     __syncthreads();
     for (uint32_t i = threadIdx.x; i < SBINS; i += BLOCK) {
@@ -123,9 +141,10 @@ __global__ __launch_bounds__(BLOCK) void spec_predict_kernel(SpecState* ss,
                                                              uint64_t n_prunable,
                                                              double margin_sigmas) {
     constexpr uint32_t SEG = 256, NSEG = SBINS / SEG;   // 64 segments
-    static_assert(NSEG <= BLOCK, "one segment sum per thread");
+    static_assert(NSEG == 64, "one segment per lane, one segment sum per thread");
     __shared__ uint64_t smem[BLOCK / 64 + 1];
     __shared__ uint32_t seg_sum[NSEG];
+    __shared__ uint64_t s_base[NSEG];
     __shared__ uint32_t s_bin[3];
     const uint32_t lane = threadIdx.x & 63u, wid = threadIdx.x >> 6;
     for (uint32_t sg = wid; sg < NSEG; sg += BLOCK / 64) {
@@ -152,15 +171,28 @@ __global__ __launch_bounds__(BLOCK) void spec_predict_kernel(SpecState* ss,
         r[1] = centre + delta;
         r[2] = centre;
     }
-    // bin holding the r-th sample: the thread whose segment covers that rank walks it
-    for (uint32_t q = 0; q < 3; ++q) {
-        if (!use || r[q] < 0.0 || r[q] >= (double)m) continue;
-        const uint64_t target = (uint64_t)r[q];
-        if (base <= target && target < base + mine) {
-            uint64_t run = base;
-            for (uint32_t i = 0; i < SEG; ++i) {
-                run += shist[threadIdx.x * SEG + i];
-                if (run > target) { s_bin[q] = threadIdx.x * SEG + i; break; }
+    // bin holding the r-th sample, one wavefront per rank: the segment from the segment
+    // bases (one per lane), then a scan over the segment's 256 bins (four per lane)
+    if (threadIdx.x < NSEG) s_base[threadIdx.x] = base;
+    __syncthreads();
+    if (wid < 3 && use && r[wid] >= 0.0 && r[wid] < (double)m) {
+        const uint64_t target = (uint64_t)r[wid];
+        const uint32_t sg = (uint32_t)__popcll(__ballot(s_base[lane] <= target)) - 1u;   // bases ascend from 0
+        const uint4 x = reinterpret_cast<const uint4*>(shist + sg * SEG)[lane];
+        const uint32_t mine4 = x.x + x.y + x.z + x.w;
+        uint32_t incl = mine4;
+        for (uint32_t d = 1; d < 64; d <<= 1) {
+            const uint32_t y = __shfl_up(incl, d, 64);
+            if (lane >= d) incl += y;
+        }
+        const uint64_t seg_base = s_base[sg];
+        const unsigned long long over = __ballot(seg_base + incl > target);
+        if (over != 0 && lane == (uint32_t)__ffsll(over) - 1u) {
+            uint64_t run = seg_base + incl - mine4;
+            const uint32_t v[4] = {x.x, x.y, x.z, x.w};
+            for (uint32_t i = 0; i < 4; ++i) {
+                run += v[i];
+                if (run > target) { s_bin[wid] = sg * SEG + lane * 4 + i; break; }
             }
         }
     }
@@ -640,8 +672,10 @@ __global__ __launch_bounds__(BLOCK) void spec_fixup_kernel(
 void launch_spec_sample(shifter_ctx* ctx, const shifter_model* m, const float* d_w) {
     const auto& b = m->b;
     const uint32_t sampled = (m->n_tiles + m->sample_tile_stride - 1) / m->sample_tile_stride;
-    const uint32_t grid = std::min(512u, (sampled + 15) / 16);   // 16 tiles per block and step
-    spec_sample_kernel<<<grid, BLOCK, 0, ctx->stream>>>(b.tens, b.tile_prefix, (uint32_t)m->t.size(),
+    // one block per CU: more blocks shorten the loop but every block flushes its LDS
+    // histogram with global atomics (measured 22 us at 256 blocks, 24 at 512, 34 at 128 or 1024)
+    const uint32_t grid = std::min(256u, (sampled + 15) / 16);   // 16 tiles per block and step
+    spec_sample_kernel<<<grid, BLOCK, 0, ctx->stream>>>(b.tens, b.tile_prefix, b.tile_tensor,
                                                         m->n_tiles, m->sample_tile_stride, d_w,
                                                         b.shist);
 }
