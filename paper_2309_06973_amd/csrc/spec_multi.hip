@@ -64,31 +64,41 @@ __global__ __launch_bounds__(BLOCK) void ms_init_kernel(MultiState* ms, uint32_t
 
 // One block: inclusive prefix of the sample histogram in LDS, then for every rank the
 // interval from the sample's order statistics at P/N -/+ margin, then monotone ends.
-__global__ __launch_bounds__(BLOCK) void ms_predict_kernel(MultiState* ms,
-                                                           const uint32_t* __restrict__ shist,
-                                                           uint64_t n_prunable,
-                                                           double margin_sigmas) {
-    constexpr uint32_t SEG = 256, NSEG = MS_BINS / SEG;
+constexpr uint32_t PREDICT_THREADS = 1024;
+
+__global__ __launch_bounds__(PREDICT_THREADS) void ms_predict_kernel(MultiState* ms,
+                                                                     const uint32_t* __restrict__ shist,
+                                                                     uint64_t n_prunable,
+                                                                     double margin_sigmas) {
+    constexpr uint32_t SEG = 256, NSEG = MS_BINS / SEG, WAVES = PREDICT_THREADS / 64;
+    static_assert(NSEG == 64, "one segment per lane in the scan of the segment sums");
     __shared__ uint32_t prefix[MS_BINS];          // 64 KB
-    __shared__ uint64_t smem[BLOCK / 64 + 1];
     __shared__ uint32_t seg_sum[NSEG];
+    __shared__ uint32_t s_total;
     __shared__ uint32_t s_lo[MAXK], s_hi[MAXK], s_mid[MAXK];
     const uint32_t lane = threadIdx.x & 63u, wid = threadIdx.x >> 6;
-    // phase 1: segment sums
-    for (uint32_t sg = wid; sg < NSEG; sg += BLOCK / 64) {
+    // phase 1: segment sums, then their exclusive scan by the first wavefront
+    for (uint32_t sg = wid; sg < NSEG; sg += WAVES) {
         const uint4 x = reinterpret_cast<const uint4*>(shist + sg * SEG)[lane];
         uint32_t v = x.x + x.y + x.z + x.w;
         for (uint32_t d = 32; d > 0; d >>= 1) v += __shfl_down(v, d, 64);
         if (lane == 0) seg_sum[sg] = v;
     }
     __syncthreads();
-    const uint64_t mine = threadIdx.x < NSEG ? seg_sum[threadIdx.x] : 0;
-    uint64_t total;
-    const uint64_t base = block_excl_scan_u64(mine, smem, &total);
-    if (threadIdx.x < NSEG) seg_sum[threadIdx.x] = (uint32_t)base;   // exclusive segment base
+    if (wid == 0) {
+        const uint32_t v = seg_sum[lane];
+        uint32_t incl = v;
+        for (uint32_t d = 1; d < 64; d <<= 1) {
+            const uint32_t y = __shfl_up(incl, d, 64);
+            if (lane >= d) incl += y;
+        }
+        seg_sum[lane] = incl - v;                 // exclusive segment base
+        if (lane == 63) s_total = incl;
+    }
     __syncthreads();
+    const uint64_t total = s_total;
     // phase 2: inclusive prefix per bin
-    for (uint32_t sg = wid; sg < NSEG; sg += BLOCK / 64) {
+    for (uint32_t sg = wid; sg < NSEG; sg += WAVES) {
         const uint4 x = reinterpret_cast<const uint4*>(shist + sg * SEG)[lane];
         const uint32_t mine4 = x.x + x.y + x.z + x.w;
         uint32_t incl = mine4;
@@ -827,7 +837,7 @@ void launch_spec_multi(shifter_ctx* ctx, const shifter_model* m, const float* d_
         }
         {
             ProfileScope ps(ctx, K_SPEC_PREDICT);
-            ms_predict_kernel<<<1, BLOCK, 0, s>>>(b.multi, b.shist, m->info.n_prunable,
+            ms_predict_kernel<<<1, PREDICT_THREADS, 0, s>>>(b.multi, b.shist, m->info.n_prunable,
                                                   ctx->margin_sigmas);
         }
     }
