@@ -209,7 +209,7 @@ def measure(name, steps, warmup, lean_run=True):
     # the liveness-fixpoint plan (kernel-level index + rounds + rebuild) on the same sparse
     # arena, for the single-variant workloads: what it costs and what it removes on top
     fixpoint = None
-    if k_var == 1:
+    if k_var == 1 and lean_run:
         step()                      # the copy above overwrote the sparse arena
         pl.kernel_scan()
         pl.propagate_groups_fixpoint(0)
@@ -273,7 +273,8 @@ def main():
                          "the default workload, none otherwise)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-lean", action="store_true",
-                    help="skip the extra timing of portfolios without sparse arenas")
+                    help="skip the extra timings (portfolio without sparse arenas, liveness "
+                         "fixpoint): for profiling runs")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 (the pass "
