@@ -82,7 +82,7 @@ static void unbind(shifter_model* m) {
     if (!b.ctx) return;
     (void)hipSetDevice(b.device);
     void* ptrs[] = {b.tens, b.groups, b.vecs, b.producers, b.tile_prefix, b.tile_tensor, b.sel, b.ghist,
-                    b.tile_cnt, b.plan_t, b.plan_v, b.plan_h, b.out_tile_prefix, b.rect_prefix, b.rowtab_prefix, b.coltab_prefix, b.rowtab, b.coltab, b.kernel_off, b.fix_prefix, b.cons_prefix, b.consumers, b.fix_alive,
+                    b.tile_cnt, b.plan_t, b.plan_v, b.plan_h, b.plan_pack, b.out_tile_prefix, b.rect_prefix, b.rowtab_prefix, b.coltab_prefix, b.rowtab, b.coltab, b.kernel_off, b.fix_prefix, b.cons_prefix, b.consumers, b.fix_alive,
                     b.fix_produced, b.fix_read, b.fix_out_flags, b.fix_removed, b.levels, b.spec, b.shist,
                     b.spec_cnt, b.partial, b.cand, b.list, b.ranked_ids, b.multi, b.multi_cnt,
                     b.multi_partial, b.multi_seg, b.multi_seg_cnt};
@@ -392,6 +392,8 @@ static int bind(shifter_ctx* ctx, const shifter_model* cm) {
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.plan_t), sizeof(PlanTensor) * n_t * MAXK));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.plan_v), sizeof(PlanVec) * std::max<size_t>(n_v, 1) * MAXK));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.plan_h), sizeof(PlanHeader) * MAXK));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.plan_pack),
+                           (sizeof(PlanHeader) + sizeof(PlanTensor) * n_t + sizeof(PlanVec) * n_v) * MAXK));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.out_tile_prefix), sizeof(uint32_t) * (n_t + 1) * MAXK));
     if ((rc = upload(ctx, &b.kernel_off, m->kernel_off.data(), m->kernel_off.size()))) return rc;
     if ((rc = upload(ctx, &b.fix_prefix, m->fix_prefix.data(), m->fix_prefix.size()))) return rc;
@@ -427,7 +429,7 @@ static int bind(shifter_ctx* ctx, const shifter_model* cm) {
                          sizeof(SpecState) + sizeof(MultiState) + 256;
     HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&b.host_stage), b.host_stage_bytes, hipHostMallocDefault));
     HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&b.host_spec),
-                               sizeof(SpecState) + sizeof(shifter_threshold), hipHostMallocDefault));
+                               sizeof(SpecState), hipHostMallocDefault));
     return SHIFTER_OK;
 }
 
@@ -450,11 +452,9 @@ static int after_launch(shifter_ctx* ctx, const char* fn) {
 }
 
 // Enqueues the read-back of the single-pass selection's outcome into pinned memory `st`.
-static int spec_result_enqueue(shifter_ctx* ctx, const shifter_model* model,
-                               const shifter_threshold* d_thr, uint8_t* st) {
+static int spec_result_enqueue(shifter_ctx* ctx, const shifter_model* model, uint8_t* st) {
+    // the state holds a copy of the record: one read-back
     HIP_TRY(ctx, hipMemcpyAsync(st, model->b.spec, sizeof(SpecState), hipMemcpyDeviceToHost, ctx->stream));
-    HIP_TRY(ctx, hipMemcpyAsync(st + sizeof(SpecState), d_thr, sizeof(shifter_threshold),
-                                hipMemcpyDeviceToHost, ctx->stream));
     return SHIFTER_OK;
 }
 
@@ -474,15 +474,15 @@ static int spec_result_collect(shifter_ctx* ctx, const uint8_t* st, shifter_thre
         return fail(ctx, SHIFTER_ERR_NONFINITE, "NaN among the prunable weights");
     *decided = (ss.status & 1u) ? 0 : 1;
     if (*decided) {
-        memcpy(&ctx->last_record, st + sizeof(SpecState), sizeof(shifter_threshold));
+        ctx->last_record = ss.rec;
         if (h_thr) *h_thr = ctx->last_record;
     }
     return SHIFTER_OK;
 }
 
-static int spec_result(shifter_ctx* ctx, const shifter_model* model, const shifter_threshold* d_thr,
-                       shifter_threshold* h_thr, int* decided) {
-    int rc = spec_result_enqueue(ctx, model, d_thr, model->b.host_stage);
+static int spec_result(shifter_ctx* ctx, const shifter_model* model, shifter_threshold* h_thr,
+                       int* decided) {
+    int rc = spec_result_enqueue(ctx, model, model->b.host_stage);
     if (rc) return rc;
     return spec_result_collect(ctx, model->b.host_stage, h_thr, decided);
 }
@@ -510,7 +510,7 @@ extern "C" int shifter_global_threshold(shifter_ctx* ctx, const shifter_model* m
         launch_spec_select(ctx, model, d_w, pc.p[0], d_thr, nullptr, nullptr, nullptr, nullptr);
         if ((rc = after_launch(ctx, "global_threshold"))) return rc;
         int decided = 0;
-        if ((rc = spec_result(ctx, model, d_thr, h_thr, &decided))) return rc;
+        if ((rc = spec_result(ctx, model, h_thr, &decided))) return rc;
         if (decided) return SHIFTER_OK;
     }
     if (h_thr && K > 1 && ctx->select_path == 0) {
@@ -627,12 +627,12 @@ extern "C" int shifter_prune_fused(shifter_ctx* ctx, const shifter_model* model,
         if ((rc = after_launch(ctx, "prune_fused"))) return rc;
         if (!h_thr) {
             // deferred: the outcome is read back behind the kernels and looked at later
-            if ((rc = spec_result_enqueue(ctx, model, d_thr, model->b.host_spec))) return rc;
+            if ((rc = spec_result_enqueue(ctx, model, model->b.host_spec))) return rc;
             ctx->pending = {true, model, d_w, n_prune, d_thr, d_w_out, d_mask, d_out_alive, d_in_alive};
             return SHIFTER_OK;
         }
         int decided = 0;
-        if ((rc = spec_result(ctx, model, d_thr, h_thr, &decided))) return rc;
+        if ((rc = spec_result(ctx, model, h_thr, &decided))) return rc;
         if (decided) return SHIFTER_OK;
     }
     // the single pass could not decide (or is switched off): rank, then mask and scan
@@ -913,32 +913,33 @@ static int compact_impl(shifter_ctx* ctx, const shifter_model* model, const floa
     if (h_out_tensors || h_out_vecs || h_elems_w || h_elems_v) {
         const auto& b = model->b;
         uint8_t* st = b.host_stage;
-        PlanHeader* hh = reinterpret_cast<PlanHeader*>(st);
-        PlanTensor* ht = reinterpret_cast<PlanTensor*>(st + sizeof(PlanHeader) * K);
-        PlanVec* hv = reinterpret_cast<PlanVec*>(st + sizeof(PlanHeader) * K + sizeof(PlanTensor) * n_t * K);
-        HIP_TRY(ctx, hipMemcpyAsync(hh, b.plan_h, sizeof(PlanHeader) * K, hipMemcpyDeviceToHost, ctx->stream));
-        HIP_TRY(ctx, hipMemcpyAsync(ht, b.plan_t, sizeof(PlanTensor) * n_t * K, hipMemcpyDeviceToHost, ctx->stream));
-        if (n_v) HIP_TRY(ctx, hipMemcpyAsync(hv, b.plan_v, sizeof(PlanVec) * n_v * K, hipMemcpyDeviceToHost, ctx->stream));
+        const size_t stride = sizeof(PlanHeader) + sizeof(PlanTensor) * n_t + sizeof(PlanVec) * n_v;
+        HIP_TRY(ctx, hipMemcpyAsync(st, b.plan_pack, stride * K, hipMemcpyDeviceToHost, ctx->stream));
         HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+        auto hh = [&](uint32_t k) { return reinterpret_cast<const PlanHeader*>(st + stride * k); };
+        auto ht = [&](uint32_t k) { return reinterpret_cast<const PlanTensor*>(st + stride * k + sizeof(PlanHeader)); };
+        auto hv = [&](uint32_t k) {
+            return reinterpret_cast<const PlanVec*>(st + stride * k + sizeof(PlanHeader) + sizeof(PlanTensor) * n_t);
+        };
         uint32_t status = 0;
         for (uint32_t k = 0; k < K; ++k) {
-            status |= hh[k].status;
-            if (h_elems_w) h_elems_w[k] = hh[k].elems_w;
-            if (h_elems_v) h_elems_v[k] = hh[k].elems_v;
+            status |= hh(k)->status;
+            if (h_elems_w) h_elems_w[k] = hh(k)->elems_w;
+            if (h_elems_v) h_elems_v[k] = hh(k)->elems_v;
             if (h_out_tensors) {
                 for (size_t i = 0; i < n_t; ++i) {
                     shifter_tensor_desc d = model->t[i];
-                    d.offset = ht[k * n_t + i].out_off;
-                    d.out_ch = ht[k * n_t + i].o2;
-                    d.in_ch = ht[k * n_t + i].c2 * d.in_mult;
+                    d.offset = ht(k)[i].out_off;
+                    d.out_ch = ht(k)[i].o2;
+                    d.in_ch = ht(k)[i].c2 * d.in_mult;
                     h_out_tensors[k * n_t + i] = d;
                 }
             }
             if (h_out_vecs) {
                 for (size_t i = 0; i < n_v; ++i) {
                     shifter_vec_desc d = model->v[i];
-                    d.offset = hv[k * n_v + i].out_off;
-                    d.len = hv[k * n_v + i].len2;
+                    d.offset = hv(k)[i].out_off;
+                    d.len = hv(k)[i].len2;
                     h_out_vecs[k * n_v + i] = d;
                 }
             }

@@ -90,6 +90,8 @@ struct SpecState {
     uint32_t status;     // bit 0: not decided, use the multi-pass select; bit 1: NaN seen
     uint32_t bin, bin_cnt;
     uint32_t list_cnt;
+    uint32_t pad;
+    shifter_threshold rec;   // copy of the record written to the caller's d_thr (one read-back)
 };
 
 // State of the single-pass selection for all prune counts of a portfolio (ranks sorted by
@@ -188,6 +190,7 @@ struct shifter_model {
         shifter::PlanTensor* plan_t = nullptr;
         shifter::PlanVec* plan_v = nullptr;
         shifter::PlanHeader* plan_h = nullptr;
+        uint8_t* plan_pack = nullptr;         // per variant: header, tensors, vectors, packed for one read-back
         uint32_t* out_tile_prefix = nullptr;  // MAXK * (n_tensors + 1)
         uint32_t* rect_prefix = nullptr;      // n_tensors + 1 each
         uint32_t* rowtab_prefix = nullptr;

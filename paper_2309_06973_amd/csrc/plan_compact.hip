@@ -82,7 +82,7 @@ __global__ __launch_bounds__(BLOCK) void plan_kernel(
     uint32_t n_v, const DevGroup* __restrict__ groups, uint32_t n_g,
     const uint32_t* __restrict__ new_width, uint64_t cap_w, uint64_t cap_v,
     PlanTensor* __restrict__ pt, PlanVec* __restrict__ pv, uint32_t* __restrict__ oup,
-    PlanHeader* __restrict__ hdr) {
+    PlanHeader* __restrict__ hdr, uint8_t* __restrict__ pack) {
     __shared__ uint64_t smem[BLOCK / 64 + 1];
     __shared__ uint32_t s_collapse;
     // blockIdx.x = variant of a batch
@@ -91,6 +91,12 @@ __global__ __launch_bounds__(BLOCK) void plan_kernel(
     pv += blockIdx.x * n_v;
     oup += blockIdx.x * (n_t + 1);
     hdr += blockIdx.x;
+    // the same records once more, packed per variant (header, tensors, vectors), so that
+    // the host fetches a plan with one copy
+    pack += (uint64_t)blockIdx.x * (sizeof(PlanHeader) + n_t * sizeof(PlanTensor) + n_v * sizeof(PlanVec));
+    PlanHeader* pack_h = reinterpret_cast<PlanHeader*>(pack);
+    PlanTensor* pack_t = reinterpret_cast<PlanTensor*>(pack + sizeof(PlanHeader));
+    PlanVec* pack_v = reinterpret_cast<PlanVec*>(pack + sizeof(PlanHeader) + n_t * sizeof(PlanTensor));
     if (threadIdx.x == 0) s_collapse = 0;
     uint64_t off = 0, units = 0, tot;
     for (uint32_t t0 = 0; t0 < n_t; t0 += BLOCK) {
@@ -117,6 +123,7 @@ __global__ __launch_bounds__(BLOCK) void plan_kernel(
         if (t < n_t) {
             p.out_off = my_off;
             pt[t] = p;
+            pack_t[t] = p;
             oup[t] = (uint32_t)my_unit0;
         }
     }
@@ -128,7 +135,10 @@ __global__ __launch_bounds__(BLOCK) void plan_kernel(
         p.pad = 0;
         p.out_off = voff + block_excl_scan_u64(p.len2, smem, &tot);
         voff += tot;
-        if (v < n_v) pv[v] = p;
+        if (v < n_v) {
+            pv[v] = p;
+            pack_v[v] = p;
+        }
     }
     for (uint32_t g = threadIdx.x; g < n_g; g += BLOCK)
         if (new_width[g] == 0) s_collapse = 1;
@@ -140,6 +150,7 @@ __global__ __launch_bounds__(BLOCK) void plan_kernel(
         hdr->elems_v = voff;
         hdr->total_units = (status & 1u) ? 0u : (uint32_t)units;   // does not fit: gather nothing
         hdr->status = status;
+        *pack_h = *hdr;
     }
 }
 
@@ -618,7 +629,7 @@ void launch_compact(shifter_ctx* ctx, const shifter_model* m, const float* d_w, 
         plan_kernel<<<k_var, BLOCK, 0, ctx->stream>>>(b.tens, n_t, b.vecs, n_v, b.groups,
                                                       (uint32_t)m->g.size(), d_new_width, cap_w,
                                                       cap_v, b.plan_t, b.plan_v, b.out_tile_prefix,
-                                                      b.plan_h);
+                                                      b.plan_h, b.plan_pack);
     }
     {
         // the unit counts are only known on the device: the grid covers the case that

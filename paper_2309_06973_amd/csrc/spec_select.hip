@@ -505,6 +505,7 @@ __global__ __launch_bounds__(BLOCK) void spec_rank_kernel(SpecState* ss,
         if (threadIdx.x == 0) {
             out.cut = 0; out.t_key = 0; out.g_cut = ~0ull; out.n_less = 0; out.n_equal = 0;
             *thr = out;
+            ss->rec = out;
         }
         return;
     }
@@ -584,6 +585,7 @@ __global__ __launch_bounds__(BLOCK) void spec_rank_kernel(SpecState* ss,
         out.n_less = ss->less + s_less2 + s_lt;
         out.n_equal = s_eq;
         *thr = out;
+        ss->rec = out;
     }
 }
 
