@@ -277,7 +277,7 @@ def main():
                          "fixpoint): for profiling runs")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only; --gpus must be 1 (the pass "
+        print("bench.py: the library runs on one GPU only; --gpus must be 1 (the pass "
               "shards by variant or by arena range, but no multi-GPU path is built)",
               file=sys.stderr)
         sys.exit(2)

@@ -521,3 +521,33 @@ def test_deferred_fused_pass_and_its_redo():
             pl.prune_result()
         finally:
             pl.close()
+
+
+@pytest.mark.gpu
+def test_model_without_prunable_tensors():
+    """N = 0: nothing can be removed; every step still runs and reproduces its input."""
+    spec, w, v = synth.generate_config(1)
+    for t in spec.tensors:
+        t.prunable = 0
+    ref = O.prune_and_compact(w, v, spec.tensors, spec.vecs, spec.groups, [0])[0]
+    pl = Pipeline(spec, w, v)
+    try:
+        assert pl.model.info.n_prunable == 0
+        rec = pl.global_threshold([0])[0]
+        assert rec.cut == 0 and rec.n_prune == 0
+        with pytest.raises(S.ShifterError):
+            pl.global_threshold([1])
+        rec, (rc, ot, ov, ew, ev) = pl.single(0)
+        assert rec.cut == 0
+        assert np.array_equal(bits(pl.d_w_sparse.cpu().numpy()[:w.size]), bits(ref.w_sparse))
+        assert ew == ref.compacted.w.size and ev == ref.compacted.v.size
+        assert np.array_equal(bits(pl.d_w_out[:ew].cpu().numpy()), bits(ref.compacted.w))
+        pl.enable_batch(2)
+        recs, (rc, ots, ovs, ews, evs) = pl.portfolio([0, 0], fused=True)
+        assert [r.cut for r in recs] == [0, 0]
+        for k in range(2):
+            assert ews[k] == ref.compacted.w.size
+            wc = pl.b_w_out[k * pl.cap_w:k * pl.cap_w + ews[k]].cpu().numpy()
+            assert np.array_equal(bits(wc), bits(ref.compacted.w))
+    finally:
+        pl.close()
