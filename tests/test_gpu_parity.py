@@ -551,3 +551,15 @@ def test_model_without_prunable_tensors():
             assert np.array_equal(bits(wc), bits(ref.compacted.w))
     finally:
         pl.close()
+
+
+@pytest.mark.gpu
+def test_batch_of_the_maximum_number_of_variants():
+    """64 prune counts, more than the single pass takes: the multi-pass select ranks them
+    and the batched passes handle all 64 variants (a few checked against the oracle)."""
+    spec, w, v = synth.generate_config(1)
+    n = spec.n_prunable
+    counts = [(n * (k + 1)) // 66 for k in range(S.SHIFTER_MAX_VARIANTS)]
+    counts[5] = 0
+    counts[40] = counts[41]          # equal counts in two variants
+    check_batch(spec, w, v, counts, check=[0, 5, 33, 40, 41, 63])
