@@ -341,6 +341,58 @@ def residual_toy_spec(width: int = 6, mid: int = 5, n_blocks: int = 2) -> NetSpe
     return b.s
 
 
+@dataclass
+class FoldDesc:
+    """One layer of the conv + BatchNorm fold (Sec. III-D, Module 1): which vectors of the
+    unfused network normalise the filters of ``tensor`` and where the layer's bias goes in
+    the vector arena of the fused network.  -1 marks a vector the layer does not have; a
+    layer with a bias and no BatchNorm (the classifier) passes its bias through."""
+    tensor: int
+    gamma: int
+    beta: int
+    mean: int
+    var: int
+    bias: int
+    out_offset: int
+
+
+def fused_spec(spec: NetSpec) -> Tuple[NetSpec, List[FoldDesc]]:
+    """The network of ``spec`` after Module 1: same tensors and groups (same weight-arena
+    layout), every conv + BatchNorm pair replaced by a conv with a bias, so the vector
+    arena holds one bias per layer and nothing else.  Structure only: the arithmetic of
+    the fold is the library's (and, separately, the oracle's)."""
+    f = NetSpec(name=spec.name + "_fused", input_hw=spec.input_hw,
+                lognormal_sigma=spec.lognormal_sigma, kill_prob=spec.kill_prob)
+    f.tensors = [TensorDesc(**vars(t)) for t in spec.tensors]
+    f.groups = [GroupDesc(g.width, g.pinned) for g in spec.groups]
+    f.w_elems = spec.w_elems
+    folds: List[FoldDesc] = []
+
+    def bias_vec(t: int) -> int:
+        td = spec.tensors[t]
+        f.vecs.append(VecDesc(f.v_elems, td.out_ch, td.out_group))
+        f.v_elems += td.out_ch
+        return len(f.vecs) - 1
+
+    last_conv = None
+    for op in spec.ops:
+        if op[0] == "conv":
+            last_conv = op[1]
+            f.ops.append(op)
+        elif op[0] == "bn":
+            g, b_, m, var = op[1]
+            bv = bias_vec(last_conv)
+            folds.append(FoldDesc(last_conv, g, b_, m, var, -1, f.vecs[bv].offset))
+            f.ops.append(("bias", bv, op[2]))
+        elif op[0] == "linear" and op[2] is not None:
+            bv = bias_vec(op[1])
+            folds.append(FoldDesc(op[1], -1, -1, -1, -1, op[2], f.vecs[bv].offset))
+            f.ops.append(("linear", op[1], bv, op[3], op[4]))
+        else:
+            f.ops.append(op)
+    return f, folds
+
+
 def adversarial_arena(kind: str, n: int, seed: int = 0) -> np.ndarray:
     """Value patterns that exercise tie-breaking and special floats."""
     rng = np.random.Generator(np.random.Philox(SEED_BASE + 77 + seed))

@@ -27,6 +27,8 @@ def forward(spec, tensor_arrays, vec_arrays, x, dtype=torch.float32):
             sh = (1, -1, 1, 1)
             y = (y - V[m].view(sh)) / torch.sqrt(V[var].view(sh) + BN_EPS)
             act[a] = y * V[g].view(sh) + V[b].view(sh)
+        elif kind == "bias":
+            act[op[2]] = act[op[2]] + V[op[1]].view(1, -1, 1, 1)
         elif kind == "relu":
             act[op[1]] = torch.relu(act[op[1]])
         elif kind == "maxpool":
