@@ -304,6 +304,46 @@ int shifter_propagate_groups_fixpoint(shifter_ctx* ctx, const shifter_model* mod
                                       uint32_t* d_keep, uint32_t* d_new_width,
                                       uint32_t* h_new_width, uint32_t* h_rounds);
 
+/* --- Module 1, Model Pre-Processor (Sec. III-D): conv + BatchNorm fold ----------------
+ *
+ * Merges every layer with the BatchNorm that follows it, so that the later modules see
+ * convolutions with a bias and nothing else.  For a listed tensor with a BatchNorm
+ * (gamma, beta, running mean, running variance), in fp32:
+ *   s_o      = gamma_o / sqrt(var_o + eps)
+ *   W'[o, :] = W[o, :] * s_o
+ *   b'_o     = beta_o + (b_o - mean_o) * s_o      (b_o = 0 without a bias vector)
+ * A listed tensor without a BatchNorm keeps its weights and gets b' = b.  Tensors that
+ * are not listed are copied unchanged.  Zero weights stay zero, so a sparse arena keeps
+ * its zero structure (gamma_o = 0 zeroes filter o).  Each result is the correctly rounded
+ * fp32 operation sequence above (the product (b_o - mean_o) * s_o is not rounded before
+ * beta_o is added); against exact arithmetic the weights are within 4 * 2^-24 relative.
+ *
+ * One entry per layer; vector fields index the model's vector descriptors, -1 = absent.
+ * gamma, beta, mean and var are given together or not at all; every vector named must
+ * have the tensor's out_ch elements. */
+typedef struct {
+    uint32_t tensor;
+    int32_t gamma, beta, mean, var;
+    int32_t bias;
+    uint64_t out_offset;   /* fp32 element offset of the layer's out_ch biases in d_bias_out */
+} shifter_fold_desc;
+
+/*   h_fold, n_fold   host, the layers to fold; a tensor may be listed once; the
+ *                    [out_offset, out_offset + out_ch) ranges must not overlap
+ *   eps              the BatchNorm's epsilon, finite and >= 0
+ *   d_w              device, weight arena in the model's layout (dense or sparse)
+ *   d_vecs           device, the model's vector arena
+ *   d_w_out          device, weight arena of the same layout; may be d_w (in place);
+ *                    elements outside the tensors are not touched
+ *   d_bias_out       device, cap_bias floats; only the listed ranges are written
+ * Waits for the work already on the context's stream (the layer table goes through a
+ * staging buffer), then enqueues the fold and returns without waiting for it.
+ * Errors: SHIFTER_ERR_INVALID_ARG for a bad list (nothing is enqueued). */
+int shifter_fold_bn(shifter_ctx* ctx, const shifter_model* model,
+                    const shifter_fold_desc* h_fold, uint32_t n_fold, float eps,
+                    const float* d_w, const float* d_vecs, float* d_w_out,
+                    float* d_bias_out, uint64_t cap_bias);
+
 /* Module 4, Model Pruner (Algorithm 2, Sec. III-D): every layer rebuilt without its
  * prunable channels.  For tensor t with out-group A, in-group B, m = in_mult:
  *   W'[o', i', y, x] = W[keep_A[o'], keep_B[i' / m] * m + i' % m, y, x]

@@ -1,6 +1,7 @@
 // Host side of the C ABI: descriptor validation, device tables and scratch, argument
 // checks, stream-ordered launches and the small read-backs the ABI documents.
 #include <algorithm>
+#include <cmath>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -14,7 +15,7 @@ namespace shifter {
 const char* const kKernelNames[K_COUNT] = {
     "sel_init", "hist_round0", "hist_round1", "hist_round2", "select", "tie_count",
     "tie_final", "zero_flags", "mask_scan", "scan", "propagate", "plan", "gather",
-    "copy", "kernel_scan", "fix_round", "mask_scan_batch", "expand_levels", "spec_init", "spec_sample", "spec_predict", "spec_pass",
+    "copy", "kernel_scan", "fix_round", "fold_scale", "fold_apply", "mask_scan_batch", "expand_levels", "spec_init", "spec_sample", "spec_predict", "spec_pass",
     "spec_hist_locate", "spec_filter_rank", "spec_fixup"};
 
 ProfileScope::ProfileScope(shifter_ctx* c, int id) : ctx(c), idx(-1) {
@@ -83,7 +84,7 @@ static void unbind(shifter_model* m) {
     (void)hipSetDevice(b.device);
     void* ptrs[] = {b.tens, b.groups, b.vecs, b.producers, b.tile_prefix, b.tile_tensor, b.sel, b.ghist,
                     b.tile_cnt, b.plan_t, b.plan_v, b.plan_h, b.plan_pack, b.out_tile_prefix, b.rect_prefix, b.rowtab_prefix, b.coltab_prefix, b.rowtab, b.coltab, b.kernel_off, b.fix_prefix, b.cons_prefix, b.consumers, b.fix_alive,
-                    b.fix_produced, b.fix_read, b.fix_out_flags, b.fix_removed, b.levels, b.spec, b.shist,
+                    b.fix_produced, b.fix_read, b.fix_out_flags, b.fix_removed, b.fold, b.fold_scale, b.levels, b.spec, b.shist,
                     b.spec_cnt, b.partial, b.cand, b.list, b.ranked_ids, b.multi, b.multi_cnt,
                     b.multi_partial, b.multi_seg, b.multi_seg_cnt};
     for (void* p : ptrs)
@@ -404,6 +405,9 @@ static int bind(shifter_ctx* ctx, const shifter_model* cm) {
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.fix_read), std::max<uint64_t>(m->info.sum_in_ch, 16)));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.fix_out_flags), std::max<uint64_t>(m->info.sum_out_ch, 16)));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.fix_removed), 16));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.fold), sizeof(FoldTensor) * std::max<size_t>(n_t, 1)));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.fold_scale),
+                           sizeof(float) * std::max<uint64_t>(m->info.sum_out_ch, 4)));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.levels),
                            sizeof(uint32_t) * (m->info.sum_out_ch + m->info.sum_in_ch)));
     if ((rc = upload(ctx, &b.ranked_ids, m->ranked_ids.data(), m->ranked_ids.size()))) return rc;
@@ -887,6 +891,63 @@ extern "C" int shifter_propagate_groups_fixpoint(shifter_ctx* ctx, const shifter
     return shifter_propagate_groups_batch(ctx, model, b.fix_out_flags, 1,
                                           flags & SHIFTER_PAPER_FREEZE_RESIDUAL, d_group_alive,
                                           d_index_map, d_keep, d_new_width, h_new_width);
+}
+
+extern "C" int shifter_fold_bn(shifter_ctx* ctx, const shifter_model* model,
+                               const shifter_fold_desc* h_fold, uint32_t n_fold, float eps,
+                               const float* d_w, const float* d_vecs, float* d_w_out,
+                               float* d_bias_out, uint64_t cap_bias) {
+    int rc = enter(ctx, model, "fold_bn");
+    if (rc) return rc;
+    if (!d_w || !d_w_out || (n_fold && (!h_fold || !d_vecs || !d_bias_out)))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "fold_bn: NULL pointer argument");
+    if (misaligned(d_w, 16) || misaligned(d_w_out, 16) || misaligned(d_vecs, 4) || misaligned(d_bias_out, 4))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "fold_bn: weight arenas must be 16-byte aligned");
+    if (!(eps >= 0.0f) || !std::isfinite(eps))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "fold_bn: eps must be finite and not negative");
+    const size_t n_t = model->t.size(), n_v = model->v.size();
+    std::vector<FoldTensor> tab(n_t, FoldTensor{-1, -1, -1, -1, -1, -1});
+    std::vector<std::pair<uint64_t, uint64_t>> spans;
+    for (uint32_t i = 0; i < n_fold; ++i) {
+        const shifter_fold_desc& f = h_fold[i];
+        const std::string at = "fold_bn: entry " + std::to_string(i) + ": ";
+        if (f.tensor >= n_t) return fail(ctx, SHIFTER_ERR_INVALID_ARG, at + "tensor index out of range");
+        if (tab[f.tensor].out_offset >= 0)
+            return fail(ctx, SHIFTER_ERR_INVALID_ARG, at + "tensor listed twice");
+        const uint32_t out_ch = model->t[f.tensor].out_ch;
+        const int32_t bn[4] = {f.gamma, f.beta, f.mean, f.var};
+        const bool has_bn = f.gamma >= 0;
+        int64_t off[5];
+        const int32_t ids[5] = {f.gamma, f.beta, f.mean, f.var, f.bias};
+        for (int j = 0; j < 4; ++j)
+            if ((bn[j] >= 0) != has_bn)
+                return fail(ctx, SHIFTER_ERR_INVALID_ARG, at + "gamma, beta, mean and var go together");
+        for (int j = 0; j < 5; ++j) {
+            off[j] = -1;
+            if (ids[j] < 0) continue;
+            if ((size_t)ids[j] >= n_v) return fail(ctx, SHIFTER_ERR_INVALID_ARG, at + "vector index out of range");
+            if (model->v[ids[j]].len != out_ch)
+                return fail(ctx, SHIFTER_ERR_INVALID_ARG, at + "vector length differs from the tensor's out_ch");
+            off[j] = (int64_t)model->v[ids[j]].offset;
+        }
+        if (f.out_offset > cap_bias || out_ch > cap_bias - f.out_offset)
+            return fail(ctx, SHIFTER_ERR_INVALID_ARG, at + "bias range exceeds cap_bias");
+        spans.push_back({f.out_offset, f.out_offset + out_ch});
+        tab[f.tensor] = FoldTensor{off[0], off[1], off[2], off[3], off[4], (int64_t)f.out_offset};
+    }
+    std::sort(spans.begin(), spans.end());
+    for (size_t i = 1; i < spans.size(); ++i)
+        if (spans[i].first < spans[i - 1].second)
+            return fail(ctx, SHIFTER_ERR_INVALID_ARG, "fold_bn: bias ranges overlap");
+    if (n_t == 0) return SHIFTER_OK;
+    // the pinned staging area may still feed an earlier upload: wait before rewriting it
+    // (read-backs into it are enqueued behind this upload, so they cannot overtake it)
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    memcpy(model->b.host_stage, tab.data(), sizeof(FoldTensor) * n_t);
+    HIP_TRY(ctx, hipMemcpyAsync(model->b.fold, model->b.host_stage, sizeof(FoldTensor) * n_t,
+                                hipMemcpyHostToDevice, ctx->stream));
+    launch_fold(ctx, model, d_w, d_vecs, eps, d_w_out, d_bias_out);
+    return after_launch(ctx, "fold_bn");
 }
 
 // d_thr == NULL: d_w holds K sparse arenas w_stride apart; else d_w is the dense arena

@@ -111,6 +111,12 @@ struct MultiPerm {
     uint32_t v[MAXK];
 };
 
+// Conv + BatchNorm fold: element offsets of a tensor's vectors in the vector arena and of
+// its folded bias in the bias arena; -1: not present.
+struct FoldTensor {
+    int64_t gamma, beta, mean, var, bias, out_offset;
+};
+
 struct PruneCounts {
     uint64_t p[MAXK];
 };
@@ -140,7 +146,7 @@ struct PlanHeader {
 enum KernelId {
     K_SEL_INIT = 0, K_HIST0, K_HIST1, K_HIST2, K_SELECT, K_TIE_COUNT, K_TIE_FINAL,
     K_ZERO_FLAGS, K_MASK_SCAN, K_SCAN, K_PROPAGATE, K_PLAN, K_GATHER,
-    K_COPY, K_KERNEL_SCAN, K_FIX_ROUND, K_MASK_SCAN_BATCH, K_EXPAND_LEVELS, K_SPEC_INIT, K_SPEC_SAMPLE, K_SPEC_PREDICT, K_SPEC_PASS, K_SPEC_FINISH, K_SPEC_FINISH2, K_SPEC_FIXUP,
+    K_COPY, K_KERNEL_SCAN, K_FIX_ROUND, K_FOLD_SCALE, K_FOLD_APPLY, K_MASK_SCAN_BATCH, K_EXPAND_LEVELS, K_SPEC_INIT, K_SPEC_SAMPLE, K_SPEC_PREDICT, K_SPEC_PASS, K_SPEC_FINISH, K_SPEC_FINISH2, K_SPEC_FIXUP,
     K_COUNT
 };
 extern const char* const kKernelNames[K_COUNT];
@@ -207,6 +213,8 @@ struct shifter_model {
         uint8_t* fix_read = nullptr;          // sum_in_ch
         uint8_t* fix_out_flags = nullptr;     // sum_out_ch
         uint32_t* fix_removed = nullptr;      // 1
+        shifter::FoldTensor* fold = nullptr;  // n_tensors
+        float* fold_scale = nullptr;          // sum_out_ch
         shifter::SpecState* spec = nullptr;
         uint32_t* shist = nullptr;            // 65536 sample bins
         uint32_t* spec_cnt = nullptr;         // 2 * SPEC_SUB counters, one 128-byte line each
@@ -302,6 +310,8 @@ void launch_kernel_scan(shifter_ctx* ctx, const shifter_model* m, const float* d
 void launch_fix_begin(shifter_ctx* ctx, const shifter_model* m);
 void launch_fix_round(shifter_ctx* ctx, const shifter_model* m, const uint8_t* d_nz, uint32_t flags);
 void launch_fix_out_flags(shifter_ctx* ctx, const shifter_model* m);
+void launch_fold(shifter_ctx* ctx, const shifter_model* m, const float* d_w, const float* d_vecs,
+                 float eps, float* d_w_out, float* d_bias_out);
 
 // Event bracketing for per-kernel timing.
 struct ProfileScope {

@@ -96,6 +96,15 @@ class Pipeline:
                                           self.d_index_map, self.d_keep, self.d_new_width,
                                           sync)
 
+    def fold_bn(self, folds, n_bias: int, eps: float, src=None, dst=None):
+        """Conv + BatchNorm fold of an arena (default: the sparse one) into ``dst`` (default:
+        a new arena).  Returns (folded weight arena, bias arena of n_bias floats)."""
+        src = self.d_w_sparse if src is None else src
+        dst = torch.empty_like(src) if dst is None else dst
+        d_bias = torch.zeros(max(n_bias, 4), dtype=torch.float32, device=self.dev)
+        S.shifter_fold_bn(self.ctx, self.model, folds, eps, src, self.d_vecs, dst, d_bias)
+        return dst, d_bias
+
     def kernel_scan(self, src=None):
         """Kernel-level zero index of the sparse arena (input of the liveness fixpoint)."""
         if getattr(self, "d_kernel_nz", None) is None:

@@ -57,6 +57,12 @@ class ModelInfo(C.Structure):
 
 THRESHOLD_BYTES = C.sizeof(Threshold)
 
+class FoldDesc(C.Structure):
+    _fields_ = [("tensor", C.c_uint32), ("gamma", C.c_int32), ("beta", C.c_int32),
+                ("mean", C.c_int32), ("var", C.c_int32), ("bias", C.c_int32),
+                ("out_offset", C.c_uint64)]
+
+
 EXPORTS = {
     "shifter_create": [C.POINTER(C.c_void_p), C.c_int, C.c_void_p],
     "shifter_destroy": [C.c_void_p],
@@ -77,6 +83,8 @@ EXPORTS = {
     "shifter_prune_fused": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p,
                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                             C.POINTER(Threshold)],
+    "shifter_fold_bn": [C.c_void_p, C.c_void_p, C.POINTER(FoldDesc), C.c_uint32, C.c_float,
+                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64],
     "shifter_apply_mask": [C.c_void_p] * 8,
     "shifter_dead_channel_scan": [C.c_void_p] * 5,
     "shifter_propagate_groups": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
@@ -310,6 +318,19 @@ def shifter_prune_fused_batch(ctx: Context, model: Model, d_w, n_prune: Sequence
         ctx.handle, model.handle, _ptr(d_w), arr, k, _ptr(d_thr), _ptr(d_w_out), w_stride,
         _ptr(d_mask), mask_stride, _ptr(d_out_alive), _ptr(d_in_alive), h), ctx.handle)
     return list(h)[:k]
+
+
+def shifter_fold_bn(ctx: Context, model: Model, folds, eps: float, d_w, d_vecs, d_w_out,
+                    d_bias_out) -> None:
+    """folds: objects with tensor, gamma, beta, mean, var, bias, out_offset (-1: absent).
+    The capacity of the bias arena is the length of d_bias_out."""
+    arr = (FoldDesc * max(len(folds), 1))()
+    for i, f in enumerate(folds):
+        arr[i] = FoldDesc(f.tensor, f.gamma, f.beta, f.mean, f.var, f.bias, f.out_offset)
+    cap = d_bias_out.numel() if d_bias_out is not None else 0
+    _check(load_library().shifter_fold_bn(ctx.handle, model.handle, arr, len(folds), eps,
+                                          _ptr(d_w), _ptr(d_vecs), _ptr(d_w_out),
+                                          _ptr(d_bias_out), cap), ctx.handle)
 
 
 def shifter_kernel_scan(ctx: Context, model: Model, d_w_sparse, d_kernel_nz) -> None:
