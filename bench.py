@@ -232,6 +232,28 @@ def measure(name, steps, warmup, lean_run=True):
         fixpoint["kernel_scan_us"] = round(ks_ms * 1e3, 2)
         fixpoint["kernel_scan_read_gbs"] = round(4 * n / (ks_ms * 1e-3) / 1e9, 1)
 
+    # Module 1's conv + BatchNorm fold of the sparse arena: one read and one write of every
+    # weight (8 bytes per weight), a streaming kernel of its own
+    fold = None
+    if k_var == 1 and lean_run:
+        step()
+        fspec, folds = synth.fused_spec(spec)
+        dst = torch.empty_like(pl.d_w_sparse)
+        pl.fold_bn(folds, fspec.v_elems, 1e-5, dst=dst)
+        S.shifter_profile_enable(pl.ctx, True)
+        for _ in range(5):
+            pl.fold_bn(folds, fspec.v_elems, 1e-5, dst=dst)
+        fp = S.shifter_profile_read(pl.ctx)
+        S.shifter_profile_enable(pl.ctx, False)
+        fa_ms = fp["fold_apply"][1] / fp["fold_apply"][0]
+        fs_ms = fp["fold_scale"][1] / fp["fold_scale"][0]
+        fbytes = 8 * spec.w_elems
+        fold = {"fold_apply_us": round(fa_ms * 1e3, 2), "fold_scale_us": round(fs_ms * 1e3, 2),
+                "bytes_per_launch": fbytes,
+                "gbs": round(fbytes / (fa_ms * 1e-3) / 1e9, 1),
+                "frac_of_peak": round(fbytes / (fa_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        del dst
+
     out = {
         "value": round(gbs, 2),
         "unit": "GB/s",
@@ -256,6 +278,8 @@ def measure(name, steps, warmup, lean_run=True):
         out["without_sparse_arenas"] = lean
     if fixpoint is not None:
         out["liveness_fixpoint"] = fixpoint
+    if fold is not None:
+        out["conv_bn_fold"] = fold
     pl.close()
     del pl
     torch.cuda.empty_cache()

@@ -7,10 +7,12 @@ import numpy as np
 import pytest
 import torch
 
+from oracle import fold_oracle as FO
 from oracle import shifter_oracle as O
 from paper_2309_06973_amd import shifter as S
 from paper_2309_06973_amd import synth
 from paper_2309_06973_amd.pipeline import Pipeline
+from test_gpu_fold import bias_bound
 
 pytestmark = pytest.mark.gpu
 
@@ -100,6 +102,20 @@ def test_c5_single_sweep_fused(c5):
         assert ew == comp_f.w.size and ev == comp_f.v.size and ew <= comp.w.size
         assert np.array_equal(bits(pl.d_w_out[:ew].cpu().numpy()), bits(comp_f.w))
         assert np.array_equal(bits(pl.d_vecs_out[:ev].cpu().numpy()), bits(comp_f.v))
+        # Module 1's fold of the sparse arena, in place, against the fp64 oracle at the
+        # bound of its four roundings (see the fold tests); zeros stay zeros
+        fspec, folds = synth.fused_spec(spec)
+        eps = float(np.float32(1e-5))
+        ref_w, ref_b = FO.fold_bn(ws, v, spec.tensors, spec.vecs, folds, eps, fspec.v_elems)
+        got_w, got_b = pl.fold_bn(folds, fspec.v_elems, eps, dst=pl.d_w_sparse)
+        torch.cuda.synchronize()
+        gw = got_w.cpu().numpy()
+        u = 2.0 ** -24
+        assert np.all(np.abs(gw - ref_w) <= 4 * u * np.abs(ref_w) + 2.0 ** -149)
+        assert np.array_equal(gw == 0, ws == 0)
+        gb = got_b.cpu().numpy()[:fspec.v_elems]
+        assert np.all(np.abs(gb - ref_b) <= 4 * u * bias_bound(v, spec, folds, fspec.v_elems, eps)
+                      + u * np.abs(ref_b) + 2.0 ** -149)
     finally:
         pl.close()
 
