@@ -344,6 +344,54 @@ int shifter_fold_bn(shifter_ctx* ctx, const shifter_model* model,
                     const float* d_w, const float* d_vecs, float* d_w_out,
                     float* d_bias_out, uint64_t cap_bias);
 
+/* --- Phase 3 codec (Sec. III-E): Module 7 deflates inactive models, Module 8 inflates --
+ *
+ * shifter_deflate turns a byte buffer (a model's arena) into one DEFLATE stream (RFC
+ * 1951) that any inflater reads, laid out for chunk-parallel decoding:
+ *   - the input is cut into chunks of SHIFTER_CODEC_CHUNK bytes and every chunk into
+ *     sub-chunks of SHIFTER_CODEC_SUB bytes; chunk c becomes the byte-aligned segment
+ *     [seg_off[c], seg_off[c + 1]) of the stream;
+ *   - tokens of a sub-chunk, left to right: a maximal run of r >= 4 equal bytes (cut at the
+ *     sub-chunk's end) is one literal and distance-1 matches over the other r - 1 bytes
+ *     (258 while more than 260 remain; then one piece, or the pieces (rest - 3, 3) when 259
+ *     or 260 remain); every other byte is a literal;
+ *   - a segment is either a fixed-Huffman block (BFINAL = 0; the tokens; end of block)
+ *     followed by an empty stored block that pads to a byte boundary, or, when that is
+ *     not shorter, one stored block holding the chunk; BFINAL = 1 only on the last block
+ *     of the last segment; an empty input gives the 5-byte stream 01 00 00 FF FF;
+ *   - side information, not part of the stream: seg_off, and per sub-chunk the number of
+ *     token bits (0 for stored segments).
+ * The output is a deterministic function of the input.
+ *
+ * shifter_codec_layout   sizes for n_bytes of input: chunks (at least 1), bytes of
+ *                        workspace, and the largest possible stream (any of the three
+ *                        outputs may be NULL)
+ * shifter_deflate
+ *   d_in, n_bytes        device, 16-byte aligned input (may be NULL when n_bytes = 0)
+ *   d_work, work_bytes   device, 256-byte aligned scratch of at least the layout's size
+ *   d_stream, stream_cap device, 16-byte aligned; capacity in bytes
+ *   d_seg_off            device, n_chunks + 1 uint64; the last entry is the stream's size
+ *   d_sub_bits           device, n_chunks * (CHUNK / SUB) uint16
+ *   h_stream_bytes       host or NULL.  Non-NULL: the call waits for the stream and stores
+ *                        the stream's size; returns SHIFTER_ERR_CAPACITY (size still
+ *                        stored, nothing written to d_stream) when stream_cap is too small
+ * shifter_inflate        decodes a stream made by shifter_deflate, given its side
+ *                        information, into n_bytes at d_out (device, 16-byte aligned).
+ *                        Always waits; SHIFTER_ERR_INVALID_ARG with "bad stream" when the
+ *                        stream, the offsets or the bit counts do not fit together (all
+ *                        accesses stay inside the buffers; d_out is then unspecified).
+ * The first codec call on a context allocates 16 bytes of device and of pinned memory. */
+#define SHIFTER_CODEC_CHUNK 32768u
+#define SHIFTER_CODEC_SUB 512u
+int shifter_codec_layout(uint64_t n_bytes, uint64_t* h_n_chunks, uint64_t* h_work_bytes,
+                         uint64_t* h_stream_bound);
+int shifter_deflate(shifter_ctx* ctx, const void* d_in, uint64_t n_bytes, void* d_work,
+                    uint64_t work_bytes, uint8_t* d_stream, uint64_t stream_cap,
+                    uint64_t* d_seg_off, uint16_t* d_sub_bits, uint64_t* h_stream_bytes);
+int shifter_inflate(shifter_ctx* ctx, const uint8_t* d_stream, uint64_t stream_bytes,
+                    const uint64_t* d_seg_off, const uint16_t* d_sub_bits, uint64_t n_bytes,
+                    void* d_out);
+
 /* Module 4, Model Pruner (Algorithm 2, Sec. III-D): every layer rebuilt without its
  * prunable channels.  For tensor t with out-group A, in-group B, m = in_mult:
  *   W'[o', i', y, x] = W[keep_A[o'], keep_B[i' / m] * m + i' % m, y, x]

@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libshifter.so")
 SOURCES = ["api.hip", "select.hip", "spec_select.hip", "spec_multi.hip", "mask_scan.hip", "batch.hip", "plan_compact.hip",
-           "fixpoint.hip", "fold.hip"]
+           "fixpoint.hip", "fold.hip", "codec.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall",
          "-Wno-unused-result",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

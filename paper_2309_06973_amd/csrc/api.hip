@@ -15,7 +15,7 @@ namespace shifter {
 const char* const kKernelNames[K_COUNT] = {
     "sel_init", "hist_round0", "hist_round1", "hist_round2", "select", "tie_count",
     "tie_final", "zero_flags", "mask_scan", "scan", "propagate", "plan", "gather",
-    "copy", "kernel_scan", "fix_round", "fold_scale", "fold_apply", "mask_scan_batch", "expand_levels", "spec_init", "spec_sample", "spec_predict", "spec_pass",
+    "copy", "kernel_scan", "fix_round", "fold_scale", "fold_apply", "deflate_chunk", "codec_scan", "codec_pack", "inflate_chunk", "mask_scan_batch", "expand_levels", "spec_init", "spec_sample", "spec_predict", "spec_pass",
     "spec_hist_locate", "spec_filter_rank", "spec_fixup"};
 
 ProfileScope::ProfileScope(shifter_ctx* c, int id) : ctx(c), idx(-1) {
@@ -100,6 +100,8 @@ extern "C" int shifter_destroy(shifter_ctx* ctx) {
     (void)hipStreamSynchronize(ctx->stream);
     for (auto& r : ctx->recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     for (auto e : ctx->pool) (void)hipEventDestroy(e);
+    if (ctx->d_codec) (void)hipFree(ctx->d_codec);
+    if (ctx->h_codec) (void)hipHostFree(ctx->h_codec);
     delete ctx;
     return SHIFTER_OK;
 }
@@ -1084,6 +1086,99 @@ extern "C" int shifter_profile_read(shifter_ctx* ctx, const char** names, uint32
         ++n;
     }
     *n_out = n < cap ? n : cap;
+    return SHIFTER_OK;
+}
+
+static uint64_t codec_chunks(uint64_t n_bytes) {
+    return n_bytes == 0 ? 1 : (n_bytes + SHIFTER_CODEC_CHUNK - 1) / SHIFTER_CODEC_CHUNK;
+}
+static uint64_t codec_work_bytes(uint64_t n_chunks) {
+    return codec_slots_offset(n_chunks) + n_chunks * (uint64_t)(SHIFTER_CODEC_CHUNK + 8u);
+}
+
+extern "C" int shifter_codec_layout(uint64_t n_bytes, uint64_t* h_n_chunks, uint64_t* h_work_bytes,
+                                    uint64_t* h_stream_bound) {
+    const uint64_t n_chunks = codec_chunks(n_bytes);
+    if (h_n_chunks) *h_n_chunks = n_chunks;
+    if (h_work_bytes) *h_work_bytes = codec_work_bytes(n_chunks);
+    if (h_stream_bound) *h_stream_bound = n_bytes + 5u * n_chunks;   // every segment stored
+    return SHIFTER_OK;
+}
+
+static int codec_enter(shifter_ctx* ctx, const char* fn) {
+    if (!ctx) return fail(nullptr, SHIFTER_ERR_INVALID_ARG, std::string(fn) + ": ctx is NULL");
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    if (!ctx->d_codec) {
+        HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->d_codec), 2 * sizeof(uint64_t)));
+        HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->h_codec), 2 * sizeof(uint64_t),
+                                   hipHostMallocDefault));
+    }
+    return SHIFTER_OK;
+}
+
+static int codec_result(shifter_ctx* ctx, uint64_t* total, uint64_t* status) {
+    HIP_TRY(ctx, hipMemcpyAsync(ctx->h_codec, ctx->d_codec, 2 * sizeof(uint64_t), hipMemcpyDeviceToHost,
+                                ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    *total = ctx->h_codec[0];
+    *status = ctx->h_codec[1];
+    return SHIFTER_OK;
+}
+
+extern "C" int shifter_deflate(shifter_ctx* ctx, const void* d_in, uint64_t n_bytes, void* d_work,
+                               uint64_t work_bytes, uint8_t* d_stream, uint64_t stream_cap,
+                               uint64_t* d_seg_off, uint16_t* d_sub_bits, uint64_t* h_stream_bytes) {
+    int rc = codec_enter(ctx, "deflate");
+    if (rc) return rc;
+    if ((!d_in && n_bytes) || !d_work || !d_stream || !d_seg_off || !d_sub_bits)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "deflate: NULL pointer argument");
+    if (misaligned(d_in, 16) || misaligned(d_work, 256) || misaligned(d_stream, 16) ||
+        misaligned(d_seg_off, 8) || misaligned(d_sub_bits, 2))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG,
+                    "deflate: input and stream must be 16-byte aligned, the workspace 256-byte aligned");
+    const uint64_t n_chunks = codec_chunks(n_bytes);
+    if (n_chunks >= (1ull << 31))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "deflate: input too large (2^31 chunks or more)");
+    if (work_bytes < codec_work_bytes(n_chunks))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG,
+                    "deflate: workspace too small, needs " + std::to_string(codec_work_bytes(n_chunks)) + " bytes");
+    launch_deflate(ctx, static_cast<const uint8_t*>(d_in), n_bytes, (uint32_t)n_chunks,
+                   static_cast<uint8_t*>(d_work), d_stream, stream_cap, d_seg_off, d_sub_bits);
+    if ((rc = after_launch(ctx, "deflate"))) return rc;
+    if (!h_stream_bytes) return SHIFTER_OK;
+    uint64_t total, status;
+    if ((rc = codec_result(ctx, &total, &status))) return rc;
+    *h_stream_bytes = total;
+    if (status)
+        return fail(ctx, SHIFTER_ERR_CAPACITY,
+                    "deflate: the stream takes " + std::to_string(total) + " bytes, capacity " +
+                        std::to_string(stream_cap));
+    return SHIFTER_OK;
+}
+
+extern "C" int shifter_inflate(shifter_ctx* ctx, const uint8_t* d_stream, uint64_t stream_bytes,
+                               const uint64_t* d_seg_off, const uint16_t* d_sub_bits,
+                               uint64_t n_bytes, void* d_out) {
+    int rc = codec_enter(ctx, "inflate");
+    if (rc) return rc;
+    if (!d_stream || !d_seg_off || !d_sub_bits || (!d_out && n_bytes))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "inflate: NULL pointer argument");
+    if (misaligned(d_stream, 16) || misaligned(d_out, 16) || misaligned(d_seg_off, 8) ||
+        misaligned(d_sub_bits, 2))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "inflate: stream and output must be 16-byte aligned");
+    const uint64_t n_chunks = codec_chunks(n_bytes);
+    if (n_chunks >= (1ull << 31))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "inflate: output too large (2^31 chunks or more)");
+    if (stream_bytes < 5u * n_chunks)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "inflate: bad stream (shorter than its segments' headers)");
+    launch_inflate(ctx, d_stream, stream_bytes, d_seg_off, d_sub_bits, n_bytes, (uint32_t)n_chunks,
+                   static_cast<uint8_t*>(d_out));
+    if ((rc = after_launch(ctx, "inflate"))) return rc;
+    uint64_t total, status;
+    if ((rc = codec_result(ctx, &total, &status))) return rc;
+    if (status)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG,
+                    "inflate: bad stream (segments, offsets and bit counts do not fit together)");
     return SHIFTER_OK;
 }
 

@@ -1,0 +1,443 @@
+// Portfolio codec (Sec. III-E, Modules 7 and 8): inactive models are kept as DEFLATE
+// streams (RFC 1951) and inflated when they are to run.  The encoder is built for
+// chunk-parallel work on both sides:
+//   - chunks of 32768 bytes, each its own byte-aligned segment of the stream; inside a
+//     chunk 64 sub-chunks of 512 bytes, one lane each;
+//   - tokens: literals, and for a run of r >= 4 equal bytes inside a sub-chunk one literal
+//     followed by distance-1 matches over the other r - 1 bytes (258 while more than 260
+//     remain, then one piece, or (rest - 3, 3) when 259 or 260 remain);
+//   - a segment is a fixed-Huffman block (header, tokens, end of block) followed by an
+//     empty stored block that pads to a byte, or, when that is not shorter, one stored
+//     block with the chunk verbatim; BFINAL only on the last block of the last segment;
+//   - side information for the decoder: the byte offset of every segment and the token
+//     bits of every sub-chunk (0 for stored segments).
+// Any inflater reads the stream; the decoder here reads this encoder's streams, one wave
+// per chunk, one lane per sub-chunk.
+#include <string>
+
+#include "dev_common.h"
+
+namespace shifter {
+
+constexpr uint32_t CODEC_CHUNK = SHIFTER_CODEC_CHUNK;
+constexpr uint32_t CODEC_SUB = SHIFTER_CODEC_SUB;
+constexpr uint32_t CODEC_NSUB = CODEC_CHUNK / CODEC_SUB;      // 64: one wave
+constexpr uint32_t CODEC_SUBW = CODEC_SUB / 4;                // dwords per sub-chunk
+constexpr uint32_t CODEC_SLOT = CODEC_CHUNK + 8;              // bytes of a chunk's slot in the workspace
+static_assert(CODEC_NSUB == 64, "one lane per sub-chunk");
+
+enum : uint32_t { CODEC_BAD_STREAM = 1u, CODEC_CAPACITY = 2u };
+
+// Sub-chunk l, dword j of the chunk staged in LDS: rotated by the lane so that the lanes
+// of a wave, each walking its own sub-chunk at the same pace, hit different banks.
+__device__ __forceinline__ uint32_t sub_word(uint32_t l, uint32_t j) {
+    return l * CODEC_SUBW + ((j + l) & (CODEC_SUBW - 1));
+}
+
+// Fixed literal code of RFC 1951 section 3.2.6, bit-reversed so that it can be appended
+// from the least significant bit; returns the number of bits.
+__device__ __forceinline__ uint32_t literal_code(uint32_t v, uint32_t* code) {
+    if (v < 144u) { *code = __brev(0x30u + v) >> 24; return 8u; }
+    *code = __brev(0x190u + (v - 144u)) >> 23;
+    return 9u;
+}
+
+// A match of `len` (3..258) at distance 1: length code, extra bits, 5-bit distance code 0.
+__device__ __forceinline__ uint32_t match_code(uint32_t len, uint32_t* code) {
+    uint32_t idx, e = 0, extra = 0;
+    if (len == 258u) {
+        idx = 28u;
+    } else if (len < 11u) {
+        idx = len - 3u;
+    } else {
+        const uint32_t x = len - 3u;              // 8..254
+        e = 29u - (uint32_t)__clz(x);             // floor(log2 x) - 2
+        idx = 4u * e + 4u + ((x >> e) & 3u);
+        extra = x & ((1u << e) - 1u);
+    }
+    uint32_t c, n;
+    if (idx < 23u) { c = __brev(1u + idx) >> 25; n = 7u; }         // symbols 257..279
+    else { c = __brev(0xC0u + (idx - 23u)) >> 24; n = 8u; }        // symbols 280..285
+    *code = c | (extra << n);
+    return n + e + 5u;
+}
+
+struct BitCounter {
+    uint32_t bits = 0;
+    __device__ __forceinline__ void put(uint32_t, uint32_t n) { bits += n; }
+};
+
+// Appends bits to the chunk's bit buffer in LDS.  Dwords that a lane fills completely are
+// its own; its first and its last dword may be shared with the neighbours and are OR-ed.
+struct BitWriter {
+    uint32_t* buf;
+    uint64_t acc;
+    uint32_t cnt, widx;
+    bool first;
+    __device__ __forceinline__ BitWriter(uint32_t* b, uint32_t start_bit)
+        : buf(b), acc(0), cnt(start_bit & 31u), widx(start_bit >> 5), first(true) {}
+    __device__ __forceinline__ void put(uint32_t code, uint32_t n) {
+        acc |= (uint64_t)code << cnt;
+        cnt += n;
+        if (cnt >= 32u) {
+            if (first) { atomicOr(&buf[widx], (uint32_t)acc); first = false; }
+            else buf[widx] = (uint32_t)acc;
+            ++widx;
+            acc >>= 32;
+            cnt -= 32u;
+        }
+    }
+    __device__ __forceinline__ void finish() {
+        if (cnt) atomicOr(&buf[widx], (uint32_t)acc);
+    }
+};
+
+// Tokens of sub-chunk `l` (n bytes) of the chunk in s_in, sent to `sink`.
+template <class Sink>
+__device__ __forceinline__ void encode_sub(const uint32_t* s_in, uint32_t l, uint32_t n, Sink& sink) {
+    auto word = [&](uint32_t j) { return s_in[sub_word(l, j)]; };
+    auto byte = [&](uint32_t i) { return (word(i >> 2) >> ((i & 3u) * 8u)) & 0xffu; };
+    uint32_t i = 0;
+    while (i < n) {
+        const uint32_t b = byte(i);
+        uint32_t j = i + 1;
+        bool same = true;
+        while (j < n && (j & 3u)) {
+            if (byte(j) != b) { same = false; break; }
+            ++j;
+        }
+        if (same) {
+            const uint32_t pat = b * 0x01010101u;
+            while (j + 4u <= n && word(j >> 2) == pat) j += 4u;
+            while (j < n && byte(j) == b) ++j;
+        }
+        const uint32_t r = j - i;
+        uint32_t code;
+        uint32_t nb = literal_code(b, &code);
+        sink.put(code, nb);
+        if (r >= 4u) {
+            uint32_t rest = r - 1u;
+            while (rest > 260u) {
+                nb = match_code(258u, &code);
+                sink.put(code, nb);
+                rest -= 258u;
+            }
+            if (rest <= 258u) {
+                nb = match_code(rest, &code);
+                sink.put(code, nb);
+            } else {
+                nb = match_code(rest - 3u, &code);
+                sink.put(code, nb);
+                nb = match_code(3u, &code);
+                sink.put(code, nb);
+            }
+            i += r;
+        } else {
+            i += 1u;
+        }
+    }
+}
+
+__device__ __forceinline__ uint32_t wave_excl_scan(uint32_t v, uint32_t lane, uint32_t* total) {
+    uint32_t x = v;
+    for (uint32_t d = 1; d < 64; d <<= 1) {
+        const uint32_t y = __shfl_up(x, d, 64);
+        if (lane >= d) x += y;
+    }
+    *total = __shfl(x, 63, 64);
+    return x - v;
+}
+
+// One wave per chunk: stages the chunk in LDS, counts the token bits of every sub-chunk,
+// chooses the segment type, builds the segment in LDS (Huffman) and writes it to the
+// chunk's slot of the workspace together with its size.
+__global__ __launch_bounds__(64) void deflate_chunk_kernel(
+    const uint8_t* __restrict__ in, uint64_t n_bytes, uint32_t n_chunks,
+    uint8_t* __restrict__ slots, uint32_t* __restrict__ seg_size, uint16_t* __restrict__ sub_bits) {
+    __shared__ uint32_t s_in[CODEC_CHUNK / 4];
+    __shared__ uint32_t s_out[CODEC_CHUNK / 4 + 8];
+    const uint32_t c = blockIdx.x, lane = threadIdx.x;
+    const uint64_t base = (uint64_t)c * CODEC_CHUNK;
+    const uint32_t m = (uint32_t)min((uint64_t)CODEC_CHUNK, n_bytes - min(n_bytes, base));
+    const uint32_t last = c + 1u == n_chunks ? 1u : 0u;
+    // stage: whole dwords coalesced, the ragged tail byte by byte, the rest zero
+    const uint32_t* in32 = reinterpret_cast<const uint32_t*>(in + base);
+    for (uint32_t g = lane; g < CODEC_CHUNK / 4; g += 64u) {
+        uint32_t v = 0;
+        if (g * 4u + 4u <= m) {
+            v = in32[g];
+        } else {
+            for (uint32_t k = 0; k < 4u; ++k)
+                if (g * 4u + k < m) v |= (uint32_t)in[base + g * 4u + k] << (8u * k);
+        }
+        s_in[sub_word(g / CODEC_SUBW, g % CODEC_SUBW)] = v;
+    }
+    __syncthreads();
+    const uint32_t n_l = min(CODEC_SUB, m - min(m, lane * CODEC_SUB));
+    BitCounter cnt;
+    encode_sub(s_in, lane, n_l, cnt);
+    uint32_t tok_total;
+    const uint32_t tok_start = wave_excl_scan(cnt.bits, lane, &tok_total);
+    const uint32_t body = 3u + tok_total + 10u;             // header, tokens, end of block, next header
+    const uint32_t pad = (8u - (body & 7u)) & 7u;
+    const uint32_t huff_bytes = (body + pad) / 8u + 4u;
+    uint32_t* slot32 = reinterpret_cast<uint32_t*>(slots + (uint64_t)c * CODEC_SLOT);
+    if (m + 5u <= huff_bytes) {
+        // stored block: header byte, LEN, NLEN, then the chunk, shifted by five bytes
+        sub_bits[(uint64_t)c * CODEC_NSUB + lane] = 0;
+        if (lane == 0) seg_size[c] = m + 5u;
+        const uint32_t n_w = (m + 5u + 3u) / 4u;
+        auto src = [&](uint32_t g) {               // dword g of the chunk (0 beyond it)
+            return g < CODEC_CHUNK / 4 ? s_in[sub_word(g / CODEC_SUBW, g % CODEC_SUBW)] : 0u;
+        };
+        for (uint32_t k = lane; k < n_w; k += 64u) {
+            uint32_t v;
+            if (k == 0) v = last | (m << 8) | ((m ^ 0xffffu) << 24);
+            else if (k == 1) v = ((m ^ 0xffffu) >> 8) | (src(0) << 8);
+            else v = (src(k - 2) >> 24) | (src(k - 1) << 8);
+            slot32[k] = v;
+        }
+        return;
+    }
+    sub_bits[(uint64_t)c * CODEC_NSUB + lane] = (uint16_t)cnt.bits;
+    if (lane == 0) seg_size[c] = huff_bytes;
+    // bit range of this lane: lane 0 also writes the header, lane 63 the tail
+    const uint32_t start = lane == 0 ? 0u : 3u + tok_start;
+    const uint32_t end = lane == 63u ? huff_bytes * 8u : 3u + tok_start + cnt.bits;
+    if (end > start) {
+        s_out[start >> 5] = 0;
+        s_out[(end - 1u) >> 5] = 0;
+    }
+    __syncthreads();
+    if (end > start) {
+        BitWriter w(s_out, start);
+        if (lane == 0) w.put(2u, 3u);              // BFINAL = 0, BTYPE = 01
+        encode_sub(s_in, lane, n_l, w);
+        if (lane == 63u) {
+            w.put(0u, 7u);                         // end of block
+            w.put(last, 3u);                       // empty stored block: BFINAL, BTYPE = 00
+            w.put(0u, pad);
+            w.put(0x0000u, 16u);
+            w.put(0xffffu, 16u);
+        }
+        w.finish();
+    }
+    __syncthreads();
+    const uint32_t n_w = (huff_bytes + 3u) / 4u;
+    for (uint32_t k = lane; k < n_w; k += 64u) slot32[k] = s_out[k];
+}
+
+// Byte offsets of the segments: exclusive prefix sums of their sizes (one block).
+__global__ __launch_bounds__(1024) void codec_scan_kernel(const uint32_t* __restrict__ seg_size,
+                                                          uint32_t n_chunks,
+                                                          uint64_t* __restrict__ seg_off,
+                                                          uint64_t stream_cap,
+                                                          uint64_t* __restrict__ result) {
+    __shared__ uint64_t s_wave[16];
+    __shared__ uint64_t s_carry;
+    const uint32_t lane = threadIdx.x & 63u, wid = threadIdx.x >> 6;
+    if (threadIdx.x == 0) s_carry = 0;
+    __syncthreads();
+    for (uint32_t b0 = 0; b0 < n_chunks; b0 += 1024u) {
+        const uint32_t i = b0 + threadIdx.x;
+        const uint64_t v = i < n_chunks ? seg_size[i] : 0u;
+        unsigned long long x = v;
+        for (uint32_t d = 1; d < 64; d <<= 1) {
+            const unsigned long long y = __shfl_up(x, d, 64);
+            if (lane >= d) x += y;
+        }
+        if (lane == 63u) s_wave[wid] = x;
+        __syncthreads();
+        uint64_t off = s_carry;
+        for (uint32_t k = 0; k < wid; ++k) off += s_wave[k];
+        if (i < n_chunks) seg_off[i] = off + x - v;
+        __syncthreads();
+        if (threadIdx.x == 1023u) s_carry = off + x;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        seg_off[n_chunks] = s_carry;
+        result[0] = s_carry;
+        result[1] = s_carry > stream_cap ? CODEC_CAPACITY : 0u;
+    }
+}
+
+// Moves every segment from its slot to its place in the stream (one wave per chunk).  The
+// slot is dword aligned, the destination is not: whole destination dwords are assembled
+// from two source dwords, the ragged ends go byte by byte.
+__global__ __launch_bounds__(64) void codec_pack_kernel(const uint8_t* __restrict__ slots,
+                                                        const uint32_t* __restrict__ seg_size,
+                                                        const uint64_t* __restrict__ seg_off,
+                                                        const uint64_t* __restrict__ result,
+                                                        uint8_t* __restrict__ stream) {
+    if (result[1] != 0) return;                       // the stream does not fit: write nothing
+    const uint32_t c = blockIdx.x, lane = threadIdx.x;
+    const uint8_t* src = slots + (uint64_t)c * CODEC_SLOT;
+    const uint32_t* src32 = reinterpret_cast<const uint32_t*>(src);
+    uint8_t* dst = stream + seg_off[c];
+    const uint32_t len = seg_size[c];
+    const uint32_t head = min(len, (uint32_t)((4u - (reinterpret_cast<uintptr_t>(dst) & 3u)) & 3u));
+    if (lane < head) dst[lane] = src[lane];
+    const uint32_t n_w = (len - head) / 4u;
+    uint32_t* dst32 = reinterpret_cast<uint32_t*>(dst + head);
+    const uint32_t sh = head * 8u;
+    for (uint32_t k = lane; k < n_w; k += 64u) {
+        // bytes head + 4k .. head + 4k + 3 of the slot (its last dword + 1 is still inside it)
+        const uint32_t lo = src32[k];
+        dst32[k] = sh ? (lo >> sh) | (src32[k + 1] << (32u - sh)) : lo;
+    }
+    const uint32_t done = head + n_w * 4u;
+    if (lane < len - done) dst[done + lane] = src[done + lane];
+}
+
+// One wave per chunk.  A stored segment is copied; in a Huffman segment every lane decodes
+// the tokens of its sub-chunk (the side information says where they start) into LDS, and
+// the chunk is written out coalesced.  Anything but this library's own token set marks the
+// stream as bad; no access leaves the stream or the output.
+__global__ __launch_bounds__(64) void inflate_chunk_kernel(
+    const uint8_t* __restrict__ stream, uint64_t stream_bytes, const uint64_t* __restrict__ seg_off,
+    const uint16_t* __restrict__ sub_bits, uint64_t n_bytes, uint32_t n_chunks,
+    uint8_t* __restrict__ out, uint64_t* __restrict__ result) {
+    __shared__ uint32_t s_out[CODEC_CHUNK / 4];
+    const uint32_t c = blockIdx.x, lane = threadIdx.x;
+    const uint64_t base = (uint64_t)c * CODEC_CHUNK;
+    const uint32_t m = (uint32_t)min((uint64_t)CODEC_CHUNK, n_bytes - min(n_bytes, base));
+    const uint64_t s0 = seg_off[c], s1 = seg_off[c + 1];
+    auto bad = [&]() { atomicOr(reinterpret_cast<unsigned long long*>(&result[1]), (unsigned long long)CODEC_BAD_STREAM); };
+    if (s1 < s0 || s1 > stream_bytes || s1 - s0 < 5u || s1 - s0 > CODEC_SLOT) {
+        if (lane == 0) bad();
+        return;
+    }
+    const uint8_t* seg = stream + s0;
+    const uint32_t seg_len = (uint32_t)(s1 - s0);
+    const uint32_t btype = (seg[0] >> 1) & 3u;
+    uint8_t* dst = out + base;
+    if (btype == 0u) {
+        const uint32_t len = seg[1] | ((uint32_t)seg[2] << 8), nlen = seg[3] | ((uint32_t)seg[4] << 8);
+        if (len != m || (len ^ nlen) != 0xffffu || seg_len != m + 5u) {
+            if (lane == 0) bad();
+            return;
+        }
+        for (uint32_t k = lane; k < m; k += 64u) dst[k] = seg[5u + k];
+        return;
+    }
+    if (btype != 1u) {
+        if (lane == 0) bad();
+        return;
+    }
+    const uint32_t n_l = min(CODEC_SUB, m - min(m, lane * CODEC_SUB));
+    const uint32_t my_bits = sub_bits[(uint64_t)c * CODEC_NSUB + lane];
+    uint32_t tok_total;
+    const uint32_t tok_start = wave_excl_scan(my_bits, lane, &tok_total);
+    bool ok = (uint64_t)3u + tok_total + 10u <= (uint64_t)seg_len * 8u;
+    // the window is read as dwords aligned to the stream's start; never beyond its end
+    const uint64_t seg_bit0 = (s0 & 3u) * 8u;
+    const uint32_t* seg32 = reinterpret_cast<const uint32_t*>(stream + (s0 & ~(uint64_t)3u));
+    const uint32_t max_w = (uint32_t)(((stream_bytes + 3u) / 4u) - (s0 >> 2)) - 1u;   // last readable dword
+    const bool tail_partial = (stream_bytes & 3u) != 0;
+    auto load_w = [&](uint32_t w) -> uint32_t {
+        if (w > max_w) return 0u;
+        if (w == max_w && tail_partial) {          // the stream's last, partial dword: bytes
+            uint32_t v = 0;
+            const uint64_t b0 = (s0 & ~(uint64_t)3u) + (uint64_t)w * 4u;
+            for (uint32_t k = 0; k < 4u; ++k)
+                if (b0 + k < stream_bytes) v |= (uint32_t)stream[b0 + k] << (8u * k);
+            return v;
+        }
+        return seg32[w];
+    };
+    auto put_byte = [&](uint32_t i, uint32_t b) {
+        reinterpret_cast<uint8_t*>(s_out)[sub_word(lane, i >> 2) * 4u + (i & 3u)] = (uint8_t)b;
+    };
+    uint32_t i = 0;                                // bytes produced in this sub-chunk
+    if (ok) {
+        uint64_t pos = seg_bit0 + 3u + tok_start;  // bit position relative to seg32
+        const uint64_t end = pos + my_bits;
+        uint32_t prev = 0;
+        while (pos < end) {
+            const uint32_t w = (uint32_t)(pos >> 5), sh = (uint32_t)(pos & 31u);
+            const uint64_t two = (uint64_t)load_w(w) | ((uint64_t)load_w(w + 1) << 32);
+            const uint32_t win = (uint32_t)(two >> sh);            // at least 32 valid bits
+            const uint32_t c9 = __brev(win & 0x1ffu) >> 23;        // first 9 bits, code order
+            uint32_t sym, used;
+            if ((c9 >> 2) <= 23u) { sym = 256u + (c9 >> 2); used = 7u; }
+            else if ((c9 >> 1) <= 0xBFu) { sym = (c9 >> 1) - 0x30u; used = 8u; }
+            else if ((c9 >> 1) <= 0xC7u) { sym = 280u + (c9 >> 1) - 0xC0u; used = 8u; }
+            else { sym = 144u + c9 - 0x190u; used = 9u; }
+            if (sym < 256u) {
+                if (i >= n_l) { ok = false; break; }
+                put_byte(i, sym);
+                prev = sym;
+                ++i;
+            } else {
+                const uint32_t idx = sym - 257u;
+                if (sym == 256u || idx > 28u || i == 0u) { ok = false; break; }
+                uint32_t len;
+                if (idx < 8u) {
+                    len = 3u + idx;
+                } else if (idx == 28u) {
+                    len = 258u;
+                } else {
+                    const uint32_t e = (idx - 4u) >> 2;
+                    len = 3u + ((4u + (idx & 3u)) << e) + ((win >> used) & ((1u << e) - 1u));
+                    used += e;
+                }
+                if (((win >> used) & 31u) != 0u || len > n_l - i) { ok = false; break; }   // distance 1 only
+                used += 5u;
+                for (uint32_t k = 0; k < len; ++k) put_byte(i + k, prev);
+                i += len;
+            }
+            pos += used;
+        }
+        if (pos != end) ok = false;
+    }
+    if (!ok || i != n_l) bad();
+    __syncthreads();
+    // write-out: whole dwords coalesced, the ragged tail of the last chunk byte by byte
+    uint32_t* dst32 = reinterpret_cast<uint32_t*>(dst);
+    for (uint32_t g = lane; g < (m + 3u) / 4u; g += 64u) {
+        const uint32_t v = s_out[sub_word(g / CODEC_SUBW, g % CODEC_SUBW)];
+        if (g * 4u + 4u <= m) {
+            dst32[g] = v;
+        } else {
+            for (uint32_t k = 0; g * 4u + k < m; ++k) dst[g * 4u + k] = (uint8_t)(v >> (8u * k));
+        }
+    }
+}
+
+__global__ void codec_clear_kernel(uint64_t* result) {
+    result[0] = 0;
+    result[1] = 0;
+}
+
+void launch_deflate(shifter_ctx* ctx, const uint8_t* d_in, uint64_t n_bytes, uint32_t n_chunks,
+                    uint8_t* d_work, uint8_t* d_stream, uint64_t stream_cap, uint64_t* d_seg_off,
+                    uint16_t* d_sub_bits) {
+    uint32_t* seg_size = reinterpret_cast<uint32_t*>(d_work);
+    uint8_t* slots = d_work + codec_slots_offset(n_chunks);
+    {
+        ProfileScope ps(ctx, K_DEFLATE_CHUNK);
+        deflate_chunk_kernel<<<n_chunks, 64, 0, ctx->stream>>>(d_in, n_bytes, n_chunks, slots,
+                                                               seg_size, d_sub_bits);
+    }
+    {
+        ProfileScope ps(ctx, K_CODEC_SCAN);
+        codec_scan_kernel<<<1, 1024, 0, ctx->stream>>>(seg_size, n_chunks, d_seg_off, stream_cap,
+                                                       ctx->d_codec);
+    }
+    ProfileScope ps(ctx, K_CODEC_PACK);
+    codec_pack_kernel<<<n_chunks, 64, 0, ctx->stream>>>(slots, seg_size, d_seg_off, ctx->d_codec,
+                                                        d_stream);
+}
+
+void launch_inflate(shifter_ctx* ctx, const uint8_t* d_stream, uint64_t stream_bytes,
+                    const uint64_t* d_seg_off, const uint16_t* d_sub_bits, uint64_t n_bytes,
+                    uint32_t n_chunks, uint8_t* d_out) {
+    codec_clear_kernel<<<1, 1, 0, ctx->stream>>>(ctx->d_codec);
+    ProfileScope ps(ctx, K_INFLATE_CHUNK);
+    inflate_chunk_kernel<<<n_chunks, 64, 0, ctx->stream>>>(d_stream, stream_bytes, d_seg_off,
+                                                           d_sub_bits, n_bytes, n_chunks, d_out,
+                                                           ctx->d_codec);
+}
+
+}  // namespace shifter

@@ -146,7 +146,7 @@ struct PlanHeader {
 enum KernelId {
     K_SEL_INIT = 0, K_HIST0, K_HIST1, K_HIST2, K_SELECT, K_TIE_COUNT, K_TIE_FINAL,
     K_ZERO_FLAGS, K_MASK_SCAN, K_SCAN, K_PROPAGATE, K_PLAN, K_GATHER,
-    K_COPY, K_KERNEL_SCAN, K_FIX_ROUND, K_FOLD_SCALE, K_FOLD_APPLY, K_MASK_SCAN_BATCH, K_EXPAND_LEVELS, K_SPEC_INIT, K_SPEC_SAMPLE, K_SPEC_PREDICT, K_SPEC_PASS, K_SPEC_FINISH, K_SPEC_FINISH2, K_SPEC_FIXUP,
+    K_COPY, K_KERNEL_SCAN, K_FIX_ROUND, K_FOLD_SCALE, K_FOLD_APPLY, K_DEFLATE_CHUNK, K_CODEC_SCAN, K_CODEC_PACK, K_INFLATE_CHUNK, K_MASK_SCAN_BATCH, K_EXPAND_LEVELS, K_SPEC_INIT, K_SPEC_SAMPLE, K_SPEC_PREDICT, K_SPEC_PASS, K_SPEC_FINISH, K_SPEC_FINISH2, K_SPEC_FIXUP,
     K_COUNT
 };
 extern const char* const kKernelNames[K_COUNT];
@@ -248,6 +248,8 @@ struct shifter_ctx {
     shifter::SpecState last_spec{};  // outcome of the last single-pass selection
     int last_path = 0;               // 1: single pass decided; 2: multi-pass select ran
     shifter_threshold last_record{};  // record of the last shifter_prune_fused that waited
+    uint64_t* d_codec = nullptr;      // codec: [0] stream bytes, [1] status bits (device)
+    uint64_t* h_codec = nullptr;      // pinned copy of the two
     // a shifter_prune_fused call whose outcome has not been collected yet
     struct Pending {
         bool active = false;
@@ -310,6 +312,14 @@ void launch_kernel_scan(shifter_ctx* ctx, const shifter_model* m, const float* d
 void launch_fix_begin(shifter_ctx* ctx, const shifter_model* m);
 void launch_fix_round(shifter_ctx* ctx, const shifter_model* m, const uint8_t* d_nz, uint32_t flags);
 void launch_fix_out_flags(shifter_ctx* ctx, const shifter_model* m);
+// Codec workspace: segment sizes (u32 per chunk) first, then one slot per chunk.
+inline uint64_t codec_slots_offset(uint64_t n_chunks) { return (n_chunks * 4u + 255u) & ~(uint64_t)255u; }
+void launch_deflate(shifter_ctx* ctx, const uint8_t* d_in, uint64_t n_bytes, uint32_t n_chunks,
+                    uint8_t* d_work, uint8_t* d_stream, uint64_t stream_cap, uint64_t* d_seg_off,
+                    uint16_t* d_sub_bits);
+void launch_inflate(shifter_ctx* ctx, const uint8_t* d_stream, uint64_t stream_bytes,
+                    const uint64_t* d_seg_off, const uint16_t* d_sub_bits, uint64_t n_bytes,
+                    uint32_t n_chunks, uint8_t* d_out);
 void launch_fold(shifter_ctx* ctx, const shifter_model* m, const float* d_w, const float* d_vecs,
                  float eps, float* d_w_out, float* d_bias_out);
 

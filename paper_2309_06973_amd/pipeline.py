@@ -199,3 +199,54 @@ class Pipeline:
             self.dead_channel_scan()
         self.propagate_groups(flags, sync=False)
         return self.compact(sync)
+
+
+class Package:
+    """One deflated buffer: the DEFLATE stream and the side information for inflating it."""
+    def __init__(self, stream, seg_off, sub_bits, n_bytes: int):
+        self.stream, self.seg_off, self.sub_bits, self.n_bytes = stream, seg_off, sub_bits, n_bytes
+
+    @property
+    def stream_bytes(self) -> int:
+        return self.stream.numel()
+
+
+class Codec:
+    """Buffers for deflating and inflating device tensors (marshalling only)."""
+    def __init__(self, device: int = 0, ctx=None):
+        if not torch.cuda.is_available():
+            raise RuntimeError("no ROCm device visible: the codec has no CPU path")
+        self.dev = torch.device("cuda", device)
+        torch.cuda.set_device(self.dev)
+        self.own = ctx is None
+        self.ctx = ctx or S.shifter_create(device, torch.cuda.current_stream().cuda_stream)
+        self.work = None
+
+    def close(self):
+        if self.own and self.ctx is not None:
+            S.shifter_destroy(self.ctx)
+        self.ctx = None
+
+    def deflate(self, t, stream=None) -> Package:
+        """Deflates the bytes of the contiguous device tensor ``t``.  ``stream``: a uint8
+        buffer to write into (default: one of the largest possible size); the package's
+        stream is the used part of it."""
+        n_bytes = t.numel() * t.element_size()
+        n_chunks, work_bytes, bound = S.shifter_codec_layout(n_bytes)
+        if self.work is None or self.work.numel() < work_bytes:
+            self.work = torch.empty(work_bytes, dtype=torch.uint8, device=self.dev)
+        if stream is None:
+            stream = torch.empty(bound, dtype=torch.uint8, device=self.dev)
+        seg_off = torch.empty(n_chunks + 1, dtype=torch.int64, device=self.dev)
+        sub_bits = torch.empty(n_chunks * (S.SHIFTER_CODEC_CHUNK // S.SHIFTER_CODEC_SUB),
+                               dtype=torch.int16, device=self.dev)
+        total = S.shifter_deflate(self.ctx, t if n_bytes else None, n_bytes, self.work, stream,
+                                  seg_off, sub_bits)
+        return Package(stream[:total], seg_off, sub_bits, n_bytes)
+
+    def inflate(self, p: Package, out=None):
+        if out is None:
+            out = torch.empty(max(p.n_bytes, 16), dtype=torch.uint8, device=self.dev)
+        S.shifter_inflate(self.ctx, p.stream, p.stream_bytes, p.seg_off, p.sub_bits, p.n_bytes,
+                          out)
+        return out

@@ -85,6 +85,12 @@ EXPORTS = {
                             C.POINTER(Threshold)],
     "shifter_fold_bn": [C.c_void_p, C.c_void_p, C.POINTER(FoldDesc), C.c_uint32, C.c_float,
                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64],
+    "shifter_codec_layout": [C.c_uint64, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64),
+                             C.POINTER(C.c_uint64)],
+    "shifter_deflate": [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64, C.c_void_p,
+                        C.c_uint64, C.c_void_p, C.c_void_p, C.POINTER(C.c_uint64)],
+    "shifter_inflate": [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_uint64,
+                        C.c_void_p],
     "shifter_apply_mask": [C.c_void_p] * 8,
     "shifter_dead_channel_scan": [C.c_void_p] * 5,
     "shifter_propagate_groups": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
@@ -331,6 +337,37 @@ def shifter_fold_bn(ctx: Context, model: Model, folds, eps: float, d_w, d_vecs, 
     _check(load_library().shifter_fold_bn(ctx.handle, model.handle, arr, len(folds), eps,
                                           _ptr(d_w), _ptr(d_vecs), _ptr(d_w_out),
                                           _ptr(d_bias_out), cap), ctx.handle)
+
+
+SHIFTER_CODEC_CHUNK = 32768
+SHIFTER_CODEC_SUB = 512
+
+
+def shifter_codec_layout(n_bytes: int):
+    """(chunks, workspace bytes, largest possible stream) for n_bytes of input."""
+    a, b, c = C.c_uint64(), C.c_uint64(), C.c_uint64()
+    _check(load_library().shifter_codec_layout(n_bytes, C.byref(a), C.byref(b), C.byref(c)))
+    return int(a.value), int(b.value), int(c.value)
+
+
+def shifter_deflate(ctx: Context, d_in, n_bytes: int, d_work, d_stream, d_seg_off, d_sub_bits,
+                    sync: bool = True) -> Optional[int]:
+    """Capacities are the byte sizes of d_work and d_stream.  Returns the stream's size when
+    sync (raises ShifterError with code SHIFTER_ERR_CAPACITY if it does not fit)."""
+    total = C.c_uint64()
+    nbytes = lambda t: t.numel() * t.element_size()
+    _check(load_library().shifter_deflate(
+        ctx.handle, _ptr(d_in), n_bytes, _ptr(d_work), nbytes(d_work), _ptr(d_stream),
+        nbytes(d_stream), _ptr(d_seg_off), _ptr(d_sub_bits), C.byref(total) if sync else None),
+        ctx.handle)
+    return int(total.value) if sync else None
+
+
+def shifter_inflate(ctx: Context, d_stream, stream_bytes: int, d_seg_off, d_sub_bits,
+                    n_bytes: int, d_out) -> None:
+    _check(load_library().shifter_inflate(ctx.handle, _ptr(d_stream), stream_bytes,
+                                          _ptr(d_seg_off), _ptr(d_sub_bits), n_bytes,
+                                          _ptr(d_out)), ctx.handle)
 
 
 def shifter_kernel_scan(ctx: Context, model: Model, d_w_sparse, d_kernel_nz) -> None:
