@@ -254,6 +254,39 @@ def measure(name, steps, warmup, lean_run=True):
                 "frac_of_peak": round(fbytes / (fa_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         del dst
 
+    # Phase 3 codec on the sparse arena: deflate (Module 7) and inflate (Module 8); the
+    # stream is a DEFLATE stream, the ratio is raw bytes over stream bytes
+    codec = None
+    if k_var == 1 and lean_run:
+        from paper_2309_06973_amd.pipeline import Codec
+        step()
+        cd = Codec(device=0, ctx=pl.ctx)
+        raw = pl.d_w_sparse[:spec.w_elems]
+        n_raw = 4 * spec.w_elems
+        stream_buf = torch.empty(S.shifter_codec_layout(n_raw)[2], dtype=torch.uint8, device=pl.dev)
+        pkg = cd.deflate(raw, stream=stream_buf)
+        back = cd.inflate(pkg)
+        S.shifter_profile_enable(pl.ctx, True)
+        for _ in range(5):
+            pkg = cd.deflate(raw, stream=stream_buf)
+            cd.inflate(pkg, out=back)
+        cp = S.shifter_profile_read(pl.ctx)
+        S.shifter_profile_enable(pl.ctx, False)
+        avg = lambda kn: cp[kn][1] / cp[kn][0]
+        enc_ms = avg("deflate_chunk") + avg("codec_scan") + avg("codec_pack")
+        dec_ms = avg("inflate_chunk")
+        moved = n_raw + pkg.stream_bytes           # bytes either direction has to move
+        codec = {"raw_bytes": n_raw, "stream_bytes": pkg.stream_bytes,
+                 "ratio": round(n_raw / pkg.stream_bytes, 3),
+                 "round_trip_equal": bool(torch.equal(back[:n_raw].view(torch.int32),
+                                                      raw.view(torch.int32))),
+                 "deflate_us": round(enc_ms * 1e3, 1), "inflate_us": round(dec_ms * 1e3, 1),
+                 "deflate_chunk_us": round(avg("deflate_chunk") * 1e3, 1),
+                 "deflate_gbs": round(moved / (enc_ms * 1e-3) / 1e9, 1),
+                 "inflate_gbs": round(moved / (dec_ms * 1e-3) / 1e9, 1),
+                 "inflate_frac_of_peak": round(moved / (dec_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        del stream_buf, back, pkg, cd
+
     out = {
         "value": round(gbs, 2),
         "unit": "GB/s",
@@ -280,6 +313,8 @@ def measure(name, steps, warmup, lean_run=True):
         out["liveness_fixpoint"] = fixpoint
     if fold is not None:
         out["conv_bn_fold"] = fold
+    if codec is not None:
+        out["codec"] = codec
     pl.close()
     del pl
     torch.cuda.empty_cache()

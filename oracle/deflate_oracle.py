@@ -22,16 +22,21 @@ because the zero weights of sparse models repeat.  Two things are defined here:
     sub-chunk's end) is one literal followed by matches of distance 1 that cover the other
     R = r - 1 bytes: pieces of 258 while more than 260 bytes remain, then one piece if at
     most 258 remain, else the two pieces (remaining - 3, 3); everything else is literals;
-  - a Huffman segment is: block header BFINAL=0, BTYPE=01 (fixed codes), the tokens of all
-    sub-chunks, end-of-block, then an empty stored block (header, padding to a byte,
-    LEN=0, NLEN=0xFFFF) that re-aligns the stream;
-  - a stored segment is one stored block holding the chunk verbatim (m + 5 bytes); it is
-    chosen when it is not longer than the Huffman segment;
-  - BFINAL=1 is set on the last block of the last segment only; an empty input is the
-    single segment 01 00 00 FF FF;
+  - a sub-chunk whose tokens take more than 8 * (its bytes) + STORED_MARGIN bits is
+    *stored*: it becomes a stored block of its own (its bytes verbatim), which is both
+    shorter and copied rather than decoded; the others are *coded*;
+  - a segment is built sub-chunk by sub-chunk (empty ones are skipped): a coded sub-chunk
+    opens a fixed-Huffman block (BFINAL=0, BTYPE=01) unless one is open, and appends its
+    tokens; a stored sub-chunk closes the open block with end-of-block, then is a stored
+    block (BFINAL=0, BTYPE=00, padding to a byte, LEN, NLEN, the bytes); after the last
+    sub-chunk the open block is closed, and an empty stored block (header, padding, LEN=0,
+    NLEN=0xFFFF) re-aligns the stream and carries BFINAL=1 in the last segment;
+  - if that is not shorter than one stored block holding the whole chunk (m + 5 bytes),
+    the segment is that stored block instead (BFINAL=1 in the last segment); an empty
+    input is the single segment 01 00 00 FF FF;
   - side information for parallel decoding (not part of the DEFLATE stream): the byte
-    offset of every segment, and per sub-chunk the number of token bits (0 for stored
-    segments).
+    offset of every segment, and per sub-chunk the number of token bits if it is coded,
+    0xFFFF if it is stored (all 0 when the whole chunk is one stored block).
 
 Both are pinned by tests that do not go through them: ``inflate`` against the zlib
 library on streams of every block type and against streams assembled by hand from the
@@ -44,6 +49,8 @@ from typing import List, Tuple
 
 CHUNK = 32768
 SUB = 512
+STORED_MARGIN = 48
+STORED_MARK = 0xFFFF
 
 # RFC 1951 section 3.2.5: base length and number of extra bits of length codes 257..285
 LENGTH_BASE = [3, 4, 5, 6, 7, 8, 9, 10, 11, 13, 15, 17, 19, 23, 27, 31, 35, 43, 51, 59, 67, 83,
@@ -253,29 +260,62 @@ def tokenize_sub(b: bytes) -> List[Tuple[int, int]]:
     return toks
 
 
+def _emit_tokens(w: _BitWriter, toks) -> None:
+    for kind, val in toks:
+        if kind == 0:
+            _fixed_literal(w, val)
+        else:
+            _fixed_match(w, val)
+
+
+def token_bits(toks) -> int:
+    w = _BitWriter()
+    _emit_tokens(w, toks)
+    return 8 * len(w.out) + w.n
+
+
 def deflate_runs(data: bytes) -> Tuple[bytes, List[int], List[int]]:
-    """Returns (stream, segment byte offsets [n_chunks + 1], token bits per sub-chunk
+    """Returns (stream, segment byte offsets [n_chunks + 1], side information per sub-chunk
     [n_chunks * (CHUNK // SUB)])."""
     n = len(data)
     n_chunks = max(1, (n + CHUNK - 1) // CHUNK)
-    stream, seg_off, sub_bits = bytearray(), [0], []
+    nsub = CHUNK // SUB
+    stream, seg_off, side = bytearray(), [0], []
     for c in range(n_chunks):
         chunk = data[c * CHUNK:(c + 1) * CHUNK]
         m = len(chunk)
         last = 1 if c == n_chunks - 1 else 0
         w = _BitWriter()
-        w.bits(0, 1)
-        w.bits(1, 2)
-        bits_here = []
-        for s in range(CHUNK // SUB):
-            before = 8 * len(w.out) + w.n
-            for kind, val in tokenize_sub(chunk[s * SUB:(s + 1) * SUB]):
-                if kind == 0:
-                    _fixed_literal(w, val)
-                else:
-                    _fixed_match(w, val)
-            bits_here.append(8 * len(w.out) + w.n - before)
-        _fixed_literal(w, 256)
+        in_block = False
+        side_here = []
+        for s in range(nsub):
+            sub = chunk[s * SUB:(s + 1) * SUB]
+            if not sub:
+                side_here.append(0)
+                continue
+            toks = tokenize_sub(sub)
+            t_bits = token_bits(toks)
+            if t_bits > 8 * len(sub) + STORED_MARGIN:
+                if in_block:
+                    _fixed_literal(w, 256)
+                    in_block = False
+                w.bits(0, 1)
+                w.bits(0, 2)
+                w.align()
+                w.bits(len(sub), 16)
+                w.bits(len(sub) ^ 0xFFFF, 16)
+                for b in sub:
+                    w.bits(b, 8)
+                side_here.append(STORED_MARK)
+            else:
+                if not in_block:
+                    w.bits(0, 1)
+                    w.bits(1, 2)
+                    in_block = True
+                _emit_tokens(w, toks)
+                side_here.append(t_bits)
+        if in_block:
+            _fixed_literal(w, 256)
         w.bits(last, 1)
         w.bits(0, 2)
         w.align()
@@ -284,10 +324,10 @@ def deflate_runs(data: bytes) -> Tuple[bytes, List[int], List[int]]:
         if m + 5 <= len(w.out):
             seg = bytes([last]) + m.to_bytes(2, "little") + (m ^ 0xFFFF).to_bytes(2, "little") \
                 + chunk
-            bits_here = [0] * (CHUNK // SUB)
+            side_here = [0] * nsub
         else:
             seg = bytes(w.out)
         stream += seg
         seg_off.append(len(stream))
-        sub_bits += bits_here
-    return bytes(stream), seg_off, sub_bits
+        side += side_here
+    return bytes(stream), seg_off, side

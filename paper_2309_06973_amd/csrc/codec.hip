@@ -161,16 +161,35 @@ __global__ __launch_bounds__(64) void deflate_chunk_kernel(
     const uint32_t m = (uint32_t)min((uint64_t)CODEC_CHUNK, n_bytes - min(n_bytes, base));
     const uint32_t last = c + 1u == n_chunks ? 1u : 0u;
     // stage: whole dwords coalesced, the ragged tail byte by byte, the rest zero
-    const uint32_t* in32 = reinterpret_cast<const uint32_t*>(in + base);
-    for (uint32_t g = lane; g < CODEC_CHUNK / 4; g += 64u) {
-        uint32_t v = 0;
-        if (g * 4u + 4u <= m) {
-            v = in32[g];
-        } else {
-            for (uint32_t k = 0; k < 4u; ++k)
-                if (g * 4u + k < m) v |= (uint32_t)in[base + g * 4u + k] << (8u * k);
+    if (m == CODEC_CHUNK) {
+        // 32 loads of 16 bytes per lane, eight in flight at a time
+        const uint4* in128 = reinterpret_cast<const uint4*>(in + base);
+        for (uint32_t b = 0; b < 4u; ++b) {
+            uint4 v[8];
+#pragma unroll
+            for (uint32_t u = 0; u < 8u; ++u) v[u] = in128[(b * 8u + u) * 64u + lane];
+#pragma unroll
+            for (uint32_t u = 0; u < 8u; ++u) {
+                const uint32_t g = ((b * 8u + u) * 64u + lane) * 4u;
+                const uint32_t l = g / CODEC_SUBW, j = g % CODEC_SUBW;
+                s_in[sub_word(l, j)] = v[u].x;
+                s_in[sub_word(l, j + 1u)] = v[u].y;
+                s_in[sub_word(l, j + 2u)] = v[u].z;
+                s_in[sub_word(l, j + 3u)] = v[u].w;
+            }
         }
-        s_in[sub_word(g / CODEC_SUBW, g % CODEC_SUBW)] = v;
+    } else {
+        const uint32_t* in32 = reinterpret_cast<const uint32_t*>(in + base);
+        for (uint32_t g = lane; g < CODEC_CHUNK / 4; g += 64u) {
+            uint32_t v = 0;
+            if (g * 4u + 4u <= m) {
+                v = in32[g];
+            } else {
+                for (uint32_t k = 0; k < 4u; ++k)
+                    if (g * 4u + k < m) v |= (uint32_t)in[base + g * 4u + k] << (8u * k);
+            }
+            s_in[sub_word(g / CODEC_SUBW, g % CODEC_SUBW)] = v;
+        }
     }
     __syncthreads();
     const uint32_t n_l = min(CODEC_SUB, m - min(m, lane * CODEC_SUB));
@@ -290,15 +309,19 @@ __global__ __launch_bounds__(64) void codec_pack_kernel(const uint8_t* __restric
     if (lane < len - done) dst[done + lane] = src[done + lane];
 }
 
+constexpr uint32_t CODEC_SEG_LDS = 2048;   // dwords of a segment kept in LDS (8 KiB)
+
 // One wave per chunk.  A stored segment is copied; in a Huffman segment every lane decodes
-// the tokens of its sub-chunk (the side information says where they start) into LDS, and
-// the chunk is written out coalesced.  Anything but this library's own token set marks the
-// stream as bad; no access leaves the stream or the output.
+// the tokens of its sub-chunk (the side information says where they start) into a zeroed
+// LDS image of the chunk, which is then written out coalesced.  Segments of up to 8 KiB
+// are read through LDS, longer ones from global memory.  Anything but this library's own
+// token set marks the stream as bad; no access leaves the stream or the output.
 __global__ __launch_bounds__(64) void inflate_chunk_kernel(
     const uint8_t* __restrict__ stream, uint64_t stream_bytes, const uint64_t* __restrict__ seg_off,
     const uint16_t* __restrict__ sub_bits, uint64_t n_bytes, uint32_t n_chunks,
     uint8_t* __restrict__ out, uint64_t* __restrict__ result) {
-    __shared__ uint32_t s_out[CODEC_CHUNK / 4];
+    __shared__ __align__(16) uint32_t s_out[CODEC_CHUNK / 4];
+    __shared__ uint32_t s_seg[CODEC_SEG_LDS];
     const uint32_t c = blockIdx.x, lane = threadIdx.x;
     const uint64_t base = (uint64_t)c * CODEC_CHUNK;
     const uint32_t m = (uint32_t)min((uint64_t)CODEC_CHUNK, n_bytes - min(n_bytes, base));
@@ -310,15 +333,38 @@ __global__ __launch_bounds__(64) void inflate_chunk_kernel(
     }
     const uint8_t* seg = stream + s0;
     const uint32_t seg_len = (uint32_t)(s1 - s0);
+    // the segment is read as dwords aligned to the stream's start; never beyond its end
+    const uint32_t byte0 = (uint32_t)(s0 & 3u);
+    const uint64_t al0 = s0 & ~(uint64_t)3u;
+    const uint32_t* seg32 = reinterpret_cast<const uint32_t*>(stream + al0);
+    const uint32_t max_w = (uint32_t)(((stream_bytes + 3u) / 4u) - (s0 >> 2)) - 1u;   // last readable dword
+    const bool tail_partial = (stream_bytes & 3u) != 0;
+    auto load_w = [&](uint32_t w) -> uint32_t {
+        if (w > max_w) return 0u;
+        if (w == max_w && tail_partial) {          // the stream's last, partial dword: bytes
+            uint32_t v = 0;
+            for (uint32_t k = 0; k < 4u; ++k)
+                if (al0 + (uint64_t)w * 4u + k < stream_bytes) v |= (uint32_t)stream[al0 + (uint64_t)w * 4u + k] << (8u * k);
+            return v;
+        }
+        return seg32[w];
+    };
     const uint32_t btype = (seg[0] >> 1) & 3u;
     uint8_t* dst = out + base;
+    uint32_t* dst32 = reinterpret_cast<uint32_t*>(dst);
     if (btype == 0u) {
         const uint32_t len = seg[1] | ((uint32_t)seg[2] << 8), nlen = seg[3] | ((uint32_t)seg[4] << 8);
         if (len != m || (len ^ nlen) != 0xffffu || seg_len != m + 5u) {
             if (lane == 0) bad();
             return;
         }
-        for (uint32_t k = lane; k < m; k += 64u) dst[k] = seg[5u + k];
+        // output dword k = segment bytes 5 + 4k .. 5 + 4k + 3, assembled from two dwords
+        for (uint32_t k = lane; k < m / 4u; k += 64u) {
+            const uint32_t b = byte0 + 5u + 4u * k, sh = (b & 3u) * 8u;
+            const uint32_t lo = load_w(b >> 2);
+            dst32[k] = sh ? (lo >> sh) | (load_w((b >> 2) + 1u) << (32u - sh)) : lo;
+        }
+        if (lane < (m & 3u)) dst[(m & ~3u) + lane] = seg[5u + (m & ~3u) + lane];
         return;
     }
     if (btype != 1u) {
@@ -330,35 +376,34 @@ __global__ __launch_bounds__(64) void inflate_chunk_kernel(
     uint32_t tok_total;
     const uint32_t tok_start = wave_excl_scan(my_bits, lane, &tok_total);
     bool ok = (uint64_t)3u + tok_total + 10u <= (uint64_t)seg_len * 8u;
-    // the window is read as dwords aligned to the stream's start; never beyond its end
-    const uint64_t seg_bit0 = (s0 & 3u) * 8u;
-    const uint32_t* seg32 = reinterpret_cast<const uint32_t*>(stream + (s0 & ~(uint64_t)3u));
-    const uint32_t max_w = (uint32_t)(((stream_bytes + 3u) / 4u) - (s0 >> 2)) - 1u;   // last readable dword
-    const bool tail_partial = (stream_bytes & 3u) != 0;
-    auto load_w = [&](uint32_t w) -> uint32_t {
-        if (w > max_w) return 0u;
-        if (w == max_w && tail_partial) {          // the stream's last, partial dword: bytes
-            uint32_t v = 0;
-            const uint64_t b0 = (s0 & ~(uint64_t)3u) + (uint64_t)w * 4u;
-            for (uint32_t k = 0; k < 4u; ++k)
-                if (b0 + k < stream_bytes) v |= (uint32_t)stream[b0 + k] << (8u * k);
-            return v;
-        }
-        return seg32[w];
-    };
+    // zeroed image of the chunk; the segment's dwords (two more than it covers, for the
+    // decoder's look-ahead) when they fit
+    for (uint32_t k = lane; k < CODEC_CHUNK / 16; k += 64u)
+        reinterpret_cast<uint4*>(s_out)[k] = make_uint4(0, 0, 0, 0);
+    const uint32_t seg_w = (byte0 + seg_len + 3u) / 4u + 2u;
+    const bool in_lds = seg_w <= CODEC_SEG_LDS;
+    if (in_lds)
+        for (uint32_t k = lane; k < seg_w; k += 64u) s_seg[k] = load_w(k);
+    __syncthreads();
     auto put_byte = [&](uint32_t i, uint32_t b) {
-        reinterpret_cast<uint8_t*>(s_out)[sub_word(lane, i >> 2) * 4u + (i & 3u)] = (uint8_t)b;
+        reinterpret_cast<uint8_t*>(s_out)[lane * CODEC_SUB + i] = (uint8_t)b;
     };
     uint32_t i = 0;                                // bytes produced in this sub-chunk
     if (ok) {
-        uint64_t pos = seg_bit0 + 3u + tok_start;  // bit position relative to seg32
-        const uint64_t end = pos + my_bits;
-        uint32_t prev = 0;
+        uint32_t pos = byte0 * 8u + 3u + tok_start;   // bit position relative to seg32
+        const uint32_t end = pos + my_bits;
+        uint64_t win = 0;                          // the next `avail` bits of the stream
+        uint32_t avail = 0, prev = 0;
         while (pos < end) {
-            const uint32_t w = (uint32_t)(pos >> 5), sh = (uint32_t)(pos & 31u);
-            const uint64_t two = (uint64_t)load_w(w) | ((uint64_t)load_w(w + 1) << 32);
-            const uint32_t win = (uint32_t)(two >> sh);            // at least 32 valid bits
-            const uint32_t c9 = __brev(win & 0x1ffu) >> 23;        // first 9 bits, code order
+            if (avail < 19u) {                     // the longest token: 8 + 5 + 5 bits
+                const uint32_t w = pos >> 5, sh = pos & 31u;
+                const uint32_t lo = in_lds ? s_seg[w] : load_w(w);
+                const uint32_t hi = in_lds ? s_seg[w + 1u] : load_w(w + 1u);
+                win = ((uint64_t)lo | ((uint64_t)hi << 32)) >> sh;
+                avail = 64u - sh;
+            }
+            const uint32_t lowbits = (uint32_t)win;
+            const uint32_t c9 = __brev(lowbits & 0x1ffu) >> 23;    // first 9 bits, code order
             uint32_t sym, used;
             if ((c9 >> 2) <= 23u) { sym = 256u + (c9 >> 2); used = 7u; }
             else if ((c9 >> 1) <= 0xBFu) { sym = (c9 >> 1) - 0x30u; used = 8u; }
@@ -366,7 +411,7 @@ __global__ __launch_bounds__(64) void inflate_chunk_kernel(
             else { sym = 144u + c9 - 0x190u; used = 9u; }
             if (sym < 256u) {
                 if (i >= n_l) { ok = false; break; }
-                put_byte(i, sym);
+                if (sym) put_byte(i, sym);
                 prev = sym;
                 ++i;
             } else {
@@ -379,28 +424,31 @@ __global__ __launch_bounds__(64) void inflate_chunk_kernel(
                     len = 258u;
                 } else {
                     const uint32_t e = (idx - 4u) >> 2;
-                    len = 3u + ((4u + (idx & 3u)) << e) + ((win >> used) & ((1u << e) - 1u));
+                    len = 3u + ((4u + (idx & 3u)) << e) + ((lowbits >> used) & ((1u << e) - 1u));
                     used += e;
                 }
-                if (((win >> used) & 31u) != 0u || len > n_l - i) { ok = false; break; }   // distance 1 only
+                if (((lowbits >> used) & 31u) != 0u || len > n_l - i) { ok = false; break; }   // distance 1 only
                 used += 5u;
-                for (uint32_t k = 0; k < len; ++k) put_byte(i + k, prev);
+                if (prev)                          // zero runs are already there
+                    for (uint32_t k = 0; k < len; ++k) put_byte(i + k, prev);
                 i += len;
             }
             pos += used;
+            win >>= used;
+            avail -= used;
         }
         if (pos != end) ok = false;
     }
     if (!ok || i != n_l) bad();
     __syncthreads();
-    // write-out: whole dwords coalesced, the ragged tail of the last chunk byte by byte
-    uint32_t* dst32 = reinterpret_cast<uint32_t*>(dst);
-    for (uint32_t g = lane; g < (m + 3u) / 4u; g += 64u) {
-        const uint32_t v = s_out[sub_word(g / CODEC_SUBW, g % CODEC_SUBW)];
-        if (g * 4u + 4u <= m) {
-            dst32[g] = v;
+    // write-out: 16 bytes per lane and step, the ragged tail of the last chunk byte by byte
+    for (uint32_t q = lane; q < (m + 15u) / 16u; q += 64u) {
+        const uint4 v = reinterpret_cast<const uint4*>(s_out)[q];
+        if (q * 16u + 16u <= m) {
+            reinterpret_cast<uint4*>(dst)[q] = v;
         } else {
-            for (uint32_t k = 0; g * 4u + k < m; ++k) dst[g * 4u + k] = (uint8_t)(v >> (8u * k));
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+            for (uint32_t k = q * 16u; k < m; ++k) dst[k] = (uint8_t)(w[(k >> 2) & 3u] >> (8u * (k & 3u)));
         }
     }
 }

@@ -137,32 +137,64 @@ def encoder_inputs():
         yield b"ab" + b"\7" * run + b"cd"                # runs across sub-chunks and chunks
         yield b"x" * (S - 130) + bytes(run) + b"\xff" * 700
     yield bytes(range(256)) * 300                         # nothing repeats: stored segments
+    noise = rng.integers(0, 256, 4 * C, dtype=np.uint8).tobytes()
+    # coded and stored sub-chunks in one segment, in every order
+    yield bytes(S) + noise[:S] + bytes(3 * S) + noise[S:3 * S] + bytes(100)
+    yield noise[:S] + bytes(S) + noise[S:2 * S + 7] + bytes(2 * S - 7) + noise[:S // 2]
+    yield noise[:3 * S] + bytes(C - 3 * S) + bytes(C - S) + noise[:S] + noise[:S] + bytes(77)
+    yield sparse_floats(C // 4, 0.9, 8) + noise[:C // 2] + sparse_floats(C // 4 + 31, 0.6, 9)
     yield (b"\0\0\0\0\x12\x34\x56\x3f" * 9000)[:2 * C + 4000]
+
+
+def expected_segment_bytes(side, sub_lens):
+    """Length of a sub-chunk-built segment from its side information: the same walk as
+    the encoder's, on bit counts only."""
+    pos, in_block = 0, False
+    for v, n in zip(side, sub_lens):
+        if n == 0:
+            assert v == 0
+            continue
+        if v == D.STORED_MARK:
+            pos += (7 if in_block else 0) + 3
+            pos = (pos + 7) // 8 * 8 + 32 + 8 * n
+            in_block = False
+        else:
+            pos += (0 if in_block else 3) + v
+            in_block = True
+    pos += (7 if in_block else 0) + 3
+    return (pos + 7) // 8 + 4
 
 
 def test_encoder_output_inflates_with_zlib_and_sizes_add_up():
     nsub = D.CHUNK // D.SUB
+    mixed = 0
     for data in encoder_inputs():
-        stream, seg_off, sub_bits = D.deflate_runs(data)
+        stream, seg_off, side = D.deflate_runs(data)
         assert zinflate(stream) == data
         n_chunks = max(1, -(-len(data) // D.CHUNK))
         assert len(seg_off) == n_chunks + 1 and seg_off[0] == 0 and seg_off[-1] == len(stream)
-        assert len(sub_bits) == n_chunks * nsub
+        assert len(side) == n_chunks * nsub
         for c in range(n_chunks):
             seg = stream[seg_off[c]:seg_off[c + 1]]
             chunk = data[c * D.CHUNK:(c + 1) * D.CHUNK]
             d = zlib.decompressobj(-15)                   # every segment stands alone
             assert d.decompress(seg) == chunk and d.unused_data == b""
             assert d.eof == (c == n_chunks - 1)
-            bits = sub_bits[c * nsub:(c + 1) * nsub]
-            if (seg[0] >> 1) & 3 == 0:                    # stored
-                assert len(seg) == len(chunk) + 5 and not any(bits)
+            here = side[c * nsub:(c + 1) * nsub]
+            sub_lens = [len(chunk[s * D.SUB:(s + 1) * D.SUB]) for s in range(nsub)]
+            if not any(here):                             # the whole chunk in one stored block
+                assert len(seg) == len(chunk) + 5 and (seg[0] >> 1) & 3 == 0
             else:
-                assert len(seg) == (3 + sum(bits) + 7 + 3 + 7) // 8 + 4
-                assert len(seg) < len(chunk) + 5
+                assert len(seg) == expected_segment_bytes(here, sub_lens) < len(chunk) + 5
                 assert seg[-4:] == b"\x00\x00\xff\xff"
+                for v, n, s in zip(here, sub_lens, range(nsub)):
+                    toks = D.tokenize_sub(chunk[s * D.SUB:(s + 1) * D.SUB])
+                    t = D.token_bits(toks)
+                    assert v == (D.STORED_MARK if t > 8 * n + D.STORED_MARGIN else t)
+                mixed += D.STORED_MARK in here and any(0 < v < D.STORED_MARK for v in here)
         if len(data) <= 3000:
             assert D.inflate(stream) == (data, len(stream))
+    assert mixed >= 3                                     # segments with both kinds occur
 
 
 def test_encoder_closed_forms_and_hand_packed_streams():
@@ -171,6 +203,16 @@ def test_encoder_closed_forms_and_hand_packed_streams():
     stream, seg_off, sub_bits = D.deflate_runs(bytes(5))
     assert stream == pack("0 10 00110000 0000010 00000 0000000 1 00") + bytes.fromhex("0000ffff")
     assert sub_bits[:2] == [20, 0] and seg_off == [0, 9]
+    # 512 zeros, then 60 bytes that take 9 bits each: a coded and a stored sub-chunk.
+    # 253 = code 284 (11000100) with extra bits 26, least significant first: 01011
+    tail = bytes([200, 201] * 30)
+    stream, seg_off, side = D.deflate_runs(bytes(512) + tail)
+    assert side[:3] == [39, D.STORED_MARK, 0]
+    assert stream == (pack("0 10 00110000 11000101 00000 11000100 01011 00000 0000000 0 00")
+                      + bytes.fromhex("3c00c3ff") + tail + bytes.fromhex("010000ffff"))
+    assert len(pack("0 10 00110000 11000101 00000 11000100 01011 00000 0000000 0 00")) == 7
+    # alone, the same 60 bytes are one stored block: the sub-chunk form would be longer
+    assert D.deflate_runs(tail)[0] == bytes.fromhex("013c00c3ff") + tail
     # four bytes would take 9 bytes as a Huffman segment, and take 9 stored: stored wins ties
     assert D.deflate_runs(b"abcd")[0] == bytes.fromhex("010400fbff") + b"abcd"
     # a chunk of zeros: per sub-chunk literal (8) + 258 (8 + 5) + 253 (8 + 5 extra + 5) bits
