@@ -6,11 +6,15 @@
 //   - tokens: literals, and for a run of r >= 4 equal bytes inside a sub-chunk one literal
 //     followed by distance-1 matches over the other r - 1 bytes (258 while more than 260
 //     remain, then one piece, or (rest - 3, 3) when 259 or 260 remain);
-//   - a segment is a fixed-Huffman block (header, tokens, end of block) followed by an
-//     empty stored block that pads to a byte, or, when that is not shorter, one stored
-//     block with the chunk verbatim; BFINAL only on the last block of the last segment;
-//   - side information for the decoder: the byte offset of every segment and the token
-//     bits of every sub-chunk (0 for stored segments).
+//   - a sub-chunk whose tokens would take more than 8 * bytes + 48 bits is stored: a stored
+//     block of its own; the others are coded with the fixed Huffman codes;
+//   - a segment walks its sub-chunks: a coded one opens a fixed-Huffman block unless one is
+//     open and appends its tokens, a stored one closes the open block and is a stored
+//     block; at the end the open block is closed and an empty stored block pads to a byte
+//     (and carries BFINAL in the last segment).  If that is not shorter than one stored
+//     block with the whole chunk, the segment is that block;
+//   - side information for the decoder: the byte offset of every segment, and per
+//     sub-chunk its token bits, or 0xFFFF if stored (all 0: whole chunk in one block).
 // Any inflater reads the stream; the decoder here reads this encoder's streams, one wave
 // per chunk, one lane per sub-chunk.
 #include <string>
@@ -24,6 +28,9 @@ constexpr uint32_t CODEC_SUB = SHIFTER_CODEC_SUB;
 constexpr uint32_t CODEC_NSUB = CODEC_CHUNK / CODEC_SUB;      // 64: one wave
 constexpr uint32_t CODEC_SUBW = CODEC_SUB / 4;                // dwords per sub-chunk
 constexpr uint32_t CODEC_SLOT = CODEC_CHUNK + 8;              // bytes of a chunk's slot in the workspace
+constexpr uint32_t CODEC_MARGIN = 48;                         // bits a stored sub-chunk must save
+constexpr uint32_t CODEC_STORED = 0xFFFFu;                    // side information of a stored sub-chunk
+constexpr uint32_t CODEC_MASKW = CODEC_SUB / 32 + 1;          // run-start mask words per lane, padded
 static_assert(CODEC_NSUB == 64, "one lane per sub-chunk");
 
 enum : uint32_t { CODEC_BAD_STREAM = 1u, CODEC_CAPACITY = 2u };
@@ -68,7 +75,8 @@ struct BitCounter {
 };
 
 // Appends bits to the chunk's bit buffer in LDS.  Dwords that a lane fills completely are
-// its own; its first and its last dword may be shared with the neighbours and are OR-ed.
+// its own; its first and its last dword may be shared with the neighbours and are OR-ed
+// (the caller has zeroed those two).  At most 32 bits per call.
 struct BitWriter {
     uint32_t* buf;
     uint64_t acc;
@@ -92,26 +100,21 @@ struct BitWriter {
     }
 };
 
-// Tokens of sub-chunk `l` (n bytes) of the chunk in s_in, sent to `sink`.
+// Tokens of sub-chunk `l` (n bytes), run by run.  s_mask holds one bit per byte of the
+// sub-chunk, set where a run starts (bit n is set too when n < 512).
 template <class Sink>
-__device__ __forceinline__ void encode_sub(const uint32_t* s_in, uint32_t l, uint32_t n, Sink& sink) {
-    auto word = [&](uint32_t j) { return s_in[sub_word(l, j)]; };
-    auto byte = [&](uint32_t i) { return (word(i >> 2) >> ((i & 3u) * 8u)) & 0xffu; };
-    uint32_t i = 0;
-    while (i < n) {
-        const uint32_t b = byte(i);
-        uint32_t j = i + 1;
-        bool same = true;
-        while (j < n && (j & 3u)) {
-            if (byte(j) != b) { same = false; break; }
-            ++j;
-        }
-        if (same) {
-            const uint32_t pat = b * 0x01010101u;
-            while (j + 4u <= n && word(j >> 2) == pat) j += 4u;
-            while (j < n && byte(j) == b) ++j;
-        }
-        const uint32_t r = j - i;
+__device__ __forceinline__ void encode_sub(const uint32_t* s_in, const uint32_t* s_mask, uint32_t l,
+                                           uint32_t n, Sink& sink) {
+    const uint32_t* mk = s_mask + l * CODEC_MASKW;
+    uint32_t p = 0;
+    while (p < n) {
+        // next run start after p
+        uint32_t a = (p + 1u) >> 5;
+        uint32_t mw = a < CODEC_SUB / 32 ? mk[a] & (~0u << ((p + 1u) & 31u)) : 0u;
+        while (mw == 0u && ++a < CODEC_SUB / 32) mw = mk[a];
+        const uint32_t q = mw ? a * 32u + (uint32_t)__ffs((int)mw) - 1u : CODEC_SUB;
+        const uint32_t r = q - p;
+        const uint32_t b = (s_in[sub_word(l, p >> 2)] >> ((p & 3u) * 8u)) & 0xffu;
         uint32_t code;
         uint32_t nb = literal_code(b, &code);
         sink.put(code, nb);
@@ -131,10 +134,11 @@ __device__ __forceinline__ void encode_sub(const uint32_t* s_in, uint32_t l, uin
                 nb = match_code(3u, &code);
                 sink.put(code, nb);
             }
-            i += r;
         } else {
-            i += 1u;
+            if (r >= 2u) sink.put(code, nb);
+            if (r == 3u) sink.put(code, nb);
         }
+        p = q;
     }
 }
 
@@ -148,14 +152,59 @@ __device__ __forceinline__ uint32_t wave_excl_scan(uint32_t v, uint32_t lane, ui
     return x - v;
 }
 
-// One wave per chunk: stages the chunk in LDS, counts the token bits of every sub-chunk,
-// chooses the segment type, builds the segment in LDS (Huffman) and writes it to the
-// chunk's slot of the workspace together with its size.
+// Where every sub-chunk's part of a segment starts, from the side information (s_side:
+// token bits, or CODEC_STORED) and the chunk's size.  start: bit position of the first bit
+// this lane's sub-chunk is responsible for (a coded one: the block header if it opens a
+// block, then its tokens; a stored one: the end-of-block of the block it closes, then its
+// own header); in_block: whether a Huffman block is open at that point.  tail_*: the same
+// for what follows the last sub-chunk.  Returns the segment's size in bytes.
+__device__ __forceinline__ uint32_t place_subs(const uint32_t* s_side, uint32_t m, uint32_t lane,
+                                               bool any_stored, uint32_t* start, bool* in_block,
+                                               uint32_t* tail_start, bool* tail_in_block) {
+    uint32_t pos = 0;
+    bool open = false;
+    if (!any_stored) {
+        // one Huffman block: positions are prefix sums of the token bits
+        uint32_t total;
+        const uint32_t ex = wave_excl_scan(s_side[lane], lane, &total);
+        *start = lane == 0 ? 0u : 3u + ex;
+        *in_block = lane != 0;
+        pos = 3u + total;
+        open = true;
+    } else {
+        *start = 0;
+        *in_block = false;
+        for (uint32_t s = 0; s < CODEC_NSUB; ++s) {
+            const uint32_t n_s = min(CODEC_SUB, m - min(m, s * CODEC_SUB));
+            if (s == lane) { *start = pos; *in_block = open; }
+            if (n_s == 0u) continue;
+            const uint32_t v = s_side[s];
+            if (v == CODEC_STORED) {
+                pos += (open ? 7u : 0u) + 3u;
+                pos = ((pos + 7u) & ~7u) + 32u + 8u * n_s;
+                open = false;
+            } else {
+                pos += (open ? 0u : 3u) + v;
+                open = true;
+            }
+        }
+    }
+    *tail_start = pos;
+    *tail_in_block = open;
+    pos += (open ? 7u : 0u) + 3u;
+    return ((pos + 7u) >> 3) + 4u;
+}
+
+// One wave per chunk: stages the chunk in LDS, marks the run starts, counts the token bits
+// of every sub-chunk, chooses coded or stored per sub-chunk and for the chunk, builds the
+// segment in LDS and writes it to the chunk's slot of the workspace together with its size.
 __global__ __launch_bounds__(64) void deflate_chunk_kernel(
     const uint8_t* __restrict__ in, uint64_t n_bytes, uint32_t n_chunks,
-    uint8_t* __restrict__ slots, uint32_t* __restrict__ seg_size, uint16_t* __restrict__ sub_bits) {
+    uint8_t* __restrict__ slots, uint32_t* __restrict__ seg_size, uint16_t* __restrict__ side) {
     __shared__ uint32_t s_in[CODEC_CHUNK / 4];
     __shared__ uint32_t s_out[CODEC_CHUNK / 4 + 8];
+    __shared__ uint32_t s_mask[CODEC_NSUB * CODEC_MASKW];
+    __shared__ uint32_t s_side[CODEC_NSUB];
     const uint32_t c = blockIdx.x, lane = threadIdx.x;
     const uint64_t base = (uint64_t)c * CODEC_CHUNK;
     const uint32_t m = (uint32_t)min((uint64_t)CODEC_CHUNK, n_bytes - min(n_bytes, base));
@@ -193,17 +242,42 @@ __global__ __launch_bounds__(64) void deflate_chunk_kernel(
     }
     __syncthreads();
     const uint32_t n_l = min(CODEC_SUB, m - min(m, lane * CODEC_SUB));
+    // run starts of this lane's sub-chunk: byte i starts a run iff it differs from byte i - 1
+    {
+        uint32_t carry = 0x100u;                       // no byte equals it: byte 0 starts a run
+#pragma unroll
+        for (uint32_t a = 0; a < CODEC_SUB / 32; ++a) {
+            uint32_t mw = 0;
+#pragma unroll
+            for (uint32_t b = 0; b < 8u; ++b) {
+                const uint32_t w = s_in[sub_word(lane, a * 8u + b)];
+                const uint32_t x = w ^ ((w << 8) | (carry & 0xffu));
+                uint32_t nib = ((x & 0xffu) ? 1u : 0u) | ((x & 0xff00u) ? 2u : 0u) |
+                               ((x & 0xff0000u) ? 4u : 0u) | ((x & 0xff000000u) ? 8u : 0u);
+                if (a == 0 && b == 0) nib |= carry >> 8;
+                carry = w >> 24;
+                mw |= nib << (4u * b);
+            }
+            if (n_l < CODEC_SUB && (n_l >> 5) == a) mw |= 1u << (n_l & 31u);   // the data ends here
+            s_mask[lane * CODEC_MASKW + a] = mw;
+        }
+    }
+    // no barrier needed: every lane reads only the mask words it wrote itself
     BitCounter cnt;
-    encode_sub(s_in, lane, n_l, cnt);
-    uint32_t tok_total;
-    const uint32_t tok_start = wave_excl_scan(cnt.bits, lane, &tok_total);
-    const uint32_t body = 3u + tok_total + 10u;             // header, tokens, end of block, next header
-    const uint32_t pad = (8u - (body & 7u)) & 7u;
-    const uint32_t huff_bytes = (body + pad) / 8u + 4u;
+    encode_sub(s_in, s_mask, lane, n_l, cnt);
+    const bool stored_sub = n_l > 0u && cnt.bits > 8u * n_l + CODEC_MARGIN;
+    const uint32_t my_side = stored_sub ? CODEC_STORED : cnt.bits;
+    s_side[lane] = my_side;
+    __syncthreads();
+    const bool any_stored = __ballot(stored_sub) != 0ull;
+    uint32_t start, tail_start;
+    bool in_block, tail_in_block;
+    const uint32_t seg_bytes = place_subs(s_side, m, lane, any_stored, &start, &in_block,
+                                          &tail_start, &tail_in_block);
     uint32_t* slot32 = reinterpret_cast<uint32_t*>(slots + (uint64_t)c * CODEC_SLOT);
-    if (m + 5u <= huff_bytes) {
-        // stored block: header byte, LEN, NLEN, then the chunk, shifted by five bytes
-        sub_bits[(uint64_t)c * CODEC_NSUB + lane] = 0;
+    if (m + 5u <= seg_bytes) {
+        // one stored block: header byte, LEN, NLEN, then the chunk, shifted by five bytes
+        side[(uint64_t)c * CODEC_NSUB + lane] = 0;
         if (lane == 0) seg_size[c] = m + 5u;
         const uint32_t n_w = (m + 5u + 3u) / 4u;
         auto src = [&](uint32_t g) {               // dword g of the chunk (0 beyond it)
@@ -218,11 +292,11 @@ __global__ __launch_bounds__(64) void deflate_chunk_kernel(
         }
         return;
     }
-    sub_bits[(uint64_t)c * CODEC_NSUB + lane] = (uint16_t)cnt.bits;
-    if (lane == 0) seg_size[c] = huff_bytes;
-    // bit range of this lane: lane 0 also writes the header, lane 63 the tail
-    const uint32_t start = lane == 0 ? 0u : 3u + tok_start;
-    const uint32_t end = lane == 63u ? huff_bytes * 8u : 3u + tok_start + cnt.bits;
+    side[(uint64_t)c * CODEC_NSUB + lane] = (uint16_t)my_side;
+    if (lane == 0) seg_size[c] = seg_bytes;
+    // bit range of this lane: to the next lane's start; lane 63 also writes the tail
+    uint32_t end = __shfl_down(start, 1, 64);
+    if (lane == 63u) end = seg_bytes * 8u;
     if (end > start) {
         s_out[start >> 5] = 0;
         s_out[(end - 1u) >> 5] = 0;
@@ -230,19 +304,32 @@ __global__ __launch_bounds__(64) void deflate_chunk_kernel(
     __syncthreads();
     if (end > start) {
         BitWriter w(s_out, start);
-        if (lane == 0) w.put(2u, 3u);              // BFINAL = 0, BTYPE = 01
-        encode_sub(s_in, lane, n_l, w);
+        if (n_l > 0u && !stored_sub) {
+            if (!in_block) w.put(2u, 3u);          // BFINAL = 0, BTYPE = 01
+            encode_sub(s_in, s_mask, lane, n_l, w);
+        } else if (n_l > 0u) {
+            if (in_block) w.put(0u, 7u);           // end of the open block
+            w.put(0u, 3u);                         // BFINAL = 0, BTYPE = 00
+            const uint32_t at = start + (in_block ? 10u : 3u);
+            w.put(0u, (8u - (at & 7u)) & 7u);
+            w.put(n_l, 16u);
+            w.put(n_l ^ 0xffffu, 16u);
+            for (uint32_t j = 0; j < n_l / 4u; ++j) w.put(s_in[sub_word(lane, j)], 32u);
+            for (uint32_t i = n_l & ~3u; i < n_l; ++i)
+                w.put((s_in[sub_word(lane, i >> 2)] >> ((i & 3u) * 8u)) & 0xffu, 8u);
+        }
         if (lane == 63u) {
-            w.put(0u, 7u);                         // end of block
+            if (tail_in_block) w.put(0u, 7u);      // end of block
             w.put(last, 3u);                       // empty stored block: BFINAL, BTYPE = 00
-            w.put(0u, pad);
+            const uint32_t at = tail_start + (tail_in_block ? 10u : 3u);
+            w.put(0u, (8u - (at & 7u)) & 7u);
             w.put(0x0000u, 16u);
             w.put(0xffffu, 16u);
         }
         w.finish();
     }
     __syncthreads();
-    const uint32_t n_w = (huff_bytes + 3u) / 4u;
+    const uint32_t n_w = (seg_bytes + 3u) / 4u;
     for (uint32_t k = lane; k < n_w; k += 64u) slot32[k] = s_out[k];
 }
 
@@ -309,19 +396,22 @@ __global__ __launch_bounds__(64) void codec_pack_kernel(const uint8_t* __restric
     if (lane < len - done) dst[done + lane] = src[done + lane];
 }
 
-constexpr uint32_t CODEC_SEG_LDS = 2048;   // dwords of a segment kept in LDS (8 KiB)
+constexpr uint32_t CODEC_SEG_LDS = 4096;   // dwords of a segment kept in LDS (16 KiB)
 
-// One wave per chunk.  A stored segment is copied; in a Huffman segment every lane decodes
-// the tokens of its sub-chunk (the side information says where they start) into a zeroed
-// LDS image of the chunk, which is then written out coalesced.  Segments of up to 8 KiB
-// are read through LDS, longer ones from global memory.  Anything but this library's own
-// token set marks the stream as bad; no access leaves the stream or the output.
+// One wave per chunk.  A chunk stored as one block is copied.  Otherwise every lane finds
+// its sub-chunk's place from the side information, then either decodes its tokens or
+// copies its stored bytes into a zeroed LDS image of the chunk, which is written out
+// coalesced.  Segments of up to 16 KiB are read through LDS, longer ones from global
+// memory.  The segment's size must be what the side information implies; anything but
+// this library's own token set marks the stream as bad; no access leaves the stream or
+// the output.
 __global__ __launch_bounds__(64) void inflate_chunk_kernel(
     const uint8_t* __restrict__ stream, uint64_t stream_bytes, const uint64_t* __restrict__ seg_off,
-    const uint16_t* __restrict__ sub_bits, uint64_t n_bytes, uint32_t n_chunks,
+    const uint16_t* __restrict__ side, uint64_t n_bytes, uint32_t n_chunks,
     uint8_t* __restrict__ out, uint64_t* __restrict__ result) {
     __shared__ __align__(16) uint32_t s_out[CODEC_CHUNK / 4];
     __shared__ uint32_t s_seg[CODEC_SEG_LDS];
+    __shared__ uint32_t s_side[CODEC_NSUB];
     const uint32_t c = blockIdx.x, lane = threadIdx.x;
     const uint64_t base = (uint64_t)c * CODEC_CHUNK;
     const uint32_t m = (uint32_t)min((uint64_t)CODEC_CHUNK, n_bytes - min(n_bytes, base));
@@ -349,33 +439,39 @@ __global__ __launch_bounds__(64) void inflate_chunk_kernel(
         }
         return seg32[w];
     };
-    const uint32_t btype = (seg[0] >> 1) & 3u;
     uint8_t* dst = out + base;
     uint32_t* dst32 = reinterpret_cast<uint32_t*>(dst);
-    if (btype == 0u) {
+    const uint32_t n_l = min(CODEC_SUB, m - min(m, lane * CODEC_SUB));
+    const uint32_t my_side = side[(uint64_t)c * CODEC_NSUB + lane];
+    if (__ballot(my_side != 0u) == 0ull) {
+        // the whole chunk in one stored block
         const uint32_t len = seg[1] | ((uint32_t)seg[2] << 8), nlen = seg[3] | ((uint32_t)seg[4] << 8);
-        if (len != m || (len ^ nlen) != 0xffffu || seg_len != m + 5u) {
+        if (((seg[0] >> 1) & 3u) != 0u || len != m || (len ^ nlen) != 0xffffu || seg_len != m + 5u) {
             if (lane == 0) bad();
             return;
         }
         // output dword k = segment bytes 5 + 4k .. 5 + 4k + 3, assembled from two dwords
-        for (uint32_t k = lane; k < m / 4u; k += 64u) {
-            const uint32_t b = byte0 + 5u + 4u * k, sh = (b & 3u) * 8u;
-            const uint32_t lo = load_w(b >> 2);
-            dst32[k] = sh ? (lo >> sh) | (load_w((b >> 2) + 1u) << (32u - sh)) : lo;
+        for (uint32_t k0 = 0; k0 < m / 4u; k0 += 64u * 8u) {
+            uint32_t lo[8], hi[8];
+#pragma unroll
+            for (uint32_t u = 0; u < 8u; ++u) {
+                const uint32_t b = byte0 + 5u + 4u * (k0 + u * 64u + lane);
+                lo[u] = load_w(b >> 2);
+                hi[u] = load_w((b >> 2) + 1u);
+            }
+            const uint32_t sh = ((byte0 + 5u) & 3u) * 8u;
+#pragma unroll
+            for (uint32_t u = 0; u < 8u; ++u) {
+                const uint32_t k = k0 + u * 64u + lane;
+                if (k < m / 4u) dst32[k] = sh ? (lo[u] >> sh) | (hi[u] << (32u - sh)) : lo[u];
+            }
         }
         if (lane < (m & 3u)) dst[(m & ~3u) + lane] = seg[5u + (m & ~3u) + lane];
         return;
     }
-    if (btype != 1u) {
-        if (lane == 0) bad();
-        return;
-    }
-    const uint32_t n_l = min(CODEC_SUB, m - min(m, lane * CODEC_SUB));
-    const uint32_t my_bits = sub_bits[(uint64_t)c * CODEC_NSUB + lane];
-    uint32_t tok_total;
-    const uint32_t tok_start = wave_excl_scan(my_bits, lane, &tok_total);
-    bool ok = (uint64_t)3u + tok_total + 10u <= (uint64_t)seg_len * 8u;
+    const bool stored_sub = my_side == CODEC_STORED;
+    bool ok = stored_sub ? n_l > 0u : (n_l > 0u ? my_side <= 8u * n_l + CODEC_MARGIN : my_side == 0u);
+    s_side[lane] = ok ? my_side : 0u;
     // zeroed image of the chunk; the segment's dwords (two more than it covers, for the
     // decoder's look-ahead) when they fit
     for (uint32_t k = lane; k < CODEC_CHUNK / 16; k += 64u)
@@ -385,20 +481,74 @@ __global__ __launch_bounds__(64) void inflate_chunk_kernel(
     if (in_lds)
         for (uint32_t k = lane; k < seg_w; k += 64u) s_seg[k] = load_w(k);
     __syncthreads();
+    const bool all_ok = __ballot(!ok) == 0ull;
+    const bool any_stored = __ballot(stored_sub) != 0ull;
+    uint32_t start, tail_start;
+    bool in_block, tail_in_block;
+    const uint32_t seg_bytes = place_subs(s_side, m, lane, any_stored, &start, &in_block,
+                                          &tail_start, &tail_in_block);
+    if (!all_ok || seg_bytes != seg_len) {
+        if (lane == 0) bad();
+        return;
+    }
+    auto get_w = [&](uint32_t w) -> uint32_t { return in_lds ? s_seg[w] : load_w(w); };
     auto put_byte = [&](uint32_t i, uint32_t b) {
         reinterpret_cast<uint8_t*>(s_out)[lane * CODEC_SUB + i] = (uint8_t)b;
     };
+    auto peek = [&](uint32_t pos, uint32_t n) -> uint32_t {      // n <= 32 bits at bit position pos
+        const uint32_t w = pos >> 5, sh = pos & 31u;
+        const uint64_t two = (uint64_t)get_w(w) | ((uint64_t)get_w(w + 1u) << 32);
+        return (uint32_t)(two >> sh) & (n >= 32u ? ~0u : (1u << n) - 1u);
+    };
+    const uint32_t bit0 = byte0 * 8u;
+    // the structure around the sub-chunks: block headers, ends of blocks, the closing
+    // empty stored block
+    if (n_l > 0u) {
+        if (!stored_sub && !in_block && peek(bit0 + start, 3u) != 2u) ok = false;
+        if (stored_sub && peek(bit0 + start, in_block ? 10u : 3u) != 0u) ok = false;
+    }
+    if (lane == 63u) {
+        const uint32_t last = c + 1u == n_chunks ? 1u : 0u;
+        uint32_t at = bit0 + tail_start;
+        if (tail_in_block) {
+            if (peek(at, 7u) != 0u) ok = false;
+            at += 7u;
+        }
+        if (peek(at, 3u) != last) ok = false;
+        at = (at + 3u + 7u) & ~7u;
+        if (peek(at, 32u) != 0xffff0000u) ok = false;
+    }
     uint32_t i = 0;                                // bytes produced in this sub-chunk
-    if (ok) {
-        uint32_t pos = byte0 * 8u + 3u + tok_start;   // bit position relative to seg32
-        const uint32_t end = pos + my_bits;
+    if (stored_sub && ok) {
+        // end-of-block of the open block (7 zero bits), header 000, padding, LEN, NLEN, bytes
+        const uint32_t at = byte0 * 8u + start + (in_block ? 10u : 3u);
+        const uint32_t b0 = ((at + 7u) >> 3);      // byte position of LEN, relative to seg32
+        auto byte_at = [&](uint32_t b) { return (get_w(b >> 2) >> ((b & 3u) * 8u)) & 0xffu; };
+        const uint32_t len = byte_at(b0) | (byte_at(b0 + 1u) << 8);
+        const uint32_t nlen = byte_at(b0 + 2u) | (byte_at(b0 + 3u) << 8);
+        if (len != n_l || (len ^ nlen) != 0xffffu) {
+            ok = false;
+        } else {
+            const uint32_t d0 = b0 + 4u, sh = (d0 & 3u) * 8u;
+#pragma unroll 8
+            for (uint32_t k = 0; k < n_l / 4u; ++k) {
+                const uint32_t lo = get_w((d0 >> 2) + k);
+                const uint32_t v = sh ? (lo >> sh) | (get_w((d0 >> 2) + k + 1u) << (32u - sh)) : lo;
+                s_out[lane * CODEC_SUBW + k] = v;
+            }
+            for (uint32_t k = n_l & ~3u; k < n_l; ++k) put_byte(k, byte_at(d0 + k));
+            i = n_l;
+        }
+    } else if (n_l > 0u && ok) {
+        uint32_t pos = byte0 * 8u + start + (in_block ? 0u : 3u);   // bit position relative to seg32
+        const uint32_t end = pos + my_side;
         uint64_t win = 0;                          // the next `avail` bits of the stream
         uint32_t avail = 0, prev = 0;
         while (pos < end) {
             if (avail < 19u) {                     // the longest token: 8 + 5 + 5 bits
                 const uint32_t w = pos >> 5, sh = pos & 31u;
-                const uint32_t lo = in_lds ? s_seg[w] : load_w(w);
-                const uint32_t hi = in_lds ? s_seg[w + 1u] : load_w(w + 1u);
+                const uint32_t lo = get_w(w);
+                const uint32_t hi = get_w(w + 1u);
                 win = ((uint64_t)lo | ((uint64_t)hi << 32)) >> sh;
                 avail = 64u - sh;
             }
