@@ -396,70 +396,93 @@ __global__ __launch_bounds__(64) void codec_pack_kernel(const uint8_t* __restric
     if (lane < len - done) dst[done + lane] = src[done + lane];
 }
 
-constexpr uint32_t CODEC_SEG_LDS = 4096;   // dwords of a segment kept in LDS (16 KiB)
+// Dwords of a segment kept in LDS by the three instances of the decoder: 7.5 KiB, 16 KiB
+// and a whole segment.  The less LDS, the more chunks a CU works on at a time.
+constexpr uint32_t CODEC_SEG_SMALL = 1920;
+constexpr uint32_t CODEC_SEG_MEDIUM = 4096;
+constexpr uint32_t CODEC_SEG_LARGE = (CODEC_SLOT + 3) / 4 + 3;
+constexpr uint32_t CODEC_STAGE = 128;                  // output bytes per lane and stage
+constexpr uint32_t CODEC_STAGE_W = CODEC_STAGE / 4;
 
-// One wave per chunk.  A chunk stored as one block is copied.  Otherwise every lane finds
-// its sub-chunk's place from the side information, then either decodes its tokens or
-// copies its stored bytes into a zeroed LDS image of the chunk, which is written out
-// coalesced.  Segments of up to 16 KiB are read through LDS, longer ones from global
-// memory.  The segment's size must be what the side information implies; anything but
-// this library's own token set marks the stream as bad; no access leaves the stream or
-// the output.
+// n <= 32 bits at bit position pos of the staged segment
+__device__ __forceinline__ uint32_t seg_peek(const uint32_t* s_seg, uint32_t pos, uint32_t n) {
+    const uint32_t w = pos >> 5, sh = pos & 31u;
+    const uint64_t two = (uint64_t)s_seg[w] | ((uint64_t)s_seg[w + 1u] << 32);
+    return (uint32_t)(two >> sh) & (n >= 32u ? ~0u : (1u << n) - 1u);
+}
+__device__ __forceinline__ uint32_t seg_byte(const uint32_t* s_seg, uint32_t b) {
+    return (s_seg[b >> 2] >> ((b & 3u) * 8u)) & 0xffu;
+}
+
+// Dword j (0..31) of lane l's 128-byte piece of the stage image: the dword index is XOR-ed
+// with the lane so that lanes at the same offset use different banks.
+__device__ __forceinline__ uint32_t img_word(uint32_t l, uint32_t j) {
+    return l * CODEC_STAGE_W + (j ^ (l & (CODEC_STAGE_W - 1u)));
+}
+__device__ __forceinline__ uint32_t img_byte(uint32_t l, uint32_t k) {   // byte k (0..127) of lane l's piece
+    return img_word(l, k >> 2) * 4u + (k & 3u);
+}
+
+// One wave per chunk.  A chunk stored as one block is copied.  Otherwise the segment is
+// staged in LDS and every lane finds its sub-chunk's place from the side information; the
+// chunk is then produced in four stages of 128 bytes per sub-chunk: every lane decodes
+// tokens (or copies stored bytes) into a zeroed LDS image of the stage, which is written
+// out as whole 128-byte lines.  Three instances share the chunks by segment size (SEG_DW
+// dwords of LDS for the segment); the smallest also takes the chunks stored as one block.
+// The segment's size must be what the side information implies; anything but this
+// library's own token set marks the stream as bad; no access leaves the stream or the
+// output.
+template <uint32_t SEG_DW, uint32_t SEG_MIN>
 __global__ __launch_bounds__(64) void inflate_chunk_kernel(
     const uint8_t* __restrict__ stream, uint64_t stream_bytes, const uint64_t* __restrict__ seg_off,
     const uint16_t* __restrict__ side, uint64_t n_bytes, uint32_t n_chunks,
     uint8_t* __restrict__ out, uint64_t* __restrict__ result) {
-    __shared__ __align__(16) uint32_t s_out[CODEC_CHUNK / 4];
-    __shared__ uint32_t s_seg[CODEC_SEG_LDS];
+    __shared__ uint32_t s_img[CODEC_NSUB * CODEC_STAGE_W];
+    __shared__ uint32_t s_seg[SEG_DW];
     __shared__ uint32_t s_side[CODEC_NSUB];
+    constexpr bool FIRST = SEG_MIN == 0;
     const uint32_t c = blockIdx.x, lane = threadIdx.x;
     const uint64_t base = (uint64_t)c * CODEC_CHUNK;
     const uint32_t m = (uint32_t)min((uint64_t)CODEC_CHUNK, n_bytes - min(n_bytes, base));
     const uint64_t s0 = seg_off[c], s1 = seg_off[c + 1];
-    auto bad = [&]() { atomicOr(reinterpret_cast<unsigned long long*>(&result[1]), (unsigned long long)CODEC_BAD_STREAM); };
+    const uint32_t my_side = side[(uint64_t)c * CODEC_NSUB + lane];
+    unsigned long long* status = reinterpret_cast<unsigned long long*>(&result[1]);
     if (s1 < s0 || s1 > stream_bytes || s1 - s0 < 5u || s1 - s0 > CODEC_SLOT) {
-        if (lane == 0) bad();
+        if (FIRST && lane == 0) atomicOr(status, (unsigned long long)CODEC_BAD_STREAM);
         return;
     }
-    const uint8_t* seg = stream + s0;
     const uint32_t seg_len = (uint32_t)(s1 - s0);
-    // the segment is read as dwords aligned to the stream's start; never beyond its end
+    // The segment is read as dwords aligned to the stream's start.  The stream's last dword
+    // may be partly beyond stream_bytes: an aligned dword never crosses a page, and what
+    // lies beyond the segment is never interpreted.
     const uint32_t byte0 = (uint32_t)(s0 & 3u);
-    const uint64_t al0 = s0 & ~(uint64_t)3u;
-    const uint32_t* seg32 = reinterpret_cast<const uint32_t*>(stream + al0);
+    const uint32_t* seg32 = reinterpret_cast<const uint32_t*>(stream + (s0 & ~(uint64_t)3u));
     const uint32_t max_w = (uint32_t)(((stream_bytes + 3u) / 4u) - (s0 >> 2)) - 1u;   // last readable dword
-    const bool tail_partial = (stream_bytes & 3u) != 0;
-    auto load_w = [&](uint32_t w) -> uint32_t {
-        if (w > max_w) return 0u;
-        if (w == max_w && tail_partial) {          // the stream's last, partial dword: bytes
-            uint32_t v = 0;
-            for (uint32_t k = 0; k < 4u; ++k)
-                if (al0 + (uint64_t)w * 4u + k < stream_bytes) v |= (uint32_t)stream[al0 + (uint64_t)w * 4u + k] << (8u * k);
-            return v;
-        }
-        return seg32[w];
-    };
+    const uint32_t seg_w = (byte0 + seg_len + 3u) / 4u + 2u;       // two more for the look-ahead
+    const bool whole = __ballot(my_side != 0u) == 0ull;
+    const uint32_t size_class = whole ? 0u : seg_w;
+    if (size_class < SEG_MIN || size_class > SEG_DW) return;       // another instance's chunk
     uint8_t* dst = out + base;
-    uint32_t* dst32 = reinterpret_cast<uint32_t*>(dst);
     const uint32_t n_l = min(CODEC_SUB, m - min(m, lane * CODEC_SUB));
-    const uint32_t my_side = side[(uint64_t)c * CODEC_NSUB + lane];
-    if (__ballot(my_side != 0u) == 0ull) {
+    if (whole) {
         // the whole chunk in one stored block
+        uint32_t* dst32 = reinterpret_cast<uint32_t*>(dst);
+        const uint8_t* seg = stream + s0;
         const uint32_t len = seg[1] | ((uint32_t)seg[2] << 8), nlen = seg[3] | ((uint32_t)seg[4] << 8);
         if (((seg[0] >> 1) & 3u) != 0u || len != m || (len ^ nlen) != 0xffffu || seg_len != m + 5u) {
-            if (lane == 0) bad();
+            if (lane == 0) atomicOr(status, (unsigned long long)CODEC_BAD_STREAM);
             return;
         }
         // output dword k = segment bytes 5 + 4k .. 5 + 4k + 3, assembled from two dwords
+        const uint32_t sh = ((byte0 + 5u) & 3u) * 8u, w0 = (byte0 + 5u) >> 2;
         for (uint32_t k0 = 0; k0 < m / 4u; k0 += 64u * 8u) {
             uint32_t lo[8], hi[8];
 #pragma unroll
             for (uint32_t u = 0; u < 8u; ++u) {
-                const uint32_t b = byte0 + 5u + 4u * (k0 + u * 64u + lane);
-                lo[u] = load_w(b >> 2);
-                hi[u] = load_w((b >> 2) + 1u);
+                const uint32_t w = w0 + k0 + u * 64u + lane;
+                lo[u] = w <= max_w ? seg32[w] : 0u;
+                hi[u] = w + 1u <= max_w ? seg32[w + 1u] : 0u;
             }
-            const uint32_t sh = ((byte0 + 5u) & 3u) * 8u;
 #pragma unroll
             for (uint32_t u = 0; u < 8u; ++u) {
                 const uint32_t k = k0 + u * 64u + lane;
@@ -472,14 +495,7 @@ __global__ __launch_bounds__(64) void inflate_chunk_kernel(
     const bool stored_sub = my_side == CODEC_STORED;
     bool ok = stored_sub ? n_l > 0u : (n_l > 0u ? my_side <= 8u * n_l + CODEC_MARGIN : my_side == 0u);
     s_side[lane] = ok ? my_side : 0u;
-    // zeroed image of the chunk; the segment's dwords (two more than it covers, for the
-    // decoder's look-ahead) when they fit
-    for (uint32_t k = lane; k < CODEC_CHUNK / 16; k += 64u)
-        reinterpret_cast<uint4*>(s_out)[k] = make_uint4(0, 0, 0, 0);
-    const uint32_t seg_w = (byte0 + seg_len + 3u) / 4u + 2u;
-    const bool in_lds = seg_w <= CODEC_SEG_LDS;
-    if (in_lds)
-        for (uint32_t k = lane; k < seg_w; k += 64u) s_seg[k] = load_w(k);
+    for (uint32_t k = lane; k < seg_w; k += 64u) s_seg[k] = k <= max_w ? seg32[k] : 0u;
     __syncthreads();
     const bool all_ok = __ballot(!ok) == 0ull;
     const bool any_stored = __ballot(stored_sub) != 0ull;
@@ -488,119 +504,125 @@ __global__ __launch_bounds__(64) void inflate_chunk_kernel(
     const uint32_t seg_bytes = place_subs(s_side, m, lane, any_stored, &start, &in_block,
                                           &tail_start, &tail_in_block);
     if (!all_ok || seg_bytes != seg_len) {
-        if (lane == 0) bad();
+        if (lane == 0) atomicOr(status, (unsigned long long)CODEC_BAD_STREAM);
         return;
     }
-    auto get_w = [&](uint32_t w) -> uint32_t { return in_lds ? s_seg[w] : load_w(w); };
-    auto put_byte = [&](uint32_t i, uint32_t b) {
-        reinterpret_cast<uint8_t*>(s_out)[lane * CODEC_SUB + i] = (uint8_t)b;
-    };
-    auto peek = [&](uint32_t pos, uint32_t n) -> uint32_t {      // n <= 32 bits at bit position pos
-        const uint32_t w = pos >> 5, sh = pos & 31u;
-        const uint64_t two = (uint64_t)get_w(w) | ((uint64_t)get_w(w + 1u) << 32);
-        return (uint32_t)(two >> sh) & (n >= 32u ? ~0u : (1u << n) - 1u);
-    };
     const uint32_t bit0 = byte0 * 8u;
     // the structure around the sub-chunks: block headers, ends of blocks, the closing
     // empty stored block
     if (n_l > 0u) {
-        if (!stored_sub && !in_block && peek(bit0 + start, 3u) != 2u) ok = false;
-        if (stored_sub && peek(bit0 + start, in_block ? 10u : 3u) != 0u) ok = false;
+        if (!stored_sub && !in_block && seg_peek(s_seg, bit0 + start, 3u) != 2u) ok = false;
+        if (stored_sub && seg_peek(s_seg, bit0 + start, in_block ? 10u : 3u) != 0u) ok = false;
     }
     if (lane == 63u) {
         const uint32_t last = c + 1u == n_chunks ? 1u : 0u;
         uint32_t at = bit0 + tail_start;
         if (tail_in_block) {
-            if (peek(at, 7u) != 0u) ok = false;
+            if (seg_peek(s_seg, at, 7u) != 0u) ok = false;
             at += 7u;
         }
-        if (peek(at, 3u) != last) ok = false;
+        if (seg_peek(s_seg, at, 3u) != last) ok = false;
         at = (at + 3u + 7u) & ~7u;
-        if (peek(at, 32u) != 0xffff0000u) ok = false;
+        if (seg_peek(s_seg, at, 32u) != 0xffff0000u) ok = false;
     }
+    // per-lane decoder state, carried from stage to stage
     uint32_t i = 0;                                // bytes produced in this sub-chunk
+    uint32_t pos = 0, end = 0, d0 = 0;             // token bits [pos, end), or first stored byte
+    uint32_t prev = 0, pending = 0;                // pending: bytes of a run not yet produced
     if (stored_sub && ok) {
         // end-of-block of the open block (7 zero bits), header 000, padding, LEN, NLEN, bytes
-        const uint32_t at = byte0 * 8u + start + (in_block ? 10u : 3u);
+        const uint32_t at = bit0 + start + (in_block ? 10u : 3u);
         const uint32_t b0 = ((at + 7u) >> 3);      // byte position of LEN, relative to seg32
-        auto byte_at = [&](uint32_t b) { return (get_w(b >> 2) >> ((b & 3u) * 8u)) & 0xffu; };
-        const uint32_t len = byte_at(b0) | (byte_at(b0 + 1u) << 8);
-        const uint32_t nlen = byte_at(b0 + 2u) | (byte_at(b0 + 3u) << 8);
-        if (len != n_l || (len ^ nlen) != 0xffffu) {
-            ok = false;
-        } else {
-            const uint32_t d0 = b0 + 4u, sh = (d0 & 3u) * 8u;
+        const uint32_t len = seg_byte(s_seg, b0) | (seg_byte(s_seg, b0 + 1u) << 8);
+        const uint32_t nlen = seg_byte(s_seg, b0 + 2u) | (seg_byte(s_seg, b0 + 3u) << 8);
+        if (len != n_l || (len ^ nlen) != 0xffffu) ok = false;
+        d0 = b0 + 4u;
+    } else if (ok) {
+        pos = bit0 + start + (in_block ? 0u : 3u);
+        end = pos + my_side;
+    }
+    uint8_t* img8 = reinterpret_cast<uint8_t*>(s_img);
+    for (uint32_t st = 0; st < CODEC_SUB / CODEC_STAGE; ++st) {
+        const uint32_t lo_b = st * CODEC_STAGE;
+        const uint32_t hi_b = min(n_l, lo_b + CODEC_STAGE);     // this lane produces [i, hi_b)
+#pragma unroll
+        for (uint32_t j = 0; j < CODEC_STAGE_W; ++j) s_img[lane * CODEC_STAGE_W + j] = 0;
+        if (stored_sub) {
+            if (ok && hi_b > lo_b) {
+                const uint32_t sh = (d0 & 3u) * 8u, w0 = (d0 + lo_b) >> 2;
+                const uint32_t nw = (hi_b - lo_b) / 4u;
 #pragma unroll 8
-            for (uint32_t k = 0; k < n_l / 4u; ++k) {
-                const uint32_t lo = get_w((d0 >> 2) + k);
-                const uint32_t v = sh ? (lo >> sh) | (get_w((d0 >> 2) + k + 1u) << (32u - sh)) : lo;
-                s_out[lane * CODEC_SUBW + k] = v;
-            }
-            for (uint32_t k = n_l & ~3u; k < n_l; ++k) put_byte(k, byte_at(d0 + k));
-            i = n_l;
-        }
-    } else if (n_l > 0u && ok) {
-        uint32_t pos = byte0 * 8u + start + (in_block ? 0u : 3u);   // bit position relative to seg32
-        const uint32_t end = pos + my_side;
-        uint64_t win = 0;                          // the next `avail` bits of the stream
-        uint32_t avail = 0, prev = 0;
-        while (pos < end) {
-            if (avail < 19u) {                     // the longest token: 8 + 5 + 5 bits
-                const uint32_t w = pos >> 5, sh = pos & 31u;
-                const uint32_t lo = get_w(w);
-                const uint32_t hi = get_w(w + 1u);
-                win = ((uint64_t)lo | ((uint64_t)hi << 32)) >> sh;
-                avail = 64u - sh;
-            }
-            const uint32_t lowbits = (uint32_t)win;
-            const uint32_t c9 = __brev(lowbits & 0x1ffu) >> 23;    // first 9 bits, code order
-            uint32_t sym, used;
-            if ((c9 >> 2) <= 23u) { sym = 256u + (c9 >> 2); used = 7u; }
-            else if ((c9 >> 1) <= 0xBFu) { sym = (c9 >> 1) - 0x30u; used = 8u; }
-            else if ((c9 >> 1) <= 0xC7u) { sym = 280u + (c9 >> 1) - 0xC0u; used = 8u; }
-            else { sym = 144u + c9 - 0x190u; used = 9u; }
-            if (sym < 256u) {
-                if (i >= n_l) { ok = false; break; }
-                if (sym) put_byte(i, sym);
-                prev = sym;
-                ++i;
-            } else {
-                const uint32_t idx = sym - 257u;
-                if (sym == 256u || idx > 28u || i == 0u) { ok = false; break; }
-                uint32_t len;
-                if (idx < 8u) {
-                    len = 3u + idx;
-                } else if (idx == 28u) {
-                    len = 258u;
-                } else {
-                    const uint32_t e = (idx - 4u) >> 2;
-                    len = 3u + ((4u + (idx & 3u)) << e) + ((lowbits >> used) & ((1u << e) - 1u));
-                    used += e;
+                for (uint32_t k = 0; k < nw; ++k) {
+                    const uint32_t lo = s_seg[w0 + k];
+                    s_img[img_word(lane, k)] = sh ? (lo >> sh) | (s_seg[w0 + k + 1u] << (32u - sh)) : lo;
                 }
-                if (((lowbits >> used) & 31u) != 0u || len > n_l - i) { ok = false; break; }   // distance 1 only
-                used += 5u;
-                if (prev)                          // zero runs are already there
-                    for (uint32_t k = 0; k < len; ++k) put_byte(i + k, prev);
-                i += len;
+                for (uint32_t k = lo_b + nw * 4u; k < hi_b; ++k) img8[img_byte(lane, k - lo_b)] = (uint8_t)seg_byte(s_seg, d0 + k);
+                i = hi_b;
             }
-            pos += used;
-            win >>= used;
-            avail -= used;
-        }
-        if (pos != end) ok = false;
-    }
-    if (!ok || i != n_l) bad();
-    __syncthreads();
-    // write-out: 16 bytes per lane and step, the ragged tail of the last chunk byte by byte
-    for (uint32_t q = lane; q < (m + 15u) / 16u; q += 64u) {
-        const uint4 v = reinterpret_cast<const uint4*>(s_out)[q];
-        if (q * 16u + 16u <= m) {
-            reinterpret_cast<uint4*>(dst)[q] = v;
         } else {
-            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-            for (uint32_t k = q * 16u; k < m; ++k) dst[k] = (uint8_t)(w[(k >> 2) & 3u] >> (8u * (k & 3u)));
+            // what is left of a run that crossed the stage boundary
+            if (ok && pending && i < hi_b) {
+                const uint32_t k = min(pending, hi_b - i);
+                if (prev)
+                    for (uint32_t t = 0; t < k; ++t) img8[img_byte(lane, i - lo_b + t)] = (uint8_t)prev;
+                i += k;
+                pending -= k;
+            }
+            // one token per turn, decoded without branches: both readings (literal, match)
+            // are computed and one is kept
+            while (ok && i < hi_b) {
+                if (pos >= end) { ok = false; break; }
+                const uint32_t w = pos >> 5, sh = pos & 31u;
+                const uint32_t x = (uint32_t)(((uint64_t)s_seg[w] | ((uint64_t)s_seg[w + 1u] << 32)) >> sh);
+                const uint32_t c9 = __brev(x) >> 23;   // the first 9 bits in code order
+                const bool nine = c9 >= 0x190u;        // 9 bits: literals 144..255
+                const bool lit = nine || c9 - 0x60u < 0x120u;   // 8 bits: literals 0..143
+                const uint32_t sym = nine ? c9 - 0x100u : (c9 >> 1) - 0x30u;
+                const bool seven = (c9 >> 2) <= 23u;   // 7 bits: 256..279; else 8 bits: 280..287
+                const uint32_t idx = seven ? (c9 >> 2) - 1u : 23u + (c9 >> 1) - 0xC0u;   // symbol - 257
+                const uint32_t ncode = seven ? 7u : 8u;
+                const uint32_t e = (idx < 8u || idx >= 28u) ? 0u : (idx - 4u) >> 2;
+                const uint32_t lbase = idx < 8u ? 3u + idx : (idx == 28u ? 258u : 3u + ((4u + (idx & 3u)) << e));
+                const uint32_t len = lbase + ((x >> ncode) & ((1u << e) - 1u));
+                const bool match_ok = idx <= 28u && i != 0u && ((x >> (ncode + e)) & 31u) == 0u &&
+                                      len <= n_l - i;             // distance 1 only
+                if (lit) {
+                    img8[img_byte(lane, i - lo_b)] = (uint8_t)sym;
+                    prev = sym;
+                    i += 1u;
+                    pos += nine ? 9u : 8u;
+                } else {
+                    if (!match_ok) { ok = false; break; }
+                    pos += ncode + e + 5u;
+                    const uint32_t k = min(len, hi_b - i);
+                    if (prev)                      // zero runs are already there
+                        for (uint32_t t = 0; t < k; ++t) img8[img_byte(lane, i - lo_b + t)] = (uint8_t)prev;
+                    i += k;
+                    pending = len - k;
+                }
+            }
         }
+        __syncthreads();
+        // write-out: eight lanes per 128-byte line, eight lines per step
+        for (uint32_t r = 0; r < CODEC_NSUB / 8u; ++r) {
+            const uint32_t p = r * 8u + (lane >> 3), q = lane & 7u;     // piece, 16-byte vector
+            const uint32_t n_p = min(CODEC_SUB, m - min(m, p * CODEC_SUB));
+            const uint32_t valid = n_p - min(n_p, lo_b);                // bytes of this stage's piece
+            if (q * 16u >= valid) continue;
+            uint32_t v[4];
+#pragma unroll
+            for (uint32_t t = 0; t < 4u; ++t) v[t] = s_img[img_word(p, q * 4u + t)];
+            uint8_t* o = dst + p * CODEC_SUB + lo_b + q * 16u;
+            if (q * 16u + 16u <= valid) {
+                *reinterpret_cast<uint4*>(o) = make_uint4(v[0], v[1], v[2], v[3]);
+            } else {
+                for (uint32_t k = 0; q * 16u + k < valid; ++k) o[k] = (uint8_t)(v[k >> 2] >> (8u * (k & 3u)));
+            }
+        }
+        __syncthreads();
     }
+    if (!ok || i != n_l || pending != 0u || (!stored_sub && pos != end))
+        atomicOr(status, (unsigned long long)CODEC_BAD_STREAM);
 }
 
 __global__ void codec_clear_kernel(uint64_t* result) {
@@ -633,9 +655,12 @@ void launch_inflate(shifter_ctx* ctx, const uint8_t* d_stream, uint64_t stream_b
                     uint32_t n_chunks, uint8_t* d_out) {
     codec_clear_kernel<<<1, 1, 0, ctx->stream>>>(ctx->d_codec);
     ProfileScope ps(ctx, K_INFLATE_CHUNK);
-    inflate_chunk_kernel<<<n_chunks, 64, 0, ctx->stream>>>(d_stream, stream_bytes, d_seg_off,
-                                                           d_sub_bits, n_bytes, n_chunks, d_out,
-                                                           ctx->d_codec);
+    inflate_chunk_kernel<CODEC_SEG_SMALL, 0><<<n_chunks, 64, 0, ctx->stream>>>(
+        d_stream, stream_bytes, d_seg_off, d_sub_bits, n_bytes, n_chunks, d_out, ctx->d_codec);
+    inflate_chunk_kernel<CODEC_SEG_MEDIUM, CODEC_SEG_SMALL + 1><<<n_chunks, 64, 0, ctx->stream>>>(
+        d_stream, stream_bytes, d_seg_off, d_sub_bits, n_bytes, n_chunks, d_out, ctx->d_codec);
+    inflate_chunk_kernel<CODEC_SEG_LARGE, CODEC_SEG_MEDIUM + 1><<<n_chunks, 64, 0, ctx->stream>>>(
+        d_stream, stream_bytes, d_seg_off, d_sub_bits, n_bytes, n_chunks, d_out, ctx->d_codec);
 }
 
 }  // namespace shifter
