@@ -44,9 +44,9 @@ __device__ __forceinline__ uint32_t sub_word(uint32_t l, uint32_t j) {
 // Fixed literal code of RFC 1951 section 3.2.6, bit-reversed so that it can be appended
 // from the least significant bit; returns the number of bits.
 __device__ __forceinline__ uint32_t literal_code(uint32_t v, uint32_t* code) {
-    if (v < 144u) { *code = __brev(0x30u + v) >> 24; return 8u; }
-    *code = __brev(0x190u + (v - 144u)) >> 23;
-    return 9u;
+    const bool nine = v >= 144u;                  // 0x30 + v in 8 bits, or 0x190 + (v - 144) in 9
+    *code = __brev(nine ? 0x100u + v : 0x30u + v) >> (nine ? 23u : 24u);
+    return nine ? 9u : 8u;
 }
 
 // A match of `len` (3..258) at distance 1: length code, extra bits, 5-bit distance code 0.
@@ -74,22 +74,20 @@ struct BitCounter {
     __device__ __forceinline__ void put(uint32_t, uint32_t n) { bits += n; }
 };
 
-// Appends bits to the chunk's bit buffer in LDS.  Dwords that a lane fills completely are
-// its own; its first and its last dword may be shared with the neighbours and are OR-ed
-// (the caller has zeroed those two).  At most 32 bits per call.
+// Appends bits to the chunk's bit buffer in LDS, which starts zeroed: every dword is OR-ed
+// in, so neighbouring lanes may share the dwords at the ends of their ranges.  At most 32
+// bits per call.
 struct BitWriter {
     uint32_t* buf;
     uint64_t acc;
     uint32_t cnt, widx;
-    bool first;
     __device__ __forceinline__ BitWriter(uint32_t* b, uint32_t start_bit)
-        : buf(b), acc(0), cnt(start_bit & 31u), widx(start_bit >> 5), first(true) {}
+        : buf(b), acc(0), cnt(start_bit & 31u), widx(start_bit >> 5) {}
     __device__ __forceinline__ void put(uint32_t code, uint32_t n) {
         acc |= (uint64_t)code << cnt;
         cnt += n;
         if (cnt >= 32u) {
-            if (first) { atomicOr(&buf[widx], (uint32_t)acc); first = false; }
-            else buf[widx] = (uint32_t)acc;
+            atomicOr(&buf[widx], (uint32_t)acc);
             ++widx;
             acc >>= 32;
             cnt -= 32u;
@@ -100,44 +98,48 @@ struct BitWriter {
     }
 };
 
-// Tokens of sub-chunk `l` (n bytes), run by run.  s_mask holds one bit per byte of the
-// sub-chunk, set where a run starts (bit n is set too when n < 512).
+// Bits of the distance-1 matches that cover the `rest` >= 3 bytes after a run's first byte.
 template <class Sink>
-__device__ __forceinline__ void encode_sub(const uint32_t* s_in, const uint32_t* s_mask, uint32_t l,
+__device__ __forceinline__ void put_matches(uint32_t rest, Sink& sink) {
+    uint32_t code, nb;
+    while (rest > 260u) {
+        nb = match_code(258u, &code);
+        sink.put(code, nb);
+        rest -= 258u;
+    }
+    if (rest <= 258u) {
+        nb = match_code(rest, &code);
+        sink.put(code, nb);
+    } else {
+        nb = match_code(rest - 3u, &code);
+        sink.put(code, nb);
+        nb = match_code(3u, &code);
+        sink.put(code, nb);
+    }
+}
+
+// First set bit of the mask row `mk` at a position after p (the row ends with a set bit).
+__device__ __forceinline__ uint32_t next_bit(const uint32_t* mk, uint32_t p) {
+    uint32_t a = (p + 1u) >> 5;
+    uint32_t mw = mk[a] & (~0u << ((p + 1u) & 31u));
+    while (mw == 0u && a + 1u < CODEC_MASKW) mw = mk[++a];
+    return mw ? a * 32u + (uint32_t)__ffs((int)mw) - 1u : CODEC_SUB;
+}
+
+// Tokens of sub-chunk `l` (n > 0 bytes).  mk: one bit per byte that is sent as a literal
+// (run starts, and every byte of a run shorter than 4), plus a set bit at position n: the
+// distance from a literal to the next one is 1, or the length of the run it starts.
+template <class Sink>
+__device__ __forceinline__ void encode_sub(const uint32_t* s_in, const uint32_t* mk, uint32_t l,
                                            uint32_t n, Sink& sink) {
-    const uint32_t* mk = s_mask + l * CODEC_MASKW;
     uint32_t p = 0;
     while (p < n) {
-        // next run start after p
-        uint32_t a = (p + 1u) >> 5;
-        uint32_t mw = a < CODEC_SUB / 32 ? mk[a] & (~0u << ((p + 1u) & 31u)) : 0u;
-        while (mw == 0u && ++a < CODEC_SUB / 32) mw = mk[a];
-        const uint32_t q = mw ? a * 32u + (uint32_t)__ffs((int)mw) - 1u : CODEC_SUB;
-        const uint32_t r = q - p;
+        const uint32_t q = next_bit(mk, p);
         const uint32_t b = (s_in[sub_word(l, p >> 2)] >> ((p & 3u) * 8u)) & 0xffu;
         uint32_t code;
-        uint32_t nb = literal_code(b, &code);
+        const uint32_t nb = literal_code(b, &code);
         sink.put(code, nb);
-        if (r >= 4u) {
-            uint32_t rest = r - 1u;
-            while (rest > 260u) {
-                nb = match_code(258u, &code);
-                sink.put(code, nb);
-                rest -= 258u;
-            }
-            if (rest <= 258u) {
-                nb = match_code(rest, &code);
-                sink.put(code, nb);
-            } else {
-                nb = match_code(rest - 3u, &code);
-                sink.put(code, nb);
-                nb = match_code(3u, &code);
-                sink.put(code, nb);
-            }
-        } else {
-            if (r >= 2u) sink.put(code, nb);
-            if (r == 3u) sink.put(code, nb);
-        }
+        if (q - p >= 4u) put_matches(q - p - 1u, sink);
         p = q;
     }
 }
@@ -204,6 +206,7 @@ __global__ __launch_bounds__(64) void deflate_chunk_kernel(
     __shared__ uint32_t s_in[CODEC_CHUNK / 4];
     __shared__ uint32_t s_out[CODEC_CHUNK / 4 + 8];
     __shared__ uint32_t s_mask[CODEC_NSUB * CODEC_MASKW];
+    __shared__ uint32_t s_run[CODEC_NSUB * CODEC_MASKW];
     __shared__ uint32_t s_side[CODEC_NSUB];
     const uint32_t c = blockIdx.x, lane = threadIdx.x;
     const uint64_t base = (uint64_t)c * CODEC_CHUNK;
@@ -242,31 +245,81 @@ __global__ __launch_bounds__(64) void deflate_chunk_kernel(
     }
     __syncthreads();
     const uint32_t n_l = min(CODEC_SUB, m - min(m, lane * CODEC_SUB));
-    // run starts of this lane's sub-chunk: byte i starts a run iff it differs from byte i - 1
+    // Bit masks over the bytes of this lane's sub-chunk, 16 words each: S, byte i starts a run
+    // (it differs from byte i - 1; position n_l counts as a start); G, byte i >= 144 (its
+    // literal code has 9 bits).  From S: the bytes sent as literals (L: starts, and the
+    // second and third byte of runs shorter than 4) and the starts of runs of 4 or more (M).
+    uint32_t* mk = s_mask + lane * CODEC_MASKW;
+    uint32_t tok_bits = 0;
     {
+        constexpr uint32_t NW = CODEC_SUB / 32;
+        uint32_t S[NW + 1], G[NW];
         uint32_t carry = 0x100u;                       // no byte equals it: byte 0 starts a run
 #pragma unroll
-        for (uint32_t a = 0; a < CODEC_SUB / 32; ++a) {
-            uint32_t mw = 0;
+        for (uint32_t a = 0; a < NW; ++a) {
+            uint32_t sw = 0, gw = 0;
 #pragma unroll
             for (uint32_t b = 0; b < 8u; ++b) {
                 const uint32_t w = s_in[sub_word(lane, a * 8u + b)];
                 const uint32_t x = w ^ ((w << 8) | (carry & 0xffu));
-                uint32_t nib = ((x & 0xffu) ? 1u : 0u) | ((x & 0xff00u) ? 2u : 0u) |
-                               ((x & 0xff0000u) ? 4u : 0u) | ((x & 0xff000000u) ? 8u : 0u);
-                if (a == 0 && b == 0) nib |= carry >> 8;
+                // bit 7 of every byte: the byte of x is not 0; the byte of w is >= 0x90
+                uint32_t ne = ((((x & 0x7f7f7f7fu) + 0x7f7f7f7fu) | x) & 0x80808080u) >> 7;
+                uint32_t ge = (w & (((w & 0x70707070u) + 0x70707070u)) & 0x80808080u) >> 7;
+                ne = (ne | (ne >> 7) | (ne >> 14) | (ne >> 21)) & 0xfu;
+                ge = (ge | (ge >> 7) | (ge >> 14) | (ge >> 21)) & 0xfu;
+                if (a == 0 && b == 0) ne |= 1u;
                 carry = w >> 24;
-                mw |= nib << (4u * b);
+                sw |= ne << (4u * b);
+                gw |= ge << (4u * b);
             }
-            if (n_l < CODEC_SUB && (n_l >> 5) == a) mw |= 1u << (n_l & 31u);   // the data ends here
-            s_mask[lane * CODEC_MASKW + a] = mw;
+            S[a] = sw;
+            G[a] = gw;
         }
+        S[NW] = 1u;                                    // position 512 ends the last run
+        if (n_l < CODEC_SUB) {
+#pragma unroll
+            for (uint32_t a = 0; a < NW; ++a)
+                if ((n_l >> 5) == a) S[a] |= 1u << (n_l & 31u);
+        }
+        uint32_t n_lit = 0, n_nine = 0;
+#pragma unroll
+        for (uint32_t a = 0; a < NW; ++a) {
+            const uint32_t s0 = S[a], sp = a ? S[a - 1] : 0u, sn = S[a + 1];
+            const uint32_t z0 = ~s0, zp = a ? ~S[a - 1] : 0u, zn = ~S[a + 1];
+            const uint32_t s_b1 = (s0 << 1) | (sp >> 31), s_b2 = (s0 << 2) | (sp >> 30);   // bit p: S at p - 1, p - 2
+            const uint32_t z_b1 = (z0 << 1) | (zp >> 31);
+            const uint32_t s_f1 = (s0 >> 1) | (sn << 31), s_f2 = (s0 >> 2) | (sn << 30);   // bit p: S at p + 1, p + 2
+            const uint32_t z_f1 = (z0 >> 1) | (zn << 31), z_f2 = (z0 >> 2) | (zn << 30),
+                           z_f3 = (z0 >> 3) | (zn << 29);
+            const uint32_t valid = n_l >= 32u * (a + 1u) ? ~0u : (n_l <= 32u * a ? 0u : (1u << (n_l - 32u * a)) - 1u);
+            const uint32_t lit = (s0 | (z0 & s_b1 & s_f1) | (z0 & s_b1 & z_f1 & s_f2) |
+                                  (z0 & z_b1 & s_b2 & s_f1)) & valid;
+            const uint32_t run4 = s0 & z_f1 & z_f2 & z_f3 & valid;
+            n_lit += (uint32_t)__popc(lit);
+            n_nine += (uint32_t)__popc(lit & G[a]);
+            const uint32_t end_bit = (n_l < CODEC_SUB && (n_l >> 5) == a) ? 1u << (n_l & 31u) : 0u;
+            mk[a] = lit | end_bit;
+            s_run[lane * CODEC_MASKW + a] = run4;
+        }
+        mk[NW] = 1u;
+        tok_bits = 8u * n_lit + n_nine;
     }
-    // no barrier needed: every lane reads only the mask words it wrote itself
-    BitCounter cnt;
-    encode_sub(s_in, s_mask, lane, n_l, cnt);
-    const bool stored_sub = n_l > 0u && cnt.bits > 8u * n_l + CODEC_MARGIN;
-    const uint32_t my_side = stored_sub ? CODEC_STORED : cnt.bits;
+    // the matches of the runs of 4 or more (every lane reads only the rows it wrote itself)
+    {
+        BitCounter cnt;
+        const uint32_t* rk = s_run + lane * CODEC_MASKW;
+        for (uint32_t a = 0; a < CODEC_SUB / 32; ++a) {
+            uint32_t mw = rk[a];
+            while (mw) {
+                const uint32_t p = a * 32u + (uint32_t)__ffs((int)mw) - 1u;
+                mw &= mw - 1u;
+                put_matches(next_bit(mk, p) - p - 1u, cnt);
+            }
+        }
+        tok_bits += cnt.bits;
+    }
+    const bool stored_sub = n_l > 0u && tok_bits > 8u * n_l + CODEC_MARGIN;
+    const uint32_t my_side = stored_sub ? CODEC_STORED : tok_bits;
     s_side[lane] = my_side;
     __syncthreads();
     const bool any_stored = __ballot(stored_sub) != 0ull;
@@ -297,16 +350,14 @@ __global__ __launch_bounds__(64) void deflate_chunk_kernel(
     // bit range of this lane: to the next lane's start; lane 63 also writes the tail
     uint32_t end = __shfl_down(start, 1, 64);
     if (lane == 63u) end = seg_bytes * 8u;
-    if (end > start) {
-        s_out[start >> 5] = 0;
-        s_out[(end - 1u) >> 5] = 0;
-    }
+    const uint32_t n_w = (seg_bytes + 3u) / 4u;
+    for (uint32_t k = lane; k < n_w; k += 64u) s_out[k] = 0;
     __syncthreads();
     if (end > start) {
         BitWriter w(s_out, start);
         if (n_l > 0u && !stored_sub) {
             if (!in_block) w.put(2u, 3u);          // BFINAL = 0, BTYPE = 01
-            encode_sub(s_in, s_mask, lane, n_l, w);
+            encode_sub(s_in, mk, lane, n_l, w);
         } else if (n_l > 0u) {
             if (in_block) w.put(0u, 7u);           // end of the open block
             w.put(0u, 3u);                         // BFINAL = 0, BTYPE = 00
@@ -329,7 +380,6 @@ __global__ __launch_bounds__(64) void deflate_chunk_kernel(
         w.finish();
     }
     __syncthreads();
-    const uint32_t n_w = (seg_bytes + 3u) / 4u;
     for (uint32_t k = lane; k < n_w; k += 64u) slot32[k] = s_out[k];
 }
 
