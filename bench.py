@@ -102,7 +102,7 @@ def cpu_baseline_sample(spec, w, v, sparsity):
                       f"{1.0 / dt:.4f} variants/s"}
 
 
-def measure(name, steps, warmup, lean_run=True):
+def measure(name, steps, warmup, lean_run=True, cpu_leg=True):
     """Times `steps` steps of one workload; returns the fields of its report."""
     import torch
     from paper_2309_06973_amd import shifter as S
@@ -285,6 +285,19 @@ def measure(name, steps, warmup, lean_run=True):
                  "deflate_gbs": round(moved / (enc_ms * 1e-3) / 1e9, 1),
                  "inflate_gbs": round(moved / (dec_ms * 1e-3) / 1e9, 1),
                  "inflate_frac_of_peak": round(moved / (dec_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        # the zlib library on one host core, on the first 64 MiB of the same bytes
+        if cpu_leg:
+            import zlib
+            sample = raw[:(64 << 20) // 4].cpu().numpy().tobytes()
+            t0 = time.perf_counter()
+            z = zlib.compress(sample, 6)
+            t1 = time.perf_counter()
+            zlib.decompress(z)
+            t2 = time.perf_counter()
+            codec["zlib_level6_one_core"] = {
+                "sample_bytes": len(sample), "ratio": round(len(sample) / len(z), 3),
+                "deflate_gbs": round(len(sample) / (t1 - t0) / 1e9, 3),
+                "inflate_gbs": round(len(sample) / (t2 - t1) / 1e9, 3)}
         del stream_buf, back, pkg, cd
 
     out = {
@@ -360,7 +373,7 @@ def main():
             ap.error(f"unknown workload {o!r}")
 
     main_out, (spec, w, v, sparsities) = measure(args.workload, args.steps, args.warmup,
-                                                  not args.no_lean)
+                                                  not args.no_lean, not args.no_cpu_baseline)
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline_sample(spec, w, v, sparsities[-1])

@@ -355,12 +355,19 @@ int shifter_fold_bn(shifter_ctx* ctx, const shifter_model* model,
  *     sub-chunk's end) is one literal and distance-1 matches over the other r - 1 bytes
  *     (258 while more than 260 remain; then one piece, or the pieces (rest - 3, 3) when 259
  *     or 260 remain); every other byte is a literal;
- *   - a segment is either a fixed-Huffman block (BFINAL = 0; the tokens; end of block)
- *     followed by an empty stored block that pads to a byte boundary, or, when that is
- *     not shorter, one stored block holding the chunk; BFINAL = 1 only on the last block
- *     of the last segment; an empty input gives the 5-byte stream 01 00 00 FF FF;
- *   - side information, not part of the stream: seg_off, and per sub-chunk the number of
- *     token bits (0 for stored segments).
+ *   - a sub-chunk whose tokens would take more than 8 * (its bytes) + 48 bits is stored
+ *     (a stored block of its own: shorter, and copied instead of decoded); the others are
+ *     coded with the fixed Huffman codes;
+ *   - a segment walks its sub-chunks: a coded one opens a fixed-Huffman block (BFINAL = 0)
+ *     unless one is open and appends its tokens; a stored one closes the open block with
+ *     end-of-block and is a stored block (BFINAL = 0, padding to a byte, LEN, NLEN, the
+ *     bytes); after the last sub-chunk the open block is closed and an empty stored block
+ *     pads to a byte boundary.  If that is not shorter than one stored block holding the
+ *     whole chunk (its size + 5 bytes), the segment is that block.  BFINAL = 1 only on the
+ *     last block of the last segment; an empty input gives the 5-byte stream
+ *     01 00 00 FF FF;
+ *   - side information, not part of the stream: seg_off, and per sub-chunk a uint16: its
+ *     token bits if coded, 0xFFFF if stored (all 0 when the chunk is one stored block).
  * The output is a deterministic function of the input.
  *
  * shifter_codec_layout   sizes for n_bytes of input: chunks (at least 1), bytes of
@@ -371,16 +378,20 @@ int shifter_fold_bn(shifter_ctx* ctx, const shifter_model* model,
  *   d_work, work_bytes   device, 256-byte aligned scratch of at least the layout's size
  *   d_stream, stream_cap device, 16-byte aligned; capacity in bytes
  *   d_seg_off            device, n_chunks + 1 uint64; the last entry is the stream's size
- *   d_sub_bits           device, n_chunks * (CHUNK / SUB) uint16
+ *   d_sub_bits           device, n_chunks * (CHUNK / SUB) uint16: the per-sub-chunk side
+ *                        information
  *   h_stream_bytes       host or NULL.  Non-NULL: the call waits for the stream and stores
  *                        the stream's size; returns SHIFTER_ERR_CAPACITY (size still
  *                        stored, nothing written to d_stream) when stream_cap is too small
  * shifter_inflate        decodes a stream made by shifter_deflate, given its side
  *                        information, into n_bytes at d_out (device, 16-byte aligned).
  *                        Always waits; SHIFTER_ERR_INVALID_ARG with "bad stream" when the
- *                        stream, the offsets or the bit counts do not fit together (all
- *                        accesses stay inside the buffers; d_out is then unspecified).
- * The first codec call on a context allocates 16 bytes of device and of pinned memory. */
+ *                        stream, the offsets or the side information do not fit together
+ *                        (sizes, block headers and token set are checked; all accesses
+ *                        stay inside the buffers up to the 4-byte granule that holds the
+ *                        stream's last byte; d_out is then unspecified).  DEFLATE carries
+ *                        no checksum: a damaged literal that still parses is not found.
+ * The codec calls need no model and allocate nothing. */
 #define SHIFTER_CODEC_CHUNK 32768u
 #define SHIFTER_CODEC_SUB 512u
 int shifter_codec_layout(uint64_t n_bytes, uint64_t* h_n_chunks, uint64_t* h_work_bytes,

@@ -74,6 +74,14 @@ extern "C" int shifter_create(shifter_ctx** out, int device, void* hip_stream) {
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, device) == hipSuccess && prop.multiProcessorCount > 0)
         c->hist_grid = (uint32_t)prop.multiProcessorCount * 8u;
+    // result words of the codec calls (stream size, status), device and pinned host copy
+    if (hipMalloc(reinterpret_cast<void**>(&c->d_codec), 2 * sizeof(uint64_t)) != hipSuccess ||
+        hipHostMalloc(reinterpret_cast<void**>(&c->h_codec), 2 * sizeof(uint64_t), hipHostMallocDefault) != hipSuccess) {
+        (void)hipGetLastError();
+        if (c->d_codec) (void)hipFree(c->d_codec);
+        delete c;
+        return fail(nullptr, SHIFTER_ERR_OOM, "shifter_create: allocation failed");
+    }
     *out = c;
     return SHIFTER_OK;
 }
@@ -1108,11 +1116,6 @@ extern "C" int shifter_codec_layout(uint64_t n_bytes, uint64_t* h_n_chunks, uint
 static int codec_enter(shifter_ctx* ctx, const char* fn) {
     if (!ctx) return fail(nullptr, SHIFTER_ERR_INVALID_ARG, std::string(fn) + ": ctx is NULL");
     HIP_TRY(ctx, hipSetDevice(ctx->device));
-    if (!ctx->d_codec) {
-        HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->d_codec), 2 * sizeof(uint64_t)));
-        HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->h_codec), 2 * sizeof(uint64_t),
-                                   hipHostMallocDefault));
-    }
     return SHIFTER_OK;
 }
 

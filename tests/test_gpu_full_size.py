@@ -3,15 +3,18 @@ configurations the benchmark times.  The oracle's full sort would take minutes h
 the threshold is checked through the counting definition of the P-th smallest
 (|w|, index) pair, which holds at any size; everything downstream of the threshold (mask,
 sparse weights, alive flags, plan, rebuilt tensors) is the oracle's, element by element."""
+import zlib
+
 import numpy as np
 import pytest
 import torch
 
+from oracle import deflate_oracle as DO
 from oracle import fold_oracle as FO
 from oracle import shifter_oracle as O
 from paper_2309_06973_amd import shifter as S
 from paper_2309_06973_amd import synth
-from paper_2309_06973_amd.pipeline import Pipeline
+from paper_2309_06973_amd.pipeline import Codec, Pipeline
 from test_gpu_fold import bias_bound
 
 pytestmark = pytest.mark.gpu
@@ -116,6 +119,37 @@ def test_c5_single_sweep_fused(c5):
         gb = got_b.cpu().numpy()[:fspec.v_elems]
         assert np.all(np.abs(gb - ref_b) <= 4 * u * bias_bound(v, spec, folds, fspec.v_elems, eps)
                       + u * np.abs(ref_b) + 2.0 ** -149)
+        # Phase 3 codec on the sparse arena (1.29 GB): the stream through zlib (an independent
+        # inflater) and through the library's inflate gives the arena back; sampled chunks
+        # equal the oracle encoder's segments (a segment depends on its chunk alone, apart
+        # from the BFINAL bit of the last one)
+        del ref_w, gw
+        raw = ws.tobytes()
+        cd = Codec(ctx=pl.ctx)
+        d_raw = torch.from_numpy(ws).to(pl.dev)
+        pkg = cd.deflate(d_raw)
+        stream = pkg.stream.cpu().numpy().tobytes()
+        seg_off = pkg.seg_off.cpu().numpy().tolist()
+        assert seg_off[-1] == len(stream) and 5 < len(raw) / len(stream) < 40
+        dz = zlib.decompressobj(-15)
+        back, at = bytearray(), 0
+        while at < len(stream):                                  # bounded pieces: memory
+            back += dz.decompress(stream[at:at + (64 << 20)])
+            at += 64 << 20
+        assert dz.eof and dz.unused_data == b"" and bytes(back) == raw
+        del back
+        out = cd.inflate(pkg)
+        assert torch.equal(out[:len(raw)].view(torch.int32), d_raw.view(torch.int32))
+        n_chunks = len(seg_off) - 1
+        rng = np.random.default_rng(3)
+        for c in [0, 1, n_chunks - 2, n_chunks - 1] + rng.integers(0, n_chunks - 1, 12).tolist():
+            ref_stream, ref_off, ref_side = DO.deflate_runs(raw[c * DO.CHUNK:(c + 2) * DO.CHUNK])
+            side = pkg.sub_bits[c * 64:(c + 1) * 64].cpu().numpy().view(np.uint16).tolist()
+            assert side == ref_side[:64]
+            if c < n_chunks - 1:
+                assert stream[seg_off[c]:seg_off[c + 1]] == ref_stream[:ref_off[1]]
+            else:
+                assert stream[seg_off[c]:] == ref_stream
     finally:
         pl.close()
 
