@@ -464,14 +464,52 @@ __device__ __forceinline__ uint32_t seg_byte(const uint32_t* s_seg, uint32_t b) 
     return (s_seg[b >> 2] >> ((b & 3u) * 8u)) & 0xffu;
 }
 
-// Dword j (0..31) of lane l's 128-byte piece of the stage image: the dword index is XOR-ed
-// with the lane so that lanes at the same offset use different banks.
+// Dword j (0..31) of lane l's 128-byte piece of the stage image: the index of the 16-byte
+// vector is XOR-ed with the lane, so that lanes at the same offset spread over the banks
+// and a vector stays whole for the write-out.
 __device__ __forceinline__ uint32_t img_word(uint32_t l, uint32_t j) {
-    return l * CODEC_STAGE_W + (j ^ (l & (CODEC_STAGE_W - 1u)));
+    return l * CODEC_STAGE_W + ((((j >> 2) ^ l) & 7u) << 2) + (j & 3u);
 }
 __device__ __forceinline__ uint32_t img_byte(uint32_t l, uint32_t k) {   // byte k (0..127) of lane l's piece
     return img_word(l, k >> 2) * 4u + (k & 3u);
 }
+
+// What the next 9 bits of a fixed-Huffman block mean (RFC 1951 section 3.2.6), indexed by
+// those bits as they come out of the stream (first bit = bit 0):
+//   bits 0-4 bits used (a match: code + extra + 5 distance bits); bit 5 match; bit 6 not a
+//   token (end of block, 286, 287); bits 8-16 the literal, or the match's base length;
+//   bits 20-23 length of the code; bits 24-26 number of extra bits.
+struct TokenTable {
+    uint32_t v[512];
+};
+constexpr TokenTable make_token_table() {
+    TokenTable t{};
+    for (uint32_t r = 0; r < 512u; ++r) {
+        uint32_t c9 = 0;                               // the 9 bits in code order
+        for (uint32_t k = 0; k < 9u; ++k) c9 |= ((r >> k) & 1u) << (8u - k);
+        uint32_t e = 0;
+        if (c9 >= 0x190u) {                            // 9 bits: literals 144..255
+            e = 9u | ((c9 - 0x100u) << 8);
+        } else if ((c9 >> 1) >= 0x30u && (c9 >> 1) <= 0xBFu) {   // 8 bits: literals 0..143
+            e = 8u | (((c9 >> 1) - 0x30u) << 8);
+        } else {
+            const bool seven = (c9 >> 2) <= 23u;       // 7 bits: 256..279; 8 bits: 280..287
+            const uint32_t sym = seven ? 256u + (c9 >> 2) : 280u + (c9 >> 1) - 0xC0u;
+            const uint32_t ncode = seven ? 7u : 8u;
+            if (sym == 256u || sym > 285u) {
+                e = ncode | 32u | 64u | (ncode << 20);
+            } else {
+                const uint32_t idx = sym - 257u;
+                const uint32_t ex = (idx < 8u || idx == 28u) ? 0u : (idx - 4u) >> 2;
+                const uint32_t lbase = idx < 8u ? 3u + idx : (idx == 28u ? 258u : 3u + ((4u + (idx & 3u)) << ex));
+                e = (ncode + ex + 5u) | 32u | (lbase << 8) | (ncode << 20) | (ex << 24);
+            }
+        }
+        t.v[r] = e;
+    }
+    return t;
+}
+static __device__ const TokenTable kTokenTable = make_token_table();
 
 // One wave per chunk.  A chunk stored as one block is copied.  Otherwise the segment is
 // staged in LDS and every lane finds its sub-chunk's place from the side information; the
@@ -487,8 +525,9 @@ __global__ __launch_bounds__(64) void inflate_chunk_kernel(
     const uint8_t* __restrict__ stream, uint64_t stream_bytes, const uint64_t* __restrict__ seg_off,
     const uint16_t* __restrict__ side, uint64_t n_bytes, uint32_t n_chunks,
     uint8_t* __restrict__ out, uint64_t* __restrict__ result) {
-    __shared__ uint32_t s_img[CODEC_NSUB * CODEC_STAGE_W];
+    __shared__ __align__(16) uint32_t s_img[CODEC_NSUB * CODEC_STAGE_W];
     __shared__ uint32_t s_seg[SEG_DW];
+    __shared__ uint32_t s_tab[512];
     __shared__ uint32_t s_side[CODEC_NSUB];
     constexpr bool FIRST = SEG_MIN == 0;
     const uint32_t c = blockIdx.x, lane = threadIdx.x;
@@ -546,6 +585,8 @@ __global__ __launch_bounds__(64) void inflate_chunk_kernel(
     bool ok = stored_sub ? n_l > 0u : (n_l > 0u ? my_side <= 8u * n_l + CODEC_MARGIN : my_side == 0u);
     s_side[lane] = ok ? my_side : 0u;
     for (uint32_t k = lane; k < seg_w; k += 64u) s_seg[k] = k <= max_w ? seg32[k] : 0u;
+#pragma unroll
+    for (uint32_t k = 0; k < 8u; ++k) s_tab[k * 64u + lane] = kTokenTable.v[k * 64u + lane];
     __syncthreads();
     const bool all_ok = __ballot(!ok) == 0ull;
     const bool any_stored = __ballot(stored_sub) != 0ull;
@@ -596,7 +637,8 @@ __global__ __launch_bounds__(64) void inflate_chunk_kernel(
         const uint32_t lo_b = st * CODEC_STAGE;
         const uint32_t hi_b = min(n_l, lo_b + CODEC_STAGE);     // this lane produces [i, hi_b)
 #pragma unroll
-        for (uint32_t j = 0; j < CODEC_STAGE_W; ++j) s_img[lane * CODEC_STAGE_W + j] = 0;
+        for (uint32_t j = 0; j < CODEC_STAGE_W / 4; ++j)
+            reinterpret_cast<uint4*>(s_img)[lane * (CODEC_STAGE_W / 4) + j] = make_uint4(0, 0, 0, 0);
         if (stored_sub) {
             if (ok && hi_b > lo_b) {
                 const uint32_t sh = (d0 & 3u) * 8u, w0 = (d0 + lo_b) >> 2;
@@ -618,35 +660,29 @@ __global__ __launch_bounds__(64) void inflate_chunk_kernel(
                 i += k;
                 pending -= k;
             }
-            // one token per turn, decoded without branches: both readings (literal, match)
-            // are computed and one is kept
+            // one token per turn: the next 9 bits index the token table
             while (ok && i < hi_b) {
                 if (pos >= end) { ok = false; break; }
                 const uint32_t w = pos >> 5, sh = pos & 31u;
                 const uint32_t x = (uint32_t)(((uint64_t)s_seg[w] | ((uint64_t)s_seg[w + 1u] << 32)) >> sh);
-                const uint32_t c9 = __brev(x) >> 23;   // the first 9 bits in code order
-                const bool nine = c9 >= 0x190u;        // 9 bits: literals 144..255
-                const bool lit = nine || c9 - 0x60u < 0x120u;   // 8 bits: literals 0..143
-                const uint32_t sym = nine ? c9 - 0x100u : (c9 >> 1) - 0x30u;
-                const bool seven = (c9 >> 2) <= 23u;   // 7 bits: 256..279; else 8 bits: 280..287
-                const uint32_t idx = seven ? (c9 >> 2) - 1u : 23u + (c9 >> 1) - 0xC0u;   // symbol - 257
-                const uint32_t ncode = seven ? 7u : 8u;
-                const uint32_t e = (idx < 8u || idx >= 28u) ? 0u : (idx - 4u) >> 2;
-                const uint32_t lbase = idx < 8u ? 3u + idx : (idx == 28u ? 258u : 3u + ((4u + (idx & 3u)) << e));
-                const uint32_t len = lbase + ((x >> ncode) & ((1u << e) - 1u));
-                const bool match_ok = idx <= 28u && i != 0u && ((x >> (ncode + e)) & 31u) == 0u &&
-                                      len <= n_l - i;             // distance 1 only
-                if (lit) {
-                    img8[img_byte(lane, i - lo_b)] = (uint8_t)sym;
-                    prev = sym;
+                const uint32_t t = s_tab[x & 511u];
+                const uint32_t val = (t >> 8) & 0x1ffu;
+                pos += t & 31u;
+                if (!(t & 32u)) {
+                    img8[img_byte(lane, i - lo_b)] = (uint8_t)val;
+                    prev = val;
                     i += 1u;
-                    pos += nine ? 9u : 8u;
                 } else {
-                    if (!match_ok) { ok = false; break; }
-                    pos += ncode + e + 5u;
+                    const uint32_t ncode = (t >> 20) & 15u, e = (t >> 24) & 7u;
+                    const uint32_t len = val + ((x >> ncode) & ((1u << e) - 1u));
+                    // a token, after a first byte, at distance 1, inside the sub-chunk
+                    if ((t & 64u) || i == 0u || ((x >> (ncode + e)) & 31u) != 0u || len > n_l - i) {
+                        ok = false;
+                        break;
+                    }
                     const uint32_t k = min(len, hi_b - i);
                     if (prev)                      // zero runs are already there
-                        for (uint32_t t = 0; t < k; ++t) img8[img_byte(lane, i - lo_b + t)] = (uint8_t)prev;
+                        for (uint32_t u = 0; u < k; ++u) img8[img_byte(lane, i - lo_b + u)] = (uint8_t)prev;
                     i += k;
                     pending = len - k;
                 }
@@ -654,19 +690,27 @@ __global__ __launch_bounds__(64) void inflate_chunk_kernel(
         }
         __syncthreads();
         // write-out: eight lanes per 128-byte line, eight lines per step
-        for (uint32_t r = 0; r < CODEC_NSUB / 8u; ++r) {
-            const uint32_t p = r * 8u + (lane >> 3), q = lane & 7u;     // piece, 16-byte vector
-            const uint32_t n_p = min(CODEC_SUB, m - min(m, p * CODEC_SUB));
-            const uint32_t valid = n_p - min(n_p, lo_b);                // bytes of this stage's piece
-            if (q * 16u >= valid) continue;
-            uint32_t v[4];
+        if (m == CODEC_CHUNK) {
 #pragma unroll
-            for (uint32_t t = 0; t < 4u; ++t) v[t] = s_img[img_word(p, q * 4u + t)];
-            uint8_t* o = dst + p * CODEC_SUB + lo_b + q * 16u;
-            if (q * 16u + 16u <= valid) {
-                *reinterpret_cast<uint4*>(o) = make_uint4(v[0], v[1], v[2], v[3]);
-            } else {
-                for (uint32_t k = 0; q * 16u + k < valid; ++k) o[k] = (uint8_t)(v[k >> 2] >> (8u * (k & 3u)));
+            for (uint32_t r = 0; r < CODEC_NSUB / 8u; ++r) {
+                const uint32_t p = r * 8u + (lane >> 3), q = lane & 7u;     // piece, 16-byte vector
+                const uint4 v = reinterpret_cast<const uint4*>(s_img)[p * 8u + ((q ^ p) & 7u)];
+                *reinterpret_cast<uint4*>(dst + p * CODEC_SUB + lo_b + q * 16u) = v;
+            }
+        } else {
+            for (uint32_t r = 0; r < CODEC_NSUB / 8u; ++r) {
+                const uint32_t p = r * 8u + (lane >> 3), q = lane & 7u;
+                const uint32_t n_p = min(CODEC_SUB, m - min(m, p * CODEC_SUB));
+                const uint32_t valid = n_p - min(n_p, lo_b);            // bytes of this stage's piece
+                if (q * 16u >= valid) continue;
+                const uint4 v4 = reinterpret_cast<const uint4*>(s_img)[p * 8u + ((q ^ p) & 7u)];
+                const uint32_t v[4] = {v4.x, v4.y, v4.z, v4.w};
+                uint8_t* o = dst + p * CODEC_SUB + lo_b + q * 16u;
+                if (q * 16u + 16u <= valid) {
+                    *reinterpret_cast<uint4*>(o) = v4;
+                } else {
+                    for (uint32_t k = 0; q * 16u + k < valid; ++k) o[k] = (uint8_t)(v[k >> 2] >> (8u * (k & 3u)));
+                }
             }
         }
         __syncthreads();
