@@ -391,7 +391,8 @@ int shifter_fold_bn(shifter_ctx* ctx, const shifter_model* model,
  *                        stay inside the buffers up to the 4-byte granule that holds the
  *                        stream's last byte; d_out is then unspecified).  DEFLATE carries
  *                        no checksum: a damaged literal that still parses is not found.
- * The codec calls need no model and allocate nothing. */
+ * The codec calls need no model.  shifter_inflate keeps 8 bytes per chunk of device memory
+ * in the context, allocated when a stream with more chunks than before comes. */
 #define SHIFTER_CODEC_CHUNK 32768u
 #define SHIFTER_CODEC_SUB 512u
 int shifter_codec_layout(uint64_t n_bytes, uint64_t* h_n_chunks, uint64_t* h_work_bytes,

@@ -75,10 +75,12 @@ extern "C" int shifter_create(shifter_ctx** out, int device, void* hip_stream) {
     if (hipGetDeviceProperties(&prop, device) == hipSuccess && prop.multiProcessorCount > 0)
         c->hist_grid = (uint32_t)prop.multiProcessorCount * 8u;
     // result words of the codec calls (stream size, status), device and pinned host copy
-    if (hipMalloc(reinterpret_cast<void**>(&c->d_codec), 2 * sizeof(uint64_t)) != hipSuccess ||
-        hipHostMalloc(reinterpret_cast<void**>(&c->h_codec), 2 * sizeof(uint64_t), hipHostMallocDefault) != hipSuccess) {
+    if (hipMalloc(reinterpret_cast<void**>(&c->d_codec), 4 * sizeof(uint64_t)) != hipSuccess ||
+        hipHostMalloc(reinterpret_cast<void**>(&c->h_codec), 4 * sizeof(uint64_t), hipHostMallocDefault) != hipSuccess ||
+        hipEventCreateWithFlags(&c->codec_ev, hipEventDisableTiming) != hipSuccess) {
         (void)hipGetLastError();
         if (c->d_codec) (void)hipFree(c->d_codec);
+        if (c->h_codec) (void)hipHostFree(c->h_codec);
         delete c;
         return fail(nullptr, SHIFTER_ERR_OOM, "shifter_create: allocation failed");
     }
@@ -110,6 +112,8 @@ extern "C" int shifter_destroy(shifter_ctx* ctx) {
     for (auto e : ctx->pool) (void)hipEventDestroy(e);
     if (ctx->d_codec) (void)hipFree(ctx->d_codec);
     if (ctx->h_codec) (void)hipHostFree(ctx->h_codec);
+    if (ctx->d_codec_list) (void)hipFree(ctx->d_codec_list);
+    if (ctx->codec_ev) (void)hipEventDestroy(ctx->codec_ev);
     delete ctx;
     return SHIFTER_OK;
 }
@@ -1174,8 +1178,8 @@ extern "C" int shifter_inflate(shifter_ctx* ctx, const uint8_t* d_stream, uint64
         return fail(ctx, SHIFTER_ERR_INVALID_ARG, "inflate: output too large (2^31 chunks or more)");
     if (stream_bytes < 5u * n_chunks)
         return fail(ctx, SHIFTER_ERR_INVALID_ARG, "inflate: bad stream (shorter than its segments' headers)");
-    launch_inflate(ctx, d_stream, stream_bytes, d_seg_off, d_sub_bits, n_bytes, (uint32_t)n_chunks,
-                   static_cast<uint8_t*>(d_out));
+    HIP_TRY(ctx, (hipError_t)launch_inflate(ctx, d_stream, stream_bytes, d_seg_off, d_sub_bits, n_bytes,
+                                            (uint32_t)n_chunks, static_cast<uint8_t*>(d_out)));
     if ((rc = after_launch(ctx, "inflate"))) return rc;
     uint64_t total, status;
     if ((rc = codec_result(ctx, &total, &status))) return rc;

@@ -524,13 +524,13 @@ template <uint32_t SEG_DW, uint32_t SEG_MIN>
 __global__ __launch_bounds__(64) void inflate_chunk_kernel(
     const uint8_t* __restrict__ stream, uint64_t stream_bytes, const uint64_t* __restrict__ seg_off,
     const uint16_t* __restrict__ side, uint64_t n_bytes, uint32_t n_chunks,
-    uint8_t* __restrict__ out, uint64_t* __restrict__ result) {
+    uint8_t* __restrict__ out, uint64_t* __restrict__ result, const uint32_t* __restrict__ list) {
     __shared__ __align__(16) uint32_t s_img[CODEC_NSUB * CODEC_STAGE_W];
     __shared__ uint32_t s_seg[SEG_DW];
     __shared__ uint32_t s_tab[512];
     __shared__ uint32_t s_side[CODEC_NSUB];
     constexpr bool FIRST = SEG_MIN == 0;
-    const uint32_t c = blockIdx.x, lane = threadIdx.x;
+    const uint32_t c = list ? list[blockIdx.x] : blockIdx.x, lane = threadIdx.x;   // list: the chunks of this instance
     const uint64_t base = (uint64_t)c * CODEC_CHUNK;
     const uint32_t m = (uint32_t)min((uint64_t)CODEC_CHUNK, n_bytes - min(n_bytes, base));
     const uint64_t s0 = seg_off[c], s1 = seg_off[c + 1];
@@ -549,6 +549,11 @@ __global__ __launch_bounds__(64) void inflate_chunk_kernel(
     const uint32_t max_w = (uint32_t)(((stream_bytes + 3u) / 4u) - (s0 >> 2)) - 1u;   // last readable dword
     const uint32_t seg_w = (byte0 + seg_len + 3u) / 4u + 2u;       // two more for the look-ahead
     const bool whole = __ballot(my_side != 0u) == 0ull;
+    // the lists of the other instances are made from the first sub-chunk's side information
+    if (whole != (__shfl(my_side, 0, 64) == 0u)) {
+        if (FIRST && lane == 0) atomicOr(status, (unsigned long long)CODEC_BAD_STREAM);
+        return;
+    }
     const uint32_t size_class = whole ? 0u : seg_w;
     if (size_class < SEG_MIN || size_class > SEG_DW) return;       // another instance's chunk
     uint8_t* dst = out + base;
@@ -722,6 +727,8 @@ __global__ __launch_bounds__(64) void inflate_chunk_kernel(
 __global__ void codec_clear_kernel(uint64_t* result) {
     result[0] = 0;
     result[1] = 0;
+    result[2] = 0;      // lengths of the two chunk lists of the decoder
+    result[3] = 0;
 }
 
 void launch_deflate(shifter_ctx* ctx, const uint8_t* d_in, uint64_t n_bytes, uint32_t n_chunks,
@@ -744,17 +751,62 @@ void launch_deflate(shifter_ctx* ctx, const uint8_t* d_in, uint64_t n_bytes, uin
                                                         d_stream);
 }
 
-void launch_inflate(shifter_ctx* ctx, const uint8_t* d_stream, uint64_t stream_bytes,
-                    const uint64_t* d_seg_off, const uint16_t* d_sub_bits, uint64_t n_bytes,
-                    uint32_t n_chunks, uint8_t* d_out) {
+// Lists of the chunks whose segments need the medium and the large instance of the decoder
+// (the same rule as inside the instances); counts in result[2] and result[3].
+__global__ __launch_bounds__(BLOCK) void codec_classify_kernel(
+    uint64_t stream_bytes, const uint64_t* __restrict__ seg_off, const uint16_t* __restrict__ side,
+    uint32_t n_chunks, uint32_t* __restrict__ list_medium, uint32_t* __restrict__ list_large,
+    uint64_t* __restrict__ result) {
+    const uint32_t c = blockIdx.x * BLOCK + threadIdx.x;
+    if (c >= n_chunks) return;
+    const uint64_t s0 = seg_off[c], s1 = seg_off[c + 1];
+    if (s1 < s0 || s1 > stream_bytes || s1 - s0 < 5u || s1 - s0 > CODEC_SLOT) return;   // the first instance reports it
+    if (side[(uint64_t)c * CODEC_NSUB] == 0u) return;                                     // one stored block
+    const uint32_t seg_w = ((uint32_t)(s0 & 3u) + (uint32_t)(s1 - s0) + 3u) / 4u + 2u;
+    if (seg_w > CODEC_SEG_MEDIUM)
+        list_large[atomicAdd(reinterpret_cast<uint32_t*>(&result[3]), 1u)] = c;
+    else if (seg_w > CODEC_SEG_SMALL)
+        list_medium[atomicAdd(reinterpret_cast<uint32_t*>(&result[2]), 1u)] = c;
+}
+
+// Waits (on an event) for the two list lengths.  Returns a HIP error code (0: fine).
+int launch_inflate(shifter_ctx* ctx, const uint8_t* d_stream, uint64_t stream_bytes,
+                   const uint64_t* d_seg_off, const uint16_t* d_sub_bits, uint64_t n_bytes,
+                   uint32_t n_chunks, uint8_t* d_out) {
+    // room for the two lists, kept by the context and grown when a longer stream comes
+    if (ctx->codec_list_cap < 2ull * n_chunks) {
+        if (ctx->d_codec_list) {
+            hipError_t e = hipFree(ctx->d_codec_list);
+            ctx->d_codec_list = nullptr;
+            ctx->codec_list_cap = 0;
+            if (e != hipSuccess) return (int)e;
+        }
+        hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->d_codec_list), sizeof(uint32_t) * 2ull * n_chunks);
+        if (e != hipSuccess) return (int)e;
+        ctx->codec_list_cap = 2ull * n_chunks;
+    }
+    uint32_t* list_medium = ctx->d_codec_list;
+    uint32_t* list_large = ctx->d_codec_list + n_chunks;
     codec_clear_kernel<<<1, 1, 0, ctx->stream>>>(ctx->d_codec);
     ProfileScope ps(ctx, K_INFLATE_CHUNK);
+    codec_classify_kernel<<<(n_chunks + BLOCK - 1) / BLOCK, BLOCK, 0, ctx->stream>>>(
+        stream_bytes, d_seg_off, d_sub_bits, n_chunks, list_medium, list_large, ctx->d_codec);
+    hipError_t e = hipMemcpyAsync(ctx->h_codec + 2, ctx->d_codec + 2, 2 * sizeof(uint64_t),
+                                  hipMemcpyDeviceToHost, ctx->stream);
+    if (e != hipSuccess) return (int)e;
+    if ((e = hipEventRecord(ctx->codec_ev, ctx->stream)) != hipSuccess) return (int)e;
+    // the first instance (it skips the chunks of the other two) runs while the counts travel
     inflate_chunk_kernel<CODEC_SEG_SMALL, 0><<<n_chunks, 64, 0, ctx->stream>>>(
-        d_stream, stream_bytes, d_seg_off, d_sub_bits, n_bytes, n_chunks, d_out, ctx->d_codec);
-    inflate_chunk_kernel<CODEC_SEG_MEDIUM, CODEC_SEG_SMALL + 1><<<n_chunks, 64, 0, ctx->stream>>>(
-        d_stream, stream_bytes, d_seg_off, d_sub_bits, n_bytes, n_chunks, d_out, ctx->d_codec);
-    inflate_chunk_kernel<CODEC_SEG_LARGE, CODEC_SEG_MEDIUM + 1><<<n_chunks, 64, 0, ctx->stream>>>(
-        d_stream, stream_bytes, d_seg_off, d_sub_bits, n_bytes, n_chunks, d_out, ctx->d_codec);
+        d_stream, stream_bytes, d_seg_off, d_sub_bits, n_bytes, n_chunks, d_out, ctx->d_codec, nullptr);
+    if ((e = hipEventSynchronize(ctx->codec_ev)) != hipSuccess) return (int)e;
+    const uint32_t n_medium = (uint32_t)ctx->h_codec[2], n_large = (uint32_t)ctx->h_codec[3];
+    if (n_medium)
+        inflate_chunk_kernel<CODEC_SEG_MEDIUM, CODEC_SEG_SMALL + 1><<<n_medium, 64, 0, ctx->stream>>>(
+            d_stream, stream_bytes, d_seg_off, d_sub_bits, n_bytes, n_chunks, d_out, ctx->d_codec, list_medium);
+    if (n_large)
+        inflate_chunk_kernel<CODEC_SEG_LARGE, CODEC_SEG_MEDIUM + 1><<<n_large, 64, 0, ctx->stream>>>(
+            d_stream, stream_bytes, d_seg_off, d_sub_bits, n_bytes, n_chunks, d_out, ctx->d_codec, list_large);
+    return 0;
 }
 
 }  // namespace shifter

@@ -248,8 +248,11 @@ struct shifter_ctx {
     shifter::SpecState last_spec{};  // outcome of the last single-pass selection
     int last_path = 0;               // 1: single pass decided; 2: multi-pass select ran
     shifter_threshold last_record{};  // record of the last shifter_prune_fused that waited
-    uint64_t* d_codec = nullptr;      // codec: [0] stream bytes, [1] status bits (device)
-    uint64_t* h_codec = nullptr;      // pinned copy of the two
+    uint64_t* d_codec = nullptr;      // codec: [0] stream bytes, [1] status bits, [2], [3] list lengths (device)
+    uint64_t* h_codec = nullptr;      // pinned copy of the four
+    uint32_t* d_codec_list = nullptr; // decoder: chunk lists of the medium and the large instance
+    uint64_t codec_list_cap = 0;      //   its capacity in entries
+    hipEvent_t codec_ev = nullptr;
     // a shifter_prune_fused call whose outcome has not been collected yet
     struct Pending {
         bool active = false;
@@ -317,9 +320,9 @@ inline uint64_t codec_slots_offset(uint64_t n_chunks) { return (n_chunks * 4u + 
 void launch_deflate(shifter_ctx* ctx, const uint8_t* d_in, uint64_t n_bytes, uint32_t n_chunks,
                     uint8_t* d_work, uint8_t* d_stream, uint64_t stream_cap, uint64_t* d_seg_off,
                     uint16_t* d_sub_bits);
-void launch_inflate(shifter_ctx* ctx, const uint8_t* d_stream, uint64_t stream_bytes,
-                    const uint64_t* d_seg_off, const uint16_t* d_sub_bits, uint64_t n_bytes,
-                    uint32_t n_chunks, uint8_t* d_out);
+int launch_inflate(shifter_ctx* ctx, const uint8_t* d_stream, uint64_t stream_bytes,
+                   const uint64_t* d_seg_off, const uint16_t* d_sub_bits, uint64_t n_bytes,
+                   uint32_t n_chunks, uint8_t* d_out);
 void launch_fold(shifter_ctx* ctx, const shifter_model* m, const float* d_w, const float* d_vecs,
                  float eps, float* d_w_out, float* d_bias_out);
 
