@@ -213,22 +213,22 @@ __global__ __launch_bounds__(64) void deflate_chunk_kernel(
     const uint32_t m = (uint32_t)min((uint64_t)CODEC_CHUNK, n_bytes - min(n_bytes, base));
     const uint32_t last = c + 1u == n_chunks ? 1u : 0u;
     // stage: whole dwords coalesced, the ragged tail byte by byte, the rest zero
+    uint32_t any_bits = m == CODEC_CHUNK ? 0u : 1u;    // stays 0 only for a full chunk of zeros
     if (m == CODEC_CHUNK) {
-        // 32 loads of 16 bytes per lane, eight in flight at a time
+        // 32 loads of 16 bytes per lane, all in flight together
         const uint4* in128 = reinterpret_cast<const uint4*>(in + base);
-        for (uint32_t b = 0; b < 4u; ++b) {
-            uint4 v[8];
+        uint4 v[32];
 #pragma unroll
-            for (uint32_t u = 0; u < 8u; ++u) v[u] = in128[(b * 8u + u) * 64u + lane];
+        for (uint32_t u = 0; u < 32u; ++u) v[u] = in128[u * 64u + lane];
 #pragma unroll
-            for (uint32_t u = 0; u < 8u; ++u) {
-                const uint32_t g = ((b * 8u + u) * 64u + lane) * 4u;
-                const uint32_t l = g / CODEC_SUBW, j = g % CODEC_SUBW;
-                s_in[sub_word(l, j)] = v[u].x;
-                s_in[sub_word(l, j + 1u)] = v[u].y;
-                s_in[sub_word(l, j + 2u)] = v[u].z;
-                s_in[sub_word(l, j + 3u)] = v[u].w;
-            }
+        for (uint32_t u = 0; u < 32u; ++u) {
+            any_bits |= v[u].x | v[u].y | v[u].z | v[u].w;
+            const uint32_t g = (u * 64u + lane) * 4u;
+            const uint32_t l = g / CODEC_SUBW, j = g % CODEC_SUBW;
+            s_in[sub_word(l, j)] = v[u].x;
+            s_in[sub_word(l, j + 1u)] = v[u].y;
+            s_in[sub_word(l, j + 2u)] = v[u].z;
+            s_in[sub_word(l, j + 3u)] = v[u].w;
         }
     } else {
         const uint32_t* in32 = reinterpret_cast<const uint32_t*>(in + base);
@@ -251,7 +251,16 @@ __global__ __launch_bounds__(64) void deflate_chunk_kernel(
     // second and third byte of runs shorter than 4) and the starts of runs of 4 or more (M).
     uint32_t* mk = s_mask + lane * CODEC_MASKW;
     uint32_t tok_bits = 0;
-    {
+    if (__ballot(any_bits != 0u) == 0ull) {
+        // a chunk of zeros (common in sparse models): every sub-chunk is one literal and the
+        // matches 258 + 253
+#pragma unroll
+        for (uint32_t a = 0; a < CODEC_MASKW; ++a) {
+            mk[a] = (a == 0 || a == CODEC_SUB / 32) ? 1u : 0u;
+            s_run[lane * CODEC_MASKW + a] = a == 0 ? 1u : 0u;
+        }
+        tok_bits = 8u;
+    } else {
         constexpr uint32_t NW = CODEC_SUB / 32;
         uint32_t S[NW + 1], G[NW];
         uint32_t carry = 0x100u;                       // no byte equals it: byte 0 starts a run
