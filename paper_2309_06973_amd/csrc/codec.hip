@@ -35,10 +35,11 @@ static_assert(CODEC_NSUB == 64, "one lane per sub-chunk");
 
 enum : uint32_t { CODEC_BAD_STREAM = 1u, CODEC_CAPACITY = 2u };
 
-// Sub-chunk l, dword j of the chunk staged in LDS: rotated by the lane so that the lanes
-// of a wave, each walking its own sub-chunk at the same pace, hit different banks.
+// Sub-chunk l, dword j of the chunk staged in LDS: every row is rotated by l 16-byte
+// vectors, so that the lanes of a wave, each walking its own sub-chunk at the same pace,
+// spread over the banks while a vector stays whole.
 __device__ __forceinline__ uint32_t sub_word(uint32_t l, uint32_t j) {
-    return l * CODEC_SUBW + ((j + l) & (CODEC_SUBW - 1));
+    return l * CODEC_SUBW + ((j + 4u * l) & (CODEC_SUBW - 1));
 }
 
 // Fixed literal code of RFC 1951 section 3.2.6, bit-reversed so that it can be appended
@@ -203,7 +204,7 @@ __device__ __forceinline__ uint32_t place_subs(const uint32_t* s_side, uint32_t 
 __global__ __launch_bounds__(64) void deflate_chunk_kernel(
     const uint8_t* __restrict__ in, uint64_t n_bytes, uint32_t n_chunks,
     uint8_t* __restrict__ slots, uint32_t* __restrict__ seg_size, uint16_t* __restrict__ side) {
-    __shared__ uint32_t s_in[CODEC_CHUNK / 4];
+    __shared__ __align__(16) uint32_t s_in[CODEC_CHUNK / 4];
     __shared__ uint32_t s_out[CODEC_CHUNK / 4 + 8];
     __shared__ uint32_t s_mask[CODEC_NSUB * CODEC_MASKW];
     __shared__ uint32_t s_run[CODEC_NSUB * CODEC_MASKW];
@@ -225,10 +226,7 @@ __global__ __launch_bounds__(64) void deflate_chunk_kernel(
             any_bits |= v[u].x | v[u].y | v[u].z | v[u].w;
             const uint32_t g = (u * 64u + lane) * 4u;
             const uint32_t l = g / CODEC_SUBW, j = g % CODEC_SUBW;
-            s_in[sub_word(l, j)] = v[u].x;
-            s_in[sub_word(l, j + 1u)] = v[u].y;
-            s_in[sub_word(l, j + 2u)] = v[u].z;
-            s_in[sub_word(l, j + 3u)] = v[u].w;
+            *reinterpret_cast<uint4*>(&s_in[sub_word(l, j)]) = v[u];
         }
     } else {
         const uint32_t* in32 = reinterpret_cast<const uint32_t*>(in + base);
@@ -267,9 +265,13 @@ __global__ __launch_bounds__(64) void deflate_chunk_kernel(
 #pragma unroll
         for (uint32_t a = 0; a < NW; ++a) {
             uint32_t sw = 0, gw = 0;
+            uint4 q4[2];
+            q4[0] = *reinterpret_cast<const uint4*>(&s_in[sub_word(lane, a * 8u)]);
+            q4[1] = *reinterpret_cast<const uint4*>(&s_in[sub_word(lane, a * 8u + 4u)]);
+            const uint32_t ws[8] = {q4[0].x, q4[0].y, q4[0].z, q4[0].w, q4[1].x, q4[1].y, q4[1].z, q4[1].w};
 #pragma unroll
             for (uint32_t b = 0; b < 8u; ++b) {
-                const uint32_t w = s_in[sub_word(lane, a * 8u + b)];
+                const uint32_t w = ws[b];
                 const uint32_t x = w ^ ((w << 8) | (carry & 0xffu));
                 // bit 7 of every byte: the byte of x is not 0; the byte of w is >= 0x90
                 uint32_t ne = ((((x & 0x7f7f7f7fu) + 0x7f7f7f7fu) | x) & 0x80808080u) >> 7;
@@ -652,7 +654,8 @@ __global__ __launch_bounds__(64) void inflate_chunk_kernel(
         const uint32_t hi_b = min(n_l, lo_b + CODEC_STAGE);     // this lane produces [i, hi_b)
 #pragma unroll
         for (uint32_t j = 0; j < CODEC_STAGE_W / 4; ++j)
-            reinterpret_cast<uint4*>(s_img)[lane * (CODEC_STAGE_W / 4) + j] = make_uint4(0, 0, 0, 0);
+            reinterpret_cast<uint4*>(s_img)[j * CODEC_NSUB + lane] = make_uint4(0, 0, 0, 0);
+        __syncthreads();
         if (stored_sub) {
             if (ok && hi_b > lo_b) {
                 const uint32_t sh = (d0 & 3u) * 8u, w0 = (d0 + lo_b) >> 2;
