@@ -42,6 +42,19 @@ def test_struct_sizes_match_header_layout():
     assert C.sizeof(S.ModelInfo) == 80
 
 
+def test_codec_layout_and_fold_descriptor(lib):
+    # sizes of the codec's buffers are plain host arithmetic
+    chunk = S.SHIFTER_CODEC_CHUNK
+    for n, chunks in ((0, 1), (1, 1), (chunk - 1, 1), (chunk, 1), (chunk + 1, 2), (10 * chunk, 10),
+                      (1289317376, 39347)):
+        n_chunks, work, bound = S.shifter_codec_layout(n)
+        assert n_chunks == chunks
+        assert bound == n + 5 * chunks                       # every segment one stored block
+        assert work >= chunks * (chunk + 8) + 4 * chunks and work % 8 == 0
+    assert S.SHIFTER_CODEC_CHUNK // S.SHIFTER_CODEC_SUB == 64
+    assert C.sizeof(S.FoldDesc) == 32
+
+
 def test_model_info_and_layout(lib):
     spec = synth.build_config(3)
     m = S.shifter_model_create(spec.tensors, spec.vecs, spec.groups)
