@@ -56,6 +56,16 @@ extern "C" const char* shifter_last_error(const shifter_ctx* ctx) {
     return ctx ? ctx->err.c_str() : g_err.c_str();
 }
 
+static void destroy_codec_objects(shifter_ctx* c) {
+    for (hipStream_t st : c->codec_aux)
+        if (st) { (void)hipStreamSynchronize(st); (void)hipStreamDestroy(st); }
+    for (hipEvent_t ev : {c->codec_ev, c->codec_fork, c->codec_join[0], c->codec_join[1]})
+        if (ev) (void)hipEventDestroy(ev);
+    if (c->d_codec) (void)hipFree(c->d_codec);
+    if (c->h_codec) (void)hipHostFree(c->h_codec);
+    if (c->d_codec_list) (void)hipFree(c->d_codec_list);
+}
+
 extern "C" int shifter_create(shifter_ctx** out, int device, void* hip_stream) {
     if (!out) return fail(nullptr, SHIFTER_ERR_INVALID_ARG, "shifter_create: out is NULL");
     *out = nullptr;
@@ -77,10 +87,14 @@ extern "C" int shifter_create(shifter_ctx** out, int device, void* hip_stream) {
     // result words of the codec calls (stream size, status), device and pinned host copy
     if (hipMalloc(reinterpret_cast<void**>(&c->d_codec), 4 * sizeof(uint64_t)) != hipSuccess ||
         hipHostMalloc(reinterpret_cast<void**>(&c->h_codec), 4 * sizeof(uint64_t), hipHostMallocDefault) != hipSuccess ||
-        hipEventCreateWithFlags(&c->codec_ev, hipEventDisableTiming) != hipSuccess) {
+        hipEventCreateWithFlags(&c->codec_ev, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->codec_fork, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->codec_join[0], hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->codec_join[1], hipEventDisableTiming) != hipSuccess ||
+        hipStreamCreateWithFlags(&c->codec_aux[0], hipStreamNonBlocking) != hipSuccess ||
+        hipStreamCreateWithFlags(&c->codec_aux[1], hipStreamNonBlocking) != hipSuccess) {
         (void)hipGetLastError();
-        if (c->d_codec) (void)hipFree(c->d_codec);
-        if (c->h_codec) (void)hipHostFree(c->h_codec);
+        destroy_codec_objects(c);
         delete c;
         return fail(nullptr, SHIFTER_ERR_OOM, "shifter_create: allocation failed");
     }
@@ -110,10 +124,7 @@ extern "C" int shifter_destroy(shifter_ctx* ctx) {
     (void)hipStreamSynchronize(ctx->stream);
     for (auto& r : ctx->recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     for (auto e : ctx->pool) (void)hipEventDestroy(e);
-    if (ctx->d_codec) (void)hipFree(ctx->d_codec);
-    if (ctx->h_codec) (void)hipHostFree(ctx->h_codec);
-    if (ctx->d_codec_list) (void)hipFree(ctx->d_codec_list);
-    if (ctx->codec_ev) (void)hipEventDestroy(ctx->codec_ev);
+    destroy_codec_objects(ctx);
     delete ctx;
     return SHIFTER_OK;
 }

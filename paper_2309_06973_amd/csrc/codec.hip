@@ -781,43 +781,71 @@ __global__ __launch_bounds__(BLOCK) void codec_classify_kernel(
         list_medium[atomicAdd(reinterpret_cast<uint32_t*>(&result[2]), 1u)] = c;
 }
 
-// Waits (on an event) for the two list lengths.  Returns a HIP error code (0: fine).
+// Streams of this many chunks or more get lists for the two larger instances (a block that
+// finds a chunk is not its own costs about 2 us of a CU slot); for shorter ones all three
+// instances visit every chunk and the call needs no wait in the middle.
+constexpr uint32_t CODEC_LIST_MIN_CHUNKS = 16384;
+
+// Returns a HIP error code (0: fine).
 int launch_inflate(shifter_ctx* ctx, const uint8_t* d_stream, uint64_t stream_bytes,
                    const uint64_t* d_seg_off, const uint16_t* d_sub_bits, uint64_t n_bytes,
                    uint32_t n_chunks, uint8_t* d_out) {
-    // room for the two lists, kept by the context and grown when a longer stream comes
-    if (ctx->codec_list_cap < 2ull * n_chunks) {
-        if (ctx->d_codec_list) {
-            hipError_t e = hipFree(ctx->d_codec_list);
-            ctx->d_codec_list = nullptr;
-            ctx->codec_list_cap = 0;
+    const bool lists = n_chunks >= CODEC_LIST_MIN_CHUNKS;
+    uint32_t *list_medium = nullptr, *list_large = nullptr;
+    if (lists) {
+        // room for the two lists, kept by the context and grown when a longer stream comes
+        if (ctx->codec_list_cap < 2ull * n_chunks) {
+            if (ctx->d_codec_list) {
+                hipError_t e = hipFree(ctx->d_codec_list);
+                ctx->d_codec_list = nullptr;
+                ctx->codec_list_cap = 0;
+                if (e != hipSuccess) return (int)e;
+            }
+            hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->d_codec_list), sizeof(uint32_t) * 2ull * n_chunks);
             if (e != hipSuccess) return (int)e;
+            ctx->codec_list_cap = 2ull * n_chunks;
         }
-        hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->d_codec_list), sizeof(uint32_t) * 2ull * n_chunks);
-        if (e != hipSuccess) return (int)e;
-        ctx->codec_list_cap = 2ull * n_chunks;
+        list_medium = ctx->d_codec_list;
+        list_large = ctx->d_codec_list + n_chunks;
     }
-    uint32_t* list_medium = ctx->d_codec_list;
-    uint32_t* list_large = ctx->d_codec_list + n_chunks;
     codec_clear_kernel<<<1, 1, 0, ctx->stream>>>(ctx->d_codec);
     ProfileScope ps(ctx, K_INFLATE_CHUNK);
-    codec_classify_kernel<<<(n_chunks + BLOCK - 1) / BLOCK, BLOCK, 0, ctx->stream>>>(
-        stream_bytes, d_seg_off, d_sub_bits, n_chunks, list_medium, list_large, ctx->d_codec);
-    hipError_t e = hipMemcpyAsync(ctx->h_codec + 2, ctx->d_codec + 2, 2 * sizeof(uint64_t),
-                                  hipMemcpyDeviceToHost, ctx->stream);
+    uint32_t n_medium = n_chunks, n_large = n_chunks;
+    if (lists) {
+        codec_classify_kernel<<<(n_chunks + BLOCK - 1) / BLOCK, BLOCK, 0, ctx->stream>>>(
+            stream_bytes, d_seg_off, d_sub_bits, n_chunks, list_medium, list_large, ctx->d_codec);
+        hipError_t e = hipMemcpyAsync(ctx->h_codec + 2, ctx->d_codec + 2, 2 * sizeof(uint64_t),
+                                      hipMemcpyDeviceToHost, ctx->stream);
+        if (e != hipSuccess) return (int)e;
+        if ((e = hipEventRecord(ctx->codec_ev, ctx->stream)) != hipSuccess) return (int)e;
+    }
+    // The three instances are independent: the first runs on the caller's stream, the other
+    // two on streams of the context that fork from it and join it again (all of default
+    // priority), so that their blocks share the CUs instead of queueing behind each other.
+    hipError_t e = hipEventRecord(ctx->codec_fork, ctx->stream);
     if (e != hipSuccess) return (int)e;
-    if ((e = hipEventRecord(ctx->codec_ev, ctx->stream)) != hipSuccess) return (int)e;
     // the first instance (it skips the chunks of the other two) runs while the counts travel
     inflate_chunk_kernel<CODEC_SEG_SMALL, 0><<<n_chunks, 64, 0, ctx->stream>>>(
         d_stream, stream_bytes, d_seg_off, d_sub_bits, n_bytes, n_chunks, d_out, ctx->d_codec, nullptr);
-    if ((e = hipEventSynchronize(ctx->codec_ev)) != hipSuccess) return (int)e;
-    const uint32_t n_medium = (uint32_t)ctx->h_codec[2], n_large = (uint32_t)ctx->h_codec[3];
-    if (n_medium)
-        inflate_chunk_kernel<CODEC_SEG_MEDIUM, CODEC_SEG_SMALL + 1><<<n_medium, 64, 0, ctx->stream>>>(
-            d_stream, stream_bytes, d_seg_off, d_sub_bits, n_bytes, n_chunks, d_out, ctx->d_codec, list_medium);
-    if (n_large)
-        inflate_chunk_kernel<CODEC_SEG_LARGE, CODEC_SEG_MEDIUM + 1><<<n_large, 64, 0, ctx->stream>>>(
+    if (lists) {
+        if ((e = hipEventSynchronize(ctx->codec_ev)) != hipSuccess) return (int)e;
+        n_medium = (uint32_t)ctx->h_codec[2];
+        n_large = (uint32_t)ctx->h_codec[3];
+    }
+    if (n_large) {
+        if ((e = hipStreamWaitEvent(ctx->codec_aux[0], ctx->codec_fork, 0)) != hipSuccess) return (int)e;
+        inflate_chunk_kernel<CODEC_SEG_LARGE, CODEC_SEG_MEDIUM + 1><<<n_large, 64, 0, ctx->codec_aux[0]>>>(
             d_stream, stream_bytes, d_seg_off, d_sub_bits, n_bytes, n_chunks, d_out, ctx->d_codec, list_large);
+        if ((e = hipEventRecord(ctx->codec_join[0], ctx->codec_aux[0])) != hipSuccess) return (int)e;
+        if ((e = hipStreamWaitEvent(ctx->stream, ctx->codec_join[0], 0)) != hipSuccess) return (int)e;
+    }
+    if (n_medium) {
+        if ((e = hipStreamWaitEvent(ctx->codec_aux[1], ctx->codec_fork, 0)) != hipSuccess) return (int)e;
+        inflate_chunk_kernel<CODEC_SEG_MEDIUM, CODEC_SEG_SMALL + 1><<<n_medium, 64, 0, ctx->codec_aux[1]>>>(
+            d_stream, stream_bytes, d_seg_off, d_sub_bits, n_bytes, n_chunks, d_out, ctx->d_codec, list_medium);
+        if ((e = hipEventRecord(ctx->codec_join[1], ctx->codec_aux[1])) != hipSuccess) return (int)e;
+        if ((e = hipStreamWaitEvent(ctx->stream, ctx->codec_join[1], 0)) != hipSuccess) return (int)e;
+    }
     return 0;
 }
 

@@ -252,7 +252,9 @@ struct shifter_ctx {
     uint64_t* h_codec = nullptr;      // pinned copy of the four
     uint32_t* d_codec_list = nullptr; // decoder: chunk lists of the medium and the large instance
     uint64_t codec_list_cap = 0;      //   its capacity in entries
-    hipEvent_t codec_ev = nullptr;
+    hipEvent_t codec_ev = nullptr;    //   its two lengths have arrived on the host
+    hipStream_t codec_aux[2] = {nullptr, nullptr};   // decoder: streams of the two larger instances
+    hipEvent_t codec_fork = nullptr, codec_join[2] = {nullptr, nullptr};
     // a shifter_prune_fused call whose outcome has not been collected yet
     struct Pending {
         bool active = false;
