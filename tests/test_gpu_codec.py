@@ -90,6 +90,45 @@ def test_codec_small_inputs_bit_exact():
         codec.close()
 
 
+def random_mixture(rng):
+    """Pieces of every kind the encoder treats differently, at random lengths and offsets."""
+    total = int(rng.integers(1, 3 * C_ + 2000))
+    out = bytearray()
+    while len(out) < total:
+        kind = int(rng.integers(0, 8))
+        n = int(rng.choice([1, 2, 3, 4, 5, 7, 64, 257, 258, 259, 260, 261, 262, 300, 511, 512, 513,
+                            700, 1500, 5000, int(rng.integers(1, 20000))]))
+        if kind == 0:
+            out += bytes(n)                                              # zeros
+        elif kind == 1:
+            out += rng.integers(0, 256, n, dtype=np.uint8).tobytes()     # noise: stored
+        elif kind == 2:
+            out += bytes([int(rng.integers(0, 256))]) * n                # one byte repeated
+        elif kind == 3:
+            out += rng.integers(144, 256, n, dtype=np.uint8).tobytes()   # 9-bit literals only
+        elif kind == 4:
+            out += rng.integers(0, 3, n, dtype=np.uint8).tobytes()       # many short runs
+        elif kind == 5:
+            out += sparse_floats(n // 4 + 1, float(rng.choice([0.3, 0.7, 0.9, 0.99])),
+                                 int(rng.integers(0, 1 << 30)))
+        elif kind == 6:
+            out += (bytes([int(rng.integers(0, 256))]) * int(rng.integers(1, 6))
+                    + bytes(int(rng.integers(0, 9)))) * (n // 4 + 1)     # runs of 1-5 and 0-8
+        else:
+            out += rng.integers(0, 144, n, dtype=np.uint8).tobytes()     # 8-bit literals only
+    return bytes(out[:total])
+
+
+def test_codec_random_mixtures_bit_exact():
+    rng = np.random.default_rng(20230913)
+    codec = Codec()
+    try:
+        for _ in range(120):
+            check(codec, random_mixture(rng))
+    finally:
+        codec.close()
+
+
 @pytest.mark.parametrize("c,s", [(1, 0.9), (3, 0.8), (3, 0.97)])
 def test_codec_sparse_arenas_bit_exact(c, s):
     spec, w, v = synth.generate_config(c)
