@@ -35,7 +35,11 @@
  *     descriptor errors are found on the host before anything is launched.
  *   - The library allocates device memory only in shifter_create and the first call
  *     that uses a model with a context (tables and scratch sized from the model);
- *     later calls allocate nothing.
+ *     later calls allocate nothing (shifter_inflate is the one exception, see there).
+ *   - A context, and a model bound to it, serve one call at a time: calls on the same
+ *     context from several host threads must be serialised by the caller (the scratch
+ *     of a model is shared by all calls that use it).  Different contexts are
+ *     independent.
  */
 #ifndef SHIFTER_H
 #define SHIFTER_H
