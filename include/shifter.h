@@ -35,7 +35,7 @@
  *     descriptor errors are found on the host before anything is launched.
  *   - The library allocates device memory only in shifter_create and the first call
  *     that uses a model with a context (tables and scratch sized from the model);
- *     later calls allocate nothing (shifter_inflate is the one exception, see there).
+ *     later calls allocate nothing (the codec calls are the one exception, see there).
  *   - A context, and a model bound to it, serve one call at a time: calls on the same
  *     context from several host threads must be serialised by the caller (the scratch
  *     of a model is shared by all calls that use it).  Different contexts are
@@ -386,7 +386,9 @@ int shifter_fold_bn(shifter_ctx* ctx, const shifter_model* model,
  *                        information
  *   h_stream_bytes       host or NULL.  Non-NULL: the call waits for the stream and stores
  *                        the stream's size; returns SHIFTER_ERR_CAPACITY (size still
- *                        stored, nothing written to d_stream) when stream_cap is too small
+ *                        stored, nothing written to d_stream) when stream_cap is too small.
+ *                        NULL: the call still waits once in the middle (for its first
+ *                        pass), then returns with the rest enqueued
  * shifter_inflate        decodes a stream made by shifter_deflate, given its side
  *                        information, into n_bytes at d_out (device, 16-byte aligned).
  *                        Always waits; SHIFTER_ERR_INVALID_ARG with "bad stream" when the
@@ -395,8 +397,8 @@ int shifter_fold_bn(shifter_ctx* ctx, const shifter_model* model,
  *                        stay inside the buffers up to the 4-byte granule that holds the
  *                        stream's last byte; d_out is then unspecified).  DEFLATE carries
  *                        no checksum: a damaged literal that still parses is not found.
- * The codec calls need no model.  shifter_inflate keeps 8 bytes per chunk of device memory
- * in the context, allocated when a stream with more chunks than before comes. */
+ * The codec calls need no model.  They keep chunk lists of 8 bytes per chunk of device
+ * memory in the context, allocated when an input with more chunks than before comes. */
 #define SHIFTER_CODEC_CHUNK 32768u
 #define SHIFTER_CODEC_SUB 512u
 int shifter_codec_layout(uint64_t n_bytes, uint64_t* h_n_chunks, uint64_t* h_work_bytes,

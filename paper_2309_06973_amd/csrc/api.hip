@@ -1160,8 +1160,9 @@ extern "C" int shifter_deflate(shifter_ctx* ctx, const void* d_in, uint64_t n_by
     if (work_bytes < codec_work_bytes(n_chunks))
         return fail(ctx, SHIFTER_ERR_INVALID_ARG,
                     "deflate: workspace too small, needs " + std::to_string(codec_work_bytes(n_chunks)) + " bytes");
-    launch_deflate(ctx, static_cast<const uint8_t*>(d_in), n_bytes, (uint32_t)n_chunks,
-                   static_cast<uint8_t*>(d_work), d_stream, stream_cap, d_seg_off, d_sub_bits);
+    HIP_TRY(ctx, (hipError_t)launch_deflate(ctx, static_cast<const uint8_t*>(d_in), n_bytes, (uint32_t)n_chunks,
+                                            static_cast<uint8_t*>(d_work), d_stream, stream_cap, d_seg_off,
+                                            d_sub_bits));
     if ((rc = after_launch(ctx, "deflate"))) return rc;
     if (!h_stream_bytes) return SHIFTER_OK;
     uint64_t total, status;

@@ -201,15 +201,22 @@ __device__ __forceinline__ uint32_t place_subs(const uint32_t* s_side, uint32_t 
 // One wave per chunk: stages the chunk in LDS, marks the run starts, counts the token bits
 // of every sub-chunk, chooses coded or stored per sub-chunk and for the chunk, builds the
 // segment in LDS and writes it to the chunk's slot of the workspace together with its size.
+// Two instances: OUT_DW = CODEC_OUT_SMALL (12 KiB of LDS for the segment, three waves per CU)
+// takes every chunk first and passes those with a longer segment on to a list, which the
+// instance with room for any segment (two waves per CU) works through.
+constexpr uint32_t CODEC_OUT_SMALL = 3072;
+constexpr uint32_t CODEC_OUT_FULL = CODEC_CHUNK / 4 + 8;
+template <uint32_t OUT_DW>
 __global__ __launch_bounds__(64) void deflate_chunk_kernel(
     const uint8_t* __restrict__ in, uint64_t n_bytes, uint32_t n_chunks,
-    uint8_t* __restrict__ slots, uint32_t* __restrict__ seg_size, uint16_t* __restrict__ side) {
+    uint8_t* __restrict__ slots, uint32_t* __restrict__ seg_size, uint16_t* __restrict__ side,
+    const uint32_t* __restrict__ list, uint32_t* __restrict__ long_list,
+    uint32_t* __restrict__ long_count) {
     __shared__ __align__(16) uint32_t s_in[CODEC_CHUNK / 4];
-    __shared__ uint32_t s_out[CODEC_CHUNK / 4 + 8];
+    __shared__ uint32_t s_out[OUT_DW];
     __shared__ uint32_t s_mask[CODEC_NSUB * CODEC_MASKW];
-    __shared__ uint32_t s_run[CODEC_NSUB * CODEC_MASKW];
     __shared__ uint32_t s_side[CODEC_NSUB];
-    const uint32_t c = blockIdx.x, lane = threadIdx.x;
+    const uint32_t c = list ? list[blockIdx.x] : blockIdx.x, lane = threadIdx.x;
     const uint64_t base = (uint64_t)c * CODEC_CHUNK;
     const uint32_t m = (uint32_t)min((uint64_t)CODEC_CHUNK, n_bytes - min(n_bytes, base));
     const uint32_t last = c + 1u == n_chunks ? 1u : 0u;
@@ -246,17 +253,15 @@ __global__ __launch_bounds__(64) void deflate_chunk_kernel(
     // Bit masks over the bytes of this lane's sub-chunk, 16 words each: S, byte i starts a run
     // (it differs from byte i - 1; position n_l counts as a start); G, byte i >= 144 (its
     // literal code has 9 bits).  From S: the bytes sent as literals (L: starts, and the
-    // second and third byte of runs shorter than 4) and the starts of runs of 4 or more (M).
+    // second and third byte of runs shorter than 4); a literal not followed by a literal
+    // starts a run of 4 or more.
     uint32_t* mk = s_mask + lane * CODEC_MASKW;
     uint32_t tok_bits = 0;
     if (__ballot(any_bits != 0u) == 0ull) {
         // a chunk of zeros (common in sparse models): every sub-chunk is one literal and the
         // matches 258 + 253
 #pragma unroll
-        for (uint32_t a = 0; a < CODEC_MASKW; ++a) {
-            mk[a] = (a == 0 || a == CODEC_SUB / 32) ? 1u : 0u;
-            s_run[lane * CODEC_MASKW + a] = a == 0 ? 1u : 0u;
-        }
+        for (uint32_t a = 0; a < CODEC_MASKW; ++a) mk[a] = (a == 0 || a == CODEC_SUB / 32) ? 1u : 0u;
         tok_bits = 8u;
     } else {
         constexpr uint32_t NW = CODEC_SUB / 32;
@@ -300,31 +305,28 @@ __global__ __launch_bounds__(64) void deflate_chunk_kernel(
             const uint32_t s_b1 = (s0 << 1) | (sp >> 31), s_b2 = (s0 << 2) | (sp >> 30);   // bit p: S at p - 1, p - 2
             const uint32_t z_b1 = (z0 << 1) | (zp >> 31);
             const uint32_t s_f1 = (s0 >> 1) | (sn << 31), s_f2 = (s0 >> 2) | (sn << 30);   // bit p: S at p + 1, p + 2
-            const uint32_t z_f1 = (z0 >> 1) | (zn << 31), z_f2 = (z0 >> 2) | (zn << 30),
-                           z_f3 = (z0 >> 3) | (zn << 29);
+            const uint32_t z_f1 = (z0 >> 1) | (zn << 31);
             const uint32_t valid = n_l >= 32u * (a + 1u) ? ~0u : (n_l <= 32u * a ? 0u : (1u << (n_l - 32u * a)) - 1u);
             const uint32_t lit = (s0 | (z0 & s_b1 & s_f1) | (z0 & s_b1 & z_f1 & s_f2) |
                                   (z0 & z_b1 & s_b2 & s_f1)) & valid;
-            const uint32_t run4 = s0 & z_f1 & z_f2 & z_f3 & valid;
             n_lit += (uint32_t)__popc(lit);
             n_nine += (uint32_t)__popc(lit & G[a]);
             const uint32_t end_bit = (n_l < CODEC_SUB && (n_l >> 5) == a) ? 1u << (n_l & 31u) : 0u;
             mk[a] = lit | end_bit;
-            s_run[lane * CODEC_MASKW + a] = run4;
         }
         mk[NW] = 1u;
         tok_bits = 8u * n_lit + n_nine;
     }
-    // the matches of the runs of 4 or more (every lane reads only the rows it wrote itself)
+    // the matches of the runs of 4 or more: a literal whose next byte is not a literal starts
+    // one (every byte of a shorter run is a literal); every lane reads only its own row
     {
         BitCounter cnt;
-        const uint32_t* rk = s_run + lane * CODEC_MASKW;
         for (uint32_t a = 0; a < CODEC_SUB / 32; ++a) {
-            uint32_t mw = rk[a];
+            uint32_t mw = mk[a] & ~((mk[a] >> 1) | (mk[a + 1u] << 31));
             while (mw) {
                 const uint32_t p = a * 32u + (uint32_t)__ffs((int)mw) - 1u;
                 mw &= mw - 1u;
-                put_matches(next_bit(mk, p) - p - 1u, cnt);
+                if (p < n_l) put_matches(next_bit(mk, p) - p - 1u, cnt);
             }
         }
         tok_bits += cnt.bits;
@@ -354,6 +356,10 @@ __global__ __launch_bounds__(64) void deflate_chunk_kernel(
             else v = (src(k - 2) >> 24) | (src(k - 1) << 8);
             slot32[k] = v;
         }
+        return;
+    }
+    if (OUT_DW < CODEC_OUT_FULL && (seg_bytes + 3u) / 4u > OUT_DW) {
+        if (lane == 0) long_list[atomicAdd(long_count, 1u)] = c;   // for the other instance
         return;
     }
     side[(uint64_t)c * CODEC_NSUB + lane] = (uint16_t)my_side;
@@ -743,15 +749,43 @@ __global__ void codec_clear_kernel(uint64_t* result) {
     result[3] = 0;
 }
 
-void launch_deflate(shifter_ctx* ctx, const uint8_t* d_in, uint64_t n_bytes, uint32_t n_chunks,
-                    uint8_t* d_work, uint8_t* d_stream, uint64_t stream_cap, uint64_t* d_seg_off,
-                    uint16_t* d_sub_bits) {
+// Room for chunk lists, kept by the context and grown when a longer input comes.
+static hipError_t codec_ensure_list(shifter_ctx* ctx, uint64_t entries) {
+    if (ctx->codec_list_cap >= entries) return hipSuccess;
+    if (ctx->d_codec_list) {
+        hipError_t e = hipFree(ctx->d_codec_list);
+        ctx->d_codec_list = nullptr;
+        ctx->codec_list_cap = 0;
+        if (e != hipSuccess) return e;
+    }
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->d_codec_list), sizeof(uint32_t) * entries);
+    if (e == hipSuccess) ctx->codec_list_cap = entries;
+    return e;
+}
+
+// Waits (on an event) for the first instance and the length of its list.  Returns a HIP
+// error code (0: fine).
+int launch_deflate(shifter_ctx* ctx, const uint8_t* d_in, uint64_t n_bytes, uint32_t n_chunks,
+                   uint8_t* d_work, uint8_t* d_stream, uint64_t stream_cap, uint64_t* d_seg_off,
+                   uint16_t* d_sub_bits) {
+    hipError_t e = codec_ensure_list(ctx, 2ull * n_chunks);
+    if (e != hipSuccess) return (int)e;
     uint32_t* seg_size = reinterpret_cast<uint32_t*>(d_work);
     uint8_t* slots = d_work + codec_slots_offset(n_chunks);
+    uint32_t* long_count = reinterpret_cast<uint32_t*>(ctx->d_codec + 2);
+    codec_clear_kernel<<<1, 1, 0, ctx->stream>>>(ctx->d_codec);
     {
         ProfileScope ps(ctx, K_DEFLATE_CHUNK);
-        deflate_chunk_kernel<<<n_chunks, 64, 0, ctx->stream>>>(d_in, n_bytes, n_chunks, slots,
-                                                               seg_size, d_sub_bits);
+        deflate_chunk_kernel<CODEC_OUT_SMALL><<<n_chunks, 64, 0, ctx->stream>>>(
+            d_in, n_bytes, n_chunks, slots, seg_size, d_sub_bits, nullptr, ctx->d_codec_list, long_count);
+        if ((e = hipMemcpyAsync(ctx->h_codec + 2, ctx->d_codec + 2, sizeof(uint64_t), hipMemcpyDeviceToHost,
+                                ctx->stream)) != hipSuccess) return (int)e;
+        if ((e = hipEventRecord(ctx->codec_ev, ctx->stream)) != hipSuccess) return (int)e;
+        if ((e = hipEventSynchronize(ctx->codec_ev)) != hipSuccess) return (int)e;
+        const uint32_t n_long = (uint32_t)ctx->h_codec[2];
+        if (n_long)
+            deflate_chunk_kernel<CODEC_OUT_FULL><<<n_long, 64, 0, ctx->stream>>>(
+                d_in, n_bytes, n_chunks, slots, seg_size, d_sub_bits, ctx->d_codec_list, nullptr, nullptr);
     }
     {
         ProfileScope ps(ctx, K_CODEC_SCAN);
@@ -761,6 +795,7 @@ void launch_deflate(shifter_ctx* ctx, const uint8_t* d_in, uint64_t n_bytes, uin
     ProfileScope ps(ctx, K_CODEC_PACK);
     codec_pack_kernel<<<n_chunks, 64, 0, ctx->stream>>>(slots, seg_size, d_seg_off, ctx->d_codec,
                                                         d_stream);
+    return 0;
 }
 
 // Lists of the chunks whose segments need the medium and the large instance of the decoder
@@ -793,18 +828,8 @@ int launch_inflate(shifter_ctx* ctx, const uint8_t* d_stream, uint64_t stream_by
     const bool lists = n_chunks >= CODEC_LIST_MIN_CHUNKS;
     uint32_t *list_medium = nullptr, *list_large = nullptr;
     if (lists) {
-        // room for the two lists, kept by the context and grown when a longer stream comes
-        if (ctx->codec_list_cap < 2ull * n_chunks) {
-            if (ctx->d_codec_list) {
-                hipError_t e = hipFree(ctx->d_codec_list);
-                ctx->d_codec_list = nullptr;
-                ctx->codec_list_cap = 0;
-                if (e != hipSuccess) return (int)e;
-            }
-            hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->d_codec_list), sizeof(uint32_t) * 2ull * n_chunks);
-            if (e != hipSuccess) return (int)e;
-            ctx->codec_list_cap = 2ull * n_chunks;
-        }
+        hipError_t e0 = codec_ensure_list(ctx, 2ull * n_chunks);
+        if (e0 != hipSuccess) return (int)e0;
         list_medium = ctx->d_codec_list;
         list_large = ctx->d_codec_list + n_chunks;
     }

@@ -319,9 +319,9 @@ void launch_fix_round(shifter_ctx* ctx, const shifter_model* m, const uint8_t* d
 void launch_fix_out_flags(shifter_ctx* ctx, const shifter_model* m);
 // Codec workspace: segment sizes (u32 per chunk) first, then one slot per chunk.
 inline uint64_t codec_slots_offset(uint64_t n_chunks) { return (n_chunks * 4u + 255u) & ~(uint64_t)255u; }
-void launch_deflate(shifter_ctx* ctx, const uint8_t* d_in, uint64_t n_bytes, uint32_t n_chunks,
-                    uint8_t* d_work, uint8_t* d_stream, uint64_t stream_cap, uint64_t* d_seg_off,
-                    uint16_t* d_sub_bits);
+int launch_deflate(shifter_ctx* ctx, const uint8_t* d_in, uint64_t n_bytes, uint32_t n_chunks,
+                   uint8_t* d_work, uint8_t* d_stream, uint64_t stream_cap, uint64_t* d_seg_off,
+                   uint16_t* d_sub_bits);
 int launch_inflate(shifter_ctx* ctx, const uint8_t* d_stream, uint64_t stream_bytes,
                    const uint64_t* d_seg_off, const uint16_t* d_sub_bits, uint64_t n_bytes,
                    uint32_t n_chunks, uint8_t* d_out);
