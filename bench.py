@@ -95,11 +95,22 @@ def cpu_baseline_sample(spec, w, v, sparsity):
     dt = time.perf_counter() - t0
     n2 = int(r.compacted.w.size)
     b_alg = 13 * tot + 8 * n2
-    return {"value": round(b_alg / dt / 1e9, 4), "unit": "GB/s", "cores": 1,
+    base = {"value": round(b_alg / dt / 1e9, 4), "unit": "GB/s", "cores": 1,
             "kind": "oracle",
             "sample": f"first {n_t} weight tensors of the workload ({tot} weights), one "
                       f"variant at s={sparsity:.4f}; {dt:.2f} s; "
                       f"{1.0 / dt:.4f} variants/s"}
+    # the same sample through a CPU program that selects instead of sorting (checked against
+    # the oracle by the tests): the figure to compare a GPU speed-up with
+    from oracle import fast_baseline as FB
+    t0 = time.perf_counter()
+    out = FB.prune_and_compact_fast(w, v, tensors, vecs, groups, p)
+    dt2 = time.perf_counter() - t0
+    assert int(out[3].size) == n2
+    fast = {"value": round(b_alg / dt2 / 1e9, 4), "unit": "GB/s", "cores": 1,
+            "kind": "selection by partition, vectorised masks and gathers (numpy)",
+            "sample": f"the same sample; {dt2:.2f} s; {1.0 / dt2:.4f} variants/s"}
+    return base, fast
 
 
 def measure(name, steps, warmup, lean_run=True, cpu_leg=True):
@@ -205,6 +216,26 @@ def measure(name, steps, warmup, lean_run=True, cpu_leg=True):
         lean = {"ms_per_step": round(dt2 * 1e3, 4), "variants_per_s": round(k_var / dt2, 2),
                 "algorithmic_bytes_per_step": b2, "gbs": round(b2 / dt2 / 1e9, 2),
                 "pct_hbm_peak": round(100.0 * b2 / dt2 / 1e9 / HBM_PEAK_GBS, 2)}
+
+    # arenas that fit the last-level cache: the same step with the caches evicted before it
+    # (a 1.5 GB buffer is rewritten between steps); the headline figure is back-to-back
+    cold = None
+    if lean_run and pl.model.info.w_extent * 4 <= (256 << 20):
+        scratch = torch.zeros(3 << 27, dtype=torch.float32, device=pl.dev)
+        tot = 0.0
+        for it in range(steps + 2):
+            scratch.add_(1.0)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            step()
+            torch.cuda.synchronize()
+            if it >= 2:
+                tot += time.perf_counter() - t0
+        dtc = tot / steps
+        cold = {"ms_per_step": round(dtc * 1e3, 4), "gbs": round(b_alg / dtc / 1e9, 2),
+                "pct_hbm_peak": round(100.0 * b_alg / dtc / 1e9 / HBM_PEAK_GBS, 2),
+                "variants_per_s": round(k_var / dtc, 2)}
+        del scratch
 
     # the liveness-fixpoint plan (kernel-level index + rounds + rebuild) on the same sparse
     # arena, for the single-variant workloads: what it costs and what it removes on top
@@ -320,6 +351,8 @@ def measure(name, steps, warmup, lean_run=True, cpu_leg=True):
                         "frac_of_peak": round(copy_gbs / HBM_PEAK_GBS, 4)},
         "kernels": kernels,
     }
+    if cold is not None:
+        out["cold_cache"] = cold
     if lean is not None:
         out["without_sparse_arenas"] = lean
     if fixpoint is not None:
@@ -374,9 +407,9 @@ def main():
 
     main_out, (spec, w, v, sparsities) = measure(args.workload, args.steps, args.warmup,
                                                   not args.no_lean, not args.no_cpu_baseline)
-    cpu = None
+    cpu = cpu_fast = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline_sample(spec, w, v, sparsities[-1])
+        cpu, cpu_fast = cpu_baseline_sample(spec, w, v, sparsities[-1])
     del spec, w, v
 
     out = {
@@ -397,6 +430,7 @@ def main():
     out.update(main_out)
     if cpu is not None:
         out["cpu_baseline"] = cpu
+        out["cpu_fast_baseline"] = cpu_fast
     if others:
         # same measurement, same fields, for the other full-size workloads; keyed by name,
         # sorted so that workloads sharing an arena are generated once

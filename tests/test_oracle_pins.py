@@ -440,3 +440,34 @@ def test_planted_mistakes_are_caught(monkeypatch):
     a = np.abs(w_eq)
     wrong = np.lexsort((-np.arange(a.size), a))[:100]
     assert sorted(wrong.tolist()) != brute_force_pruned([float(x) for x in a], 100)
+
+
+# ----------------------------------------------------------------------------- the faster CPU baseline
+def test_fast_baseline_equals_the_oracle():
+    """The benchmark's faster CPU program (selection instead of a sort) gives the oracle's
+    results bit for bit: configs, a residual net, ties, special values, edge counts."""
+    from oracle import fast_baseline as FB
+    cases = []
+    for c, s_ in ((1, 0.9), (1, 0.5), (3, 0.8), (3, 0.97)):
+        spec, w, v = synth.generate_config(c)
+        cases.append((spec, w, v, synth.prune_count(spec.n_prunable, s_)))
+    spec = synth.residual_toy_spec(width=8, mid=6, n_blocks=3)
+    w, v = synth.generate_weights(spec, 21)
+    cases += [(spec, w, v, p) for p in (0, 1, spec.n_prunable // 2, spec.n_prunable - 1,
+                                        spec.n_prunable)]
+    spec = synth.chain_spec([9, 11, 6], k=3, in_ch=2, n_cls=5)
+    _, v = synth.generate_weights(spec, 1)
+    for kind in synth.ADVERSARIAL_KINDS:
+        if kind == "nan":
+            continue
+        w = synth.adversarial_arena(kind, spec.w_elems, seed=3)
+        cases += [(spec, w, v, p) for p in (spec.n_prunable // 3, 2 * spec.n_prunable // 3)]
+    for spec, w, v, p in cases:
+        ref = O.prune_and_compact(w, v, spec.tensors, spec.vecs, spec.groups, [p])[0]
+        ws, mask, nw, cw, cv = FB.prune_and_compact_fast(w, v, spec.tensors, spec.vecs,
+                                                         spec.groups, p)
+        assert np.array_equal(ws.view(np.uint32), ref.w_sparse.view(np.uint32))
+        assert np.array_equal(mask, ref.mask)
+        assert np.array_equal(nw, ref.plan.new_width)
+        assert np.array_equal(cw.view(np.uint32), ref.compacted.w.view(np.uint32))
+        assert np.array_equal(cv.view(np.uint32), ref.compacted.v.view(np.uint32))
