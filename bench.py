@@ -316,6 +316,31 @@ def measure(name, steps, warmup, lean_run=True, cpu_leg=True):
                  "deflate_gbs": round(moved / (enc_ms * 1e-3) / 1e9, 1),
                  "inflate_gbs": round(moved / (dec_ms * 1e-3) / 1e9, 1),
                  "inflate_frac_of_peak": round(moved / (dec_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        # the compacted (structurally pruned) variant of the same step: what is left after
+        # the zero filters and channels are gone still holds the zeros inside the survivors
+        step()
+        n_c = int(kept[0])
+        comp = pl.d_w_out[:n_c]
+        cbuf = torch.empty(S.shifter_codec_layout(4 * n_c)[2], dtype=torch.uint8, device=pl.dev)
+        cpkg = cd.deflate(comp, stream=cbuf)
+        cback = cd.inflate(cpkg)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(10):
+            cd.inflate(cpkg, out=cback)
+        torch.cuda.synchronize()
+        t_inf = (time.perf_counter() - t0) / 10
+        t0 = time.perf_counter()
+        for _ in range(10):
+            cd.deflate(comp, stream=cbuf)
+        torch.cuda.synchronize()
+        t_def = (time.perf_counter() - t0) / 10
+        codec["compacted_variant"] = {
+            "raw_bytes": 4 * n_c, "stream_bytes": cpkg.stream_bytes,
+            "ratio": round(4 * n_c / cpkg.stream_bytes, 3),
+            "round_trip_equal": bool(torch.equal(cback[:4 * n_c].view(torch.int32), comp.view(torch.int32))),
+            "deflate_call_us": round(t_def * 1e6, 1), "inflate_call_us": round(t_inf * 1e6, 1)}
+        del cbuf, cback, cpkg
         # the zlib library on one host core, on the first 64 MiB of the same bytes
         if cpu_leg:
             import zlib
