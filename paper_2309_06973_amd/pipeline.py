@@ -201,6 +201,22 @@ class Pipeline:
         return self.compact(sync)
 
 
+def deflate_portfolio(pl: "Pipeline", elems_w: Sequence[int], elems_v: Sequence[int], codec=None):
+    """Module 7 (Sec. III-E) on the rebuilt variants of the last portfolio() call: the
+    variants ordered by size (smallest first, as the paper's switcher walks them) and each
+    deflated (weights and per-channel vectors as one buffer).  elems_w / elems_v: the sizes
+    portfolio() returned.  Returns [(variant index, Package)]."""
+    codec = codec or Codec(device=pl.dev.index or 0, ctx=pl.ctx)
+    order = sorted(range(len(elems_w)), key=lambda k: (int(elems_w[k]) + int(elems_v[k]), k))
+    out = []
+    for k in order:
+        nw, nv = int(elems_w[k]), int(elems_v[k])
+        buf = torch.cat((pl.b_w_out[k * pl.cap_w:k * pl.cap_w + nw],
+                         pl.b_vecs_out[k * pl.cap_v:k * pl.cap_v + nv]))
+        out.append((k, codec.deflate(buf)))
+    return out
+
+
 class Package:
     """One deflated buffer: the DEFLATE stream and the side information for inflating it."""
     def __init__(self, stream, seg_off, sub_bits, n_bytes: int):

@@ -214,3 +214,27 @@ def test_codec_statuses_and_reuse():
                               pkg.seg_off, pkg.sub_bits)
     finally:
         codec.close()
+
+
+def test_portfolio_package_sorted_by_size_and_lossless():
+    """Module 7 on a whole portfolio: the rebuilt variants, smallest first, each deflated;
+    every package inflates (zlib and the library) to the oracle's rebuilt variant."""
+    from paper_2309_06973_amd.pipeline import Pipeline, deflate_portfolio
+    spec, w, v = synth.generate_config(3)
+    ps = [synth.prune_count(spec.n_prunable, s) for s in synth.config_sparsities(3)][2:12:3]
+    refs = O.prune_and_compact(w, v, spec.tensors, spec.vecs, spec.groups, ps)
+    pl = Pipeline(spec, w, v)
+    try:
+        pl.enable_batch(len(ps))
+        _, (rc, ot, ov, ew, ev) = pl.portfolio(ps, 0)
+        codec = Codec(ctx=pl.ctx)
+        pkgs = deflate_portfolio(pl, ew, ev, codec)
+        sizes = [int(ew[k]) + int(ev[k]) for k, _ in pkgs]
+        assert sizes == sorted(sizes) and sorted(k for k, _ in pkgs) == list(range(len(ps)))
+        for k, pkg in pkgs:
+            want = np.concatenate((refs[k].compacted.w, refs[k].compacted.v)).tobytes()
+            assert pkg.n_bytes == len(want)
+            assert zinflate(pkg.stream.cpu().numpy().tobytes()) == want
+            assert codec.inflate(pkg)[:len(want)].cpu().numpy().tobytes() == want
+    finally:
+        pl.close()
