@@ -476,6 +476,19 @@ int shifter_prune_fused_batch(shifter_ctx* ctx, const shifter_model* model, cons
                               float* d_w_out, uint64_t w_stride, uint8_t* d_mask,
                               uint64_t mask_stride, uint8_t* d_out_alive, uint8_t* d_in_alive,
                               shifter_threshold* h_thr);
+/* shifter_global_threshold in two halves, so that a portfolio step waits once: _begin
+ * enqueues the ranking of the K prune counts (the single pass over the arena where it
+ * applies) and returns; the caller enqueues the later steps, which read d_thr on the
+ * device, and waits for them; _end then waits for the stream (a formality by then), stores
+ * the K records in h_thr (or NULL) and says in *h_redone (or NULL) whether the single pass
+ * had to be replaced by the multi-pass select: if so, d_thr now holds the exact records
+ * and everything enqueued behind _begin must be repeated (rare: heavy ties).  One
+ * _begin at a time per context.  SHIFTER_ERR_NONFINITE from _end if a prunable weight
+ * is NaN. */
+int shifter_global_threshold_begin(shifter_ctx* ctx, const shifter_model* model,
+                                   const float* d_w, const uint64_t* h_n_prune, uint32_t K,
+                                   shifter_threshold* d_thr);
+int shifter_global_threshold_end(shifter_ctx* ctx, shifter_threshold* h_thr, int* h_redone);
 int shifter_apply_mask_batch(shifter_ctx* ctx, const shifter_model* model, const float* d_w,
                              const shifter_threshold* d_thr, uint32_t K, float* d_w_out,
                              uint64_t w_stride, uint8_t* d_mask, uint64_t mask_stride,

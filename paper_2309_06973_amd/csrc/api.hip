@@ -115,6 +115,7 @@ static void unbind(shifter_model* m) {
         if (p) (void)hipFree(p);
     if (b.host_stage) (void)hipHostFree(b.host_stage);
     if (b.host_spec) (void)hipHostFree(b.host_spec);
+    if (b.host_multi) (void)hipHostFree(b.host_multi);
     b = shifter_model::Bound();
 }
 
@@ -459,6 +460,8 @@ static int bind(shifter_ctx* ctx, const shifter_model* cm) {
     HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&b.host_stage), b.host_stage_bytes, hipHostMallocDefault));
     HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&b.host_spec),
                                sizeof(SpecState), hipHostMallocDefault));
+    HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&b.host_multi),
+                               64 + sizeof(shifter_threshold) * MAXK, hipHostMallocDefault));
     return SHIFTER_OK;
 }
 
@@ -589,6 +592,106 @@ extern "C" int shifter_global_threshold(shifter_ctx* ctx, const shifter_model* m
         if (nan_seen)
             return fail(ctx, SHIFTER_ERR_NONFINITE, "global_threshold: NaN among the prunable weights");
     }
+    return SHIFTER_OK;
+}
+
+// Enqueues the read-back of a ranking's outcome (a status word, then the K records) into
+// the model's pinned buffer.
+static int rank_result_enqueue(shifter_ctx* ctx, const shifter_model* model, const uint32_t* d_status,
+                               const shifter_threshold* d_thr, uint32_t K) {
+    uint8_t* st = model->b.host_multi;
+    HIP_TRY(ctx, hipMemcpyAsync(st, d_status, sizeof(uint32_t), hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipMemcpyAsync(st + 64, d_thr, sizeof(shifter_threshold) * K, hipMemcpyDeviceToHost, ctx->stream));
+    return SHIFTER_OK;
+}
+
+extern "C" int shifter_global_threshold_begin(shifter_ctx* ctx, const shifter_model* model,
+                                              const float* d_w, const uint64_t* h_n_prune, uint32_t K,
+                                              shifter_threshold* d_thr) {
+    int rc = enter(ctx, model, "global_threshold_begin");
+    if (rc) return rc;
+    if (ctx->pending_rank.active)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG,
+                    "global_threshold_begin: the previous one has not been collected (global_threshold_end)");
+    if (!d_w || !h_n_prune || !d_thr)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "global_threshold_begin: NULL pointer argument");
+    if (misaligned(d_w, 16) || misaligned(d_thr, 8))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "global_threshold_begin: d_w must be 16-byte aligned");
+    if (K == 0 || K > MAXK)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "global_threshold_begin: K must be in [1, SHIFTER_MAX_VARIANTS]");
+    auto& pr = ctx->pending_rank;
+    memset(&pr.pc, 0, sizeof pr.pc);
+    for (uint32_t k = 0; k < K; ++k) {
+        if (h_n_prune[k] > model->info.n_prunable)
+            return fail(ctx, SHIFTER_ERR_INVALID_ARG, "global_threshold_begin: prune count exceeds N");
+        pr.pc.p[k] = h_n_prune[k];
+    }
+    uint32_t idx[MAXK], k_eff = 0;
+    uint64_t zero_mask = 0;
+    for (uint32_t k = 0; k < K; ++k) {
+        if (pr.pc.p[k] == 0) zero_mask |= 1ull << k; else idx[k_eff++] = k;
+    }
+    pr.single_pass = ctx->select_path == 0 && k_eff <= SPEC_MULTI_MAXK;
+    if (pr.single_pass) {
+        PruneCounts sp;
+        MultiPerm perm;
+        memset(&sp, 0, sizeof sp);
+        memset(&perm, 0, sizeof perm);
+        std::stable_sort(idx, idx + k_eff, [&](uint32_t a, uint32_t b) { return pr.pc.p[a] < pr.pc.p[b]; });
+        for (uint32_t i = 0; i < k_eff; ++i) { sp.p[i] = pr.pc.p[idx[i]]; perm.v[i] = idx[i]; }
+        launch_spec_multi(ctx, model, d_w, sp, perm, k_eff, zero_mask, d_thr, nullptr);
+        if ((rc = after_launch(ctx, "global_threshold_begin"))) return rc;
+        if ((rc = rank_result_enqueue(ctx, model, &model->b.multi->status, d_thr, K))) return rc;
+    } else {
+        launch_select(ctx, model, d_w, pr.pc, K, d_thr);
+        if ((rc = after_launch(ctx, "global_threshold_begin"))) return rc;
+        if ((rc = rank_result_enqueue(ctx, model, &model->b.sel->nan_seen, d_thr, K))) return rc;
+    }
+    pr.active = true;
+    pr.model = model;
+    pr.d_w = d_w;
+    pr.k = K;
+    pr.d_thr = d_thr;
+    return SHIFTER_OK;
+}
+
+extern "C" int shifter_global_threshold_end(shifter_ctx* ctx, shifter_threshold* h_thr, int* h_redone) {
+    if (!ctx) return fail(nullptr, SHIFTER_ERR_INVALID_ARG, "global_threshold_end: ctx is NULL");
+    auto& pr = ctx->pending_rank;
+    if (!pr.active)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "global_threshold_end: nothing to collect");
+    pr.active = false;
+    if (h_redone) *h_redone = 0;
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    const shifter_model* model = pr.model;
+    uint8_t* st = model->b.host_multi;
+    uint32_t status;
+    memcpy(&status, st, sizeof status);
+    if (pr.single_pass) {
+        if (status & 2u)
+            return fail(ctx, SHIFTER_ERR_NONFINITE, "global_threshold_end: NaN among the prunable weights");
+        ctx->last_path = (status & 1u) ? 2 : 1;
+        if (status & 1u) {
+            // the single pass could not decide: the multi-pass select, and the caller repeats
+            // what it had enqueued behind the ranking
+            if (ctx->margin_sigmas < 64.0) ctx->margin_sigmas *= 2.0;
+            launch_select(ctx, model, pr.d_w, pr.pc, pr.k, pr.d_thr);
+            int rc = after_launch(ctx, "global_threshold_end");
+            if (rc) return rc;
+            if ((rc = rank_result_enqueue(ctx, model, &model->b.sel->nan_seen, pr.d_thr, pr.k))) return rc;
+            HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+            memcpy(&status, st, sizeof status);
+            if (status)
+                return fail(ctx, SHIFTER_ERR_NONFINITE, "global_threshold_end: NaN among the prunable weights");
+            if (h_redone) *h_redone = 1;
+        }
+    } else {
+        ctx->last_path = 2;
+        if (status)
+            return fail(ctx, SHIFTER_ERR_NONFINITE, "global_threshold_end: NaN among the prunable weights");
+    }
+    if (h_thr) memcpy(h_thr, st + 64, sizeof(shifter_threshold) * pr.k);
     return SHIFTER_OK;
 }
 

@@ -230,6 +230,7 @@ struct shifter_model {
         uint32_t* multi_seg_cnt = nullptr;    // SPEC_MULTI_MAXK * SPEC_SUB
         uint8_t* host_stage = nullptr;        // pinned, for small read-backs
         uint8_t* host_spec = nullptr;         // pinned: outcome of a deferred shifter_prune_fused
+        uint8_t* host_multi = nullptr;        // pinned: outcome of shifter_global_threshold_begin
         size_t host_stage_bytes = 0;
     } b;
 };
@@ -267,6 +268,16 @@ struct shifter_ctx {
         uint8_t* d_out_alive = nullptr;
         uint8_t* d_in_alive = nullptr;
     } pending;
+    // a shifter_global_threshold_begin whose outcome has not been collected yet
+    struct PendingRank {
+        bool active = false;
+        const shifter_model* model = nullptr;
+        const float* d_w = nullptr;
+        shifter::PruneCounts pc{};
+        uint32_t k = 0;
+        shifter_threshold* d_thr = nullptr;
+        bool single_pass = false;
+    } pending_rank;
 };
 
 namespace shifter {

@@ -163,32 +163,46 @@ class Pipeline:
         k = len(n_prune)
         assert k == self.bk
         self.n_thr = k
+        recs = None
         if fused is None:
             fused = self.model.info.w_extent * 4 > (192 << 20)
+        def later_steps():
+            S.shifter_propagate_groups_batch(self.ctx, self.model, self.b_out_alive, k, flags,
+                                             self.b_group_alive, self.b_index_map, self.b_keep,
+                                             self.b_new_width, sync=False)
+            if from_sparse:
+                return S.shifter_compact_batch(self.ctx, self.model, self.b_w_sparse,
+                                               self.w_stride, self.d_vecs, self.b_keep,
+                                               self.b_new_width, k, self.b_w_out, self.cap_w,
+                                               self.b_vecs_out, self.cap_v, sync=sync)
+            return S.shifter_compact_batch_masked(self.ctx, self.model, self.d_w, self.d_thr,
+                                                  self.d_vecs, self.b_keep, self.b_new_width, k,
+                                                  self.b_w_out, self.cap_w, self.b_vecs_out,
+                                                  self.cap_v, sync=sync)
+
         if fused:
             recs = S.shifter_prune_fused_batch(
                 self.ctx, self.model, self.d_w, n_prune, self.d_thr,
                 self.b_w_sparse if sparse_arenas else None, self.w_stride, self.b_mask,
                 self.m_stride, self.b_out_alive, self.b_in_alive if with_in_alive else None)
+            out = later_steps()
         else:
-            recs = self.global_threshold(n_prune, sync=True)
-            S.shifter_apply_mask_batch(self.ctx, self.model, self.d_w, self.d_thr, k,
-                                       self.b_w_sparse if sparse_arenas else None,
-                                       self.w_stride, self.b_mask, self.m_stride, self.b_out_alive,
-                                       self.b_in_alive if with_in_alive else None)
-        S.shifter_propagate_groups_batch(self.ctx, self.model, self.b_out_alive, k, flags,
-                                         self.b_group_alive, self.b_index_map, self.b_keep,
-                                         self.b_new_width, sync=False)
-        if from_sparse:
-            out = S.shifter_compact_batch(self.ctx, self.model, self.b_w_sparse, self.w_stride,
-                                          self.d_vecs, self.b_keep, self.b_new_width, k,
-                                          self.b_w_out, self.cap_w, self.b_vecs_out, self.cap_v,
-                                          sync=sync)
-        else:
-            out = S.shifter_compact_batch_masked(self.ctx, self.model, self.d_w, self.d_thr,
-                                                 self.d_vecs, self.b_keep, self.b_new_width, k,
-                                                 self.b_w_out, self.cap_w, self.b_vecs_out,
-                                                 self.cap_v, sync=sync)
+            # the ranking is enqueued and everything else behind it: one wait for the whole
+            # step; in the rare case that the single pass could not decide, the later steps
+            # are repeated on the exact records
+            S.shifter_global_threshold_begin(self.ctx, self.model, self.d_w, n_prune, self.d_thr)
+            while True:
+                S.shifter_apply_mask_batch(self.ctx, self.model, self.d_w, self.d_thr, k,
+                                           self.b_w_sparse if sparse_arenas else None,
+                                           self.w_stride, self.b_mask, self.m_stride,
+                                           self.b_out_alive,
+                                           self.b_in_alive if with_in_alive else None)
+                out = later_steps()
+                if recs is not None:
+                    break
+                recs, redone = S.shifter_global_threshold_end(self.ctx)
+                if not redone:
+                    break
         return recs, out
 
     def variant(self, k: int = 0, flags: int = 0, fused_scan: bool = True,

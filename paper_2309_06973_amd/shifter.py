@@ -77,6 +77,9 @@ EXPORTS = {
     "shifter_global_threshold": [C.c_void_p, C.c_void_p, C.c_void_p,
                                  C.POINTER(C.c_uint64), C.c_uint32, C.c_void_p,
                                  C.POINTER(Threshold)],
+    "shifter_global_threshold_begin": [C.c_void_p, C.c_void_p, C.c_void_p,
+                                       C.POINTER(C.c_uint64), C.c_uint32, C.c_void_p],
+    "shifter_global_threshold_end": [C.c_void_p, C.POINTER(Threshold), C.POINTER(C.c_int)],
     "shifter_set_select_path": [C.c_void_p, C.c_int],
     "shifter_set_margin_sigmas": [C.c_void_p, C.c_double],
     "shifter_get_select_stats": [C.c_void_p, C.POINTER(C.c_uint64)],
@@ -368,6 +371,23 @@ def shifter_inflate(ctx: Context, d_stream, stream_bytes: int, d_seg_off, d_sub_
     _check(load_library().shifter_inflate(ctx.handle, _ptr(d_stream), stream_bytes,
                                           _ptr(d_seg_off), _ptr(d_sub_bits), n_bytes,
                                           _ptr(d_out)), ctx.handle)
+
+
+def shifter_global_threshold_begin(ctx: Context, model: Model, d_w, n_prune, d_thr) -> None:
+    k = len(n_prune)
+    arr = (C.c_uint64 * k)(*[int(p) for p in n_prune])
+    _check(load_library().shifter_global_threshold_begin(ctx.handle, model.handle, _ptr(d_w), arr,
+                                                         k, _ptr(d_thr)), ctx.handle)
+    ctx._rank_k = k
+
+
+def shifter_global_threshold_end(ctx: Context):
+    """(records, redone) of the last shifter_global_threshold_begin."""
+    k = ctx._rank_k
+    h = (Threshold * k)()
+    redone = C.c_int()
+    _check(load_library().shifter_global_threshold_end(ctx.handle, h, C.byref(redone)), ctx.handle)
+    return list(h), bool(redone.value)
 
 
 def shifter_kernel_scan(ctx: Context, model: Model, d_w_sparse, d_kernel_nz) -> None:

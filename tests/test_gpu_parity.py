@@ -524,6 +524,47 @@ def test_deferred_fused_pass_and_its_redo():
 
 
 @pytest.mark.gpu
+def test_deferred_portfolio_ranking_and_its_redo():
+    """A portfolio step with one wait: the ranking's two halves around the later steps.  On
+    continuous weights the single pass decides; on an arena of ties it cannot, the multi-pass
+    select replaces it and the later steps are repeated: either way the oracle's results."""
+    spec, w, v = synth.generate_config(3)
+    n = spec.n_prunable
+    ps = [synth.prune_count(n, s) for s in (0.5, 0.8, 0.9, 0.0)]
+    tied = np.where(w != 0, np.sign(w) * 0.25, w).astype(np.float32)
+    for arena, expect_redone in ((w, False), (tied, True)):
+        refs = O.prune_and_compact(arena, v, spec.tensors, spec.vecs, spec.groups, ps)
+        a = np.abs(O.gather_prunable(arena, spec.tensors))
+        pl = Pipeline(spec, arena, v)
+        try:
+            pl.enable_batch(len(ps))
+            S.shifter_global_threshold_begin(pl.ctx, pl.model, pl.d_w, ps, pl.d_thr)
+            with pytest.raises(S.ShifterError):          # one at a time
+                S.shifter_global_threshold_begin(pl.ctx, pl.model, pl.d_w, ps, pl.d_thr)
+            recs, redone = S.shifter_global_threshold_end(pl.ctx)
+            assert redone == expect_redone
+            assert S.shifter_get_select_stats(pl.ctx)["path"] == (2 if expect_redone else 1)
+            for k in range(len(ps)):
+                check_threshold(recs[k], refs[k].sel, a)
+            with pytest.raises(S.ShifterError):          # nothing left to collect
+                S.shifter_global_threshold_end(pl.ctx)
+            # the whole step through the wrapper (it repeats the later steps when needed)
+            recs, (rc, ots, ovs, ews, evs) = pl.portfolio(ps, 0, fused=False)
+            torch.cuda.synchronize()
+            for k in range(len(ps)):
+                ref = refs[k]
+                check_threshold(recs[k], ref.sel, a)
+                assert np.array_equal(pl.b_mask[k * pl.m_stride:k * pl.m_stride + n].cpu().numpy(), ref.mask)
+                ws = pl.b_w_sparse[k * pl.w_stride:k * pl.w_stride + ref.w_sparse.size].cpu().numpy()
+                assert np.array_equal(bits(ws), bits(ref.w_sparse))
+                assert ews[k] == ref.compacted.w.size and evs[k] == ref.compacted.v.size
+                wo = pl.b_w_out[k * pl.cap_w:k * pl.cap_w + ews[k]].cpu().numpy()
+                assert np.array_equal(bits(wo), bits(ref.compacted.w))
+        finally:
+            pl.close()
+
+
+@pytest.mark.gpu
 def test_model_without_prunable_tensors():
     """N = 0: nothing can be removed; every step still runs and reproduces its input."""
     spec, w, v = synth.generate_config(1)
