@@ -166,16 +166,19 @@ int shifter_model_get_layout(const shifter_model* model, uint64_t* h_out_flag_of
  *   h_thr      host, K records, or NULL.  Non-NULL: the call waits for the stream,
  *              copies the records and reports SHIFTER_ERR_NONFINITE if a prunable
  *              weight is NaN.  NULL: no wait and no NaN report (a NaN compares above
- *              +inf; the records are then meaningless).  A waiting call with K = 1 may
- *              use the single-pass selection (see shifter_set_select_path). */
+ *              +inf; the records are then meaningless).  A waiting call may use the
+ *              single-pass selection (see shifter_set_select_path). */
 int shifter_global_threshold(shifter_ctx* ctx, const shifter_model* model,
                              const float* d_w, const uint64_t* h_n_prune, uint32_t K,
                              shifter_threshold* d_thr, shifter_threshold* h_thr);
 
 /* Which selection algorithm shifter_global_threshold and shifter_prune_fused may use:
- * 0 (default) the single-pass selection where it applies (one prune count, waiting
- * call), with the multi-pass radix select as its fall-back; 1 the multi-pass radix
- * select only.  Both give the same records. */
+ * 0 (default) the single-pass selection where it applies (waiting or two-call form,
+ * at most 32 prune counts above zero), with the multi-pass radix select as its
+ * fall-back (taken when the pass's own check fails: a sample that misjudged a quantile,
+ * tens of thousands of weights equal to a threshold, or - for several prune counts -
+ * an index space beyond about 10^9 weights); 1 the multi-pass radix select only.  Both
+ * give the same records. */
 int shifter_set_select_path(shifter_ctx* ctx, int path);
 
 /* Half-width of the key interval the single-pass selection predicts from its sample,

@@ -199,6 +199,7 @@ extern "C" int shifter_model_create(const shifter_tensor_desc* tensors, uint32_t
         const uint64_t numel = (uint64_t)t.out_ch * t.in_ch * khw;
         if (khw >= (1ull << 32) || numel >= (1ull << 32) - 2 * TILE || khw * t.in_mult >= (1ull << 32))
             return bad("tensor of 2^32 or more elements", i);
+        if (t.offset >= (1ull << 62)) return bad("tensor offset beyond 2^62", i);
         DevTensor& d = m->dt[i];
         d.offset = t.offset;
         d.gbase = t.prunable ? gbase : 0;
@@ -272,6 +273,7 @@ extern "C" int shifter_model_create(const shifter_tensor_desc* tensors, uint32_t
         spans.push_back({t.offset, t.offset + numel});
         if (so >= (1ull << 32) || si >= (1ull << 32) || tiles >= (1ull << 31))
             return bad("model too large for 32-bit flag or tile indices", i);
+        if (gbase >= (1ull << 32) - 1) return bad("prunable weights reach 2^32 - 1 (32-bit global index)", i);
     }
     m->tile_prefix.push_back((uint32_t)tiles);
     m->n_tiles = (uint32_t)tiles;
@@ -289,8 +291,14 @@ extern "C" int shifter_model_create(const shifter_tensor_desc* tensors, uint32_t
     m->n_ranked = (uint32_t)m->ranked_ids.size();
     // the single-pass selection samples one 16-weight sector per 1024 weights of every
     // sample_tile_stride-th tile (see spec_sample_kernel); its size is fixed by the
-    // descriptors.  N / 64 samples for models up to 164 M weights, at most 2.6 M beyond.
-    m->sample_tile_stride = (m->n_tiles + 39999u) / 40000u;   // 1 up to 164 M weights
+    // descriptors.  N / 64 samples for models up to 164 M weights; beyond that 40000
+    // tiles (2.6 M samples), and from 1.3 G weights on every 8th tile: the candidate
+    // interval is about N / sqrt(samples) weights wide, and the finishing passes hold a
+    // fixed number of them.
+    {
+        const uint32_t sampled = std::max(40000u, m->n_tiles / 8u);
+        m->sample_tile_stride = (m->n_tiles + sampled - 1) / sampled;   // 1 up to 164 M weights
+    }
     for (uint32_t tile = 0, ti = 0; tile < m->n_tiles; tile += m->sample_tile_stride) {
         while (m->tile_prefix[ti + 1] <= tile) ++ti;
         if (!tensors[ti].prunable) continue;
@@ -312,6 +320,7 @@ extern "C" int shifter_model_create(const shifter_tensor_desc* tensors, uint32_t
         const shifter_vec_desc& v = vecs[i];
         if (v.group < 0 || (uint32_t)v.group >= n_groups) return bad("vector group index out of range", i);
         if (groups[v.group].width != v.len) return bad("vector length differs from the width of its group", i);
+        if (v.offset >= (1ull << 62)) return bad("vector offset beyond 2^62", i);
         m->dv[i] = {v.offset, v.len, v.group};
         v_ext = std::max(v_ext, v.offset + v.len);
         v_el += v.len;
@@ -322,19 +331,26 @@ extern "C" int shifter_model_create(const shifter_tensor_desc* tensors, uint32_t
         if (spans[i].first < spans[i - 1].second) return bad("vectors overlap in the vector arena", (uint32_t)i);
 
     // consumers of each group, in tensor order
-    for (uint32_t g = 0; g < n_groups; ++g) {
-        m->cons_prefix.push_back((uint32_t)m->consumers.size());
-        for (uint32_t i = 0; i < n_tensors; ++i)
-            if ((uint32_t)tensors[i].in_group == g) m->consumers.push_back(i);
+    {
+        std::vector<uint32_t> at(n_groups + 1, 0);
+        for (uint32_t i = 0; i < n_tensors; ++i) ++at[tensors[i].in_group + 1];
+        for (uint32_t g = 0; g < n_groups; ++g) at[g + 1] += at[g];
+        m->cons_prefix.assign(at.begin(), at.end());
+        m->consumers.resize(n_tensors);
+        for (uint32_t i = 0; i < n_tensors; ++i) m->consumers[at[tensors[i].in_group]++] = i;
     }
-    m->cons_prefix.push_back((uint32_t)m->consumers.size());
     // producers of each group, in tensor order
-    for (uint32_t g = 0; g < n_groups; ++g) {
-        m->dg[g].prod_begin = (uint32_t)m->producers.size();
-        for (uint32_t i = 0; i < n_tensors; ++i)
-            if ((uint32_t)tensors[i].out_group == g) m->producers.push_back(i);
-        m->dg[g].prod_end = (uint32_t)m->producers.size();
-        m->dg[g].pad = 0;
+    {
+        std::vector<uint32_t> at(n_groups + 1, 0);
+        for (uint32_t i = 0; i < n_tensors; ++i) ++at[tensors[i].out_group + 1];
+        for (uint32_t g = 0; g < n_groups; ++g) at[g + 1] += at[g];
+        for (uint32_t g = 0; g < n_groups; ++g) {
+            m->dg[g].prod_begin = at[g];
+            m->dg[g].prod_end = at[g + 1];
+            m->dg[g].pad = 0;
+        }
+        m->producers.resize(n_tensors);
+        for (uint32_t i = 0; i < n_tensors; ++i) m->producers[at[tensors[i].out_group]++] = i;
     }
     shifter_model_info& inf = m->info;
     inf.n_prunable = gbase;
@@ -383,15 +399,24 @@ static int upload(shifter_ctx* ctx, T** dptr, const T* src, size_t n) {
     return SHIFTER_OK;
 }
 
-// Device tables and scratch of a model, created once per (model, context).
+static int bind_tables(shifter_ctx* ctx, shifter_model* m);
+
+// Device tables and scratch of a model, created once per (model, context).  A binding that
+// fails half way is taken down again, so that a later call starts from nothing.
 static int bind(shifter_ctx* ctx, const shifter_model* cm) {
     shifter_model* m = const_cast<shifter_model*>(cm);
     if (m->b.ctx == ctx) return SHIFTER_OK;
     unbind(m);
     HIP_TRY(ctx, hipSetDevice(ctx->device));
+    m->b.ctx = ctx;
+    m->b.device = ctx->device;
+    const int rc = bind_tables(ctx, m);
+    if (rc) unbind(m);
+    return rc;
+}
+
+static int bind_tables(shifter_ctx* ctx, shifter_model* m) {
     auto& b = m->b;
-    b.ctx = ctx;
-    b.device = ctx->device;
     int rc;
     const size_t n_t = m->t.size(), n_v = m->v.size();
     if ((rc = upload(ctx, &b.tens, m->dt.data(), n_t))) return rc;

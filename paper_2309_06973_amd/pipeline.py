@@ -13,8 +13,10 @@ from . import shifter as S
 
 
 class Pipeline:
-    def __init__(self, spec, w: np.ndarray, v: np.ndarray, device: int = 0,
+    def __init__(self, spec, w, v, device: int = 0,
                  max_variants: int = S.SHIFTER_MAX_VARIANTS):
+        """w, v: the fp32 weight and vector arenas, numpy arrays (copied to the device) or
+        float32 tensors already on it (used as they are)."""
         if not torch.cuda.is_available():
             raise RuntimeError("no ROCm device visible: the prune-and-compact pass has no "
                                "CPU path")
@@ -24,10 +26,12 @@ class Pipeline:
         self.ctx = S.shifter_create(device, torch.cuda.current_stream().cuda_stream)
         self.model = S.shifter_model_create(spec.tensors, spec.vecs, spec.groups)
         info = self.model.info
-        assert w.size >= info.w_extent and v.size >= info.v_extent
         u8 = dict(dtype=torch.uint8, device=self.dev)
-        self.d_w = torch.from_numpy(w).to(self.dev)
-        self.d_vecs = torch.from_numpy(v).to(self.dev)
+        self.d_w = w if isinstance(w, torch.Tensor) else torch.from_numpy(w).to(self.dev)
+        self.d_vecs = v if isinstance(v, torch.Tensor) else torch.from_numpy(v).to(self.dev)
+        for a, need in ((self.d_w, info.w_extent), (self.d_vecs, info.v_extent)):
+            assert a.dtype == torch.float32 and a.device == self.dev and a.is_contiguous()
+            assert a.numel() >= need
         self.d_w_sparse = torch.empty_like(self.d_w)
         self.d_mask = torch.empty(max(info.n_prunable, 4), **u8)
         self.d_out_alive = torch.empty(info.sum_out_ch, **u8)

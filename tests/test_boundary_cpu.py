@@ -99,6 +99,30 @@ def test_model_validation_errors(lib):
     assert e.value.code == S.SHIFTER_ERR_INVALID_ARG
 
 
+def test_model_size_limits(lib):
+    """The global index is 32 bits wide: N stops short of 2^32 - 1; arena offsets stop at
+    2^62 so that offset + size cannot wrap."""
+    T, G = synth.TensorDesc, synth.GroupDesc
+    groups = [G(1 << 15, 1), G(1 << 16, 0), G(1 << 15, 1)]
+    half = 1 << 31                                  # 2^15 x 2^16 weights per tensor
+    one = [T(0, 1 << 16, 1 << 15, 1, 1, 1, 1, 0, 1)]
+    m = S.shifter_model_create(one, [], groups)
+    assert m.info.n_prunable == half
+    S.shifter_model_destroy(m)
+    two = one + [T(half, 1 << 15, 1 << 16, 1, 1, 1, 2, 1, 1)]
+    with pytest.raises(S.ShifterError) as e:
+        S.shifter_model_create(two, [], groups)
+    assert e.value.code == S.SHIFTER_ERR_BAD_MODEL and "2^32 - 1" in str(e.value)
+    two[1].prunable = 0                             # not ranked: only the arena grows
+    m = S.shifter_model_create(two, [], groups)
+    assert m.info.n_prunable == half and m.info.w_elems == 2 * half
+    S.shifter_model_destroy(m)
+    far = [T(1 << 62, 1 << 16, 1 << 15, 1, 1, 1, 1, 0, 1)]
+    with pytest.raises(S.ShifterError) as e:
+        S.shifter_model_create(far, [], groups)
+    assert e.value.code == S.SHIFTER_ERR_BAD_MODEL and "2^62" in str(e.value)
+
+
 def test_no_device_is_an_error_not_a_fallback(lib):
     import torch
     if torch.cuda.is_available():

@@ -1,0 +1,229 @@
+"""The largest index space the interface admits: N = 2^32 - 4097 prunable weights (the
+global index is 32 bits wide and N must stay below 2^32 - 1), 17 GB of fp32.
+
+Nothing of this size is sorted on the host.  The threshold is checked through the
+counting definition of the P-th smallest (|w|, index) pair, and every element of the
+mask, the sparse arena, the alive flags and the rebuilt tensors against the plain
+definition of each step (Sec. III-C and III-D, Algorithms 1 and 2) written out in torch
+tensor operations, tensor by tensor; the prune plan between the flags and the rebuild is
+the oracle's.  One prune count is chosen so that the threshold falls inside a run of
+several hundred thousand equal magnitudes, where the order is by index alone (more ties
+than the single pass holds: the multi-pass select decides, as documented); the others
+have the single pass decide."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import shifter_oracle as O
+from paper_2309_06973_amd import shifter as S
+from paper_2309_06973_amd import synth
+from paper_2309_06973_amd.pipeline import Pipeline
+
+pytestmark = pytest.mark.gpu
+
+T, V, G = synth.TensorDesc, synth.VecDesc, synth.GroupDesc
+KEY_TWO = 0x40000000                      # bit pattern of 2.0f
+
+
+def build_spec():
+    groups = [G(8192, 1), G(8192, 0), G(8192, 0), G(32768, 0), G(32768, 0), G(28671, 0), G(1, 1)]
+    #          out    in     kh kw in_mult out_group in_group
+    shapes = [(8192, 8192, 3, 3, 1, 1, 0),        # two wide 3x3 convolutions
+              (8192, 8192, 3, 3, 1, 2, 1),
+              (32768, 32768, 1, 1, 4, 3, 2),      # flatten (4 features per channel) + linear
+              (32768, 32768, 1, 1, 1, 4, 3),
+              (28671, 32768, 1, 1, 1, 5, 4),
+              (1, 28671, 1, 1, 1, 6, 5)]
+    tensors, off = [], 0
+    for o, i, kh, kw, m, go, gi in shapes:
+        tensors.append(T(off, o, i, kh, kw, m, go, gi, 1))
+        off += o * i * kh * kw
+    vecs, voff = [], 0
+    for g in (1, 2, 3, 4, 5):
+        vecs.append(V(voff, groups[g].width, g))
+        voff += groups[g].width
+    spec = synth.NetSpec("max-size", tensors, vecs, groups)
+    spec.w_elems, spec.v_elems = off, voff
+    assert off == (1 << 32) - 4097
+    return spec
+
+
+def keys(x):
+    return x.view(torch.int32) & 0x7fffffff            # non-negative: int32 order is key order
+
+
+@pytest.fixture(scope="module")
+def big():
+    spec = build_spec()
+    dev = torch.device("cuda", 0)
+    gen = torch.Generator(device=dev).manual_seed(20230913)
+    w = torch.empty(spec.w_elems, dtype=torch.float32, device=dev)
+    for ti, t in enumerate(spec.tensors):
+        x = w[t.offset:t.offset + t.numel]
+        x.normal_(generator=gen)
+        x3 = x.view(t.out_ch, t.in_ch, t.kh * t.kw)
+        x3[(ti + 1) % 6::6] *= 1e-4                     # filters that no sweep leaves alive
+        x3[:, 3::7] *= 1e-4                             # input features likewise
+    t3 = spec.tensors[3]
+    q = w[t3.offset + 4096 * 5:t3.offset + 4096 * 5 + (1 << 26)]
+    q.copy_(torch.round(q * 8) / 8)                     # ties, at 2.0 and at zero among others
+    v = torch.empty(max(spec.v_elems, 4), dtype=torch.float32, device=dev).normal_(generator=gen)
+    n_less = sum(int((keys(w[t.offset:t.offset + t.numel]) < KEY_TWO).sum()) for t in spec.tensors)
+    n_eq = sum(int((keys(w[t.offset:t.offset + t.numel]) == KEY_TWO).sum()) for t in spec.tensors)
+    assert n_eq > 100000
+    p_tie = n_less + n_eq // 3 + 1                      # the cut falls inside the run of 2.0s
+    yield spec, w, v, p_tie
+    del w, v
+    torch.cuda.empty_cache()
+
+
+def check_record(spec, w, rec, p):
+    """Counting definition of the P-th smallest pair; returns (t_key, g_cut)."""
+    tk = int(rec.t_key)
+    less = [int((keys(w[t.offset:t.offset + t.numel]) < tk).sum()) for t in spec.tensors]
+    eq = [int((keys(w[t.offset:t.offset + t.numel]) == tk).sum()) for t in spec.tensors]
+    assert rec.n_prune == p and rec.n_less == sum(less) and rec.n_equal == sum(eq)
+    assert sum(less) < p <= sum(less) + sum(eq)
+    r, gbase = p - sum(less), 0                         # the r-th equal weight, by index
+    for t, e in zip(spec.tensors, eq):
+        if r <= e:
+            where = torch.nonzero(keys(w[t.offset:t.offset + t.numel]) == tk).view(-1)
+            assert rec.g_cut == gbase + int(where[r - 1])
+            break
+        r -= e
+        gbase += t.numel
+    assert rec.cut == ((tk << 32) | int(rec.g_cut)) + 1
+    return tk, int(rec.g_cut)
+
+
+def removed_of(w, t, gbase, tk, g_cut):
+    k = keys(w[t.offset:t.offset + t.numel])
+    g = torch.arange(gbase, gbase + t.numel, dtype=torch.int64, device=w.device)
+    return (k < tk) | ((k == tk) & (g <= g_cut))
+
+
+def check_variant(spec, w, v, tk, g_cut, p, d_mask, d_ws, d_out_alive, d_in_alive, d_keep,
+                  d_new_width, d_w_out, d_v_out, ot, ew, ev, group_off):
+    n_removed, gbase, so, si = 0, 0, 0, 0
+    out_alive = []
+    for t in spec.tensors:
+        rem = removed_of(w, t, gbase, tk, g_cut)
+        n_removed += int(rem.sum())
+        assert torch.equal(d_mask[gbase:gbase + t.numel], (~rem).to(torch.uint8))
+        ws = torch.where(rem, torch.zeros((), device=w.device), w[t.offset:t.offset + t.numel])
+        assert torch.equal(d_ws[t.offset:t.offset + t.numel].view(torch.int32), ws.view(torch.int32))
+        nz = (ws.view(t.out_ch, t.in_ch, t.kh * t.kw) != 0).any(dim=2)
+        oa, ia = nz.any(dim=1).to(torch.uint8), nz.any(dim=0).to(torch.uint8)
+        assert torch.equal(d_out_alive[so:so + t.out_ch], oa)
+        assert torch.equal(d_in_alive[si:si + t.in_ch], ia)
+        out_alive.append(oa.cpu().numpy())
+        gbase, so, si = gbase + t.numel, so + t.out_ch, si + t.in_ch
+        del rem, ws, nz
+    assert n_removed == p
+    plan = O.propagate_groups(spec.tensors, spec.groups, out_alive)
+    assert np.array_equal(d_new_width.cpu().numpy().view(np.uint32), plan.new_width)
+    kp = d_keep.cpu().numpy().view(np.uint32)
+    for gi in range(len(spec.groups)):
+        assert np.array_equal(kp[group_off[gi]:group_off[gi] + plan.keep[gi].size], plan.keep[gi])
+    assert 0 < int(plan.new_width[3]) < spec.groups[3].width        # channels did go
+    off = 0
+    for t, d in zip(spec.tensors, ot):
+        ko = torch.from_numpy(plan.keep[t.out_group].astype(np.int64)).to(w.device)
+        ki = torch.from_numpy(plan.keep[t.in_group].astype(np.int64)).to(w.device)
+        cols = (ki[:, None] * t.in_mult + torch.arange(t.in_mult, device=w.device)[None, :]).view(-1)
+        x = d_ws[t.offset:t.offset + t.numel].view(t.out_ch, t.in_ch, t.kh * t.kw)
+        want = x.index_select(0, ko).index_select(1, cols).reshape(-1)
+        assert (d.offset, d.out_ch, d.in_ch, d.kh, d.kw) == (off, ko.numel(), cols.numel(), t.kh, t.kw)
+        assert torch.equal(d_w_out[off:off + want.numel()].view(torch.int32), want.view(torch.int32))
+        off += want.numel()
+        del x, want
+    assert ew == off
+    voff = 0
+    for vd in spec.vecs:
+        k = torch.from_numpy(plan.keep[vd.group].astype(np.int64)).to(w.device)
+        want = v[vd.offset:vd.offset + vd.length].index_select(0, k)
+        assert torch.equal(d_v_out[voff:voff + k.numel()].view(torch.int32), want.view(torch.int32))
+        voff += k.numel()
+    assert ev == voff
+
+
+def test_single_sweep_at_the_largest_index_space(big):
+    spec, w, v, p_tie = big
+    n = spec.n_prunable
+    pl = Pipeline(spec, w, v, max_variants=2)
+    try:
+        assert pl.model.info.n_prunable == (1 << 32) - 4097
+        for p, path in ((synth.prune_count(n, 0.95), 1), (p_tie, 2)):
+            rec, (rc, ot, ov, ew, ev) = pl.single(p)
+            torch.cuda.synchronize()
+            assert rc == S.SHIFTER_OK
+            assert S.shifter_get_select_stats(pl.ctx)["path"] == path
+            tk, g_cut = check_record(spec, w, rec, p)
+            assert (tk == KEY_TWO) == (p == p_tie)
+            check_variant(spec, w, v, tk, g_cut, p, pl.d_mask, pl.d_w_sparse, pl.d_out_alive,
+                          pl.d_in_alive, pl.d_keep, pl.d_new_width, pl.d_w_out, pl.d_vecs_out,
+                          ot, ew, ev, pl.model.group_off)
+        # the multi-pass radix select alone gives the same records, also next to the far end
+        ps = [p, n - 3]
+        S.shifter_set_select_path(pl.ctx, 1)
+        recs = pl.global_threshold(ps)
+        S.shifter_set_select_path(pl.ctx, 0)
+        for name, _ in S.Threshold._fields_:
+            assert getattr(recs[0], name) == getattr(rec, name)
+        check_record(spec, w, recs[1], n - 3)
+    finally:
+        pl.close()
+
+
+def test_portfolio_at_the_largest_index_space(big):
+    spec, w, v, p_tie = big
+    n = spec.n_prunable
+    ps = [n // 2, synth.prune_count(n, 0.95)]
+    pl = Pipeline(spec, w, v, max_variants=2)
+    try:
+        del pl.d_w_sparse, pl.d_w_out, pl.d_mask                   # single-variant buffers: unused here
+        pl.enable_batch(2)
+        info = pl.model.info
+        so, si, ng, sg = info.sum_out_ch, info.sum_in_ch, info.n_groups, info.sum_group_width
+        recs, (rc, ots, ovs, ews, evs) = pl.portfolio(ps, fused=True)
+        torch.cuda.synchronize()
+        # (at this size the K-rank single pass hands over to the multi-pass select: a bin
+        # of its sample histogram alone holds more weights than its finishing passes do)
+        assert S.shifter_get_select_stats(pl.ctx)["path"] == 2
+        for k in range(2):
+            tk, g_cut = check_record(spec, w, recs[k], ps[k])
+            check_variant(spec, w, v, tk, g_cut, ps[k],
+                          pl.b_mask[k * pl.m_stride:], pl.b_w_sparse[k * pl.w_stride:],
+                          pl.b_out_alive[k * so:(k + 1) * so], pl.b_in_alive[k * si:(k + 1) * si],
+                          pl.b_keep[k * sg:(k + 1) * sg], pl.b_new_width[k * ng:(k + 1) * ng],
+                          pl.b_w_out[k * pl.cap_w:], pl.b_vecs_out[k * pl.cap_v:],
+                          ots[k * len(spec.tensors):(k + 1) * len(spec.tensors)], ews[k], evs[k],
+                          pl.model.group_off)
+        # the two-call form (ranking, then the batched mask pass): same bytes everywhere
+        first = [x.clone() for x in (pl.b_mask, pl.b_out_alive, pl.b_in_alive, pl.b_keep,
+                                      pl.b_new_width)]
+        rebuilt = [pl.b_w_out[k * pl.cap_w:k * pl.cap_w + ews[k]].clone() for k in range(2)]
+        pl.b_mask.zero_(); pl.b_w_out.zero_(); pl.b_out_alive.zero_()
+        recs2, (rc, ots2, ovs2, ews2, evs2) = pl.portfolio(ps, fused=False, sparse_arenas=False)
+        torch.cuda.synchronize()
+        for a, b in zip(recs, recs2):
+            for name, _ in S.Threshold._fields_:
+                assert getattr(a, name) == getattr(b, name)
+        assert list(ews2) == list(ews) and list(evs2) == list(evs)
+        for a, b in zip(first, (pl.b_mask, pl.b_out_alive, pl.b_in_alive, pl.b_keep, pl.b_new_width)):
+            assert torch.equal(a, b)
+        for k in range(2):
+            assert torch.equal(rebuilt[k].view(torch.int32),
+                               pl.b_w_out[k * pl.cap_w:k * pl.cap_w + ews[k]].view(torch.int32))
+        # a portfolio whose ranking the single pass cannot decide (the run of ties)
+        del first, rebuilt
+        ps = [p_tie, n - 3]
+        recs, _ = pl.portfolio(ps, fused=True)
+        torch.cuda.synchronize()
+        assert S.shifter_get_select_stats(pl.ctx)["path"] == 2
+        for k in range(2):
+            check_record(spec, w, recs[k], ps[k])
+            kept = int(pl.b_mask[k * pl.m_stride:k * pl.m_stride + n].sum(dtype=torch.int64))
+            assert kept == n - ps[k]
+    finally:
+        pl.close()
