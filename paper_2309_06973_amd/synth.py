@@ -431,3 +431,83 @@ def adversarial_arena(kind: str, n: int, seed: int = 0) -> np.ndarray:
 
 ADVERSARIAL_KINDS = ("ramp", "ramp_desc_signed", "all_equal", "all_zero", "half_zero",
                      "quantised", "denormal", "inf_negzero", "gauss")
+
+
+# ---------------------------------------------------------------------------
+# Random networks: arbitrary group graphs for parity tests (not timed).
+# ---------------------------------------------------------------------------
+
+def random_spec(seed: int, max_weights: int = 250_000) -> NetSpec:
+    """A random valid network description: tensors reading and writing a random graph of
+    channel groups (several producers per group as residual adds make them, several
+    consumers, groups nobody reads), kernel shapes from 1x1 to long thin ones, flatten
+    multipliers, non-prunable tensors, gaps and odd offsets in both arenas, vectors on any
+    group.  No forward semantics (``ops`` stays empty)."""
+    rng = np.random.Generator(np.random.Philox(SEED_BASE + 1000 + seed))
+    s = NetSpec(name=f"random{seed}")
+    pick = lambda *xs: xs[int(rng.integers(0, len(xs)))]
+    s.groups.append(GroupDesc(int(rng.integers(1, 6)), 1))            # the network input
+    readable, writable = [0], []
+    n_layers = int(rng.integers(2, 9))
+    budget = max_weights
+    for layer in range(n_layers):
+        in_group = pick(*readable)
+        in_mult = pick(1, 1, 1, 1, 2, 4) if s.groups[in_group].width <= 64 else 1
+        shape = pick((1, 1), (1, 1), (3, 3), (3, 3), (3, 3), (2, 2), (5, 5), (1, 3), (3, 1), (7, 1))
+        if rng.random() < 0.04:
+            shape = pick((40, 30), (95, 90), (17, 70))    # kernels beyond the small-divisor tables
+        if in_mult > 1:
+            shape = (1, 1)
+        kh, kw = shape
+        in_ch = s.groups[in_group].width * in_mult
+        last = layer == n_layers - 1
+        if not last and writable and rng.random() < 0.3:
+            out_group = pick(*writable)                   # a second producer: residual add
+        else:
+            room = max(1, budget // max(1, in_ch * kh * kw * (n_layers - layer)))
+            width = int(min(room, pick(1, 2, 3, 7, 16, 33, 64, 100, 257, 640)))
+            s.groups.append(GroupDesc(width, 1 if last or rng.random() < 0.05 else 0))
+            out_group = len(s.groups) - 1
+            if not s.groups[out_group].pinned:
+                writable.append(out_group)
+            readable.append(out_group)
+        out_ch = s.groups[out_group].width
+        s.w_elems += int(rng.integers(0, 10)) if rng.random() < 0.5 else 0      # a gap
+        t = TensorDesc(s.w_elems, out_ch, in_ch, kh, kw, in_mult, out_group, in_group,
+                       0 if rng.random() < 0.12 else 1)
+        s.tensors.append(t)
+        s.w_elems += t.numel
+        budget -= t.numel
+    if not any(t.prunable for t in s.tensors):
+        s.tensors[0].prunable = 1
+    for g, grp in enumerate(s.groups):
+        for _ in range(int(rng.integers(0, 4))):
+            s.v_elems += int(rng.integers(0, 4)) if rng.random() < 0.3 else 0
+            s.vecs.append(VecDesc(s.v_elems, grp.width, g))
+            s.v_elems += grp.width
+    s.w_elems += int(rng.integers(0, 5))
+    return s
+
+
+def random_weights(spec: NetSpec, seed: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Arenas for ``random_spec``: per tensor one of the adversarial value patterns or
+    filter-scaled Gaussians, then whole filters and whole input features scaled to almost
+    nothing or set to zero; gaps hold a sentinel that no step may touch."""
+    rng = np.random.Generator(np.random.Philox(SEED_BASE + 2000 + seed))
+    w = np.full(max(spec.w_elems, 4), 12345.0, dtype=np.float32)
+    v = rng.standard_normal(max(spec.v_elems, 4)).astype(np.float32)
+    kinds = ("gauss", "gauss", "gauss", "half_zero", "quantised", "inf_negzero", "denormal",
+             "all_equal", "all_zero", "ramp_desc_signed")
+    for ti, t in enumerate(spec.tensors):
+        kind = kinds[int(rng.integers(0, len(kinds)))]
+        x = adversarial_arena(kind, t.numel, seed * 131 + ti).reshape(t.out_ch, t.in_ch, t.kh * t.kw)
+        if kind == "gauss":
+            x = x * np.exp(rng.normal(0.0, 1.5, size=(t.out_ch, 1, 1))).astype(np.float32)
+        rows = rng.random(t.out_ch) < 0.3
+        cols = rng.random(t.in_ch) < 0.2
+        with np.errstate(invalid="ignore"):
+            x[rows] *= np.float32(0.0 if rng.random() < 0.5 else 1e-6)
+            x[:, cols] *= np.float32(0.0 if rng.random() < 0.5 else 1e-6)
+        x[np.isnan(x)] = np.float32("inf")                # inf * 0: NaN is not a valid weight
+        w[t.offset:t.offset + t.numel] = x.reshape(-1)
+    return w, v

@@ -74,3 +74,32 @@ def test_sparsity_schedule():
     s = synth.config_sparsities(4)
     assert len(s) == 20 and abs(s[-1] - 0.98847) < 1e-5
     assert len(synth.config_sparsities(2)) == 10 and len(synth.config_sparsities(3)) == 15
+
+
+def test_random_nets_are_valid_and_deterministic():
+    """The random descriptions pass the library's own validation (host only), are the same
+    on every call, hold no NaN, and leave their gaps to a sentinel."""
+    from paper_2309_06973_amd import shifter as S
+    shapes = set()
+    for seed in range(40):
+        spec = synth.random_spec(seed)
+        again = synth.random_spec(seed)
+        assert spec.tensors == again.tensors and spec.vecs == again.vecs and spec.groups == again.groups
+        m = S.shifter_model_create(spec.tensors, spec.vecs, spec.groups)
+        assert m.info.n_prunable == spec.n_prunable > 0
+        S.shifter_model_destroy(m)
+        w, v = synth.random_weights(spec, seed)
+        w2, _ = synth.random_weights(spec, seed)
+        assert np.array_equal(w.view(np.uint32), w2.view(np.uint32))
+        assert not np.isnan(w).any() and w.size >= spec.w_elems
+        covered = np.zeros(w.size, dtype=bool)
+        for t in spec.tensors:
+            covered[t.offset:t.offset + t.numel] = True
+            shapes.add((t.kh, t.kw, t.in_mult > 1, bool(t.prunable)))
+        assert np.all(w[~covered] == np.float32(12345.0))
+    assert len(shapes) >= 12                       # the shapes really vary
+    producers = {}
+    for seed in range(40):
+        for t in synth.random_spec(seed).tensors:
+            producers[(seed, t.out_group)] = producers.get((seed, t.out_group), 0) + 1
+    assert max(producers.values()) >= 2            # residual-style groups occur
