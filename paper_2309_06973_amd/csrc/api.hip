@@ -13,10 +13,13 @@ using namespace shifter;
 
 namespace shifter {
 const char* const kKernelNames[K_COUNT] = {
-    "sel_init", "hist_round0", "hist_round1", "hist_round2", "select", "tie_count",
-    "tie_final", "zero_flags", "mask_scan", "scan", "propagate", "plan", "gather",
-    "copy", "kernel_scan", "fix_round", "fold_scale", "fold_apply", "deflate_chunk", "codec_scan", "codec_pack", "inflate_chunk", "mask_scan_batch", "expand_levels", "spec_init", "spec_sample", "spec_predict", "spec_pass",
-    "spec_hist_locate", "spec_filter_rank", "spec_fixup"};
+    "sel_init", "hist_round0", "hist_round1", "hist_round2", "select", "tie_count", "tie_final",
+    "zero_flags", "mask_scan", "scan", "propagate", "plan", "gather",
+    "copy", "kernel_scan", "fix_round", "fold_scale", "fold_apply",
+    "deflate_chunk", "codec_scan", "codec_pack", "inflate_chunk",
+    "mask_scan_batch", "expand_levels",
+    "spec_init", "spec_sample", "spec_predict", "spec_pass", "spec_hist_locate", "spec_filter_rank",
+    "spec_fixup"};
 
 ProfileScope::ProfileScope(shifter_ctx* c, int id) : ctx(c), idx(-1) {
     if (!c->profiling) return;
@@ -106,11 +109,14 @@ static void unbind(shifter_model* m) {
     auto& b = m->b;
     if (!b.ctx) return;
     (void)hipSetDevice(b.device);
-    void* ptrs[] = {b.tens, b.groups, b.vecs, b.producers, b.tile_prefix, b.tile_tensor, b.sel, b.ghist,
-                    b.tile_cnt, b.plan_t, b.plan_v, b.plan_h, b.plan_pack, b.out_tile_prefix, b.rect_prefix, b.rowtab_prefix, b.coltab_prefix, b.rowtab, b.coltab, b.kernel_off, b.fix_prefix, b.cons_prefix, b.consumers, b.fix_alive,
-                    b.fix_produced, b.fix_read, b.fix_out_flags, b.fix_removed, b.fold, b.fold_scale, b.levels, b.spec, b.shist,
-                    b.spec_cnt, b.partial, b.cand, b.list, b.ranked_ids, b.multi, b.multi_cnt,
-                    b.multi_partial, b.multi_seg, b.multi_seg_cnt};
+    void* ptrs[] = {b.tens, b.groups, b.vecs, b.producers, b.tile_prefix, b.tile_tensor, b.sel,
+                    b.ghist, b.tile_cnt, b.plan_t, b.plan_v, b.plan_h, b.plan_pack,
+                    b.out_tile_prefix, b.rect_prefix, b.rowtab_prefix, b.coltab_prefix, b.rowtab,
+                    b.coltab, b.kernel_off, b.fix_prefix, b.cons_prefix, b.consumers, b.fix_alive,
+                    b.fix_produced, b.fix_read, b.fix_out_flags, b.fix_removed, b.fold,
+                    b.fold_scale, b.levels, b.spec, b.shist, b.spec_cnt, b.partial, b.cand, b.list,
+                    b.ranked_ids, b.multi, b.multi_cnt, b.multi_partial, b.multi_seg,
+                    b.multi_seg_cnt};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     if (b.host_stage) (void)hipHostFree(b.host_stage);

@@ -18,7 +18,7 @@ constexpr uint32_t MAXK = SHIFTER_MAX_VARIANTS;
 constexpr uint32_t SLOTS_PER_PASS = 8;
 constexpr uint32_t GATHER_CHUNK = 1024;  // columns of a gather work unit (16 per lane)
 constexpr uint32_t GATHER_ROWS = 16;
-constexpr uint32_t RECT_ELEMS = 8192;    // floats of a source rectangle staged in LDS by the portfolio rebuild     // its rows, for rows of GATHER_CHUNK or more columns
+constexpr uint32_t RECT_ELEMS = 8192;    // floats of a source rectangle staged in LDS by the portfolio rebuild
 
 // Device-side view of one weight tensor.
 struct DevTensor {
@@ -146,7 +146,11 @@ struct PlanHeader {
 enum KernelId {
     K_SEL_INIT = 0, K_HIST0, K_HIST1, K_HIST2, K_SELECT, K_TIE_COUNT, K_TIE_FINAL,
     K_ZERO_FLAGS, K_MASK_SCAN, K_SCAN, K_PROPAGATE, K_PLAN, K_GATHER,
-    K_COPY, K_KERNEL_SCAN, K_FIX_ROUND, K_FOLD_SCALE, K_FOLD_APPLY, K_DEFLATE_CHUNK, K_CODEC_SCAN, K_CODEC_PACK, K_INFLATE_CHUNK, K_MASK_SCAN_BATCH, K_EXPAND_LEVELS, K_SPEC_INIT, K_SPEC_SAMPLE, K_SPEC_PREDICT, K_SPEC_PASS, K_SPEC_FINISH, K_SPEC_FINISH2, K_SPEC_FIXUP,
+    K_COPY, K_KERNEL_SCAN, K_FIX_ROUND, K_FOLD_SCALE, K_FOLD_APPLY,
+    K_DEFLATE_CHUNK, K_CODEC_SCAN, K_CODEC_PACK, K_INFLATE_CHUNK,
+    K_MASK_SCAN_BATCH, K_EXPAND_LEVELS,
+    K_SPEC_INIT, K_SPEC_SAMPLE, K_SPEC_PREDICT, K_SPEC_PASS, K_SPEC_FINISH, K_SPEC_FINISH2,
+    K_SPEC_FIXUP,
     K_COUNT
 };
 extern const char* const kKernelNames[K_COUNT];

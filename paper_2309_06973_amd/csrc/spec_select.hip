@@ -393,10 +393,21 @@ __device__ __forceinline__ void for_each_candidate(const uint32_t* cnt, const ui
     const uint32_t parts = gridDim.x / SPEC_SUB;
     const uint32_t n = min(cnt[(CNT_CAND * SPEC_SUB + sb) * 32u], cap_sb);
     const uint2* src = cand + (size_t)sb * cap_sb;
-    for (uint32_t i0 = part * BLOCK; i0 < n; i0 += parts * BLOCK) {
-        const uint32_t i = i0 + threadIdx.x;
-        const bool valid = i < n;
-        f(valid ? src[i] : make_uint2(0, 0), valid);
+    // four chunks per step: the loads of a step are all in flight before the first is used
+    // (a block holds few wavefronts, so one load per thread at a time leaves the walk
+    // waiting on memory latency)
+    constexpr uint32_t U = 4;
+    for (uint32_t i0 = part * BLOCK; i0 < n; i0 += U * parts * BLOCK) {
+        uint2 c[U];
+        bool valid[U];
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u) {
+            const uint32_t i = i0 + u * parts * BLOCK + threadIdx.x;
+            valid[u] = i < n;
+            c[u] = valid[u] ? src[i] : make_uint2(0, 0);
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u) f(c[u], valid[u]);
     }
 }
 
