@@ -115,7 +115,8 @@ static void unbind(shifter_model* m) {
                     b.coltab, b.kernel_off, b.fix_prefix, b.cons_prefix, b.consumers, b.fix_alive,
                     b.fix_produced, b.fix_read, b.fix_out_flags, b.fix_removed, b.fold,
                     b.fold_scale, b.levels, b.spec, b.shist, b.spec_cnt, b.partial, b.cand, b.list,
-                    b.ranked_ids, b.multi, b.multi_cnt, b.multi_partial, b.multi_seg,
+                    b.ranked_ids, b.multi, b.multi_cnt, b.multi_tab, b.multi_partial,
+                    b.multi_seg,
                     b.multi_seg_cnt};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
@@ -479,6 +480,7 @@ static int bind_tables(shifter_ctx* ctx, shifter_model* m) {
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.list), sizeof(uint2) * SPEC_LIST_CAP));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.multi), sizeof(MultiState)));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.multi_cnt), sizeof(uint32_t) * (MAXK + 2) * SPEC_SUB * 32));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.multi_tab), 4096));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.multi_partial),
                            sizeof(uint32_t) * SPEC_SUB * SPEC_MULTI_MAXK * 256));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.multi_seg),

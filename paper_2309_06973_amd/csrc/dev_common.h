@@ -62,8 +62,9 @@ __device__ __forceinline__ uint32_t key_of(float w) {
     return __float_as_uint(w) & 0x7fffffffu;
 }
 
-// Exclusive scan of one u64 per thread over a block of BLOCK threads.
-// smem: at least BLOCK / 64 + 1 entries.  Contains two barriers.
+// Exclusive scan of one u64 per thread over a block of THREADS threads.
+// smem: at least THREADS / 64 + 1 entries.  Contains two barriers.
+template <uint32_t THREADS = BLOCK>
 __device__ __forceinline__ uint64_t block_excl_scan_u64(uint64_t v, uint64_t* smem,
                                                         uint64_t* total) {
     const uint32_t lane = threadIdx.x & 63u, wid = threadIdx.x >> 6;
@@ -76,7 +77,7 @@ __device__ __forceinline__ uint64_t block_excl_scan_u64(uint64_t v, uint64_t* sm
     if (lane == 63) smem[wid] = x;
     __syncthreads();
     uint64_t woff = 0, tot = 0;
-    for (uint32_t i = 0; i < BLOCK / 64; ++i) {
+    for (uint32_t i = 0; i < THREADS / 64; ++i) {
         const uint64_t s = smem[i];
         if (i < wid) woff += s;
         tot += s;

@@ -229,6 +229,7 @@ struct shifter_model {
         uint32_t* ranked_ids = nullptr;
         shifter::MultiState* multi = nullptr;
         uint32_t* multi_cnt = nullptr;        // (MAXK + 2) * SPEC_SUB counters, 128-byte lines
+        uint8_t* multi_tab = nullptr;         // 4096 bucket entries of the K-rank pass
         uint32_t* multi_partial = nullptr;    // SPEC_SUB * SPEC_MULTI_MAXK * 256
         uint2* multi_seg = nullptr;           // SPEC_MULTI_MAXK * SPEC_SUB * SPEC_SEG_CAP pairs
         uint32_t* multi_seg_cnt = nullptr;    // SPEC_MULTI_MAXK * SPEC_SUB

@@ -7,15 +7,22 @@
 
 namespace shifter {
 
-// One block per group (and per variant of a batch).  alive[c] = frozen | OR over producers of out_alive[p][c];
-// an exclusive scan of alive gives the old -> new map and the keep list.
-__global__ __launch_bounds__(BLOCK) void propagate_kernel(
+// One block per group (and per variant of a batch).  alive[c] = frozen | OR over producers of
+// out_alive[p][c]; an exclusive scan of alive gives the old -> new map and the keep list.
+// The producers' flag offsets are fetched once (two dependent loads each) and a channel's
+// flags are then loaded side by side: the kernel is a handful of memory latencies long,
+// and a 1024-thread block covers most groups in one or two rounds.
+constexpr uint32_t PROP_THREADS = 1024, PROP_LDS_PRODUCERS = 64;
+
+__global__ __launch_bounds__(PROP_THREADS) void propagate_kernel(
     const DevGroup* __restrict__ groups, const uint32_t* __restrict__ producers,
     const DevTensor* __restrict__ tens, const uint8_t* __restrict__ out_alive,
     uint32_t flags, uint8_t* __restrict__ group_alive, int32_t* __restrict__ index_map,
     uint32_t* __restrict__ keep, uint32_t* __restrict__ new_width, uint64_t out_alive_stride,
     uint64_t group_stride, uint32_t n_groups) {
-    __shared__ uint32_t wave_cnt[BLOCK / 64];
+    constexpr uint32_t WAVES = PROP_THREADS / 64;
+    __shared__ uint32_t wave_cnt[WAVES];
+    __shared__ uint32_t s_flag_off[PROP_LDS_PRODUCERS];
     // blockIdx.y = variant of a batch
     out_alive += blockIdx.y * out_alive_stride;
     group_alive += blockIdx.y * group_stride;
@@ -26,20 +33,28 @@ __global__ __launch_bounds__(BLOCK) void propagate_kernel(
     const uint32_t n_prod = G.prod_end - G.prod_begin;
     const bool frozen = G.pinned || ((flags & SHIFTER_PAPER_FREEZE_RESIDUAL) && n_prod > 1);
     const uint32_t lane = threadIdx.x & 63u, wid = threadIdx.x >> 6;
+    if (!frozen && threadIdx.x < min(n_prod, PROP_LDS_PRODUCERS))
+        s_flag_off[threadIdx.x] = tens[producers[G.prod_begin + threadIdx.x]].out_flag_off;
+    __syncthreads();
     uint32_t base = 0;
-    for (uint32_t c0 = 0; c0 < G.width; c0 += BLOCK) {
+    for (uint32_t c0 = 0; c0 < G.width; c0 += PROP_THREADS) {
         const uint32_t c = c0 + threadIdx.x;
         uint32_t a = 0;
         if (c < G.width) {
             a = frozen ? 1u : 0u;
-            for (uint32_t p = G.prod_begin; p < G.prod_end && !a; ++p)
-                a = out_alive[tens[producers[p]].out_flag_off + c] ? 1u : 0u;
+            if (!frozen) {
+                const uint32_t n_lds = min(n_prod, PROP_LDS_PRODUCERS);
+                for (uint32_t p = 0; p < n_lds; ++p) a |= out_alive[s_flag_off[p] + c];
+                for (uint32_t p = G.prod_begin + n_lds; p < G.prod_end && !a; ++p)
+                    a = out_alive[tens[producers[p]].out_flag_off + c];
+                a = a ? 1u : 0u;
+            }
         }
         const unsigned long long bal = __ballot(a);
         if (lane == 0) wave_cnt[wid] = (uint32_t)__popcll(bal);
         __syncthreads();
         uint32_t woff = 0, tot = 0;
-        for (uint32_t i = 0; i < BLOCK / 64; ++i) {
+        for (uint32_t i = 0; i < WAVES; ++i) {
             const uint32_t x = wave_cnt[i];
             if (i < wid) woff += x;
             tot += x;
@@ -53,7 +68,7 @@ __global__ __launch_bounds__(BLOCK) void propagate_kernel(
         base += tot;
         __syncthreads();
     }
-    for (uint32_t c = base + threadIdx.x; c < G.width; c += BLOCK) keep[G.off + c] = 0xffffffffu;
+    for (uint32_t c = base + threadIdx.x; c < G.width; c += PROP_THREADS) keep[G.off + c] = 0xffffffffu;
     if (threadIdx.x == 0) new_width[blockIdx.x] = base;
 }
 
@@ -612,7 +627,7 @@ void launch_propagate(shifter_ctx* ctx, const shifter_model* m, const uint8_t* d
                       uint32_t* d_keep, uint32_t* d_new_width, uint32_t k_var) {
     const auto& b = m->b;
     ProfileScope p(ctx, K_PROPAGATE);
-    propagate_kernel<<<dim3((uint32_t)m->g.size(), k_var), BLOCK, 0, ctx->stream>>>(
+    propagate_kernel<<<dim3((uint32_t)m->g.size(), k_var), PROP_THREADS, 0, ctx->stream>>>(
         b.groups, b.producers, b.tens, d_out_alive, flags, d_group_alive, d_index_map, d_keep,
         d_new_width, m->info.sum_out_ch, m->info.sum_group_width, (uint32_t)m->g.size());
 }

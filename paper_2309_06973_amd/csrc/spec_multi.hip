@@ -19,6 +19,10 @@ constexpr uint32_t MS_SHIFT = 17;        // top 14 of the 31 key bits
 constexpr uint32_t MF_BINS1 = 256;       // round-1 finishing histogram, per rank
 constexpr uint32_t MF_BINS2 = 4096;      // round-2, one block per rank
 constexpr uint32_t MF_BLOCKS = SPEC_SUB; // blocks of the passes over the candidates
+constexpr uint32_t TAB_SHIFT = 19;       // the pass's bucket table: 4096 buckets of 2^19 keys
+constexpr uint32_t TAB_SIZE = 1u << (31 - TAB_SHIFT);
+constexpr uint32_t MF_THREADS = 1024;    // their size: one block per CU, and its sixteen wavefronts
+                                         // hide the latency of the walk's loads and LDS searches
 
 enum { MC_CAND = 0, MC_BELOW = 1 };   // cnt layout: [MC_CAND][sb]*32, then [1 + j][sb]*32
 
@@ -66,23 +70,31 @@ __global__ __launch_bounds__(BLOCK) void ms_init_kernel(MultiState* ms, uint32_t
 // interval from the sample's order statistics at P/N -/+ margin, then monotone ends.
 constexpr uint32_t PREDICT_THREADS = 1024;
 
-__global__ __launch_bounds__(PREDICT_THREADS) void ms_predict_kernel(MultiState* ms,
-                                                                     const uint32_t* __restrict__ shist,
-                                                                     uint64_t n_prunable,
-                                                                     double margin_sigmas) {
+__global__ __launch_bounds__(PREDICT_THREADS) void ms_predict_kernel(
+    MultiState* ms, const uint32_t* __restrict__ shist, uint64_t n_prunable, double margin_sigmas,
+    uint8_t* __restrict__ tab) {
     constexpr uint32_t SEG = 256, NSEG = MS_BINS / SEG, WAVES = PREDICT_THREADS / 64;
     static_assert(NSEG == 64, "one segment per lane in the scan of the segment sums");
     __shared__ uint32_t prefix[MS_BINS];          // 64 KB
     __shared__ uint32_t seg_sum[NSEG];
     __shared__ uint32_t s_total;
-    __shared__ uint32_t s_lo[MAXK], s_hi[MAXK], s_mid[MAXK];
+    __shared__ uint32_t s_lo[MAXK];
     const uint32_t lane = threadIdx.x & 63u, wid = threadIdx.x >> 6;
+    constexpr uint32_t PER_WAVE = NSEG / WAVES;   // segments per wavefront
+    // each wavefront's segments are loaded once, all loads in flight together
+    uint4 x[PER_WAVE];
+#pragma unroll
+    for (uint32_t i = 0; i < PER_WAVE; ++i)
+        x[i] = reinterpret_cast<const uint4*>(shist + (wid + i * WAVES) * SEG)[lane];
+    const uint32_t k_var = ms->k;
+    const uint32_t m = ms->m_valid;
+    const uint64_t p = threadIdx.x < k_var ? ms->p[threadIdx.x] : 0;
     // phase 1: segment sums, then their exclusive scan by the first wavefront
-    for (uint32_t sg = wid; sg < NSEG; sg += WAVES) {
-        const uint4 x = reinterpret_cast<const uint4*>(shist + sg * SEG)[lane];
-        uint32_t v = x.x + x.y + x.z + x.w;
+#pragma unroll
+    for (uint32_t i = 0; i < PER_WAVE; ++i) {
+        uint32_t v = x[i].x + x[i].y + x[i].z + x[i].w;
         for (uint32_t d = 32; d > 0; d >>= 1) v += __shfl_down(v, d, 64);
-        if (lane == 0) seg_sum[sg] = v;
+        if (lane == 0) seg_sum[wid + i * WAVES] = v;
     }
     __syncthreads();
     if (wid == 0) {
@@ -98,9 +110,10 @@ __global__ __launch_bounds__(PREDICT_THREADS) void ms_predict_kernel(MultiState*
     __syncthreads();
     const uint64_t total = s_total;
     // phase 2: inclusive prefix per bin
-    for (uint32_t sg = wid; sg < NSEG; sg += WAVES) {
-        const uint4 x = reinterpret_cast<const uint4*>(shist + sg * SEG)[lane];
-        const uint32_t mine4 = x.x + x.y + x.z + x.w;
+#pragma unroll
+    for (uint32_t i = 0; i < PER_WAVE; ++i) {
+        const uint32_t sg = wid + i * WAVES;
+        const uint32_t mine4 = x[i].x + x[i].y + x[i].z + x[i].w;
         uint32_t incl = mine4;
         for (uint32_t d = 1; d < 64; d <<= 1) {
             const uint32_t y = __shfl_up(incl, d, 64);
@@ -108,18 +121,16 @@ __global__ __launch_bounds__(PREDICT_THREADS) void ms_predict_kernel(MultiState*
         }
         uint32_t run = seg_sum[sg] + incl - mine4;
         uint32_t* out = prefix + sg * SEG + lane * 4;
-        run += x.x; out[0] = run;
-        run += x.y; out[1] = run;
-        run += x.z; out[2] = run;
-        run += x.w; out[3] = run;
+        run += x[i].x; out[0] = run;
+        run += x[i].y; out[1] = run;
+        run += x[i].z; out[2] = run;
+        run += x[i].w; out[3] = run;
     }
     __syncthreads();
-    const uint32_t k_var = ms->k;
-    const uint32_t m = ms->m_valid;
-    if (threadIdx.x < k_var) {
-        const uint64_t p = ms->p[threadIdx.x];
+    // the first wavefront: lane k takes rank k (k_var <= 64)
+    if (wid == 0) {
         uint32_t lo = 0, hi = 0x7fffffffu, mid = 0;
-        if (p > 0 && m >= 256 && n_prunable > 0 && total == m) {
+        if (lane < k_var && p > 0 && m >= 256 && n_prunable > 0 && total == m) {
             const double frac = (double)p / (double)n_prunable;
             const double centre = frac * (double)m;
             const double delta = margin_sigmas * sqrt((double)m * frac * (1.0 - frac)) + 16.0;
@@ -137,28 +148,56 @@ __global__ __launch_bounds__(PREDICT_THREADS) void ms_predict_kernel(MultiState*
             if (r_hi < (double)(m - 1)) hi = ((bin_of(r_hi) + 1u) << MS_SHIFT) - 1u;
             mid = bin_of(min(max(centre, 0.0), (double)(m - 1))) << MS_SHIFT;
         }
-        s_lo[threadIdx.x] = lo;
-        s_hi[threadIdx.x] = hi;
-        s_mid[threadIdx.x] = mid;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        // widen so that both ends are non-decreasing in k (ranks are sorted by P)
-        for (uint32_t k = 1; k < k_var; ++k) s_hi[k] = max(s_hi[k], s_hi[k - 1]);
-        for (uint32_t k = k_var - 1; k > 0; --k) s_lo[k - 1] = min(s_lo[k - 1], s_lo[k]);
-        uint32_t prev_mid = 0;
-        for (uint32_t k = 0; k < k_var; ++k) {
-            uint32_t sh = 0;
-            while (((s_hi[k] - s_lo[k]) >> sh) >= MF_BINS1) ++sh;
-            ms->lo[k] = s_lo[k];
-            ms->hi[k] = s_hi[k];
-            ms->sh[k] = sh;
-            // provisional threshold of the fused pass: inside the interval, non-decreasing
-            prev_mid = max(prev_mid, min(max(s_mid[k], s_lo[k]), s_hi[k]));
-            ms->mid[k] = min(prev_mid, s_hi[k]);
-            prev_mid = ms->mid[k];
+        // widen so that both ends are non-decreasing in k (ranks are sorted by P): a running
+        // maximum of hi from the left, a running minimum of lo from the right; lanes past
+        // the last rank hold the neutral values
+        if (lane >= k_var) { lo = 0xffffffffu; hi = 0; }
+        for (uint32_t d = 1; d < 64; d <<= 1) {
+            const uint32_t yh = __shfl_up(hi, d, 64);
+            const uint32_t yl = __shfl_down(lo, d, 64);
+            if (lane >= d) hi = max(hi, yh);
+            if (lane + d < 64) lo = min(lo, yl);
+        }
+        // provisional threshold of the fused pass: inside the interval, non-decreasing (a
+        // running maximum: it stays below hi because hi is non-decreasing)
+        uint32_t pm = lane < k_var ? min(max(mid, lo), hi) : 0u;
+        for (uint32_t d = 1; d < 64; d <<= 1) {
+            const uint32_t y = __shfl_up(pm, d, 64);
+            if (lane >= d) pm = max(pm, y);
+        }
+        if (lane < k_var) {
+            const uint32_t span = hi - lo;   // smallest sh with (span >> sh) < MF_BINS1
+            const uint32_t sh = span < MF_BINS1 ? 0u : (32u - (uint32_t)__clz(span)) - 8u;
+            static_assert(MF_BINS1 == 256, "sh from the bit length of the span");
+            ms->lo[lane] = lo;
+            ms->hi[lane] = hi;
+            ms->sh[lane] = sh;
+            ms->mid[lane] = pm;
+            s_lo[lane] = lo;
         }
     }
+    // The pass's bucket table.  Entry b covers the keys [b << TAB_SHIFT, (b + 1) << TAB_SHIFT):
+    // bits 0-5 = #{k : lo_k <= first key of the bucket}, bits 6-7 = how many lo_k lie
+    // above that inside the bucket (3: three or more).  With a few dozen ranks almost every
+    // bucket holds none, and a weight's j is then the entry itself.
+    __syncthreads();
+    constexpr uint32_t PER_THREAD = TAB_SIZE / PREDICT_THREADS;
+    uint32_t j0[PER_THREAD], inside[PER_THREAD];
+#pragma unroll
+    for (uint32_t i = 0; i < PER_THREAD; ++i) j0[i] = inside[i] = 0;
+    for (uint32_t k = 0; k < k_var; ++k) {
+        const uint32_t lo = s_lo[k];
+#pragma unroll
+        for (uint32_t i = 0; i < PER_THREAD; ++i) {
+            const uint32_t first = (threadIdx.x + i * PREDICT_THREADS) << TAB_SHIFT;
+            const uint32_t last = first + ((1u << TAB_SHIFT) - 1u);
+            j0[i] += lo <= first ? 1u : 0u;
+            inside[i] += (lo > first && lo <= last) ? 1u : 0u;
+        }
+    }
+#pragma unroll
+    for (uint32_t i = 0; i < PER_THREAD; ++i)
+        tab[threadIdx.x + i * PREDICT_THREADS] = (uint8_t)(j0[i] | (min(inside[i], 3u) << 6));
 }
 
 // The one pass over the arena: counts per j and candidate pairs.
@@ -166,11 +205,16 @@ template <bool NT>
 __global__ __launch_bounds__(BLOCK) void ms_pass_kernel(
     const DevTensor* __restrict__ tens, const uint32_t* __restrict__ tile_prefix, uint32_t n_t,
     const float* __restrict__ w, MultiState* ms, uint32_t* cnt, uint2* __restrict__ cand,
-    uint32_t cap_sb) {
-    __shared__ uint32_t s_lo[MAXK + 1], s_hi[MAXK + 1];
-    // counts per j: one private column per thread (no conflicts, no atomics), summed at
-    // the end; rows 0 .. k_var
-    __shared__ uint32_t s_col[(SPEC_MULTI_MAXK + 1) * BLOCK];
+    uint32_t cap_sb, const uint8_t* __restrict__ tab) {
+    // s_hi1[j] = hi_(j-1) + 1, s_hi1[0] = 0: a weight with j lower ends at or below it is a
+    // candidate (of rank j - 1) iff key < s_hi1[j]
+    __shared__ uint32_t s_lo[MAXK + 1], s_hi1[MAXK + 1];
+    // counts per j: one private byte column per thread (a thread sees 16 weights; no
+    // conflicts, no atomics), summed at the end; rows 0 .. k_var of BLOCK bytes (the launch
+    // sizes it).  Small, so that a CU holds as many blocks as it has wavefront slots: a
+    // block's life is a chain of memory latencies, which only other blocks can hide.
+    extern __shared__ uint32_t s_col[];
+    __shared__ __align__(16) uint8_t s_tab[TAB_SIZE];
     __shared__ uint32_t s_nan, s_base, s_wtot[BLOCK / 64];
     const uint32_t tile = blockIdx.x;
     const uint32_t t = find_tensor(tile_prefix, n_t, tile);
@@ -182,37 +226,56 @@ __global__ __launch_bounds__(BLOCK) void ms_pass_kernel(
     const uint32_t lane = threadIdx.x & 63u, wid = threadIdx.x >> 6;
     const uint32_t sb = blockIdx.x & (SPEC_SUB - 1);
     uint2* my_cand = cand + (size_t)sb * cap_sb;
+    // the tile's loads go out first: the set-up below runs while they are in flight
+    const float* src = w + T.offset + e0;
+    const bool whole = n == TILE && (T.offset & 3u) == 0;
+    constexpr uint32_t U = TILE / BLOCK / 4;
+    uint4 v[U];
+    if (whole) {
+        const uint4* s4 = reinterpret_cast<const uint4*>(src);
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u) v[u] = load_u4<NT>(s4 + threadIdx.x + BLOCK * u);
+    }
     const uint32_t k_var = ms->k;
     if (threadIdx.x <= MAXK) {
         s_lo[threadIdx.x] = threadIdx.x < MAXK ? ms->lo[threadIdx.x] : 0xffffffffu;
-        s_hi[threadIdx.x] = threadIdx.x < MAXK ? ms->hi[threadIdx.x] : 0xffffffffu;
+        s_hi1[threadIdx.x] = (threadIdx.x >= 1 && threadIdx.x <= k_var) ? ms->hi[threadIdx.x - 1] + 1u : 0u;
     }
-    for (uint32_t j = 0; j <= k_var; ++j) s_col[j * BLOCK + threadIdx.x] = 0;
+    for (uint32_t i = threadIdx.x; i < (k_var + 1) * (BLOCK / 4); i += BLOCK) s_col[i] = 0;
+    static_assert(TAB_SIZE == BLOCK * 16, "one 16-byte piece of the table per thread");
+    reinterpret_cast<uint4*>(s_tab)[threadIdx.x] = reinterpret_cast<const uint4*>(tab)[threadIdx.x];
     if (threadIdx.x == 0) { s_nan = 0; s_base = 0; }
     __syncthreads();
 
-    uint32_t nan = 0;
-    // classify one weight; returns whether it is a candidate; adds it to the count of j
+    uint32_t key_max = 0;   // a NaN's key is above that of +inf
+    uint8_t* my_col = reinterpret_cast<uint8_t*>(s_col) + threadIdx.x;
+    // classify one weight; returns whether it is a candidate; adds it to the count of
+    // j = #{k : lo_k <= key}: the bucket table's entry, plus a compare or two in the few
+    // buckets that hold a rank's lower end (the binary search where three or more meet)
     auto one = [&](uint32_t bits) -> bool {
         const uint32_t key = bits & 0x7fffffffu;
-        nan |= key > 0x7f800000u ? 1u : 0u;
-        uint32_t j = 0;
+        key_max = max(key_max, key);
+        const uint32_t e = s_tab[key >> TAB_SHIFT];
+        uint32_t j = e & 63u;
+        if (e >> 6) {
+            if ((e >> 6) == 3u) {
+                j = 0;
 #pragma unroll
-        for (uint32_t step = MAXK / 2; step >= 1; step >>= 1)
-            if (s_lo[j + step - 1] <= key) j += step;
-        j += s_lo[j] <= key ? 1u : 0u;          // j in [0, MAXK]; s_lo[MAXK] is padding
-        const bool is_cand = j >= 1 && key <= s_hi[j - 1];
-        s_col[j * BLOCK + threadIdx.x] += 1;    // j <= k_var <= SPEC_MULTI_MAXK
-        return is_cand;
+                for (uint32_t step = MAXK / 2; step >= 1; step >>= 1)
+                    if (s_lo[j + step - 1] <= key) j += step;
+                j += s_lo[j] <= key ? 1u : 0u;      // j in [0, MAXK]; s_lo[MAXK] is padding
+            } else {
+                // the lower ends are sorted: the second one counts only if the first does
+                const uint32_t j0 = j;
+                j += s_lo[j0] <= key ? 1u : 0u;
+                j += ((e >> 6) == 2u && s_lo[j0 + 1] <= key) ? 1u : 0u;
+            }
+        }
+        my_col[j * BLOCK] += 1;                 // private byte, at most 16
+        return key < s_hi1[j];                  // j <= k_var <= SPEC_MULTI_MAXK
     };
 
-    const float* src = w + T.offset + e0;
-    if (n == TILE && (T.offset & 3u) == 0) {
-        constexpr uint32_t U = TILE / BLOCK / 4;
-        const uint4* s4 = reinterpret_cast<const uint4*>(src);
-        uint4 v[U];
-#pragma unroll
-        for (uint32_t u = 0; u < U; ++u) v[u] = load_u4<NT>(s4 + threadIdx.x + BLOCK * u);
+    if (whole) {
         uint32_t cmask = 0;
 #pragma unroll
         for (uint32_t u = 0; u < U; ++u) {
@@ -265,21 +328,27 @@ __global__ __launch_bounds__(BLOCK) void ms_pass_kernel(
             }
         }
     }
-    for (uint32_t d = 32; d > 0; d >>= 1) nan |= __shfl_down(nan, d, 64);
-    if (lane == 0 && nan) s_nan = 1;
+    if (key_max > 0x7f800000u) s_nan = 1;
     __syncthreads();
-    // column sums: four threads per j, a quarter of the columns each
+    // column sums: four threads per j, a quarter of the row's words each (rotated by j: the
+    // rows start in the same bank); bytes are added in two 16-bit lanes per word
     if (threadIdx.x < 4 * (k_var + 1)) {
         const uint32_t j = threadIdx.x >> 2, q = threadIdx.x & 3u;
-        uint32_t c = 0;
-        for (uint32_t i = 0; i < BLOCK / 4; ++i) c += s_col[j * BLOCK + ((i * 4 + q + j) & (BLOCK - 1))];
+        constexpr uint32_t ROW_W = BLOCK / 4;
+        uint32_t even = 0, odd = 0;
+        for (uint32_t i = 0; i < ROW_W / 4; ++i) {
+            const uint32_t x = s_col[j * ROW_W + ((q * (ROW_W / 4) + i + j) & (ROW_W - 1))];
+            even += x & 0x00ff00ffu;
+            odd += (x >> 8) & 0x00ff00ffu;
+        }
+        const uint32_t c = (even & 0xffffu) + (even >> 16) + (odd & 0xffffu) + (odd >> 16);
         if (c) atomicAdd(mcnt(cnt, MC_BELOW + j, sb), c);
     }
     if (threadIdx.x == 0 && s_nan) atomicOr(&ms->status, 2u);
 }
 
-// Visits every candidate pair (see the one-count selection).
-template <typename F>
+// Visits every candidate pair (see the one-count selection); THREADS: the block size.
+template <uint32_t THREADS = BLOCK, typename F>
 __device__ __forceinline__ void ms_for_each_candidate(const uint32_t* cnt, const uint2* cand,
                                                       uint32_t cap_sb, F&& f) {
     const uint32_t sb = blockIdx.x % SPEC_SUB, part = blockIdx.x / SPEC_SUB;
@@ -290,12 +359,12 @@ __device__ __forceinline__ void ms_for_each_candidate(const uint32_t* cnt, const
     // (a block holds few wavefronts, so one load per thread at a time leaves the walk
     // waiting on memory latency)
     constexpr uint32_t U = 4;
-    for (uint32_t i0 = part * BLOCK; i0 < n; i0 += U * parts * BLOCK) {
+    for (uint32_t i0 = part * THREADS; i0 < n; i0 += U * parts * THREADS) {
         uint2 c[U];
         bool valid[U];
 #pragma unroll
         for (uint32_t u = 0; u < U; ++u) {
-            const uint32_t i = i0 + u * parts * BLOCK + threadIdx.x;
+            const uint32_t i = i0 + u * parts * THREADS + threadIdx.x;
             valid[u] = i < n;
             c[u] = valid[u] ? src[i] : make_uint2(0, 0);
         }
@@ -320,22 +389,20 @@ __device__ __forceinline__ void rank_range(const uint32_t* s_lo, const uint32_t*
 }
 
 // Round 1: per block and per rank a 256-bin LDS histogram of (key - lo_k) >> sh_k.
-__global__ __launch_bounds__(BLOCK) void ms_hist_kernel(const MultiState* __restrict__ ms,
-                                                        const uint32_t* __restrict__ cnt,
-                                                        const uint2* __restrict__ cand,
-                                                        uint32_t cap_sb,
-                                                        uint32_t* __restrict__ partial) {
+__global__ __launch_bounds__(MF_THREADS) void ms_hist_kernel(
+    const MultiState* __restrict__ ms, const uint32_t* __restrict__ cnt,
+    const uint2* __restrict__ cand, uint32_t cap_sb, uint32_t* __restrict__ partial) {
     extern __shared__ uint32_t h[];   // k_var * 256
     __shared__ uint32_t s_lo[MAXK + 1], s_hi[MAXK + 1], s_sh[MAXK];
     const uint32_t k_var = ms->k;
-    for (uint32_t i = threadIdx.x; i < k_var * MF_BINS1; i += BLOCK) h[i] = 0;
+    for (uint32_t i = threadIdx.x; i < k_var * MF_BINS1; i += MF_THREADS) h[i] = 0;
     if (threadIdx.x <= MAXK) {
         s_lo[threadIdx.x] = threadIdx.x < MAXK ? ms->lo[threadIdx.x] : 0xffffffffu;
         s_hi[threadIdx.x] = threadIdx.x < MAXK ? ms->hi[threadIdx.x] : 0xffffffffu;
         if (threadIdx.x < MAXK) s_sh[threadIdx.x] = ms->sh[threadIdx.x];
     }
     __syncthreads();
-    ms_for_each_candidate(cnt, cand, cap_sb, [&](uint2 c, bool valid) {
+    ms_for_each_candidate<MF_THREADS>(cnt, cand, cap_sb, [&](uint2 c, bool valid) {
         if (!valid) return;
         const uint32_t key = c.x & 0x7fffffffu;
         uint32_t ka, kb;
@@ -344,43 +411,59 @@ __global__ __launch_bounds__(BLOCK) void ms_hist_kernel(const MultiState* __rest
             atomicAdd(&h[k * MF_BINS1 + ((key - s_lo[k]) >> s_sh[k])], 1u);
     });
     __syncthreads();
-    for (uint32_t i = threadIdx.x; i < k_var * MF_BINS1; i += BLOCK)
+    for (uint32_t i = threadIdx.x; i < k_var * MF_BINS1; i += MF_THREADS)
         partial[(size_t)blockIdx.x * k_var * MF_BINS1 + i] = h[i];
 }
 
 // One block per rank: totals, the check that makes the result exact, the round-1 bin.
-__global__ __launch_bounds__(BLOCK) void ms_locate_kernel(MultiState* ms,
-                                                          const uint32_t* __restrict__ cnt,
-                                                          const uint32_t* __restrict__ partial,
-                                                          uint32_t cap_sb) {
-    __shared__ uint64_t smem[BLOCK / 64 + 1];
+// Thread t of each quarter of the block owns bin t and sums a quarter of the partial
+// histograms (the loads are what the kernel waits for); the first quarter then decides.
+constexpr uint32_t LOCATE_THREADS = 1024, LOCATE_PARTS = LOCATE_THREADS / MF_BINS1;
+
+__global__ __launch_bounds__(LOCATE_THREADS) void ms_locate_kernel(
+    MultiState* ms, const uint32_t* __restrict__ cnt, const uint32_t* __restrict__ partial,
+    uint32_t cap_sb) {
+    __shared__ uint64_t smem[LOCATE_THREADS / 64 + 1];
+    __shared__ uint32_t s_part[LOCATE_PARTS - 1][MF_BINS1];
     __shared__ uint32_t s_over;
     const uint32_t k = blockIdx.x, k_var = ms->k;
+    const uint32_t bin = threadIdx.x & (MF_BINS1 - 1), part = threadIdx.x / MF_BINS1;
     const uint64_t p = ms->p[k];
     if (threadIdx.x == 0) s_over = 0;
     __syncthreads();
-    static_assert(SPEC_SUB == BLOCK, "one split counter per thread");
+    static_assert(SPEC_SUB == MF_BINS1, "one split counter per thread of the first quarter");
+    static_assert(MF_BLOCKS % LOCATE_PARTS == 0, "the partial histograms split evenly");
     uint64_t below, inside;
     {
         uint32_t b = 0;
-        for (uint32_t j = 0; j <= k; ++j) b += cnt[((size_t)(MC_BELOW + j) * SPEC_SUB + threadIdx.x) * 32u];
-        block_excl_scan_u64(b, smem, &below);
-        if (cnt[((size_t)MC_CAND * SPEC_SUB + threadIdx.x) * 32u] > cap_sb) s_over = 1;
+        if (part == 0) {
+            for (uint32_t j = 0; j <= k; ++j) b += cnt[((size_t)(MC_BELOW + j) * SPEC_SUB + bin) * 32u];
+            if (cnt[((size_t)MC_CAND * SPEC_SUB + bin) * 32u] > cap_sb) s_over = 1;
+        }
+        block_excl_scan_u64<LOCATE_THREADS>(b, smem, &below);
     }
-    // this rank's round-1 histogram: thread t owns bin t
+    // this rank's round-1 histogram
     uint32_t c = 0;
+    constexpr uint32_t PER = MF_BLOCKS / LOCATE_PARTS;
 #pragma unroll 8
-    for (uint32_t q = 0; q < MF_BLOCKS; ++q)
-        c += partial[((size_t)q * k_var + k) * MF_BINS1 + threadIdx.x];
-    const uint64_t base = block_excl_scan_u64(c, smem, &inside);
+    for (uint32_t q = part * PER; q < (part + 1) * PER; ++q)
+        c += partial[((size_t)q * k_var + k) * MF_BINS1 + bin];
+    if (part) s_part[part - 1][bin] = c;
+    __syncthreads();
+    if (part == 0) {
+        for (uint32_t i = 0; i < LOCATE_PARTS - 1; ++i) c += s_part[i][bin];
+    } else {
+        c = 0;
+    }
+    const uint64_t base = block_excl_scan_u64<LOCATE_THREADS>(c, smem, &inside);
     __syncthreads();
     if (s_over || !(below < p && p <= below + inside)) {
         if (threadIdx.x == 0) atomicOr(&ms->status, 1u);
         return;
     }
     const uint64_t r = p - below;
-    if (base < r && r <= base + c) {
-        ms->bin[k] = threadIdx.x;
+    if (part == 0 && base < r && r <= base + c) {
+        ms->bin[k] = bin;
         ms->bin_cnt[k] = c;
         ms->r2[k] = r - base;
         ms->less[k] = below + base;
@@ -390,11 +473,9 @@ __global__ __launch_bounds__(BLOCK) void ms_locate_kernel(MultiState* ms,
 
 // Candidates of each rank's selected bin -> that rank's list, one segment per block
 // (LDS counters only: no global atomics).
-__global__ __launch_bounds__(BLOCK) void ms_filter_kernel(MultiState* ms,
-                                                          const uint32_t* __restrict__ cnt,
-                                                          const uint2* __restrict__ cand,
-                                                          uint32_t cap_sb, uint2* __restrict__ seg,
-                                                          uint32_t* __restrict__ seg_cnt) {
+__global__ __launch_bounds__(MF_THREADS) void ms_filter_kernel(
+    MultiState* ms, const uint32_t* __restrict__ cnt, const uint2* __restrict__ cand,
+    uint32_t cap_sb, uint2* __restrict__ seg, uint32_t* __restrict__ seg_cnt) {
     __shared__ uint32_t s_lo[MAXK + 1], s_hi[MAXK + 1], s_sh[MAXK], s_bin[MAXK], s_n[MAXK];
     const uint32_t k_var = ms->k;
     if (ms->status & 1u) return;
@@ -408,7 +489,7 @@ __global__ __launch_bounds__(BLOCK) void ms_filter_kernel(MultiState* ms,
         }
     }
     __syncthreads();
-    ms_for_each_candidate(cnt, cand, cap_sb, [&](uint2 c, bool valid) {
+    ms_for_each_candidate<MF_THREADS>(cnt, cand, cap_sb, [&](uint2 c, bool valid) {
         if (!valid) return;
         const uint32_t key = c.x & 0x7fffffffu;
         uint32_t ka, kb;
@@ -849,7 +930,7 @@ void launch_spec_multi(shifter_ctx* ctx, const shifter_model* m, const float* d_
         {
             ProfileScope ps(ctx, K_SPEC_PREDICT);
             ms_predict_kernel<<<1, PREDICT_THREADS, 0, s>>>(b.multi, b.shist, m->info.n_prunable,
-                                                  ctx->margin_sigmas);
+                                                            ctx->margin_sigmas, b.multi_tab);
         }
     }
     const bool nt = m->info.w_extent * 4 > (192ull << 20);
@@ -868,19 +949,19 @@ void launch_spec_multi(shifter_ctx* ctx, const shifter_model* m, const float* d_
     } else {
         ProfileScope ps(ctx, K_SPEC_PASS);
         auto kern = nt ? ms_pass_kernel<true> : ms_pass_kernel<false>;
-        kern<<<m->n_tiles, BLOCK, 0, s>>>(b.tens, b.tile_prefix, n_t, d_w, b.multi, b.multi_cnt,
-                                          b.cand, b.cand_cap_sb);
+        kern<<<m->n_tiles, BLOCK, (k + 1) * BLOCK, s>>>(
+            b.tens, b.tile_prefix, n_t, d_w, b.multi, b.multi_cnt, b.cand, b.cand_cap_sb, b.multi_tab);
     }
     if (k != 0) {
         {
             ProfileScope ps(ctx, K_SPEC_FINISH);
-            ms_hist_kernel<<<MF_BLOCKS, BLOCK, k * MF_BINS1 * sizeof(uint32_t), s>>>(
+            ms_hist_kernel<<<MF_BLOCKS, MF_THREADS, k * MF_BINS1 * sizeof(uint32_t), s>>>(
                 b.multi, b.multi_cnt, b.cand, b.cand_cap_sb, b.multi_partial);
-            ms_locate_kernel<<<k, BLOCK, 0, s>>>(b.multi, b.multi_cnt, b.multi_partial, b.cand_cap_sb);
+            ms_locate_kernel<<<k, LOCATE_THREADS, 0, s>>>(b.multi, b.multi_cnt, b.multi_partial, b.cand_cap_sb);
         }
         {
             ProfileScope ps(ctx, K_SPEC_FINISH2);
-            ms_filter_kernel<<<MF_BLOCKS, BLOCK, 0, s>>>(b.multi, b.multi_cnt, b.cand, b.cand_cap_sb,
+            ms_filter_kernel<<<MF_BLOCKS, MF_THREADS, 0, s>>>(b.multi, b.multi_cnt, b.cand, b.cand_cap_sb,
                                                          b.multi_seg, b.multi_seg_cnt);
             ms_rank_kernel<<<k, BLOCK, 0, s>>>(b.multi, b.multi_seg, b.multi_seg_cnt, d_thr);
         }
