@@ -30,6 +30,12 @@
  *   - Every call enqueues its kernels on the context's stream and returns without
  *     waiting, except where a non-NULL h_* output is passed (documented per call):
  *     then the call waits for the stream and fills it.
+ *   - A call that is given no h_* output puts kernels on the stream and nothing else
+ *     (no allocation once the model is bound, no wait, no memset): such calls can be
+ *     recorded into a HIP graph by capturing the context's stream after one eager call
+ *     has bound the model.  A graph holds the pointers and prune counts of the recorded
+ *     calls, not the data.  shifter_global_threshold with h_thr = NULL is the ranking
+ *     to record: it needs no decision on the host.
  *   - Every function returns a shifter_status.  No exceptions or aborts cross the
  *     ABI; shifter_last_error() gives the text of the last failure.  Argument and
  *     descriptor errors are found on the host before anything is launched.
