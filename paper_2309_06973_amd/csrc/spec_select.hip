@@ -74,16 +74,18 @@ __host__ __device__ __forceinline__ uint32_t sample_sector(uint32_t tile, uint32
     return (tile * 37u + quarter * 11u) & 63u;
 }
 
-__global__ __launch_bounds__(BLOCK) void spec_sample_kernel(
+constexpr uint32_t SAMPLE_THREADS = 1024;   // sixteen wavefronts on the block's CU keep its loads in flight
+
+__global__ __launch_bounds__(SAMPLE_THREADS) void spec_sample_kernel(
     const DevTensor* __restrict__ tens, const uint32_t* __restrict__ tile_prefix,
     const uint16_t* __restrict__ tile_tensor, uint32_t n_tiles, uint32_t tile_stride,
     const float* __restrict__ w, uint32_t* shist) {
     __shared__ uint32_t h[SBINS];
-    for (uint32_t i = threadIdx.x; i < SBINS; i += BLOCK) h[i] = 0;
+    for (uint32_t i = threadIdx.x; i < SBINS; i += SAMPLE_THREADS) h[i] = 0;
     __syncthreads();
     const uint32_t lane = threadIdx.x & 63u;
-    const uint32_t wave = blockIdx.x * (BLOCK / 64) + (threadIdx.x >> 6);
-    const uint32_t n_waves = gridDim.x * (BLOCK / 64);
+    const uint32_t wave = blockIdx.x * (SAMPLE_THREADS / 64) + (threadIdx.x >> 6);
+    const uint32_t n_waves = gridDim.x * (SAMPLE_THREADS / 64);
     const uint32_t quarter = (lane >> 2) & 3u, part = lane & 3u;
     // address of this lane's four samples of sampled tile s, or nullptr; the tensor of a
     // tile comes from a table (one load instead of a search per lane)
@@ -126,7 +128,7 @@ __global__ __launch_bounds__(BLOCK) void spec_sample_kernel(
         count(pb, xb);
     }
     __syncthreads();
-    for (uint32_t i = threadIdx.x; i < SBINS; i += BLOCK) {
+    for (uint32_t i = threadIdx.x; i < SBINS; i += SAMPLE_THREADS) {
         const uint32_t c = h[i];
         if (c) atomicAdd(&shist[i], c);
     }
@@ -686,9 +688,10 @@ void launch_spec_sample(shifter_ctx* ctx, const shifter_model* m, const float* d
     const auto& b = m->b;
     const uint32_t sampled = (m->n_tiles + m->sample_tile_stride - 1) / m->sample_tile_stride;
     // one block per CU: more blocks shorten the loop but every block flushes its LDS
-    // histogram with global atomics (measured 22 us at 256 blocks, 24 at 512, 34 at 128 or 1024)
-    const uint32_t grid = std::min(256u, (sampled + 15) / 16);   // 16 tiles per block and step
-    spec_sample_kernel<<<grid, BLOCK, 0, ctx->stream>>>(b.tens, b.tile_prefix, b.tile_tensor,
+    // histogram with global atomics (measured with 256-thread blocks: 22 us at 256 blocks,
+    // 24 at 512, 34 at 128 or 1024; 1024-thread blocks brought the 256 to 15 us)
+    const uint32_t grid = std::min(256u, (sampled + 63) / 64);   // 64 tiles per block and step
+    spec_sample_kernel<<<grid, SAMPLE_THREADS, 0, ctx->stream>>>(b.tens, b.tile_prefix, b.tile_tensor,
                                                         m->n_tiles, m->sample_tile_stride, d_w,
                                                         b.shist);
 }
