@@ -227,3 +227,57 @@ def test_portfolio_at_the_largest_index_space(big):
             assert kept == n - ps[k]
     finally:
         pl.close()
+
+
+def test_codec_beyond_4_gib(big):
+    """The codec on 17 GB buffers: chunk, segment and stream offsets past 2^32.  The sparse
+    arena (95 % zeros) gives a stream below 4 GiB from an input above it; the dense one
+    is stored, so its stream runs past 4 GiB too.  Each is inflated back on the device, and
+    sampled segments (first, last, around the 4 GiB marks) are the oracle's, byte for
+    byte."""
+    from oracle import deflate_oracle as D
+    from paper_2309_06973_amd.pipeline import Codec
+    spec, w, v, _ = big
+    n_bytes = w.numel() * 4
+    C_ = D.CHUNK
+    n_chunks = (n_bytes + C_ - 1) // C_
+    mark = (1 << 32) // C_                                  # first chunk past 4 GiB of input
+    codec = Codec()
+    try:
+        for kind in ("sparse", "dense"):
+            if kind == "sparse":
+                data = torch.where(w.abs() < 2.0, torch.zeros((), device=w.device), w)
+            else:
+                data = w
+            pkg = codec.deflate(data)
+            seg_off = pkg.seg_off.cpu().numpy()
+            assert int(seg_off[0]) == 0 and int(seg_off[-1]) == pkg.stream_bytes
+            assert np.all(np.diff(seg_off.astype(np.int64)) >= 5)
+            if kind == "sparse":
+                assert 8 < n_bytes / pkg.stream_bytes < 40 and pkg.stream_bytes < (1 << 32)
+            else:
+                # (the quantised stretch of the arena compresses a little; the rest is stored)
+                assert 0.99 * n_bytes < pkg.stream_bytes <= n_bytes + 5 * n_chunks
+                assert pkg.stream_bytes > (1 << 32)
+            out = codec.inflate(pkg)
+            assert torch.equal(out[:n_bytes].view(torch.int32), data.view(torch.int32))
+            del out
+            raw = data.view(torch.uint8)
+            past = int(np.searchsorted(seg_off, 1 << 32))   # first segment past 4 GiB of stream
+            picks = {0, 1, mark - 1, mark, mark + 1, n_chunks // 2, 3 * mark, n_chunks - 2,
+                     n_chunks - 1}
+            if kind == "dense":
+                picks |= {past - 1, past, past + 1}
+            for c in sorted(p for p in picks if 0 <= p < n_chunks):
+                piece = raw[c * C_:(c + 2) * C_].cpu().numpy().tobytes()
+                ref_stream, ref_off, ref_side = D.deflate_runs(piece)
+                side = pkg.sub_bits[c * 64:(c + 1) * 64].cpu().numpy().view(np.uint16).tolist()
+                assert side == ref_side[:64], (kind, c)
+                a, b = int(seg_off[c]), int(seg_off[c + 1])
+                got = pkg.stream[a:b].cpu().numpy().tobytes()
+                want = ref_stream[:ref_off[1]] if c < n_chunks - 1 else ref_stream
+                assert got == want, (kind, c)
+            del pkg, data, raw
+            torch.cuda.empty_cache()
+    finally:
+        codec.close()
