@@ -604,3 +604,41 @@ def test_batch_of_the_maximum_number_of_variants():
     counts[5] = 0
     counts[40] = counts[41]          # equal counts in two variants
     check_batch(spec, w, v, counts, check=[0, 5, 33, 40, 41, 63])
+
+
+@pytest.mark.gpu
+def test_two_contexts_on_two_streams_interleaved():
+    """Contexts are independent: two networks on two streams, their calls enqueued in turn
+    without waiting in between, each result the oracle's."""
+    jobs = []
+    for c, s in ((3, 0.9), (1, 0.8)):
+        spec, w, v = synth.generate_config(c)
+        p = synth.prune_count(spec.n_prunable, s)
+        ref = O.prune_and_compact(w, v, spec.tensors, spec.vecs, spec.groups, [p], 0)[0]
+        stream = torch.cuda.Stream()
+        with torch.cuda.stream(stream):
+            pl = Pipeline(spec, w, v)
+        jobs.append((spec, w, v, p, ref, stream, pl))
+    try:
+        for rounds in range(3):
+            for spec, w, v, p, ref, stream, pl in jobs:
+                with torch.cuda.stream(stream):
+                    pl.d_w_sparse.fill_(float("nan"))
+                    pl.prune_fused(p, defer=True)
+                    pl.propagate_groups(0, sync=False)
+            outs = []
+            for spec, w, v, p, ref, stream, pl in jobs:
+                outs.append(pl.compact(sync=True))
+            for (spec, w, v, p, ref, stream, pl), (rc, ot, ov, ew, ev) in zip(jobs, outs):
+                rec, redone = pl.prune_result()
+                assert not redone
+                a = np.abs(O.gather_prunable(w, spec.tensors))
+                check_threshold(rec, ref.sel, a)
+                assert ew == ref.compacted.w.size and ev == ref.compacted.v.size
+                assert np.array_equal(bits(pl.d_w_out[:ew].cpu().numpy()), bits(ref.compacted.w))
+                assert np.array_equal(bits(pl.d_vecs_out[:ev].cpu().numpy()), bits(ref.compacted.v))
+                assert np.array_equal(bits(pl.d_w_sparse.cpu().numpy()[:spec.w_elems]),
+                                      bits(ref.w_sparse[:spec.w_elems]))
+    finally:
+        for job in jobs:
+            job[-1].close()
