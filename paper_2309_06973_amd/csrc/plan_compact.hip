@@ -447,29 +447,46 @@ __global__ __launch_bounds__(BLOCK) void gather_rect_kernel(
         }
         if (threadIdx.x == 0) next_k = 0;
         // stage rows r0 .. r0 + nr, columns c_base .. c_base + wsrc: a row takes 1 << lgt
-        // threads (16 bytes each), so the block covers BLOCK >> lgt rows per round
+        // threads (16 bytes each), so the block covers BLOCK >> lgt rows per round.  The
+        // loads of eight rounds go out back to back before the first is written to LDS (one
+        // trip for all but the odd shapes that pad a row to twice its threads)
         {
             const uint32_t qpr = (wsrc + 3u) >> 2;
             uint32_t lgt = 0;
             while ((1u << lgt) < qpr) ++lgt;
             const uint32_t c = (threadIdx.x & ((1u << lgt) - 1u)) * 4u;
+            const uint32_t rstep = BLOCK >> lgt;
+            constexpr uint32_t S = 8;
             if (c < wsrc) {
                 float* d = tile + rect_swizzle(c);
-                for (uint32_t r = threadIdx.x >> lgt; r < nr; r += BLOCK >> lgt) {
-                    const uint64_t gi = T.offset + (uint64_t)(r0 + r) * row_len + c_base + c;
-                    float x0, x1, x2, x3;
-                    if (gi + 3 < w_extent) {
-                        const float4_a4 x = *reinterpret_cast<const float4_a4*>(w + gi);
-                        x0 = x.x; x1 = x.y; x2 = x.z; x3 = x.w;
-                    } else {
-                        x0 = w[gi];
-                        x1 = gi + 1 < w_extent ? w[gi + 1] : 0.0f;
-                        x2 = gi + 2 < w_extent ? w[gi + 2] : 0.0f;
-                        x3 = 0.0f;
+                for (uint32_t rb = threadIdx.x >> lgt; rb < nr; rb += S * rstep) {
+                    float4_a4 x[S];
+#pragma unroll
+                    for (uint32_t i = 0; i < S; ++i) {
+                        const uint32_t r = rb + i * rstep;
+                        const uint64_t gi = T.offset + (uint64_t)(r0 + r) * row_len + c_base + c;
+                        x[i] = float4_a4{0.0f, 0.0f, 0.0f, 0.0f};
+                        if (r < nr && gi + 3 < w_extent) x[i] = *reinterpret_cast<const float4_a4*>(w + gi);
+                    }
+#pragma unroll
+                    for (uint32_t i = 0; i < S; ++i) {
+                        const uint32_t r = rb + i * rstep;
+                        const uint64_t gi = T.offset + (uint64_t)(r0 + r) * row_len + c_base + c;
+                        if (r < nr && gi + 3 >= w_extent) {   // the last floats of the arena
+                            x[i].x = w[gi];
+                            if (gi + 1 < w_extent) x[i].y = w[gi + 1];
+                            if (gi + 2 < w_extent) x[i].z = w[gi + 2];
+                        }
                     }
                     // columns c .. c + 3 share (c & ~127) and (c >> 2) & 31: positions 32 apart
-                    float* dr = d + r * wp;
-                    dr[0] = x0; dr[32] = x1; dr[64] = x2; dr[96] = x3;
+#pragma unroll
+                    for (uint32_t i = 0; i < S; ++i) {
+                        const uint32_t r = rb + i * rstep;
+                        if (r < nr) {
+                            float* dr = d + r * wp;
+                            dr[0] = x[i].x; dr[32] = x[i].y; dr[64] = x[i].z; dr[96] = x[i].w;
+                        }
+                    }
                 }
             }
         }
