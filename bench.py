@@ -165,6 +165,15 @@ def measure(name, steps, warmup, lean_run=True, cpu_leg=True):
     # each variant reads 4N, writes 4N sparse + N mask, and moves 4N' in and 4N' out
     b_alg = 4 * n + sum(9 * n + 8 * n2 for n2 in kept)
     gbs = b_alg / (dt / steps) / 1e9
+    # what this path has to move at the least: one variant rides the ranking on the mask
+    # pass (9N + 8N'); a portfolio reads the arena once per pass over it (ranking and
+    # masks: one fused pass or two), writes K sparse arenas and masks, and the rebuild
+    # reads the dense arena once more for all variants and writes the survivors
+    if k_var == 1:
+        b_moved = 9 * n + 8 * kept[0]
+    else:
+        fused_batch = pl.model.info.w_extent * 4 > (192 << 20)      # pipeline.portfolio's choice
+        b_moved = (4 * n) * (1 if fused_batch else 2) + 5 * n * k_var + 4 * n + 4 * sum(kept)
 
     # dominant kernel: HIP events around each launch, on the stream the kernels run on,
     # over a second timed run of the same steps
@@ -365,6 +374,11 @@ def measure(name, steps, warmup, lean_run=True, cpu_leg=True):
                    "sparsities": [round(s, 5) for s in sparsities],
                    "kept_weights": kept, "algorithmic_bytes_per_step": b_alg},
         "pct_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
+        # `value` credits every variant with its own read of the weights (the metric's
+        # definition); the bytes this path must really move per step are fewer
+        "bytes_moved_per_step": b_moved,
+        "moved_gbs": round(b_moved / (dt / steps) / 1e9, 2),
+        "moved_pct_hbm_peak": round(100.0 * b_moved / (dt / steps) / 1e9 / HBM_PEAK_GBS, 2),
         "variants_per_s": round(k_var / (dt / steps), 2),
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
