@@ -642,3 +642,15 @@ def test_two_contexts_on_two_streams_interleaved():
     finally:
         for job in jobs:
             job[-1].close()
+
+
+@pytest.mark.gpu
+def test_paper_portfolio_of_compression_ratios_2_to_256():
+    """The paper's own portfolio setting (Sec. IV-B.1: n = 8 variants, each twice as
+    compressed as the one before, up to compression ratio 2^8 = 256) on the VGG-16 /
+    CIFAR-10 shape, the batched path against the oracle."""
+    spec, w, v = synth.generate_config(2)
+    n = spec.n_prunable
+    ps = [synth.prune_count(n, 1.0 - 1.0 / (1 << k)) for k in range(1, 9)]
+    assert n - ps[-1] == int(np.floor(n / 256 + 0.5))
+    check_batch(spec, w, v, ps, check=[0, 3, 7])
