@@ -178,6 +178,30 @@ int shifter_global_threshold(shifter_ctx* ctx, const shifter_model* model,
                              const float* d_w, const uint64_t* h_n_prune, uint32_t K,
                              shifter_threshold* d_thr, shifter_threshold* h_thr);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving or training loops, harnesses that forbid it): the ranking of
+ * shifter_global_threshold for ONE flat run of n weights (global index = element index; a
+ * single tensor's weights, or an arena without gaps), with no model and no allocation.  It
+ * calls no hipMalloc / hipFree and no allocating routine, puts only kernels on the
+ * context's stream (no wait, no copy, no memset) and keeps its tables, histograms and
+ * per-tile counts in a device array that is part of the library's code object: about
+ * 4.7 MB that every GPU the library runs on holds until the process ends.
+ *   d_w        device, n floats, 16-byte aligned, read only (may be NULL when n = 0)
+ *   h_n_prune  host, K prune counts, each <= n; 1 <= K <= SHIFTER_MAX_VARIANTS
+ *   d_thr      device, K records, written (same records as shifter_global_threshold's
+ *              multi-pass select on a model of one prunable tensor of n weights; no NaN
+ *              report, as with h_thr = NULL there)
+ * Limits: n <= SHIFTER_STATIC_MAX_WEIGHTS and K * ceil(n / 4096) <=
+ * SHIFTER_STATIC_MAX_TILE_COUNTS, else SHIFTER_ERR_CAPACITY (nothing is enqueued).
+ * All calls on one GPU share that GPU's array, whatever their context or stream: calls
+ * that overlap in time on one GPU race; calls on one stream, or otherwise ordered, are
+ * fine.  What must start at zero is cleared by the call's first kernel. */
+#define SHIFTER_STATIC_MAX_WEIGHTS (1ull << 28)
+#define SHIFTER_STATIC_MAX_TILE_COUNTS (1ull << 20)
+int shifter_global_threshold_static(shifter_ctx* ctx, const float* d_w, uint64_t n,
+                                    const uint64_t* h_n_prune, uint32_t K,
+                                    shifter_threshold* d_thr);
+
 /* Which selection algorithm shifter_global_threshold and shifter_prune_fused may use:
  * 0 (default) the single-pass selection where it applies (waiting or two-call form,
  * at most 32 prune counts above zero), with the multi-pass radix select as its

@@ -5,6 +5,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "internal.h"
@@ -40,6 +41,31 @@ ProfileScope::~ProfileScope() {
 }  // namespace shifter
 
 static thread_local std::string g_err;
+
+// Scratch of shifter_global_threshold_static: the tables, histograms and per-tile counts of
+// the multi-pass select for one flat run of weights, in a file-scope device array instead
+// of allocated memory.  Every device the library runs on holds its own copy at its own
+// address; the name below is only a host-side handle for hipGetSymbolAddress, never a
+// pointer to pass to a kernel or a copy.
+static __device__ __align__(256) uint8_t scratch[shifter::STATIC_SCRATCH_BYTES];
+constexpr int STATIC_MAX_DEVICES = 64;
+static uint8_t* g_static_ptr[STATIC_MAX_DEVICES];   // device address of `scratch`, per device
+static std::mutex g_static_mutex;
+
+// Device address of this device's copy of the scratch array, resolved once per device with
+// that device current.
+static hipError_t static_scratch_address(int device, uint8_t** out) {
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (device < 0 || device >= STATIC_MAX_DEVICES) return hipErrorInvalidDevice;
+    if (!g_static_ptr[device]) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        g_static_ptr[device] = static_cast<uint8_t*>(p);
+    }
+    *out = g_static_ptr[device];
+    return hipSuccess;
+}
 
 static int fail(shifter_ctx* ctx, int code, const std::string& msg) {
     g_err = msg;
@@ -84,6 +110,14 @@ extern "C" int shifter_create(shifter_ctx** out, int device, void* hip_stream) {
     if (!c) return fail(nullptr, SHIFTER_ERR_OOM, "shifter_create: host allocation failed");
     c->device = device;
     c->stream = reinterpret_cast<hipStream_t>(hip_stream);
+    {
+        const hipError_t e = static_scratch_address(device, &c->static_scratch);
+        if (e != hipSuccess) {
+            delete c;
+            return fail(nullptr, SHIFTER_ERR_HIP,
+                        std::string("shifter_create: hipGetSymbolAddress(scratch): ") + hipGetErrorString(e));
+        }
+    }
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, device) == hipSuccess && prop.multiProcessorCount > 0)
         c->hist_grid = (uint32_t)prop.multiProcessorCount * 8u;
@@ -626,6 +660,43 @@ extern "C" int shifter_global_threshold(shifter_ctx* ctx, const shifter_model* m
             return fail(ctx, SHIFTER_ERR_NONFINITE, "global_threshold: NaN among the prunable weights");
     }
     return SHIFTER_OK;
+}
+
+extern "C" int shifter_global_threshold_static(shifter_ctx* ctx, const float* d_w, uint64_t n,
+                                               const uint64_t* h_n_prune, uint32_t K,
+                                               shifter_threshold* d_thr) {
+    if (!ctx) return fail(nullptr, SHIFTER_ERR_INVALID_ARG, "global_threshold_static: ctx is NULL");
+    if ((!d_w && n) || !h_n_prune || !d_thr)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "global_threshold_static: NULL pointer argument");
+    if (misaligned(d_w, 16) || misaligned(d_thr, 8))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "global_threshold_static: d_w must be 16-byte aligned");
+    if (K == 0 || K > MAXK)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "global_threshold_static: K must be in [1, SHIFTER_MAX_VARIANTS]");
+    const uint64_t n_tiles = (n + TILE - 1) / TILE;
+    if (n > STATIC_MAX_WEIGHTS || n_tiles * K > STATIC_MAX_TILE_COUNTS)
+        return fail(ctx, SHIFTER_ERR_CAPACITY,
+                    "global_threshold_static: " + std::to_string(n) + " weights and " + std::to_string(K) +
+                        " prune counts exceed the static scratch (at most " +
+                        std::to_string(STATIC_MAX_WEIGHTS) + " weights and K * ceil(n / 4096) <= " +
+                        std::to_string(STATIC_MAX_TILE_COUNTS) + ")");
+    PruneCounts pc;
+    memset(&pc, 0, sizeof pc);
+    for (uint32_t k = 0; k < K; ++k) {
+        if (h_n_prune[k] > n)
+            return fail(ctx, SHIFTER_ERR_INVALID_ARG, "global_threshold_static: prune count exceeds n");
+        pc.p[k] = h_n_prune[k];
+    }
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    uint8_t* base = ctx->static_scratch;   // the array's device address, never its name
+    DevTensor* tens = reinterpret_cast<DevTensor*>(base + STATIC_OFF_TENSOR);
+    uint32_t* prefix = reinterpret_cast<uint32_t*>(base + STATIC_OFF_PREFIX);
+    launch_flat_tables(ctx, tens, prefix, n);
+    const SelectTables tb{tens, prefix, 1u, (uint32_t)n_tiles,
+                          reinterpret_cast<SelState*>(base + STATIC_OFF_SEL),
+                          reinterpret_cast<uint32_t*>(base + STATIC_OFF_GHIST),
+                          reinterpret_cast<uint32_t*>(base + STATIC_OFF_TILE_CNT)};
+    launch_select_tables(ctx, tb, d_w, pc, K, d_thr);
+    return after_launch(ctx, "global_threshold_static");
 }
 
 // Enqueues the read-back of a ranking's outcome (a status word, then the K records) into

@@ -243,6 +243,7 @@ struct shifter_model {
 struct shifter_ctx {
     int device = 0;
     hipStream_t stream = nullptr;
+    uint8_t* static_scratch = nullptr;   // this device's copy of the library's static scratch array
     std::string err;
     bool profiling = false;
     struct Rec { int id; hipEvent_t a, b; };
@@ -290,6 +291,31 @@ namespace shifter {
 // Launchers (defined next to their kernels).  All enqueue on ctx->stream.
 void launch_select(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
                    const PruneCounts& pc, uint32_t k, shifter_threshold* d_thr);
+// The tables and scratch the multi-pass select works on: a model's, or the ones laid out in
+// the static scratch array for one flat run of weights.
+struct SelectTables {
+    const DevTensor* tens;
+    const uint32_t* tile_prefix;
+    uint32_t n_t, n_tiles;
+    SelState* sel;
+    uint32_t* ghist;      // MAXK * HIST_BINS
+    uint32_t* tile_cnt;   // k * n_tiles
+};
+void launch_select_tables(shifter_ctx* ctx, const SelectTables& tb, const float* d_w,
+                          const PruneCounts& pc, uint32_t k, shifter_threshold* d_thr);
+// Layout of the static scratch array used by shifter_global_threshold_static (byte offsets
+// from its 256-byte aligned start) and the limits that follow from its size.
+constexpr uint64_t STATIC_MAX_WEIGHTS = 1ull << 28;       // weights of one flat run
+constexpr uint64_t STATIC_MAX_TILE_COUNTS = 1ull << 20;   // K * tiles of the run
+constexpr size_t STATIC_OFF_TENSOR = 0;
+constexpr size_t STATIC_OFF_PREFIX = 256;
+constexpr size_t STATIC_OFF_SEL = 512;
+constexpr size_t STATIC_OFF_GHIST = STATIC_OFF_SEL + ((sizeof(SelState) + 255) / 256) * 256;
+constexpr size_t STATIC_OFF_TILE_CNT = STATIC_OFF_GHIST + sizeof(uint32_t) * MAXK * HIST_BINS;
+constexpr size_t STATIC_SCRATCH_BYTES = STATIC_OFF_TILE_CNT + sizeof(uint32_t) * STATIC_MAX_TILE_COUNTS;
+static_assert(sizeof(DevTensor) <= 256, "the one-tensor table fits its slot");
+// Writes the one-tensor table of a flat run of n weights (one prunable tensor at offset 0).
+void launch_flat_tables(shifter_ctx* ctx, DevTensor* tens, uint32_t* tile_prefix, uint64_t n);
 void launch_spec_select(shifter_ctx* ctx, const shifter_model* m, const float* d_w, uint64_t p,
                         shifter_threshold* d_thr, float* d_w_out, uint8_t* d_mask,
                         uint8_t* d_out_alive, uint8_t* d_in_alive);

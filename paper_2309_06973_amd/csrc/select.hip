@@ -266,53 +266,89 @@ __global__ __launch_bounds__(BLOCK) void tie_final_kernel(
     }
 }
 
+// A flat run of n weights as a one-tensor model: filter 0 of a 1 x n linear layer at
+// element 0, prunable, global index = element index.
+__global__ void flat_tables_kernel(DevTensor* tens, uint32_t* tile_prefix, uint64_t n) {
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    DevTensor d;
+    d.offset = 0;
+    d.gbase = 0;
+    d.numel = (uint32_t)n;
+    d.out_ch = 1;
+    d.in_ch = (uint32_t)n;
+    d.khw = 1;
+    d.row_len = (uint32_t)n;
+    d.kk = 1;
+    d.cin = (uint32_t)n;
+    d.magic_khw = d.magic_row = d.magic_in = d.magic_kk = d.shift_kk = 0;
+    d.out_group = 1;
+    d.in_group = 0;
+    d.out_flag_off = d.in_flag_off = 0;
+    d.prunable = 1;
+    d.band_rows = d.chunk_ch = d.src_chunks = 1;
+    tens[0] = d;
+    tile_prefix[0] = 0;
+    tile_prefix[1] = (uint32_t)((n + TILE - 1) / TILE);
+}
+
+void launch_flat_tables(shifter_ctx* ctx, DevTensor* tens, uint32_t* tile_prefix, uint64_t n) {
+    flat_tables_kernel<<<1, 64, 0, ctx->stream>>>(tens, tile_prefix, n);
+}
+
 void launch_select(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
                    const PruneCounts& pc, uint32_t k, shifter_threshold* d_thr) {
     const auto& b = m->b;
-    const uint32_t n_t = (uint32_t)m->t.size();
-    const uint32_t grid = min(m->n_tiles, ctx->hist_grid);
+    const SelectTables tb{b.tens, b.tile_prefix, (uint32_t)m->t.size(), m->n_tiles, b.sel, b.ghist,
+                          b.tile_cnt};
+    launch_select_tables(ctx, tb, d_w, pc, k, d_thr);
+}
+
+void launch_select_tables(shifter_ctx* ctx, const SelectTables& tb, const float* d_w,
+                          const PruneCounts& pc, uint32_t k, shifter_threshold* d_thr) {
+    const uint32_t n_t = tb.n_t, n_tiles = tb.n_tiles;
+    const uint32_t grid = max(1u, min(n_tiles, ctx->hist_grid));
     hipStream_t s = ctx->stream;
     {
         ProfileScope p(ctx, K_SEL_INIT);
-        sel_init_kernel<<<64, BLOCK, 0, s>>>(b.sel, b.ghist, pc, k);
+        sel_init_kernel<<<64, BLOCK, 0, s>>>(tb.sel, tb.ghist, pc, k);
     }
     {
         ProfileScope p(ctx, K_HIST0);
-        hist_kernel<0><<<grid, BLOCK, 0, s>>>(b.tens, b.tile_prefix, n_t, m->n_tiles, d_w,
-                                              b.sel, b.ghist, 0);
+        hist_kernel<0><<<grid, BLOCK, 0, s>>>(tb.tens, tb.tile_prefix, n_t, n_tiles, d_w, tb.sel,
+                                              tb.ghist, 0);
     }
     {
         ProfileScope p(ctx, K_SELECT);
-        select_kernel<<<1, BLOCK, 0, s>>>(b.sel, b.ghist, 0);
+        select_kernel<<<1, BLOCK, 0, s>>>(tb.sel, tb.ghist, 0);
     }
     const uint32_t passes = (k + SLOTS_PER_PASS - 1) / SLOTS_PER_PASS;
     for (uint32_t pass = 0; pass < passes; ++pass) {
         ProfileScope p(ctx, K_HIST1);
-        hist_kernel<1><<<grid, BLOCK, 0, s>>>(b.tens, b.tile_prefix, n_t, m->n_tiles, d_w,
-                                              b.sel, b.ghist, pass);
+        hist_kernel<1><<<grid, BLOCK, 0, s>>>(tb.tens, tb.tile_prefix, n_t, n_tiles, d_w, tb.sel,
+                                              tb.ghist, pass);
     }
     {
         ProfileScope p(ctx, K_SELECT);
-        select_kernel<<<1, BLOCK, 0, s>>>(b.sel, b.ghist, 1);
+        select_kernel<<<1, BLOCK, 0, s>>>(tb.sel, tb.ghist, 1);
     }
     for (uint32_t pass = 0; pass < passes; ++pass) {
         ProfileScope p(ctx, K_HIST2);
-        hist_kernel<2><<<grid, BLOCK, 0, s>>>(b.tens, b.tile_prefix, n_t, m->n_tiles, d_w,
-                                              b.sel, b.ghist, pass);
+        hist_kernel<2><<<grid, BLOCK, 0, s>>>(tb.tens, tb.tile_prefix, n_t, n_tiles, d_w, tb.sel,
+                                              tb.ghist, pass);
     }
     {
         ProfileScope p(ctx, K_SELECT);
-        select_kernel<<<1, BLOCK, 0, s>>>(b.sel, b.ghist, 2);
+        select_kernel<<<1, BLOCK, 0, s>>>(tb.sel, tb.ghist, 2);
     }
     {
         ProfileScope p(ctx, K_TIE_COUNT);
-        tie_count_kernel<<<grid, BLOCK, 0, s>>>(b.tens, b.tile_prefix, n_t, m->n_tiles, d_w,
-                                                b.sel, b.tile_cnt);
+        tie_count_kernel<<<grid, BLOCK, 0, s>>>(tb.tens, tb.tile_prefix, n_t, n_tiles, d_w, tb.sel,
+                                                tb.tile_cnt);
     }
     {
         ProfileScope p(ctx, K_TIE_FINAL);
-        tie_final_kernel<<<k, BLOCK, 0, s>>>(b.tens, b.tile_prefix, n_t, m->n_tiles, d_w,
-                                             b.sel, b.tile_cnt, pc, d_thr);
+        tie_final_kernel<<<k, BLOCK, 0, s>>>(tb.tens, tb.tile_prefix, n_t, n_tiles, d_w, tb.sel,
+                                             tb.tile_cnt, pc, d_thr);
     }
 }
 

@@ -77,6 +77,8 @@ EXPORTS = {
     "shifter_global_threshold": [C.c_void_p, C.c_void_p, C.c_void_p,
                                  C.POINTER(C.c_uint64), C.c_uint32, C.c_void_p,
                                  C.POINTER(Threshold)],
+    "shifter_global_threshold_static": [C.c_void_p, C.c_void_p, C.c_uint64,
+                                        C.POINTER(C.c_uint64), C.c_uint32, C.c_void_p],
     "shifter_global_threshold_begin": [C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.POINTER(C.c_uint64), C.c_uint32, C.c_void_p],
     "shifter_global_threshold_end": [C.c_void_p, C.POINTER(Threshold), C.POINTER(C.c_int)],
@@ -251,6 +253,20 @@ def shifter_global_threshold(ctx: Context, model: Model, d_w, n_prune: Sequence[
     _check(load_library().shifter_global_threshold(ctx.handle, model.handle, _ptr(d_w), arr, k,
                                                    _ptr(d_thr), h), ctx.handle)
     return list(h)[:k] if sync else None
+
+
+SHIFTER_STATIC_MAX_WEIGHTS = 1 << 28
+SHIFTER_STATIC_MAX_TILE_COUNTS = 1 << 20
+
+
+def shifter_global_threshold_static(ctx: Context, d_w, n: int, n_prune: Sequence[int],
+                                    d_thr) -> None:
+    """The ranking for one flat run of n weights, no model, no allocation, enqueue only.
+    d_thr: uint8 device tensor of len(n_prune) * THRESHOLD_BYTES bytes."""
+    k = len(n_prune)
+    arr = (C.c_uint64 * max(k, 1))(*[int(p) for p in n_prune])
+    _check(load_library().shifter_global_threshold_static(ctx.handle, _ptr(d_w), int(n), arr, k,
+                                                          _ptr(d_thr)), ctx.handle)
 
 
 def shifter_set_select_path(ctx: Context, path: int) -> None:
