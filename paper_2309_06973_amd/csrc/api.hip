@@ -144,19 +144,18 @@ static void unbind(shifter_model* m) {
     if (!b.ctx) return;
     (void)hipSetDevice(b.device);
     void* ptrs[] = {b.tens, b.groups, b.vecs, b.producers, b.tile_prefix, b.tile_tensor, b.sel,
-                    b.ghist, b.tile_cnt, b.plan_t, b.plan_v, b.plan_h, b.plan_pack,
+                    b.ghist, b.tile_cnt, b.plan_t, b.plan_v, b.plan_h,
                     b.out_tile_prefix, b.rect_prefix, b.rowtab_prefix, b.coltab_prefix, b.rowtab,
                     b.coltab, b.kernel_off, b.fix_prefix, b.cons_prefix, b.consumers, b.fix_alive,
                     b.fix_produced, b.fix_read, b.fix_out_flags, b.fix_removed, b.fold,
                     b.fold_scale, b.levels, b.spec, b.shist, b.spec_cnt, b.partial, b.cand, b.list,
-                    b.ranked_ids, b.multi, b.multi_cnt, b.multi_tab, b.multi_partial,
-                    b.multi_seg,
-                    b.multi_seg_cnt};
+                    b.ranked_ids, b.multi, b.multi_cnt, b.multi_tab, b.plan_done};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     if (b.host_stage) (void)hipHostFree(b.host_stage);
     if (b.host_spec) (void)hipHostFree(b.host_spec);
     if (b.host_multi) (void)hipHostFree(b.host_multi);
+    if (b.host_plan) (void)hipHostFree(b.host_plan);
     b = shifter_model::Bound();
 }
 
@@ -485,8 +484,6 @@ static int bind_tables(shifter_ctx* ctx, shifter_model* m) {
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.plan_t), sizeof(PlanTensor) * n_t * MAXK));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.plan_v), sizeof(PlanVec) * std::max<size_t>(n_v, 1) * MAXK));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.plan_h), sizeof(PlanHeader) * MAXK));
-    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.plan_pack),
-                           (sizeof(PlanHeader) + sizeof(PlanTensor) * n_t + sizeof(PlanVec) * n_v) * MAXK));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.out_tile_prefix), sizeof(uint32_t) * (n_t + 1) * MAXK));
     if ((rc = upload(ctx, &b.kernel_off, m->kernel_off.data(), m->kernel_off.size()))) return rc;
     if ((rc = upload(ctx, &b.fix_prefix, m->fix_prefix.data(), m->fix_prefix.size()))) return rc;
@@ -504,7 +501,9 @@ static int bind_tables(shifter_ctx* ctx, shifter_model* m) {
                            sizeof(uint32_t) * (m->info.sum_out_ch + m->info.sum_in_ch)));
     if ((rc = upload(ctx, &b.ranked_ids, m->ranked_ids.data(), m->ranked_ids.size()))) return rc;
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.spec), sizeof(SpecState)));
+    // every ranking reads the sample histogram and leaves it cleared for the next one
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.shist), sizeof(uint32_t) * 65536));
+    HIP_TRY(ctx, hipMemset(b.shist, 0, sizeof(uint32_t) * 65536));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.spec_cnt), sizeof(uint32_t) * 2 * SPEC_SUB * 32));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.partial), sizeof(uint32_t) * SPEC_FIN_BLOCKS * 256));
     // candidate pairs: 1/4 of N in total (a 20-variant portfolio on a mid-size model makes
@@ -513,13 +512,10 @@ static int bind_tables(shifter_ctx* ctx, shifter_model* m) {
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.cand), sizeof(uint2) * (size_t)b.cand_cap_sb * SPEC_SUB));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.list), sizeof(uint2) * SPEC_LIST_CAP));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.multi), sizeof(MultiState)));
-    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.multi_cnt), sizeof(uint32_t) * (MAXK + 2) * SPEC_SUB * 32));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.multi_cnt), sizeof(uint32_t) * (2 * MAXK + 1) * SPEC_SUB * 32));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.multi_tab), 4096));
-    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.multi_partial),
-                           sizeof(uint32_t) * SPEC_SUB * SPEC_MULTI_MAXK * 256));
-    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.multi_seg),
-                           sizeof(uint2) * (size_t)SPEC_MULTI_MAXK * SPEC_SUB * SPEC_SEG_CAP));
-    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.multi_seg_cnt), sizeof(uint32_t) * SPEC_MULTI_MAXK * SPEC_SUB));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.plan_done), sizeof(uint32_t) * MAXK));
+    HIP_TRY(ctx, hipMemset(b.plan_done, 0, sizeof(uint32_t) * MAXK));
     b.host_stage_bytes = sizeof(SelState) + sizeof(shifter_threshold) * MAXK +
                          MAXK * (sizeof(PlanHeader) + sizeof(PlanTensor) * n_t + sizeof(PlanVec) * n_v +
                                  sizeof(uint32_t) * m->g.size()) +
@@ -527,8 +523,22 @@ static int bind_tables(shifter_ctx* ctx, shifter_model* m) {
     HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&b.host_stage), b.host_stage_bytes, hipHostMallocDefault));
     HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&b.host_spec),
                                sizeof(SpecState), hipHostMallocDefault));
+    // mirrors written by kernels: host-coherent pinned memory, addressed through its device pointer
+    const size_t plan_stride = sizeof(PlanHeader) + sizeof(PlanTensor) * n_t + sizeof(PlanVec) * n_v;
     HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&b.host_multi),
-                               64 + sizeof(shifter_threshold) * MAXK, hipHostMallocDefault));
+                               MULTI_MIRROR_REC_OFF + sizeof(shifter_threshold) * MAXK,
+                               hipHostMallocMapped | hipHostMallocCoherent));
+    HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&b.host_plan), plan_stride * MAXK,
+                               hipHostMallocMapped | hipHostMallocCoherent));
+    memset(b.host_multi, 0, MULTI_MIRROR_REC_OFF + sizeof(shifter_threshold) * MAXK);
+    memset(b.host_plan, 0, plan_stride * MAXK);
+    void* dp = nullptr;
+    HIP_TRY(ctx, hipHostGetDevicePointer(&dp, b.host_multi, 0));
+    b.dev_multi_status = reinterpret_cast<uint32_t*>(dp);
+    b.dev_multi_rec = reinterpret_cast<shifter_threshold*>(static_cast<uint8_t*>(dp) + MULTI_MIRROR_REC_OFF);
+    HIP_TRY(ctx, hipHostGetDevicePointer(&dp, b.host_plan, 0));
+    b.dev_plan = static_cast<uint8_t*>(dp);
+    HIP_TRY(ctx, hipDeviceSynchronize());     // the memsets above are done before any kernel of the model
     return SHIFTER_OK;
 }
 
@@ -586,6 +596,27 @@ static int spec_result(shifter_ctx* ctx, const shifter_model* model, shifter_thr
     return spec_result_collect(ctx, model->b.host_stage, h_thr, decided);
 }
 
+// Waits for the stream and evaluates the outcome of the K-rank single pass, which its
+// kernels left in the model's pinned mirror: one status word per sorted rank (bit 0: could
+// not decide, bit 1: NaN) and the K records.
+static int multi_result(shifter_ctx* ctx, const shifter_model* model, uint32_t k_eff, uint32_t K,
+                        shifter_threshold* h_thr, int* decided, const char* fn) {
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    const uint32_t* hs = reinterpret_cast<const uint32_t*>(model->b.host_multi);
+    uint32_t status = 0;
+    for (uint32_t k = 0; k < k_eff; ++k) status |= hs[k];
+    if (status & 2u)
+        return fail(ctx, SHIFTER_ERR_NONFINITE, std::string(fn) + ": NaN among the prunable weights");
+    ctx->last_path = (status & 1u) ? 2 : 1;
+    *decided = (status & 1u) ? 0 : 1;
+    if (*decided) {
+        if (h_thr) memcpy(h_thr, model->b.host_multi + MULTI_MIRROR_REC_OFF, sizeof(shifter_threshold) * K);
+    } else if (ctx->margin_sigmas < 64.0) {
+        ctx->margin_sigmas *= 2.0;
+    }
+    return SHIFTER_OK;
+}
+
 extern "C" int shifter_global_threshold(shifter_ctx* ctx, const shifter_model* model,
                                         const float* d_w, const uint64_t* h_n_prune, uint32_t K,
                                         shifter_threshold* d_thr, shifter_threshold* h_thr) {
@@ -629,20 +660,9 @@ extern "C" int shifter_global_threshold(shifter_ctx* ctx, const shifter_model* m
             for (uint32_t i = 0; i < k_eff; ++i) { sp.p[i] = pc.p[idx[i]]; perm.v[i] = idx[i]; }
             launch_spec_multi(ctx, model, d_w, sp, perm, k_eff, zero_mask, d_thr, nullptr);
             if ((rc = after_launch(ctx, "global_threshold"))) return rc;
-            uint8_t* st = model->b.host_stage;
-            HIP_TRY(ctx, hipMemcpyAsync(st, &model->b.multi->status, sizeof(uint32_t), hipMemcpyDeviceToHost, ctx->stream));
-            HIP_TRY(ctx, hipMemcpyAsync(st + 64, d_thr, sizeof(shifter_threshold) * K, hipMemcpyDeviceToHost, ctx->stream));
-            HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
-            uint32_t status;
-            memcpy(&status, st, sizeof status);
-            if (status & 2u)
-                return fail(ctx, SHIFTER_ERR_NONFINITE, "global_threshold: NaN among the prunable weights");
-            ctx->last_path = (status & 1u) ? 2 : 1;
-            if (!(status & 1u)) {
-                memcpy(h_thr, st + 64, sizeof(shifter_threshold) * K);
-                return SHIFTER_OK;
-            }
-            if (ctx->margin_sigmas < 64.0) ctx->margin_sigmas *= 2.0;
+            int decided = 0;
+            if ((rc = multi_result(ctx, model, k_eff, K, h_thr, &decided, "global_threshold"))) return rc;
+            if (decided) return SHIFTER_OK;
         }
     }
     launch_select(ctx, model, d_w, pc, K, d_thr);
@@ -705,7 +725,8 @@ static int rank_result_enqueue(shifter_ctx* ctx, const shifter_model* model, con
                                const shifter_threshold* d_thr, uint32_t K) {
     uint8_t* st = model->b.host_multi;
     HIP_TRY(ctx, hipMemcpyAsync(st, d_status, sizeof(uint32_t), hipMemcpyDeviceToHost, ctx->stream));
-    HIP_TRY(ctx, hipMemcpyAsync(st + 64, d_thr, sizeof(shifter_threshold) * K, hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipMemcpyAsync(st + MULTI_MIRROR_REC_OFF, d_thr, sizeof(shifter_threshold) * K,
+                                hipMemcpyDeviceToHost, ctx->stream));
     return SHIFTER_OK;
 }
 
@@ -743,9 +764,10 @@ extern "C" int shifter_global_threshold_begin(shifter_ctx* ctx, const shifter_mo
         memset(&perm, 0, sizeof perm);
         std::stable_sort(idx, idx + k_eff, [&](uint32_t a, uint32_t b) { return pr.pc.p[a] < pr.pc.p[b]; });
         for (uint32_t i = 0; i < k_eff; ++i) { sp.p[i] = pr.pc.p[idx[i]]; perm.v[i] = idx[i]; }
+        // the kernels leave the outcome in the pinned mirror themselves
         launch_spec_multi(ctx, model, d_w, sp, perm, k_eff, zero_mask, d_thr, nullptr);
         if ((rc = after_launch(ctx, "global_threshold_begin"))) return rc;
-        if ((rc = rank_result_enqueue(ctx, model, &model->b.multi->status, d_thr, K))) return rc;
+        pr.k_eff = k_eff;
     } else {
         launch_select(ctx, model, d_w, pr.pc, K, d_thr);
         if ((rc = after_launch(ctx, "global_threshold_begin"))) return rc;
@@ -767,35 +789,28 @@ extern "C" int shifter_global_threshold_end(shifter_ctx* ctx, shifter_threshold*
     pr.active = false;
     if (h_redone) *h_redone = 0;
     HIP_TRY(ctx, hipSetDevice(ctx->device));
-    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     const shifter_model* model = pr.model;
     uint8_t* st = model->b.host_multi;
     uint32_t status;
-    memcpy(&status, st, sizeof status);
     if (pr.single_pass) {
-        if (status & 2u)
-            return fail(ctx, SHIFTER_ERR_NONFINITE, "global_threshold_end: NaN among the prunable weights");
-        ctx->last_path = (status & 1u) ? 2 : 1;
-        if (status & 1u) {
-            // the single pass could not decide: the multi-pass select, and the caller repeats
-            // what it had enqueued behind the ranking
-            if (ctx->margin_sigmas < 64.0) ctx->margin_sigmas *= 2.0;
-            launch_select(ctx, model, pr.d_w, pr.pc, pr.k, pr.d_thr);
-            int rc = after_launch(ctx, "global_threshold_end");
-            if (rc) return rc;
-            if ((rc = rank_result_enqueue(ctx, model, &model->b.sel->nan_seen, pr.d_thr, pr.k))) return rc;
-            HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
-            memcpy(&status, st, sizeof status);
-            if (status)
-                return fail(ctx, SHIFTER_ERR_NONFINITE, "global_threshold_end: NaN among the prunable weights");
-            if (h_redone) *h_redone = 1;
-        }
+        int decided = 0;
+        int rc = multi_result(ctx, model, pr.k_eff, pr.k, h_thr, &decided, "global_threshold_end");
+        if (rc) return rc;
+        if (decided) return SHIFTER_OK;
+        // the single pass could not decide: the multi-pass select, and the caller repeats
+        // what it had enqueued behind the ranking
+        launch_select(ctx, model, pr.d_w, pr.pc, pr.k, pr.d_thr);
+        if ((rc = after_launch(ctx, "global_threshold_end"))) return rc;
+        if ((rc = rank_result_enqueue(ctx, model, &model->b.sel->nan_seen, pr.d_thr, pr.k))) return rc;
+        if (h_redone) *h_redone = 1;
     } else {
         ctx->last_path = 2;
-        if (status)
-            return fail(ctx, SHIFTER_ERR_NONFINITE, "global_threshold_end: NaN among the prunable weights");
     }
-    if (h_thr) memcpy(h_thr, st + 64, sizeof(shifter_threshold) * pr.k);
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    memcpy(&status, st, sizeof status);
+    if (status)
+        return fail(ctx, SHIFTER_ERR_NONFINITE, "global_threshold_end: NaN among the prunable weights");
+    if (h_thr) memcpy(h_thr, st + MULTI_MIRROR_REC_OFF, sizeof(shifter_threshold) * pr.k);
     return SHIFTER_OK;
 }
 
@@ -998,20 +1013,9 @@ extern "C" int shifter_prune_fused_batch(shifter_ctx* ctx, const shifter_model* 
         FusedBatch fb{K, d_w_out, w_stride, d_mask, mask_stride, d_out_alive, d_in_alive};
         launch_spec_multi(ctx, model, d_w, sp, perm, k_eff, zero_mask, d_thr, &fb);
         if ((rc = after_launch(ctx, "prune_fused_batch"))) return rc;
-        uint8_t* st = model->b.host_stage;
-        HIP_TRY(ctx, hipMemcpyAsync(st, &model->b.multi->status, sizeof(uint32_t), hipMemcpyDeviceToHost, ctx->stream));
-        HIP_TRY(ctx, hipMemcpyAsync(st + 64, d_thr, sizeof(shifter_threshold) * K, hipMemcpyDeviceToHost, ctx->stream));
-        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
-        uint32_t status;
-        memcpy(&status, st, sizeof status);
-        if (status & 2u)
-            return fail(ctx, SHIFTER_ERR_NONFINITE, "prune_fused_batch: NaN among the prunable weights");
-        ctx->last_path = (status & 1u) ? 2 : 1;
-        if (!(status & 1u)) {
-            memcpy(h_thr, st + 64, sizeof(shifter_threshold) * K);
-            return SHIFTER_OK;
-        }
-        if (ctx->margin_sigmas < 64.0) ctx->margin_sigmas *= 2.0;
+        int decided = 0;
+        if ((rc = multi_result(ctx, model, k_eff, K, h_thr, &decided, "prune_fused_batch"))) return rc;
+        if (decided) return SHIFTER_OK;
     }
     // the single pass could not decide (or is switched off, or too many counts): rank with
     // the multi-pass select, then mask and scan
@@ -1182,6 +1186,52 @@ extern "C" int shifter_fold_bn(shifter_ctx* ctx, const shifter_model* model,
     return after_launch(ctx, "fold_bn");
 }
 
+// The plans of K variants, read from the pinned mirror the planning kernel wrote (the stream
+// must have been waited for): descriptors and sizes of the rebuilt tensors and vectors, and
+// the status they imply.
+static int plan_readout(shifter_ctx* ctx, const shifter_model* model, uint32_t K,
+                        shifter_tensor_desc* h_out_tensors, shifter_vec_desc* h_out_vecs,
+                        uint64_t* h_elems_w, uint64_t* h_elems_v) {
+    const size_t n_t = model->t.size(), n_v = model->v.size();
+    const uint8_t* st = model->b.host_plan;
+    const size_t stride = sizeof(PlanHeader) + sizeof(PlanTensor) * n_t + sizeof(PlanVec) * n_v;
+    auto hh = [&](uint32_t k) { return reinterpret_cast<const PlanHeader*>(st + stride * k); };
+    auto ht = [&](uint32_t k) { return reinterpret_cast<const PlanTensor*>(st + stride * k + sizeof(PlanHeader)); };
+    auto hv = [&](uint32_t k) {
+        return reinterpret_cast<const PlanVec*>(st + stride * k + sizeof(PlanHeader) + sizeof(PlanTensor) * n_t);
+    };
+    uint32_t status = 0;
+    for (uint32_t k = 0; k < K; ++k) {
+        status |= hh(k)->status;
+        if (h_elems_w) h_elems_w[k] = hh(k)->elems_w;
+        if (h_elems_v) h_elems_v[k] = hh(k)->elems_v;
+        if (h_out_tensors) {
+            for (size_t i = 0; i < n_t; ++i) {
+                shifter_tensor_desc d = model->t[i];
+                d.offset = ht(k)[i].out_off;
+                d.out_ch = ht(k)[i].o2;
+                d.in_ch = ht(k)[i].c2 * d.in_mult;
+                h_out_tensors[k * n_t + i] = d;
+            }
+        }
+        if (h_out_vecs) {
+            for (size_t i = 0; i < n_v; ++i) {
+                shifter_vec_desc d = model->v[i];
+                d.offset = hv(k)[i].out_off;
+                d.len = hv(k)[i].len2;
+                h_out_vecs[k * n_v + i] = d;
+            }
+        }
+    }
+    if (status & 1u)
+        return fail(ctx, SHIFTER_ERR_CAPACITY, "compact: output capacity too small; nothing gathered");
+    if (status & 2u) {
+        fail(ctx, SHIFTER_WARN_COLLAPSE, "compact: a group kept no channel (layer collapse)");
+        return SHIFTER_WARN_COLLAPSE;
+    }
+    return SHIFTER_OK;
+}
+
 // d_thr == NULL: d_w holds K sparse arenas w_stride apart; else d_w is the dense arena
 // (w_stride 0) and variant k is masked by d_thr[k] while it is gathered.
 static int compact_impl(shifter_ctx* ctx, const shifter_model* model, const float* d_w_sparse,
@@ -1192,7 +1242,7 @@ static int compact_impl(shifter_ctx* ctx, const shifter_model* model, const floa
                         uint64_t* h_elems_w, uint64_t* h_elems_v) {
     int rc = enter(ctx, model, "compact");
     if (rc) return rc;
-    const size_t n_t = model->t.size(), n_v = model->v.size();
+    const size_t n_v = model->v.size();
     if (!d_w_sparse || !d_keep || !d_new_width || !d_w_out || (n_v && (!d_vecs || !d_vecs_out)))
         return fail(ctx, SHIFTER_ERR_INVALID_ARG, "compact: NULL pointer argument");
     if (K == 0 || K > MAXK)
@@ -1204,45 +1254,8 @@ static int compact_impl(shifter_ctx* ctx, const shifter_model* model, const floa
                    d_vecs_out, cap_v, K, d_thr);
     if ((rc = after_launch(ctx, "compact"))) return rc;
     if (h_out_tensors || h_out_vecs || h_elems_w || h_elems_v) {
-        const auto& b = model->b;
-        uint8_t* st = b.host_stage;
-        const size_t stride = sizeof(PlanHeader) + sizeof(PlanTensor) * n_t + sizeof(PlanVec) * n_v;
-        HIP_TRY(ctx, hipMemcpyAsync(st, b.plan_pack, stride * K, hipMemcpyDeviceToHost, ctx->stream));
         HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
-        auto hh = [&](uint32_t k) { return reinterpret_cast<const PlanHeader*>(st + stride * k); };
-        auto ht = [&](uint32_t k) { return reinterpret_cast<const PlanTensor*>(st + stride * k + sizeof(PlanHeader)); };
-        auto hv = [&](uint32_t k) {
-            return reinterpret_cast<const PlanVec*>(st + stride * k + sizeof(PlanHeader) + sizeof(PlanTensor) * n_t);
-        };
-        uint32_t status = 0;
-        for (uint32_t k = 0; k < K; ++k) {
-            status |= hh(k)->status;
-            if (h_elems_w) h_elems_w[k] = hh(k)->elems_w;
-            if (h_elems_v) h_elems_v[k] = hh(k)->elems_v;
-            if (h_out_tensors) {
-                for (size_t i = 0; i < n_t; ++i) {
-                    shifter_tensor_desc d = model->t[i];
-                    d.offset = ht(k)[i].out_off;
-                    d.out_ch = ht(k)[i].o2;
-                    d.in_ch = ht(k)[i].c2 * d.in_mult;
-                    h_out_tensors[k * n_t + i] = d;
-                }
-            }
-            if (h_out_vecs) {
-                for (size_t i = 0; i < n_v; ++i) {
-                    shifter_vec_desc d = model->v[i];
-                    d.offset = hv(k)[i].out_off;
-                    d.len = hv(k)[i].len2;
-                    h_out_vecs[k * n_v + i] = d;
-                }
-            }
-        }
-        if (status & 1u)
-            return fail(ctx, SHIFTER_ERR_CAPACITY, "compact: output capacity too small; nothing gathered");
-        if (status & 2u) {
-            fail(ctx, SHIFTER_WARN_COLLAPSE, "compact: a group kept no channel (layer collapse)");
-            return SHIFTER_WARN_COLLAPSE;
-        }
+        return plan_readout(ctx, model, K, h_out_tensors, h_out_vecs, h_elems_w, h_elems_v);
     }
     return SHIFTER_OK;
 }

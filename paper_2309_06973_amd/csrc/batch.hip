@@ -207,11 +207,18 @@ void launch_mask_scan_batch(shifter_ctx* ctx, const shifter_model* m, const floa
                             const shifter_threshold* d_thr, uint32_t k_var, float* d_w_out,
                             uint64_t w_stride, uint8_t* d_mask, uint64_t mask_stride,
                             uint8_t* d_out_alive, uint8_t* d_in_alive) {
+    launch_zero_levels(ctx, m);
+    launch_mask_scan_batch_core(ctx, m, d_w, d_thr, k_var, d_w_out, w_stride, d_mask, mask_stride);
+    launch_expand_levels(ctx, m, d_thr, k_var, d_out_alive, d_in_alive);
+}
+
+void launch_mask_scan_batch_core(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
+                                 const shifter_threshold* d_thr, uint32_t k_var, float* d_w_out,
+                                 uint64_t w_stride, uint8_t* d_mask, uint64_t mask_stride) {
     const auto& b = m->b;
     const uint32_t n_t = (uint32_t)m->t.size();
     const uint64_t n_out = m->info.sum_out_ch;
     hipStream_t s = ctx->stream;
-    launch_zero_levels(ctx, m);
     {
         ProfileScope p(ctx, K_MASK_SCAN_BATCH);
         // measured: with ten output streams per block the non-temporal hint costs about
@@ -223,7 +230,6 @@ void launch_mask_scan_batch(shifter_ctx* ctx, const shifter_model* m, const floa
         k<<<m->n_tiles, BLOCK, 0, s>>>(b.tens, b.tile_prefix, n_t, d_w, d_thr, k_var, d_w_out,
                                        w_stride, d_mask, mask_stride, b.levels, b.levels + n_out);
     }
-    launch_expand_levels(ctx, m, d_thr, k_var, d_out_alive, d_in_alive);
 }
 
 }  // namespace shifter

@@ -96,15 +96,15 @@ struct SpecState {
 
 // State of the single-pass selection for all prune counts of a portfolio (ranks sorted by
 // prune count, zero counts left out).
-constexpr uint32_t SPEC_MULTI_MAXK = 32;   // LDS of the round-1 histograms: 1 KB per rank
-constexpr uint32_t SPEC_SEG_CAP = 256;     // pairs per (rank, block) list segment
+constexpr uint32_t SPEC_MULTI_MAXK = 32;   // LDS of the fused pass's private counters: 256 B per rank
 struct MultiState {
     uint64_t p[MAXK];
-    uint64_t r2[MAXK], less[MAXK];
     uint32_t perm[MAXK];   // original position of sorted rank k
-    uint32_t lo[MAXK], hi[MAXK], sh[MAXK];
+    uint32_t lo[MAXK], hi[MAXK];   // candidate interval; ranks whose intervals met share one (a cluster)
+    uint32_t sh[MAXK];     // first refinement level of the finish: bin = (key - lo) >> sh
     uint32_t mid[MAXK];    // predicted threshold key of rank k, lo <= mid <= hi, non-decreasing
-    uint32_t bin[MAXK], bin_cnt[MAXK];
+    uint32_t clast[MAXK];  // last rank of rank k's cluster: the owner of the cluster's candidate region
+    uint32_t cand_off[MAXK], cand_cap[MAXK];   // region of the cluster ending at rank k: first pair, pairs per sub-buffer
     uint32_t k, m_valid, status, pad;
 };
 struct MultiPerm {
@@ -200,7 +200,6 @@ struct shifter_model {
         shifter::PlanTensor* plan_t = nullptr;
         shifter::PlanVec* plan_v = nullptr;
         shifter::PlanHeader* plan_h = nullptr;
-        uint8_t* plan_pack = nullptr;         // per variant: header, tensors, vectors, packed for one read-back
         uint32_t* out_tile_prefix = nullptr;  // MAXK * (n_tensors + 1)
         uint32_t* rect_prefix = nullptr;      // n_tensors + 1 each
         uint32_t* rowtab_prefix = nullptr;
@@ -228,14 +227,18 @@ struct shifter_model {
         uint2* list = nullptr;                // SPEC_LIST_CAP pairs
         uint32_t* ranked_ids = nullptr;
         shifter::MultiState* multi = nullptr;
-        uint32_t* multi_cnt = nullptr;        // (MAXK + 2) * SPEC_SUB counters, 128-byte lines
+        uint32_t* multi_cnt = nullptr;        // (2 * MAXK + 1) * SPEC_SUB counters, 128-byte lines
         uint8_t* multi_tab = nullptr;         // 4096 bucket entries of the K-rank pass
-        uint32_t* multi_partial = nullptr;    // SPEC_SUB * SPEC_MULTI_MAXK * 256
-        uint2* multi_seg = nullptr;           // SPEC_MULTI_MAXK * SPEC_SUB * SPEC_SEG_CAP pairs
-        uint32_t* multi_seg_cnt = nullptr;    // SPEC_MULTI_MAXK * SPEC_SUB
+        uint32_t* plan_done = nullptr;        // MAXK tickets of the planner (zero between launches)
         uint8_t* host_stage = nullptr;        // pinned, for small read-backs
         uint8_t* host_spec = nullptr;         // pinned: outcome of a deferred shifter_prune_fused
-        uint8_t* host_multi = nullptr;        // pinned: outcome of shifter_global_threshold_begin
+        // pinned mirrors the kernels write themselves (no copy on the stream): the K-rank
+        // ranking's status words (MAXK) and records (MAXK), and the packed plans of MAXK variants
+        uint8_t* host_multi = nullptr;
+        uint32_t* dev_multi_status = nullptr;       // device addresses of the same memory
+        shifter_threshold* dev_multi_rec = nullptr;
+        uint8_t* host_plan = nullptr;
+        uint8_t* dev_plan = nullptr;
         size_t host_stage_bytes = 0;
     } b;
 };
@@ -280,7 +283,7 @@ struct shifter_ctx {
         const shifter_model* model = nullptr;
         const float* d_w = nullptr;
         shifter::PruneCounts pc{};
-        uint32_t k = 0;
+        uint32_t k = 0, k_eff = 0;   // counts asked for; counts above zero (single pass)
         shifter_threshold* d_thr = nullptr;
         bool single_pass = false;
     } pending_rank;
@@ -330,10 +333,13 @@ struct FusedBatch {
     uint8_t* d_out_alive;
     uint8_t* d_in_alive;     // or nullptr
 };
+// zero_ptr / zero_n: an array of 32-bit words the ranking's set-up clears on the way (or
+// nullptr), for the step that follows it.
 void launch_spec_multi(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
                        const shifter::PruneCounts& sorted_p, const shifter::MultiPerm& perm,
                        uint32_t k, uint64_t zero_mask, shifter_threshold* d_thr,
-                       const FusedBatch* fb);
+                       const FusedBatch* fb, uint32_t* zero_ptr = nullptr, uint32_t zero_n = 0);
+constexpr size_t MULTI_MIRROR_REC_OFF = 256;   // records follow the MAXK status words
 void launch_zero_levels(shifter_ctx* ctx, const shifter_model* m);
 void launch_expand_levels(shifter_ctx* ctx, const shifter_model* m, const shifter_threshold* d_thr,
                           uint32_t k_var, uint8_t* d_out_alive, uint8_t* d_in_alive);
@@ -354,6 +360,24 @@ void launch_compact(shifter_ctx* ctx, const shifter_model* m, const float* d_w, 
                     const uint32_t* d_new_width, float* d_w_out, uint64_t cap_w,
                     float* d_vecs_out, uint64_t cap_v, uint32_t k_var,
                     const shifter_threshold* d_thr);
+// Device buffers of one portfolio step (shifter_portfolio_begin's arguments, checked).
+struct PortfolioBuffers {
+    const float* d_w; const float* d_vecs;
+    uint32_t k_var, flags;
+    shifter_threshold* d_thr;
+    float* d_w_sparse; uint64_t w_stride;          // or nullptr
+    uint8_t* d_mask; uint64_t mask_stride;         // or nullptr
+    uint8_t* d_out_alive; uint8_t* d_in_alive;     // in: or nullptr
+    uint8_t* d_group_alive; int32_t* d_index_map; uint32_t* d_keep; uint32_t* d_new_width;
+    float* d_w_out; uint64_t cap_w; float* d_vecs_out; uint64_t cap_v;
+};
+void launch_plan_and_gather(shifter_ctx* ctx, const shifter_model* m, const PortfolioBuffers& a,
+                            bool from_levels);
+// The batched mask pass alone: with_zero clears the level arrays first, with_expand turns
+// them into the variants' flag bytes afterwards.
+void launch_mask_scan_batch_core(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
+                                 const shifter_threshold* d_thr, uint32_t k_var, float* d_w_out,
+                                 uint64_t w_stride, uint8_t* d_mask, uint64_t mask_stride);
 void launch_copy(shifter_ctx* ctx, const float* src, float* dst, uint64_t n);
 void launch_kernel_scan(shifter_ctx* ctx, const shifter_model* m, const float* d_w, uint8_t* d_nz);
 void launch_fix_begin(shifter_ctx* ctx, const shifter_model* m);

@@ -12,30 +12,27 @@ namespace shifter {
 // The producers' flag offsets are fetched once (two dependent loads each) and a channel's
 // flags are then loaded side by side: the kernel is a handful of memory latencies long,
 // and a 1024-thread block covers most groups in one or two rounds.
+// Liveness of filter i of the whole model comes either from a variant's flag bytes
+// (out_alive) or, in a portfolio step, straight from the level array of the batched mask
+// pass: alive <=> level[i] > pos, pos = number of variants with a smaller cut.
 constexpr uint32_t PROP_THREADS = 1024, PROP_LDS_PRODUCERS = 64;
 
-__global__ __launch_bounds__(PROP_THREADS) void propagate_kernel(
-    const DevGroup* __restrict__ groups, const uint32_t* __restrict__ producers,
-    const DevTensor* __restrict__ tens, const uint8_t* __restrict__ out_alive,
+__device__ __forceinline__ void propagate_group(
+    const DevGroup G, const uint32_t* __restrict__ producers, const DevTensor* __restrict__ tens,
+    const uint8_t* __restrict__ out_alive, const uint32_t* __restrict__ out_level, uint32_t pos,
     uint32_t flags, uint8_t* __restrict__ group_alive, int32_t* __restrict__ index_map,
-    uint32_t* __restrict__ keep, uint32_t* __restrict__ new_width, uint64_t out_alive_stride,
-    uint64_t group_stride, uint32_t n_groups) {
+    uint32_t* __restrict__ keep, uint32_t* __restrict__ new_width_g, uint32_t* wave_cnt,
+    uint32_t* s_flag_off) {
     constexpr uint32_t WAVES = PROP_THREADS / 64;
-    __shared__ uint32_t wave_cnt[WAVES];
-    __shared__ uint32_t s_flag_off[PROP_LDS_PRODUCERS];
-    // blockIdx.y = variant of a batch
-    out_alive += blockIdx.y * out_alive_stride;
-    group_alive += blockIdx.y * group_stride;
-    index_map += blockIdx.y * group_stride;
-    keep += blockIdx.y * group_stride;
-    new_width += blockIdx.y * n_groups;
-    const DevGroup G = groups[blockIdx.x];
     const uint32_t n_prod = G.prod_end - G.prod_begin;
     const bool frozen = G.pinned || ((flags & SHIFTER_PAPER_FREEZE_RESIDUAL) && n_prod > 1);
     const uint32_t lane = threadIdx.x & 63u, wid = threadIdx.x >> 6;
     if (!frozen && threadIdx.x < min(n_prod, PROP_LDS_PRODUCERS))
         s_flag_off[threadIdx.x] = tens[producers[G.prod_begin + threadIdx.x]].out_flag_off;
     __syncthreads();
+    auto alive_at = [&](uint32_t i) -> uint32_t {
+        return out_level ? (out_level[i] > pos ? 1u : 0u) : (uint32_t)out_alive[i];
+    };
     uint32_t base = 0;
     for (uint32_t c0 = 0; c0 < G.width; c0 += PROP_THREADS) {
         const uint32_t c = c0 + threadIdx.x;
@@ -44,9 +41,9 @@ __global__ __launch_bounds__(PROP_THREADS) void propagate_kernel(
             a = frozen ? 1u : 0u;
             if (!frozen) {
                 const uint32_t n_lds = min(n_prod, PROP_LDS_PRODUCERS);
-                for (uint32_t p = 0; p < n_lds; ++p) a |= out_alive[s_flag_off[p] + c];
+                for (uint32_t p = 0; p < n_lds; ++p) a |= alive_at(s_flag_off[p] + c);
                 for (uint32_t p = G.prod_begin + n_lds; p < G.prod_end && !a; ++p)
-                    a = out_alive[tens[producers[p]].out_flag_off + c];
+                    a = alive_at(tens[producers[p]].out_flag_off + c);
                 a = a ? 1u : 0u;
             }
         }
@@ -59,17 +56,32 @@ __global__ __launch_bounds__(PROP_THREADS) void propagate_kernel(
             if (i < wid) woff += x;
             tot += x;
         }
-        const uint32_t pos = base + woff + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
+        const uint32_t pos_c = base + woff + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
         if (c < G.width) {
             group_alive[G.off + c] = (uint8_t)a;
-            index_map[G.off + c] = a ? (int32_t)pos : -1;
-            if (a) keep[G.off + pos] = c;
+            index_map[G.off + c] = a ? (int32_t)pos_c : -1;
+            if (a) keep[G.off + pos_c] = c;
         }
         base += tot;
         __syncthreads();
     }
     for (uint32_t c = base + threadIdx.x; c < G.width; c += PROP_THREADS) keep[G.off + c] = 0xffffffffu;
-    if (threadIdx.x == 0) new_width[blockIdx.x] = base;
+    if (threadIdx.x == 0) *new_width_g = base;
+}
+
+__global__ __launch_bounds__(PROP_THREADS) void propagate_kernel(
+    const DevGroup* __restrict__ groups, const uint32_t* __restrict__ producers,
+    const DevTensor* __restrict__ tens, const uint8_t* __restrict__ out_alive,
+    uint32_t flags, uint8_t* __restrict__ group_alive, int32_t* __restrict__ index_map,
+    uint32_t* __restrict__ keep, uint32_t* __restrict__ new_width, uint64_t out_alive_stride,
+    uint64_t group_stride, uint32_t n_groups) {
+    __shared__ uint32_t wave_cnt[PROP_THREADS / 64];
+    __shared__ uint32_t s_flag_off[PROP_LDS_PRODUCERS];
+    // blockIdx.y = variant of a batch
+    propagate_group(groups[blockIdx.x], producers, tens, out_alive + blockIdx.y * out_alive_stride,
+                    nullptr, 0, flags, group_alive + blockIdx.y * group_stride,
+                    index_map + blockIdx.y * group_stride, keep + blockIdx.y * group_stride,
+                    new_width + blockIdx.y * n_groups + blockIdx.x, wave_cnt, s_flag_off);
 }
 
 // log2 of the column slots one row takes in a gather work unit: 10 (all 1024) for rows of
@@ -87,34 +99,32 @@ __host__ __device__ __forceinline__ uint32_t gather_unit_rows(uint32_t lg) {
 }
 
 // One block per variant: sizes and offsets of every rebuilt tensor and vector (Algorithm 2,
-// the "create new layer" step), the work-unit prefix of the gather launch, capacity check.
+// the step that creates the smaller layer), the work-unit prefix of the gather launch,
+// capacity check.
 // A gather work unit is a 2-D piece of one rebuilt tensor: GATHER_CHUNK consecutive
 // columns (elements of a filter) times gather_unit_rows() rows (filters); for filters
 // shorter than GATHER_CHUNK the wavefront's 1024 column slots hold several rows side by
 // side (rows padded to a power of two, at least 64).  Every unit is four row steps deep.
-__global__ __launch_bounds__(BLOCK) void plan_kernel(
-    const DevTensor* __restrict__ tens, uint32_t n_t, const DevVec* __restrict__ vecs,
-    uint32_t n_v, const DevGroup* __restrict__ groups, uint32_t n_g,
-    const uint32_t* __restrict__ new_width, uint64_t cap_w, uint64_t cap_v,
+// The records also go, packed per variant (header, tensors, vectors), to a mirror in
+// pinned host memory, so that the host reads a plan without a copy on the stream.
+template <uint32_t THREADS>
+__device__ __forceinline__ void plan_variant(
+    uint32_t k, const DevTensor* __restrict__ tens, uint32_t n_t, const DevVec* __restrict__ vecs,
+    uint32_t n_v, uint32_t n_g, const uint32_t* new_width, uint64_t cap_w, uint64_t cap_v,
     PlanTensor* __restrict__ pt, PlanVec* __restrict__ pv, uint32_t* __restrict__ oup,
-    PlanHeader* __restrict__ hdr, uint8_t* __restrict__ pack) {
-    __shared__ uint64_t smem[BLOCK / 64 + 1];
-    __shared__ uint32_t s_collapse;
-    // blockIdx.x = variant of a batch
-    new_width += blockIdx.x * n_g;
-    pt += blockIdx.x * n_t;
-    pv += blockIdx.x * n_v;
-    oup += blockIdx.x * (n_t + 1);
-    hdr += blockIdx.x;
-    // the same records once more, packed per variant (header, tensors, vectors), so that
-    // the host fetches a plan with one copy
-    pack += (uint64_t)blockIdx.x * (sizeof(PlanHeader) + n_t * sizeof(PlanTensor) + n_v * sizeof(PlanVec));
+    PlanHeader* __restrict__ hdr, uint8_t* __restrict__ pack, uint64_t* smem, uint32_t* s_collapse) {
+    new_width += k * n_g;
+    pt += k * n_t;
+    pv += k * n_v;
+    oup += k * (n_t + 1);
+    hdr += k;
+    pack += (uint64_t)k * (sizeof(PlanHeader) + n_t * sizeof(PlanTensor) + n_v * sizeof(PlanVec));
     PlanHeader* pack_h = reinterpret_cast<PlanHeader*>(pack);
     PlanTensor* pack_t = reinterpret_cast<PlanTensor*>(pack + sizeof(PlanHeader));
     PlanVec* pack_v = reinterpret_cast<PlanVec*>(pack + sizeof(PlanHeader) + n_t * sizeof(PlanTensor));
-    if (threadIdx.x == 0) s_collapse = 0;
+    if (threadIdx.x == 0) *s_collapse = 0;
     uint64_t off = 0, units = 0, tot;
-    for (uint32_t t0 = 0; t0 < n_t; t0 += BLOCK) {
+    for (uint32_t t0 = 0; t0 < n_t; t0 += THREADS) {
         const uint32_t t = t0 + threadIdx.x;
         PlanTensor p;
         p.o2 = p.c2 = p.numel2 = p.row2 = p.chunks = 0;
@@ -131,9 +141,9 @@ __global__ __launch_bounds__(BLOCK) void plan_kernel(
                 my_units = p.chunks * ((p.o2 + p.rb - 1) / p.rb);
             }
         }
-        const uint64_t my_off = off + block_excl_scan_u64(p.numel2, smem, &tot);
+        const uint64_t my_off = off + block_excl_scan_u64<THREADS>(p.numel2, smem, &tot);
         off += tot;
-        const uint64_t my_unit0 = units + block_excl_scan_u64(my_units, smem, &tot);
+        const uint64_t my_unit0 = units + block_excl_scan_u64<THREADS>(my_units, smem, &tot);
         units += tot;
         if (t < n_t) {
             p.out_off = my_off;
@@ -143,30 +153,47 @@ __global__ __launch_bounds__(BLOCK) void plan_kernel(
         }
     }
     uint64_t voff = 0;
-    for (uint32_t v0 = 0; v0 < n_v; v0 += BLOCK) {
+    for (uint32_t v0 = 0; v0 < n_v; v0 += THREADS) {
         const uint32_t v = v0 + threadIdx.x;
         PlanVec p;
         p.len2 = v < n_v ? new_width[vecs[v].group] : 0;
         p.pad = 0;
-        p.out_off = voff + block_excl_scan_u64(p.len2, smem, &tot);
+        p.out_off = voff + block_excl_scan_u64<THREADS>(p.len2, smem, &tot);
         voff += tot;
         if (v < n_v) {
             pv[v] = p;
             pack_v[v] = p;
         }
     }
-    for (uint32_t g = threadIdx.x; g < n_g; g += BLOCK)
-        if (new_width[g] == 0) s_collapse = 1;
+    __syncthreads();
+    for (uint32_t g = threadIdx.x; g < n_g; g += THREADS)
+        if (new_width[g] == 0) *s_collapse = 1;
     __syncthreads();
     if (threadIdx.x == 0) {
-        const uint32_t status = ((off > cap_w || voff > cap_v) ? 1u : 0u) | (s_collapse ? 2u : 0u);
+        const uint32_t status = ((off > cap_w || voff > cap_v) ? 1u : 0u) | (*s_collapse ? 2u : 0u);
+        PlanHeader h;
+        h.elems_w = off;
+        h.elems_v = voff;
+        h.total_units = (status & 1u) ? 0u : (uint32_t)units;   // does not fit: gather nothing
+        h.status = status;
         oup[n_t] = (uint32_t)units;
-        hdr->elems_w = off;
-        hdr->elems_v = voff;
-        hdr->total_units = (status & 1u) ? 0u : (uint32_t)units;   // does not fit: gather nothing
-        hdr->status = status;
-        *pack_h = *hdr;
+        *hdr = h;
+        *pack_h = h;
     }
+}
+
+__global__ __launch_bounds__(BLOCK) void plan_kernel(
+    const DevTensor* __restrict__ tens, uint32_t n_t, const DevVec* __restrict__ vecs,
+    uint32_t n_v, const DevGroup* __restrict__ groups, uint32_t n_g,
+    const uint32_t* __restrict__ new_width, uint64_t cap_w, uint64_t cap_v,
+    PlanTensor* __restrict__ pt, PlanVec* __restrict__ pv, uint32_t* __restrict__ oup,
+    PlanHeader* __restrict__ hdr, uint8_t* __restrict__ pack) {
+    __shared__ uint64_t smem[BLOCK / 64 + 1];
+    __shared__ uint32_t s_collapse;
+    (void)groups;
+    // blockIdx.x = variant of a batch
+    plan_variant<BLOCK>(blockIdx.x, tens, n_t, vecs, n_v, n_g, new_width, cap_w, cap_v, pt, pv, oup, hdr,
+                        pack, smem, &s_collapse);
 }
 
 // x / d for any 32-bit x with the (magic, shift) pair the host derived from d >= 2.
@@ -326,15 +353,12 @@ __global__ __launch_bounds__(BLOCK) void gather_kernel(
 // every chunk of chunk_ch source channels the number of surviving channels below its
 // first one (keep lists are ascending, so these are lower bounds).  What a variant keeps
 // of a source rectangle is then the range between two neighbouring entries of each.
-__global__ __launch_bounds__(BLOCK) void rect_tables_kernel(
-    const DevTensor* __restrict__ tens, const DevGroup* __restrict__ groups, uint32_t n_t,
-    const uint32_t* __restrict__ rowtab_prefix, const uint32_t* __restrict__ coltab_prefix,
-    const uint32_t* __restrict__ keep_all, const uint32_t* __restrict__ new_width_all,
-    uint64_t group_stride, uint32_t n_groups, uint32_t* __restrict__ rowtab,
-    uint32_t* __restrict__ coltab) {
-    const uint32_t k = blockIdx.y;
+__device__ __forceinline__ void rect_table_entry(
+    uint32_t i, uint32_t k, const DevTensor* __restrict__ tens, const DevGroup* __restrict__ groups,
+    uint32_t n_t, const uint32_t* __restrict__ rowtab_prefix, const uint32_t* __restrict__ coltab_prefix,
+    const uint32_t* keep_all, const uint32_t* new_width_all, uint64_t group_stride, uint32_t n_groups,
+    uint32_t* __restrict__ rowtab, uint32_t* __restrict__ coltab) {
     const uint32_t n_row = rowtab_prefix[n_t], n_col = coltab_prefix[n_t];
-    const uint32_t i = blockIdx.x * BLOCK + threadIdx.x;
     if (i >= n_row + n_col) return;
     const bool is_row = i < n_row;
     const uint32_t e = is_row ? i : i - n_row;
@@ -356,6 +380,103 @@ __global__ __launch_bounds__(BLOCK) void rect_tables_kernel(
         if (keep[a + half] < x) { a += half + 1; len -= half + 1; } else len = half;
     }
     (is_row ? rowtab + (uint64_t)k * n_row : coltab + (uint64_t)k * n_col)[e] = a;
+}
+
+__global__ __launch_bounds__(BLOCK) void rect_tables_kernel(
+    const DevTensor* __restrict__ tens, const DevGroup* __restrict__ groups, uint32_t n_t,
+    const uint32_t* __restrict__ rowtab_prefix, const uint32_t* __restrict__ coltab_prefix,
+    const uint32_t* __restrict__ keep_all, const uint32_t* __restrict__ new_width_all,
+    uint64_t group_stride, uint32_t n_groups, uint32_t* __restrict__ rowtab,
+    uint32_t* __restrict__ coltab) {
+    rect_table_entry(blockIdx.x * BLOCK + threadIdx.x, blockIdx.y, tens, groups, n_t, rowtab_prefix,
+                     coltab_prefix, keep_all, new_width_all, group_stride, n_groups, rowtab, coltab);
+}
+
+// The whole planning of a portfolio step in one launch (Module 3 for every group and
+// variant, then Module 4's sizes and tables per variant).  blockIdx.y = variant.  Blocks
+// 0 .. n_groups - 1 each plan one group; the block that finishes a variant's last group
+// goes on to that variant's rebuild plan and, for the portfolio rebuild, its row and
+// column tables: it takes a ticket after a device-wide fence, so it sees what the other
+// blocks of its variant wrote, and it waits for nothing.  With levels as the source of
+// liveness the blocks from n_groups on expand them into the variant's flag bytes (the
+// outputs of the batched mask pass, which nothing in this launch reads).
+struct PlanAllArgs {
+    const DevGroup* groups; const uint32_t* producers; const DevTensor* tens; uint32_t n_t;
+    const DevVec* vecs; uint32_t n_v; uint32_t n_groups;
+    const uint8_t* out_alive;          // flag bytes of every variant, or nullptr: take levels
+    const uint32_t* out_level; const uint32_t* in_level; const shifter_threshold* thr;
+    uint64_t n_out, n_in;
+    uint8_t* exp_out_alive; uint8_t* exp_in_alive;   // where the levels are expanded to (in: may be nullptr)
+    uint32_t flags;
+    uint8_t* group_alive; int32_t* index_map; uint32_t* keep; uint32_t* new_width;
+    uint64_t group_stride;
+    uint64_t cap_w, cap_v;
+    PlanTensor* pt; PlanVec* pv; uint32_t* oup; PlanHeader* hdr; uint8_t* pack;
+    const uint32_t* rowtab_prefix; const uint32_t* coltab_prefix; uint32_t* rowtab; uint32_t* coltab;
+    uint32_t want_tables;
+    uint32_t* done;                    // one ticket counter per variant, zero between launches
+    uint32_t k_var;
+};
+
+__global__ __launch_bounds__(PROP_THREADS) void plan_all_kernel(const PlanAllArgs A) {
+    __shared__ uint32_t wave_cnt[PROP_THREADS / 64];
+    __shared__ uint32_t s_flag_off[PROP_LDS_PRODUCERS];
+    __shared__ uint64_t s_cut[MAXK];
+    __shared__ uint32_t s_pos[MAXK];
+    __shared__ uint64_t smem[PROP_THREADS / 64 + 1];
+    __shared__ uint32_t s_collapse, s_last;
+    const uint32_t k = blockIdx.y;
+    uint32_t pos = 0;
+    if (!A.out_alive) {
+        // pos = number of variants whose cut is smaller than variant k's (ties by index)
+        if (threadIdx.x < A.k_var) s_cut[threadIdx.x] = A.thr[threadIdx.x].cut;
+        __syncthreads();
+        if (threadIdx.x < A.k_var) {
+            const uint64_t mine = s_cut[threadIdx.x];
+            uint32_t p = 0;
+            for (uint32_t j = 0; j < A.k_var; ++j) {
+                const uint64_t c = s_cut[j];
+                p += (c < mine || (c == mine && j < threadIdx.x)) ? 1u : 0u;
+            }
+            s_pos[threadIdx.x] = p;
+        }
+        __syncthreads();
+        pos = s_pos[k];
+    }
+    if (blockIdx.x >= A.n_groups) {
+        const uint64_t i = (uint64_t)(blockIdx.x - A.n_groups) * PROP_THREADS + threadIdx.x;
+        if (i < A.n_out) A.exp_out_alive[(uint64_t)k * A.n_out + i] = A.out_level[i] > pos ? 1 : 0;
+        if (i < A.n_in && A.exp_in_alive) A.exp_in_alive[(uint64_t)k * A.n_in + i] = A.in_level[i] > pos ? 1 : 0;
+        return;
+    }
+    propagate_group(A.groups[blockIdx.x], A.producers, A.tens,
+                    A.out_alive ? A.out_alive + (uint64_t)k * A.n_out : nullptr,
+                    A.out_alive ? nullptr : A.out_level, pos, A.flags,
+                    A.group_alive + k * A.group_stride, A.index_map + k * A.group_stride,
+                    A.keep + k * A.group_stride, A.new_width + k * A.n_groups + blockIdx.x, wave_cnt,
+                    s_flag_off);
+    // the last block of this variant to get here plans its rebuild
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t ticket = __hip_atomic_fetch_add(&A.done[k], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        s_last = ticket + 1u == A.n_groups ? 1u : 0u;
+        if (s_last) A.done[k] = 0;      // for the next launch
+    }
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    // what the other blocks wrote is read through pointers the compiler knows nothing
+    // about, after the fence
+    const uint32_t* new_width = const_cast<const uint32_t*>(A.new_width);
+    plan_variant<PROP_THREADS>(k, A.tens, A.n_t, A.vecs, A.n_v, A.n_groups, new_width, A.cap_w, A.cap_v,
+                               A.pt, A.pv, A.oup, A.hdr, A.pack, smem, &s_collapse);
+    if (A.want_tables) {
+        const uint32_t n_tab = A.rowtab_prefix[A.n_t] + A.coltab_prefix[A.n_t];
+        for (uint32_t i = threadIdx.x; i < n_tab; i += PROP_THREADS)
+            rect_table_entry(i, k, A.tens, A.groups, A.n_t, A.rowtab_prefix, A.coltab_prefix, A.keep,
+                             A.new_width, A.group_stride, A.n_groups, A.rowtab, A.coltab);
+    }
 }
 
 // Position of column c of a staged rectangle row in LDS: within each group of 128
@@ -649,6 +770,40 @@ void launch_propagate(shifter_ctx* ctx, const shifter_model* m, const uint8_t* d
         d_new_width, m->info.sum_out_ch, m->info.sum_group_width, (uint32_t)m->g.size());
 }
 
+// Whether the rebuild of k_var variants takes the rectangle kernel (one read of a shared
+// dense source) or the output-ordered gather.
+static bool use_rect(const shifter_model* m, uint32_t k_var, const shifter_threshold* d_thr) {
+    (void)k_var;
+    return d_thr && m->rect_ok && m->rect_prefix.back() > 0;
+}
+
+// The gather launch alone; the plan (and, for the rectangle kernel, the tables) must be
+// on the device already.
+static void launch_gather(shifter_ctx* ctx, const shifter_model* m, const float* d_w, uint64_t w_stride,
+                          const float* d_vecs, const uint32_t* d_keep, float* d_w_out, uint64_t cap_w,
+                          float* d_vecs_out, uint64_t cap_v, uint32_t k_var,
+                          const shifter_threshold* d_thr) {
+    const auto& b = m->b;
+    const uint32_t n_t = (uint32_t)m->t.size(), n_v = (uint32_t)m->v.size();
+    // the unit counts are only known on the device: the grid covers the case that
+    // nothing is removed; wavefronts past the real count exit at once
+    ProfileScope p(ctx, K_GATHER);
+    if (use_rect(m, k_var, d_thr)) {
+        const uint32_t n_rects = m->rect_prefix.back();
+        gather_rect_kernel<<<std::max(1u, n_rects), BLOCK, 0, ctx->stream>>>(
+            b.tens, b.groups, n_t, b.plan_t, b.rect_prefix, b.rowtab_prefix, b.coltab_prefix,
+            b.rowtab, b.coltab, b.plan_h, d_w, m->info.w_extent, d_keep, d_w_out, b.vecs, n_v,
+            b.plan_v, d_vecs, d_vecs_out, m->info.sum_group_width, cap_w, cap_v, d_thr, k_var,
+            n_rects);
+        return;
+    }
+    const uint32_t grid = std::max(1u, (m->gather_units_bound + BLOCK / 64 - 1) / (BLOCK / 64));
+    gather_kernel<<<dim3(grid, k_var), BLOCK, 0, ctx->stream>>>(
+        b.tens, b.groups, n_t, b.plan_t, b.out_tile_prefix, b.plan_h, d_w, d_keep, d_w_out,
+        b.vecs, n_v, b.plan_v, d_vecs, d_vecs_out, w_stride, m->info.sum_group_width, cap_w,
+        cap_v, d_thr);
+}
+
 void launch_compact(shifter_ctx* ctx, const shifter_model* m, const float* d_w, uint64_t w_stride,
                     const float* d_vecs, const uint32_t* d_keep,
                     const uint32_t* d_new_width, float* d_w_out, uint64_t cap_w,
@@ -661,34 +816,56 @@ void launch_compact(shifter_ctx* ctx, const shifter_model* m, const float* d_w, 
         plan_kernel<<<k_var, BLOCK, 0, ctx->stream>>>(b.tens, n_t, b.vecs, n_v, b.groups,
                                                       (uint32_t)m->g.size(), d_new_width, cap_w,
                                                       cap_v, b.plan_t, b.plan_v, b.out_tile_prefix,
-                                                      b.plan_h, b.plan_pack);
-    }
-    {
-        // the unit counts are only known on the device: the grid covers the case that
-        // nothing is removed; wavefronts past the real count exit at once
-        ProfileScope p(ctx, K_GATHER);
-        if (d_thr && k_var > 1 && m->rect_ok && m->rect_prefix.back() > 0) {
+                                                      b.plan_h, b.dev_plan);
+        if (use_rect(m, k_var, d_thr)) {
             // K rebuilds from one shared source: one read of it, see gather_rect_kernel
             // (with K separate sparse arenas as the source there is nothing to share and
-            // the output-ordered kernel below is used)
-            const uint32_t n_rects = m->rect_prefix.back();
+            // the output-ordered kernel is used)
             const uint32_t n_tab = m->rowtab_prefix.back() + m->coltab_prefix.back();
             rect_tables_kernel<<<dim3((n_tab + BLOCK - 1) / BLOCK, k_var), BLOCK, 0, ctx->stream>>>(
                 b.tens, b.groups, n_t, b.rowtab_prefix, b.coltab_prefix, d_keep, d_new_width,
                 m->info.sum_group_width, (uint32_t)m->g.size(), b.rowtab, b.coltab);
-            gather_rect_kernel<<<std::max(1u, n_rects), BLOCK, 0, ctx->stream>>>(
-                b.tens, b.groups, n_t, b.plan_t, b.rect_prefix, b.rowtab_prefix, b.coltab_prefix,
-                b.rowtab, b.coltab, b.plan_h, d_w, m->info.w_extent, d_keep, d_w_out, b.vecs, n_v,
-                b.plan_v, d_vecs, d_vecs_out, m->info.sum_group_width, cap_w, cap_v, d_thr, k_var,
-                n_rects);
-            return;
         }
-        const uint32_t grid = std::max(1u, (m->gather_units_bound + BLOCK / 64 - 1) / (BLOCK / 64));
-        gather_kernel<<<dim3(grid, k_var), BLOCK, 0, ctx->stream>>>(
-            b.tens, b.groups, n_t, b.plan_t, b.out_tile_prefix, b.plan_h, d_w, d_keep, d_w_out,
-            b.vecs, n_v, b.plan_v, d_vecs, d_vecs_out, w_stride, m->info.sum_group_width, cap_w,
-            cap_v, d_thr);
     }
+    launch_gather(ctx, m, d_w, w_stride, d_vecs, d_keep, d_w_out, cap_w, d_vecs_out, cap_v, k_var, d_thr);
+}
+
+// Steps 4 and 5 of a portfolio step behind its mask pass: one planning launch (groups,
+// rebuild plans, tables; with from_levels also the variants' flag bytes, expanded from the
+// level arrays the batched mask pass left) and the gather.
+void launch_plan_and_gather(shifter_ctx* ctx, const shifter_model* m, const PortfolioBuffers& a,
+                            bool from_levels) {
+    const auto& b = m->b;
+    const uint32_t n_t = (uint32_t)m->t.size(), n_v = (uint32_t)m->v.size();
+    const uint32_t n_g = (uint32_t)m->g.size();
+    const uint64_t n_out = m->info.sum_out_ch, n_in = m->info.sum_in_ch;
+    // the source of the rebuild: the dense arena masked on the way, unless only the sparse
+    // arenas can serve the output-ordered gather
+    const bool rect = use_rect(m, a.k_var, a.d_thr);
+    PlanAllArgs A;
+    A.groups = b.groups; A.producers = b.producers; A.tens = b.tens; A.n_t = n_t;
+    A.vecs = b.vecs; A.n_v = n_v; A.n_groups = n_g;
+    A.out_alive = from_levels ? nullptr : a.d_out_alive;
+    A.out_level = b.levels; A.in_level = b.levels + n_out; A.thr = a.d_thr;
+    A.n_out = n_out; A.n_in = n_in;
+    A.exp_out_alive = a.d_out_alive; A.exp_in_alive = a.d_in_alive;
+    A.flags = a.flags;
+    A.group_alive = a.d_group_alive; A.index_map = a.d_index_map; A.keep = a.d_keep;
+    A.new_width = a.d_new_width; A.group_stride = m->info.sum_group_width;
+    A.cap_w = a.cap_w; A.cap_v = a.cap_v;
+    A.pt = b.plan_t; A.pv = b.plan_v; A.oup = b.out_tile_prefix; A.hdr = b.plan_h; A.pack = b.dev_plan;
+    A.rowtab_prefix = b.rowtab_prefix; A.coltab_prefix = b.coltab_prefix; A.rowtab = b.rowtab;
+    A.coltab = b.coltab; A.want_tables = rect ? 1u : 0u;
+    A.done = b.plan_done; A.k_var = a.k_var;
+    const uint64_t mx = std::max<uint64_t>(n_out > n_in ? n_out : n_in, 1);
+    const uint32_t expand_blocks = from_levels ? (uint32_t)((mx + PROP_THREADS - 1) / PROP_THREADS) : 0u;
+    {
+        ProfileScope p(ctx, K_PLAN);
+        plan_all_kernel<<<dim3(n_g + expand_blocks, a.k_var), PROP_THREADS, 0, ctx->stream>>>(A);
+    }
+    const bool dense_src = rect || !a.d_w_sparse;
+    launch_gather(ctx, m, dense_src ? a.d_w : a.d_w_sparse, dense_src ? 0 : a.w_stride, a.d_vecs, a.d_keep,
+                  a.d_w_out, a.cap_w, a.d_vecs_out, a.cap_v, a.k_var, dense_src ? a.d_thr : nullptr);
 }
 
 void launch_copy(shifter_ctx* ctx, const float* src, float* dst, uint64_t n) {

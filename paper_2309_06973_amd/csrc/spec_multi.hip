@@ -3,76 +3,63 @@
 //
 // Same scheme as the one-count selection (sample, predict, one pass, finish), with the
 // prune counts sorted ascending so that the predicted key intervals [lo_k, hi_k] have
-// non-decreasing ends.  For a weight with key x let j = #{k : lo_k <= x}; then
+// non-decreasing ends.  Intervals that overlap are merged into one (a cluster of ranks
+// sharing lo and hi), so two intervals are either the same or disjoint.  For a weight with
+// key x let j = #{k : lo_k <= x}; then
 //   x < lo_k  <=>  j <= k            (so below_k is a prefix sum of the counts per j)
-//   x is a candidate of some rank  <=>  j >= 1 and x <= hi_{j-1}
-//   x is a candidate of rank k  <=>  first{k : hi_k >= x} <= k < j
-// so one binary search per weight replaces K interval tests.  The candidates of all
-// ranks share the 256 sub-buffers; the finishing passes visit each candidate once and
-// update every rank whose interval holds it.
+//   x is a candidate  <=>  j >= 1 and x <= hi_{j-1}; it belongs to the cluster whose last
+//                          rank is j - 1
+// so one search per weight replaces K interval tests.  The pass appends a candidate to the
+// region of its cluster (split 256 ways by block, one reservation per block and cluster);
+// the finish is one launch, one block per rank, which walks its cluster's region.
 #include "dev_common.h"
 
 namespace shifter {
 
 constexpr uint32_t MS_BINS = 16384;      // sample histogram bins
 constexpr uint32_t MS_SHIFT = 17;        // top 14 of the 31 key bits
-constexpr uint32_t MF_BINS1 = 256;       // round-1 finishing histogram, per rank
-constexpr uint32_t MF_BINS2 = 4096;      // round-2, one block per rank
-constexpr uint32_t MF_BLOCKS = SPEC_SUB; // blocks of the passes over the candidates
 constexpr uint32_t TAB_SHIFT = 19;       // the pass's bucket table: 4096 buckets of 2^19 keys
 constexpr uint32_t TAB_SIZE = 1u << (31 - TAB_SHIFT);
-constexpr uint32_t MF_THREADS = 1024;    // their size: one block per CU, and its sixteen wavefronts
-                                         // hide the latency of the walk's loads and LDS searches
+constexpr uint32_t FIN_THREADS = 1024;   // the finish: one block per rank
+constexpr uint32_t FIN_BINS = 4096;      // bins of one refinement level
+constexpr uint32_t FIN_LIST = 1024;      // pairs settled by counting
+constexpr uint32_t FIN_DEPTH = 8;        // loads a lane keeps in flight while walking a region
 
-enum { MC_CAND = 0, MC_BELOW = 1 };   // cnt layout: [MC_CAND][sb]*32, then [1 + j][sb]*32
-
-__device__ __forceinline__ uint32_t* mcnt(uint32_t* cnt, uint32_t which, uint32_t sb) {
-    return cnt + ((size_t)which * SPEC_SUB + sb) * 32u;
+// Split counters, one 128-byte line each: row j (0 <= j <= MAXK) counts the weights with
+// exactly j lower ends at or below their key; row MAXK + 1 + r the candidates appended to
+// the region of the cluster whose last rank is r.
+__device__ __forceinline__ uint32_t* mcnt_below(uint32_t* cnt, uint32_t j, uint32_t sb) {
+    return cnt + ((size_t)j * SPEC_SUB + sb) * 32u;
+}
+__device__ __forceinline__ uint32_t* mcnt_cand(uint32_t* cnt, uint32_t r, uint32_t sb) {
+    return cnt + ((size_t)(MAXK + 1u + r) * SPEC_SUB + sb) * 32u;
 }
 
+// #{k : lo_k <= key} by a branch-free binary search; s_lo holds MAXK + 1 entries, padded
+// with 0xffffffff.
+__device__ __forceinline__ uint32_t count_lower_ends(const uint32_t* s_lo, uint32_t key) {
+    uint32_t j = 0;
+#pragma unroll
+    for (uint32_t step = MAXK / 2; step >= 1; step >>= 1)
+        if (s_lo[j + step - 1] <= key) j += step;
+    return j + (s_lo[j] <= key ? 1u : 0u);
+}
+
+// One block.  First the set-up of a ranking (the state, the zero-count records, the split
+// counters; the sample histogram is read into registers and cleared for the next call;
+// `zero_ptr` is an optional array the caller wants cleared before the pass), then the
+// inclusive prefix of the sample histogram in LDS, for every rank the interval from the
+// sample's order statistics at P/N -/+ margin, monotone ends, clusters, and each cluster's
+// share of the candidate buffer.
 // sorted_p / perm: the k prune counts > 0 in ascending order and their original positions;
 // zero_mask: bit i set = original position i asked for P = 0 and gets its record here.
-__global__ __launch_bounds__(BLOCK) void ms_init_kernel(MultiState* ms, uint32_t* shist,
-                                                        uint32_t* cnt, PruneCounts sorted_p,
-                                                        MultiPerm perm, uint32_t k,
-                                                        uint32_t m_valid, uint64_t zero_mask,
-                                                        shifter_threshold* thr) {
-    const uint64_t tid = (uint64_t)blockIdx.x * BLOCK + threadIdx.x;
-    const uint64_t stride = (uint64_t)gridDim.x * BLOCK;
-    for (uint64_t i = tid; i < MS_BINS; i += stride) shist[i] = 0;
-    for (uint64_t i = tid; i < (uint64_t)(k + 2) * SPEC_SUB * 32u; i += stride) cnt[i] = 0;
-    if (tid < MAXK) {
-        ms->p[tid] = tid < k ? sorted_p.p[tid] : 0;
-        ms->perm[tid] = tid < k ? perm.v[tid] : 0;
-        ms->lo[tid] = 0xffffffffu;     // padding sorts last in the searches
-        ms->hi[tid] = 0xffffffffu;
-        ms->mid[tid] = 0xffffffffu;
-        ms->sh[tid] = 0;
-        ms->bin[tid] = 0;
-        ms->bin_cnt[tid] = 0;
-        ms->r2[tid] = 0;
-        ms->less[tid] = 0;
-    }
-    if (tid < MAXK && ((zero_mask >> tid) & 1ull)) {
-        shifter_threshold out;
-        out.cut = 0; out.t_key = 0; out.reserved = 0; out.g_cut = ~0ull; out.n_prune = 0;
-        out.n_less = 0; out.n_equal = 0;
-        thr[tid] = out;
-    }
-    if (tid == 0) {
-        ms->k = k;
-        ms->m_valid = m_valid;
-        ms->status = 0;
-    }
-}
-
-// One block: inclusive prefix of the sample histogram in LDS, then for every rank the
-// interval from the sample's order statistics at P/N -/+ margin, then monotone ends.
 constexpr uint32_t PREDICT_THREADS = 1024;
 
 __global__ __launch_bounds__(PREDICT_THREADS) void ms_predict_kernel(
-    MultiState* ms, const uint32_t* __restrict__ shist, uint64_t n_prunable, double margin_sigmas,
-    uint8_t* __restrict__ tab) {
+    MultiState* ms, uint32_t* shist, uint32_t* cnt, PruneCounts sorted_p, MultiPerm perm,
+    uint32_t k_var, uint32_t m, uint64_t zero_mask, shifter_threshold* thr,
+    shifter_threshold* host_rec, uint64_t n_prunable, double margin_sigmas,
+    uint8_t* __restrict__ tab, uint32_t cap_sb_total, uint32_t* zero_ptr, uint32_t zero_n) {
     constexpr uint32_t SEG = 256, NSEG = MS_BINS / SEG, WAVES = PREDICT_THREADS / 64;
     static_assert(NSEG == 64, "one segment per lane in the scan of the segment sums");
     __shared__ uint32_t prefix[MS_BINS];          // 64 KB
@@ -81,14 +68,50 @@ __global__ __launch_bounds__(PREDICT_THREADS) void ms_predict_kernel(
     __shared__ uint32_t s_lo[MAXK];
     const uint32_t lane = threadIdx.x & 63u, wid = threadIdx.x >> 6;
     constexpr uint32_t PER_WAVE = NSEG / WAVES;   // segments per wavefront
-    // each wavefront's segments are loaded once, all loads in flight together
+    // each wavefront's segments are loaded once, all loads in flight together; the bins
+    // are then cleared: the next ranking's sample adds to them
     uint4 x[PER_WAVE];
 #pragma unroll
     for (uint32_t i = 0; i < PER_WAVE; ++i)
         x[i] = reinterpret_cast<const uint4*>(shist + (wid + i * WAVES) * SEG)[lane];
-    const uint32_t k_var = ms->k;
-    const uint32_t m = ms->m_valid;
-    const uint64_t p = threadIdx.x < k_var ? ms->p[threadIdx.x] : 0;
+#pragma unroll
+    for (uint32_t i = 0; i < PER_WAVE; ++i)
+        reinterpret_cast<uint4*>(shist + (wid + i * WAVES) * SEG)[lane] = make_uint4(0, 0, 0, 0);
+    // the split counters this ranking uses: rows 0 .. k_var and MAXK + 1 .. MAXK + k_var
+    for (uint32_t i = threadIdx.x; i < (2u * k_var + 1u) * SPEC_SUB; i += PREDICT_THREADS) {
+        const uint32_t row = i / SPEC_SUB, sb = i % SPEC_SUB;
+        const uint32_t r = row <= k_var ? row : MAXK + 1u + (row - (k_var + 1u));
+        cnt[((size_t)r * SPEC_SUB + sb) * 32u] = 0;
+    }
+    for (uint32_t i = threadIdx.x; i < zero_n; i += PREDICT_THREADS) zero_ptr[i] = 0;
+    if (threadIdx.x < MAXK) {
+        const uint32_t t = threadIdx.x;
+        ms->p[t] = t < k_var ? sorted_p.p[t] : 0;
+        ms->perm[t] = t < k_var ? perm.v[t] : 0;
+        if (t >= k_var) {                  // padding sorts last in the searches
+            ms->lo[t] = 0xffffffffu;
+            ms->hi[t] = 0xffffffffu;
+            ms->mid[t] = 0xffffffffu;
+            ms->sh[t] = 0;
+            ms->clast[t] = t;
+            ms->cand_off[t] = 0;
+            ms->cand_cap[t] = 0;
+        }
+        if ((zero_mask >> t) & 1ull) {
+            shifter_threshold out;
+            out.cut = 0; out.t_key = 0; out.reserved = 0; out.g_cut = ~0ull; out.n_prune = 0;
+            out.n_less = 0; out.n_equal = 0;
+            thr[t] = out;
+            host_rec[t] = out;
+        }
+    }
+    if (threadIdx.x == 0) {
+        ms->k = k_var;
+        ms->m_valid = m;
+        ms->status = 0;
+    }
+    if (k_var == 0) return;
+    const uint64_t p = threadIdx.x < k_var ? sorted_p.p[threadIdx.x] : 0;
     // phase 1: segment sums, then their exclusive scan by the first wavefront
 #pragma unroll
     for (uint32_t i = 0; i < PER_WAVE; ++i) {
@@ -158,6 +181,18 @@ __global__ __launch_bounds__(PREDICT_THREADS) void ms_predict_kernel(
             if (lane >= d) hi = max(hi, yh);
             if (lane + d < 64) lo = min(lo, yl);
         }
+        // clusters: rank k opens one unless its interval meets that of rank k - 1; every
+        // rank of a cluster takes the first one's lo and the last one's hi
+        const uint32_t hi_prev = __shfl_up(hi, 1, 64);
+        const bool opens = lane < k_var && (lane == 0 || lo > hi_prev);
+        const unsigned long long open_mask = __ballot(opens);
+        const unsigned long long upto = open_mask & (~0ull >> (63u - lane));     // openers at or below this lane
+        const uint32_t first = upto ? 63u - (uint32_t)__clzll(upto) : 0u;
+        const unsigned long long after = lane < 63u ? open_mask >> (lane + 1u) : 0ull;   // openers above it
+        uint32_t last = after ? lane + (uint32_t)__ffsll(after) - 1u : k_var - 1u;
+        if (lane >= k_var) last = lane;
+        lo = __shfl(lo, first, 64);
+        hi = __shfl(hi, min(last, 63u), 64);
         // provisional threshold of the fused pass: inside the interval, non-decreasing (a
         // running maximum: it stays below hi because hi is non-decreasing)
         uint32_t pm = lane < k_var ? min(max(mid, lo), hi) : 0u;
@@ -165,14 +200,34 @@ __global__ __launch_bounds__(PREDICT_THREADS) void ms_predict_kernel(
             const uint32_t y = __shfl_up(pm, d, 64);
             if (lane >= d) pm = max(pm, y);
         }
+        // each cluster's share of the candidate buffer, in proportion to the samples inside
+        // its interval (plus a little for the empty ones); the region belongs to the
+        // cluster's last rank
+        uint32_t wt = 0;
+        if (lane < k_var && last == lane) {
+            const uint32_t b_lo = lo >> MS_SHIFT, b_hi = min(hi >> MS_SHIFT, MS_BINS - 1u);
+            wt = prefix[b_hi] - (b_lo ? prefix[b_lo - 1u] : 0u) + 64u;
+        }
+        uint64_t wsum = wt;
+        for (uint32_t d = 32; d > 0; d >>= 1) wsum += __shfl_down(wsum, d, 64);
+        wsum = __shfl(wsum, 0, 64);
+        const uint32_t cap = wt ? (uint32_t)((uint64_t)cap_sb_total * wt / wsum) : 0u;
+        uint32_t cinc = cap;
+        for (uint32_t d = 1; d < 64; d <<= 1) {
+            const uint32_t y = __shfl_up(cinc, d, 64);
+            if (lane >= d) cinc += y;
+        }
         if (lane < k_var) {
-            const uint32_t span = hi - lo;   // smallest sh with (span >> sh) < MF_BINS1
-            const uint32_t sh = span < MF_BINS1 ? 0u : (32u - (uint32_t)__clz(span)) - 8u;
-            static_assert(MF_BINS1 == 256, "sh from the bit length of the span");
+            const uint32_t span = hi - lo;   // smallest sh with (span >> sh) < FIN_BINS
+            const uint32_t sh = span < FIN_BINS ? 0u : (32u - (uint32_t)__clz(span)) - 12u;
+            static_assert(FIN_BINS == 4096, "sh from the bit length of the span");
             ms->lo[lane] = lo;
             ms->hi[lane] = hi;
             ms->sh[lane] = sh;
             ms->mid[lane] = pm;
+            ms->clast[lane] = last;
+            ms->cand_cap[lane] = cap;
+            ms->cand_off[lane] = (cinc - cap) * SPEC_SUB;     // at most cap_sb_total * SPEC_SUB pairs
             s_lo[lane] = lo;
         }
     }
@@ -200,22 +255,52 @@ __global__ __launch_bounds__(PREDICT_THREADS) void ms_predict_kernel(
         tab[threadIdx.x + i * PREDICT_THREADS] = (uint8_t)(j0[i] | (min(inside[i], 3u) << 6));
 }
 
+// Appends the candidates a block found to the regions of their clusters: count per cluster
+// in LDS, one global reservation per cluster the block met, then the writes.  `for_each`
+// calls its argument once per candidate of the calling thread with (bits, global index).
+// All threads of the block call this; it contains barriers.
+template <typename ForEach>
+__device__ __forceinline__ void ms_append_candidates(
+    bool have, const uint32_t* s_lo, const uint32_t* s_coff, const uint32_t* s_ccap,
+    uint32_t* s_rc, uint32_t* s_rc2, uint32_t* s_rbase, uint32_t k_var, uint32_t* cnt, uint32_t sb,
+    uint2* __restrict__ cand, ForEach&& for_each) {
+    if (!__syncthreads_or(have ? 1 : 0)) return;      // uniform: no candidate in this block
+    if (have)
+        for_each([&](uint32_t bits, uint32_t) {
+            atomicAdd(&s_rc[count_lower_ends(s_lo, bits & 0x7fffffffu) - 1u], 1u);
+        });
+    __syncthreads();
+    if (threadIdx.x < k_var) {
+        const uint32_t c = s_rc[threadIdx.x];
+        if (c) s_rbase[threadIdx.x] = atomicAdd(mcnt_cand(cnt, threadIdx.x, sb), c);
+    }
+    __syncthreads();
+    if (have)
+        for_each([&](uint32_t bits, uint32_t g) {
+            const uint32_t cl = count_lower_ends(s_lo, bits & 0x7fffffffu) - 1u;
+            const uint32_t pos = s_rbase[cl] + atomicAdd(&s_rc2[cl], 1u);
+            const uint32_t cap = s_ccap[cl];
+            if (pos < cap) cand[(size_t)s_coff[cl] + (size_t)sb * cap + pos] = make_uint2(bits, g);
+        });
+}
+
 // The one pass over the arena: counts per j and candidate pairs.
 template <bool NT>
 __global__ __launch_bounds__(BLOCK) void ms_pass_kernel(
     const DevTensor* __restrict__ tens, const uint32_t* __restrict__ tile_prefix, uint32_t n_t,
     const float* __restrict__ w, MultiState* ms, uint32_t* cnt, uint2* __restrict__ cand,
-    uint32_t cap_sb, const uint8_t* __restrict__ tab) {
+    const uint8_t* __restrict__ tab) {
     // s_hi1[j] = hi_(j-1) + 1, s_hi1[0] = 0: a weight with j lower ends at or below it is a
-    // candidate (of rank j - 1) iff key < s_hi1[j]
+    // candidate (of the cluster ending at rank j - 1) iff key < s_hi1[j]
     __shared__ uint32_t s_lo[MAXK + 1], s_hi1[MAXK + 1];
+    __shared__ uint32_t s_coff[MAXK], s_ccap[MAXK], s_rc[MAXK], s_rc2[MAXK], s_rbase[MAXK];
     // counts per j: one private byte column per thread (a thread sees 16 weights; no
     // conflicts, no atomics), summed at the end; rows 0 .. k_var of BLOCK bytes (the launch
     // sizes it).  Small, so that a CU holds as many blocks as it has wavefront slots: a
     // block's life is a chain of memory latencies, which only other blocks can hide.
     extern __shared__ uint32_t s_col[];
     __shared__ __align__(16) uint8_t s_tab[TAB_SIZE];
-    __shared__ uint32_t s_nan, s_base, s_wtot[BLOCK / 64];
+    __shared__ uint32_t s_nan;
     const uint32_t tile = blockIdx.x;
     const uint32_t t = find_tensor(tile_prefix, n_t, tile);
     if (!tens[t].prunable) return;
@@ -223,9 +308,7 @@ __global__ __launch_bounds__(BLOCK) void ms_pass_kernel(
     const uint32_t e0 = (tile - tile_prefix[t]) * TILE;
     const uint32_t n = min(TILE, T.numel - e0);
     const uint32_t g0 = (uint32_t)(T.gbase + e0);
-    const uint32_t lane = threadIdx.x & 63u, wid = threadIdx.x >> 6;
     const uint32_t sb = blockIdx.x & (SPEC_SUB - 1);
-    uint2* my_cand = cand + (size_t)sb * cap_sb;
     // the tile's loads go out first: the set-up below runs while they are in flight
     const float* src = w + T.offset + e0;
     const bool whole = n == TILE && (T.offset & 3u) == 0;
@@ -241,10 +324,16 @@ __global__ __launch_bounds__(BLOCK) void ms_pass_kernel(
         s_lo[threadIdx.x] = threadIdx.x < MAXK ? ms->lo[threadIdx.x] : 0xffffffffu;
         s_hi1[threadIdx.x] = (threadIdx.x >= 1 && threadIdx.x <= k_var) ? ms->hi[threadIdx.x - 1] + 1u : 0u;
     }
+    if (threadIdx.x < MAXK) {
+        s_coff[threadIdx.x] = ms->cand_off[threadIdx.x];
+        s_ccap[threadIdx.x] = ms->cand_cap[threadIdx.x];
+        s_rc[threadIdx.x] = 0;
+        s_rc2[threadIdx.x] = 0;
+    }
     for (uint32_t i = threadIdx.x; i < (k_var + 1) * (BLOCK / 4); i += BLOCK) s_col[i] = 0;
     static_assert(TAB_SIZE == BLOCK * 16, "one 16-byte piece of the table per thread");
     reinterpret_cast<uint4*>(s_tab)[threadIdx.x] = reinterpret_cast<const uint4*>(tab)[threadIdx.x];
-    if (threadIdx.x == 0) { s_nan = 0; s_base = 0; }
+    if (threadIdx.x == 0) s_nan = 0;
     __syncthreads();
 
     uint32_t key_max = 0;   // a NaN's key is above that of +inf
@@ -259,11 +348,7 @@ __global__ __launch_bounds__(BLOCK) void ms_pass_kernel(
         uint32_t j = e & 63u;
         if (e >> 6) {
             if ((e >> 6) == 3u) {
-                j = 0;
-#pragma unroll
-                for (uint32_t step = MAXK / 2; step >= 1; step >>= 1)
-                    if (s_lo[j + step - 1] <= key) j += step;
-                j += s_lo[j] <= key ? 1u : 0u;      // j in [0, MAXK]; s_lo[MAXK] is padding
+                j = count_lower_ends(s_lo, key);    // j in [0, MAXK]; s_lo[MAXK] is padding
             } else {
                 // the lower ends are sorted: the second one counts only if the first does
                 const uint32_t j0 = j;
@@ -282,48 +367,28 @@ __global__ __launch_bounds__(BLOCK) void ms_pass_kernel(
             cmask |= ((one(v[u].x) ? 1u : 0u) | (one(v[u].y) ? 2u : 0u) | (one(v[u].z) ? 4u : 0u) |
                       (one(v[u].w) ? 8u : 0u)) << (4 * u);
         }
-        const uint32_t c = __popc(cmask);
-        uint32_t incl = c;
-        for (uint32_t d = 1; d < 64; d <<= 1) {
-            const uint32_t y = __shfl_up(incl, d, 64);
-            if (lane >= d) incl += y;
-        }
-        if (lane == 63) s_wtot[wid] = incl;
-        __syncthreads();
-        uint32_t woff = 0, btot = 0;
+        ms_append_candidates(cmask != 0, s_lo, s_coff, s_ccap, s_rc, s_rc2, s_rbase, k_var, cnt, sb, cand,
+                             [&](auto&& f) {
 #pragma unroll
-        for (uint32_t i = 0; i < BLOCK / 64; ++i) {
-            const uint32_t x = s_wtot[i];
-            if (i < wid) woff += x;
-            btot += x;
-        }
-        if (btot) {   // uniform over the block
-            if (threadIdx.x == 0) s_base = atomicAdd(mcnt(cnt, MC_CAND, sb), btot);
-            __syncthreads();
-            uint32_t pos = s_base + woff + incl - c;
-            if (cmask) {
+                                 for (uint32_t u = 0; u < U; ++u) {
+                                     const uint32_t j = (threadIdx.x + BLOCK * u) * 4;
+                                     const uint32_t vv[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
 #pragma unroll
-                for (uint32_t u = 0; u < U; ++u) {
-                    const uint32_t j = (threadIdx.x + BLOCK * u) * 4;
-                    const uint32_t vv[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
-#pragma unroll
-                    for (uint32_t q = 0; q < 4; ++q) {
-                        if (cmask & (1u << (4 * u + q))) {
-                            if (pos < cap_sb) my_cand[pos] = make_uint2(vv[q], g0 + j + q);
-                            ++pos;
-                        }
-                    }
-                }
-            }
-        }
+                                     for (uint32_t q = 0; q < 4; ++q)
+                                         if (cmask & (1u << (4 * u + q))) f(vv[q], g0 + j + q);
+                                 }
+                             });
     } else {
+        // ragged or unaligned tile (a few per tensor): one global atomic per candidate
         for (uint32_t j0 = 0; j0 < n; j0 += BLOCK) {
             const uint32_t j = j0 + threadIdx.x;
             if (j < n) {
                 const uint32_t bits = __float_as_uint(src[j]);
                 if (one(bits)) {
-                    const uint32_t pos = atomicAdd(mcnt(cnt, MC_CAND, sb), 1u);
-                    if (pos < cap_sb) my_cand[pos] = make_uint2(bits, g0 + j);
+                    const uint32_t cl = count_lower_ends(s_lo, bits & 0x7fffffffu) - 1u;
+                    const uint32_t pos = atomicAdd(mcnt_cand(cnt, cl, sb), 1u);
+                    const uint32_t cap = s_ccap[cl];
+                    if (pos < cap) cand[(size_t)s_coff[cl] + (size_t)sb * cap + pos] = make_uint2(bits, g0 + j);
                 }
             }
         }
@@ -342,254 +407,140 @@ __global__ __launch_bounds__(BLOCK) void ms_pass_kernel(
             odd += (x >> 8) & 0x00ff00ffu;
         }
         const uint32_t c = (even & 0xffffu) + (even >> 16) + (odd & 0xffffu) + (odd >> 16);
-        if (c) atomicAdd(mcnt(cnt, MC_BELOW + j, sb), c);
+        if (c) atomicAdd(mcnt_below(cnt, j, sb), c);
     }
     if (threadIdx.x == 0 && s_nan) atomicOr(&ms->status, 2u);
 }
 
-// Visits every candidate pair (see the one-count selection); THREADS: the block size.
-template <uint32_t THREADS = BLOCK, typename F>
-__device__ __forceinline__ void ms_for_each_candidate(const uint32_t* cnt, const uint2* cand,
-                                                      uint32_t cap_sb, F&& f) {
-    const uint32_t sb = blockIdx.x % SPEC_SUB, part = blockIdx.x / SPEC_SUB;
-    const uint32_t parts = gridDim.x / SPEC_SUB;
-    const uint32_t n = min(cnt[((size_t)MC_CAND * SPEC_SUB + sb) * 32u], cap_sb);
-    const uint2* src = cand + (size_t)sb * cap_sb;
-    // four chunks per step: the loads of a step are all in flight before the first is used
-    // (a block holds few wavefronts, so one load per thread at a time leaves the walk
-    // waiting on memory latency)
-    constexpr uint32_t U = 4;
-    for (uint32_t i0 = part * THREADS; i0 < n; i0 += U * parts * THREADS) {
-        uint2 c[U];
-        bool valid[U];
+// Calls f(pair) for every pair of cluster `cl`'s region: a wavefront takes the region's
+// sub-buffers in turn and keeps FIN_DEPTH loads per lane in flight (one block per rank has
+// to pull about a megabyte through one CU; the loads' latency is what it waits for).
+template <typename F>
+__device__ __forceinline__ void ms_walk_region(const uint2* __restrict__ region, uint32_t cap,
+                                               const uint32_t* s_n, F&& f) {
+    const uint32_t lane = threadIdx.x & 63u, wid = threadIdx.x >> 6;
+    for (uint32_t sb = wid; sb < SPEC_SUB; sb += FIN_THREADS / 64) {
+        const uint32_t n = s_n[sb];
+        const uint2* src = region + (size_t)sb * cap;
+        for (uint32_t i0 = 0; i0 < n; i0 += 64u * FIN_DEPTH) {
+            uint2 c[FIN_DEPTH];
 #pragma unroll
-        for (uint32_t u = 0; u < U; ++u) {
-            const uint32_t i = i0 + u * parts * THREADS + threadIdx.x;
-            valid[u] = i < n;
-            c[u] = valid[u] ? src[i] : make_uint2(0, 0);
+            for (uint32_t u = 0; u < FIN_DEPTH; ++u) {
+                const uint32_t i = i0 + u * 64u + lane;
+                c[u] = i < n ? src[i] : make_uint2(0xffffffffu, 0xffffffffu);
+            }
+#pragma unroll
+            for (uint32_t u = 0; u < FIN_DEPTH; ++u)
+                if (i0 + u * 64u + lane < n) f(c[u]);
         }
-#pragma unroll
-        for (uint32_t u = 0; u < U; ++u) f(c[u], valid[u]);
     }
 }
 
-// ranks whose interval holds key: [ka, kb)
-__device__ __forceinline__ void rank_range(const uint32_t* s_lo, const uint32_t* s_hi, uint32_t key,
-                                           uint32_t* ka, uint32_t* kb) {
-    uint32_t j = 0, a = 0;
-#pragma unroll
-    for (uint32_t step = MAXK / 2; step >= 1; step >>= 1) {
-        if (s_lo[j + step - 1] <= key) j += step;
-        if (s_hi[a + step - 1] < key) a += step;
-    }
-    j += s_lo[j] <= key ? 1u : 0u;
-    a += s_hi[a] < key ? 1u : 0u;
-    *ka = a;   // first k with hi_k >= key
-    *kb = j;   // #{k : lo_k <= key}
-}
-
-// Round 1: per block and per rank a 256-bin LDS histogram of (key - lo_k) >> sh_k.
-__global__ __launch_bounds__(MF_THREADS) void ms_hist_kernel(
-    const MultiState* __restrict__ ms, const uint32_t* __restrict__ cnt,
-    const uint2* __restrict__ cand, uint32_t cap_sb, uint32_t* __restrict__ partial) {
-    extern __shared__ uint32_t h[];   // k_var * 256
-    __shared__ uint32_t s_lo[MAXK + 1], s_hi[MAXK + 1], s_sh[MAXK];
-    const uint32_t k_var = ms->k;
-    for (uint32_t i = threadIdx.x; i < k_var * MF_BINS1; i += MF_THREADS) h[i] = 0;
-    if (threadIdx.x <= MAXK) {
-        s_lo[threadIdx.x] = threadIdx.x < MAXK ? ms->lo[threadIdx.x] : 0xffffffffu;
-        s_hi[threadIdx.x] = threadIdx.x < MAXK ? ms->hi[threadIdx.x] : 0xffffffffu;
-        if (threadIdx.x < MAXK) s_sh[threadIdx.x] = ms->sh[threadIdx.x];
-    }
-    __syncthreads();
-    ms_for_each_candidate<MF_THREADS>(cnt, cand, cap_sb, [&](uint2 c, bool valid) {
-        if (!valid) return;
-        const uint32_t key = c.x & 0x7fffffffu;
-        uint32_t ka, kb;
-        rank_range(s_lo, s_hi, key, &ka, &kb);
-        for (uint32_t k = ka; k < kb; ++k)
-            atomicAdd(&h[k * MF_BINS1 + ((key - s_lo[k]) >> s_sh[k])], 1u);
-    });
-    __syncthreads();
-    for (uint32_t i = threadIdx.x; i < k_var * MF_BINS1; i += MF_THREADS)
-        partial[(size_t)blockIdx.x * k_var * MF_BINS1 + i] = h[i];
-}
-
-// One block per rank: totals, the check that makes the result exact, the round-1 bin.
-// Thread t of each quarter of the block owns bin t and sums a quarter of the partial
-// histograms (the loads are what the kernel waits for); the first quarter then decides.
-constexpr uint32_t LOCATE_THREADS = 1024, LOCATE_PARTS = LOCATE_THREADS / MF_BINS1;
-
-__global__ __launch_bounds__(LOCATE_THREADS) void ms_locate_kernel(
-    MultiState* ms, const uint32_t* __restrict__ cnt, const uint32_t* __restrict__ partial,
-    uint32_t cap_sb) {
-    __shared__ uint64_t smem[LOCATE_THREADS / 64 + 1];
-    __shared__ uint32_t s_part[LOCATE_PARTS - 1][MF_BINS1];
-    __shared__ uint32_t s_over;
-    const uint32_t k = blockIdx.x, k_var = ms->k;
-    const uint32_t bin = threadIdx.x & (MF_BINS1 - 1), part = threadIdx.x / MF_BINS1;
+// The finish, one block per rank: totals of the split counters, the check that makes the
+// result exact (below < P <= below + candidates of the rank's cluster), then the P-th pair
+// among the candidates by histogram refinement - 4096 bins over the interval, again over
+// the selected bin while it holds more than FIN_LIST pairs - and an exact rank by counting
+// inside the last bin.  The record goes to d_thr and to its mirror in pinned host memory;
+// every block leaves its status word there as well (bit 0: could not decide, bit 1: NaN).
+__global__ __launch_bounds__(FIN_THREADS) void ms_finish_kernel(
+    MultiState* ms, const uint32_t* __restrict__ cnt, const uint2* __restrict__ cand,
+    shifter_threshold* thr, shifter_threshold* host_rec, uint32_t* host_status) {
+    __shared__ uint32_t h[FIN_BINS];
+    __shared__ uint64_t comp[FIN_LIST];
+    __shared__ uint64_t smem[FIN_THREADS / 64 + 1];
+    __shared__ uint32_t s_n[SPEC_SUB];
+    __shared__ uint64_t s_sel, s_base;
+    __shared__ uint32_t s_over, s_bin, s_cnt, s_lt, s_eq, s_nb;
+    const uint32_t k = blockIdx.x;
+    const uint32_t cl = ms->clast[k];
     const uint64_t p = ms->p[k];
-    if (threadIdx.x == 0) s_over = 0;
+    const uint32_t cap = ms->cand_cap[cl];
+    const uint2* region = cand + ms->cand_off[cl];
+    const uint32_t nan_bit = ms->status & 2u;      // the pass has ended
+    auto give_up = [&]() {
+        if (threadIdx.x == 0) {
+            atomicOr(&ms->status, 1u);
+            host_status[k] = 1u | nan_bit;
+        }
+    };
+    if (threadIdx.x == 0) { s_over = 0; s_sel = 0; s_nb = 0; s_lt = 0; s_eq = 0; }
     __syncthreads();
-    static_assert(SPEC_SUB == MF_BINS1, "one split counter per thread of the first quarter");
-    static_assert(MF_BLOCKS % LOCATE_PARTS == 0, "the partial histograms split evenly");
     uint64_t below, inside;
     {
-        uint32_t b = 0;
-        if (part == 0) {
-            for (uint32_t j = 0; j <= k; ++j) b += cnt[((size_t)(MC_BELOW + j) * SPEC_SUB + bin) * 32u];
-            if (cnt[((size_t)MC_CAND * SPEC_SUB + bin) * 32u] > cap_sb) s_over = 1;
+        static_assert(SPEC_SUB <= FIN_THREADS, "one split counter column per thread");
+        uint32_t b = 0, c = 0;
+        if (threadIdx.x < SPEC_SUB) {
+            for (uint32_t j = 0; j <= k; ++j) b += cnt[((size_t)j * SPEC_SUB + threadIdx.x) * 32u];
+            c = cnt[((size_t)(MAXK + 1u + cl) * SPEC_SUB + threadIdx.x) * 32u];
+            if (c > cap) s_over = 1;
+            s_n[threadIdx.x] = min(c, cap);
         }
-        block_excl_scan_u64<LOCATE_THREADS>(b, smem, &below);
-    }
-    // this rank's round-1 histogram
-    uint32_t c = 0;
-    constexpr uint32_t PER = MF_BLOCKS / LOCATE_PARTS;
-#pragma unroll 8
-    for (uint32_t q = part * PER; q < (part + 1) * PER; ++q)
-        c += partial[((size_t)q * k_var + k) * MF_BINS1 + bin];
-    if (part) s_part[part - 1][bin] = c;
-    __syncthreads();
-    if (part == 0) {
-        for (uint32_t i = 0; i < LOCATE_PARTS - 1; ++i) c += s_part[i][bin];
-    } else {
-        c = 0;
-    }
-    const uint64_t base = block_excl_scan_u64<LOCATE_THREADS>(c, smem, &inside);
-    __syncthreads();
-    if (s_over || !(below < p && p <= below + inside)) {
-        if (threadIdx.x == 0) atomicOr(&ms->status, 1u);
-        return;
-    }
-    const uint64_t r = p - below;
-    if (part == 0 && base < r && r <= base + c) {
-        ms->bin[k] = bin;
-        ms->bin_cnt[k] = c;
-        ms->r2[k] = r - base;
-        ms->less[k] = below + base;
-        if (c > SPEC_LIST_CAP) atomicOr(&ms->status, 1u);
-    }
-}
-
-// Candidates of each rank's selected bin -> that rank's list, one segment per block
-// (LDS counters only: no global atomics).
-__global__ __launch_bounds__(MF_THREADS) void ms_filter_kernel(
-    MultiState* ms, const uint32_t* __restrict__ cnt, const uint2* __restrict__ cand,
-    uint32_t cap_sb, uint2* __restrict__ seg, uint32_t* __restrict__ seg_cnt) {
-    __shared__ uint32_t s_lo[MAXK + 1], s_hi[MAXK + 1], s_sh[MAXK], s_bin[MAXK], s_n[MAXK];
-    const uint32_t k_var = ms->k;
-    if (ms->status & 1u) return;
-    if (threadIdx.x <= MAXK) {
-        s_lo[threadIdx.x] = threadIdx.x < MAXK ? ms->lo[threadIdx.x] : 0xffffffffu;
-        s_hi[threadIdx.x] = threadIdx.x < MAXK ? ms->hi[threadIdx.x] : 0xffffffffu;
-        if (threadIdx.x < MAXK) {
-            s_sh[threadIdx.x] = ms->sh[threadIdx.x];
-            s_bin[threadIdx.x] = ms->bin[threadIdx.x];
-            s_n[threadIdx.x] = 0;
-        }
+        block_excl_scan_u64<FIN_THREADS>(b, smem, &below);
+        block_excl_scan_u64<FIN_THREADS>(c, smem, &inside);
     }
     __syncthreads();
-    ms_for_each_candidate<MF_THREADS>(cnt, cand, cap_sb, [&](uint2 c, bool valid) {
-        if (!valid) return;
-        const uint32_t key = c.x & 0x7fffffffu;
-        uint32_t ka, kb;
-        rank_range(s_lo, s_hi, key, &ka, &kb);
-        for (uint32_t k = ka; k < kb; ++k) {
-            if (((key - s_lo[k]) >> s_sh[k]) == s_bin[k]) {
-                const uint32_t pos = atomicAdd(&s_n[k], 1u);
-                if (pos < SPEC_SEG_CAP)
-                    seg[((size_t)k * MF_BLOCKS + blockIdx.x) * SPEC_SEG_CAP + pos] = c;
+    if (s_over || !(below < p && p <= below + inside)) { give_up(); return; }
+    uint64_t r = p - below;          // 1-based rank among the pairs still in play
+    uint64_t less = below;           // weights below them
+    uint32_t lo_cur = ms->lo[k], sh = ms->sh[k];
+    uint32_t width_sh = 32;          // the pairs in play have (key - lo_cur) >> width_sh == 0
+    uint32_t cnt_sel;
+    for (;;) {
+        for (uint32_t i = threadIdx.x; i < FIN_BINS; i += FIN_THREADS) h[i] = 0;
+        __syncthreads();
+        ms_walk_region(region, cap, s_n, [&](uint2 c) {
+            const uint32_t d = (c.x & 0x7fffffffu) - lo_cur;      // wraps for keys below lo_cur
+            if (width_sh >= 32 || (d >> width_sh) == 0) atomicAdd(&h[d >> sh], 1u);
+        });
+        __syncthreads();
+        constexpr uint32_t PER = FIN_BINS / FIN_THREADS;
+        const uint32_t b0 = threadIdx.x * PER;
+        uint64_t sum = 0, tot;
+        uint32_t c4[PER];
+#pragma unroll
+        for (uint32_t i = 0; i < PER; ++i) { c4[i] = h[b0 + i]; sum += c4[i]; }
+        uint64_t base = block_excl_scan_u64<FIN_THREADS>(sum, smem, &tot);
+        if (base < r && r <= base + sum) {
+#pragma unroll
+            for (uint32_t i = 0; i < PER; ++i) {
+                if (base < r && r <= base + c4[i]) { s_bin = b0 + i; s_cnt = c4[i]; s_base = base; }
+                base += c4[i];
             }
+        }
+        __syncthreads();
+        if (tot < r) { give_up(); return; }     // cannot happen unless the buffers were disturbed
+        less += s_base;
+        r -= s_base;
+        lo_cur += s_bin << sh;
+        width_sh = sh;
+        cnt_sel = s_cnt;
+        __syncthreads();
+        if (cnt_sel <= FIN_LIST) break;
+        if (sh == 0) { give_up(); return; }     // more equal keys than the list holds: the multi-pass select ranks ties
+        sh = sh > 12u ? sh - 12u : 0u;
+    }
+    // the pairs of the last bin, then the r-th of them by counting
+    ms_walk_region(region, cap, s_n, [&](uint2 c) {
+        const uint32_t key = c.x & 0x7fffffffu, d = key - lo_cur;
+        if ((d >> width_sh) == 0) {
+            const uint32_t pos = atomicAdd(&s_nb, 1u);
+            if (pos < FIN_LIST) comp[pos] = ((uint64_t)key << 32) | c.y;
         }
     });
     __syncthreads();
-    if (threadIdx.x < k_var) {
-        const uint32_t nn = s_n[threadIdx.x];
-        seg_cnt[threadIdx.x * MF_BLOCKS + blockIdx.x] = min(nn, SPEC_SEG_CAP);
-        if (nn > SPEC_SEG_CAP) atomicOr(&ms->status, 1u);
-    }
-}
-
-// One block per rank: round-2 histogram over the rank's list (thread t walks segment t),
-// exact rank by counting inside the selected bin, the record.
-__global__ __launch_bounds__(BLOCK) void ms_rank_kernel(MultiState* ms,
-                                                        const uint2* __restrict__ seg,
-                                                        const uint32_t* __restrict__ seg_cnt,
-                                                        shifter_threshold* thr) {
-    __shared__ uint32_t h[MF_BINS2];
-    __shared__ uint64_t comp[SPEC_SMALL_CAP];
-    __shared__ uint64_t smem[BLOCK / 64 + 1];
-    __shared__ uint64_t s_sel, s_less2, s_r3;
-    __shared__ uint32_t s_lt, s_eq, s_bin2, s_cnt2, s_nb;
-    const uint32_t k = blockIdx.x;
-    shifter_threshold out;
-    out.reserved = 0;
-    out.n_prune = ms->p[k];
-    shifter_threshold* dst = thr + ms->perm[k];
-    if (ms->status & 1u) return;
-    static_assert(MF_BLOCKS == BLOCK, "one list segment per thread");
-    const uint32_t my_n = seg_cnt[k * MF_BLOCKS + threadIdx.x];
-    const uint2* my_seg = seg + ((size_t)k * MF_BLOCKS + threadIdx.x) * SPEC_SEG_CAP;
-    uint64_t n_tot;
-    block_excl_scan_u64(my_n, smem, &n_tot);
-    if (n_tot != ms->bin_cnt[k]) {   // cannot happen unless the buffers were disturbed
-        if (threadIdx.x == 0) atomicOr(&ms->status, 1u);
-        return;
-    }
-    const uint32_t sh = ms->sh[k];
-    const uint32_t sh2 = sh > 12 ? sh - 12 : 0;   // 2^sh keys over 2^12 bins
-    const uint32_t lo1 = ms->lo[k] + (ms->bin[k] << sh);
-    for (uint32_t i = threadIdx.x; i < MF_BINS2; i += BLOCK) h[i] = 0;
-    if (threadIdx.x == 0) { s_lt = 0; s_eq = 0; s_sel = 0; s_nb = 0; s_cnt2 = 0; s_bin2 = 0; }
-    __syncthreads();
-    for (uint32_t i = 0; i < my_n; ++i) atomicAdd(&h[((my_seg[i].x & 0x7fffffffu) - lo1) >> sh2], 1u);
-    __syncthreads();
-    constexpr uint32_t PER = MF_BINS2 / BLOCK;
-    const uint32_t b0 = threadIdx.x * PER;
-    uint64_t sum = 0, tot;
-    for (uint32_t i = 0; i < PER; ++i) sum += h[b0 + i];
-    uint64_t base = block_excl_scan_u64(sum, smem, &tot);
-    const uint64_t r = ms->r2[k];
-    if (base < r && r <= base + sum) {
-        for (uint32_t i = 0; i < PER; ++i) {
-            const uint32_t c = h[b0 + i];
-            if (r <= base + c) {
-                s_bin2 = b0 + i;
-                s_cnt2 = c;
-                s_r3 = r - base;
-                s_less2 = base;
-                break;
-            }
-            base += c;
-        }
-    }
-    __syncthreads();
-    const uint32_t bin2 = s_bin2, cnt2 = s_cnt2;
-    if (cnt2 == 0 || cnt2 > SPEC_SMALL_CAP) {
-        if (threadIdx.x == 0) atomicOr(&ms->status, 1u);
-        return;
-    }
-    for (uint32_t i = 0; i < my_n; ++i) {
-        const uint2 c = my_seg[i];
-        const uint32_t key = c.x & 0x7fffffffu;
-        if (((key - lo1) >> sh2) == bin2) {
-            const uint32_t pos = atomicAdd(&s_nb, 1u);
-            comp[pos] = ((uint64_t)key << 32) | c.y;   // pos < cnt2 <= SPEC_SMALL_CAP
-        }
-    }
-    __syncthreads();
-    const uint64_t want = s_r3 - 1;
-    for (uint32_t i = threadIdx.x; i < cnt2; i += BLOCK) {
+    if (s_nb != cnt_sel) { give_up(); return; }
+    const uint64_t want = r - 1;
+    for (uint32_t i = threadIdx.x; i < cnt_sel; i += FIN_THREADS) {
         const uint64_t c = comp[i];
         uint32_t rank = 0;
-        for (uint32_t f = 0; f < cnt2; ++f) rank += comp[f] < c;
-        if (rank == want) s_sel = c;
+        for (uint32_t f = 0; f < cnt_sel; ++f) rank += comp[f] < c;
+        if (rank == want) s_sel = c;        // composites are distinct: exactly one hit
     }
     __syncthreads();
     const uint64_t sel = s_sel;
     const uint32_t key = (uint32_t)(sel >> 32);
     uint32_t lt = 0, eq = 0;
-    for (uint32_t i = threadIdx.x; i < cnt2; i += BLOCK) {
+    for (uint32_t i = threadIdx.x; i < cnt_sel; i += FIN_THREADS) {
         const uint32_t kk = (uint32_t)(comp[i] >> 32);
         lt += kk < key;
         eq += kk == key;
@@ -598,12 +549,18 @@ __global__ __launch_bounds__(BLOCK) void ms_rank_kernel(MultiState* ms,
     if (eq) atomicAdd(&s_eq, eq);
     __syncthreads();
     if (threadIdx.x == 0) {
+        shifter_threshold out;
+        out.reserved = 0;
+        out.n_prune = p;
         out.t_key = key;
         out.g_cut = sel & 0xffffffffull;
         out.cut = sel + 1;
-        out.n_less = ms->less[k] + s_less2 + s_lt;
+        out.n_less = less + s_lt;
         out.n_equal = s_eq;
-        *dst = out;
+        const uint32_t dst = ms->perm[k];
+        thr[dst] = out;
+        host_rec[dst] = out;
+        host_status[k] = nan_bit;
     }
 }
 
@@ -627,16 +584,17 @@ template <bool NT>
 __global__ __launch_bounds__(BLOCK) void ms_fused_kernel(
     const DevTensor* __restrict__ tens, const uint32_t* __restrict__ tile_prefix, uint32_t n_t,
     const float* __restrict__ w, MultiState* ms, uint32_t* cnt, uint2* __restrict__ cand,
-    uint32_t cap_sb, VariantRanks rv, uint32_t k_all, float* __restrict__ w_out,
+    VariantRanks rv, uint32_t k_all, float* __restrict__ w_out,
     uint64_t w_stride, uint8_t* __restrict__ mask, uint64_t mask_stride, uint32_t* out_level,
     uint32_t* in_level) {
     __shared__ uint32_t rowmax[TILE + 16];
     __shared__ uint32_t colmax[TILE + 16];
     __shared__ uint32_t s_lo[MAXK + 1], s_hi[MAXK + 1], s_mid[MAXK + 1];
+    __shared__ uint32_t s_coff[MAXK], s_ccap[MAXK], s_rc[MAXK], s_rc2[MAXK], s_rbase[MAXK];
     __shared__ int32_t s_rv[MAXK];
     __shared__ uint8_t s_col[(SPEC_MULTI_MAXK + 1) * BLOCK];   // private counters, <= 16 each
     __shared__ __align__(16) uint32_t s_xm[TILE / 4];
-    __shared__ uint32_t s_nan, s_base, s_wtot[BLOCK / 64];
+    __shared__ uint32_t s_nan;
 
     const uint32_t tile = blockIdx.x;
     const uint32_t t = find_tensor(tile_prefix, n_t, tile);
@@ -647,7 +605,6 @@ __global__ __launch_bounds__(BLOCK) void ms_fused_kernel(
     const uint32_t g0 = (uint32_t)(T.gbase + e0);
     const uint32_t lane = threadIdx.x & 63u, wid = threadIdx.x >> 6;
     const uint32_t sb = blockIdx.x & (SPEC_SUB - 1);
-    uint2* my_cand = cand + (size_t)sb * cap_sb;
     const uint32_t k_var = ms->k;
     const uint32_t c0 = e0 % T.khw, r0 = e0 % T.row_len;
     const uint32_t nrows = (r0 + n - 1) / T.row_len + 1;
@@ -659,9 +616,15 @@ __global__ __launch_bounds__(BLOCK) void ms_fused_kernel(
         s_hi[threadIdx.x] = threadIdx.x < MAXK ? ms->hi[threadIdx.x] : 0xffffffffu;
         s_mid[threadIdx.x] = threadIdx.x < MAXK ? ms->mid[threadIdx.x] : 0xffffffffu;
     }
-    if (threadIdx.x < MAXK) s_rv[threadIdx.x] = rv.r[threadIdx.x];
+    if (threadIdx.x < MAXK) {
+        s_rv[threadIdx.x] = rv.r[threadIdx.x];
+        s_coff[threadIdx.x] = ms->cand_off[threadIdx.x];
+        s_ccap[threadIdx.x] = ms->cand_cap[threadIdx.x];
+        s_rc[threadIdx.x] = 0;
+        s_rc2[threadIdx.x] = 0;
+    }
     for (uint32_t j = 0; j <= k_var; ++j) s_col[j * BLOCK + threadIdx.x] = 0;
-    if (threadIdx.x == 0) { s_nan = 0; s_base = 0; }
+    if (threadIdx.x == 0) s_nan = 0;
     __syncthreads();
 
     uint32_t nan = 0;
@@ -673,11 +636,7 @@ __global__ __launch_bounds__(BLOCK) void ms_fused_kernel(
         if (!ranked) return 127u;
         const uint32_t key = bits & 0x7fffffffu;
         nan |= key > 0x7f800000u ? 1u : 0u;
-        uint32_t j = 0;
-#pragma unroll
-        for (uint32_t step = MAXK / 2; step >= 1; step >>= 1)
-            if (s_lo[j + step - 1] <= key) j += step;
-        j += s_lo[j] <= key ? 1u : 0u;
+        uint32_t j = count_lower_ends(s_lo, key);
         is_cand = j >= 1 && key <= s_hi[j - 1];
         s_col[j * BLOCK + threadIdx.x] += 1;
         // a candidate is written as kept by the ranks below j - 1 and, by rank j - 1 (with
@@ -755,41 +714,18 @@ __global__ __launch_bounds__(BLOCK) void ms_fused_kernel(
             for (uint32_t q = 0; q < 4; ++q)
                 if (!(cmask & (1u << (4 * u + q)))) mark(j + q, b[q], lvl[u][q]);
         }
-        // candidate pairs: one reservation per block in this block's sub-buffer
-        const uint32_t c = __popc(cmask);
-        uint32_t incl = c;
-        for (uint32_t d = 1; d < 64; d <<= 1) {
-            const uint32_t y = __shfl_up(incl, d, 64);
-            if (lane >= d) incl += y;
-        }
-        if (lane == 63) s_wtot[wid] = incl;
-        __syncthreads();
-        uint32_t woff = 0, btot = 0;
+        // candidate pairs: to the regions of their clusters
+        ms_append_candidates(cmask != 0, s_lo, s_coff, s_ccap, s_rc, s_rc2, s_rbase, k_var, cnt, sb, cand,
+                             [&](auto&& f) {
 #pragma unroll
-        for (uint32_t i = 0; i < BLOCK / 64; ++i) {
-            const uint32_t x = s_wtot[i];
-            if (i < wid) woff += x;
-            btot += x;
-        }
-        if (btot) {   // uniform over the block
-            if (threadIdx.x == 0) s_base = atomicAdd(mcnt(cnt, MC_CAND, sb), btot);
-            __syncthreads();
-            uint32_t pos = s_base + woff + incl - c;
-            if (cmask) {
+                                 for (uint32_t u = 0; u < U; ++u) {
+                                     const uint32_t j = (q0 + 64u * u) * 4;
+                                     const uint32_t vv[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
 #pragma unroll
-                for (uint32_t u = 0; u < U; ++u) {
-                    const uint32_t j = (q0 + 64u * u) * 4;
-                    const uint32_t vv[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
-#pragma unroll
-                    for (uint32_t q = 0; q < 4; ++q) {
-                        if (cmask & (1u << (4 * u + q))) {
-                            if (pos < cap_sb) my_cand[pos] = make_uint2(vv[q], g0 + j + q);
-                            ++pos;
-                        }
-                    }
-                }
-            }
-        }
+                                     for (uint32_t q = 0; q < 4; ++q)
+                                         if (cmask & (1u << (4 * u + q))) f(vv[q], g0 + j + q);
+                                 }
+                             });
     } else {
         for (uint32_t j0 = 0; j0 < n; j0 += BLOCK) {
             const uint32_t j = j0 + threadIdx.x;
@@ -806,8 +742,10 @@ __global__ __launch_bounds__(BLOCK) void ms_fused_kernel(
                     if (want_mask) mask[(uint64_t)k * mask_stride + T.gbase + e0 + j] = keep ? 1 : 0;
                 }
                 if (is_cand) {
-                    const uint32_t pos = atomicAdd(mcnt(cnt, MC_CAND, sb), 1u);
-                    if (pos < cap_sb) my_cand[pos] = make_uint2(bits, g0 + j);
+                    const uint32_t cl = count_lower_ends(s_lo, bits & 0x7fffffffu) - 1u;
+                    const uint32_t pos = atomicAdd(mcnt_cand(cnt, cl, sb), 1u);
+                    const uint32_t cap = s_ccap[cl];
+                    if (pos < cap) cand[(size_t)s_coff[cl] + (size_t)sb * cap + pos] = make_uint2(bits, g0 + j);
                 } else {
                     mark(j, bits, level);
                 }
@@ -822,7 +760,7 @@ __global__ __launch_bounds__(BLOCK) void ms_fused_kernel(
         const uint32_t j = threadIdx.x >> 2, q = threadIdx.x & 3u;
         uint32_t c = 0;
         for (uint32_t i = 0; i < BLOCK / 4; ++i) c += s_col[j * BLOCK + ((i * 4 + q + j) & (BLOCK - 1))];
-        if (c) atomicAdd(mcnt(cnt, MC_BELOW + j, sb), c);
+        if (c) atomicAdd(mcnt_below(cnt, j, sb), c);
     }
     if (threadIdx.x == 0 && s_nan) atomicOr(&ms->status, 2u);
     // levels of the tile's filters and input features
@@ -844,15 +782,31 @@ __global__ __launch_bounds__(BLOCK) void ms_fused_kernel(
     }
 }
 
+// ranks whose interval holds key: [ka, kb)
+__device__ __forceinline__ void rank_range(const uint32_t* s_lo, const uint32_t* s_hi, uint32_t key,
+                                           uint32_t* ka, uint32_t* kb) {
+    uint32_t j = 0, a = 0;
+#pragma unroll
+    for (uint32_t step = MAXK / 2; step >= 1; step >>= 1) {
+        if (s_lo[j + step - 1] <= key) j += step;
+        if (s_hi[a + step - 1] < key) a += step;
+    }
+    j += s_lo[j] <= key ? 1u : 0u;
+    a += s_hi[a] < key ? 1u : 0u;
+    *ka = a;   // first k with hi_k >= key
+    *kb = j;   // #{k : lo_k <= key}
+}
+
 // Settles the candidates of ms_fused_kernel with the exact cuts: the pass wrote a
 // candidate of ranks [a, j) as kept in all of them but the last, and in rank j - 1 iff
 // key >= mid_{j-1}; here it is rewritten in every rank where that was the wrong side of
 // the exact cut, and its level (variants that keep it: those that remove nothing, the
 // ranks below a, and the ranks of [a, j) that keep it) goes into the level arrays.
+// blockIdx.x: sub-buffer, blockIdx.y: rank (only a cluster's last rank owns a region).
 __global__ __launch_bounds__(BLOCK) void ms_fixup_kernel(
     const DevTensor* __restrict__ tens, const uint32_t* __restrict__ ranked_ids, uint32_t n_ranked,
     const MultiState* __restrict__ ms, const uint32_t* __restrict__ cnt,
-    const uint2* __restrict__ cand, uint32_t cap_sb, const shifter_threshold* __restrict__ thr,
+    const uint2* __restrict__ cand, const shifter_threshold* __restrict__ thr,
     uint32_t n_zero, float* __restrict__ w_out, uint64_t w_stride, uint8_t* __restrict__ mask,
     uint64_t mask_stride, uint32_t* out_level, uint32_t* in_level) {
     constexpr uint32_t LDS_T = 1024;
@@ -860,6 +814,12 @@ __global__ __launch_bounds__(BLOCK) void ms_fixup_kernel(
     __shared__ uint32_t s_lo[MAXK + 1], s_hi[MAXK + 1], s_mid[MAXK], s_perm[MAXK];
     __shared__ uint64_t s_cut[MAXK];
     if (ms->status & 1u) return;
+    const uint32_t cl = blockIdx.y, sb = blockIdx.x;
+    if (ms->clast[cl] != cl) return;
+    const uint32_t cap = ms->cand_cap[cl];
+    const uint32_t n = min(cnt[((size_t)(MAXK + 1u + cl) * SPEC_SUB + sb) * 32u], cap);
+    if (n == 0) return;
+    const uint2* src = cand + (size_t)ms->cand_off[cl] + (size_t)sb * cap;
     const uint32_t k_var = ms->k;
     const bool in_lds = n_ranked <= LDS_T;
     if (in_lds)
@@ -875,8 +835,7 @@ __global__ __launch_bounds__(BLOCK) void ms_fixup_kernel(
         s_mid[threadIdx.x] = ms->mid[threadIdx.x];
     }
     __syncthreads();
-    ms_for_each_candidate(cnt, cand, cap_sb, [&](uint2 c, bool valid) {
-        if (!valid) return;
+    auto settle = [&](uint2 c) {
         const uint32_t key = c.x & 0x7fffffffu;
         uint32_t ka, kb;
         rank_range(s_lo, s_hi, key, &ka, &kb);
@@ -907,70 +866,74 @@ __global__ __launch_bounds__(BLOCK) void ms_fixup_kernel(
             f = in_level + T.in_flag_off + (e / T.khw) % T.in_ch;
             if (*f < level) atomicMax(f, level);
         }
-    });
+    };
+    // four pairs per thread and step, their loads in flight together
+    constexpr uint32_t U = 4;
+    for (uint32_t i0 = 0; i0 < n; i0 += U * BLOCK) {
+        uint2 c[U];
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u) {
+            const uint32_t i = i0 + u * BLOCK + threadIdx.x;
+            c[u] = i < n ? src[i] : make_uint2(0, 0);
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u)
+            if (i0 + u * BLOCK + threadIdx.x < n) settle(c[u]);
+    }
 }
 
 void launch_spec_multi(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
                        const PruneCounts& sorted_p, const MultiPerm& perm, uint32_t k,
-                       uint64_t zero_mask, shifter_threshold* d_thr, const FusedBatch* fb) {
+                       uint64_t zero_mask, shifter_threshold* d_thr, const FusedBatch* fb,
+                       uint32_t* zero_ptr, uint32_t zero_n) {
     const auto& b = m->b;
     const uint32_t n_t = (uint32_t)m->t.size();
     hipStream_t s = ctx->stream;
+    if (k != 0) {
+        ProfileScope ps(ctx, K_SPEC_SAMPLE);
+        launch_spec_sample(ctx, m, d_w);     // adds to the sample histogram, which every ranking leaves cleared
+    }
     {
-        ProfileScope ps(ctx, K_SPEC_INIT);
-        ms_init_kernel<<<64, BLOCK, 0, s>>>(b.multi, b.shist, b.multi_cnt, sorted_p, perm, k,
-                                            m->sample_size, zero_mask, d_thr);
+        // with the fused pass the level arrays are cleared here, ahead of it
+        if (fb && !zero_ptr) {
+            zero_ptr = b.levels;
+            zero_n = (uint32_t)(m->info.sum_out_ch + m->info.sum_in_ch);
+        }
+        ProfileScope ps(ctx, K_SPEC_PREDICT);
+        ms_predict_kernel<<<1, PREDICT_THREADS, 0, s>>>(
+            b.multi, b.shist, b.multi_cnt, sorted_p, perm, k, m->sample_size, zero_mask, d_thr,
+            b.dev_multi_rec, m->info.n_prunable, ctx->margin_sigmas, b.multi_tab, b.cand_cap_sb,
+            zero_ptr, zero_n);
     }
     if (k == 0 && !fb) return;   // every count was zero
-    if (k != 0) {
-        {
-            ProfileScope ps(ctx, K_SPEC_SAMPLE);
-            launch_spec_sample(ctx, m, d_w);
-        }
-        {
-            ProfileScope ps(ctx, K_SPEC_PREDICT);
-            ms_predict_kernel<<<1, PREDICT_THREADS, 0, s>>>(b.multi, b.shist, m->info.n_prunable,
-                                                            ctx->margin_sigmas, b.multi_tab);
-        }
-    }
     const bool nt = m->info.w_extent * 4 > (192ull << 20);
     if (fb) {
         VariantRanks rv;
         for (uint32_t v = 0; v < MAXK; ++v) rv.r[v] = -1;
         for (uint32_t r = 0; r < k; ++r) rv.r[perm.v[r]] = (int32_t)r;
-        launch_zero_levels(ctx, m);
         ProfileScope ps(ctx, K_MASK_SCAN_BATCH);
         // non-temporal hint as in the batched mask pass: only for cache-sized arenas
         auto kern = !nt ? ms_fused_kernel<true> : ms_fused_kernel<false>;
         kern<<<m->n_tiles, BLOCK, 0, s>>>(b.tens, b.tile_prefix, n_t, d_w, b.multi, b.multi_cnt, b.cand,
-                                          b.cand_cap_sb, rv, fb->k_all, fb->d_w_out, fb->w_stride,
+                                          rv, fb->k_all, fb->d_w_out, fb->w_stride,
                                           fb->d_mask, fb->mask_stride, b.levels,
                                           b.levels + m->info.sum_out_ch);
     } else {
         ProfileScope ps(ctx, K_SPEC_PASS);
         auto kern = nt ? ms_pass_kernel<true> : ms_pass_kernel<false>;
         kern<<<m->n_tiles, BLOCK, (k + 1) * BLOCK, s>>>(
-            b.tens, b.tile_prefix, n_t, d_w, b.multi, b.multi_cnt, b.cand, b.cand_cap_sb, b.multi_tab);
+            b.tens, b.tile_prefix, n_t, d_w, b.multi, b.multi_cnt, b.cand, b.multi_tab);
     }
     if (k != 0) {
-        {
-            ProfileScope ps(ctx, K_SPEC_FINISH);
-            ms_hist_kernel<<<MF_BLOCKS, MF_THREADS, k * MF_BINS1 * sizeof(uint32_t), s>>>(
-                b.multi, b.multi_cnt, b.cand, b.cand_cap_sb, b.multi_partial);
-            ms_locate_kernel<<<k, LOCATE_THREADS, 0, s>>>(b.multi, b.multi_cnt, b.multi_partial, b.cand_cap_sb);
-        }
-        {
-            ProfileScope ps(ctx, K_SPEC_FINISH2);
-            ms_filter_kernel<<<MF_BLOCKS, MF_THREADS, 0, s>>>(b.multi, b.multi_cnt, b.cand, b.cand_cap_sb,
-                                                         b.multi_seg, b.multi_seg_cnt);
-            ms_rank_kernel<<<k, BLOCK, 0, s>>>(b.multi, b.multi_seg, b.multi_seg_cnt, d_thr);
-        }
+        ProfileScope ps(ctx, K_SPEC_FINISH);
+        ms_finish_kernel<<<k, FIN_THREADS, 0, s>>>(b.multi, b.multi_cnt, b.cand, d_thr,
+                                                   b.dev_multi_rec, b.dev_multi_status);
     }
     if (fb) {
         if (k != 0) {
             ProfileScope ps(ctx, K_SPEC_FIXUP);
-            ms_fixup_kernel<<<MF_BLOCKS * 4, BLOCK, 0, s>>>(
-                b.tens, b.ranked_ids, m->n_ranked, b.multi, b.multi_cnt, b.cand, b.cand_cap_sb, d_thr,
+            ms_fixup_kernel<<<dim3(SPEC_SUB, k), BLOCK, 0, s>>>(
+                b.tens, b.ranked_ids, m->n_ranked, b.multi, b.multi_cnt, b.cand, d_thr,
                 fb->k_all - k, fb->d_w_out, fb->w_stride, fb->d_mask, fb->mask_stride, b.levels,
                 b.levels + m->info.sum_out_ch);
         }
