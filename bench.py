@@ -131,16 +131,9 @@ def measure(name, steps, warmup, lean_run=True, cpu_leg=True):
         pl.enable_batch(k_var)
 
     def step(collect=None, sparse_arenas=True):
-        if k_var == 1:
-            # one prune count: ranking, mask and scan in a single read of the arena; plan
-            # and rebuild enqueued behind it, one wait for the whole step
-            _, out = pl.single(n_prune[0])
-            if collect is not None:
-                collect.append(out[3])
-            return
-        # a portfolio: one ranking call for all counts, then one batched call per step
-        _, out = pl.portfolio(n_prune, 0, with_in_alive=True, sync=True,
-                              sparse_arenas=sparse_arenas)
+        # one pair of calls per step: the library enqueues ranking, masks, scan, plans and
+        # rebuilds for all prune counts and waits once
+        _, out = pl.step(n_prune, 0, with_in_alive=True, sparse_arenas=sparse_arenas)
         if collect is not None:
             collect.extend(int(x) for x in out[3])
 

@@ -518,6 +518,59 @@ int shifter_prune_fused_batch(shifter_ctx* ctx, const shifter_model* model, cons
  * and everything enqueued behind _begin must be repeated (rare: heavy ties).  One
  * _begin at a time per context.  SHIFTER_ERR_NONFINITE from _end if a prunable weight
  * is NaN. */
+/* All five steps for the K prune counts of a portfolio (K = 1 included) behind one pair of
+ * calls (Sec. III-C, Sec. III-D Modules 2-4): _begin checks the arguments and enqueues the
+ * whole step - ranking, sparse arenas, masks, flags, group plans, rebuilt variants - in the
+ * order and with the kernel fusion that suits the arena's size, and returns without
+ * waiting; _end waits for the stream once and returns the records and the rebuilt
+ * variants' descriptors.  Every output is identical to what the single steps give
+ * (shifter_global_threshold, shifter_apply_mask_batch, shifter_propagate_groups_batch,
+ * shifter_compact_batch).  If the single-pass ranking could not decide (rare: heavy ties),
+ * _end runs the multi-pass select and repeats the later steps itself before it returns.
+ *   d_w, d_vecs       device, the dense weight arena and the vector arena
+ *   h_n_prune, K      host, K prune counts
+ *   flags             as shifter_propagate_groups
+ *   d_thr             device, K records, written
+ *   d_w_sparse        device, K sparse arenas w_stride floats apart, or NULL (not materialised)
+ *   d_mask            device, K masks mask_stride bytes apart, or NULL
+ *   d_out_alive       device, K * sum_out_ch bytes; d_in_alive: K * sum_in_ch bytes, or NULL
+ *   d_group_alive, d_index_map, d_keep: device, K * sum_group_width entries each;
+ *   d_new_width       device, K * n_groups
+ *   d_w_out, cap_w    device, K output arenas cap_w floats apart (a multiple of 4 if K > 1)
+ *   d_vecs_out, cap_v device, K vector arenas cap_v floats apart
+ * The pointers must stay valid until _end; one _begin at a time per context, and no other
+ * call on the context in between.
+ * _end: h_thr K records; h_out_tensors K * n_tensors, h_out_vecs K * n_vecs, h_elems_w /
+ * h_elems_v K entries; each may be NULL.  Returns SHIFTER_ERR_NONFINITE (NaN among the
+ * prunable weights), SHIFTER_ERR_CAPACITY (a variant does not fit and was not gathered),
+ * SHIFTER_WARN_COLLAPSE (some variant lost a whole group; outputs valid). */
+typedef struct {
+    const float* d_w;
+    const float* d_vecs;
+    const uint64_t* h_n_prune;
+    uint32_t K;
+    uint32_t flags;
+    shifter_threshold* d_thr;
+    float* d_w_sparse;
+    uint64_t w_stride;
+    uint8_t* d_mask;
+    uint64_t mask_stride;
+    uint8_t* d_out_alive;
+    uint8_t* d_in_alive;
+    uint8_t* d_group_alive;
+    int32_t* d_index_map;
+    uint32_t* d_keep;
+    uint32_t* d_new_width;
+    float* d_w_out;
+    uint64_t cap_w;
+    float* d_vecs_out;
+    uint64_t cap_v;
+} shifter_portfolio_args;
+int shifter_portfolio_begin(shifter_ctx* ctx, const shifter_model* model,
+                            const shifter_portfolio_args* args);
+int shifter_portfolio_end(shifter_ctx* ctx, shifter_threshold* h_thr,
+                          shifter_tensor_desc* h_out_tensors, shifter_vec_desc* h_out_vecs,
+                          uint64_t* h_elems_w, uint64_t* h_elems_v);
 int shifter_global_threshold_begin(shifter_ctx* ctx, const shifter_model* model,
                                    const float* d_w, const uint64_t* h_n_prune, uint32_t K,
                                    shifter_threshold* d_thr);

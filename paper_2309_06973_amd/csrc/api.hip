@@ -20,7 +20,7 @@ const char* const kKernelNames[K_COUNT] = {
     "deflate_chunk", "codec_scan", "codec_pack", "inflate_chunk",
     "mask_scan_batch", "expand_levels",
     "spec_init", "spec_sample", "spec_predict", "spec_pass", "spec_hist_locate", "spec_filter_rank",
-    "spec_fixup"};
+    "spec_fixup", "spec_rank"};
 
 ProfileScope::ProfileScope(shifter_ctx* c, int id) : ctx(c), idx(-1) {
     if (!c->profiling) return;
@@ -149,7 +149,8 @@ static void unbind(shifter_model* m) {
                     b.coltab, b.kernel_off, b.fix_prefix, b.cons_prefix, b.consumers, b.fix_alive,
                     b.fix_produced, b.fix_read, b.fix_out_flags, b.fix_removed, b.fold,
                     b.fold_scale, b.levels, b.spec, b.shist, b.spec_cnt, b.partial, b.cand, b.list,
-                    b.ranked_ids, b.multi, b.multi_cnt, b.multi_tab, b.plan_done};
+                    b.ranked_ids, b.multi, b.multi_cnt, b.multi_tab, b.below, b.multi_hist,
+                    b.multi_list, b.multi_list_cnt, b.multi_rowsum};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     if (b.host_stage) (void)hipHostFree(b.host_stage);
@@ -514,8 +515,13 @@ static int bind_tables(shifter_ctx* ctx, shifter_model* m) {
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.multi), sizeof(MultiState)));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.multi_cnt), sizeof(uint32_t) * (2 * MAXK + 1) * SPEC_SUB * 32));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.multi_tab), 4096));
-    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.plan_done), sizeof(uint32_t) * MAXK));
-    HIP_TRY(ctx, hipMemset(b.plan_done, 0, sizeof(uint32_t) * MAXK));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.multi_hist), sizeof(uint32_t) * MAXK * 256));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.multi_list),
+                           sizeof(uint2) * (size_t)SPEC_MULTI_MAXK * SPEC_LIST_CAP));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.multi_list_cnt), sizeof(uint32_t) * MAXK));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.multi_rowsum), sizeof(uint64_t) * (MAXK + 1)));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.below),
+                           sizeof(uint32_t) * MAXK * (m->info.sum_group_width + m->g.size())));
     b.host_stage_bytes = sizeof(SelState) + sizeof(shifter_threshold) * MAXK +
                          MAXK * (sizeof(PlanHeader) + sizeof(PlanTensor) * n_t + sizeof(PlanVec) * n_v +
                                  sizeof(uint32_t) * m->g.size()) +
@@ -611,8 +617,8 @@ static int multi_result(shifter_ctx* ctx, const shifter_model* model, uint32_t k
     *decided = (status & 1u) ? 0 : 1;
     if (*decided) {
         if (h_thr) memcpy(h_thr, model->b.host_multi + MULTI_MIRROR_REC_OFF, sizeof(shifter_threshold) * K);
-    } else if (ctx->margin_sigmas < 64.0) {
-        ctx->margin_sigmas *= 2.0;
+    } else if (!(status & 4u) && ctx->margin_sigmas < 64.0) {
+        ctx->margin_sigmas *= 2.0;     // a prediction missed: wider intervals from now on
     }
     return SHIFTER_OK;
 }
@@ -1258,6 +1264,151 @@ static int compact_impl(shifter_ctx* ctx, const shifter_model* model, const floa
         return plan_readout(ctx, model, K, h_out_tensors, h_out_vecs, h_elems_w, h_elems_v);
     }
     return SHIFTER_OK;
+}
+
+// ---- a whole portfolio step behind one call ---------------------------------------------
+
+// The multi-pass ranking and everything behind it for a portfolio step: the path of a step
+// whose single pass is switched off, does not apply or could not decide.
+// Position of every variant in the order of the cuts: the cut grows strictly with the prune
+// count (P = 0 gives cut 0), so it is the position of its count, ties by index - known on
+// the host before any record exists.
+static MultiPerm cut_positions(const PruneCounts& pc, uint32_t K) {
+    MultiPerm pos;
+    memset(&pos, 0, sizeof pos);
+    for (uint32_t k = 0; k < K; ++k)
+        for (uint32_t j = 0; j < K; ++j)
+            pos.v[k] += (pc.p[j] < pc.p[k] || (pc.p[j] == pc.p[k] && j < k)) ? 1u : 0u;
+    return pos;
+}
+
+static int portfolio_radix(shifter_ctx* ctx, const shifter_model* model, const PruneCounts& pc,
+                           const PortfolioBuffers& a) {
+    int rc;
+    launch_select(ctx, model, a.d_w, pc, a.k_var, a.d_thr);
+    if ((rc = after_launch(ctx, "portfolio"))) return rc;
+    if ((rc = rank_result_enqueue(ctx, model, &model->b.sel->nan_seen, a.d_thr, a.k_var))) return rc;
+    launch_zero_levels(ctx, model);
+    launch_mask_scan_batch_core(ctx, model, a.d_w, a.d_thr, a.k_var, a.d_w_sparse, a.w_stride, a.d_mask,
+                                a.mask_stride);
+    launch_plan_and_gather(ctx, model, a, true, cut_positions(pc, a.k_var));
+    return after_launch(ctx, "portfolio");
+}
+
+extern "C" int shifter_portfolio_begin(shifter_ctx* ctx, const shifter_model* model,
+                                       const shifter_portfolio_args* args) {
+    int rc = enter(ctx, model, "portfolio_begin");
+    if (rc) return rc;
+    if (!args) return fail(ctx, SHIFTER_ERR_INVALID_ARG, "portfolio_begin: args is NULL");
+    if (ctx->pending_portfolio.active || ctx->pending.active || ctx->pending_rank.active)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG,
+                    "portfolio_begin: an earlier deferred call on this context has not been collected");
+    const shifter_portfolio_args& g = *args;
+    const size_t n_v = model->v.size();
+    if (!g.d_w || !g.h_n_prune || !g.d_thr || !g.d_out_alive || !g.d_group_alive || !g.d_index_map ||
+        !g.d_keep || !g.d_new_width || !g.d_w_out || (n_v && (!g.d_vecs || !g.d_vecs_out)))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "portfolio_begin: NULL pointer argument");
+    const uint32_t K = g.K;
+    if (K == 0 || K > MAXK)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "portfolio_begin: K must be in [1, SHIFTER_MAX_VARIANTS]");
+    if (misaligned(g.d_w, 16) || misaligned(g.d_w_sparse, 16) || misaligned(g.d_mask, 4) ||
+        misaligned(g.d_thr, 8) || misaligned(g.d_w_out, 16) || (K > 1 && (g.cap_w & 3u)))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG,
+                    "portfolio_begin: arenas must be 16-byte aligned, masks 4-byte aligned, cap_w a "
+                    "multiple of 4 for several variants");
+    if ((g.d_w_sparse && K > 1 && g.w_stride < model->info.w_extent) ||
+        (g.d_mask && K > 1 && g.mask_stride < model->info.n_prunable))
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "portfolio_begin: stride smaller than one variant");
+    if (g.d_w_sparse == g.d_w)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "portfolio_begin: cannot work in place");
+    if (g.flags & ~SHIFTER_PAPER_FREEZE_RESIDUAL)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "portfolio_begin: unknown flag bits");
+    auto& pp = ctx->pending_portfolio;
+    memset(&pp.pc, 0, sizeof pp.pc);
+    uint32_t idx[MAXK], k_eff = 0;
+    uint64_t zero_mask = 0;
+    for (uint32_t k = 0; k < K; ++k) {
+        if (g.h_n_prune[k] > model->info.n_prunable)
+            return fail(ctx, SHIFTER_ERR_INVALID_ARG, "portfolio_begin: prune count exceeds N");
+        pp.pc.p[k] = g.h_n_prune[k];
+        if (pp.pc.p[k] == 0) zero_mask |= 1ull << k; else idx[k_eff++] = k;
+    }
+    pp.buf = PortfolioBuffers{g.d_w, g.d_vecs, K, g.flags, g.d_thr, g.d_w_sparse, g.w_stride, g.d_mask,
+                              g.mask_stride, g.d_out_alive, g.d_in_alive, g.d_group_alive, g.d_index_map,
+                              g.d_keep, g.d_new_width, g.d_w_out, g.cap_w, g.d_vecs_out, g.cap_v};
+    pp.model = model;
+    pp.k_eff = k_eff;
+    const auto& b = model->b;
+    if (ctx->select_path == 0 && K == 1 && g.d_w_sparse && g.d_in_alive) {
+        // one prune count: ranking, sparse arena, mask and flags in a single read
+        pp.mode = 1;
+        launch_spec_select(ctx, model, g.d_w, pp.pc.p[0], g.d_thr, g.d_w_sparse, g.d_mask, g.d_out_alive,
+                           g.d_in_alive);
+        if ((rc = after_launch(ctx, "portfolio_begin"))) return rc;
+        if ((rc = spec_result_enqueue(ctx, model, b.host_spec))) return rc;
+        launch_plan_and_gather(ctx, model, pp.buf, false, cut_positions(pp.pc, K));
+    } else if (ctx->select_path == 0 && k_eff <= SPEC_MULTI_MAXK) {
+        PruneCounts sp;
+        MultiPerm perm;
+        memset(&sp, 0, sizeof sp);
+        memset(&perm, 0, sizeof perm);
+        std::stable_sort(idx, idx + k_eff, [&](uint32_t x, uint32_t y) { return pp.pc.p[x] < pp.pc.p[y]; });
+        for (uint32_t i = 0; i < k_eff; ++i) { sp.p[i] = pp.pc.p[idx[i]]; perm.v[i] = idx[i]; }
+        pp.mode = 2;
+        if (model->info.w_extent * 4 > (192ull << 20)) {
+            // an arena beyond the last-level cache: ranking, masks and levels in one read of it
+            FusedBatch fb{K, g.d_w_sparse, g.w_stride, g.d_mask, g.mask_stride, g.d_out_alive, g.d_in_alive};
+            launch_spec_multi(ctx, model, g.d_w, sp, perm, k_eff, zero_mask, g.d_thr, &fb);
+            launch_plan_and_gather(ctx, model, pp.buf, false, cut_positions(pp.pc, K));
+        } else {
+            // a cache-sized arena: the counting pass, then the mask pass reads it again; the
+            // planning launch expands the levels into the variants' flags on the way
+            launch_spec_multi(ctx, model, g.d_w, sp, perm, k_eff, zero_mask, g.d_thr, nullptr, b.levels,
+                              (uint32_t)(model->info.sum_out_ch + model->info.sum_in_ch));
+            launch_mask_scan_batch_core(ctx, model, g.d_w, g.d_thr, K, g.d_w_sparse, g.w_stride, g.d_mask,
+                                        g.mask_stride);
+            launch_plan_and_gather(ctx, model, pp.buf, true, cut_positions(pp.pc, K));
+        }
+    } else {
+        pp.mode = 3;
+        if ((rc = portfolio_radix(ctx, model, pp.pc, pp.buf))) return rc;
+    }
+    if ((rc = after_launch(ctx, "portfolio_begin"))) return rc;
+    pp.active = true;
+    return SHIFTER_OK;
+}
+
+extern "C" int shifter_portfolio_end(shifter_ctx* ctx, shifter_threshold* h_thr,
+                                     shifter_tensor_desc* h_out_tensors, shifter_vec_desc* h_out_vecs,
+                                     uint64_t* h_elems_w, uint64_t* h_elems_v) {
+    if (!ctx) return fail(nullptr, SHIFTER_ERR_INVALID_ARG, "portfolio_end: ctx is NULL");
+    auto& pp = ctx->pending_portfolio;
+    if (!pp.active) return fail(ctx, SHIFTER_ERR_INVALID_ARG, "portfolio_end: nothing to collect");
+    pp.active = false;
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    const shifter_model* model = pp.model;
+    const uint32_t K = pp.buf.k_var;
+    int rc, decided = 0;
+    if (pp.mode == 1) {
+        if ((rc = spec_result_collect(ctx, model->b.host_spec, h_thr, &decided))) return rc;
+    } else if (pp.mode == 2) {
+        if ((rc = multi_result(ctx, model, pp.k_eff, K, h_thr, &decided, "portfolio_end"))) return rc;
+    }
+    if (!decided) {
+        if (pp.mode != 3) {
+            // the single pass could not decide: the multi-pass select, and every later step again
+            if ((rc = portfolio_radix(ctx, model, pp.pc, pp.buf))) return rc;
+        }
+        ctx->last_path = 2;
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+        const uint8_t* st = model->b.host_multi;
+        uint32_t nan_seen;
+        memcpy(&nan_seen, st, sizeof nan_seen);
+        if (nan_seen)
+            return fail(ctx, SHIFTER_ERR_NONFINITE, "portfolio_end: NaN among the prunable weights");
+        if (h_thr) memcpy(h_thr, st + MULTI_MIRROR_REC_OFF, sizeof(shifter_threshold) * K);
+    }
+    return plan_readout(ctx, model, K, h_out_tensors, h_out_vecs, h_elems_w, h_elems_v);
 }
 
 extern "C" int shifter_compact_batch(shifter_ctx* ctx, const shifter_model* model, const float* d_w_sparse,

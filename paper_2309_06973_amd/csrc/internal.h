@@ -97,14 +97,29 @@ struct SpecState {
 // State of the single-pass selection for all prune counts of a portfolio (ranks sorted by
 // prune count, zero counts left out).
 constexpr uint32_t SPEC_MULTI_MAXK = 32;   // LDS of the fused pass's private counters: 256 B per rank
+// What the finish of one rank reads (written by the predict kernel) and what its filter step
+// leaves for its last step: one cache line each instead of a line per field.
+struct RankIn {
+    uint64_t p;
+    uint32_t lo, sh;                       // its cluster's interval start; the first histogram's shift (256 bins)
+    uint32_t clast, cand_off, cand_cap;    // its cluster's last rank and candidate region
+    uint32_t perm;                         // original position of this rank
+};
+struct RankOut {
+    uint64_t r2, less;     // rank of the P-th pair inside the selected bin; weights below that bin
+    uint32_t bin, bin_cnt;
+    uint32_t fail;         // why the finish gave up (0: it has not)
+    uint32_t pad;
+};
 struct MultiState {
     uint64_t p[MAXK];
     uint32_t perm[MAXK];   // original position of sorted rank k
     uint32_t lo[MAXK], hi[MAXK];   // candidate interval; ranks whose intervals met share one (a cluster)
-    uint32_t sh[MAXK];     // first refinement level of the finish: bin = (key - lo) >> sh
     uint32_t mid[MAXK];    // predicted threshold key of rank k, lo <= mid <= hi, non-decreasing
     uint32_t clast[MAXK];  // last rank of rank k's cluster: the owner of the cluster's candidate region
-    uint32_t cand_off[MAXK], cand_cap[MAXK];   // region of the cluster ending at rank k: first pair, pairs per sub-buffer
+    uint32_t cand_off[MAXK], cand_cap[MAXK];   // region of the cluster ending at rank k: first pair, pairs per part
+    RankIn rin[MAXK];
+    RankOut rout[MAXK];
     uint32_t k, m_valid, status, pad;
 };
 struct MultiPerm {
@@ -150,11 +165,25 @@ enum KernelId {
     K_DEFLATE_CHUNK, K_CODEC_SCAN, K_CODEC_PACK, K_INFLATE_CHUNK,
     K_MASK_SCAN_BATCH, K_EXPAND_LEVELS,
     K_SPEC_INIT, K_SPEC_SAMPLE, K_SPEC_PREDICT, K_SPEC_PASS, K_SPEC_FINISH, K_SPEC_FINISH2,
-    K_SPEC_FIXUP,
+    K_SPEC_FIXUP, K_SPEC_RANK,
     K_COUNT
 };
 extern const char* const kKernelNames[K_COUNT];
 
+}  // namespace shifter
+
+namespace shifter {
+// Device buffers of one portfolio step (shifter_portfolio_begin's arguments, checked).
+struct PortfolioBuffers {
+    const float* d_w; const float* d_vecs;
+    uint32_t k_var, flags;
+    shifter_threshold* d_thr;
+    float* d_w_sparse; uint64_t w_stride;          // or nullptr
+    uint8_t* d_mask; uint64_t mask_stride;         // or nullptr
+    uint8_t* d_out_alive; uint8_t* d_in_alive;     // in: or nullptr
+    uint8_t* d_group_alive; int32_t* d_index_map; uint32_t* d_keep; uint32_t* d_new_width;
+    float* d_w_out; uint64_t cap_w; float* d_vecs_out; uint64_t cap_v;
+};
 }  // namespace shifter
 
 struct shifter_model {
@@ -229,7 +258,11 @@ struct shifter_model {
         shifter::MultiState* multi = nullptr;
         uint32_t* multi_cnt = nullptr;        // (2 * MAXK + 1) * SPEC_SUB counters, 128-byte lines
         uint8_t* multi_tab = nullptr;         // 4096 bucket entries of the K-rank pass
-        uint32_t* plan_done = nullptr;        // MAXK tickets of the planner (zero between launches)
+        uint32_t* multi_hist = nullptr;       // MAXK * 256: the clusters' first histograms
+        uint64_t* multi_rowsum = nullptr;     // MAXK + 1: totals of the split counters' rows
+        uint2* multi_list = nullptr;          // SPEC_MULTI_MAXK * SPEC_LIST_CAP pairs: the ranks' selected bins
+        uint32_t* multi_list_cnt = nullptr;   // MAXK
+        uint32_t* below = nullptr;            // MAXK * (sum_group_width + n_groups): survivors below a channel
         uint8_t* host_stage = nullptr;        // pinned, for small read-backs
         uint8_t* host_spec = nullptr;         // pinned: outcome of a deferred shifter_prune_fused
         // pinned mirrors the kernels write themselves (no copy on the stream): the K-rank
@@ -287,6 +320,15 @@ struct shifter_ctx {
         shifter_threshold* d_thr = nullptr;
         bool single_pass = false;
     } pending_rank;
+    // a shifter_portfolio_begin whose outcome has not been collected yet
+    struct PendingPortfolio {
+        bool active = false;
+        const shifter_model* model = nullptr;
+        shifter::PortfolioBuffers buf{};
+        shifter::PruneCounts pc{};
+        uint32_t k_eff = 0;
+        int mode = 0;    // 1: one-count single pass; 2: K-rank single pass; 3: multi-pass select
+    } pending_portfolio;
 };
 
 namespace shifter {
@@ -322,7 +364,20 @@ void launch_flat_tables(shifter_ctx* ctx, DevTensor* tens, uint32_t* tile_prefix
 void launch_spec_select(shifter_ctx* ctx, const shifter_model* m, const float* d_w, uint64_t p,
                         shifter_threshold* d_thr, float* d_w_out, uint8_t* d_mask,
                         uint8_t* d_out_alive, uint8_t* d_in_alive);
-void launch_spec_sample(shifter_ctx* ctx, const shifter_model* m, const float* d_w);
+// Scratch of the K-rank ranking that the sample kernel clears on the way (cnt == nullptr:
+// nothing): the split counters' rows in use, the clusters' histograms, the list lengths
+// and the finish's per-rank outcome.
+struct SampleZero {
+    uint32_t* cnt = nullptr;
+    uint32_t k = 0;
+    uint32_t* ghist = nullptr;
+    uint32_t* list_cnt = nullptr;
+    RankOut* rout = nullptr;
+    uint32_t* extra = nullptr;     // one more array of extra_n words to clear
+    uint32_t extra_n = 0;
+};
+void launch_spec_sample(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
+                        const SampleZero& z = SampleZero());
 // Outputs of the fused portfolio pass (steps 1-3 in one read): k_all variants in caller order.
 struct FusedBatch {
     uint32_t k_all;
@@ -360,19 +415,9 @@ void launch_compact(shifter_ctx* ctx, const shifter_model* m, const float* d_w, 
                     const uint32_t* d_new_width, float* d_w_out, uint64_t cap_w,
                     float* d_vecs_out, uint64_t cap_v, uint32_t k_var,
                     const shifter_threshold* d_thr);
-// Device buffers of one portfolio step (shifter_portfolio_begin's arguments, checked).
-struct PortfolioBuffers {
-    const float* d_w; const float* d_vecs;
-    uint32_t k_var, flags;
-    shifter_threshold* d_thr;
-    float* d_w_sparse; uint64_t w_stride;          // or nullptr
-    uint8_t* d_mask; uint64_t mask_stride;         // or nullptr
-    uint8_t* d_out_alive; uint8_t* d_in_alive;     // in: or nullptr
-    uint8_t* d_group_alive; int32_t* d_index_map; uint32_t* d_keep; uint32_t* d_new_width;
-    float* d_w_out; uint64_t cap_w; float* d_vecs_out; uint64_t cap_v;
-};
+// pos[k] = number of variants that remove fewer weights than variant k (ties by index).
 void launch_plan_and_gather(shifter_ctx* ctx, const shifter_model* m, const PortfolioBuffers& a,
-                            bool from_levels);
+                            bool from_levels, const MultiPerm& pos);
 // The batched mask pass alone: with_zero clears the level arrays first, with_expand turns
 // them into the variants' flag bytes afterwards.
 void launch_mask_scan_batch_core(shifter_ctx* ctx, const shifter_model* m, const float* d_w,

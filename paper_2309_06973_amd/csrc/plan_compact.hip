@@ -22,7 +22,7 @@ __device__ __forceinline__ void propagate_group(
     const uint8_t* __restrict__ out_alive, const uint32_t* __restrict__ out_level, uint32_t pos,
     uint32_t flags, uint8_t* __restrict__ group_alive, int32_t* __restrict__ index_map,
     uint32_t* __restrict__ keep, uint32_t* __restrict__ new_width_g, uint32_t* wave_cnt,
-    uint32_t* s_flag_off) {
+    uint32_t* s_flag_off, uint32_t* below = nullptr) {
     constexpr uint32_t WAVES = PROP_THREADS / 64;
     const uint32_t n_prod = G.prod_end - G.prod_begin;
     const bool frozen = G.pinned || ((flags & SHIFTER_PAPER_FREEZE_RESIDUAL) && n_prod > 1);
@@ -61,12 +61,16 @@ __device__ __forceinline__ void propagate_group(
             group_alive[G.off + c] = (uint8_t)a;
             index_map[G.off + c] = a ? (int32_t)pos_c : -1;
             if (a) keep[G.off + pos_c] = c;
+            if (below) below[c] = pos_c;      // surviving channels below c
         }
         base += tot;
         __syncthreads();
     }
     for (uint32_t c = base + threadIdx.x; c < G.width; c += PROP_THREADS) keep[G.off + c] = 0xffffffffu;
-    if (threadIdx.x == 0) *new_width_g = base;
+    if (threadIdx.x == 0) {
+        *new_width_g = base;
+        if (below) below[G.width] = base;
+    }
 }
 
 __global__ __launch_bounds__(PROP_THREADS) void propagate_kernel(
@@ -392,90 +396,74 @@ __global__ __launch_bounds__(BLOCK) void rect_tables_kernel(
                      coltab_prefix, keep_all, new_width_all, group_stride, n_groups, rowtab, coltab);
 }
 
-// The whole planning of a portfolio step in one launch (Module 3 for every group and
-// variant, then Module 4's sizes and tables per variant).  blockIdx.y = variant.  Blocks
-// 0 .. n_groups - 1 each plan one group; the block that finishes a variant's last group
-// goes on to that variant's rebuild plan and, for the portfolio rebuild, its row and
-// column tables: it takes a ticket after a device-wide fence, so it sees what the other
-// blocks of its variant wrote, and it waits for nothing.  With levels as the source of
-// liveness the blocks from n_groups on expand them into the variant's flag bytes (the
-// outputs of the batched mask pass, which nothing in this launch reads).
+// The group planning of a portfolio step in one launch (Module 3 for every group and
+// variant, and the tables of Module 4's rebuild).  blockIdx.y = variant.  Blocks
+// 0 .. n_groups - 1 each plan one group and, for the portfolio rebuild, fill the row and
+// column tables of the tensors around it.  With levels as the source of liveness the blocks
+// from n_groups on expand them into the variant's flag bytes (the outputs of the batched
+// mask pass, which nothing in this launch reads).  The rebuild plans, which need every
+// group's new width, follow in plan_kernel: a rendezvous inside this launch (the last
+// block of a variant going on after a device-wide fence) was measured at 250 us - such a
+// fence writes back the whole L2 of the block's XCD, just filled by the mask pass.
 struct PlanAllArgs {
     const DevGroup* groups; const uint32_t* producers; const DevTensor* tens; uint32_t n_t;
     const DevVec* vecs; uint32_t n_v; uint32_t n_groups;
     const uint8_t* out_alive;          // flag bytes of every variant, or nullptr: take levels
-    const uint32_t* out_level; const uint32_t* in_level; const shifter_threshold* thr;
+    const uint32_t* out_level; const uint32_t* in_level;
+    MultiPerm pos;                     // with levels: variants that remove less than variant k
     uint64_t n_out, n_in;
     uint8_t* exp_out_alive; uint8_t* exp_in_alive;   // where the levels are expanded to (in: may be nullptr)
     uint32_t flags;
     uint8_t* group_alive; int32_t* index_map; uint32_t* keep; uint32_t* new_width;
     uint64_t group_stride;
-    uint64_t cap_w, cap_v;
-    PlanTensor* pt; PlanVec* pv; uint32_t* oup; PlanHeader* hdr; uint8_t* pack;
     const uint32_t* rowtab_prefix; const uint32_t* coltab_prefix; uint32_t* rowtab; uint32_t* coltab;
     uint32_t want_tables;
-    uint32_t* done;                    // one ticket counter per variant, zero between launches
+    uint32_t* below;                   // scratch: per variant and group, width + 1 counts of survivors below a channel
+    const uint32_t* cons_prefix; const uint32_t* consumers;
     uint32_t k_var;
 };
 
 __global__ __launch_bounds__(PROP_THREADS) void plan_all_kernel(const PlanAllArgs A) {
     __shared__ uint32_t wave_cnt[PROP_THREADS / 64];
     __shared__ uint32_t s_flag_off[PROP_LDS_PRODUCERS];
-    __shared__ uint64_t s_cut[MAXK];
-    __shared__ uint32_t s_pos[MAXK];
-    __shared__ uint64_t smem[PROP_THREADS / 64 + 1];
-    __shared__ uint32_t s_collapse, s_last;
     const uint32_t k = blockIdx.y;
-    uint32_t pos = 0;
-    if (!A.out_alive) {
-        // pos = number of variants whose cut is smaller than variant k's (ties by index)
-        if (threadIdx.x < A.k_var) s_cut[threadIdx.x] = A.thr[threadIdx.x].cut;
-        __syncthreads();
-        if (threadIdx.x < A.k_var) {
-            const uint64_t mine = s_cut[threadIdx.x];
-            uint32_t p = 0;
-            for (uint32_t j = 0; j < A.k_var; ++j) {
-                const uint64_t c = s_cut[j];
-                p += (c < mine || (c == mine && j < threadIdx.x)) ? 1u : 0u;
-            }
-            s_pos[threadIdx.x] = p;
-        }
-        __syncthreads();
-        pos = s_pos[k];
-    }
+    const uint32_t pos = A.pos.v[k];
     if (blockIdx.x >= A.n_groups) {
         const uint64_t i = (uint64_t)(blockIdx.x - A.n_groups) * PROP_THREADS + threadIdx.x;
         if (i < A.n_out) A.exp_out_alive[(uint64_t)k * A.n_out + i] = A.out_level[i] > pos ? 1 : 0;
         if (i < A.n_in && A.exp_in_alive) A.exp_in_alive[(uint64_t)k * A.n_in + i] = A.in_level[i] > pos ? 1 : 0;
         return;
     }
-    propagate_group(A.groups[blockIdx.x], A.producers, A.tens,
+    const DevGroup G = A.groups[blockIdx.x];
+    uint32_t* below = A.want_tables ? A.below + k * (A.group_stride + A.n_groups) + G.off + blockIdx.x : nullptr;
+    propagate_group(G, A.producers, A.tens,
                     A.out_alive ? A.out_alive + (uint64_t)k * A.n_out : nullptr,
                     A.out_alive ? nullptr : A.out_level, pos, A.flags,
                     A.group_alive + k * A.group_stride, A.index_map + k * A.group_stride,
                     A.keep + k * A.group_stride, A.new_width + k * A.n_groups + blockIdx.x, wave_cnt,
-                    s_flag_off);
-    // the last block of this variant to get here plans its rebuild
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const uint32_t ticket = __hip_atomic_fetch_add(&A.done[k], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        s_last = ticket + 1u == A.n_groups ? 1u : 0u;
-        if (s_last) A.done[k] = 0;      // for the next launch
-    }
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-    // what the other blocks wrote is read through pointers the compiler knows nothing
-    // about, after the fence
-    const uint32_t* new_width = const_cast<const uint32_t*>(A.new_width);
-    plan_variant<PROP_THREADS>(k, A.tens, A.n_t, A.vecs, A.n_v, A.n_groups, new_width, A.cap_w, A.cap_v,
-                               A.pt, A.pv, A.oup, A.hdr, A.pack, smem, &s_collapse);
+                    s_flag_off, below);
     if (A.want_tables) {
-        const uint32_t n_tab = A.rowtab_prefix[A.n_t] + A.coltab_prefix[A.n_t];
-        for (uint32_t i = threadIdx.x; i < n_tab; i += PROP_THREADS)
-            rect_table_entry(i, k, A.tens, A.groups, A.n_t, A.rowtab_prefix, A.coltab_prefix, A.keep,
-                             A.new_width, A.group_stride, A.n_groups, A.rowtab, A.coltab);
+        // the row tables of the tensors that write this group and the column tables of those
+        // that read it: the survivors below the first filter of every band and below the
+        // first channel of every chunk, which the scan above has just counted
+        __syncthreads();
+        const uint32_t n_row = A.rowtab_prefix[A.n_t], n_col = A.coltab_prefix[A.n_t];
+        for (uint32_t p = G.prod_begin; p < G.prod_end; ++p) {
+            const uint32_t t = A.producers[p];
+            const uint32_t band_rows = A.tens[t].band_rows, out_ch = A.tens[t].out_ch;
+            const uint32_t first = A.rowtab_prefix[t], n_e = A.rowtab_prefix[t + 1] - first;
+            uint32_t* tab = A.rowtab + (uint64_t)k * n_row + first;
+            for (uint32_t j = threadIdx.x; j < n_e; j += PROP_THREADS)
+                tab[j] = below[min(j * band_rows, out_ch)];
+        }
+        for (uint32_t q = A.cons_prefix[blockIdx.x]; q < A.cons_prefix[blockIdx.x + 1]; ++q) {
+            const uint32_t t = A.consumers[q];
+            const uint32_t chunk_ch = A.tens[t].chunk_ch, cin = A.tens[t].cin;
+            const uint32_t first = A.coltab_prefix[t], n_e = A.coltab_prefix[t + 1] - first;
+            uint32_t* tab = A.coltab + (uint64_t)k * n_col + first;
+            for (uint32_t j = threadIdx.x; j < n_e; j += PROP_THREADS)
+                tab[j] = below[min(j * chunk_ch, cin)];
+        }
     }
 }
 
@@ -834,7 +822,7 @@ void launch_compact(shifter_ctx* ctx, const shifter_model* m, const float* d_w, 
 // rebuild plans, tables; with from_levels also the variants' flag bytes, expanded from the
 // level arrays the batched mask pass left) and the gather.
 void launch_plan_and_gather(shifter_ctx* ctx, const shifter_model* m, const PortfolioBuffers& a,
-                            bool from_levels) {
+                            bool from_levels, const MultiPerm& pos) {
     const auto& b = m->b;
     const uint32_t n_t = (uint32_t)m->t.size(), n_v = (uint32_t)m->v.size();
     const uint32_t n_g = (uint32_t)m->g.size();
@@ -846,22 +834,27 @@ void launch_plan_and_gather(shifter_ctx* ctx, const shifter_model* m, const Port
     A.groups = b.groups; A.producers = b.producers; A.tens = b.tens; A.n_t = n_t;
     A.vecs = b.vecs; A.n_v = n_v; A.n_groups = n_g;
     A.out_alive = from_levels ? nullptr : a.d_out_alive;
-    A.out_level = b.levels; A.in_level = b.levels + n_out; A.thr = a.d_thr;
+    A.out_level = b.levels; A.in_level = b.levels + n_out; A.pos = pos;
     A.n_out = n_out; A.n_in = n_in;
     A.exp_out_alive = a.d_out_alive; A.exp_in_alive = a.d_in_alive;
     A.flags = a.flags;
     A.group_alive = a.d_group_alive; A.index_map = a.d_index_map; A.keep = a.d_keep;
     A.new_width = a.d_new_width; A.group_stride = m->info.sum_group_width;
-    A.cap_w = a.cap_w; A.cap_v = a.cap_v;
-    A.pt = b.plan_t; A.pv = b.plan_v; A.oup = b.out_tile_prefix; A.hdr = b.plan_h; A.pack = b.dev_plan;
     A.rowtab_prefix = b.rowtab_prefix; A.coltab_prefix = b.coltab_prefix; A.rowtab = b.rowtab;
     A.coltab = b.coltab; A.want_tables = rect ? 1u : 0u;
-    A.done = b.plan_done; A.k_var = a.k_var;
+    A.below = b.below; A.cons_prefix = b.cons_prefix; A.consumers = b.consumers;
+    A.k_var = a.k_var;
     const uint64_t mx = std::max<uint64_t>(n_out > n_in ? n_out : n_in, 1);
     const uint32_t expand_blocks = from_levels ? (uint32_t)((mx + PROP_THREADS - 1) / PROP_THREADS) : 0u;
     {
-        ProfileScope p(ctx, K_PLAN);
+        ProfileScope p(ctx, K_PROPAGATE);
         plan_all_kernel<<<dim3(n_g + expand_blocks, a.k_var), PROP_THREADS, 0, ctx->stream>>>(A);
+    }
+    {
+        ProfileScope p(ctx, K_PLAN);
+        plan_kernel<<<a.k_var, BLOCK, 0, ctx->stream>>>(b.tens, n_t, b.vecs, n_v, b.groups, n_g, a.d_new_width,
+                                                        a.cap_w, a.cap_v, b.plan_t, b.plan_v,
+                                                        b.out_tile_prefix, b.plan_h, b.dev_plan);
     }
     const bool dense_src = rect || !a.d_w_sparse;
     launch_gather(ctx, m, dense_src ? a.d_w : a.d_w_sparse, dense_src ? 0 : a.w_stride, a.d_vecs, a.d_keep,

@@ -20,10 +20,16 @@ constexpr uint32_t MS_BINS = 16384;      // sample histogram bins
 constexpr uint32_t MS_SHIFT = 17;        // top 14 of the 31 key bits
 constexpr uint32_t TAB_SHIFT = 19;       // the pass's bucket table: 4096 buckets of 2^19 keys
 constexpr uint32_t TAB_SIZE = 1u << (31 - TAB_SHIFT);
-constexpr uint32_t FIN_THREADS = 1024;   // the finish: one block per rank
-constexpr uint32_t FIN_BINS = 4096;      // bins of one refinement level
+// The counters all blocks add to are split CAND_SUB ways by block (one 128-byte line per
+// part), and so is a cluster's candidate region: few enough parts that each averages over
+// hundreds of tiles - filters differ in scale by orders of magnitude, so the candidates of
+// one threshold crowd into few tiles - and enough that the additions of all blocks do not
+// queue on one address.
+constexpr uint32_t CAND_SUB = 32;
+static_assert(CAND_SUB <= SPEC_SUB, "the counters use the first CAND_SUB lines of a row");
+constexpr uint32_t FIN_THREADS = 1024;   // the last step of the finish: one block per rank
+constexpr uint32_t FIN_BINS = 4096;      // bins of one refinement level there
 constexpr uint32_t FIN_LIST = 1024;      // pairs settled by counting
-constexpr uint32_t FIN_DEPTH = 8;        // loads a lane keeps in flight while walking a region
 
 // Split counters, one 128-byte line each: row j (0 <= j <= MAXK) counts the weights with
 // exactly j lower ends at or below their key; row MAXK + 1 + r the candidates appended to
@@ -45,9 +51,8 @@ __device__ __forceinline__ uint32_t count_lower_ends(const uint32_t* s_lo, uint3
     return j + (s_lo[j] <= key ? 1u : 0u);
 }
 
-// One block.  First the set-up of a ranking (the state, the zero-count records, the split
-// counters; the sample histogram is read into registers and cleared for the next call;
-// `zero_ptr` is an optional array the caller wants cleared before the pass), then the
+// One block.  First the set-up of a ranking (the state, the zero-count records; the sample
+// histogram is read into registers and cleared for the next call), then the
 // inclusive prefix of the sample histogram in LDS, for every rank the interval from the
 // sample's order statistics at P/N -/+ margin, monotone ends, clusters, and each cluster's
 // share of the candidate buffer.
@@ -59,7 +64,7 @@ __global__ __launch_bounds__(PREDICT_THREADS) void ms_predict_kernel(
     MultiState* ms, uint32_t* shist, uint32_t* cnt, PruneCounts sorted_p, MultiPerm perm,
     uint32_t k_var, uint32_t m, uint64_t zero_mask, shifter_threshold* thr,
     shifter_threshold* host_rec, uint64_t n_prunable, double margin_sigmas,
-    uint8_t* __restrict__ tab, uint32_t cap_sb_total, uint32_t* zero_ptr, uint32_t zero_n) {
+    uint8_t* __restrict__ tab, uint32_t cap_sb_total) {
     constexpr uint32_t SEG = 256, NSEG = MS_BINS / SEG, WAVES = PREDICT_THREADS / 64;
     static_assert(NSEG == 64, "one segment per lane in the scan of the segment sums");
     __shared__ uint32_t prefix[MS_BINS];          // 64 KB
@@ -77,13 +82,6 @@ __global__ __launch_bounds__(PREDICT_THREADS) void ms_predict_kernel(
 #pragma unroll
     for (uint32_t i = 0; i < PER_WAVE; ++i)
         reinterpret_cast<uint4*>(shist + (wid + i * WAVES) * SEG)[lane] = make_uint4(0, 0, 0, 0);
-    // the split counters this ranking uses: rows 0 .. k_var and MAXK + 1 .. MAXK + k_var
-    for (uint32_t i = threadIdx.x; i < (2u * k_var + 1u) * SPEC_SUB; i += PREDICT_THREADS) {
-        const uint32_t row = i / SPEC_SUB, sb = i % SPEC_SUB;
-        const uint32_t r = row <= k_var ? row : MAXK + 1u + (row - (k_var + 1u));
-        cnt[((size_t)r * SPEC_SUB + sb) * 32u] = 0;
-    }
-    for (uint32_t i = threadIdx.x; i < zero_n; i += PREDICT_THREADS) zero_ptr[i] = 0;
     if (threadIdx.x < MAXK) {
         const uint32_t t = threadIdx.x;
         ms->p[t] = t < k_var ? sorted_p.p[t] : 0;
@@ -92,7 +90,6 @@ __global__ __launch_bounds__(PREDICT_THREADS) void ms_predict_kernel(
             ms->lo[t] = 0xffffffffu;
             ms->hi[t] = 0xffffffffu;
             ms->mid[t] = 0xffffffffu;
-            ms->sh[t] = 0;
             ms->clast[t] = t;
             ms->cand_off[t] = 0;
             ms->cand_cap[t] = 0;
@@ -211,24 +208,36 @@ __global__ __launch_bounds__(PREDICT_THREADS) void ms_predict_kernel(
         uint64_t wsum = wt;
         for (uint32_t d = 32; d > 0; d >>= 1) wsum += __shfl_down(wsum, d, 64);
         wsum = __shfl(wsum, 0, 64);
-        const uint32_t cap = wt ? (uint32_t)((uint64_t)cap_sb_total * wt / wsum) : 0u;
+        // cap_sb_total pairs per 1/SPEC_SUB of the buffer; a part of a region is 1/CAND_SUB of it
+        const uint32_t cap = wt ? (uint32_t)((uint64_t)cap_sb_total * (SPEC_SUB / CAND_SUB) * wt / wsum) : 0u;
         uint32_t cinc = cap;
         for (uint32_t d = 1; d < 64; d <<= 1) {
             const uint32_t y = __shfl_up(cinc, d, 64);
             if (lane >= d) cinc += y;
         }
         if (lane < k_var) {
-            const uint32_t span = hi - lo;   // smallest sh with (span >> sh) < FIN_BINS
-            const uint32_t sh = span < FIN_BINS ? 0u : (32u - (uint32_t)__clz(span)) - 12u;
-            static_assert(FIN_BINS == 4096, "sh from the bit length of the span");
             ms->lo[lane] = lo;
             ms->hi[lane] = hi;
-            ms->sh[lane] = sh;
             ms->mid[lane] = pm;
             ms->clast[lane] = last;
             ms->cand_cap[lane] = cap;
-            ms->cand_off[lane] = (cinc - cap) * SPEC_SUB;     // at most cap_sb_total * SPEC_SUB pairs
+            ms->cand_off[lane] = (cinc - cap) * CAND_SUB;     // at most cap_sb_total * SPEC_SUB pairs
             s_lo[lane] = lo;
+        }
+        // the finish's view of a rank: its cluster's region and first histogram
+        const uint32_t cap_cl = __shfl(cap, min(last, 63u), 64);
+        const uint32_t off_cl = __shfl((cinc - cap) * CAND_SUB, min(last, 63u), 64);
+        if (lane < k_var) {
+            const uint32_t span = hi - lo;
+            RankIn in;
+            in.p = p;
+            in.lo = lo;
+            in.sh = span < 256u ? 0u : (32u - (uint32_t)__clz(span)) - 8u;
+            in.clast = last;
+            in.cand_off = off_cl;
+            in.cand_cap = cap_cl;
+            in.perm = perm.v[lane];
+            ms->rin[lane] = in;
         }
     }
     // The pass's bucket table.  Entry b covers the keys [b << TAB_SHIFT, (b + 1) << TAB_SHIFT):
@@ -257,30 +266,27 @@ __global__ __launch_bounds__(PREDICT_THREADS) void ms_predict_kernel(
 
 // Appends the candidates a block found to the regions of their clusters: count per cluster
 // in LDS, one global reservation per cluster the block met, then the writes.  `for_each`
-// calls its argument once per candidate of the calling thread with (bits, global index).
-// All threads of the block call this; it contains barriers.
+// calls its argument once per candidate of the calling thread with (bits, global index,
+// cluster = last rank whose lower end lies at or below the key).  All threads of the block
+// call this; it contains barriers.
 template <typename ForEach>
 __device__ __forceinline__ void ms_append_candidates(
-    bool have, const uint32_t* s_lo, const uint32_t* s_coff, const uint32_t* s_ccap,
-    uint32_t* s_rc, uint32_t* s_rc2, uint32_t* s_rbase, uint32_t k_var, uint32_t* cnt, uint32_t sb,
-    uint2* __restrict__ cand, ForEach&& for_each) {
+    bool have, const uint32_t* s_coff, const uint32_t* s_ccap, uint32_t* s_rc, uint32_t* s_rc2,
+    uint32_t* s_rbase, uint32_t k_var, uint32_t* cnt, uint32_t csb, uint2* __restrict__ cand,
+    ForEach&& for_each) {
     if (!__syncthreads_or(have ? 1 : 0)) return;      // uniform: no candidate in this block
-    if (have)
-        for_each([&](uint32_t bits, uint32_t) {
-            atomicAdd(&s_rc[count_lower_ends(s_lo, bits & 0x7fffffffu) - 1u], 1u);
-        });
+    if (have) for_each([&](uint32_t, uint32_t, uint32_t cl) { atomicAdd(&s_rc[cl], 1u); });
     __syncthreads();
     if (threadIdx.x < k_var) {
         const uint32_t c = s_rc[threadIdx.x];
-        if (c) s_rbase[threadIdx.x] = atomicAdd(mcnt_cand(cnt, threadIdx.x, sb), c);
+        if (c) s_rbase[threadIdx.x] = atomicAdd(mcnt_cand(cnt, threadIdx.x, csb), c);
     }
     __syncthreads();
     if (have)
-        for_each([&](uint32_t bits, uint32_t g) {
-            const uint32_t cl = count_lower_ends(s_lo, bits & 0x7fffffffu) - 1u;
+        for_each([&](uint32_t bits, uint32_t g, uint32_t cl) {
             const uint32_t pos = s_rbase[cl] + atomicAdd(&s_rc2[cl], 1u);
             const uint32_t cap = s_ccap[cl];
-            if (pos < cap) cand[(size_t)s_coff[cl] + (size_t)sb * cap + pos] = make_uint2(bits, g);
+            if (pos < cap) cand[(size_t)s_coff[cl] + (size_t)csb * cap + pos] = make_uint2(bits, g);
         });
 }
 
@@ -289,7 +295,9 @@ template <bool NT>
 __global__ __launch_bounds__(BLOCK) void ms_pass_kernel(
     const DevTensor* __restrict__ tens, const uint32_t* __restrict__ tile_prefix, uint32_t n_t,
     const float* __restrict__ w, MultiState* ms, uint32_t* cnt, uint2* __restrict__ cand,
-    const uint8_t* __restrict__ tab) {
+    const uint8_t* __restrict__ tab, uint32_t* zero_ptr, uint32_t zero_n) {
+    // an array the step behind this pass wants cleared (or nullptr)
+    for (uint32_t i = blockIdx.x * BLOCK + threadIdx.x; i < zero_n; i += gridDim.x * BLOCK) zero_ptr[i] = 0;
     // s_hi1[j] = hi_(j-1) + 1, s_hi1[0] = 0: a weight with j lower ends at or below it is a
     // candidate (of the cluster ending at rank j - 1) iff key < s_hi1[j]
     __shared__ uint32_t s_lo[MAXK + 1], s_hi1[MAXK + 1];
@@ -341,7 +349,7 @@ __global__ __launch_bounds__(BLOCK) void ms_pass_kernel(
     // classify one weight; returns whether it is a candidate; adds it to the count of
     // j = #{k : lo_k <= key}: the bucket table's entry, plus a compare or two in the few
     // buckets that hold a rank's lower end (the binary search where three or more meet)
-    auto one = [&](uint32_t bits) -> bool {
+    auto one = [&](uint32_t bits, uint32_t& j_out) -> bool {
         const uint32_t key = bits & 0x7fffffffu;
         key_max = max(key_max, key);
         const uint32_t e = s_tab[key >> TAB_SHIFT];
@@ -357,17 +365,21 @@ __global__ __launch_bounds__(BLOCK) void ms_pass_kernel(
             }
         }
         my_col[j * BLOCK] += 1;                 // private byte, at most 16
+        j_out = j;
         return key < s_hi1[j];                  // j <= k_var <= SPEC_MULTI_MAXK
     };
 
     if (whole) {
-        uint32_t cmask = 0;
+        uint32_t cmask = 0, jj[U];
 #pragma unroll
         for (uint32_t u = 0; u < U; ++u) {
-            cmask |= ((one(v[u].x) ? 1u : 0u) | (one(v[u].y) ? 2u : 0u) | (one(v[u].z) ? 4u : 0u) |
-                      (one(v[u].w) ? 8u : 0u)) << (4 * u);
+            uint32_t j_0, j_1, j_2, j_3;
+            cmask |= ((one(v[u].x, j_0) ? 1u : 0u) | (one(v[u].y, j_1) ? 2u : 0u) |
+                      (one(v[u].z, j_2) ? 4u : 0u) | (one(v[u].w, j_3) ? 8u : 0u)) << (4 * u);
+            jj[u] = j_0 | (j_1 << 8) | (j_2 << 16) | (j_3 << 24);
         }
-        ms_append_candidates(cmask != 0, s_lo, s_coff, s_ccap, s_rc, s_rc2, s_rbase, k_var, cnt, sb, cand,
+        ms_append_candidates(cmask != 0, s_coff, s_ccap, s_rc, s_rc2, s_rbase, k_var, cnt,
+                             blockIdx.x & (CAND_SUB - 1), cand,
                              [&](auto&& f) {
 #pragma unroll
                                  for (uint32_t u = 0; u < U; ++u) {
@@ -375,7 +387,8 @@ __global__ __launch_bounds__(BLOCK) void ms_pass_kernel(
                                      const uint32_t vv[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
 #pragma unroll
                                      for (uint32_t q = 0; q < 4; ++q)
-                                         if (cmask & (1u << (4 * u + q))) f(vv[q], g0 + j + q);
+                                         if (cmask & (1u << (4 * u + q)))
+                                             f(vv[q], g0 + j + q, ((jj[u] >> (8 * q)) & 0xffu) - 1u);
                                  }
                              });
     } else {
@@ -384,11 +397,13 @@ __global__ __launch_bounds__(BLOCK) void ms_pass_kernel(
             const uint32_t j = j0 + threadIdx.x;
             if (j < n) {
                 const uint32_t bits = __float_as_uint(src[j]);
-                if (one(bits)) {
-                    const uint32_t cl = count_lower_ends(s_lo, bits & 0x7fffffffu) - 1u;
-                    const uint32_t pos = atomicAdd(mcnt_cand(cnt, cl, sb), 1u);
+                uint32_t jw;
+                if (one(bits, jw)) {
+                    const uint32_t cl = jw - 1u;
+                    const uint32_t csb = blockIdx.x & (CAND_SUB - 1);
+                    const uint32_t pos = atomicAdd(mcnt_cand(cnt, cl, csb), 1u);
                     const uint32_t cap = s_ccap[cl];
-                    if (pos < cap) cand[(size_t)s_coff[cl] + (size_t)sb * cap + pos] = make_uint2(bits, g0 + j);
+                    if (pos < cap) cand[(size_t)s_coff[cl] + (size_t)csb * cap + pos] = make_uint2(bits, g0 + j);
                 }
             }
         }
@@ -412,85 +427,193 @@ __global__ __launch_bounds__(BLOCK) void ms_pass_kernel(
     if (threadIdx.x == 0 && s_nan) atomicOr(&ms->status, 2u);
 }
 
-// Calls f(pair) for every pair of cluster `cl`'s region: a wavefront takes the region's
-// sub-buffers in turn and keeps FIN_DEPTH loads per lane in flight (one block per rank has
-// to pull about a megabyte through one CU; the loads' latency is what it waits for).
+// The finish, three launches over the candidates.
+//   hist    grid (part, rank): a 256-bin histogram of (key - lo) >> sh over one part of a
+//           cluster's region, added to the cluster's histogram in global memory;
+//   filter  grid (part, rank): every block first locates its rank - totals of the split
+//           counters, the check that makes the result exact (below < P <= below + candidates
+//           of the cluster), the bin holding the P-th pair - and then moves its part's pairs
+//           of that bin to the rank's list (one reservation per block);
+//   rank    one block per rank: refines the list with 4096-bin histograms until a bin holds
+//           at most FIN_LIST pairs, ranks those exactly by counting and writes the record,
+//           to d_thr and to its mirror in pinned host memory, with the rank's status word
+//           (bit 0: could not decide; bit 1: NaN; bit 2: a buffer was full or too many
+//           weights share the threshold's key - wider intervals would not help).
+constexpr uint32_t MF_THREADS = 1024, MF_DEPTH = 8;
+constexpr uint32_t MF_BINS1 = 256;
+constexpr uint32_t MF_STAGE = 2048;      // pairs of the selected bin one filter block may hold
+
+// f(pair) for the n pairs at src, MF_DEPTH loads per thread in flight.
 template <typename F>
-__device__ __forceinline__ void ms_walk_region(const uint2* __restrict__ region, uint32_t cap,
-                                               const uint32_t* s_n, F&& f) {
-    const uint32_t lane = threadIdx.x & 63u, wid = threadIdx.x >> 6;
-    for (uint32_t sb = wid; sb < SPEC_SUB; sb += FIN_THREADS / 64) {
-        const uint32_t n = s_n[sb];
-        const uint2* src = region + (size_t)sb * cap;
-        for (uint32_t i0 = 0; i0 < n; i0 += 64u * FIN_DEPTH) {
-            uint2 c[FIN_DEPTH];
+__device__ __forceinline__ void ms_walk(const uint2* __restrict__ src, uint32_t n, F&& f) {
+    for (uint32_t i0 = 0; i0 < n; i0 += MF_THREADS * MF_DEPTH) {
+        uint2 c[MF_DEPTH];
 #pragma unroll
-            for (uint32_t u = 0; u < FIN_DEPTH; ++u) {
-                const uint32_t i = i0 + u * 64u + lane;
-                c[u] = i < n ? src[i] : make_uint2(0xffffffffu, 0xffffffffu);
-            }
-#pragma unroll
-            for (uint32_t u = 0; u < FIN_DEPTH; ++u)
-                if (i0 + u * 64u + lane < n) f(c[u]);
+        for (uint32_t u = 0; u < MF_DEPTH; ++u) {
+            const uint32_t i = i0 + u * MF_THREADS + threadIdx.x;
+            c[u] = i < n ? src[i] : make_uint2(0xffffffffu, 0xffffffffu);
         }
+#pragma unroll
+        for (uint32_t u = 0; u < MF_DEPTH; ++u)
+            if (i0 + u * MF_THREADS + threadIdx.x < n) f(c[u]);
     }
 }
 
-// The finish, one block per rank: totals of the split counters, the check that makes the
-// result exact (below < P <= below + candidates of the rank's cluster), then the P-th pair
-// among the candidates by histogram refinement - 4096 bins over the interval, again over
-// the selected bin while it holds more than FIN_LIST pairs - and an exact rank by counting
-// inside the last bin.  The record goes to d_thr and to its mirror in pinned host memory;
-// every block leaves its status word there as well (bit 0: could not decide, bit 1: NaN).
-__global__ __launch_bounds__(FIN_THREADS) void ms_finish_kernel(
+__global__ __launch_bounds__(MF_THREADS) void ms_hist_kernel(
+    const MultiState* __restrict__ ms, const uint32_t* __restrict__ cnt,
+    const uint2* __restrict__ cand, uint32_t* ghist, uint64_t* rowsum, uint32_t k_var) {
+    __shared__ uint32_t h[MF_BINS1];
+    if (blockIdx.y == k_var) {
+        // the layer of blocks past the ranks adds up the rows of split counters (row j:
+        // weights with exactly j lower ends at or below their key), one row per wavefront
+        static_assert(SPEC_SUB == 256, "four counters per lane");
+        const uint32_t lane = threadIdx.x & 63u;
+        const uint32_t j = blockIdx.x * (MF_THREADS / 64) + (threadIdx.x >> 6);
+        if (j <= k_var) {
+            uint64_t v = 0;
+#pragma unroll
+            for (uint32_t q = 0; q < SPEC_SUB / 64; ++q) v += cnt[((size_t)j * SPEC_SUB + q * 64u + lane) * 32u];
+            for (uint32_t d = 32; d > 0; d >>= 1) v += __shfl_down(v, d, 64);
+            if (lane == 0) rowsum[j] = v;
+        }
+        return;
+    }
+    const uint32_t part = blockIdx.x, cl = blockIdx.y;
+    const RankIn R = ms->rin[cl];
+    if (R.clast != cl) return;                       // only a cluster's last rank owns a region
+    const uint32_t cap = R.cand_cap;
+    const uint32_t n = min(cnt[((size_t)(MAXK + 1u + cl) * SPEC_SUB + part) * 32u], cap);
+    if (n == 0) return;
+    if (threadIdx.x < MF_BINS1) h[threadIdx.x] = 0;
+    __syncthreads();
+    const uint32_t lo = R.lo, sh = R.sh;
+    ms_walk(cand + (size_t)R.cand_off + (size_t)part * cap, n,
+            [&](uint2 c) { atomicAdd(&h[((c.x & 0x7fffffffu) - lo) >> sh], 1u); });
+    __syncthreads();
+    if (threadIdx.x < MF_BINS1) {
+        const uint32_t c = h[threadIdx.x];
+        if (c) atomicAdd(&ghist[cl * MF_BINS1 + threadIdx.x], c);
+    }
+}
+
+__global__ __launch_bounds__(MF_THREADS) void ms_filter_kernel(
     MultiState* ms, const uint32_t* __restrict__ cnt, const uint2* __restrict__ cand,
+    const uint32_t* __restrict__ ghist, const uint64_t* __restrict__ rowsum, uint2* __restrict__ list,
+    uint32_t* list_cnt) {
+    __shared__ uint64_t smem[MF_THREADS / 64 + 1];
+    __shared__ uint2 stage[MF_STAGE];
+    __shared__ uint32_t s_over, s_bin, s_found, s_n, s_base;
+    const uint32_t part = blockIdx.x, k = blockIdx.y;
+    const RankIn R = ms->rin[k];
+    const uint32_t cl = R.clast;
+    const uint64_t p = R.p;
+    const uint32_t cap = R.cand_cap;
+    const bool publish = part == 0;
+    if (threadIdx.x == 0) { s_over = 0; s_found = 0; s_n = 0; s_bin = 0; }
+    __syncthreads();
+    // weights below the cluster's interval: rows 0 .. k of the split counters
+    uint64_t below, inside;
+    {
+        const uint64_t b = threadIdx.x <= k ? rowsum[threadIdx.x] : 0;     // k < MAXK <= MF_THREADS
+        uint32_t c = 0;
+        if (threadIdx.x < CAND_SUB) {
+            c = cnt[((size_t)(MAXK + 1u + cl) * SPEC_SUB + threadIdx.x) * 32u];
+            if (c > cap) s_over = 1;
+        }
+        block_excl_scan_u64<MF_THREADS>(b, smem, &below);
+        block_excl_scan_u64<MF_THREADS>(c, smem, &inside);
+    }
+    __syncthreads();
+    uint32_t why = 0;
+    if (s_over) why = 5u;
+    else if (!(below < p && p <= below + inside)) why = 1u;
+    uint64_t r = 0, base = 0;
+    uint32_t c = 0;
+    if (!why) {
+        r = p - below;
+        c = threadIdx.x < MF_BINS1 ? ghist[cl * MF_BINS1 + threadIdx.x] : 0u;
+        uint64_t tot;
+        base = block_excl_scan_u64<MF_THREADS>(c, smem, &tot);
+        if (threadIdx.x < MF_BINS1 && base < r && r <= base + c) {
+            s_bin = threadIdx.x;
+            s_found = 1;
+            if (publish) {
+                RankOut* o = &ms->rout[k];
+                o->bin = threadIdx.x;
+                o->bin_cnt = c;
+                o->r2 = r - base;
+                o->less = below + base;
+                if (c > SPEC_LIST_CAP) atomicOr(&o->fail, 5u);
+            }
+        }
+        __syncthreads();
+        if (!s_found) why = 1u;       // cannot happen unless the buffers were disturbed
+    }
+    if (why) {
+        if (publish && threadIdx.x == 0) atomicOr(&ms->rout[k].fail, why);
+        return;
+    }
+    // this part's pairs of the selected bin -> the rank's list
+    const uint32_t n = min(cnt[((size_t)(MAXK + 1u + cl) * SPEC_SUB + part) * 32u], cap);
+    const uint32_t lo = R.lo, sh = R.sh, bin = s_bin;
+    ms_walk(cand + (size_t)R.cand_off + (size_t)part * cap, n, [&](uint2 x) {
+        if ((((x.x & 0x7fffffffu) - lo) >> sh) == bin) {
+            const uint32_t pos = atomicAdd(&s_n, 1u);
+            if (pos < MF_STAGE) stage[pos] = x;
+        }
+    });
+    __syncthreads();
+    const uint32_t m = s_n;
+    if (m > MF_STAGE) {
+        if (threadIdx.x == 0) atomicOr(&ms->rout[k].fail, 5u);
+        return;
+    }
+    if (m == 0) return;
+    if (threadIdx.x == 0) s_base = atomicAdd(&list_cnt[k], m);
+    __syncthreads();
+    uint2* dst = list + (size_t)k * SPEC_LIST_CAP;
+    for (uint32_t i = threadIdx.x; i < m; i += MF_THREADS)
+        if (s_base + i < SPEC_LIST_CAP) dst[s_base + i] = stage[i];
+}
+
+__global__ __launch_bounds__(FIN_THREADS) void ms_rank_kernel(
+    MultiState* ms, const uint2* __restrict__ list, const uint32_t* __restrict__ list_cnt,
     shifter_threshold* thr, shifter_threshold* host_rec, uint32_t* host_status) {
     __shared__ uint32_t h[FIN_BINS];
     __shared__ uint64_t comp[FIN_LIST];
     __shared__ uint64_t smem[FIN_THREADS / 64 + 1];
-    __shared__ uint32_t s_n[SPEC_SUB];
     __shared__ uint64_t s_sel, s_base;
-    __shared__ uint32_t s_over, s_bin, s_cnt, s_lt, s_eq, s_nb;
+    __shared__ uint32_t s_bin, s_cnt, s_lt, s_eq, s_nb;
     const uint32_t k = blockIdx.x;
-    const uint32_t cl = ms->clast[k];
-    const uint64_t p = ms->p[k];
-    const uint32_t cap = ms->cand_cap[cl];
-    const uint2* region = cand + ms->cand_off[cl];
+    // everything this block needs from the state, fetched side by side
+    const RankIn R = ms->rin[k];
+    const RankOut O = ms->rout[k];
+    const uint32_t n = list_cnt[k];
     const uint32_t nan_bit = ms->status & 2u;      // the pass has ended
-    auto give_up = [&]() {
+    const uint64_t p = R.p;
+    auto give_up = [&](uint32_t why) {
         if (threadIdx.x == 0) {
             atomicOr(&ms->status, 1u);
-            host_status[k] = 1u | nan_bit;
+            host_status[k] = why | 1u | nan_bit;
         }
     };
-    if (threadIdx.x == 0) { s_over = 0; s_sel = 0; s_nb = 0; s_lt = 0; s_eq = 0; }
-    __syncthreads();
-    uint64_t below, inside;
-    {
-        static_assert(SPEC_SUB <= FIN_THREADS, "one split counter column per thread");
-        uint32_t b = 0, c = 0;
-        if (threadIdx.x < SPEC_SUB) {
-            for (uint32_t j = 0; j <= k; ++j) b += cnt[((size_t)j * SPEC_SUB + threadIdx.x) * 32u];
-            c = cnt[((size_t)(MAXK + 1u + cl) * SPEC_SUB + threadIdx.x) * 32u];
-            if (c > cap) s_over = 1;
-            s_n[threadIdx.x] = min(c, cap);
-        }
-        block_excl_scan_u64<FIN_THREADS>(b, smem, &below);
-        block_excl_scan_u64<FIN_THREADS>(c, smem, &inside);
-    }
-    __syncthreads();
-    if (s_over || !(below < p && p <= below + inside)) { give_up(); return; }
-    uint64_t r = p - below;          // 1-based rank among the pairs still in play
-    uint64_t less = below;           // weights below them
-    uint32_t lo_cur = ms->lo[k], sh = ms->sh[k];
-    uint32_t width_sh = 32;          // the pairs in play have (key - lo_cur) >> width_sh == 0
-    uint32_t cnt_sel;
-    for (;;) {
+    if (O.fail) { give_up(O.fail); return; }
+    if (n != O.bin_cnt || n > SPEC_LIST_CAP) { give_up(5u); return; }
+    const uint2* src = list + (size_t)k * SPEC_LIST_CAP;
+    if (threadIdx.x == 0) { s_sel = 0; s_nb = 0; s_lt = 0; s_eq = 0; }
+    uint64_t r = O.r2;               // 1-based rank among the pairs still in play
+    uint64_t less = O.less;          // weights below them
+    uint32_t width_sh = R.sh;        // the pairs in play have (key - lo_cur) >> width_sh == 0
+    uint32_t lo_cur = R.lo + (O.bin << width_sh);
+    uint32_t cnt_sel = n;
+    while (cnt_sel > FIN_LIST) {
+        if (width_sh == 0) { give_up(5u); return; }   // more equal keys than the list holds: the multi-pass select ranks ties
+        const uint32_t sh = width_sh > 12u ? width_sh - 12u : 0u;
         for (uint32_t i = threadIdx.x; i < FIN_BINS; i += FIN_THREADS) h[i] = 0;
         __syncthreads();
-        ms_walk_region(region, cap, s_n, [&](uint2 c) {
+        ms_walk(src, n, [&](uint2 c) {
             const uint32_t d = (c.x & 0x7fffffffu) - lo_cur;      // wraps for keys below lo_cur
-            if (width_sh >= 32 || (d >> width_sh) == 0) atomicAdd(&h[d >> sh], 1u);
+            if ((d >> width_sh) == 0) atomicAdd(&h[d >> sh], 1u);
         });
         __syncthreads();
         constexpr uint32_t PER = FIN_BINS / FIN_THREADS;
@@ -508,19 +631,17 @@ __global__ __launch_bounds__(FIN_THREADS) void ms_finish_kernel(
             }
         }
         __syncthreads();
-        if (tot < r) { give_up(); return; }     // cannot happen unless the buffers were disturbed
+        if (tot < r) { give_up(1u); return; }    // cannot happen unless the buffers were disturbed
         less += s_base;
         r -= s_base;
         lo_cur += s_bin << sh;
         width_sh = sh;
         cnt_sel = s_cnt;
         __syncthreads();
-        if (cnt_sel <= FIN_LIST) break;
-        if (sh == 0) { give_up(); return; }     // more equal keys than the list holds: the multi-pass select ranks ties
-        sh = sh > 12u ? sh - 12u : 0u;
     }
+    __syncthreads();
     // the pairs of the last bin, then the r-th of them by counting
-    ms_walk_region(region, cap, s_n, [&](uint2 c) {
+    ms_walk(src, n, [&](uint2 c) {
         const uint32_t key = c.x & 0x7fffffffu, d = key - lo_cur;
         if ((d >> width_sh) == 0) {
             const uint32_t pos = atomicAdd(&s_nb, 1u);
@@ -528,7 +649,7 @@ __global__ __launch_bounds__(FIN_THREADS) void ms_finish_kernel(
         }
     });
     __syncthreads();
-    if (s_nb != cnt_sel) { give_up(); return; }
+    if (s_nb != cnt_sel || r == 0 || r > cnt_sel) { give_up(1u); return; }
     const uint64_t want = r - 1;
     for (uint32_t i = threadIdx.x; i < cnt_sel; i += FIN_THREADS) {
         const uint64_t c = comp[i];
@@ -557,9 +678,8 @@ __global__ __launch_bounds__(FIN_THREADS) void ms_finish_kernel(
         out.cut = sel + 1;
         out.n_less = less + s_lt;
         out.n_equal = s_eq;
-        const uint32_t dst = ms->perm[k];
-        thr[dst] = out;
-        host_rec[dst] = out;
+        thr[R.perm] = out;
+        host_rec[R.perm] = out;
         host_status[k] = nan_bit;
     }
 }
@@ -631,18 +751,20 @@ __global__ __launch_bounds__(BLOCK) void ms_fused_kernel(
     // number of ranks that keep one weight in what the pass writes (127 in tensors that are
     // not ranked: no rank removes it) and whether it is a candidate; counts it under
     // j = #{r : lo_r <= key}.  Ranks below j keep a weight that is no candidate.
-    auto classify = [&](uint32_t bits, bool& is_cand) -> uint32_t {
+    auto classify = [&](uint32_t bits, bool& is_cand, bool& below_mid) -> uint32_t {
         is_cand = false;
+        below_mid = false;
         if (!ranked) return 127u;
         const uint32_t key = bits & 0x7fffffffu;
         nan |= key > 0x7f800000u ? 1u : 0u;
         uint32_t j = count_lower_ends(s_lo, key);
         is_cand = j >= 1 && key <= s_hi[j - 1];
         s_col[j * BLOCK + threadIdx.x] += 1;
-        // a candidate is written as kept by the ranks below j - 1 and, by rank j - 1 (with
-        // intervals that do not overlap, the only rank it is a candidate of), iff it does
-        // not lie below that rank's predicted threshold
-        if (is_cand && key < s_mid[j - 1]) j -= 1;
+        // a candidate is written as kept by the ranks below j - 1 and by rank j - 1 iff it
+        // does not lie below that rank's predicted threshold (the fix-up settles it, in every
+        // rank of its cluster)
+        below_mid = is_cand && key < s_mid[j - 1];
+        if (below_mid) j -= 1;
         return j;
     };
     auto mark = [&](uint32_t j, uint32_t bits, uint32_t level) {
@@ -663,14 +785,15 @@ __global__ __launch_bounds__(BLOCK) void ms_fused_kernel(
         uint4 v[U];
 #pragma unroll
         for (uint32_t u = 0; u < U; ++u) v[u] = load_u4<NT>(s4 + q0 + 64u * u);
-        uint32_t jj[U], cmask = 0, lvl[U][4];
+        uint32_t jj[U], cmask = 0, bmask = 0, lvl[U][4];
 #pragma unroll
         for (uint32_t u = 0; u < U; ++u) {
-            bool c_0, c_1, c_2, c_3;
-            const uint32_t j_0 = classify(v[u].x, c_0), j_1 = classify(v[u].y, c_1);
-            const uint32_t j_2 = classify(v[u].z, c_2), j_3 = classify(v[u].w, c_3);
+            bool c_0, c_1, c_2, c_3, b_0, b_1, b_2, b_3;
+            const uint32_t j_0 = classify(v[u].x, c_0, b_0), j_1 = classify(v[u].y, c_1, b_1);
+            const uint32_t j_2 = classify(v[u].z, c_2, b_2), j_3 = classify(v[u].w, c_3, b_3);
             jj[u] = j_0 | (j_1 << 8) | (j_2 << 16) | (j_3 << 24);
             cmask |= ((c_0 ? 1u : 0u) | (c_1 ? 2u : 0u) | (c_2 ? 4u : 0u) | (c_3 ? 8u : 0u)) << (4 * u);
+            bmask |= ((b_0 ? 1u : 0u) | (b_1 ? 2u : 0u) | (b_2 ? 4u : 0u) | (b_3 ? 8u : 0u)) << (4 * u);
             lvl[u][0] = lvl[u][1] = lvl[u][2] = lvl[u][3] = 0;
         }
         uint32_t* xm = s_xm + wid * (64u * U);
@@ -715,7 +838,8 @@ __global__ __launch_bounds__(BLOCK) void ms_fused_kernel(
                 if (!(cmask & (1u << (4 * u + q)))) mark(j + q, b[q], lvl[u][q]);
         }
         // candidate pairs: to the regions of their clusters
-        ms_append_candidates(cmask != 0, s_lo, s_coff, s_ccap, s_rc, s_rc2, s_rbase, k_var, cnt, sb, cand,
+        ms_append_candidates(cmask != 0, s_coff, s_ccap, s_rc, s_rc2, s_rbase, k_var, cnt,
+                             blockIdx.x & (CAND_SUB - 1), cand,
                              [&](auto&& f) {
 #pragma unroll
                                  for (uint32_t u = 0; u < U; ++u) {
@@ -723,7 +847,9 @@ __global__ __launch_bounds__(BLOCK) void ms_fused_kernel(
                                      const uint32_t vv[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
 #pragma unroll
                                      for (uint32_t q = 0; q < 4; ++q)
-                                         if (cmask & (1u << (4 * u + q))) f(vv[q], g0 + j + q);
+                                         if (cmask & (1u << (4 * u + q)))
+                                             f(vv[q], g0 + j + q,
+                                               ((jj[u] >> (8 * q)) & 0xffu) - 1u + ((bmask >> (4 * u + q)) & 1u));
                                  }
                              });
     } else {
@@ -731,8 +857,8 @@ __global__ __launch_bounds__(BLOCK) void ms_fused_kernel(
             const uint32_t j = j0 + threadIdx.x;
             if (j < n) {
                 const uint32_t bits = __float_as_uint(src[j]);
-                bool is_cand;
-                const uint32_t jr = classify(bits, is_cand);
+                bool is_cand, below_mid;
+                const uint32_t jr = classify(bits, is_cand, below_mid);
                 uint32_t level = 0;
                 for (uint32_t k = 0; k < k_all; ++k) {
                     const bool keep = s_rv[k] < (int32_t)jr;
@@ -742,10 +868,11 @@ __global__ __launch_bounds__(BLOCK) void ms_fused_kernel(
                     if (want_mask) mask[(uint64_t)k * mask_stride + T.gbase + e0 + j] = keep ? 1 : 0;
                 }
                 if (is_cand) {
-                    const uint32_t cl = count_lower_ends(s_lo, bits & 0x7fffffffu) - 1u;
-                    const uint32_t pos = atomicAdd(mcnt_cand(cnt, cl, sb), 1u);
+                    const uint32_t cl = jr - 1u + (below_mid ? 1u : 0u);
+                    const uint32_t csb = blockIdx.x & (CAND_SUB - 1);
+                    const uint32_t pos = atomicAdd(mcnt_cand(cnt, cl, csb), 1u);
                     const uint32_t cap = s_ccap[cl];
-                    if (pos < cap) cand[(size_t)s_coff[cl] + (size_t)sb * cap + pos] = make_uint2(bits, g0 + j);
+                    if (pos < cap) cand[(size_t)s_coff[cl] + (size_t)csb * cap + pos] = make_uint2(bits, g0 + j);
                 } else {
                     mark(j, bits, level);
                 }
@@ -802,7 +929,8 @@ __device__ __forceinline__ void rank_range(const uint32_t* s_lo, const uint32_t*
 // key >= mid_{j-1}; here it is rewritten in every rank where that was the wrong side of
 // the exact cut, and its level (variants that keep it: those that remove nothing, the
 // ranks below a, and the ranks of [a, j) that keep it) goes into the level arrays.
-// blockIdx.x: sub-buffer, blockIdx.y: rank (only a cluster's last rank owns a region).
+// blockIdx.x: part of the region, blockIdx.y: rank (only a cluster's last rank owns a
+// region), blockIdx.z: which of gridDim.z interleaved slices of the part.
 __global__ __launch_bounds__(BLOCK) void ms_fixup_kernel(
     const DevTensor* __restrict__ tens, const uint32_t* __restrict__ ranked_ids, uint32_t n_ranked,
     const MultiState* __restrict__ ms, const uint32_t* __restrict__ cnt,
@@ -869,7 +997,7 @@ __global__ __launch_bounds__(BLOCK) void ms_fixup_kernel(
     };
     // four pairs per thread and step, their loads in flight together
     constexpr uint32_t U = 4;
-    for (uint32_t i0 = 0; i0 < n; i0 += U * BLOCK) {
+    for (uint32_t i0 = blockIdx.z * U * BLOCK; i0 < n; i0 += gridDim.z * U * BLOCK) {
         uint2 c[U];
 #pragma unroll
         for (uint32_t u = 0; u < U; ++u) {
@@ -891,21 +1019,29 @@ void launch_spec_multi(shifter_ctx* ctx, const shifter_model* m, const float* d_
     hipStream_t s = ctx->stream;
     if (k != 0) {
         ProfileScope ps(ctx, K_SPEC_SAMPLE);
-        launch_spec_sample(ctx, m, d_w);     // adds to the sample histogram, which every ranking leaves cleared
+        // adds to the sample histogram, which every ranking leaves cleared; clears this
+        // ranking's counters on the way
+        SampleZero z;
+        z.cnt = b.multi_cnt; z.k = k; z.ghist = b.multi_hist; z.list_cnt = b.multi_list_cnt;
+        z.rout = b.multi->rout;
+        if (fb) {       // the fused pass adds to the level arrays
+            z.extra = b.levels;
+            z.extra_n = (uint32_t)(m->info.sum_out_ch + m->info.sum_in_ch);
+        }
+        launch_spec_sample(ctx, m, d_w, z);
+    } else if (fb) {
+        launch_zero_levels(ctx, m);
     }
     {
-        // with the fused pass the level arrays are cleared here, ahead of it
-        if (fb && !zero_ptr) {
-            zero_ptr = b.levels;
-            zero_n = (uint32_t)(m->info.sum_out_ch + m->info.sum_in_ch);
-        }
         ProfileScope ps(ctx, K_SPEC_PREDICT);
         ms_predict_kernel<<<1, PREDICT_THREADS, 0, s>>>(
             b.multi, b.shist, b.multi_cnt, sorted_p, perm, k, m->sample_size, zero_mask, d_thr,
-            b.dev_multi_rec, m->info.n_prunable, ctx->margin_sigmas, b.multi_tab, b.cand_cap_sb,
-            zero_ptr, zero_n);
+            b.dev_multi_rec, m->info.n_prunable, ctx->margin_sigmas, b.multi_tab, b.cand_cap_sb);
     }
-    if (k == 0 && !fb) return;   // every count was zero
+    if (k == 0 && !fb) {         // every count was zero: no pass, which would have cleared zero_ptr
+        if (zero_ptr) launch_zero_levels(ctx, m);
+        return;
+    }
     const bool nt = m->info.w_extent * 4 > (192ull << 20);
     if (fb) {
         VariantRanks rv;
@@ -922,17 +1058,32 @@ void launch_spec_multi(shifter_ctx* ctx, const shifter_model* m, const float* d_
         ProfileScope ps(ctx, K_SPEC_PASS);
         auto kern = nt ? ms_pass_kernel<true> : ms_pass_kernel<false>;
         kern<<<m->n_tiles, BLOCK, (k + 1) * BLOCK, s>>>(
-            b.tens, b.tile_prefix, n_t, d_w, b.multi, b.multi_cnt, b.cand, b.multi_tab);
+            b.tens, b.tile_prefix, n_t, d_w, b.multi, b.multi_cnt, b.cand, b.multi_tab, zero_ptr, zero_n);
     }
     if (k != 0) {
-        ProfileScope ps(ctx, K_SPEC_FINISH);
-        ms_finish_kernel<<<k, FIN_THREADS, 0, s>>>(b.multi, b.multi_cnt, b.cand, d_thr,
-                                                   b.dev_multi_rec, b.dev_multi_status);
+        {
+            ProfileScope ps(ctx, K_SPEC_FINISH);
+            // CAND_SUB * 16 wavefronts in the extra layer cover the MAXK + 1 rows
+            static_assert(CAND_SUB * (MF_THREADS / 64) >= MAXK + 1, "a wavefront per row of counters");
+            ms_hist_kernel<<<dim3(CAND_SUB, k + 1), MF_THREADS, 0, s>>>(b.multi, b.multi_cnt, b.cand, b.multi_hist,
+                                                                      b.multi_rowsum, k);
+        }
+        {
+            ProfileScope ps(ctx, K_SPEC_FINISH2);
+            ms_filter_kernel<<<dim3(CAND_SUB, k), MF_THREADS, 0, s>>>(b.multi, b.multi_cnt, b.cand, b.multi_hist,
+                                                                     b.multi_rowsum, b.multi_list,
+                                                                     b.multi_list_cnt);
+        }
+        {
+            ProfileScope ps(ctx, K_SPEC_RANK);
+            ms_rank_kernel<<<k, FIN_THREADS, 0, s>>>(b.multi, b.multi_list, b.multi_list_cnt, d_thr,
+                                                     b.dev_multi_rec, b.dev_multi_status);
+        }
     }
     if (fb) {
         if (k != 0) {
             ProfileScope ps(ctx, K_SPEC_FIXUP);
-            ms_fixup_kernel<<<dim3(SPEC_SUB, k), BLOCK, 0, s>>>(
+            ms_fixup_kernel<<<dim3(CAND_SUB, k, 16), BLOCK, 0, s>>>(
                 b.tens, b.ranked_ids, m->n_ranked, b.multi, b.multi_cnt, b.cand, d_thr,
                 fb->k_all - k, fb->d_w_out, fb->w_stride, fb->d_mask, fb->mask_stride, b.levels,
                 b.levels + m->info.sum_out_ch);

@@ -44,7 +44,7 @@ __global__ __launch_bounds__(BLOCK) void spec_init_kernel(SpecState* ss, uint32_
                                                           uint64_t na, uint8_t* fb, uint64_t nb) {
     const uint64_t tid = (uint64_t)blockIdx.x * BLOCK + threadIdx.x;
     const uint64_t stride = (uint64_t)gridDim.x * BLOCK;
-    for (uint64_t i = tid; i < SBINS; i += stride) shist[i] = 0;
+    (void)shist;     // every ranking leaves the sample histogram cleared (see the predict kernels)
     for (uint64_t i = tid; i < 2u * SPEC_SUB * 32u; i += stride) cnt[i] = 0;
     for (uint64_t i = tid; i < na; i += stride) fa[i] = 0;
     for (uint64_t i = tid; i < nb; i += stride) fb[i] = 0;
@@ -79,8 +79,24 @@ constexpr uint32_t SAMPLE_THREADS = 1024;   // sixteen wavefronts on the block's
 __global__ __launch_bounds__(SAMPLE_THREADS) void spec_sample_kernel(
     const DevTensor* __restrict__ tens, const uint32_t* __restrict__ tile_prefix,
     const uint16_t* __restrict__ tile_tensor, uint32_t n_tiles, uint32_t tile_stride,
-    const float* __restrict__ w, uint32_t* shist) {
+    const float* __restrict__ w, uint32_t* shist, SampleZero z) {
     __shared__ uint32_t h[SBINS];
+    if (z.cnt) {
+        // scratch of the K-rank ranking, idle until its pass: rows 0 .. k and
+        // MAXK + 1 .. MAXK + k of the split counters (the first word of each 128-byte line)
+        const uint32_t tid = blockIdx.x * SAMPLE_THREADS + threadIdx.x, nthr = gridDim.x * SAMPLE_THREADS;
+        for (uint32_t i = tid; i < (2u * z.k + 1u) * SPEC_SUB; i += nthr) {
+            const uint32_t row = i / SPEC_SUB, sb = i % SPEC_SUB;
+            const uint32_t r = row <= z.k ? row : MAXK + 1u + (row - (z.k + 1u));
+            z.cnt[((size_t)r * SPEC_SUB + sb) * 32u] = 0;
+        }
+        for (uint32_t i = tid; i < z.k * 256u; i += nthr) z.ghist[i] = 0;
+        for (uint32_t i = tid; i < z.extra_n; i += nthr) z.extra[i] = 0;
+        if (tid < MAXK) {
+            z.list_cnt[tid] = 0;
+            z.rout[tid].fail = 0;
+        }
+    }
     for (uint32_t i = threadIdx.x; i < SBINS; i += SAMPLE_THREADS) h[i] = 0;
     __syncthreads();
     const uint32_t lane = threadIdx.x & 63u;
@@ -138,8 +154,7 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void spec_sample_kernel(
 // [lo, hi] and a provisional threshold mid (the fused pass writes candidates below mid as
 // removed, the others as kept; few of them then need correcting).
 // The histogram is read as 64 segments of 256 bins, one coalesced load per wavefront.
-__global__ __launch_bounds__(BLOCK) void spec_predict_kernel(SpecState* ss,
-                                                             const uint32_t* __restrict__ shist,
+__global__ __launch_bounds__(BLOCK) void spec_predict_kernel(SpecState* ss, uint32_t* shist,
                                                              uint64_t n_prunable,
                                                              double margin_sigmas) {
     constexpr uint32_t SEG = 256, NSEG = SBINS / SEG;   // 64 segments
@@ -199,6 +214,8 @@ __global__ __launch_bounds__(BLOCK) void spec_predict_kernel(SpecState* ss,
         }
     }
     __syncthreads();
+    // the sample has been read: cleared for the next ranking, which adds to it
+    for (uint32_t i = threadIdx.x; i < SBINS; i += BLOCK) shist[i] = 0;
     if (threadIdx.x != 0) return;
     uint32_t lo = 0, hi = 0x7fffffffu;
     if (s_bin[0] != 0xffffffffu) lo = s_bin[0] << SAMPLE_SHIFT;
@@ -684,7 +701,7 @@ __global__ __launch_bounds__(BLOCK) void spec_fixup_kernel(
     });
 }
 
-void launch_spec_sample(shifter_ctx* ctx, const shifter_model* m, const float* d_w) {
+void launch_spec_sample(shifter_ctx* ctx, const shifter_model* m, const float* d_w, const SampleZero& z) {
     const auto& b = m->b;
     const uint32_t sampled = (m->n_tiles + m->sample_tile_stride - 1) / m->sample_tile_stride;
     // one block per CU: more blocks shorten the loop but every block flushes its LDS
@@ -693,7 +710,7 @@ void launch_spec_sample(shifter_ctx* ctx, const shifter_model* m, const float* d
     const uint32_t grid = std::min(256u, (sampled + 63) / 64);   // 64 tiles per block and step
     spec_sample_kernel<<<grid, SAMPLE_THREADS, 0, ctx->stream>>>(b.tens, b.tile_prefix, b.tile_tensor,
                                                         m->n_tiles, m->sample_tile_stride, d_w,
-                                                        b.shist);
+                                                        b.shist, z);
 }
 
 void launch_spec_select(shifter_ctx* ctx, const shifter_model* m, const float* d_w, uint64_t p,

@@ -209,6 +209,29 @@ class Pipeline:
                     break
         return recs, out
 
+    def step(self, n_prune: Sequence[int], flags: int = 0, with_in_alive: bool = True,
+             sparse_arenas: bool = True):
+        """All five steps for every prune count behind one pair of calls (the library
+        chooses the fusion; one wait).  Works on the batch buffers (enable_batch) for
+        several counts and on the single-variant buffers for one.  Returns (threshold
+        records, compact_batch's tuple)."""
+        k = len(n_prune)
+        self.n_thr = k
+        if k == 1 and getattr(self, "bk", 0) != 1:
+            bufs = (self.d_w_sparse if sparse_arenas else None, 0, self.d_mask, 0,
+                    self.d_out_alive, self.d_in_alive if with_in_alive else None,
+                    self.d_group_alive, self.d_index_map, self.d_keep, self.d_new_width,
+                    self.d_w_out, self.d_w_out.numel(), self.d_vecs_out, self.d_vecs_out.numel())
+        else:
+            assert k == self.bk
+            bufs = (self.b_w_sparse if sparse_arenas else None, self.w_stride, self.b_mask,
+                    self.m_stride, self.b_out_alive, self.b_in_alive if with_in_alive else None,
+                    self.b_group_alive, self.b_index_map, self.b_keep, self.b_new_width,
+                    self.b_w_out, self.cap_w, self.b_vecs_out, self.cap_v)
+        S.shifter_portfolio_begin(self.ctx, self.model, self.d_w, self.d_vecs, n_prune, flags,
+                                  self.d_thr, *bufs)
+        return S.shifter_portfolio_end(self.ctx, self.model)
+
     def variant(self, k: int = 0, flags: int = 0, fused_scan: bool = True,
                 sync: bool = True):
         """Steps 2-5 for threshold record k.  Returns compact()'s tuple."""

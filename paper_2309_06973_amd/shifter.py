@@ -57,6 +57,18 @@ class ModelInfo(C.Structure):
 
 THRESHOLD_BYTES = C.sizeof(Threshold)
 
+
+class PortfolioArgs(C.Structure):
+    _fields_ = [("d_w", C.c_void_p), ("d_vecs", C.c_void_p), ("h_n_prune", C.POINTER(C.c_uint64)),
+                ("K", C.c_uint32), ("flags", C.c_uint32), ("d_thr", C.c_void_p),
+                ("d_w_sparse", C.c_void_p), ("w_stride", C.c_uint64), ("d_mask", C.c_void_p),
+                ("mask_stride", C.c_uint64), ("d_out_alive", C.c_void_p),
+                ("d_in_alive", C.c_void_p), ("d_group_alive", C.c_void_p),
+                ("d_index_map", C.c_void_p), ("d_keep", C.c_void_p), ("d_new_width", C.c_void_p),
+                ("d_w_out", C.c_void_p), ("cap_w", C.c_uint64), ("d_vecs_out", C.c_void_p),
+                ("cap_v", C.c_uint64)]
+
+
 class FoldDesc(C.Structure):
     _fields_ = [("tensor", C.c_uint32), ("gamma", C.c_int32), ("beta", C.c_int32),
                 ("mean", C.c_int32), ("var", C.c_int32), ("bias", C.c_int32),
@@ -79,6 +91,9 @@ EXPORTS = {
                                  C.POINTER(Threshold)],
     "shifter_global_threshold_static": [C.c_void_p, C.c_void_p, C.c_uint64,
                                         C.POINTER(C.c_uint64), C.c_uint32, C.c_void_p],
+    "shifter_portfolio_begin": [C.c_void_p, C.c_void_p, C.POINTER(PortfolioArgs)],
+    "shifter_portfolio_end": [C.c_void_p, C.POINTER(Threshold), C.POINTER(TensorDesc),
+                              C.POINTER(VecDesc), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)],
     "shifter_global_threshold_begin": [C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.POINTER(C.c_uint64), C.c_uint32, C.c_void_p],
     "shifter_global_threshold_end": [C.c_void_p, C.POINTER(Threshold), C.POINTER(C.c_int)],
@@ -387,6 +402,36 @@ def shifter_inflate(ctx: Context, d_stream, stream_bytes: int, d_seg_off, d_sub_
     _check(load_library().shifter_inflate(ctx.handle, _ptr(d_stream), stream_bytes,
                                           _ptr(d_seg_off), _ptr(d_sub_bits), n_bytes,
                                           _ptr(d_out)), ctx.handle)
+
+
+def shifter_portfolio_begin(ctx: Context, model: Model, d_w, d_vecs, n_prune: Sequence[int],
+                            flags: int, d_thr, d_w_sparse, w_stride: int, d_mask, mask_stride: int,
+                            d_out_alive, d_in_alive, d_group_alive, d_index_map, d_keep,
+                            d_new_width, d_w_out, cap_w: int, d_vecs_out, cap_v: int) -> None:
+    """Enqueues a whole portfolio step; collect it with shifter_portfolio_end."""
+    k = len(n_prune)
+    arr = (C.c_uint64 * max(k, 1))(*[int(p) for p in n_prune])
+    a = PortfolioArgs(_ptr(d_w), _ptr(d_vecs), arr, k, flags, _ptr(d_thr), _ptr(d_w_sparse),
+                      w_stride, _ptr(d_mask), mask_stride, _ptr(d_out_alive), _ptr(d_in_alive),
+                      _ptr(d_group_alive), _ptr(d_index_map), _ptr(d_keep), _ptr(d_new_width),
+                      _ptr(d_w_out), cap_w, _ptr(d_vecs_out), cap_v)
+    _check(load_library().shifter_portfolio_begin(ctx.handle, model.handle, C.byref(a)), ctx.handle)
+    ctx._portfolio_k = k
+
+
+def shifter_portfolio_end(ctx: Context, model: Model):
+    """(records, (status, tensor descs, vec descs, elems_w, elems_v)) of the last
+    shifter_portfolio_begin; the descriptor arrays are flat as in shifter_compact_batch."""
+    k = ctx._portfolio_k
+    n_t, n_v = model.info.n_tensors, model.info.n_vecs
+    h = (Threshold * k)()
+    ot = (TensorDesc * (n_t * k))()
+    ov = (VecDesc * max(n_v * k, 1))()
+    ew = (C.c_uint64 * k)()
+    ev = (C.c_uint64 * k)()
+    rc = _check(load_library().shifter_portfolio_end(ctx.handle, h, ot, ov, ew, ev), ctx.handle,
+                allow=(SHIFTER_WARN_COLLAPSE,))
+    return list(h), (rc, ot, ov, ew, ev)
 
 
 def shifter_global_threshold_begin(ctx: Context, model: Model, d_w, n_prune, d_thr) -> None:

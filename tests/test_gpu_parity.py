@@ -30,12 +30,16 @@ def check_threshold(rec, sel, a_prunable):
     assert rec.n_equal == int((a_prunable == np.float32(sel.thr_value)).sum())
 
 
-def check_variant(pl, spec, w, v, ref, flags=0, fused=True, label="", steps_1_to_3_done=False):
+def check_variant(pl, spec, w, v, ref, flags=0, fused=True, label="", steps_1_to_3_done=False,
+                  done=None):
     """Runs steps 2-5 on the GPU for the threshold record already on the device (or only
-    steps 4-5 after a fused steps-1-to-3 call) and compares every output with the
-    oracle's `ref` (a VariantResult)."""
+    steps 4-5 after a fused steps-1-to-3 call; or nothing when `done` holds the outcome of a
+    call that ran all steps) and compares every output with the oracle's `ref` (a
+    VariantResult)."""
     info = pl.model.info
-    if steps_1_to_3_done:
+    if done is not None:
+        rc, ot, ov, ew, ev = done
+    elif steps_1_to_3_done:
         pl.propagate_groups(flags, sync=False)
         rc, ot, ov, ew, ev = pl.compact()
     else:
@@ -108,6 +112,19 @@ def run_config(spec, w, v, n_prune, flags=0, fused=True, check_every=1, single_e
             ref._k = 0
             check_variant(pl, spec, w, v, ref, flags, label=f"{spec.name} fused k={k}",
                           steps_1_to_3_done=True)
+            # the same count through the one-call step (K = 1), single pass and multi-pass select
+            for path in (0, 1):
+                S.shifter_set_select_path(pl.ctx, path)
+                for buf in (pl.d_w_sparse, pl.d_w_out, pl.d_vecs_out):
+                    buf.fill_(float("nan"))
+                pl.d_mask.fill_(7)
+                pl.d_out_alive.fill_(7)
+                pl.d_in_alive.fill_(7)
+                rec1, out1 = pl.step([p], flags)
+                S.shifter_set_select_path(pl.ctx, 0)
+                check_threshold(rec1[0], ref.sel, a)
+                check_variant(pl, spec, w, v, ref, flags, label=f"{spec.name} one-call k={k} path={path}",
+                              done=(out1[0], list(out1[1]), list(out1[2]), out1[3][0], out1[4][0]))
     finally:
         pl.close()
     return refs
@@ -300,6 +317,25 @@ def check_batch(spec, w, v, n_prune, flags=0, check=None, with_in_alive=True):
     try:
         pl.enable_batch(k_var)
         info = pl.model.info
+        # the one-call step: single pass, multi-pass select, and a single pass that is made to
+        # miss (no margin around the predicted thresholds) so that the call repeats the step
+        for mode, sparse_arenas in (("one_call", True), ("one_call", False), ("one_call_radix", True),
+                                    ("one_call_miss", True)):
+            for buf in (pl.b_w_out, pl.b_vecs_out, pl.b_w_sparse):
+                buf.fill_(float("nan"))
+            pl.b_mask.fill_(7)
+            pl.b_out_alive.fill_(7)
+            pl.b_in_alive.fill_(7)
+            if mode == "one_call_radix":
+                S.shifter_set_select_path(pl.ctx, 1)
+            if mode == "one_call_miss":
+                S.shifter_set_margin_sigmas(pl.ctx, 0.0)
+            try:
+                _check_batch_run(pl, spec, refs, a, n_prune, flags, check, with_in_alive, False,
+                                 sparse_arenas, mode)
+            finally:
+                S.shifter_set_select_path(pl.ctx, 0)
+                S.shifter_set_margin_sigmas(pl.ctx, 4.0)
         for fused, from_sparse, sparse_arenas in ((True, False, True), (False, True, True),
                                                   (True, False, False), (False, False, True)):
             # ranking + masks in one read or in two calls; the rebuild from the dense arena
@@ -321,9 +357,12 @@ def _check_batch_run(pl, spec, refs, a, n_prune, flags, check, with_in_alive, fr
                      sparse_arenas, fused):
     info = pl.model.info
     k_var = len(n_prune)
-    recs, (rc, ots, ovs, ews, evs) = pl.portfolio(n_prune, flags, with_in_alive,
-                                                  from_sparse=from_sparse,
-                                                  sparse_arenas=sparse_arenas, fused=fused)
+    if isinstance(fused, str):
+        recs, (rc, ots, ovs, ews, evs) = pl.step(n_prune, flags, with_in_alive, sparse_arenas)
+    else:
+        recs, (rc, ots, ovs, ews, evs) = pl.portfolio(n_prune, flags, with_in_alive,
+                                                      from_sparse=from_sparse,
+                                                      sparse_arenas=sparse_arenas, fused=fused)
     torch.cuda.synchronize()
     collapse = any((r.plan.new_width == 0).any() for r in refs)
     assert rc == (S.SHIFTER_WARN_COLLAPSE if collapse else S.SHIFTER_OK)
