@@ -155,6 +155,7 @@ static void unbind(shifter_model* m) {
         if (p) (void)hipFree(p);
     if (b.host_stage) (void)hipHostFree(b.host_stage);
     if (b.host_spec) (void)hipHostFree(b.host_spec);
+    if (b.host_spec_now) (void)hipHostFree(b.host_spec_now);
     if (b.host_multi) (void)hipHostFree(b.host_multi);
     if (b.host_plan) (void)hipHostFree(b.host_plan);
     b = shifter_model::Bound();
@@ -527,8 +528,19 @@ static int bind_tables(shifter_ctx* ctx, shifter_model* m) {
                                  sizeof(uint32_t) * m->g.size()) +
                          sizeof(SpecState) + sizeof(MultiState) + 256;
     HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&b.host_stage), b.host_stage_bytes, hipHostMallocDefault));
-    HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&b.host_spec),
-                               sizeof(SpecState), hipHostMallocDefault));
+    HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&b.host_spec), sizeof(SpecState),
+                               hipHostMallocMapped | hipHostMallocCoherent));
+    HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&b.host_spec_now), sizeof(SpecState),
+                               hipHostMallocMapped | hipHostMallocCoherent));
+    memset(b.host_spec, 0, sizeof(SpecState));
+    memset(b.host_spec_now, 0, sizeof(SpecState));
+    {
+        void* q = nullptr;
+        HIP_TRY(ctx, hipHostGetDevicePointer(&q, b.host_spec, 0));
+        b.dev_spec = static_cast<SpecState*>(q);
+        HIP_TRY(ctx, hipHostGetDevicePointer(&q, b.host_spec_now, 0));
+        b.dev_spec_now = static_cast<SpecState*>(q);
+    }
     // mirrors written by kernels: host-coherent pinned memory, addressed through its device pointer
     const size_t plan_stride = sizeof(PlanHeader) + sizeof(PlanTensor) * n_t + sizeof(PlanVec) * n_v;
     HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&b.host_multi),
@@ -566,14 +578,8 @@ static int after_launch(shifter_ctx* ctx, const char* fn) {
     return SHIFTER_OK;
 }
 
-// Enqueues the read-back of the single-pass selection's outcome into pinned memory `st`.
-static int spec_result_enqueue(shifter_ctx* ctx, const shifter_model* model, uint8_t* st) {
-    // the state holds a copy of the record: one read-back
-    HIP_TRY(ctx, hipMemcpyAsync(st, model->b.spec, sizeof(SpecState), hipMemcpyDeviceToHost, ctx->stream));
-    return SHIFTER_OK;
-}
-
-// Waits for the stream and evaluates the outcome read back into `st`.
+// Waits for the stream and evaluates the outcome the selection's last kernel left in the
+// pinned mirror `st`.
 static int spec_result_collect(shifter_ctx* ctx, const uint8_t* st, shifter_threshold* h_thr,
                                int* decided) {
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
@@ -597,9 +603,7 @@ static int spec_result_collect(shifter_ctx* ctx, const uint8_t* st, shifter_thre
 
 static int spec_result(shifter_ctx* ctx, const shifter_model* model, shifter_threshold* h_thr,
                        int* decided) {
-    int rc = spec_result_enqueue(ctx, model, model->b.host_stage);
-    if (rc) return rc;
-    return spec_result_collect(ctx, model->b.host_stage, h_thr, decided);
+    return spec_result_collect(ctx, model->b.host_spec_now, h_thr, decided);
 }
 
 // Waits for the stream and evaluates the outcome of the K-rank single pass, which its
@@ -643,7 +647,8 @@ extern "C" int shifter_global_threshold(shifter_ctx* ctx, const shifter_model* m
     }
     if (h_thr && K == 1 && ctx->select_path == 0) {
         // single pass; exact when its own check holds, else fall through to the radix select
-        launch_spec_select(ctx, model, d_w, pc.p[0], d_thr, nullptr, nullptr, nullptr, nullptr);
+        launch_spec_select(ctx, model, d_w, pc.p[0], d_thr, nullptr, nullptr, nullptr, nullptr,
+                           model->b.dev_spec_now);
         if ((rc = after_launch(ctx, "global_threshold"))) return rc;
         int decided = 0;
         if ((rc = spec_result(ctx, model, h_thr, &decided))) return rc;
@@ -880,11 +885,11 @@ extern "C" int shifter_prune_fused(shifter_ctx* ctx, const shifter_model* model,
         return fail(ctx, SHIFTER_ERR_INVALID_ARG,
                     "prune_fused: the outcome of an earlier deferred call has not been collected");
     if (ctx->select_path == 0) {
-        launch_spec_select(ctx, model, d_w, n_prune, d_thr, d_w_out, d_mask, d_out_alive, d_in_alive);
+        launch_spec_select(ctx, model, d_w, n_prune, d_thr, d_w_out, d_mask, d_out_alive, d_in_alive,
+                           h_thr ? model->b.dev_spec_now : model->b.dev_spec);
         if ((rc = after_launch(ctx, "prune_fused"))) return rc;
         if (!h_thr) {
-            // deferred: the outcome is read back behind the kernels and looked at later
-            if ((rc = spec_result_enqueue(ctx, model, model->b.host_spec))) return rc;
+            // deferred: the outcome waits in its pinned mirror and is looked at later
             ctx->pending = {true, model, d_w, n_prune, d_thr, d_w_out, d_mask, d_out_alive, d_in_alive};
             return SHIFTER_OK;
         }
@@ -1343,9 +1348,8 @@ extern "C" int shifter_portfolio_begin(shifter_ctx* ctx, const shifter_model* mo
         // one prune count: ranking, sparse arena, mask and flags in a single read
         pp.mode = 1;
         launch_spec_select(ctx, model, g.d_w, pp.pc.p[0], g.d_thr, g.d_w_sparse, g.d_mask, g.d_out_alive,
-                           g.d_in_alive);
+                           g.d_in_alive, b.dev_spec);
         if ((rc = after_launch(ctx, "portfolio_begin"))) return rc;
-        if ((rc = spec_result_enqueue(ctx, model, b.host_spec))) return rc;
         launch_plan_and_gather(ctx, model, pp.buf, false, cut_positions(pp.pc, K));
     } else if (ctx->select_path == 0 && k_eff <= SPEC_MULTI_MAXK) {
         PruneCounts sp;

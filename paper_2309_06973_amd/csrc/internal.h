@@ -264,7 +264,12 @@ struct shifter_model {
         uint32_t* multi_list_cnt = nullptr;   // MAXK
         uint32_t* below = nullptr;            // MAXK * (sum_group_width + n_groups): survivors below a channel
         uint8_t* host_stage = nullptr;        // pinned, for small read-backs
-        uint8_t* host_spec = nullptr;         // pinned: outcome of a deferred shifter_prune_fused
+        // pinned mirrors of the one-count selection's state, written by its last kernel: one
+        // for calls that wait themselves, one for a deferred call (host and device addresses)
+        uint8_t* host_spec = nullptr;
+        uint8_t* host_spec_now = nullptr;
+        shifter::SpecState* dev_spec = nullptr;
+        shifter::SpecState* dev_spec_now = nullptr;
         // pinned mirrors the kernels write themselves (no copy on the stream): the K-rank
         // ranking's status words (MAXK) and records (MAXK), and the packed plans of MAXK variants
         uint8_t* host_multi = nullptr;
@@ -361,9 +366,10 @@ constexpr size_t STATIC_SCRATCH_BYTES = STATIC_OFF_TILE_CNT + sizeof(uint32_t) *
 static_assert(sizeof(DevTensor) <= 256, "the one-tensor table fits its slot");
 // Writes the one-tensor table of a flat run of n weights (one prunable tensor at offset 0).
 void launch_flat_tables(shifter_ctx* ctx, DevTensor* tens, uint32_t* tile_prefix, uint64_t n);
+// host_mirror: device address of the pinned SpecState the last kernel leaves the outcome in.
 void launch_spec_select(shifter_ctx* ctx, const shifter_model* m, const float* d_w, uint64_t p,
                         shifter_threshold* d_thr, float* d_w_out, uint8_t* d_mask,
-                        uint8_t* d_out_alive, uint8_t* d_in_alive);
+                        uint8_t* d_out_alive, uint8_t* d_in_alive, SpecState* host_mirror);
 // Scratch of the K-rank ranking that the sample kernel clears on the way (cnt == nullptr:
 // nothing): the split counters' rows in use, the clusters' histograms, the list lengths
 // and the finish's per-rank outcome.

@@ -623,32 +623,51 @@ __global__ __launch_bounds__(BLOCK) void gather_rect_kernel(
             const uint32_t quads = (width + 3u) >> 2;
             uint32_t lgq = 0;
             while ((1u << lgq) < quads) ++lgq;
-            // this lane's quads: byte position in a staged row and column in the rectangle
-            uint32_t pos4[4][4], scol[4][4], e0[4];
+            // this lane's quads: byte position in a staged row and column in the rectangle.
+            // Every entry of the keep list the lane needs is fetched first, side by side, and
+            // only then used: one trip to memory per variant (a load placed next to its use
+            // made the compiler wait for each in turn, eight trips)
+            uint32_t pos4[4][4], scol[4][4], e0[4], kv[4][4], ee[4][4], cc[4][4];
+            if (kk >= 4) {
+                // four consecutive columns lie in at most two surviving channels
 #pragma unroll
-            for (uint32_t u = 0; u < 4; ++u) {
-                e0[u] = ((lane + 64u * u) & ((1u << lgq) - 1u)) * 4u;
-                const uint32_t eq = min(e0[u], width - 1u);
-                const uint32_t c2 = kk == 1 ? eq : div_u32(eq, T.magic_kk, T.shift_kk);
-                const uint32_t rem = eq - c2 * kk;
-                if (kk >= 4) {
-                    // four consecutive columns lie in at most two surviving channels
-                    const uint32_t base_a = (keep_i[c2] - ch0) * kk;
-                    const uint32_t base_b = (keep_i[min(c2 + 1u, n_ch - 1u)] - ch0) * kk - kk;
+                for (uint32_t u = 0; u < 4; ++u) {
+                    e0[u] = ((lane + 64u * u) & ((1u << lgq) - 1u)) * 4u;
+                    ee[u][0] = min(e0[u], width - 1u);
+                    cc[u][0] = div_u32(ee[u][0], T.magic_kk, T.shift_kk);
+                    kv[u][0] = keep_i[cc[u][0]];
+                    kv[u][1] = keep_i[min(cc[u][0] + 1u, n_ch - 1u)];
+                }
+#pragma unroll
+                for (uint32_t u = 0; u < 4; ++u) {
+                    const uint32_t rem = ee[u][0] - cc[u][0] * kk;
+                    const uint32_t base_a = (kv[u][0] - ch0) * kk;
+                    const uint32_t base_b = (kv[u][1] - ch0) * kk - kk;
 #pragma unroll
                     for (uint32_t j = 0; j < 4; ++j)
                         scol[u][j] = (rem + j >= kk ? base_b : base_a) + rem + j;
-                } else {
+                }
+            } else {
+#pragma unroll
+                for (uint32_t u = 0; u < 4; ++u) {
+                    e0[u] = ((lane + 64u * u) & ((1u << lgq) - 1u)) * 4u;
 #pragma unroll
                     for (uint32_t j = 0; j < 4; ++j) {
-                        const uint32_t e = min(e0[u] + j, width - 1u);
-                        const uint32_t cj = kk == 1 ? e : div_u32(e, T.magic_kk, T.shift_kk);
-                        scol[u][j] = (keep_i[cj] - ch0) * kk + (e - cj * kk);
+                        ee[u][j] = min(e0[u] + j, width - 1u);
+                        cc[u][j] = kk == 1 ? ee[u][j] : div_u32(ee[u][j], T.magic_kk, T.shift_kk);
+                        kv[u][j] = keep_i[cc[u][j]];
                     }
                 }
 #pragma unroll
-                for (uint32_t j = 0; j < 4; ++j) pos4[u][j] = rect_swizzle(scol[u][j]) * 4u;
+                for (uint32_t u = 0; u < 4; ++u)
+#pragma unroll
+                    for (uint32_t j = 0; j < 4; ++j)
+                        scol[u][j] = (kv[u][j] - ch0) * kk + (ee[u][j] - cc[u][j] * kk);
             }
+#pragma unroll
+            for (uint32_t u = 0; u < 4; ++u)
+#pragma unroll
+                for (uint32_t j = 0; j < 4; ++j) pos4[u][j] = rect_swizzle(scol[u][j]) * 4u;
             float* dst = w_out_all + dst_off;
             const unsigned char* tile_b = reinterpret_cast<const unsigned char*>(tile);
             if (lgq >= 6) {
@@ -761,8 +780,10 @@ void launch_propagate(shifter_ctx* ctx, const shifter_model* m, const uint8_t* d
 // Whether the rebuild of k_var variants takes the rectangle kernel (one read of a shared
 // dense source) or the output-ordered gather.
 static bool use_rect(const shifter_model* m, uint32_t k_var, const shifter_threshold* d_thr) {
-    (void)k_var;
-    return d_thr && m->rect_ok && m->rect_prefix.back() > 0;
+    // a single variant gains nothing from a shared read: the rectangle kernel reads the whole
+    // dense arena, the output-ordered gather only the rows and channels that survive
+    // (measured at 95 % sparsity on 1.3 GB: 246 us against 45)
+    return d_thr && k_var > 1 && m->rect_ok && m->rect_prefix.back() > 0;
 }
 
 // The gather launch alone; the plan (and, for the rectangle kernel, the tables) must be

@@ -29,7 +29,8 @@ constexpr uint32_t CAND_SUB = 32;
 static_assert(CAND_SUB <= SPEC_SUB, "the counters use the first CAND_SUB lines of a row");
 constexpr uint32_t FIN_THREADS = 1024;   // the last step of the finish: one block per rank
 constexpr uint32_t FIN_BINS = 4096;      // bins of one refinement level there
-constexpr uint32_t FIN_LIST = 1024;      // pairs settled by counting
+constexpr uint32_t FIN_LIST = 1024;      // pairs the last bin may hold (too many equal keys beyond that)
+constexpr uint32_t FIN_DIRECT = 96;      // pairs ranked by counting without refining further
 
 // Split counters, one 128-byte line each: row j (0 <= j <= MAXK) counts the weights with
 // exactly j lower ends at or below their key; row MAXK + 1 + r the candidates appended to
@@ -606,8 +607,13 @@ __global__ __launch_bounds__(FIN_THREADS) void ms_rank_kernel(
     uint32_t width_sh = R.sh;        // the pairs in play have (key - lo_cur) >> width_sh == 0
     uint32_t lo_cur = R.lo + (O.bin << width_sh);
     uint32_t cnt_sel = n;
-    while (cnt_sel > FIN_LIST) {
-        if (width_sh == 0) { give_up(5u); return; }   // more equal keys than the list holds: the multi-pass select ranks ties
+    // refine while it pays: ranking by counting is quadratic; a bin of equal keys cannot be
+    // refined and must fit the list
+    while (cnt_sel > FIN_DIRECT) {
+        if (width_sh == 0) {
+            if (cnt_sel > FIN_LIST) { give_up(5u); return; }   // the multi-pass select ranks so many ties
+            break;
+        }
         const uint32_t sh = width_sh > 12u ? width_sh - 12u : 0u;
         for (uint32_t i = threadIdx.x; i < FIN_BINS; i += FIN_THREADS) h[i] = 0;
         __syncthreads();

@@ -520,9 +520,16 @@ __global__ __launch_bounds__(BLOCK) void spec_hist_kernel(const SpecState* __res
 
 // One block: round-2 histogram over the list, then an exact rank (by counting) among the
 // pairs of the selected round-2 bin, then the record.
+// Whatever the outcome, the state (status, counts, the record) is left in its mirror in
+// pinned host memory as the last thing: the host reads it after waiting for the stream,
+// with no copy on the stream.
 __global__ __launch_bounds__(BLOCK) void spec_rank_kernel(SpecState* ss,
                                                           const uint2* __restrict__ list,
-                                                          shifter_threshold* thr) {
+                                                          shifter_threshold* thr, SpecState* host_mirror) {
+    // only thread 0 writes the state in this kernel, so it reads back its own writes
+    auto publish = [&]() {
+        if (threadIdx.x == 0) *host_mirror = *ss;
+    };
     __shared__ uint32_t h[FBINS];
     __shared__ uint64_t comp[SPEC_SMALL_CAP];
     __shared__ uint64_t smem[BLOCK / 64 + 1];
@@ -537,12 +544,14 @@ __global__ __launch_bounds__(BLOCK) void spec_rank_kernel(SpecState* ss,
             *thr = out;
             ss->rec = out;
         }
+        publish();
         return;
     }
-    if (ss->status & 1u) return;
+    if (ss->status & 1u) { publish(); return; }
     const uint32_t n = min(ss->list_cnt, SPEC_LIST_CAP);
     if (n != ss->bin_cnt) {   // cannot happen unless the buffers were disturbed
         if (threadIdx.x == 0) atomicOr(&ss->status, 1u);
+        publish();
         return;
     }
     // round 2: the list's keys span 2^sh values starting at lo + (bin << sh)
@@ -578,6 +587,7 @@ __global__ __launch_bounds__(BLOCK) void spec_rank_kernel(SpecState* ss,
     const uint32_t bin2 = s_bin2, cnt2 = s_cnt2;
     if (cnt2 == 0 || cnt2 > SPEC_SMALL_CAP) {
         if (threadIdx.x == 0) atomicOr(&ss->status, 1u);
+        publish();
         return;
     }
     for (uint32_t i = threadIdx.x; i < n; i += BLOCK) {
@@ -617,6 +627,7 @@ __global__ __launch_bounds__(BLOCK) void spec_rank_kernel(SpecState* ss,
         *thr = out;
         ss->rec = out;
     }
+    publish();
 }
 
 // Candidates of the selected round-1 bin -> list.  Each block stages its hits in LDS and
@@ -715,7 +726,7 @@ void launch_spec_sample(shifter_ctx* ctx, const shifter_model* m, const float* d
 
 void launch_spec_select(shifter_ctx* ctx, const shifter_model* m, const float* d_w, uint64_t p,
                         shifter_threshold* d_thr, float* d_w_out, uint8_t* d_mask,
-                        uint8_t* d_out_alive, uint8_t* d_in_alive) {
+                        uint8_t* d_out_alive, uint8_t* d_in_alive, SpecState* host_mirror) {
     const auto& b = m->b;
     const uint32_t n_t = (uint32_t)m->t.size();
     const bool fused = d_w_out != nullptr;
@@ -753,7 +764,7 @@ void launch_spec_select(shifter_ctx* ctx, const shifter_model* m, const float* d
         ProfileScope ps(ctx, K_SPEC_FINISH2);
         spec_filter_kernel<<<FIN_BLOCKS, BLOCK, 0, s>>>(b.spec, b.spec_cnt, b.partial, b.cand,
                                                         b.cand_cap_sb, b.list);
-        spec_rank_kernel<<<1, BLOCK, 0, s>>>(b.spec, b.list, d_thr);
+        spec_rank_kernel<<<1, BLOCK, 0, s>>>(b.spec, b.list, d_thr, host_mirror);
     }
     if (fused) {
         ProfileScope ps(ctx, K_SPEC_FIXUP);
