@@ -256,6 +256,17 @@ def measure(name, steps, warmup, lean_run=True, cpu_leg=True):
         dt3 = (time.perf_counter() - t0) / steps
         fixpoint = {"ms_per_step_scan_plan_rebuild": round(dt3 * 1e3, 4), "rounds": rounds,
                     "kept_weights": int(fout[3]), "kept_weights_single_pass": int(kept[0])}
+        # the same with nothing read back before the rebuild's own wait (four batches of four
+        # rounds enqueued, those after the fixpoint return at once)
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            pl.kernel_scan()
+            pl.propagate_groups_fixpoint(0, sync=False)
+            fout2 = pl.compact(sync=True)
+        torch.cuda.synchronize()
+        fixpoint["ms_per_step_one_wait"] = round((time.perf_counter() - t0) / steps * 1e3, 4)
+        fixpoint["one_wait_rounds_settled"] = list(S.shifter_fixpoint_status(pl.ctx, pl.model))
+        fixpoint["one_wait_same_result"] = int(fout2[3]) == int(fout[3])
         S.shifter_profile_enable(pl.ctx, True)
         for _ in range(5):
             pl.kernel_scan()

@@ -329,8 +329,18 @@ int shifter_propagate_groups(shifter_ctx* ctx, const shifter_model* model,
  *                  whole; SHIFTER_GROUPS_FIXPOINT is accepted
  *   outputs        as shifter_propagate_groups
  *   h_rounds       host, number of rounds run (the last one removed nothing), or NULL
- * The call waits for the stream after every round (the host decides whether another
- * round is needed). */
+ * Rounds are enqueued in batches of four with no wait between them: the kernels of a round
+ * return at once when the round before removed nothing, and each batch ends with the plan
+ * of what is alive then.  With h_new_width or h_rounds given the call waits once per
+ * batch and goes on until the fixpoint is reached (one wait for up to four rounds).  With
+ * both NULL it waits for nothing and enqueues four batches (so it can be recorded into a
+ * HIP graph); should sixteen rounds not reach the fixpoint, the plan written is that of
+ * the sixteenth round - every channel it removes is one the fixpoint removes too, so the
+ * rebuilt network still computes the same function, only larger than need be.
+ * shifter_fixpoint_status
+ *   reads what the last call's kernels reported, once the caller has waited for the
+ *   stream: h_rounds (rounds run) and h_settled (1 iff the last round removed nothing),
+ *   either may be NULL. */
 int shifter_model_get_kernel_layout(const shifter_model* model, uint64_t* h_kernel_off,
                                     uint64_t* h_sum_kernels);
 int shifter_kernel_scan(shifter_ctx* ctx, const shifter_model* model, const float* d_w_sparse,
@@ -340,6 +350,8 @@ int shifter_propagate_groups_fixpoint(shifter_ctx* ctx, const shifter_model* mod
                                       uint8_t* d_group_alive, int32_t* d_index_map,
                                       uint32_t* d_keep, uint32_t* d_new_width,
                                       uint32_t* h_new_width, uint32_t* h_rounds);
+int shifter_fixpoint_status(shifter_ctx* ctx, const shifter_model* model, uint32_t* h_rounds,
+                            uint32_t* h_settled);
 
 /* --- Module 1, Model Pre-Processor (Sec. III-D): conv + BatchNorm fold ----------------
  *
@@ -373,8 +385,11 @@ typedef struct {
  *   d_w_out          device, weight arena of the same layout; may be d_w (in place);
  *                    elements outside the tensors are not touched
  *   d_bias_out       device, cap_bias floats; only the listed ranges are written
- * Waits for the work already on the context's stream (the layer table goes through a
- * staging buffer), then enqueues the fold and returns without waiting for it.
+ * The validated layer table stays on the device with the model.  A call whose list
+ * equals that of the call before only enqueues the fold: no upload, no wait, and the call
+ * may be recorded into a HIP graph.  A call with another list (the first one included)
+ * waits for the work already on the context's stream, uploads the table, then enqueues
+ * the fold; on a capturing stream it is refused with SHIFTER_ERR_INVALID_ARG.
  * Errors: SHIFTER_ERR_INVALID_ARG for a bad list (nothing is enqueued). */
 int shifter_fold_bn(shifter_ctx* ctx, const shifter_model* model,
                     const shifter_fold_desc* h_fold, uint32_t n_fold, float eps,

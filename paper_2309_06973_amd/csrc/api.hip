@@ -1,6 +1,7 @@
 // Host side of the C ABI: descriptor validation, device tables and scratch, argument
 // checks, stream-ordered launches and the small read-backs the ABI documents.
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -108,6 +109,8 @@ extern "C" int shifter_create(shifter_ctx** out, int device, void* hip_stream) {
     HIP_TRY(nullptr, hipSetDevice(device));
     shifter_ctx* c = new (std::nothrow) shifter_ctx();
     if (!c) return fail(nullptr, SHIFTER_ERR_OOM, "shifter_create: host allocation failed");
+    static std::atomic<uint64_t> next_id{1};
+    c->id = next_id.fetch_add(1);
     c->device = device;
     c->stream = reinterpret_cast<hipStream_t>(hip_stream);
     {
@@ -158,6 +161,7 @@ static void unbind(shifter_model* m) {
     if (b.host_spec_now) (void)hipHostFree(b.host_spec_now);
     if (b.host_multi) (void)hipHostFree(b.host_multi);
     if (b.host_plan) (void)hipHostFree(b.host_plan);
+    if (b.host_width) (void)hipHostFree(b.host_width);
     b = shifter_model::Bound();
 }
 
@@ -447,10 +451,11 @@ static int bind_tables(shifter_ctx* ctx, shifter_model* m);
 // fails half way is taken down again, so that a later call starts from nothing.
 static int bind(shifter_ctx* ctx, const shifter_model* cm) {
     shifter_model* m = const_cast<shifter_model*>(cm);
-    if (m->b.ctx == ctx) return SHIFTER_OK;
+    if (m->b.ctx == ctx && m->b.ctx_id == ctx->id) return SHIFTER_OK;
     unbind(m);
     HIP_TRY(ctx, hipSetDevice(ctx->device));
     m->b.ctx = ctx;
+    m->b.ctx_id = ctx->id;
     m->b.device = ctx->device;
     const int rc = bind_tables(ctx, m);
     if (rc) unbind(m);
@@ -495,7 +500,7 @@ static int bind_tables(shifter_ctx* ctx, shifter_model* m) {
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.fix_produced), std::max<uint64_t>(m->info.sum_out_ch, 16)));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.fix_read), std::max<uint64_t>(m->info.sum_in_ch, 16)));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.fix_out_flags), std::max<uint64_t>(m->info.sum_out_ch, 16)));
-    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.fix_removed), 16));
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.fix_removed), sizeof(uint32_t) * FIX_STATE_WORDS));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.fold), sizeof(FoldTensor) * std::max<size_t>(n_t, 1)));
     HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&b.fold_scale),
                            sizeof(float) * std::max<uint64_t>(m->info.sum_out_ch, 4)));
@@ -556,6 +561,12 @@ static int bind_tables(shifter_ctx* ctx, shifter_model* m) {
     b.dev_multi_rec = reinterpret_cast<shifter_threshold*>(static_cast<uint8_t*>(dp) + MULTI_MIRROR_REC_OFF);
     HIP_TRY(ctx, hipHostGetDevicePointer(&dp, b.host_plan, 0));
     b.dev_plan = static_cast<uint8_t*>(dp);
+    HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&b.host_width),
+                               sizeof(uint32_t) * std::max<size_t>(m->g.size(), 1),
+                               hipHostMallocMapped | hipHostMallocCoherent));
+    memset(b.host_width, 0, sizeof(uint32_t) * std::max<size_t>(m->g.size(), 1));
+    HIP_TRY(ctx, hipHostGetDevicePointer(&dp, b.host_width, 0));
+    b.dev_width = static_cast<uint32_t*>(dp);
     HIP_TRY(ctx, hipDeviceSynchronize());     // the memsets above are done before any kernel of the model
     return SHIFTER_OK;
 }
@@ -1115,29 +1126,56 @@ extern "C" int shifter_propagate_groups_fixpoint(shifter_ctx* ctx, const shifter
     if (flags & ~(uint32_t)(SHIFTER_PAPER_FREEZE_RESIDUAL | SHIFTER_GROUPS_FIXPOINT))
         return fail(ctx, SHIFTER_ERR_INVALID_ARG, "propagate_groups_fixpoint: unknown flag");
     const auto& b = model->b;
+    const bool wait = h_new_width || h_rounds;
     launch_fix_begin(ctx, model);
     // every round that changes something removes at least one channel
     const uint64_t max_rounds = model->info.sum_group_width + 1;
-    uint32_t rounds = 0;
-    for (;;) {
-        launch_fix_round(ctx, model, d_kernel_nz, flags);
+    const volatile uint32_t* mirror = reinterpret_cast<const volatile uint32_t*>(b.host_multi) + FIX_MIRROR_WORD;
+    const volatile uint32_t* st = b.host_width;
+    const size_t n_g = model->g.size();
+    for (uint32_t batch = 0;; ++batch) {
+        // a batch of rounds, the flags of what is alive after it, and the plan from them
+        launch_fix_batch(ctx, model, d_kernel_nz, flags);
+        launch_propagate(ctx, model, b.fix_out_flags, flags & SHIFTER_PAPER_FREEZE_RESIDUAL, d_group_alive,
+                         d_index_map, d_keep, d_new_width, 1);
         if ((rc = after_launch(ctx, "propagate_groups_fixpoint"))) return rc;
-        ++rounds;
-        uint8_t* st = b.host_stage;
-        HIP_TRY(ctx, hipMemcpyAsync(st, b.fix_removed, sizeof(uint32_t), hipMemcpyDeviceToHost, ctx->stream));
+        if (!wait) {
+            // nothing is read back: a fixed number of batches, of which those after the
+            // fixpoint cost a few empty launches
+            if (batch + 1 == FIX_ENQUEUED_BATCHES) return SHIFTER_OK;
+            continue;
+        }
+        if (h_new_width) launch_fix_widths(ctx, model, d_new_width);
         HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
-        uint32_t removed;
-        memcpy(&removed, st, sizeof removed);
-        if (removed == 0) break;
-        if (rounds > max_rounds)
+        if (mirror[1]) break;
+        if ((uint64_t)mirror[0] > max_rounds)
             return fail(ctx, SHIFTER_ERR_INTERNAL, "propagate_groups_fixpoint: did not settle");
     }
-    if (h_rounds) *h_rounds = rounds;
-    launch_fix_out_flags(ctx, model);
-    if ((rc = after_launch(ctx, "propagate_groups_fixpoint"))) return rc;
-    return shifter_propagate_groups_batch(ctx, model, b.fix_out_flags, 1,
-                                          flags & SHIFTER_PAPER_FREEZE_RESIDUAL, d_group_alive,
-                                          d_index_map, d_keep, d_new_width, h_new_width);
+    if (h_rounds) *h_rounds = mirror[0];
+    if (h_new_width) {
+        bool collapse = false;
+        for (size_t g = 0; g < n_g; ++g) {
+            h_new_width[g] = st[g];
+            collapse |= st[g] == 0;
+        }
+        if (collapse) {
+            fail(ctx, SHIFTER_WARN_COLLAPSE, "propagate_groups_fixpoint: a group kept no channel (layer collapse)");
+            return SHIFTER_WARN_COLLAPSE;
+        }
+    }
+    return SHIFTER_OK;
+}
+
+extern "C" int shifter_fixpoint_status(shifter_ctx* ctx, const shifter_model* model, uint32_t* h_rounds,
+                                       uint32_t* h_settled) {
+    if (!ctx) return fail(nullptr, SHIFTER_ERR_INVALID_ARG, "fixpoint_status: ctx is NULL");
+    if (!model || model->b.ctx != ctx || model->b.ctx_id != ctx->id)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "fixpoint_status: the model has run nothing on this context");
+    const volatile uint32_t* mirror =
+        reinterpret_cast<const volatile uint32_t*>(model->b.host_multi) + FIX_MIRROR_WORD;
+    if (h_rounds) *h_rounds = mirror[0];
+    if (h_settled) *h_settled = mirror[1];
+    return SHIFTER_OK;
 }
 
 extern "C" int shifter_fold_bn(shifter_ctx* ctx, const shifter_model* model,
@@ -1187,12 +1225,25 @@ extern "C" int shifter_fold_bn(shifter_ctx* ctx, const shifter_model* model,
         if (spans[i].first < spans[i - 1].second)
             return fail(ctx, SHIFTER_ERR_INVALID_ARG, "fold_bn: bias ranges overlap");
     if (n_t == 0) return SHIFTER_OK;
-    // the pinned staging area may still feed an earlier upload: wait before rewriting it
-    // (read-backs into it are enqueued behind this upload, so they cannot overtake it)
-    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
-    memcpy(model->b.host_stage, tab.data(), sizeof(FoldTensor) * n_t);
-    HIP_TRY(ctx, hipMemcpyAsync(model->b.fold, model->b.host_stage, sizeof(FoldTensor) * n_t,
-                                hipMemcpyHostToDevice, ctx->stream));
+    // the validated table stays on the device: a call with the list of the call before
+    // uploads nothing and waits for nothing
+    auto& held = const_cast<shifter_model*>(model)->b.fold_host;
+    if (held.size() != n_t || memcmp(held.data(), tab.data(), sizeof(FoldTensor) * n_t) != 0) {
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        HIP_TRY(ctx, hipStreamIsCapturing(ctx->stream, &cap));
+        if (cap != hipStreamCaptureStatusNone)
+            return fail(ctx, SHIFTER_ERR_INVALID_ARG,
+                        "fold_bn: a new layer list needs an upload and a wait, which a capturing stream "
+                        "cannot take: call once with this list before the capture");
+        // the pinned staging area may still feed an earlier upload: wait before rewriting it
+        // (read-backs into it are enqueued behind this upload, so they cannot overtake it)
+        held.clear();
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+        memcpy(model->b.host_stage, tab.data(), sizeof(FoldTensor) * n_t);
+        HIP_TRY(ctx, hipMemcpyAsync(model->b.fold, model->b.host_stage, sizeof(FoldTensor) * n_t,
+                                    hipMemcpyHostToDevice, ctx->stream));
+        held = tab;
+    }
     launch_fold(ctx, model, d_w, d_vecs, eps, d_w_out, d_bias_out);
     return after_launch(ctx, "fold_bn");
 }

@@ -216,6 +216,7 @@ struct shifter_model {
     // device side, created by the first call that uses the model with a context
     struct Bound {
         shifter_ctx* ctx = nullptr;
+        uint64_t ctx_id = 0;                  // that context's id: an address alone may be reused
         int device = 0;
         shifter::DevTensor* tens = nullptr;
         shifter::DevGroup* groups = nullptr;
@@ -244,8 +245,9 @@ struct shifter_model {
         uint8_t* fix_produced = nullptr;      // sum_out_ch
         uint8_t* fix_read = nullptr;          // sum_in_ch
         uint8_t* fix_out_flags = nullptr;     // sum_out_ch
-        uint32_t* fix_removed = nullptr;      // 1
+        uint32_t* fix_removed = nullptr;      // FIX_STATE_WORDS: per-round counters of a batch, rounds so far
         shifter::FoldTensor* fold = nullptr;  // n_tensors
+        std::vector<shifter::FoldTensor> fold_host;   // the layer table the device holds (empty: none yet)
         float* fold_scale = nullptr;          // sum_out_ch
         shifter::SpecState* spec = nullptr;
         uint32_t* shist = nullptr;            // 65536 sample bins
@@ -277,11 +279,14 @@ struct shifter_model {
         shifter_threshold* dev_multi_rec = nullptr;
         uint8_t* host_plan = nullptr;
         uint8_t* dev_plan = nullptr;
+        uint32_t* host_width = nullptr;       // n_groups: the fixpoint plan's widths
+        uint32_t* dev_width = nullptr;
         size_t host_stage_bytes = 0;
     } b;
 };
 
 struct shifter_ctx {
+    uint64_t id = 0;       // unique per shifter_create in this process
     int device = 0;
     hipStream_t stream = nullptr;
     uint8_t* static_scratch = nullptr;   // this device's copy of the library's static scratch array
@@ -400,7 +405,15 @@ void launch_spec_multi(shifter_ctx* ctx, const shifter_model* m, const float* d_
                        const shifter::PruneCounts& sorted_p, const shifter::MultiPerm& perm,
                        uint32_t k, uint64_t zero_mask, shifter_threshold* d_thr,
                        const FusedBatch* fb, uint32_t* zero_ptr = nullptr, uint32_t zero_n = 0);
-constexpr size_t MULTI_MIRROR_REC_OFF = 256;   // records follow the MAXK status words
+constexpr size_t MULTI_MIRROR_REC_OFF = 512;   // records follow the MAXK status words
+// The liveness fixpoint enqueues its rounds in batches of FIX_BATCH with no wait inside a
+// batch; its state on the device is removed[0 .. FIX_BATCH] and the rounds run so far, and
+// (rounds, settled) go to two words of the status mirror behind the MAXK status words.
+constexpr uint32_t FIX_BATCH = 4;
+constexpr uint32_t FIX_STATE_WORDS = FIX_BATCH + 2;
+constexpr uint32_t FIX_MIRROR_WORD = 64;
+constexpr uint32_t FIX_ENQUEUED_BATCHES = 4;   // of a call that may not wait
+static_assert(MAXK <= FIX_MIRROR_WORD && (FIX_MIRROR_WORD + 2) * 4 <= MULTI_MIRROR_REC_OFF, "mirror layout");
 void launch_zero_levels(shifter_ctx* ctx, const shifter_model* m);
 void launch_expand_levels(shifter_ctx* ctx, const shifter_model* m, const shifter_threshold* d_thr,
                           uint32_t k_var, uint8_t* d_out_alive, uint8_t* d_in_alive);
@@ -432,8 +445,8 @@ void launch_mask_scan_batch_core(shifter_ctx* ctx, const shifter_model* m, const
 void launch_copy(shifter_ctx* ctx, const float* src, float* dst, uint64_t n);
 void launch_kernel_scan(shifter_ctx* ctx, const shifter_model* m, const float* d_w, uint8_t* d_nz);
 void launch_fix_begin(shifter_ctx* ctx, const shifter_model* m);
-void launch_fix_round(shifter_ctx* ctx, const shifter_model* m, const uint8_t* d_nz, uint32_t flags);
-void launch_fix_out_flags(shifter_ctx* ctx, const shifter_model* m);
+void launch_fix_batch(shifter_ctx* ctx, const shifter_model* m, const uint8_t* d_nz, uint32_t flags);
+void launch_fix_widths(shifter_ctx* ctx, const shifter_model* m, const uint32_t* d_new_width);
 // Codec workspace: segment sizes (u32 per chunk) first, then one slot per chunk.
 inline uint64_t codec_slots_offset(uint64_t n_chunks) { return (n_chunks * 4u + 255u) & ~(uint64_t)255u; }
 int launch_deflate(shifter_ctx* ctx, const uint8_t* d_in, uint64_t n_bytes, uint32_t n_chunks,

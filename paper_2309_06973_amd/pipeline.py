@@ -100,12 +100,13 @@ class Pipeline:
                                           self.d_index_map, self.d_keep, self.d_new_width,
                                           sync)
 
-    def fold_bn(self, folds, n_bias: int, eps: float, src=None, dst=None):
+    def fold_bn(self, folds, n_bias: int, eps: float, src=None, dst=None, bias=None):
         """Conv + BatchNorm fold of an arena (default: the sparse one) into ``dst`` (default:
         a new arena).  Returns (folded weight arena, bias arena of n_bias floats)."""
         src = self.d_w_sparse if src is None else src
         dst = torch.empty_like(src) if dst is None else dst
-        d_bias = torch.zeros(max(n_bias, 4), dtype=torch.float32, device=self.dev)
+        d_bias = (torch.zeros(max(n_bias, 4), dtype=torch.float32, device=self.dev)
+                  if bias is None else bias)
         S.shifter_fold_bn(self.ctx, self.model, folds, eps, src, self.d_vecs, dst, d_bias)
         return dst, d_bias
 
@@ -117,10 +118,10 @@ class Pipeline:
         S.shifter_kernel_scan(self.ctx, self.model, self.d_w_sparse if src is None else src,
                               self.d_kernel_nz)
 
-    def propagate_groups_fixpoint(self, flags: int = 0):
+    def propagate_groups_fixpoint(self, flags: int = 0, sync: bool = True):
         return S.shifter_propagate_groups_fixpoint(self.ctx, self.model, self.d_kernel_nz, flags,
                                                    self.d_group_alive, self.d_index_map,
-                                                   self.d_keep, self.d_new_width)
+                                                   self.d_keep, self.d_new_width, sync)
 
     def compact(self, sync: bool = True, src=None):
         return S.shifter_compact(self.ctx, self.model,

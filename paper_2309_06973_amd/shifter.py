@@ -141,6 +141,7 @@ EXPORTS = {
     "shifter_propagate_groups_fixpoint": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)],
+    "shifter_fixpoint_status": [C.c_void_p, C.c_void_p, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)],
     "shifter_prune_fused_result": [C.c_void_p, C.POINTER(Threshold), C.POINTER(C.c_int)],
     "shifter_prune_fused_batch": [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_uint64),
                                   C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p,
@@ -457,8 +458,15 @@ def shifter_kernel_scan(ctx: Context, model: Model, d_w_sparse, d_kernel_nz) -> 
 
 
 def shifter_propagate_groups_fixpoint(ctx: Context, model: Model, d_kernel_nz, flags: int,
-                                      d_group_alive, d_index_map, d_keep, d_new_width):
-    """Returns (status, new_width list, rounds).  Always waits."""
+                                      d_group_alive, d_index_map, d_keep, d_new_width,
+                                      sync: bool = True):
+    """Returns (status, new_width list, rounds); with sync=False nothing is waited for and
+    nothing read back (see shifter_fixpoint_status)."""
+    if not sync:
+        _check(load_library().shifter_propagate_groups_fixpoint(
+            ctx.handle, model.handle, _ptr(d_kernel_nz), flags, _ptr(d_group_alive),
+            _ptr(d_index_map), _ptr(d_keep), _ptr(d_new_width), None, None), ctx.handle)
+        return SHIFTER_OK, None, None
     h = (C.c_uint32 * model.info.n_groups)()
     rounds = C.c_uint32()
     rc = _check(load_library().shifter_propagate_groups_fixpoint(
@@ -466,6 +474,14 @@ def shifter_propagate_groups_fixpoint(ctx: Context, model: Model, d_kernel_nz, f
         _ptr(d_index_map), _ptr(d_keep), _ptr(d_new_width), h, C.byref(rounds)),
         ctx.handle, allow=(SHIFTER_WARN_COLLAPSE,))
     return rc, list(h), int(rounds.value)
+
+
+def shifter_fixpoint_status(ctx: Context, model: Model):
+    """(rounds, settled) of the last fixpoint call, once its stream has been waited for."""
+    rounds, settled = C.c_uint32(), C.c_uint32()
+    _check(load_library().shifter_fixpoint_status(ctx.handle, model.handle, C.byref(rounds),
+                                                  C.byref(settled)), ctx.handle)
+    return int(rounds.value), bool(settled.value)
 
 
 def shifter_compact(ctx: Context, model: Model, d_w_sparse, d_vecs, d_keep, d_new_width,

@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 import torch
 
+from oracle import fold_oracle as FO
 from oracle import shifter_oracle as O
 from paper_2309_06973_amd import shifter as S
 from paper_2309_06973_amd import synth
@@ -89,5 +90,74 @@ def test_portfolio_step_replayed_from_a_graph(c):
             graph.replay()
             stream.synchronize()
             assert same(outputs(pl), eager2)
+        finally:
+            pl.close()
+
+
+def enqueue_fold_and_fixpoint(pl, folds, d_folded, d_bias):
+    """Module 1's fold of the sparse arena, then the kernel index, the liveness fixpoint and
+    the rebuild on it, none of them waiting or reading anything back."""
+    pl.fold_bn(folds, d_bias.numel(), 1e-5, dst=d_folded, bias=d_bias)
+    pl.kernel_scan()
+    pl.propagate_groups_fixpoint(0, sync=False)
+    pl.compact(sync=False)
+
+
+@pytest.mark.parametrize("c", [1, 3])
+def test_fold_and_fixpoint_replayed_from_a_graph(c):
+    spec, w, v = synth.generate_config(c)
+    p = synth.prune_count(spec.n_prunable, 0.9)
+    fspec, folds = synth.fused_spec(spec)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        pl = Pipeline(spec, w, v)
+        try:
+            pl.single(p)
+            d_folded = torch.empty_like(pl.d_w_sparse)
+            d_bias = torch.zeros(max(fspec.v_elems, 4), dtype=torch.float32, device=pl.dev)
+            outs = lambda: [d_folded, d_bias, pl.d_kernel_nz, pl.d_group_alive, pl.d_index_map, pl.d_keep,
+                            pl.d_new_width, pl.d_w_out, pl.d_vecs_out]
+
+            def scrub():
+                for x in outs():
+                    x.view(torch.uint8).fill_(0x5a)
+                d_bias.zero_()
+
+            # eager, with the calls that wait: the reference, itself checked against the oracle
+            pl.kernel_scan()
+            scrub()
+            enqueue_fold_and_fixpoint(pl, folds, d_folded, d_bias)   # first call: uploads the layer table
+            rc, nw, rounds = pl.propagate_groups_fixpoint(0)
+            pl.compact(sync=True)
+            stream.synchronize()
+            eager = [x.clone() for x in outs()]
+            ws = pl.d_w_sparse[:spec.w_elems].cpu().numpy()
+            plan = O.propagate_groups_fixpoint(spec.tensors, spec.groups, O.kernel_scan(ws, spec.tensors))
+            assert nw == [int(x) for x in plan.new_width]
+            fw, _ = FO.fold_bn(ws, v, spec.tensors, spec.vecs, folds, 1e-5, fspec.v_elems)
+            assert np.allclose(d_folded[:spec.w_elems].cpu().numpy(), fw[:spec.w_elems], rtol=4 * 2.0 ** -23, atol=0)
+            # the enqueue-only form alone gives the same and reports the same rounds
+            scrub()
+            enqueue_fold_and_fixpoint(pl, folds, d_folded, d_bias)
+            stream.synchronize()
+            assert same(outs(), eager)
+            assert S.shifter_fixpoint_status(pl.ctx, pl.model) == (rounds, True)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                enqueue_fold_and_fixpoint(pl, folds, d_folded, d_bias)
+            for _ in range(3):
+                scrub()
+                stream.synchronize()
+                graph.replay()
+                stream.synchronize()
+                assert same(outs(), eager)
+                assert S.shifter_fixpoint_status(pl.ctx, pl.model) == (rounds, True)
+                pl.propagate_groups_fixpoint(0)            # an eager call between the replays
+            # a new layer list cannot be uploaded while the stream is capturing
+            with pytest.raises(S.ShifterError):
+                g2 = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g2, stream=stream):
+                    d_bias.zero_()
+                    pl.fold_bn(folds[:-1], d_bias.numel(), 1e-5, dst=d_folded, bias=d_bias)
         finally:
             pl.close()
