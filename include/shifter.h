@@ -219,6 +219,11 @@ int shifter_set_select_path(shifter_ctx* ctx, int path);
  * affects results. */
 int shifter_set_margin_sigmas(shifter_ctx* ctx, double sigmas);
 
+/* Blocks of the multi-pass select's histogram kernels, which walk the tiles with a stride
+ * of the grid (default eight per compute unit; 1 .. 65536).  A launch shape only: the
+ * records, and everything computed from them, are the same bytes for every value. */
+int shifter_set_select_grid(shifter_ctx* ctx, uint32_t blocks);
+
 /* Outcome of the last waiting selection on this context, for measurement:
  * out8 = { path (1 single pass decided, 2 multi-pass select ran, 0 none yet), P,
  *          weights below the interval, weights inside it, sample size, interval low key,
@@ -484,7 +489,7 @@ int shifter_compact(shifter_ctx* ctx, const shifter_model* model, const float* d
 
 /* Steps 2-5 for the K variants of a portfolio in one launch per step (Sec. III-C: the
  * variants of a portfolio mask the same dense weights at growing sparsity; Sec. III-D
- * Module 4: all channels pruned "in a single batch operation").  Results per variant are
+ * Module 4: every layer's channels removed by one operation).  Results per variant are
  * identical to the single-variant calls; variant k's buffers sit k strides after
  * variant 0's.  The dense arena is read once for all K sparse arenas.
  *

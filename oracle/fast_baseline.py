@@ -59,3 +59,86 @@ def prune_and_compact_fast(w, v, tensors, vecs, groups, n_prune: int):
     out_v = [np.asarray(v[d.offset:d.offset + d.length])[keep[d.group]] for d in vecs]
     cat = lambda xs: np.concatenate(xs) if xs else np.zeros(0, np.float32)
     return w_sparse, mask, new_width, cat(out_w), cat(out_v)
+
+
+def prune_and_compact_fast_mt(w, v, tensors, vecs, groups, n_prune: int, threads: int,
+                              slab: int = 1 << 22):
+    """The same variant on `threads` host threads (numpy's loops run outside the interpreter
+    lock).  The selection is by counting: a histogram of the keys' upper 16 bits over slabs of
+    the prunable weights, the bucket that holds the P-th smallest key, then a partition of that
+    bucket's keys alone; masks, the zero-filter scan and the gathers go tensor by tensor.
+    Same results and layouts as ``prune_and_compact_fast``."""
+    from concurrent.futures import ThreadPoolExecutor
+    w = np.asarray(w, dtype=np.float32)
+    bits = w.view(np.uint32)
+    numel = lambda t: t.out_ch * t.in_ch * t.kh * t.kw
+    slabs = []                       # (global index of the first weight, arena offset, length)
+    g = 0
+    for t in tensors:
+        if not t.prunable:
+            continue
+        m = numel(t)
+        for a in range(0, m, slab):
+            slabs.append((g + a, t.offset + a, min(slab, m - a)))
+        g += m
+    n = g
+    absmask = np.uint32(0x7FFFFFFF)
+    w_sparse = w.copy()
+    mask = np.ones(n, dtype=np.uint8)
+    with ThreadPoolExecutor(max_workers=max(1, threads)) as pool:
+        if n_prune > 0:
+            def hist(s):
+                k = bits[s[1]:s[1] + s[2]] & absmask
+                if k.size and int(k.max()) > 0x7F800000:
+                    raise ValueError("NaN among prunable weights")
+                return np.bincount(k >> np.uint32(15), minlength=1 << 16)
+            total = np.zeros(1 << 16, dtype=np.int64)
+            for h in pool.map(hist, slabs):
+                total += h
+            cum = np.cumsum(total)
+            b = int(np.searchsorted(cum, n_prune, side="left"))     # first bucket with cum >= P
+            r = n_prune - (int(cum[b - 1]) if b else 0)              # rank inside the bucket
+
+            def cands(s):
+                k = bits[s[1]:s[1] + s[2]] & absmask
+                idx = np.flatnonzero((k >> np.uint32(15)) == b)
+                return k[idx], idx.astype(np.int64) + s[0]
+            parts = list(pool.map(cands, slabs))
+            ck = np.concatenate([p[0] for p in parts])
+            cg = np.concatenate([p[1] for p in parts])               # ascending global index
+            t_key = np.partition(ck, r - 1)[r - 1]
+            need = r - int((ck < t_key).sum())
+            g_cut = int(cg[np.flatnonzero(ck == t_key)[need - 1]])   # ties go by ascending index
+
+            def apply(s):
+                k = bits[s[1]:s[1] + s[2]] & absmask
+                rem = k < t_key
+                if s[0] <= g_cut:
+                    tie = np.flatnonzero(k == t_key)
+                    rem[tie[tie + s[0] <= g_cut]] = True
+                w_sparse[s[1]:s[1] + s[2]][rem] = 0.0
+                mask[s[0]:s[0] + s[2]][rem] = 0
+            list(pool.map(apply, slabs))
+        else:
+            for s in slabs:
+                if s[2] and int((bits[s[1]:s[1] + s[2]] & absmask).max()) > 0x7F800000:
+                    raise ValueError("NaN among prunable weights")
+        sb = w_sparse.view(np.uint32)
+
+        def scan(t):
+            nz = (sb[t.offset:t.offset + numel(t)] & absmask) != 0
+            return nz.reshape(t.out_ch, -1).any(axis=1)
+        alive = [np.array([bool(gr.pinned)] * gr.width) for gr in groups]
+        for t, a in zip(tensors, pool.map(scan, tensors)):
+            alive[t.out_group] |= a
+        keep = [np.flatnonzero(a) for a in alive]
+        new_width = np.array([k.size for k in keep], dtype=np.uint32)
+
+        def gather(t):
+            x = w_sparse[t.offset:t.offset + numel(t)]
+            x = x.reshape(t.out_ch, t.in_ch // t.in_mult, t.in_mult * t.kh * t.kw)
+            return x[keep[t.out_group]][:, keep[t.in_group]].reshape(-1)
+        out_w = list(pool.map(gather, tensors))
+    out_v = [np.asarray(v[d.offset:d.offset + d.length])[keep[d.group]] for d in vecs]
+    cat = lambda xs: np.concatenate(xs) if xs else np.zeros(0, np.float32)
+    return w_sparse, mask, new_width, cat(out_w), cat(out_v)

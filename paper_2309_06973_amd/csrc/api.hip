@@ -956,6 +956,13 @@ extern "C" int shifter_set_margin_sigmas(shifter_ctx* ctx, double sigmas) {
     return SHIFTER_OK;
 }
 
+extern "C" int shifter_set_select_grid(shifter_ctx* ctx, uint32_t blocks) {
+    if (!ctx || blocks == 0 || blocks > 65536)
+        return fail(ctx, SHIFTER_ERR_INVALID_ARG, "set_select_grid: blocks must be in [1, 65536]");
+    ctx->hist_grid = blocks;
+    return SHIFTER_OK;
+}
+
 extern "C" int shifter_set_select_path(shifter_ctx* ctx, int path) {
     if (!ctx || path < 0 || path > 1)
         return fail(ctx, SHIFTER_ERR_INVALID_ARG, "set_select_path: path must be 0 or 1");

@@ -1,7 +1,7 @@
 // K variants of a portfolio in one launch per step: the dense arena is read once and
 // every variant's sparse arena and mask are written from it (Sec. III-C: a portfolio
 // ranks and masks the same weights at growing sparsity; Sec. III-D Module 4: all layers
-// pruned "in a single batch operation").
+// pruned by one operation).
 //
 // The variants' kept sets are nested - a weight kept at a cut is kept at every smaller
 // cut - so the zero-kernel / zero-channel analysis of Module 2 needs one number per

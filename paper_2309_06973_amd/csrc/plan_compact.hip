@@ -486,7 +486,7 @@ struct RectVariant {
 };
 
 // The rebuild of all K variants of a portfolio from the dense arena in one read of it
-// (Algorithm 2 for the whole portfolio; Sec. III-D Module 4's single batch operation).
+// (Algorithm 2 for the whole portfolio; Sec. III-D Module 4: all channels in one operation).
 // One block per source rectangle - band_rows filters times chunk_ch whole channels, at
 // most RECT_ELEMS floats.  All threads stage the rectangle in LDS with 16-byte loads
 // while the first K threads fetch what each variant keeps of it (rows [row_begin,

@@ -141,6 +141,7 @@ EXPORTS = {
     "shifter_propagate_groups_fixpoint": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)],
+    "shifter_set_select_grid": [C.c_void_p, C.c_uint32],
     "shifter_fixpoint_status": [C.c_void_p, C.c_void_p, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)],
     "shifter_prune_fused_result": [C.c_void_p, C.POINTER(Threshold), C.POINTER(C.c_int)],
     "shifter_prune_fused_batch": [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_uint64),
@@ -474,6 +475,10 @@ def shifter_propagate_groups_fixpoint(ctx: Context, model: Model, d_kernel_nz, f
         _ptr(d_index_map), _ptr(d_keep), _ptr(d_new_width), h, C.byref(rounds)),
         ctx.handle, allow=(SHIFTER_WARN_COLLAPSE,))
     return rc, list(h), int(rounds.value)
+
+
+def shifter_set_select_grid(ctx: Context, blocks: int) -> None:
+    _check(load_library().shifter_set_select_grid(ctx.handle, blocks), ctx.handle)
 
 
 def shifter_fixpoint_status(ctx: Context, model: Model):

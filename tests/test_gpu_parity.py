@@ -242,6 +242,50 @@ def test_in_place_mask_and_determinism():
         pl.close()
 
 
+def test_same_bytes_under_other_launch_shapes():
+    """The whole step under other launch geometries of the multi-pass select (1, 3, 257
+    blocks and the default) and through the single-pass selection, whose candidate lists
+    fill in whatever order the blocks happen to run: every output is the same bytes."""
+    spec, w, v = synth.generate_config(3)
+    ps = portfolio_counts(3, spec)
+    w_ties = w.copy()
+    w_ties[::7] = w_ties[3]                   # many equal magnitudes around some thresholds
+    for arena in (w, w_ties):
+        outs = []
+        for path, grid in ((1, 1), (1, 3), (1, 257), (1, None), (0, None), (0, None)):
+            pl = Pipeline(spec, arena, v)
+            try:
+                pl.enable_batch(len(ps))
+                S.shifter_set_select_path(pl.ctx, path)
+                if grid:
+                    S.shifter_set_select_grid(pl.ctx, grid)
+                recs, (rc, ot, ov, ew, ev) = pl.step(ps)
+                torch.cuda.synchronize()
+                got = [pl.d_thr[:len(ps) * S.THRESHOLD_BYTES], pl.b_out_alive, pl.b_in_alive, pl.b_keep,
+                       pl.b_new_width]
+                n, ext = spec.n_prunable, pl.model.info.w_extent
+                for k in range(len(ps)):                # strides pad the arenas: compare what is defined
+                    got.append(pl.b_mask[k * pl.m_stride:k * pl.m_stride + n])
+                    got.append(pl.b_w_sparse[k * pl.w_stride:k * pl.w_stride + ext])
+                got = [x.cpu().numpy().view(np.uint8).copy() for x in got]
+                for k in range(len(ps)):
+                    got.append(bits(pl.b_w_out[k * pl.cap_w:k * pl.cap_w + ew[k]].cpu().numpy()).copy())
+                    got.append(bits(pl.b_vecs_out[k * pl.cap_v:k * pl.cap_v + ev[k]].cpu().numpy()).copy())
+                outs.append(got)
+            finally:
+                pl.close()
+        for other in outs[1:]:
+            assert len(other) == len(outs[0])
+            for x, y in zip(outs[0], other):
+                assert np.array_equal(x, y)
+    with pytest.raises(S.ShifterError):
+        pl = Pipeline(spec, w, v)
+        try:
+            S.shifter_set_select_grid(pl.ctx, 0)
+        finally:
+            pl.close()
+
+
 def test_errors_on_device():
     spec, w, v = synth.generate_config(1)
     w = w.copy()

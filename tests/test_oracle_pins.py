@@ -471,3 +471,11 @@ def test_fast_baseline_equals_the_oracle():
         assert np.array_equal(nw, ref.plan.new_width)
         assert np.array_equal(cw.view(np.uint32), ref.compacted.w.view(np.uint32))
         assert np.array_equal(cv.view(np.uint32), ref.compacted.v.view(np.uint32))
+        # the threaded form of the same program, with slabs small enough to split tensors
+        ws, mask, nw, cw, cv = FB.prune_and_compact_fast_mt(w, v, spec.tensors, spec.vecs,
+                                                            spec.groups, p, threads=3, slab=1000)
+        assert np.array_equal(ws.view(np.uint32), ref.w_sparse.view(np.uint32))
+        assert np.array_equal(mask, ref.mask)
+        assert np.array_equal(nw, ref.plan.new_width)
+        assert np.array_equal(cw.view(np.uint32), ref.compacted.w.view(np.uint32))
+        assert np.array_equal(cv.view(np.uint32), ref.compacted.v.view(np.uint32))
