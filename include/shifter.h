@@ -424,7 +424,16 @@ int shifter_fold_bn(shifter_ctx* ctx, const shifter_model* model,
  *     last block of the last segment; an empty input gives the 5-byte stream
  *     01 00 00 FF FF;
  *   - side information, not part of the stream: seg_off, and per sub-chunk a uint16: its
- *     token bits if coded, 0xFFFF if stored (all 0 when the chunk is one stored block).
+ *     token bits if coded, 0xFFFF if stored (all 0 when the chunk is one stored block);
+ *   - a mark per sub-chunk (uint64), with which four lanes decode a coded sub-chunk of n
+ *     bytes side by side: for q = 1, 2, 3 let B_q = min(128 q, n), o_q the offset of the
+ *     first literal token at or after B_q (n if none) and b_q the bits of all tokens
+ *     before that literal (a run's matches go with the literal that starts it; all token
+ *     bits if none), b_0 = 0; the mark is the sum over q of
+ *     ((b_q - b_(q-1)) | (o_q - B_q) << 11) << 20 (q - 1).  Lane q decodes bits
+ *     [b_q, b_(q+1)) into bytes [o_q, o_(q+1)).  Stored and empty sub-chunks, and chunks
+ *     stored as one block, have mark 0.  Marks take 8 bytes per 512 bytes of input and the
+ *     token bits 2: together 2 % of the input, beside the stream.
  * The output is a deterministic function of the input.
  *
  * shifter_codec_layout   sizes for n_bytes of input: chunks (at least 1), bytes of
@@ -437,31 +446,44 @@ int shifter_fold_bn(shifter_ctx* ctx, const shifter_model* model,
  *   d_seg_off            device, n_chunks + 1 uint64; the last entry is the stream's size
  *   d_sub_bits           device, n_chunks * (CHUNK / SUB) uint16: the per-sub-chunk side
  *                        information
+ *   d_sub_marks          device, n_chunks * (CHUNK / SUB) uint64: the per-sub-chunk marks
  *   h_stream_bytes       host or NULL.  Non-NULL: the call waits for the stream and stores
  *                        the stream's size; returns SHIFTER_ERR_CAPACITY (size still
  *                        stored, nothing written to d_stream) when stream_cap is too small.
- *                        NULL: the call still waits once in the middle (for its first
- *                        pass), then returns with the rest enqueued
+ *                        NULL: kernels are enqueued and nothing is waited for (the size is
+ *                        the last entry of d_seg_off, and shifter_codec_status has it)
  * shifter_inflate        decodes a stream made by shifter_deflate, given its side
- *                        information, into n_bytes at d_out (device, 16-byte aligned).
- *                        Always waits; SHIFTER_ERR_INVALID_ARG with "bad stream" when the
- *                        stream, the offsets or the side information do not fit together
- *                        (sizes, block headers and token set are checked; all accesses
- *                        stay inside the buffers up to the 4-byte granule that holds the
- *                        stream's last byte; d_out is then unspecified).  DEFLATE carries
- *                        no checksum: a damaged literal that still parses is not found.
+ *                        information and marks, into n_bytes at d_out (device, 16-byte
+ *                        aligned).  stream_bytes: the bytes readable at d_stream, at least
+ *                        the stream's size (which is the last entry of d_seg_off).  wait != 0: waits, and returns SHIFTER_ERR_INVALID_ARG
+ *                        with "bad stream" when the stream, the offsets, the side
+ *                        information or the marks do not fit together (sizes, block
+ *                        headers, token set and every lane's range are checked; all
+ *                        accesses stay inside the buffers up to the 4-byte granule that
+ *                        holds the stream's last byte; d_out is then unspecified).
+ *                        wait = 0: kernels are enqueued and nothing is waited for; whether
+ *                        the stream was bad is then asked of shifter_codec_status.
+ *                        DEFLATE carries no checksum: a damaged literal that still parses
+ *                        is not found.
+ * shifter_codec_status   what the context's last codec call reported, once the caller has
+ *                        waited for the stream: the stream's size (deflate) and whether
+ *                        the stream was bad (inflate) or did not fit (deflate); either
+ *                        pointer may be NULL.
  * The codec calls need no model.  They keep chunk lists of 8 bytes per chunk of device
- * memory in the context, allocated when an input with more chunks than before comes. */
+ * memory in the context, allocated when an input with more chunks than before comes (so
+ * a call recorded into a HIP graph must follow an eager one of at least that size). */
 #define SHIFTER_CODEC_CHUNK 32768u
 #define SHIFTER_CODEC_SUB 512u
 int shifter_codec_layout(uint64_t n_bytes, uint64_t* h_n_chunks, uint64_t* h_work_bytes,
                          uint64_t* h_stream_bound);
 int shifter_deflate(shifter_ctx* ctx, const void* d_in, uint64_t n_bytes, void* d_work,
                     uint64_t work_bytes, uint8_t* d_stream, uint64_t stream_cap,
-                    uint64_t* d_seg_off, uint16_t* d_sub_bits, uint64_t* h_stream_bytes);
+                    uint64_t* d_seg_off, uint16_t* d_sub_bits, uint64_t* d_sub_marks,
+                    uint64_t* h_stream_bytes);
 int shifter_inflate(shifter_ctx* ctx, const uint8_t* d_stream, uint64_t stream_bytes,
-                    const uint64_t* d_seg_off, const uint16_t* d_sub_bits, uint64_t n_bytes,
-                    void* d_out);
+                    const uint64_t* d_seg_off, const uint16_t* d_sub_bits,
+                    const uint64_t* d_sub_marks, uint64_t n_bytes, void* d_out, int wait);
+int shifter_codec_status(shifter_ctx* ctx, uint64_t* h_stream_bytes, uint32_t* h_bad);
 
 /* Module 4, Model Pruner (Algorithm 2, Sec. III-D): every layer rebuilt without its
  * prunable channels.  For tensor t with out-group A, in-group B, m = in_mult:

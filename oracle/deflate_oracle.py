@@ -36,12 +36,22 @@ because the zero weights of sparse models repeat.  Two things are defined here:
     input is the single segment 01 00 00 FF FF;
   - side information for parallel decoding (not part of the DEFLATE stream): the byte
     offset of every segment, and per sub-chunk the number of token bits if it is coded,
-    0xFFFF if it is stored (all 0 when the whole chunk is one stored block).
+    0xFFFF if it is stored (all 0 when the whole chunk is one stored block);
+  - more side information, so that four decoders can share a coded sub-chunk of n bytes
+    (``quarter_marks``): for q = 1, 2, 3 let B_q = min(128 q, n), o_q the offset of the first
+    literal token at or after B_q (n if there is none) and b_q the bits of all tokens
+    before that literal (a run's matches go with the literal that starts it; all the
+    sub-chunk's token bits if there is none), b_0 = 0.  The mark of the sub-chunk is the
+    integer sum over q of ((b_q - b_(q-1)) + ((o_q - B_q) << 11)) << (20 (q - 1)); stored
+    and empty sub-chunks, and chunks that are one stored block, have mark 0.  Decoder q
+    starts at bit b_q and offset o_q and stops at b_(q+1), o_(q+1).
 
-Both are pinned by tests that do not go through them: ``inflate`` against the zlib
+All are pinned by tests that do not go through them: ``inflate`` against the zlib
 library on streams of every block type and against streams assembled by hand from the
 RFC's tables; ``deflate_runs`` by inflating its output with zlib, by closed forms for
-its sizes, and by hand-assembled expected streams.  Neither is "parity unpinned".
+its sizes, and by hand-assembled expected streams; ``quarter_marks`` by hand-worked
+marks, and by decoding every quarter of the encoder's streams on its own, from its mark
+alone, with the decoder's primitives.  None is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -51,6 +61,7 @@ CHUNK = 32768
 SUB = 512
 STORED_MARGIN = 48
 STORED_MARK = 0xFFFF
+QUARTER = 128                 # bytes of a sub-chunk per decoder
 
 # RFC 1951 section 3.2.5: base length and number of extra bits of length codes 257..285
 LENGTH_BASE = [3, 4, 5, 6, 7, 8, 9, 10, 11, 13, 15, 17, 19, 23, 27, 31, 35, 43, 51, 59, 67, 83,
@@ -331,3 +342,36 @@ def deflate_runs(data: bytes) -> Tuple[bytes, List[int], List[int]]:
         seg_off.append(len(stream))
         side += side_here
     return bytes(stream), seg_off, side
+
+
+def quarter_marks(sub: bytes) -> int:
+    """The mark of a coded sub-chunk: where the decoders of its second, third and fourth
+    128 bytes start (see the module's header)."""
+    n = len(sub)
+    lits, off, bit = [], 0, 0                    # (offset, bits before it) of every literal token
+    for kind, val in tokenize_sub(sub):
+        if kind == 0:
+            lits.append((off, bit))
+            off += 1
+        else:
+            off += val
+        bit += token_bits([(kind, val)])
+    mark, b_prev = 0, 0
+    for q in (1, 2, 3):
+        bound = min(QUARTER * q, n)
+        o_q, b_q = next(((o, b) for o, b in lits if o >= bound), (n, bit))
+        mark |= ((b_q - b_prev) | ((o_q - bound) << 11)) << (20 * (q - 1))
+        b_prev = b_q
+    return mark
+
+
+def deflate_marks(data: bytes, side: List[int]) -> List[int]:
+    """Marks of every sub-chunk of ``data``, given the side information ``deflate_runs``
+    returned for it."""
+    nsub = CHUNK // SUB
+    marks = []
+    for k, v in enumerate(side):
+        c, s = divmod(k, nsub)
+        sub = data[c * CHUNK + s * SUB:min(c * CHUNK + (s + 1) * SUB, (c + 1) * CHUNK)]
+        marks.append(quarter_marks(sub) if v not in (0, STORED_MARK) else 0)
+    return marks

@@ -87,10 +87,6 @@ extern "C" const char* shifter_last_error(const shifter_ctx* ctx) {
 }
 
 static void destroy_codec_objects(shifter_ctx* c) {
-    for (hipStream_t st : c->codec_aux)
-        if (st) { (void)hipStreamSynchronize(st); (void)hipStreamDestroy(st); }
-    for (hipEvent_t ev : {c->codec_ev, c->codec_fork, c->codec_join[0], c->codec_join[1]})
-        if (ev) (void)hipEventDestroy(ev);
     if (c->d_codec) (void)hipFree(c->d_codec);
     if (c->h_codec) (void)hipHostFree(c->h_codec);
     if (c->d_codec_list) (void)hipFree(c->d_codec_list);
@@ -124,20 +120,20 @@ extern "C" int shifter_create(shifter_ctx** out, int device, void* hip_stream) {
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, device) == hipSuccess && prop.multiProcessorCount > 0)
         c->hist_grid = (uint32_t)prop.multiProcessorCount * 8u;
-    // result words of the codec calls (stream size, status), device and pinned host copy
+    // result words of the codec calls (stream size, status): on the device, and a pinned
+    // mirror the last kernel of a call writes
+    void* mirror_dev = nullptr;
     if (hipMalloc(reinterpret_cast<void**>(&c->d_codec), 4 * sizeof(uint64_t)) != hipSuccess ||
-        hipHostMalloc(reinterpret_cast<void**>(&c->h_codec), 4 * sizeof(uint64_t), hipHostMallocDefault) != hipSuccess ||
-        hipEventCreateWithFlags(&c->codec_ev, hipEventDisableTiming) != hipSuccess ||
-        hipEventCreateWithFlags(&c->codec_fork, hipEventDisableTiming) != hipSuccess ||
-        hipEventCreateWithFlags(&c->codec_join[0], hipEventDisableTiming) != hipSuccess ||
-        hipEventCreateWithFlags(&c->codec_join[1], hipEventDisableTiming) != hipSuccess ||
-        hipStreamCreateWithFlags(&c->codec_aux[0], hipStreamNonBlocking) != hipSuccess ||
-        hipStreamCreateWithFlags(&c->codec_aux[1], hipStreamNonBlocking) != hipSuccess) {
+        hipHostMalloc(reinterpret_cast<void**>(&c->h_codec), 4 * sizeof(uint64_t),
+                      hipHostMallocMapped | hipHostMallocCoherent) != hipSuccess ||
+        hipHostGetDevicePointer(&mirror_dev, c->h_codec, 0) != hipSuccess) {
         (void)hipGetLastError();
         destroy_codec_objects(c);
         delete c;
         return fail(nullptr, SHIFTER_ERR_OOM, "shifter_create: allocation failed");
     }
+    c->dev_codec_mirror = static_cast<uint64_t*>(mirror_dev);
+    memset(c->h_codec, 0, 4 * sizeof(uint64_t));
     *out = c;
     return SHIFTER_OK;
 }
@@ -1567,24 +1563,25 @@ static int codec_enter(shifter_ctx* ctx, const char* fn) {
     return SHIFTER_OK;
 }
 
+// Waits for the stream and reads what the call's last kernel wrote to the pinned mirror.
 static int codec_result(shifter_ctx* ctx, uint64_t* total, uint64_t* status) {
-    HIP_TRY(ctx, hipMemcpyAsync(ctx->h_codec, ctx->d_codec, 2 * sizeof(uint64_t), hipMemcpyDeviceToHost,
-                                ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
-    *total = ctx->h_codec[0];
-    *status = ctx->h_codec[1];
+    const volatile uint64_t* mirror = ctx->h_codec;
+    *total = mirror[0];
+    *status = mirror[1];
     return SHIFTER_OK;
 }
 
 extern "C" int shifter_deflate(shifter_ctx* ctx, const void* d_in, uint64_t n_bytes, void* d_work,
                                uint64_t work_bytes, uint8_t* d_stream, uint64_t stream_cap,
-                               uint64_t* d_seg_off, uint16_t* d_sub_bits, uint64_t* h_stream_bytes) {
+                               uint64_t* d_seg_off, uint16_t* d_sub_bits, uint64_t* d_sub_marks,
+                               uint64_t* h_stream_bytes) {
     int rc = codec_enter(ctx, "deflate");
     if (rc) return rc;
-    if ((!d_in && n_bytes) || !d_work || !d_stream || !d_seg_off || !d_sub_bits)
+    if ((!d_in && n_bytes) || !d_work || !d_stream || !d_seg_off || !d_sub_bits || !d_sub_marks)
         return fail(ctx, SHIFTER_ERR_INVALID_ARG, "deflate: NULL pointer argument");
     if (misaligned(d_in, 16) || misaligned(d_work, 256) || misaligned(d_stream, 16) ||
-        misaligned(d_seg_off, 8) || misaligned(d_sub_bits, 2))
+        misaligned(d_seg_off, 8) || misaligned(d_sub_bits, 2) || misaligned(d_sub_marks, 8))
         return fail(ctx, SHIFTER_ERR_INVALID_ARG,
                     "deflate: input and stream must be 16-byte aligned, the workspace 256-byte aligned");
     const uint64_t n_chunks = codec_chunks(n_bytes);
@@ -1595,7 +1592,7 @@ extern "C" int shifter_deflate(shifter_ctx* ctx, const void* d_in, uint64_t n_by
                     "deflate: workspace too small, needs " + std::to_string(codec_work_bytes(n_chunks)) + " bytes");
     HIP_TRY(ctx, (hipError_t)launch_deflate(ctx, static_cast<const uint8_t*>(d_in), n_bytes, (uint32_t)n_chunks,
                                             static_cast<uint8_t*>(d_work), d_stream, stream_cap, d_seg_off,
-                                            d_sub_bits));
+                                            d_sub_bits, d_sub_marks));
     if ((rc = after_launch(ctx, "deflate"))) return rc;
     if (!h_stream_bytes) return SHIFTER_OK;
     uint64_t total, status;
@@ -1610,27 +1607,36 @@ extern "C" int shifter_deflate(shifter_ctx* ctx, const void* d_in, uint64_t n_by
 
 extern "C" int shifter_inflate(shifter_ctx* ctx, const uint8_t* d_stream, uint64_t stream_bytes,
                                const uint64_t* d_seg_off, const uint16_t* d_sub_bits,
-                               uint64_t n_bytes, void* d_out) {
+                               const uint64_t* d_sub_marks, uint64_t n_bytes, void* d_out, int wait) {
     int rc = codec_enter(ctx, "inflate");
     if (rc) return rc;
-    if (!d_stream || !d_seg_off || !d_sub_bits || (!d_out && n_bytes))
+    if (!d_stream || !d_seg_off || !d_sub_bits || !d_sub_marks || (!d_out && n_bytes))
         return fail(ctx, SHIFTER_ERR_INVALID_ARG, "inflate: NULL pointer argument");
     if (misaligned(d_stream, 16) || misaligned(d_out, 16) || misaligned(d_seg_off, 8) ||
-        misaligned(d_sub_bits, 2))
+        misaligned(d_sub_bits, 2) || misaligned(d_sub_marks, 8))
         return fail(ctx, SHIFTER_ERR_INVALID_ARG, "inflate: stream and output must be 16-byte aligned");
     const uint64_t n_chunks = codec_chunks(n_bytes);
     if (n_chunks >= (1ull << 31))
         return fail(ctx, SHIFTER_ERR_INVALID_ARG, "inflate: output too large (2^31 chunks or more)");
     if (stream_bytes < 5u * n_chunks)
         return fail(ctx, SHIFTER_ERR_INVALID_ARG, "inflate: bad stream (shorter than its segments' headers)");
-    HIP_TRY(ctx, (hipError_t)launch_inflate(ctx, d_stream, stream_bytes, d_seg_off, d_sub_bits, n_bytes,
-                                            (uint32_t)n_chunks, static_cast<uint8_t*>(d_out)));
+    HIP_TRY(ctx, (hipError_t)launch_inflate(ctx, d_stream, stream_bytes, d_seg_off, d_sub_bits, d_sub_marks,
+                                            n_bytes, (uint32_t)n_chunks, static_cast<uint8_t*>(d_out)));
     if ((rc = after_launch(ctx, "inflate"))) return rc;
+    if (!wait) return SHIFTER_OK;
     uint64_t total, status;
     if ((rc = codec_result(ctx, &total, &status))) return rc;
     if (status)
         return fail(ctx, SHIFTER_ERR_INVALID_ARG,
                     "inflate: bad stream (segments, offsets and bit counts do not fit together)");
+    return SHIFTER_OK;
+}
+
+extern "C" int shifter_codec_status(shifter_ctx* ctx, uint64_t* h_stream_bytes, uint32_t* h_bad) {
+    if (!ctx) return fail(nullptr, SHIFTER_ERR_INVALID_ARG, "codec_status: ctx is NULL");
+    const volatile uint64_t* mirror = ctx->h_codec;
+    if (h_stream_bytes) *h_stream_bytes = mirror[0];
+    if (h_bad) *h_bad = mirror[1] != 0;
     return SHIFTER_OK;
 }
 

@@ -302,12 +302,10 @@ struct shifter_ctx {
     int last_path = 0;               // 1: single pass decided; 2: multi-pass select ran
     shifter_threshold last_record{};  // record of the last shifter_prune_fused that waited
     uint64_t* d_codec = nullptr;      // codec: [0] stream bytes, [1] status bits, [2], [3] list lengths (device)
-    uint64_t* h_codec = nullptr;      // pinned copy of the four
-    uint32_t* d_codec_list = nullptr; // decoder: chunk lists of the medium and the large instance
+    uint64_t* h_codec = nullptr;      // pinned mirror of the first two, written by the call's last kernel
+    uint64_t* dev_codec_mirror = nullptr;   //   its device address
+    uint32_t* d_codec_list = nullptr; // chunk lists of the instances that take the longer segments
     uint64_t codec_list_cap = 0;      //   its capacity in entries
-    hipEvent_t codec_ev = nullptr;    //   its two lengths have arrived on the host
-    hipStream_t codec_aux[2] = {nullptr, nullptr};   // decoder: streams of the two larger instances
-    hipEvent_t codec_fork = nullptr, codec_join[2] = {nullptr, nullptr};
     // a shifter_prune_fused call whose outcome has not been collected yet
     struct Pending {
         bool active = false;
@@ -451,10 +449,10 @@ void launch_fix_widths(shifter_ctx* ctx, const shifter_model* m, const uint32_t*
 inline uint64_t codec_slots_offset(uint64_t n_chunks) { return (n_chunks * 4u + 255u) & ~(uint64_t)255u; }
 int launch_deflate(shifter_ctx* ctx, const uint8_t* d_in, uint64_t n_bytes, uint32_t n_chunks,
                    uint8_t* d_work, uint8_t* d_stream, uint64_t stream_cap, uint64_t* d_seg_off,
-                   uint16_t* d_sub_bits);
+                   uint16_t* d_sub_bits, uint64_t* d_sub_marks);
 int launch_inflate(shifter_ctx* ctx, const uint8_t* d_stream, uint64_t stream_bytes,
-                   const uint64_t* d_seg_off, const uint16_t* d_sub_bits, uint64_t n_bytes,
-                   uint32_t n_chunks, uint8_t* d_out);
+                   const uint64_t* d_seg_off, const uint16_t* d_sub_bits, const uint64_t* d_sub_marks,
+                   uint64_t n_bytes, uint32_t n_chunks, uint8_t* d_out);
 void launch_fold(shifter_ctx* ctx, const shifter_model* m, const float* d_w, const float* d_vecs,
                  float eps, float* d_w_out, float* d_bias_out);
 

@@ -260,9 +260,11 @@ def deflate_portfolio(pl: "Pipeline", elems_w: Sequence[int], elems_v: Sequence[
 
 
 class Package:
-    """One deflated buffer: the DEFLATE stream and the side information for inflating it."""
-    def __init__(self, stream, seg_off, sub_bits, n_bytes: int):
+    """One deflated buffer: the DEFLATE stream, and the side information and marks for
+    inflating it in parallel."""
+    def __init__(self, stream, seg_off, sub_bits, n_bytes: int, sub_marks):
         self.stream, self.seg_off, self.sub_bits, self.n_bytes = stream, seg_off, sub_bits, n_bytes
+        self.sub_marks = sub_marks
 
     @property
     def stream_bytes(self) -> int:
@@ -285,7 +287,7 @@ class Codec:
             S.shifter_destroy(self.ctx)
         self.ctx = None
 
-    def deflate(self, t, stream=None) -> Package:
+    def deflate(self, t, stream=None, sync: bool = True) -> Package:
         """Deflates the bytes of the contiguous device tensor ``t``.  ``stream``: a uint8
         buffer to write into (default: one of the largest possible size); the package's
         stream is the used part of it."""
@@ -298,13 +300,16 @@ class Codec:
         seg_off = torch.empty(n_chunks + 1, dtype=torch.int64, device=self.dev)
         sub_bits = torch.empty(n_chunks * (S.SHIFTER_CODEC_CHUNK // S.SHIFTER_CODEC_SUB),
                                dtype=torch.int16, device=self.dev)
+        sub_marks = torch.empty(sub_bits.numel(), dtype=torch.int64, device=self.dev)
         total = S.shifter_deflate(self.ctx, t if n_bytes else None, n_bytes, self.work, stream,
-                                  seg_off, sub_bits)
-        return Package(stream[:total], seg_off, sub_bits, n_bytes)
+                                  seg_off, sub_bits, sub_marks, sync)
+        return Package(stream[:total] if sync else stream, seg_off, sub_bits, n_bytes, sub_marks)
 
-    def inflate(self, p: Package, out=None):
+    def inflate(self, p: Package, out=None, sync: bool = True, stream_bytes=None):
+        """``stream_bytes``: the stream's size when the package's stream tensor is a larger
+        buffer (a package made without waiting)."""
         if out is None:
             out = torch.empty(max(p.n_bytes, 16), dtype=torch.uint8, device=self.dev)
-        S.shifter_inflate(self.ctx, p.stream, p.stream_bytes, p.seg_off, p.sub_bits, p.n_bytes,
-                          out)
+        S.shifter_inflate(self.ctx, p.stream, p.stream_bytes if stream_bytes is None else stream_bytes,
+                          p.seg_off, p.sub_bits, p.sub_marks, p.n_bytes, out, sync)
         return out

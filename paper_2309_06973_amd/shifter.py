@@ -108,9 +108,10 @@ EXPORTS = {
     "shifter_codec_layout": [C.c_uint64, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64),
                              C.POINTER(C.c_uint64)],
     "shifter_deflate": [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64, C.c_void_p,
-                        C.c_uint64, C.c_void_p, C.c_void_p, C.POINTER(C.c_uint64)],
-    "shifter_inflate": [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_uint64,
-                        C.c_void_p],
+                        C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_uint64)],
+    "shifter_inflate": [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p,
+                        C.c_uint64, C.c_void_p, C.c_int],
+    "shifter_codec_status": [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)],
     "shifter_apply_mask": [C.c_void_p] * 8,
     "shifter_dead_channel_scan": [C.c_void_p] * 5,
     "shifter_propagate_groups": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
@@ -387,23 +388,30 @@ def shifter_codec_layout(n_bytes: int):
 
 
 def shifter_deflate(ctx: Context, d_in, n_bytes: int, d_work, d_stream, d_seg_off, d_sub_bits,
-                    sync: bool = True) -> Optional[int]:
+                    d_sub_marks, sync: bool = True) -> Optional[int]:
     """Capacities are the byte sizes of d_work and d_stream.  Returns the stream's size when
     sync (raises ShifterError with code SHIFTER_ERR_CAPACITY if it does not fit)."""
     total = C.c_uint64()
     nbytes = lambda t: t.numel() * t.element_size()
     _check(load_library().shifter_deflate(
         ctx.handle, _ptr(d_in), n_bytes, _ptr(d_work), nbytes(d_work), _ptr(d_stream),
-        nbytes(d_stream), _ptr(d_seg_off), _ptr(d_sub_bits), C.byref(total) if sync else None),
-        ctx.handle)
+        nbytes(d_stream), _ptr(d_seg_off), _ptr(d_sub_bits), _ptr(d_sub_marks),
+        C.byref(total) if sync else None), ctx.handle)
     return int(total.value) if sync else None
 
 
-def shifter_inflate(ctx: Context, d_stream, stream_bytes: int, d_seg_off, d_sub_bits,
-                    n_bytes: int, d_out) -> None:
+def shifter_inflate(ctx: Context, d_stream, stream_bytes: int, d_seg_off, d_sub_bits, d_sub_marks,
+                    n_bytes: int, d_out, sync: bool = True) -> None:
     _check(load_library().shifter_inflate(ctx.handle, _ptr(d_stream), stream_bytes,
-                                          _ptr(d_seg_off), _ptr(d_sub_bits), n_bytes,
-                                          _ptr(d_out)), ctx.handle)
+                                          _ptr(d_seg_off), _ptr(d_sub_bits), _ptr(d_sub_marks),
+                                          n_bytes, _ptr(d_out), 1 if sync else 0), ctx.handle)
+
+
+def shifter_codec_status(ctx: Context):
+    """(stream bytes, bad) of the context's last codec call, once its stream has been waited for."""
+    total, bad = C.c_uint64(), C.c_uint32()
+    _check(load_library().shifter_codec_status(ctx.handle, C.byref(total), C.byref(bad)), ctx.handle)
+    return int(total.value), bool(bad.value)
 
 
 def shifter_portfolio_begin(ctx: Context, model: Model, d_w, d_vecs, n_prune: Sequence[int],

@@ -1,8 +1,8 @@
 """GPU parity of the portfolio codec (Sec. III-E, Modules 7 and 8) through the C ABI.
 
 The encoder's output is a deterministic function of the input, so the stream, the segment
-offsets and the token-bit counts are compared bit for bit with the oracle's encoder; the
-stream is also inflated by zlib (an independent RFC 1951 decoder), and the library's
+offsets, the token-bit counts and the quarter marks are compared bit for bit with the
+oracle's encoder; the stream is also inflated by zlib (an independent RFC 1951 decoder), and the library's
 inflate must give the input back."""
 import zlib
 
@@ -53,6 +53,8 @@ def check(codec, data: bytes, oracle_encoder=True):
         ref_stream, ref_off, ref_bits = D.deflate_runs(data)
         assert seg_off == ref_off and sub_bits == ref_bits
         assert stream == ref_stream
+        marks = pkg.sub_marks.cpu().numpy().view(np.uint64).tolist()
+        assert marks == D.deflate_marks(data, ref_bits)
     assert zinflate(stream) == data
     out = codec.inflate(pkg)
     torch.cuda.synchronize()
@@ -160,8 +162,11 @@ def test_codec_vgg16_sparse_and_dense_sampled_chunks():
             stream = pkg.stream.cpu().numpy().tobytes()
             seg_off = pkg.seg_off.cpu().numpy().tolist()
             n_chunks = len(seg_off) - 1
+            marks = pkg.sub_marks.cpu().numpy().view(np.uint64)
             for c in (0, 1, n_chunks // 2, n_chunks - 2, n_chunks - 1):
-                ref_stream, ref_off, _ = D.deflate_runs(data[c * C_:(c + 2) * C_])
+                ref_stream, ref_off, ref_bits = D.deflate_runs(data[c * C_:(c + 2) * C_])
+                assert marks[c * 64:(c + 1) * 64].tolist() == \
+                    D.deflate_marks(data[c * C_:(c + 2) * C_], ref_bits)[:64]
                 if c < n_chunks - 1:
                     assert stream[seg_off[c]:seg_off[c + 1]] == ref_stream[:ref_off[1]]
                 else:
@@ -197,23 +202,86 @@ def test_codec_statuses_and_reuse():
         bad_stream = pkg.stream.clone()
         bad_stream[0] |= 6                                          # reserved block type
         huge_bits = torch.full_like(pkg.sub_bits, -1)
+        # marks: a quarter that starts a bit late, one that starts a byte late, offsets out of
+        # order, bits beyond the sub-chunk's, the unused top bits, all ones
+        coded = int(torch.nonzero((pkg.sub_bits > 200) & (pkg.sub_bits != -1))[0])
+        bad_marks = []
+        for delta in (1, 1 << 11, 1 << 20, 0x7FF << 40, 1 << 60, -1 - int(pkg.sub_marks[coded])):
+            bm = pkg.sub_marks.clone()
+            bm[coded] += delta
+            bad_marks.append(bm)
+        bad_marks.append(torch.full_like(pkg.sub_marks, -1))
         from paper_2309_06973_amd.pipeline import Package
-        for broken in (Package(pkg.stream, pkg.seg_off, bad_bits, pkg.n_bytes),
-                       Package(pkg.stream, bad_off, pkg.sub_bits, pkg.n_bytes),
-                       Package(pkg.stream, pkg.seg_off, huge_bits, pkg.n_bytes),
-                       Package(pkg.stream, pkg.seg_off, pkg.sub_bits, pkg.n_bytes - S_ - 1),
-                       Package(bad_stream, pkg.seg_off, pkg.sub_bits, pkg.n_bytes)):
+        broken_pkgs = [Package(pkg.stream, pkg.seg_off, bad_bits, pkg.n_bytes, pkg.sub_marks),
+                       Package(pkg.stream, bad_off, pkg.sub_bits, pkg.n_bytes, pkg.sub_marks),
+                       Package(pkg.stream, pkg.seg_off, huge_bits, pkg.n_bytes, pkg.sub_marks),
+                       Package(pkg.stream, pkg.seg_off, pkg.sub_bits, pkg.n_bytes - S_ - 1, pkg.sub_marks),
+                       Package(bad_stream, pkg.seg_off, pkg.sub_bits, pkg.n_bytes, pkg.sub_marks)]
+        broken_pkgs += [Package(pkg.stream, pkg.seg_off, pkg.sub_bits, pkg.n_bytes, bm) for bm in bad_marks]
+        for broken in broken_pkgs:
             with pytest.raises(S.ShifterError) as e:
                 codec.inflate(broken)
             assert e.value.code == S.SHIFTER_ERR_INVALID_ARG and "bad stream" in str(e.value)
+            # the same without waiting: the status is asked for afterwards
+            codec.inflate(broken, sync=False)
+            torch.cuda.synchronize()
+            assert S.shifter_codec_status(codec.ctx)[1]
         out = codec.inflate(pkg)                                    # the good one still inflates
         assert out[:len(data)].cpu().numpy().tobytes() == data
+        codec.inflate(pkg, sync=False)
+        torch.cuda.synchronize()
+        assert not S.shifter_codec_status(codec.ctx)[1]
         # host-side argument checks
         with pytest.raises(S.ShifterError):
             S.shifter_deflate(codec.ctx, d_in, len(data), codec.work[:256], pkg.stream,
-                              pkg.seg_off, pkg.sub_bits)
+                              pkg.seg_off, pkg.sub_bits, pkg.sub_marks)
     finally:
         codec.close()
+
+
+def test_codec_calls_that_wait_for_nothing_replayed_from_a_graph():
+    """Deflate and inflate with nothing read back are kernels only: recorded into a HIP graph,
+    every replay gives the eager calls' bytes, on whatever the input buffer holds then."""
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        codec = Codec()
+        try:
+            datas = [sparse_floats(3 * C_ // 4 + 5 * C_, 0.9, 5), sparse_floats(3 * C_ // 4 + 5 * C_, 0.5, 6)]
+            d_in = to_dev(datas[0])
+            ref = [codec.deflate(to_dev(d)) for d in datas]           # eager, waiting: the reference
+            refs = [(p.stream.clone(), p.seg_off.clone(), p.sub_bits.clone(), p.sub_marks.clone()) for p in ref]
+            bound = S.shifter_codec_layout(len(datas[0]))[2]
+            buf = torch.zeros(bound, dtype=torch.uint8, device="cuda")
+            out = torch.zeros(len(datas[0]) + 16, dtype=torch.uint8, device="cuda")
+            pkg = codec.deflate(d_in, stream=buf, sync=False)         # eager, not waiting
+            stream.synchronize()
+            assert S.shifter_codec_status(codec.ctx) == (refs[0][0].numel(), False)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                S.shifter_deflate(codec.ctx, d_in, len(datas[0]), codec.work, buf, pkg.seg_off, pkg.sub_bits,
+                                  pkg.sub_marks, sync=False)
+            g2 = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g2, stream=stream):
+                codec.inflate(pkg, out=out, sync=False, stream_bytes=bound)
+            for rep in range(4):
+                k = rep & 1
+                d_in.copy_(to_dev(datas[k]))
+                buf.fill_(0x5a)
+                out.fill_(0x5a)
+                stream.synchronize()
+                graph.replay()
+                stream.synchronize()
+                size, bad = S.shifter_codec_status(codec.ctx)
+                assert (size, bad) == (refs[k][0].numel(), False)
+                assert torch.equal(buf[:size], refs[k][0]) and torch.equal(pkg.seg_off, refs[k][1])
+                assert torch.equal(pkg.sub_bits, refs[k][2]) and torch.equal(pkg.sub_marks, refs[k][3])
+                g2.replay()
+                stream.synchronize()
+                assert not S.shifter_codec_status(codec.ctx)[1]
+                assert out[:len(datas[k])].cpu().numpy().tobytes() == datas[k]
+                check(codec, datas[k][:9999])                           # eager work between the replays
+        finally:
+            codec.close()
 
 
 def test_portfolio_package_sorted_by_size_and_lossless():

@@ -174,6 +174,8 @@ def test_c5_single_sweep_fused(c5, capsys):
             ref_stream, ref_off, ref_side = DO.deflate_runs(raw[c * DO.CHUNK:(c + 2) * DO.CHUNK])
             side = pkg.sub_bits[c * 64:(c + 1) * 64].cpu().numpy().view(np.uint16).tolist()
             assert side == ref_side[:64]
+            marks = pkg.sub_marks[c * 64:(c + 1) * 64].cpu().numpy().view(np.uint64).tolist()
+            assert marks == DO.deflate_marks(raw[c * DO.CHUNK:(c + 2) * DO.CHUNK], ref_side)[:64]
             if c < n_chunks - 1:
                 assert stream[seg_off[c]:seg_off[c + 1]] == ref_stream[:ref_off[1]]
             else:

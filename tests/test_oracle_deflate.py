@@ -262,3 +262,118 @@ def test_planted_encoder_mistakes_are_caught(mistake, monkeypatch):
     except (zlib.error, AssertionError):
         ok = False
     assert not ok
+
+
+# ----------------------------------------------------------------------------- quarter marks
+def sub_bit_starts(side, sub_lens):
+    """Bit position, inside its segment, of the first token of every coded sub-chunk (the
+    layout rule of the segment written out once more, from the side information alone)."""
+    pos, in_block, starts = 0, False, []
+    for v, n in zip(side, sub_lens):
+        if n == 0:
+            starts.append(None)
+            continue
+        if v == D.STORED_MARK:
+            starts.append(None)
+            pos += (7 if in_block else 0) + 3
+            pos = (pos + 7) // 8 * 8 + 32 + 8 * n
+            in_block = False
+        else:
+            pos += 0 if in_block else 3
+            starts.append(pos)
+            pos += v
+            in_block = True
+    return starts
+
+
+def decode_quarter(seg: bytes, bit: int, bit_end: int, first_byte_known=None):
+    """Tokens from bit to bit_end with the decoder's own primitives: returns the bytes they
+    produce; the first token must be a literal."""
+    br = D._Bits(seg)
+    br.pos = bit
+    out = bytearray()
+    while br.pos < bit_end:
+        sym = D._symbol(br, D.FIXED_LIT)
+        if sym < 256:
+            out.append(sym)
+        else:
+            assert 257 <= sym <= 285 and out, "a quarter starts with a literal"
+            ln = D.LENGTH_BASE[sym - 257] + br.bits(D.LENGTH_EXTRA[sym - 257])
+            assert D._symbol(br, D.FIXED_DIST) == 0
+            out += bytes([out[-1]]) * ln
+    assert br.pos == bit_end
+    return bytes(out)
+
+
+def test_quarter_marks_by_hand():
+    f = lambda fields: sum((d | (o << 11)) << (20 * q) for q, (d, o) in enumerate(fields))
+    # 512 zeros: one literal and two matches, 39 bits, nothing starts after offset 0
+    assert D.quarter_marks(bytes(512)) == f([(39, 384), (0, 256), (0, 128)])
+    # 512 bytes without runs, all below 144: 8 bits each, a literal at every boundary
+    assert D.quarter_marks(bytes(i % 100 for i in range(512))) == f([(1024, 0)] * 3)
+    # ... all 9-bit literals
+    assert D.quarter_marks(bytes(200 + i % 50 for i in range(512))) == f([(1152, 0)] * 3)
+    # a run across the first boundary: 120 literals (8 bits), then 20 zeros from offset 120
+    # (literal 8 bits + length 19 = code 269 with 2 extra bits, 7 + 2 + 5 = 14 bits), then
+    # literals; the second decoder starts at offset 140, after 120 * 8 + 22 bits
+    sub = bytes(1 + i % 100 for i in range(120)) + bytes(20) + bytes(1 + i % 100 for i in range(372))
+    assert D.quarter_marks(sub) == f([(120 * 8 + 22, 12), ((256 - 140) * 8, 0), (1024, 0)])
+    # a short sub-chunk: 130 bytes, boundaries 128, 130, 130
+    sub = bytes(1 + i % 100 for i in range(130))
+    assert D.quarter_marks(sub) == f([(1024, 0), (16, 0), (0, 0)])
+    # 300 bytes ending in a run that covers two boundaries
+    sub = bytes(1 + i % 100 for i in range(100)) + bytes([7]) * 200
+    assert D.tokenize_sub(sub)[100:] == [(0, 7), (1, 199)]
+    # literal 7: 8 bits; length 199 = code 283 (base 195, 5 extra bits): 8 + 5 + 5 = 18 bits
+    assert D.quarter_marks(sub) == f([(100 * 8 + 26, 300 - 128), (0, 300 - 256), (0, 0)])
+
+
+def test_every_quarter_decodes_alone_from_its_mark():
+    nsub = D.CHUNK // D.SUB
+    checked = 0
+    for data in encoder_inputs():
+        stream, seg_off, side = D.deflate_runs(data)
+        marks = D.deflate_marks(data, side)
+        assert len(marks) == len(side)
+        for c in range(len(seg_off) - 1):
+            seg = stream[seg_off[c]:seg_off[c + 1]]
+            chunk = data[c * D.CHUNK:(c + 1) * D.CHUNK]
+            here = side[c * nsub:(c + 1) * nsub]
+            sub_lens = [len(chunk[s * D.SUB:(s + 1) * D.SUB]) for s in range(nsub)]
+            if not any(here):
+                assert not any(marks[c * nsub:(c + 1) * nsub])
+                continue
+            for s, (start, v, n) in enumerate(zip(sub_bit_starts(here, sub_lens), here, sub_lens)):
+                mark = marks[c * nsub + s]
+                if start is None:
+                    assert mark == 0
+                    continue
+                sub = chunk[s * D.SUB:(s + 1) * D.SUB]
+                bits, offs = [0], [0]
+                for q in (1, 2, 3):
+                    field = (mark >> (20 * (q - 1))) & 0xFFFFF
+                    bits.append(bits[-1] + (field & 0x7FF))
+                    offs.append(min(D.QUARTER * q, n) + (field >> 11))
+                bits.append(v)
+                offs.append(n)
+                assert mark >> 60 == 0 and offs == sorted(offs) and bits == sorted(bits)
+                for q in range(4):
+                    got = decode_quarter(seg, start + bits[q], start + bits[q + 1])
+                    assert got == sub[offs[q]:offs[q + 1]]
+                    # the first literal at or after the boundary, not a later one
+                    assert q == 0 or offs[q] == min(D.QUARTER * q, n) or \
+                        len(set(sub[min(D.QUARTER * q, n) - 1:offs[q]])) == 1
+                    checked += 1
+    assert checked > 2000
+
+
+def test_planted_mark_mistakes_are_caught(monkeypatch):
+    sub = bytes(1 + i % 100 for i in range(120)) + bytes(20) + bytes(1 + i % 100 for i in range(372))
+    good = D.quarter_marks(sub)
+    real = D.tokenize_sub
+    # matches counted with the wrong literal: the run's match left to the next decoder
+    monkeypatch.setattr(D, "token_bits", lambda toks: 0 if toks and toks[0][0] == 1 else
+                        8 * len(toks))
+    assert D.quarter_marks(sub) != good
+    monkeypatch.undo()
+    assert D.quarter_marks(sub) == good
