@@ -873,7 +873,8 @@ __device__ __forceinline__ void inflate_chunk(
 }
 
 template <uint32_t SEG_DW, uint32_t SEG_MIN>
-__global__ __launch_bounds__(CODEC_THREADS, 4) void inflate_chunk_kernel(
+__global__ __launch_bounds__(CODEC_THREADS, SEG_DW == CODEC_SEG_SMALL ? 4 : (SEG_DW == CODEC_SEG_MEDIUM ? 3 : 2))
+void inflate_chunk_kernel(
     const uint8_t* __restrict__ stream, uint64_t stream_bytes, const uint64_t* __restrict__ seg_off,
     const uint16_t* __restrict__ side, const uint64_t* __restrict__ marks, uint64_t n_bytes, uint32_t n_chunks,
     uint8_t* __restrict__ out, uint64_t* __restrict__ result, const uint32_t* __restrict__ list,
