@@ -8,7 +8,8 @@ HBM before the timed region starts.  Prints ONE JSON line: the headline workload
 the other full-size workloads of the target under "other_workloads".
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5|c5p|c4|c2|c3|c1]
-                  [--others c4,c5p | --others none] [--no-cpu-baseline] [--no-lean]
+                  [--others c4,c5p | --others none] [--no-cpu-baseline] [--cpu-sample]
+                  [--no-lean] [--codec-profile REPS]
 """
 import argparse
 import hashlib
@@ -44,12 +45,13 @@ def generated(c):
 
 
 def kernel_source_digest():
-    """Digest of the kernel sources: measured counter figures are only quoted while the
-    kernels are the ones they were taken on (api.hip holds host code only)."""
+    """Digest of the sources of the pass's kernels: measured counter figures are only quoted
+    while the kernels are the ones they were taken on (api.hip holds host code only;
+    codec.hip holds the codec's kernels, for which no counter figure is quoted)."""
     h = hashlib.sha256()
     d = os.path.join(ROOT, "paper_2309_06973_amd", "csrc")
     for name in sorted(os.listdir(d)):
-        if name.endswith((".hip", ".h")) and name != "api.hip":
+        if name.endswith((".hip", ".h")) and name not in ("api.hip", "codec.hip"):
             with open(os.path.join(d, name), "rb") as f:
                 h.update(name.encode() + b"\0" + f.read())
     return h.hexdigest()[:16]
@@ -346,6 +348,8 @@ def measure(name, steps, warmup, lean_run=True, cpu_leg=True):
         dec_ms = avg("inflate_chunk")
         moved = n_raw + pkg.stream_bytes           # bytes either direction has to move
         codec = {"raw_bytes": n_raw, "stream_bytes": pkg.stream_bytes,
+                 "side_information_bytes": pkg.sub_bits.numel() * 2 + pkg.sub_marks.numel() * 8
+                 + pkg.seg_off.numel() * 8,
                  "ratio": round(n_raw / pkg.stream_bytes, 3),
                  "round_trip_equal": bool(torch.equal(back[:n_raw].view(torch.int32),
                                                       raw.view(torch.int32))),
@@ -440,6 +444,37 @@ def measure(name, steps, warmup, lean_run=True, cpu_leg=True):
     return out, (spec, w, v, sparsities)
 
 
+def codec_profile(name, reps):
+    """For a kernel trace of the codec alone: deflates and inflates ONE buffer, the sparse
+    arena of the workload's first variant, `reps` times; prints its own JSON line."""
+    import torch
+    from paper_2309_06973_amd import shifter as S
+    from paper_2309_06973_amd import synth
+    from paper_2309_06973_amd.pipeline import Codec, Pipeline
+    c, sparsities, desc = WORKLOADS[name]
+    spec, w, v = generated(c)
+    s0 = (sparsities or synth.config_sparsities(c))[0 if sparsities else -1]
+    pl = Pipeline(spec, w, v, device=0)
+    pl.step([synth.prune_count(spec.n_prunable, s0)])
+    cd = Codec(device=0, ctx=pl.ctx)
+    raw = pl.d_w_sparse[:spec.w_elems]
+    n_raw = 4 * spec.w_elems
+    buf = torch.empty(S.shifter_codec_layout(n_raw)[2], dtype=torch.uint8, device=pl.dev)
+    pkg = cd.deflate(raw, stream=buf)
+    back = cd.inflate(pkg)
+    S.shifter_profile_enable(pl.ctx, True)
+    for _ in range(reps):
+        pkg = cd.deflate(raw, stream=buf)
+        cd.inflate(pkg, out=back)
+    cp = S.shifter_profile_read(pl.ctx)
+    ok = bool(torch.equal(back[:n_raw].view(torch.int32), raw.view(torch.int32)))
+    print(json.dumps({"workload": desc, "sparsity": s0, "raw_bytes": n_raw, "stream_bytes": pkg.stream_bytes,
+                      "side_information_bytes": pkg.sub_bits.numel() * 2 + pkg.sub_marks.numel() * 8
+                      + pkg.seg_off.numel() * 8, "round_trip_equal": ok, "reps": reps,
+                      "avg_us": {k: round(ms / n * 1e3, 1) for k, (n, ms) in cp.items()}}))
+    pl.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -456,6 +491,9 @@ def main():
     ap.add_argument("--no-lean", action="store_true",
                     help="skip the extra timings (portfolio without sparse arenas, liveness "
                          "fixpoint): for profiling runs")
+    ap.add_argument("--codec-profile", type=int, default=0, metavar="REPS",
+                    help="only deflate and inflate the workload's sparse arena REPS times (one "
+                         "input size; for a kernel trace of the codec)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: the library runs on one GPU only; --gpus must be 1 (the pass "
@@ -472,6 +510,10 @@ def main():
     if not os.path.exists(S._LIB_PATH):
         import __graft_entry__
         __graft_entry__.build()
+
+    if args.codec_profile:
+        codec_profile(args.workload, args.codec_profile)
+        return
 
     if args.others is None:
         others = ["c5p", "c4"] if args.workload == "c5" else []
