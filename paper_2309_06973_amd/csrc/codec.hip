@@ -512,38 +512,50 @@ __global__ __launch_bounds__(CODEC_THREADS) void deflate_chunk_kernel(
     }
 }
 
-// Byte offsets of the segments: exclusive prefix sums of their sizes (one block).
+// Byte offsets of the segments: exclusive prefix sums of their sizes (one block).  The
+// sizes of eight rounds of 1024 chunks are loaded together, then scanned round by round.
 __global__ __launch_bounds__(1024) void codec_scan_kernel(const uint32_t* __restrict__ seg_size,
                                                           uint32_t n_chunks,
                                                           uint64_t* __restrict__ seg_off,
                                                           uint64_t stream_cap,
                                                           uint64_t* __restrict__ result) {
-    __shared__ uint64_t s_wave[16];
-    __shared__ uint64_t s_carry;
+    __shared__ uint64_t s_wave[2][16];
     const uint32_t lane = threadIdx.x & 63u, wid = threadIdx.x >> 6;
-    if (threadIdx.x == 0) s_carry = 0;
-    __syncthreads();
-    for (uint32_t b0 = 0; b0 < n_chunks; b0 += 1024u) {
-        const uint32_t i = b0 + threadIdx.x;
-        const uint64_t v = i < n_chunks ? seg_size[i] : 0u;
-        unsigned long long x = v;
-        for (uint32_t d = 1; d < 64; d <<= 1) {
-            const unsigned long long y = __shfl_up(x, d, 64);
-            if (lane >= d) x += y;
+    constexpr uint32_t R = 8;
+    uint64_t carry = 0;                                 // the same in every thread
+    uint32_t flip = 0;
+    for (uint32_t b0 = 0; b0 < n_chunks; b0 += R * 1024u) {
+        uint32_t v[R];
+#pragma unroll
+        for (uint32_t u = 0; u < R; ++u) {
+            const uint32_t i = b0 + u * 1024u + threadIdx.x;
+            v[u] = i < n_chunks ? seg_size[i] : 0u;
         }
-        if (lane == 63u) s_wave[wid] = x;
-        __syncthreads();
-        uint64_t off = s_carry;
-        for (uint32_t k = 0; k < wid; ++k) off += s_wave[k];
-        if (i < n_chunks) seg_off[i] = off + x - v;
-        __syncthreads();
-        if (threadIdx.x == 1023u) s_carry = off + x;
-        __syncthreads();
+#pragma unroll
+        for (uint32_t u = 0; u < R; ++u) {
+            const uint32_t i = b0 + u * 1024u + threadIdx.x;
+            unsigned long long x = v[u];
+            for (uint32_t d = 1; d < 64; d <<= 1) {
+                const unsigned long long y = __shfl_up(x, d, 64);
+                if (lane >= d) x += y;
+            }
+            if (lane == 63u) s_wave[flip][wid] = x;
+            __syncthreads();                            // the other buffer is free again by now
+            uint64_t off = carry, total = 0;
+            for (uint32_t k = 0; k < 16u; ++k) {
+                const uint64_t w = s_wave[flip][k];
+                if (k < wid) off += w;
+                total += w;
+            }
+            if (i < n_chunks) seg_off[i] = off + x - v[u];
+            carry += total;
+            flip ^= 1u;
+        }
     }
     if (threadIdx.x == 0) {
-        seg_off[n_chunks] = s_carry;
-        result[0] = s_carry;
-        result[1] = s_carry > stream_cap ? CODEC_CAPACITY : 0u;
+        seg_off[n_chunks] = carry;
+        result[0] = carry;
+        result[1] = carry > stream_cap ? CODEC_CAPACITY : 0u;
     }
 }
 
@@ -680,12 +692,11 @@ __device__ __forceinline__ void inflate_chunk(
     const uint32_t* seg32 = reinterpret_cast<const uint32_t*>(stream + (s0 & ~(uint64_t)3u));
     const uint32_t max_w = (uint32_t)(((stream_bytes + 3u) / 4u) - (s0 >> 2)) - 1u;   // last readable dword
     const uint32_t seg_w = (byte0 + seg_len + 3u) / 4u + 2u;       // two more for the look-ahead
-    const bool whole = __syncthreads_or(my_side != 0u) == 0;
-    // the lists of the other instances are made from the first sub-chunk's side information
-    if (whole != (side0 == 0u)) {
-        if (FIRST && tid == 0) atomicOr(status, (unsigned long long)CODEC_BAD_STREAM);
-        return;
-    }
+    // One stored block iff the first sub-chunk's side information is 0 (the lists of the
+    // other instances are made from it too); every thread then checks that its own
+    // sub-chunk agrees: a coded or stored sub-chunk never has 0, a chunk stored whole has
+    // nothing else.
+    const bool whole = side0 == 0u;
     const uint32_t size_class = whole ? 0u : seg_w;
     if (size_class < SEG_MIN || size_class > SEG_DW) return;       // another instance's chunk
     uint8_t* dst = out + base;
@@ -695,6 +706,7 @@ __device__ __forceinline__ void inflate_chunk(
         uint32_t* dst32 = reinterpret_cast<uint32_t*>(dst);
         const uint8_t* seg = stream + s0;
         const uint32_t len = seg[1] | ((uint32_t)seg[2] << 8), nlen = seg[3] | ((uint32_t)seg[4] << 8);
+        if (my_side != 0u) atomicOr(status, (unsigned long long)CODEC_BAD_STREAM);
         if (((seg[0] >> 1) & 3u) != 0u || len != m || (len ^ nlen) != 0xffffu || seg_len != m + 5u) {
             if (tid == 0) atomicOr(status, (unsigned long long)CODEC_BAD_STREAM);
             return;
@@ -721,29 +733,40 @@ __device__ __forceinline__ void inflate_chunk(
     const uint64_t mark = marks[(uint64_t)c * CODEC_NSUB + l];
     const bool stored_sub = my_side == CODEC_STORED;
     bool ok = stored_sub ? n_l > 0u : (n_l > 0u ? my_side <= 8u * n_l + CODEC_MARGIN : my_side == 0u);
-    if (q == 0u) sh.side[l] = ok ? my_side : 0u;
-    for (uint32_t k = tid; k < seg_w; k += CODEC_THREADS) sh.seg[k] = k <= max_w ? seg32[k] : 0u;
-    sh.tab[tid] = kTokenTable.v[tid];
-    sh.tab[tid + CODEC_THREADS] = kTokenTable.v[tid + CODEC_THREADS];
-#pragma unroll
-    for (uint32_t j = 0; j < CODEC_CHUNK / 16 / CODEC_THREADS; ++j)
-        reinterpret_cast<uint4*>(sh.img)[j * CODEC_THREADS + tid] = make_uint4(0, 0, 0, 0);
-    const bool all_ok = __syncthreads_and(ok) != 0;
-    const bool any_stored = __syncthreads_or(stored_sub) != 0;
+    // The first wavefront, one lane per sub-chunk, works out where every sub-chunk's part of
+    // the segment starts while the others stage the segment and clear the image: one barrier
+    // before the decoding, one after it.
     if (tid < CODEC_NSUB) {
+        const uint32_t n_s = min(CODEC_SUB, m - min(m, tid * CODEC_SUB));
+        const uint32_t v = side[(uint64_t)c * CODEC_NSUB + tid];
+        const bool st = v == CODEC_STORED;
+        const bool ok_s = st ? n_s > 0u : (n_s > 0u ? v != 0u && v <= 8u * n_s + CODEC_MARGIN : v == 0u);
+        sh.side[tid] = ok_s ? v : 0u;
+        // the lanes exchange within their own wavefront only: order the LDS accesses
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const bool any_stored = __ballot(st) != 0ull;
+        const bool all_ok = __ballot(!ok_s) == 0ull;
         uint32_t start, tail_start;
         bool in_block, tail_in_block;
         const uint32_t sb = place_subs(sh.side, m, tid, any_stored, &start, &in_block, &tail_start,
                                        &tail_in_block);
         sh.start[tid] = start | (in_block ? 0x80000000u : 0u);
         if (tid == 0) {
-            sh.misc[0] = sb;
+            sh.misc[0] = all_ok ? sb : 0xffffffffu;      // never a segment's size
             sh.misc[1] = tail_start;
             sh.misc[2] = tail_in_block ? 1u : 0u;
         }
     }
+    for (uint32_t k = tid; k < seg_w; k += CODEC_THREADS) sh.seg[k] = k <= max_w ? seg32[k] : 0u;
+    sh.tab[tid] = kTokenTable.v[tid];
+    sh.tab[tid + CODEC_THREADS] = kTokenTable.v[tid + CODEC_THREADS];
+#pragma unroll
+    for (uint32_t j = 0; j < CODEC_CHUNK / 16 / CODEC_THREADS; ++j)
+        reinterpret_cast<uint4*>(sh.img)[j * CODEC_THREADS + tid] = make_uint4(0, 0, 0, 0);
     __syncthreads();
-    if (!all_ok || sh.misc[0] != seg_len) {
+    if (sh.misc[0] != seg_len) {
         if (tid == 0) atomicOr(status, (unsigned long long)CODEC_BAD_STREAM);
         return;
     }
@@ -809,14 +832,17 @@ __device__ __forceinline__ void inflate_chunk(
             uint32_t nextw = (pos >> 5) + 2u, sh_bits = pos & 31u;
             uint32_t w_lo = s_seg[pos >> 5], w_hi = s_seg[(pos >> 5) + 1u];
             uint32_t bad_bits = 0;
-            // One token per turn, without branches but for the stores: the table gives the
-            // token's bits, kind and value, and a literal reads as a match of length 1 of
-            // itself.  Offsets are not checked on the way: a store wraps inside its sub-chunk's
-            // row of the image, offsets only grow, and the end must come out exactly right.
+            // Up to two tokens per turn, without branches but for the stores: the table gives
+            // a token's bits, kind and value, and a literal reads as a match of length 1 of
+            // itself; when the token behind it is a literal (three quarters of all tokens are,
+            // in half-empty data) that one is taken in the same turn (a third one gained 1 %).  Offsets are not checked
+            // on the way: a store wraps inside its sub-chunk's row of the image, offsets only
+            // grow, and the end must come out exactly right.
             while (pos < end) {
                 const uint32_t x = __builtin_amdgcn_alignbit(w_hi, w_lo, sh_bits);
                 const uint32_t t = sh.tab[x & 511u];
                 const uint32_t nb = t & 31u;
+                const uint32_t t2 = sh.tab[(x >> nb) & 511u];              // at most 18 of the 32 bits are used
                 const uint32_t mm = 0u - ((t >> 5) & 1u);                  // all ones for a match
                 const uint32_t len = ((t >> 7) & 0x1ffu) + __builtin_amdgcn_ubfe(x, (t >> 24) & 15u, t >> 28);
                 const uint32_t byte = ((t >> 16) & 0xffu) | (prev & mm);    // a match repeats the byte before it
@@ -827,10 +853,16 @@ __device__ __forceinline__ void inflate_chunk(
                     img8[row + ((i + rot) & (CODEC_SUB - 1u))] = (uint8_t)byte;
                     for (uint32_t u = 1; u < len; ++u) img8[row + ((i + u + rot) & (CODEC_SUB - 1u))] = (uint8_t)byte;
                 }
-                prev = byte;
                 i += len;
-                pos += nb;
-                sh_bits += nb;
+                // the second token: a literal that starts before the lane's last bit
+                const bool two = (t2 & 0x60u) == 0u && pos + nb < end;
+                const uint32_t byte2 = (t2 >> 16) & 0xffu;
+                if (two && byte2 != 0u) img8[row + ((i + rot) & (CODEC_SUB - 1u))] = (uint8_t)byte2;
+                const uint32_t used = nb + (two ? t2 & 31u : 0u);          // at most 18 + 9 bits
+                prev = two ? byte2 : byte;
+                i += two ? 1u : 0u;
+                pos += used;
+                sh_bits += used;
                 const uint32_t w_new = s_seg[min(nextw, SEG_DW - 1u)];
                 const bool take = sh_bits >= 32u;
                 w_lo = take ? w_hi : w_lo;
