@@ -547,11 +547,21 @@ __global__ __launch_bounds__(BLOCK) void spec_rank_kernel(SpecState* ss,
         publish();
         return;
     }
-    if (ss->status & 1u) { publish(); return; }
+    // Undecided: the host redoes the ranking and every step behind it.  What is enqueued
+    // behind this kernel still runs once on the record it finds, so leave a harmless one
+    // (nothing removed) rather than the record of some earlier call.
+    auto undecided = [&]() {
+        if (threadIdx.x == 0) {
+            out.cut = 0; out.t_key = 0; out.g_cut = ~0ull; out.n_less = 0; out.n_equal = 0;
+            *thr = out;
+        }
+        publish();
+    };
+    if (ss->status & 1u) { undecided(); return; }
     const uint32_t n = min(ss->list_cnt, SPEC_LIST_CAP);
     if (n != ss->bin_cnt) {   // cannot happen unless the buffers were disturbed
         if (threadIdx.x == 0) atomicOr(&ss->status, 1u);
-        publish();
+        undecided();
         return;
     }
     // round 2: the list's keys span 2^sh values starting at lo + (bin << sh)
@@ -587,7 +597,7 @@ __global__ __launch_bounds__(BLOCK) void spec_rank_kernel(SpecState* ss,
     const uint32_t bin2 = s_bin2, cnt2 = s_cnt2;
     if (cnt2 == 0 || cnt2 > SPEC_SMALL_CAP) {
         if (threadIdx.x == 0) atomicOr(&ss->status, 1u);
-        publish();
+        undecided();
         return;
     }
     for (uint32_t i = threadIdx.x; i < n; i += BLOCK) {
