@@ -384,6 +384,15 @@ struct SampleZero {
     RankOut* rout = nullptr;
     uint32_t* extra = nullptr;     // one more array of extra_n words to clear
     uint32_t extra_n = 0;
+    // the one-count selection: its state to set up, its split counters and the caller's
+    // flag arrays to clear (ss == nullptr: not this call)
+    shifter::SpecState* ss = nullptr;
+    uint32_t* cnt1 = nullptr;
+    uint64_t p = 0;
+    uint32_t m_valid = 0;
+    uint8_t* fa = nullptr;
+    uint8_t* fb = nullptr;
+    uint64_t na = 0, nb = 0;
 };
 void launch_spec_sample(shifter_ctx* ctx, const shifter_model* m, const float* d_w,
                         const SampleZero& z = SampleZero());

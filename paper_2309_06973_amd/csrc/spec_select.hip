@@ -38,30 +38,6 @@ __device__ __forceinline__ uint32_t* sub_counter(uint32_t* cnt, uint32_t which, 
     return cnt + (which * SPEC_SUB + sb) * 32u;
 }
 
-__global__ __launch_bounds__(BLOCK) void spec_init_kernel(SpecState* ss, uint32_t* shist,
-                                                          uint32_t* cnt, uint64_t p,
-                                                          uint32_t m_valid, uint8_t* fa,
-                                                          uint64_t na, uint8_t* fb, uint64_t nb) {
-    const uint64_t tid = (uint64_t)blockIdx.x * BLOCK + threadIdx.x;
-    const uint64_t stride = (uint64_t)gridDim.x * BLOCK;
-    (void)shist;     // every ranking leaves the sample histogram cleared (see the predict kernels)
-    for (uint64_t i = tid; i < 2u * SPEC_SUB * 32u; i += stride) cnt[i] = 0;
-    for (uint64_t i = tid; i < na; i += stride) fa[i] = 0;
-    for (uint64_t i = tid; i < nb; i += stride) fb[i] = 0;
-    if (tid == 0) {
-        ss->p = p;
-        ss->n_below = 0;
-        ss->n_inside = 0;
-        ss->m_valid = m_valid;
-        ss->status = 0;
-        ss->list_cnt = 0;
-        ss->lo = 0;
-        ss->hi = 0x7fffffffu;
-        ss->mid = 0;
-        ss->sh = 19;
-    }
-}
-
 // The sample: from every quarter (1024 weights) of every sample_tile_stride-th tile one
 // 64-byte sector of 16 weights, at a position that rotates with the tile and the quarter.
 // Every filter of 1024 or more weights is thus sampled in proportion to its size - the
@@ -95,6 +71,29 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void spec_sample_kernel(
         if (tid < MAXK) {
             z.list_cnt[tid] = 0;
             z.rout[tid].fail = 0;
+        }
+    }
+    if (z.ss) {
+        // set-up of the one-count selection, idle until the kernels behind this one: its
+        // split counters and the caller's flag arrays cleared, its state initialised (every
+        // ranking leaves the sample histogram cleared, see the predict kernels)
+        const uint64_t tid = (uint64_t)blockIdx.x * SAMPLE_THREADS + threadIdx.x;
+        const uint64_t stride = (uint64_t)gridDim.x * SAMPLE_THREADS;
+        for (uint64_t i = tid; i < 2u * SPEC_SUB * 32u; i += stride) z.cnt1[i] = 0;
+        for (uint64_t i = tid; i < z.na; i += stride) z.fa[i] = 0;
+        for (uint64_t i = tid; i < z.nb; i += stride) z.fb[i] = 0;
+        if (tid == 0) {
+            SpecState* ss = z.ss;
+            ss->p = z.p;
+            ss->n_below = 0;
+            ss->n_inside = 0;
+            ss->m_valid = z.m_valid;
+            ss->status = 0;
+            ss->list_cnt = 0;
+            ss->lo = 0;
+            ss->hi = 0x7fffffffu;
+            ss->mid = 0;
+            ss->sh = 19;
         }
     }
     for (uint32_t i = threadIdx.x; i < SBINS; i += SAMPLE_THREADS) h[i] = 0;
@@ -742,15 +741,18 @@ void launch_spec_select(shifter_ctx* ctx, const shifter_model* m, const float* d
     const bool fused = d_w_out != nullptr;
     hipStream_t s = ctx->stream;
     {
-        ProfileScope ps(ctx, K_SPEC_INIT);
-        spec_init_kernel<<<64, BLOCK, 0, s>>>(b.spec, b.shist, b.spec_cnt, p, m->sample_size,
-                                              d_out_alive,
-                                              fused ? m->info.sum_out_ch : 0, d_in_alive,
-                                              fused ? m->info.sum_in_ch : 0);
-    }
-    {
+        // the set-up rides on the sample kernel
         ProfileScope ps(ctx, K_SPEC_SAMPLE);
-        launch_spec_sample(ctx, m, d_w);
+        SampleZero z;
+        z.ss = b.spec;
+        z.cnt1 = b.spec_cnt;
+        z.p = p;
+        z.m_valid = m->sample_size;
+        z.fa = d_out_alive;
+        z.na = fused ? m->info.sum_out_ch : 0;
+        z.fb = d_in_alive;
+        z.nb = fused ? m->info.sum_in_ch : 0;
+        launch_spec_sample(ctx, m, d_w, z);
     }
     {
         ProfileScope ps(ctx, K_SPEC_PREDICT);
