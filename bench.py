@@ -285,6 +285,11 @@ def measure(name, steps, warmup, lean_run=True, cpu_leg=True):
                     "kept_weights": int(fout[3]), "kept_weights_single_pass": int(kept[0])}
         # the same with nothing read back before the rebuild's own wait (four batches of four
         # rounds enqueued, those after the fixpoint return at once)
+        for _ in range(3):                   # the runtime's one-time work stays out of the timing
+            pl.kernel_scan()
+            pl.propagate_groups_fixpoint(0, sync=False)
+            pl.compact(sync=True)
+        torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(steps):
             pl.kernel_scan()
