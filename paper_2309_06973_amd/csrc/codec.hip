@@ -673,6 +673,12 @@ __device__ __forceinline__ void inflate_chunk(
     const uint64_t* __restrict__ marks, uint64_t n_bytes, uint32_t n_chunks, uint8_t* __restrict__ out,
     uint64_t* __restrict__ result) {
     constexpr bool FIRST = SEG_MIN == 0;
+    // The instance of the short segments (chunks that are mostly zeros) keeps no image of
+    // the chunk: it writes the chunk's zeros to memory at once, 16 bytes per thread and
+    // store, and after the block's barrier every lane stores its few non-zero bytes one by
+    // one on top.  Without the 32 KiB image many more blocks fit a compute unit, and the
+    // zeros are on their way while the segment is still being fetched.
+    constexpr bool DIRECT = SEG_DW == CODEC_SEG_SMALL;
     const uint32_t tid = threadIdx.x, l = tid >> 2, q = tid & 3u;
     const uint64_t base = (uint64_t)c * CODEC_CHUNK;
     const uint32_t m = (uint32_t)min((uint64_t)CODEC_CHUNK, n_bytes - min(n_bytes, base));
@@ -762,9 +768,24 @@ __device__ __forceinline__ void inflate_chunk(
     for (uint32_t k = tid; k < seg_w; k += CODEC_THREADS) sh.seg[k] = k <= max_w ? seg32[k] : 0u;
     sh.tab[tid] = kTokenTable.v[tid];
     sh.tab[tid + CODEC_THREADS] = kTokenTable.v[tid + CODEC_THREADS];
+    if (DIRECT) {
+        if (m == CODEC_CHUNK) {
 #pragma unroll
-    for (uint32_t j = 0; j < CODEC_CHUNK / 16 / CODEC_THREADS; ++j)
-        reinterpret_cast<uint4*>(sh.img)[j * CODEC_THREADS + tid] = make_uint4(0, 0, 0, 0);
+            for (uint32_t j = 0; j < CODEC_CHUNK / 16 / CODEC_THREADS; ++j)
+                *reinterpret_cast<uint4*>(dst + (j * CODEC_THREADS + tid) * 16u) = make_uint4(0, 0, 0, 0);
+        } else {
+            for (uint32_t g = tid; g * 16u < m; g += CODEC_THREADS) {
+                if (g * 16u + 16u <= m) *reinterpret_cast<uint4*>(dst + g * 16u) = make_uint4(0, 0, 0, 0);
+                else for (uint32_t k = g * 16u; k < m; ++k) dst[k] = 0;
+            }
+        }
+    } else {
+#pragma unroll
+        for (uint32_t j = 0; j < CODEC_CHUNK / 16 / CODEC_THREADS; ++j)
+            reinterpret_cast<uint4*>(sh.img)[j * CODEC_THREADS + tid] = make_uint4(0, 0, 0, 0);
+    }
+    // orders the block's accesses to the image, and (DIRECT) its zeros in memory before the
+    // bytes its lanes store on top of them
     __syncthreads();
     if (sh.misc[0] != seg_len) {
         if (tid == 0) atomicOr(status, (unsigned long long)CODEC_BAD_STREAM);
@@ -803,12 +824,19 @@ __device__ __forceinline__ void inflate_chunk(
         if (ok && p_hi > p_lo) {
             const uint32_t d0 = b0 + 4u + p_lo;    // this lane's first byte
             const uint32_t shb = (d0 & 3u) * 8u, w0 = d0 >> 2, nw = (p_hi - p_lo) / 4u;
+            uint32_t* out32 = reinterpret_cast<uint32_t*>(dst + l * CODEC_SUB + p_lo);   // DIRECT: 128-byte aligned
 #pragma unroll 8
             for (uint32_t k = 0; k < nw; ++k) {
                 const uint32_t lo = s_seg[w0 + k];
-                sh.img[sub_word(l, p_lo / 4u + k)] = shb ? (lo >> shb) | (s_seg[w0 + k + 1u] << (32u - shb)) : lo;
+                const uint32_t v = shb ? (lo >> shb) | (s_seg[w0 + k + 1u] << (32u - shb)) : lo;
+                if (DIRECT) out32[k] = v;
+                else sh.img[sub_word(l, p_lo / 4u + k)] = v;
             }
-            for (uint32_t k = p_lo + nw * 4u; k < p_hi; ++k) img8[img_byte(l, k)] = (uint8_t)seg_byte(s_seg, d0 + k - p_lo);
+            for (uint32_t k = p_lo + nw * 4u; k < p_hi; ++k) {
+                const uint8_t v = (uint8_t)seg_byte(s_seg, d0 + k - p_lo);
+                if (DIRECT) dst[l * CODEC_SUB + k] = v;
+                else img8[img_byte(l, k)] = v;
+            }
         }
     } else if (n_l > 0u) {
         // this lane's range from the mark: bits [b_lo, b_hi) of the sub-chunk's tokens make
@@ -850,14 +878,29 @@ __device__ __forceinline__ void inflate_chunk(
                 // at a distance other than 1
                 bad_bits |= (t & 64u) | ((__builtin_amdgcn_ubfe(x, nb - 5u, 5u) | (prev >> 8)) & mm);
                 if ((byte & 0xffu) != 0u) {                                 // zeros are already there
-                    img8[row + ((i + rot) & (CODEC_SUB - 1u))] = (uint8_t)byte;
-                    for (uint32_t u = 1; u < len; ++u) img8[row + ((i + u + rot) & (CODEC_SUB - 1u))] = (uint8_t)byte;
+                    if (DIRECT) {
+                        // no image: straight to memory, inside the sub-chunk and the output
+                        for (uint32_t u = 0; u < len; ++u) {
+                            const uint32_t at = row + ((i + u) & (CODEC_SUB - 1u));
+                            if (at < m) dst[at] = (uint8_t)byte;
+                        }
+                    } else {
+                        img8[row + ((i + rot) & (CODEC_SUB - 1u))] = (uint8_t)byte;
+                        for (uint32_t u = 1; u < len; ++u) img8[row + ((i + u + rot) & (CODEC_SUB - 1u))] = (uint8_t)byte;
+                    }
                 }
                 i += len;
                 // the second token: a literal that starts before the lane's last bit
                 const bool two = (t2 & 0x60u) == 0u && pos + nb < end;
                 const uint32_t byte2 = (t2 >> 16) & 0xffu;
-                if (two && byte2 != 0u) img8[row + ((i + rot) & (CODEC_SUB - 1u))] = (uint8_t)byte2;
+                if (two && byte2 != 0u) {
+                    if (DIRECT) {
+                        const uint32_t at = row + (i & (CODEC_SUB - 1u));
+                        if (at < m) dst[at] = (uint8_t)byte2;
+                    } else {
+                        img8[row + ((i + rot) & (CODEC_SUB - 1u))] = (uint8_t)byte2;
+                    }
+                }
                 const uint32_t used = nb + (two ? t2 & 31u : 0u);          // at most 18 + 9 bits
                 prev = two ? byte2 : byte;
                 i += two ? 1u : 0u;
@@ -881,6 +924,7 @@ __device__ __forceinline__ void inflate_chunk(
         if (tid == 0) atomicOr(status, (unsigned long long)CODEC_BAD_STREAM);
         return;
     }
+    if (DIRECT) return;
     // write-out: 16 bytes per thread and step, whole lines per wave
     if (m == CODEC_CHUNK) {
 #pragma unroll
@@ -905,13 +949,13 @@ __device__ __forceinline__ void inflate_chunk(
 }
 
 template <uint32_t SEG_DW, uint32_t SEG_MIN>
-__global__ __launch_bounds__(CODEC_THREADS, SEG_DW == CODEC_SEG_SMALL ? 4 : (SEG_DW == CODEC_SEG_MEDIUM ? 3 : 2))
+__global__ __launch_bounds__(CODEC_THREADS, SEG_DW == CODEC_SEG_SMALL ? 5 : (SEG_DW == CODEC_SEG_MEDIUM ? 3 : 2))
 void inflate_chunk_kernel(
     const uint8_t* __restrict__ stream, uint64_t stream_bytes, const uint64_t* __restrict__ seg_off,
     const uint16_t* __restrict__ side, const uint64_t* __restrict__ marks, uint64_t n_bytes, uint32_t n_chunks,
     uint8_t* __restrict__ out, uint64_t* __restrict__ result, const uint32_t* __restrict__ list,
     const uint32_t* __restrict__ list_count) {
-    __shared__ __align__(16) uint32_t s_img[CODEC_CHUNK / 4];
+    __shared__ __align__(16) uint32_t s_img[SEG_DW == CODEC_SEG_SMALL ? 4 : CODEC_CHUNK / 4];   // none for the short segments
     __shared__ uint32_t s_seg[SEG_DW];
     __shared__ uint32_t s_tab[512];
     __shared__ uint32_t s_side[CODEC_NSUB];
