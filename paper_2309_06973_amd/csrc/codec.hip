@@ -300,8 +300,7 @@ __device__ __forceinline__ void deflate_chunk(
     // Bit masks over the bytes of this lane's quarter, 4 words: S, byte i starts a run (it
     // differs from byte i - 1; position n_l counts as a start); G, byte i >= 144.  From S:
     // the bytes sent as literals (starts, and the second and third byte of runs shorter
-    // than 4); a literal not followed by a literal starts a run of 4 or more.  The words
-    // next to the quarter are worked out again rather than exchanged.
+    // than 4); a literal not followed by a literal starts a run of 4 or more.
     uint32_t* mk = sh.mask + l * CODEC_MASKW;
     const uint32_t a0 = q * CODEC_QW;
     uint32_t tok_bits = 0;
@@ -314,18 +313,22 @@ __device__ __forceinline__ void deflate_chunk(
         tok_bits = q == 0u ? 8u : 0u;
     } else {
         constexpr uint32_t NW = CODEC_SUB / 32;
+        // S[1 .. 4], G[1 .. 4]: this lane's words; S[0] and S[5]: the words next to them, from
+        // the neighbouring lanes of the sub-chunk (the lanes of a sub-chunk are neighbours in
+        // the wavefront); position 512 ends the last run
         uint32_t S[CODEC_QW + 2], G[CODEC_QW + 2];
 #pragma unroll
-        for (uint32_t k = 0; k < CODEC_QW + 2u; ++k) {
-            const uint32_t a = a0 + k - 1u;                 // a0 - 1 .. a0 + 4 (wraps for a0 = 0)
-            S[k] = 0;
-            G[k] = 0;
-            if (a < NW) {
-                mask_word(s_in, l, a, &S[k], &G[k]);
-                if (n_l < CODEC_SUB && (n_l >> 5) == a) S[k] |= 1u << (n_l & 31u);
-            } else if (a == NW) {
-                S[k] = 1u;                                  // position 512 ends the last run
-            }
+        for (uint32_t k = 1; k <= CODEC_QW; ++k) {
+            const uint32_t a = a0 + k - 1u;
+            mask_word(s_in, l, a, &S[k], &G[k]);
+            if (n_l < CODEC_SUB && (n_l >> 5) == a) S[k] |= 1u << (n_l & 31u);
+        }
+        {
+            const uint32_t from_left = __shfl_up(S[CODEC_QW], 1, CODEC_Q);
+            const uint32_t from_right = __shfl_down(S[1], 1, CODEC_Q);
+            S[0] = q == 0u ? 0u : from_left;
+            S[CODEC_QW + 1] = q == CODEC_Q - 1u ? 1u : from_right;
+            G[0] = G[CODEC_QW + 1] = 0;
         }
         uint32_t n_lit = 0, n_nine = 0;
 #pragma unroll
