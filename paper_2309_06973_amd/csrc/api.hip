@@ -1415,9 +1415,10 @@ extern "C" int shifter_portfolio_begin(shifter_ctx* ctx, const shifter_model* mo
         pp.mode = 2;
         if (model->info.w_extent * 4 > (192ull << 20)) {
             // an arena beyond the last-level cache: ranking, masks and levels in one read of it
-            FusedBatch fb{K, g.d_w_sparse, g.w_stride, g.d_mask, g.mask_stride, g.d_out_alive, g.d_in_alive};
+            // (the planning launch expands the levels into the variants' flags on the way)
+            FusedBatch fb{K, g.d_w_sparse, g.w_stride, g.d_mask, g.mask_stride, g.d_out_alive, g.d_in_alive, true};
             launch_spec_multi(ctx, model, g.d_w, sp, perm, k_eff, zero_mask, g.d_thr, &fb);
-            launch_plan_and_gather(ctx, model, pp.buf, false, cut_positions(pp.pc, K));
+            launch_plan_and_gather(ctx, model, pp.buf, true, cut_positions(pp.pc, K));
         } else {
             // a cache-sized arena: the counting pass, then the mask pass reads it again; the
             // planning launch expands the levels into the variants' flags on the way

@@ -405,6 +405,7 @@ struct FusedBatch {
     uint64_t mask_stride;
     uint8_t* d_out_alive;
     uint8_t* d_in_alive;     // or nullptr
+    bool levels_only = false;   // leave the levels unexpanded: the planning launch behind it writes the flags
 };
 // zero_ptr / zero_n: an array of 32-bit words the ranking's set-up clears on the way (or
 // nullptr), for the step that follows it.

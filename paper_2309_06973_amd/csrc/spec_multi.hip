@@ -1094,7 +1094,7 @@ void launch_spec_multi(shifter_ctx* ctx, const shifter_model* m, const float* d_
                 fb->k_all - k, fb->d_w_out, fb->w_stride, fb->d_mask, fb->mask_stride, b.levels,
                 b.levels + m->info.sum_out_ch);
         }
-        launch_expand_levels(ctx, m, d_thr, fb->k_all, fb->d_out_alive, fb->d_in_alive);
+        if (!fb->levels_only) launch_expand_levels(ctx, m, d_thr, fb->k_all, fb->d_out_alive, fb->d_in_alive);
     }
 }
 
