@@ -12,6 +12,8 @@ the other full-size workloads of the target under "other_workloads".
                   [--no-lean] [--codec-profile REPS]
 """
 import argparse
+import functools
+import gc
 import hashlib
 import json
 import os
@@ -136,6 +138,22 @@ def cpu_baselines(spec, w, v, sparsity, whole=True):
     return base, fast
 
 
+def without_gc(fn):
+    """Runs fn with the interpreter's cyclic garbage collector off, as timeit does: one
+    collection is about a millisecond of host time (two c5 steps) and falls wherever the
+    allocation counters put it, inside one run's timed steps and outside the next's."""
+    @functools.wraps(fn)
+    def wrapped(*a, **kw):
+        gc.collect()
+        gc.disable()
+        try:
+            return fn(*a, **kw)
+        finally:
+            gc.enable()
+    return wrapped
+
+
+@without_gc
 def measure(name, steps, warmup, lean_run=True, cpu_leg=True):
     """Times `steps` steps of one workload; returns the fields of its report."""
     import torch
