@@ -515,45 +515,92 @@ __global__ __launch_bounds__(CODEC_THREADS) void deflate_chunk_kernel(
     }
 }
 
-// Byte offsets of the segments: exclusive prefix sums of their sizes (one block).  The
-// sizes of eight rounds of 1024 chunks are loaded together, then scanned round by round.
+// Byte offsets of the segments: exclusive prefix sums of their sizes (one block).  A row is
+// 64 consecutive chunks, one per lane.  Every wavefront first sums its rows (every 16th),
+// eight rows' loads in flight together and nothing shared but the row sums in LDS; then one
+// block-wide scan over the thread totals of the row sums (a thread owns a run of rows); then
+// the wavefronts visit their rows again and write the offsets: the row's base from the
+// owner's total and the rows before it in the run, plus a scan across the lanes.  Three
+// barriers per SCAN_ROWS_MAX rows (2 GiB of input), whatever the number of chunks below.
+constexpr uint32_t SCAN_ROWS_MAX = 1024;
 __global__ __launch_bounds__(1024) void codec_scan_kernel(const uint32_t* __restrict__ seg_size,
                                                           uint32_t n_chunks,
                                                           uint64_t* __restrict__ seg_off,
                                                           uint64_t stream_cap,
                                                           uint64_t* __restrict__ result) {
-    __shared__ uint64_t s_wave[2][16];
+    __shared__ uint32_t s_row[SCAN_ROWS_MAX];           // a row's sizes sum to less than 2^32
+    __shared__ uint64_t s_tbase[1024];                  // exclusive prefix of the threads' runs
+    __shared__ uint64_t s_wave[16];
     const uint32_t lane = threadIdx.x & 63u, wid = threadIdx.x >> 6;
     constexpr uint32_t R = 8;
     uint64_t carry = 0;                                 // the same in every thread
-    uint32_t flip = 0;
-    for (uint32_t b0 = 0; b0 < n_chunks; b0 += R * 1024u) {
-        uint32_t v[R];
+    for (uint32_t c0 = 0; c0 < n_chunks; c0 += SCAN_ROWS_MAX * 64u) {
+        const uint32_t n_here = min(n_chunks - c0, SCAN_ROWS_MAX * 64u);
+        const uint32_t* size = seg_size + c0;
+        const uint32_t rows = (n_here + 63u) / 64u;
+        const uint32_t rpt = (rows + 1023u) / 1024u;    // rows per thread in the scan
+        for (uint32_t j0 = wid; j0 < rows; j0 += 16u * R) {
+            uint32_t v[R];
 #pragma unroll
-        for (uint32_t u = 0; u < R; ++u) {
-            const uint32_t i = b0 + u * 1024u + threadIdx.x;
-            v[u] = i < n_chunks ? seg_size[i] : 0u;
+            for (uint32_t u = 0; u < R; ++u) {
+                const uint32_t i = (j0 + 16u * u) * 64u + lane;       // rows j0, j0 + 16, ...
+                v[u] = i < n_here ? size[i] : 0u;
+            }
+#pragma unroll
+            for (uint32_t u = 0; u < R; ++u) {
+                uint32_t x = v[u];
+                for (uint32_t d = 32; d > 0; d >>= 1) x += __shfl_down(x, d, 64);
+                if (lane == 0 && j0 + 16u * u < rows) s_row[j0 + 16u * u] = x;
+            }
         }
-#pragma unroll
-        for (uint32_t u = 0; u < R; ++u) {
-            const uint32_t i = b0 + u * 1024u + threadIdx.x;
-            unsigned long long x = v[u];
+        __syncthreads();
+        {
+            uint64_t mine = 0;
+            for (uint32_t i = 0; i < rpt; ++i) {
+                const uint32_t j = threadIdx.x * rpt + i;
+                if (j < rows) mine += s_row[j];
+            }
+            unsigned long long x = mine;
             for (uint32_t d = 1; d < 64; d <<= 1) {
                 const unsigned long long y = __shfl_up(x, d, 64);
                 if (lane >= d) x += y;
             }
-            if (lane == 63u) s_wave[flip][wid] = x;
-            __syncthreads();                            // the other buffer is free again by now
+            if (lane == 63u) s_wave[wid] = x;
+            __syncthreads();
             uint64_t off = carry, total = 0;
             for (uint32_t k = 0; k < 16u; ++k) {
-                const uint64_t w = s_wave[flip][k];
+                const uint64_t w = s_wave[k];
                 if (k < wid) off += w;
                 total += w;
             }
-            if (i < n_chunks) seg_off[i] = off + x - v[u];
+            s_tbase[threadIdx.x] = off + x - mine;
             carry += total;
-            flip ^= 1u;
         }
+        __syncthreads();
+        for (uint32_t j0 = wid; j0 < rows; j0 += 16u * R) {
+            uint32_t v[R];
+#pragma unroll
+            for (uint32_t u = 0; u < R; ++u) {
+                const uint32_t i = (j0 + 16u * u) * 64u + lane;
+                v[u] = i < n_here ? size[i] : 0u;
+            }
+#pragma unroll
+            for (uint32_t u = 0; u < R; ++u) {
+                const uint32_t j = j0 + 16u * u, i = j * 64u + lane;
+                if (j < rows) {                             // the same in every lane
+                    const uint32_t owner = j / rpt;
+                    uint64_t base = s_tbase[owner];
+                    for (uint32_t r = owner * rpt; r < j; ++r) base += s_row[r];
+                    uint32_t x = v[u];
+                    for (uint32_t d = 1; d < 64; d <<= 1) {
+                        const uint32_t y = __shfl_up(x, d, 64);
+                        if (lane >= d) x += y;
+                    }
+                    if (i < n_here) seg_off[(uint64_t)c0 + i] = base + x - v[u];
+                }
+            }
+        }
+        __syncthreads();                                // s_row and s_tbase are free again
     }
     if (threadIdx.x == 0) {
         seg_off[n_chunks] = carry;
@@ -986,10 +1033,27 @@ __global__ void codec_clear_kernel(uint64_t* result) {
 }
 
 // The call's outcome (stream bytes, status bits) into the pinned mirror the host reads after
-// its wait.
-__global__ void codec_publish_kernel(const uint64_t* __restrict__ result, uint64_t* __restrict__ mirror) {
+// its wait; the result words are then cleared for the next call (zero after use: the next
+// call needs no clearing launch of its own).
+__global__ void codec_publish_kernel(uint64_t* __restrict__ result, uint64_t* __restrict__ mirror) {
     mirror[0] = result[0];
     mirror[1] = result[1];
+    result[0] = 0;
+    result[1] = 0;
+    result[2] = 0;
+    result[3] = 0;
+}
+
+// The result words are zero when a call starts: the context allocates them cleared and every
+// call's last kernel leaves them so.  Only a call that could not enqueue all of its kernels
+// leaves them in doubt; the call after it clears them itself.
+static void codec_begin(shifter_ctx* ctx) {
+    if (ctx->codec_dirty) codec_clear_kernel<<<1, 1, 0, ctx->stream>>>(ctx->d_codec);
+    ctx->codec_dirty = true;
+}
+static void codec_end(shifter_ctx* ctx) {
+    codec_publish_kernel<<<1, 1, 0, ctx->stream>>>(ctx->d_codec, ctx->dev_codec_mirror);
+    if (hipPeekAtLastError() == hipSuccess) ctx->codec_dirty = false;
 }
 
 // Room for chunk lists, kept by the context and grown when a longer input comes.
@@ -1015,7 +1079,7 @@ int launch_deflate(shifter_ctx* ctx, const uint8_t* d_in, uint64_t n_bytes, uint
     uint32_t* seg_size = reinterpret_cast<uint32_t*>(d_work);
     uint8_t* slots = d_work + codec_slots_offset(n_chunks);
     uint32_t* long_count = reinterpret_cast<uint32_t*>(ctx->d_codec + 2);
-    codec_clear_kernel<<<1, 1, 0, ctx->stream>>>(ctx->d_codec);
+    codec_begin(ctx);
     {
         ProfileScope ps(ctx, K_DEFLATE_CHUNK);
         deflate_chunk_kernel<CODEC_OUT_SMALL, false><<<n_chunks, CODEC_THREADS, 0, ctx->stream>>>(
@@ -1038,7 +1102,7 @@ int launch_deflate(shifter_ctx* ctx, const uint8_t* d_in, uint64_t n_bytes, uint
         codec_pack_kernel<<<n_chunks, 64, 0, ctx->stream>>>(slots, seg_size, d_seg_off, ctx->d_codec,
                                                             d_stream);
     }
-    codec_publish_kernel<<<1, 1, 0, ctx->stream>>>(ctx->d_codec, ctx->dev_codec_mirror);
+    codec_end(ctx);
     return 0;
 }
 
@@ -1082,7 +1146,7 @@ int launch_inflate(shifter_ctx* ctx, const uint8_t* d_stream, uint64_t stream_by
     uint32_t* list_large = ctx->d_codec_list + n_chunks;
     const uint32_t* n_medium = reinterpret_cast<const uint32_t*>(ctx->d_codec + 2);
     const uint32_t* n_large = reinterpret_cast<const uint32_t*>(ctx->d_codec + 3);
-    codec_clear_kernel<<<1, 1, 0, ctx->stream>>>(ctx->d_codec);
+    codec_begin(ctx);
     {
         ProfileScope ps(ctx, K_INFLATE_CHUNK);
         codec_classify_kernel<<<(n_chunks + BLOCK - 1) / BLOCK, BLOCK, 0, ctx->stream>>>(
@@ -1099,7 +1163,7 @@ int launch_inflate(shifter_ctx* ctx, const uint8_t* d_stream, uint64_t stream_by
             d_stream, stream_bytes, d_seg_off, d_sub_bits, d_sub_marks, n_bytes, n_chunks, d_out, ctx->d_codec,
             nullptr, nullptr);
     }
-    codec_publish_kernel<<<1, 1, 0, ctx->stream>>>(ctx->d_codec, ctx->dev_codec_mirror);
+    codec_end(ctx);
     return 0;
 }
 

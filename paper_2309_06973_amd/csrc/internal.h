@@ -306,6 +306,7 @@ struct shifter_ctx {
     uint64_t* dev_codec_mirror = nullptr;   //   its device address
     uint32_t* d_codec_list = nullptr; // chunk lists of the instances that take the longer segments
     uint64_t codec_list_cap = 0;      //   its capacity in entries
+    bool codec_dirty = true;          // the codec's result words may be non-zero (see codec_begin)
     // a shifter_prune_fused call whose outcome has not been collected yet
     struct Pending {
         bool active = false;
