@@ -1107,12 +1107,17 @@ int launch_deflate(shifter_ctx* ctx, const uint8_t* d_in, uint64_t n_bytes, uint
 }
 
 // Lists of the chunks whose segments need the medium and the large instance of the decoder
-// (the same rule as inside the instances); counts in result[2] and result[3].
-__global__ __launch_bounds__(BLOCK) void codec_classify_kernel(
+// (the same rule as inside the instances); counts in result[2] and result[3].  One atomic
+// per block and list (atomics to one address take their turns, about 10 ns each): the
+// wavefronts' counts meet in LDS and share the range the block reserves.
+constexpr uint32_t CLASSIFY_THREADS = 1024;
+__global__ __launch_bounds__(CLASSIFY_THREADS) void codec_classify_kernel(
     uint64_t stream_bytes, const uint64_t* __restrict__ seg_off, const uint16_t* __restrict__ side,
     uint32_t n_chunks, uint32_t* __restrict__ list_medium, uint32_t* __restrict__ list_large,
     uint64_t* __restrict__ result) {
-    const uint32_t c = blockIdx.x * BLOCK + threadIdx.x, lane = threadIdx.x & 63u;
+    constexpr uint32_t WAVES = CLASSIFY_THREADS / 64u;
+    __shared__ uint32_t s_cnt[2][WAVES], s_base[2];
+    const uint32_t c = blockIdx.x * CLASSIFY_THREADS + threadIdx.x, lane = threadIdx.x & 63u, wid = threadIdx.x >> 6;
     uint32_t seg_w = 0;
     if (c < n_chunks) {
         const uint64_t s0 = seg_off[c], s1 = seg_off[c + 1];
@@ -1121,18 +1126,26 @@ __global__ __launch_bounds__(BLOCK) void codec_classify_kernel(
             side[(uint64_t)c * CODEC_NSUB] != 0u)
             seg_w = ((uint32_t)(s0 & 3u) + (uint32_t)(s1 - s0) + 3u) / 4u + 2u;
     }
-    // one atomic per wave and list: the lanes that append share the range their leader takes
-    auto append = [&](bool mine, uint32_t* list, uint32_t* count) {
-        const uint64_t votes = __ballot(mine);
-        if (votes == 0ull) return;
-        const uint32_t leader = (uint32_t)__ffsll((long long)votes) - 1u;
-        uint32_t at = 0;
-        if (lane == leader) at = atomicAdd(count, (uint32_t)__popcll(votes));
-        at = __shfl(at, leader, 64);
-        if (mine) list[at + (uint32_t)__popcll(votes & ((1ull << lane) - 1ull))] = c;
-    };
-    append(seg_w > CODEC_SEG_MEDIUM, list_large, reinterpret_cast<uint32_t*>(&result[3]));
-    append(seg_w > CODEC_SEG_SMALL && seg_w <= CODEC_SEG_MEDIUM, list_medium, reinterpret_cast<uint32_t*>(&result[2]));
+    const bool large = seg_w > CODEC_SEG_MEDIUM, medium = seg_w > CODEC_SEG_SMALL && !large;
+    const uint64_t votes[2] = {__ballot(medium), __ballot(large)};
+    if (lane == 0) {
+        s_cnt[0][wid] = (uint32_t)__popcll(votes[0]);
+        s_cnt[1][wid] = (uint32_t)__popcll(votes[1]);
+    }
+    __syncthreads();
+    if (threadIdx.x < 2u) {
+        uint32_t total = 0;
+        for (uint32_t w = 0; w < WAVES; ++w) total += s_cnt[threadIdx.x][w];
+        s_base[threadIdx.x] = total ? atomicAdd(reinterpret_cast<uint32_t*>(&result[2u + threadIdx.x]), total) : 0u;
+    }
+    __syncthreads();
+    if (medium || large) {
+        const uint32_t x = large ? 1u : 0u;
+        uint32_t at = s_base[x];
+        for (uint32_t w = 0; w < wid; ++w) at += s_cnt[x][w];
+        at += (uint32_t)__popcll(votes[x] & ((1ull << lane) - 1ull));
+        (large ? list_large : list_medium)[at] = c;
+    }
 }
 
 // Kernels only, nothing waited for: the lists of the two larger instances are made on the
@@ -1149,7 +1162,7 @@ int launch_inflate(shifter_ctx* ctx, const uint8_t* d_stream, uint64_t stream_by
     codec_begin(ctx);
     {
         ProfileScope ps(ctx, K_INFLATE_CHUNK);
-        codec_classify_kernel<<<(n_chunks + BLOCK - 1) / BLOCK, BLOCK, 0, ctx->stream>>>(
+        codec_classify_kernel<<<(n_chunks + CLASSIFY_THREADS - 1) / CLASSIFY_THREADS, CLASSIFY_THREADS, 0, ctx->stream>>>(
             stream_bytes, d_seg_off, d_sub_bits, n_chunks, list_medium, list_large, ctx->d_codec);
         const uint32_t loop_grid = std::min(n_chunks, CODEC_LOOP_GRID);
         // the long segments first: their blocks run longest
