@@ -224,6 +224,13 @@ int shifter_set_margin_sigmas(shifter_ctx* ctx, double sigmas);
  * records, and everything computed from them, are the same bytes for every value. */
 int shifter_set_select_grid(shifter_ctx* ctx, uint32_t blocks);
 
+/* Arena size, in bytes, above which shifter_portfolio_begin ranks and masks a portfolio in
+ * one fused read of the arena; at or below it the counting pass and the batched mask pass
+ * run as two launches, which is faster while the arena stays in the last-level cache
+ * between them (default 192 MiB).  0: always fused; UINT64_MAX: never.  A choice of
+ * kernels only: every output is the same bytes either way. */
+int shifter_set_fused_min_bytes(shifter_ctx* ctx, uint64_t bytes);
+
 /* Outcome of the last waiting selection on this context, for measurement:
  * out8 = { path (1 single pass decided, 2 multi-pass select ran, 0 none yet), P,
  *          weights below the interval, weights inside it, sample size, interval low key,

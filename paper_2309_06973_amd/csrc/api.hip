@@ -959,6 +959,12 @@ extern "C" int shifter_set_select_grid(shifter_ctx* ctx, uint32_t blocks) {
     return SHIFTER_OK;
 }
 
+extern "C" int shifter_set_fused_min_bytes(shifter_ctx* ctx, uint64_t bytes) {
+    if (!ctx) return fail(nullptr, SHIFTER_ERR_INVALID_ARG, "set_fused_min_bytes: ctx is NULL");
+    ctx->fused_min_bytes = bytes;
+    return SHIFTER_OK;
+}
+
 extern "C" int shifter_set_select_path(shifter_ctx* ctx, int path) {
     if (!ctx || path < 0 || path > 1)
         return fail(ctx, SHIFTER_ERR_INVALID_ARG, "set_select_path: path must be 0 or 1");
@@ -1413,7 +1419,7 @@ extern "C" int shifter_portfolio_begin(shifter_ctx* ctx, const shifter_model* mo
         std::stable_sort(idx, idx + k_eff, [&](uint32_t x, uint32_t y) { return pp.pc.p[x] < pp.pc.p[y]; });
         for (uint32_t i = 0; i < k_eff; ++i) { sp.p[i] = pp.pc.p[idx[i]]; perm.v[i] = idx[i]; }
         pp.mode = 2;
-        if (model->info.w_extent * 4 > (192ull << 20)) {
+        if (model->info.w_extent * 4 > ctx->fused_min_bytes) {
             // an arena beyond the last-level cache: ranking, masks and levels in one read of it
             // (the planning launch expands the levels into the variants' flags on the way)
             FusedBatch fb{K, g.d_w_sparse, g.w_stride, g.d_mask, g.mask_stride, g.d_out_alive, g.d_in_alive, true};

@@ -298,6 +298,7 @@ struct shifter_ctx {
     uint32_t hist_grid = 2048;
     int select_path = 0;   // 0: single-pass where it applies; 1: multi-pass radix only
     double margin_sigmas = 4.0;   // half-width of the predicted interval, in binomial sigmas
+    uint64_t fused_min_bytes = 192ull << 20;   // portfolio_begin: arenas above this take the fused pass
     shifter::SpecState last_spec{};  // outcome of the last single-pass selection
     int last_path = 0;               // 1: single pass decided; 2: multi-pass select ran
     shifter_threshold last_record{};  // record of the last shifter_prune_fused that waited

@@ -143,6 +143,7 @@ EXPORTS = {
                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)],
     "shifter_set_select_grid": [C.c_void_p, C.c_uint32],
+    "shifter_set_fused_min_bytes": [C.c_void_p, C.c_uint64],
     "shifter_fixpoint_status": [C.c_void_p, C.c_void_p, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)],
     "shifter_prune_fused_result": [C.c_void_p, C.POINTER(Threshold), C.POINTER(C.c_int)],
     "shifter_prune_fused_batch": [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_uint64),
@@ -487,6 +488,10 @@ def shifter_propagate_groups_fixpoint(ctx: Context, model: Model, d_kernel_nz, f
 
 def shifter_set_select_grid(ctx: Context, blocks: int) -> None:
     _check(load_library().shifter_set_select_grid(ctx.handle, blocks), ctx.handle)
+
+
+def shifter_set_fused_min_bytes(ctx: Context, n_bytes: int) -> None:
+    _check(load_library().shifter_set_fused_min_bytes(ctx.handle, n_bytes), ctx.handle)
 
 
 def shifter_fixpoint_status(ctx: Context, model: Model):

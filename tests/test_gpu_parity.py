@@ -363,8 +363,11 @@ def check_batch(spec, w, v, n_prune, flags=0, check=None, with_in_alive=True):
         info = pl.model.info
         # the one-call step: single pass, multi-pass select, and a single pass that is made to
         # miss (no margin around the predicted thresholds) so that the call repeats the step
+        # ... and with the fused pass of large arenas forced on this small one (the branch the
+        # size rule would not take here), also missing and without sparse arenas
         for mode, sparse_arenas in (("one_call", True), ("one_call", False), ("one_call_radix", True),
-                                    ("one_call_miss", True)):
+                                    ("one_call_miss", True), ("one_call_fused", True),
+                                    ("one_call_fused", False), ("one_call_fused_miss", True)):
             for buf in (pl.b_w_out, pl.b_vecs_out, pl.b_w_sparse):
                 buf.fill_(float("nan"))
             pl.b_mask.fill_(7)
@@ -372,14 +375,17 @@ def check_batch(spec, w, v, n_prune, flags=0, check=None, with_in_alive=True):
             pl.b_in_alive.fill_(7)
             if mode == "one_call_radix":
                 S.shifter_set_select_path(pl.ctx, 1)
-            if mode == "one_call_miss":
+            if mode.endswith("_miss"):
                 S.shifter_set_margin_sigmas(pl.ctx, 0.0)
+            if "_fused" in mode:
+                S.shifter_set_fused_min_bytes(pl.ctx, 0)
             try:
                 _check_batch_run(pl, spec, refs, a, n_prune, flags, check, with_in_alive, False,
                                  sparse_arenas, mode)
             finally:
                 S.shifter_set_select_path(pl.ctx, 0)
                 S.shifter_set_margin_sigmas(pl.ctx, 4.0)
+                S.shifter_set_fused_min_bytes(pl.ctx, 192 << 20)
         for fused, from_sparse, sparse_arenas in ((True, False, True), (False, True, True),
                                                   (True, False, False), (False, False, True)):
             # ranking + masks in one read or in two calls; the rebuild from the dense arena
