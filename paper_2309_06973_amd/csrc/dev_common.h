@@ -17,6 +17,26 @@ __device__ __forceinline__ uint32_t find_tensor(const uint32_t* __restrict__ pre
     return lo;
 }
 
+// Bins of the sample histogram of the single-pass selections: SAMPLE_BINS bins of 2^15 keys
+// (1/256 of a binade, 0.27 % of a magnitude) over the 64 binades from 2^-50 to 2^14, where
+// the weights of networks live; the keys below that window (zeros among them) share bin 0,
+// the keys above it the last bin.  The intervals predicted from the sample are rounded
+// outward to whole bins, so narrow bins mean few candidates; no result depends on the
+// binning (weights all outside the window only send the selection to its multi-pass form).
+constexpr uint32_t SAMPLE_BINS = 16384;
+constexpr uint32_t SAMPLE_BIN_SHIFT = 15;
+constexpr uint32_t SAMPLE_KEY0 = (127u - 50u) << 23;      // first key of the window
+static_assert(((uint64_t)SAMPLE_BINS << SAMPLE_BIN_SHIFT) == (64ull << 23), "64 binades");
+__device__ __forceinline__ uint32_t sample_bin(uint32_t key) {
+    return key < SAMPLE_KEY0 ? 0u : min((key - SAMPLE_KEY0) >> SAMPLE_BIN_SHIFT, SAMPLE_BINS - 1u);
+}
+__device__ __forceinline__ uint32_t sample_bin_first_key(uint32_t bin) {
+    return bin == 0u ? 0u : SAMPLE_KEY0 + (bin << SAMPLE_BIN_SHIFT);
+}
+__device__ __forceinline__ uint32_t sample_bin_last_key(uint32_t bin) {
+    return bin >= SAMPLE_BINS - 1u ? 0x7fffffffu : SAMPLE_KEY0 + ((bin + 1u) << SAMPLE_BIN_SHIFT) - 1u;
+}
+
 // A value that is the same in every lane, moved to scalar registers.  The builtin returns
 // a signed int: without the casts the low word of a 64-bit value would be sign-extended.
 __device__ __forceinline__ uint32_t uniform_u32(uint32_t x) {

@@ -16,8 +16,7 @@
 
 namespace shifter {
 
-constexpr uint32_t MS_BINS = 16384;      // sample histogram bins
-constexpr uint32_t MS_SHIFT = 17;        // top 14 of the 31 key bits
+constexpr uint32_t MS_BINS = SAMPLE_BINS;   // sample histogram bins (sample_bin)
 constexpr uint32_t TAB_SHIFT = 19;       // the pass's bucket table: 4096 buckets of 2^19 keys
 constexpr uint32_t TAB_SIZE = 1u << (31 - TAB_SHIFT);
 // The counters all blocks add to are split CAND_SUB ways by block (one 128-byte line per
@@ -165,9 +164,9 @@ __global__ __launch_bounds__(PREDICT_THREADS) void ms_predict_kernel(
                 return a;
             };
             const double r_lo = centre - delta, r_hi = centre + delta;
-            if (r_lo > 0.0) lo = bin_of(r_lo) << MS_SHIFT;
-            if (r_hi < (double)(m - 1)) hi = ((bin_of(r_hi) + 1u) << MS_SHIFT) - 1u;
-            mid = bin_of(min(max(centre, 0.0), (double)(m - 1))) << MS_SHIFT;
+            if (r_lo > 0.0) lo = sample_bin_first_key(bin_of(r_lo));
+            if (r_hi < (double)(m - 1)) hi = sample_bin_last_key(bin_of(r_hi));
+            mid = sample_bin_first_key(bin_of(min(max(centre, 0.0), (double)(m - 1))));
         }
         // widen so that both ends are non-decreasing in k (ranks are sorted by P): a running
         // maximum of hi from the left, a running minimum of lo from the right; lanes past
@@ -203,7 +202,7 @@ __global__ __launch_bounds__(PREDICT_THREADS) void ms_predict_kernel(
         // cluster's last rank
         uint32_t wt = 0;
         if (lane < k_var && last == lane) {
-            const uint32_t b_lo = lo >> MS_SHIFT, b_hi = min(hi >> MS_SHIFT, MS_BINS - 1u);
+            const uint32_t b_lo = sample_bin(lo), b_hi = sample_bin(hi);
             wt = prefix[b_hi] - (b_lo ? prefix[b_lo - 1u] : 0u) + 64u;
         }
         uint64_t wsum = wt;

@@ -24,8 +24,7 @@
 
 namespace shifter {
 
-constexpr uint32_t SBINS = 16384;       // sample histogram bins
-constexpr uint32_t SAMPLE_SHIFT = 17;   // sample bins: top 14 of the 31 key bits
+constexpr uint32_t SBINS = SAMPLE_BINS;  // sample histogram bins (sample_bin)
 constexpr uint32_t FBINS1 = 256;        // round-1 finishing histogram: one bin per thread
 constexpr uint32_t FBINS = 4096;        // round-2 finishing histogram (one block, LDS)
 constexpr uint32_t FIN_BLOCKS = SPEC_FIN_BLOCKS;  // blocks of the passes over candidates
@@ -127,10 +126,10 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void spec_sample_kernel(
     };
     auto count = [&](const float* p, const float4& x) {
         if (!p) return;
-        atomicAdd(&h[key_of(x.x) >> SAMPLE_SHIFT], 1u);
-        atomicAdd(&h[key_of(x.y) >> SAMPLE_SHIFT], 1u);
-        atomicAdd(&h[key_of(x.z) >> SAMPLE_SHIFT], 1u);
-        atomicAdd(&h[key_of(x.w) >> SAMPLE_SHIFT], 1u);
+        atomicAdd(&h[sample_bin(key_of(x.x))], 1u);
+        atomicAdd(&h[sample_bin(key_of(x.y))], 1u);
+        atomicAdd(&h[sample_bin(key_of(x.z))], 1u);
+        atomicAdd(&h[sample_bin(key_of(x.w))], 1u);
     };
     // two sampled tiles per lane group and step, their loads in flight together
     const uint64_t step = (uint64_t)n_waves * 4;
@@ -217,10 +216,11 @@ __global__ __launch_bounds__(BLOCK) void spec_predict_kernel(SpecState* ss, uint
     for (uint32_t i = threadIdx.x; i < SBINS; i += BLOCK) shist[i] = 0;
     if (threadIdx.x != 0) return;
     uint32_t lo = 0, hi = 0x7fffffffu;
-    if (s_bin[0] != 0xffffffffu) lo = s_bin[0] << SAMPLE_SHIFT;
-    if (s_bin[1] != 0xffffffffu && r[1] < (double)(m - 1)) hi = ((s_bin[1] + 1u) << SAMPLE_SHIFT) - 1u;
+    if (s_bin[0] != 0xffffffffu) lo = sample_bin_first_key(s_bin[0]);
+    if (s_bin[1] != 0xffffffffu && r[1] < (double)(m - 1)) hi = sample_bin_last_key(s_bin[1]);
     uint32_t mid = lo;
-    if (s_bin[2] != 0xffffffffu) mid = (s_bin[2] << SAMPLE_SHIFT) + (1u << (SAMPLE_SHIFT - 1));
+    if (s_bin[2] != 0xffffffffu)      // the middle of the bin
+        mid = sample_bin_first_key(s_bin[2]) + (sample_bin_last_key(s_bin[2]) - sample_bin_first_key(s_bin[2])) / 2u;
     mid = max(lo, min(mid, hi));
     uint32_t sh = 0;
     while (((hi - lo) >> sh) >= FBINS1) ++sh;
