@@ -173,6 +173,20 @@ def test_scaled_wide_vgg():
     run_config(spec, w, v, ps)
 
 
+@pytest.mark.parametrize("scale_exp", [-60, -40, 13, 45])
+def test_weights_outside_and_at_the_edges_of_the_sample_window(scale_exp):
+    # the sample histogram resolves magnitudes from 2^-50 to 2^14 finely and lumps the rest
+    # into its first and last bin: models scaled out of that window, or straddling its
+    # edges, must come out the same bytes (the selection may take its multi-pass form)
+    spec, w, v = synth.generate_config(3)
+    w = (w.astype(np.float64) * 2.0 ** scale_exp).astype(np.float32)
+    assert np.isfinite(w).all() and np.count_nonzero(w) > 0.9 * w.size
+    n = spec.n_prunable
+    ps = [synth.prune_count(n, s) for s in (0.2, 0.5, 0.9, 0.99)]
+    run_config(spec, w, v, ps)
+    check_batch(spec, w, v, ps)
+
+
 @pytest.mark.parametrize("kind", synth.ADVERSARIAL_KINDS)
 def test_adversarial_values_ragged_chain(kind):
     # ragged sizes (nothing a multiple of 4 or of the tile), 1x1 / 3x3 / 5x5 kernels, ties
