@@ -142,7 +142,11 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void spec_sample_kernel(
         count(pb, xb);
     }
     __syncthreads();
-    for (uint32_t i = threadIdx.x; i < SBINS; i += SAMPLE_THREADS) {
+    // the blocks start at different segments of the histogram: the populated bins are few
+    // and neighbours, and atomics that meet at one address take their turns
+    constexpr uint32_t SEGS = SBINS / SAMPLE_THREADS;
+    for (uint32_t it = 0; it < SEGS; ++it) {
+        const uint32_t i = ((it + blockIdx.x) % SEGS) * SAMPLE_THREADS + threadIdx.x;
         const uint32_t c = h[i];
         if (c) atomicAdd(&shist[i], c);
     }
